@@ -1,0 +1,160 @@
+"""ctypes front of the CPU oracle (``bspmm_oracle.c``).  TEST INFRASTRUCTURE ONLY.
+
+Only ``tests/``, ``__graft_entry__.smoke()`` and the ``cpu_baseline`` leg of ``bench.py`` may
+import this module; it imports nothing from the HIP package and shares no code with it.
+The functions take plain numpy arrays with the batch layout of the paper's problem statement
+(per-operation CSR arrays located by offsets, packed row-major dense operands; Sec. II-B,
+Fig. 4, Sec. IV-C/IV-D) and return fp64 results.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Optional, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "bspmm_oracle.c")
+_LIB = os.path.join(_HERE, "liboracle_bspmm.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (-O2 -fopenmp).  Returns the library path."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c99", "-Wall", "-Wextra",
+               "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(_LIB)
+        i32p = ctypes.POINTER(ctypes.c_int32)
+        i64p = ctypes.POINTER(ctypes.c_int64)
+        f32p = ctypes.POINTER(ctypes.c_float)
+        f64p = ctypes.POINTER(ctypes.c_double)
+        common = [ctypes.c_int32, i32p, i32p, i32p, i64p, i64p, i64p, i64p, i32p, i32p, f32p,
+                  f32p, ctypes.c_int64, ctypes.c_int32, f64p, f64p, ctypes.c_int64]
+        lib.oracle_bspmm_forward.argtypes = common
+        lib.oracle_bspmm_forward.restype = ctypes.c_int
+        lib.oracle_bspmm_transposed.argtypes = common
+        lib.oracle_bspmm_transposed.restype = ctypes.c_int
+        lib.oracle_csr_transpose.argtypes = [ctypes.c_int32, i32p, i32p, i32p, i64p, i64p,
+                                             i32p, i32p, f32p, i64p, i32p, i32p, f32p, i32p]
+        lib.oracle_csr_transpose.restype = ctypes.c_int
+        lib.oracle_num_threads.restype = ctypes.c_int
+        lib.oracle_set_num_threads.argtypes = [ctypes.c_int]
+        _lib = lib
+    return _lib
+
+
+def _p(a: np.ndarray, ct):
+    return a.ctypes.data_as(ctypes.POINTER(ct))
+
+
+def _prep(rows, cols, nnz, rpt_off, nz_off, b_row_off, c_row_off, rpt, colids, values):
+    as_ = np.ascontiguousarray
+    return (as_(rows, dtype=np.int32), as_(cols, dtype=np.int32), as_(nnz, dtype=np.int32),
+            as_(rpt_off, dtype=np.int64), as_(nz_off, dtype=np.int64),
+            as_(b_row_off, dtype=np.int64), as_(c_row_off, dtype=np.int64),
+            as_(rpt, dtype=np.int32), as_(colids, dtype=np.int32),
+            as_(values, dtype=np.float32))
+
+
+def num_threads() -> int:
+    return int(_load().oracle_num_threads())
+
+
+def set_num_threads(n: int) -> None:
+    _load().oracle_set_num_threads(int(n))
+
+
+def forward(rows, cols, nnz, rpt_off, nz_off, b_row_off, c_row_off, rpt, colids, values,
+            B: np.ndarray, n_c_rows: int, want_scale: bool = True
+            ) -> Tuple[np.ndarray, Optional[np.ndarray]]:
+    """C_i = A_i B_i for every operation.  Returns (C, S) in fp64, shape (n_c_rows, F);
+    rows of C that belong to no operation are NaN (so an accidental read shows)."""
+    lib = _load()
+    a = _prep(rows, cols, nnz, rpt_off, nz_off, b_row_off, c_row_off, rpt, colids, values)
+    B = np.ascontiguousarray(B, dtype=np.float32)
+    F = int(B.shape[1])
+    C = np.full((int(n_c_rows), F), np.nan, dtype=np.float64)
+    S = np.full((int(n_c_rows), F), np.nan, dtype=np.float64) if want_scale else None
+    rc = lib.oracle_bspmm_forward(
+        int(a[0].shape[0]), _p(a[0], ctypes.c_int32), _p(a[1], ctypes.c_int32),
+        _p(a[2], ctypes.c_int32), _p(a[3], ctypes.c_int64), _p(a[4], ctypes.c_int64),
+        _p(a[5], ctypes.c_int64), _p(a[6], ctypes.c_int64), _p(a[7], ctypes.c_int32),
+        _p(a[8], ctypes.c_int32), _p(a[9], ctypes.c_float), _p(B, ctypes.c_float),
+        F, F, _p(C, ctypes.c_double),
+        _p(S, ctypes.c_double) if S is not None else None, F)
+    if rc != 0:
+        raise ValueError(f"oracle: malformed operation {-rc - 1}")
+    return C, S
+
+
+def transposed(rows, cols, nnz, rpt_off, nz_off, b_row_off, c_row_off, rpt, colids, values,
+               dY: np.ndarray, n_b_rows: int, want_scale: bool = True
+               ) -> Tuple[np.ndarray, Optional[np.ndarray]]:
+    """G_i = A_i^T dY_i for every operation.  dY is indexed by c_row_off (rows_i rows), the
+    result by b_row_off (cols_i rows).  Returns (G, S) in fp64, shape (n_b_rows, F)."""
+    lib = _load()
+    a = _prep(rows, cols, nnz, rpt_off, nz_off, b_row_off, c_row_off, rpt, colids, values)
+    dY = np.ascontiguousarray(dY, dtype=np.float32)
+    F = int(dY.shape[1])
+    G = np.full((int(n_b_rows), F), np.nan, dtype=np.float64)
+    S = np.full((int(n_b_rows), F), np.nan, dtype=np.float64) if want_scale else None
+    rc = lib.oracle_bspmm_transposed(
+        int(a[0].shape[0]), _p(a[0], ctypes.c_int32), _p(a[1], ctypes.c_int32),
+        _p(a[2], ctypes.c_int32), _p(a[3], ctypes.c_int64), _p(a[4], ctypes.c_int64),
+        _p(a[5], ctypes.c_int64), _p(a[6], ctypes.c_int64), _p(a[7], ctypes.c_int32),
+        _p(a[8], ctypes.c_int32), _p(a[9], ctypes.c_float), _p(dY, ctypes.c_float),
+        F, F, _p(G, ctypes.c_double),
+        _p(S, ctypes.c_double) if S is not None else None, F)
+    if rc != 0:
+        raise ValueError(f"oracle: malformed operation {-rc - 1}")
+    return G, S
+
+
+def csr_transpose(rows, cols, nnz, rpt_off, nz_off, rpt, colids, values):
+    """Stable transposed CSR of every operation.  Returns (rpt_t_off, rpt_t, colids_t,
+    values_t): op i has cols[i]+1 local row pointers at rpt_t_off[i]; its entries sit at
+    nz_off[i] like the input's."""
+    lib = _load()
+    z = np.zeros(len(rows), dtype=np.int64)
+    a = _prep(rows, cols, nnz, rpt_off, nz_off, z, z, rpt, colids, values)
+    nb = int(a[0].shape[0])
+    rpt_t_off = np.zeros(nb, dtype=np.int64)
+    if nb:
+        rpt_t_off[1:] = np.cumsum(a[1][:-1].astype(np.int64) + 1)
+    total_rpt = int((a[1].astype(np.int64) + 1).sum())
+    rpt_t = np.zeros(total_rpt, dtype=np.int32)
+    colids_t = np.zeros(a[8].shape[0], dtype=np.int32)
+    values_t = np.zeros(a[8].shape[0], dtype=np.float32)
+    scratch = np.zeros(max(int(a[1].max()) if nb else 0, 1), dtype=np.int32)
+    rc = lib.oracle_csr_transpose(
+        nb, _p(a[0], ctypes.c_int32), _p(a[1], ctypes.c_int32), _p(a[2], ctypes.c_int32),
+        _p(a[3], ctypes.c_int64), _p(a[4], ctypes.c_int64), _p(a[7], ctypes.c_int32),
+        _p(a[8], ctypes.c_int32), _p(a[9], ctypes.c_float), _p(rpt_t_off, ctypes.c_int64),
+        _p(rpt_t, ctypes.c_int32), _p(colids_t, ctypes.c_int32), _p(values_t, ctypes.c_float),
+        _p(scratch, ctypes.c_int32))
+    if rc != 0:
+        raise ValueError(f"oracle: malformed operation {-rc - 1}")
+    return rpt_t_off, rpt_t, colids_t, values_t
+
+
+def forward_batch(b, want_scale: bool = True):
+    """Convenience: forward product of a workloads.Batch-like object (duck-typed)."""
+    return forward(b.rows, b.cols, b.nnz, b.rpt_off, b.nz_off, b.b_row_off, b.c_row_off,
+                   b.rpt, b.colids, b.values, b.B, b.n_c_rows, want_scale)
+
+
+def transposed_batch(b, want_scale: bool = True):
+    """Convenience: transposed product of a Batch-like object using its ``dY``."""
+    return transposed(b.rows, b.cols, b.nnz, b.rpt_off, b.nz_off, b.b_row_off, b.c_row_off,
+                      b.rpt, b.colids, b.values, b.dY, b.n_b_rows, want_scale)

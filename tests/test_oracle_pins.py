@@ -1,0 +1,310 @@
+"""Pins of the CPU oracle against things other than itself (all CPU, no GPU).
+
+The paper prints no worked numeric example (its format figure is an image), so the oracle is
+pinned by: a hand-worked fixture, dense brute force, a library CSR product, and algebraic facts
+that any correct C = A B must satisfy (Sec. II-C definition; Fig. 2/3/4 all reduce to it).
+Each pin is chosen so that a plausible slip (dropped term, wrong index base, transposed
+operand, missing zero-initialisation, wrong offset) breaks at least one of them.
+"""
+import os
+
+import numpy as np
+import pytest
+import scipy.sparse as sp
+
+from paper_1903_11409_amd import workloads as W
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden", "hand_example.txt")
+
+
+def _read_golden():
+    out = {}
+    with open(GOLD) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            k, *v = line.split()
+            out[k] = [float(x) for x in v]
+    return out
+
+
+def _single_op(rows, cols, rpt, colids, values, dense, n_out, oracle, transposed=False):
+    z = np.zeros(1, dtype=np.int64)
+    args = ([rows], [cols], [len(colids)], z, z, z, z, rpt, colids, values, dense, n_out)
+    return (oracle.transposed if transposed else oracle.forward)(*args)
+
+
+def _dense_of(b, i):
+    """fp64 dense copy of operation i (duplicates add), built without any product."""
+    rpt, ci, va = b.op_csr(i)
+    A = np.zeros((int(b.rows[i]), int(b.cols[i])), dtype=np.float64)
+    r = np.repeat(np.arange(int(b.rows[i])), np.diff(rpt))
+    np.add.at(A, (r, ci), va.astype(np.float64))
+    return A
+
+
+def _brute(A, B):
+    """Triple loop, pure Python: the definition with nothing clever."""
+    m, k = A.shape
+    n = B.shape[1]
+    C = np.zeros((m, n), dtype=np.float64)
+    for i in range(m):
+        for j in range(n):
+            s = 0.0
+            for t in range(k):
+                s += A[i, t] * B[t, j]
+            C[i, j] = s
+    return C
+
+
+def test_hand_worked_example(oracle):
+    g = _read_golden()
+    m, n = int(g["rows"][0]), int(g["cols"][0])
+    rpt = np.array(g["rpt"], dtype=np.int32)
+    ci = np.array(g["colids"], dtype=np.int32)
+    va = np.array(g["values"], dtype=np.float32)
+    B = np.array(g["B"], dtype=np.float32).reshape(n, 2)
+    C, S = _single_op(m, n, rpt, ci, va, B, m, oracle)
+    assert np.array_equal(C, np.array(g["C"]).reshape(m, 2))
+    assert np.array_equal(S, np.array(g["S"]).reshape(m, 2))
+    Y = np.array(g["Y"], dtype=np.float32).reshape(m, 1)
+    G, _ = _single_op(m, n, rpt, ci, va, Y, n, oracle, transposed=True)
+    assert np.array_equal(G, np.array(g["G"]).reshape(n, 1))
+    z = np.zeros(1, dtype=np.int64)
+    _, rt, ct, vt = oracle.csr_transpose([m], [n], [len(ci)], z, z, rpt, ci, va)
+    assert rt.tolist() == [int(x) for x in g["rpt_t"]]
+    assert ct.tolist() == [int(x) for x in g["colids_t"]]
+    assert vt.tolist() == g["values_t"]
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_dense_brute_force_tiny(oracle, seed):
+    shapes = [(5, 7, 11), (12, 12, 30), (1, 1, 1), (3, 9, 0), (9, 3, 40), (0, 4, 0), (4, 0, 0)]
+    b = W.random_general(100 + seed, F=5, shapes=shapes, shuffle_blocks=True)
+    C, S = oracle.forward_batch(b)
+    G, SG = oracle.transposed_batch(b)
+    for i in range(b.batch):
+        A = _dense_of(b, i)
+        Bi = b.B[int(b.b_row_off[i]):int(b.b_row_off[i]) + int(b.cols[i])].astype(np.float64)
+        Yi = b.dY[int(b.c_row_off[i]):int(b.c_row_off[i]) + int(b.rows[i])].astype(np.float64)
+        ref = _brute(A, Bi)
+        got = C[int(b.c_row_off[i]):int(b.c_row_off[i]) + int(b.rows[i])]
+        assert np.allclose(got, ref, rtol=1e-12, atol=1e-14)
+        refT = _brute(A.T.copy(), Yi)
+        gotT = G[int(b.b_row_off[i]):int(b.b_row_off[i]) + int(b.cols[i])]
+        assert np.allclose(gotT, refT, rtol=1e-12, atol=1e-14)
+    # rows of the packed output that no operation owns (the gaps) were never written
+    owned = np.zeros(b.n_c_rows, dtype=bool)
+    for i in range(b.batch):
+        owned[int(b.c_row_off[i]):int(b.c_row_off[i]) + int(b.rows[i])] = True
+    assert np.all(np.isnan(C[~owned])) and not np.any(np.isnan(C[owned]))
+
+
+def test_scale_is_abs_product(oracle):
+    """S = |A| |B| needs unique entries (with duplicates |a1|+|a2| != |a1+a2|)."""
+    b = W.config1_tiny()
+    C, S = oracle.forward_batch(b)
+    for i in range(b.batch):
+        A = np.abs(_dense_of(b, i))
+        Bi = np.abs(b.B[int(b.b_row_off[i]):int(b.b_row_off[i]) + int(b.cols[i])].astype(np.float64))
+        got = S[int(b.c_row_off[i]):int(b.c_row_off[i]) + int(b.rows[i])]
+        assert np.allclose(got, A @ Bi, rtol=1e-12)
+    assert np.all(np.abs(C) <= S + 1e-300)
+
+
+@pytest.mark.parametrize("cfg", [1, 2, 3])
+def test_library_csr_product(oracle, cfg):
+    b = W.CONFIGS[cfg]() if cfg != 3 else W.config3_multichannel(graphs=64)
+    C, _ = oracle.forward_batch(b)
+    for i in range(b.batch):
+        rpt, ci, va = b.op_csr(i)
+        A = sp.csr_matrix((va.astype(np.float64), ci, rpt), shape=(int(b.rows[i]), int(b.cols[i])))
+        Bi = b.B[int(b.b_row_off[i]):int(b.b_row_off[i]) + int(b.cols[i])].astype(np.float64)
+        got = C[int(b.c_row_off[i]):int(b.c_row_off[i]) + int(b.rows[i])]
+        assert np.allclose(got, A @ Bi, rtol=1e-12, atol=1e-15)
+
+
+def test_identity_gives_B_bitwise(oracle):
+    b = W.identity_batch(7, F=9, sizes=[1, 5, 33])
+    C, S = oracle.forward_batch(b)
+    assert np.array_equal(C, b.B.astype(np.float64))
+    G, _ = oracle.transposed_batch(b)
+    assert np.array_equal(G, b.dY.astype(np.float64))
+
+
+def test_empty_rows_and_empty_ops(oracle):
+    b = W.random_general(5, F=6, shapes=[(10, 10, 4), (6, 6, 0), (0, 0, 0), (8, 3, 2)])
+    C, S = oracle.forward_batch(b)
+    for i in range(b.batch):
+        rpt, _, _ = b.op_csr(i)
+        got = C[int(b.c_row_off[i]):int(b.c_row_off[i]) + int(b.rows[i])]
+        empty = np.diff(rpt) == 0
+        assert np.all(got[empty] == 0.0)
+        assert np.all(S[int(b.c_row_off[i]):int(b.c_row_off[i]) + int(b.rows[i])][empty] == 0.0)
+    # a batch with no operation at all is fine
+    e = W.random_general(5, F=4, shapes=[])
+    C0, _ = oracle.forward_batch(e)
+    assert C0.shape == (0, 4)
+
+
+def test_linearity_in_B(oracle):
+    b = W.config2_molecule(graphs=16, F=8)
+    rng = np.random.default_rng(3)
+    B1 = rng.uniform(-1, 1, b.B.shape).astype(np.float32)
+    B2 = rng.uniform(-1, 1, b.B.shape).astype(np.float32)
+    # alpha, beta powers of two and B1 + B2 formed exactly in fp64, then the fp32 operand is
+    # avoided: the oracle takes fp32, so use values whose combination is exact in fp32
+    B1 = np.round(B1 * 1024) / 1024
+    B2 = np.round(B2 * 1024) / 1024
+    comb = (2.0 * B1 - 0.5 * B2).astype(np.float32)
+    assert np.array_equal(comb.astype(np.float64), 2.0 * B1.astype(np.float64) - 0.5 * B2.astype(np.float64))
+    import dataclasses
+    c1, _ = oracle.forward_batch(dataclasses.replace(b, B=B1.astype(np.float32)))
+    c2, _ = oracle.forward_batch(dataclasses.replace(b, B=B2.astype(np.float32)))
+    c12, _ = oracle.forward_batch(dataclasses.replace(b, B=comb))
+    assert np.allclose(c12, 2.0 * c1 - 0.5 * c2, rtol=1e-12, atol=1e-13)
+
+
+def test_node_relabelling(oracle):
+    """(P A P^T)(P B) = P (A B): relabel nodes, rebuild a sorted CSR, compare row-permuted."""
+    b = W.config1_tiny()
+    C, _ = oracle.forward_batch(b)
+    rng = np.random.default_rng(11)
+    for i in range(b.batch):
+        n = int(b.rows[i])
+        rpt, ci, va = b.op_csr(i)
+        perm = rng.permutation(n)            # new label of old node k is perm[k]
+        r = np.repeat(np.arange(n), np.diff(rpt))
+        nr, nc = perm[r], perm[ci]
+        order = np.lexsort((nc, nr))
+        rpt2 = np.zeros(n + 1, dtype=np.int32)
+        rpt2[1:] = np.cumsum(np.bincount(nr, minlength=n))
+        Bi = b.B[int(b.b_row_off[i]):int(b.b_row_off[i]) + n]
+        PB = np.empty_like(Bi)
+        PB[perm] = Bi
+        C2, _ = _single_op(n, n, rpt2, nc[order].astype(np.int32), va[order], PB, n, oracle)
+        Ci = C[int(b.c_row_off[i]):int(b.c_row_off[i]) + n]
+        PC = np.empty_like(Ci)
+        PC[perm] = Ci
+        assert np.allclose(C2, PC, rtol=1e-12, atol=1e-15)
+
+
+@pytest.mark.parametrize("cfg", [1, 2, 4])
+def test_symmetric_normalisation_eigenvector(oracle, cfg):
+    """A^ = D^-1/2 (A+I) D^-1/2 with d = rowsum(A+I) satisfies A^ sqrt(d) = sqrt(d).
+    Values are rounded to fp32, so the identity holds to a few fp32 ulps."""
+    b = W.CONFIGS[cfg](F=4) if cfg != 4 else W.config4_wide(F=4, graphs=16)
+    B = b.B.copy()
+    sq = []
+    for i in range(b.batch):
+        rpt, _, _ = b.op_csr(i)
+        d = np.diff(rpt).astype(np.float64)   # entries per row = degree + 1
+        sq.append(np.sqrt(d))
+    sq = np.concatenate(sq)
+    B[:, 2] = sq.astype(np.float32)
+    import dataclasses
+    C, _ = oracle.forward_batch(dataclasses.replace(b, B=B))
+    assert np.allclose(C[:, 2], sq, rtol=5e-7)
+
+
+def test_row_normalisation_row_sums(oracle):
+    """(D_ch^-1 A_ch) 1 = 1 on rows that have an edge of the channel, 0 on the others."""
+    b = W.config3_multichannel(graphs=32, F=3)
+    import dataclasses
+    C, _ = oracle.forward_batch(dataclasses.replace(b, B=np.ones_like(b.B)))
+    has = np.concatenate([np.diff(b.op_csr(i)[0]) > 0 for i in range(b.batch)])
+    assert np.allclose(C[has], 1.0, rtol=1e-6)
+    assert np.all(C[~has] == 0.0)
+    assert 0.2 < (~has).mean() < 0.8   # the channel split really leaves many rows empty
+
+
+def test_adjoint_identity_asymmetric(oracle):
+    """<A B, dY> = <B, A^T dY> ties the scatter (transposed) oracle to the forward one.
+    Run on asymmetric values: with symmetric A a missing transpose would go unseen."""
+    b = W.config5_skewed(graphs=24, F=8, asymmetric=True)
+    # the structure is symmetric but the values must not be
+    A0 = _dense_of(b, 0)
+    assert not np.allclose(A0, A0.T)
+    C, _ = oracle.forward_batch(b)
+    G, _ = oracle.transposed_batch(b)
+    lhs = float((C * b.dY.astype(np.float64)).sum())
+    rhs = float((b.B.astype(np.float64) * G).sum())
+    assert abs(lhs - rhs) <= 1e-11 * max(abs(lhs), 1.0)
+    # and per operation against the dense transpose through a library matmul
+    for i in range(0, b.batch, 5):
+        A = _dense_of(b, i)
+        Yi = b.dY[int(b.c_row_off[i]):int(b.c_row_off[i]) + int(b.rows[i])].astype(np.float64)
+        got = G[int(b.b_row_off[i]):int(b.b_row_off[i]) + int(b.cols[i])]
+        assert np.allclose(got, A.T @ Yi, rtol=1e-12, atol=1e-14)
+        # the forward product of the same operand is different: the pin can see a missing T
+        assert not np.allclose(got, A @ Yi, rtol=1e-3)
+
+
+def test_transposed_rectangular_general(oracle):
+    b = W.random_general(21, F=4, shapes=[(7, 13, 25), (13, 7, 25), (20, 20, 90)])
+    G, SG = oracle.transposed_batch(b)
+    for i in range(b.batch):
+        A = _dense_of(b, i)
+        Yi = b.dY[int(b.c_row_off[i]):int(b.c_row_off[i]) + int(b.rows[i])].astype(np.float64)
+        got = G[int(b.b_row_off[i]):int(b.b_row_off[i]) + int(b.cols[i])]
+        assert np.allclose(got, A.T @ Yi, rtol=1e-12, atol=1e-14)
+
+
+def test_csr_transpose_is_stable_counting_sort(oracle):
+    """Against numpy's stable sort by column, which defines the stable transpose."""
+    b = W.random_general(33, F=1, shapes=[(9, 5, 40), (5, 9, 40), (30, 30, 0), (1, 1, 1),
+                                          (0, 0, 0), (17, 17, 60)], with_dY=False)
+    off_t, rt, ct, vt = oracle.csr_transpose(b.rows, b.cols, b.nnz, b.rpt_off, b.nz_off,
+                                             b.rpt, b.colids, b.values)
+    for i in range(b.batch):
+        rpt, ci, va = b.op_csr(i)
+        m, n, z = int(b.rows[i]), int(b.cols[i]), int(b.nnz[i])
+        r = np.repeat(np.arange(m), np.diff(rpt)).astype(np.int32)
+        order = np.argsort(ci, kind="stable")
+        z0 = int(b.nz_off[i])
+        assert np.array_equal(ct[z0:z0 + z], r[order])
+        assert np.array_equal(vt[z0:z0 + z], va[order])
+        exp_rpt = np.zeros(n + 1, dtype=np.int64)
+        exp_rpt[1:] = np.cumsum(np.bincount(ci, minlength=n)) if z else 0
+        o = int(off_t[i])
+        assert np.array_equal(rt[o:o + n + 1], exp_rpt)
+
+
+def test_csr_transpose_round_trip_and_library(oracle):
+    """Sorted unique input: (A^T)^T = A exactly, and A^T matches scipy's."""
+    b = W.config2_molecule(graphs=12, F=1)
+    b3 = W.config3_multichannel(graphs=8, F=1)
+    for bb in (b, b3):
+        off_t, rt, ct, vt = oracle.csr_transpose(bb.rows, bb.cols, bb.nnz, bb.rpt_off,
+                                                 bb.nz_off, bb.rpt, bb.colids, bb.values)
+        off2, r2, c2, v2 = oracle.csr_transpose(bb.cols, bb.rows, bb.nnz, off_t, bb.nz_off,
+                                                rt, ct, vt)
+        assert np.array_equal(off2, bb.rpt_off)
+        assert np.array_equal(r2, bb.rpt) and np.array_equal(c2, bb.colids)
+        assert np.array_equal(v2, bb.values)
+        for i in range(bb.batch):
+            rpt, ci, va = bb.op_csr(i)
+            m, n, z = int(bb.rows[i]), int(bb.cols[i]), int(bb.nnz[i])
+            T = sp.csr_matrix((va, ci, rpt), shape=(m, n)).T.tocsr()
+            T.sort_indices()
+            o, z0 = int(off_t[i]), int(bb.nz_off[i])
+            assert np.array_equal(rt[o:o + n + 1], T.indptr)
+            assert np.array_equal(ct[z0:z0 + z], T.indices)
+            assert np.array_equal(vt[z0:z0 + z], T.data)
+
+
+def test_oracle_rejects_malformed(oracle):
+    z = np.zeros(1, dtype=np.int64)
+    B = np.zeros((3, 2), dtype=np.float32)
+    with pytest.raises(ValueError):   # column index out of range
+        oracle.forward([2], [3], [1], z, z, z, z, np.array([0, 1, 1], np.int32),
+                       np.array([3], np.int32), np.array([1.0], np.float32), B, 2)
+    with pytest.raises(ValueError):   # row pointer does not end at nnz
+        oracle.forward([2], [3], [2], z, z, z, z, np.array([0, 1, 1], np.int32),
+                       np.array([0, 1], np.int32), np.array([1.0, 1.0], np.float32), B, 2)
+
+
+def test_flop_formula():
+    b = W.config1_tiny()
+    assert W.flops(b) == 2 * int(b.nnz.sum()) * b.F   # 2 * nnz_A * n_B (Sec. V-A)
