@@ -238,7 +238,8 @@ def test_adjoint_identity_asymmetric(oracle):
         got = G[int(b.b_row_off[i]):int(b.b_row_off[i]) + int(b.cols[i])]
         assert np.allclose(got, A.T @ Yi, rtol=1e-12, atol=1e-14)
         # the forward product of the same operand is different: the pin can see a missing T
-        assert not np.allclose(got, A @ Yi, rtol=1e-3)
+        if not np.allclose(A, A.T):
+            assert not np.allclose(got, A @ Yi, rtol=1e-3)
 
 
 def test_transposed_rectangular_general(oracle):
