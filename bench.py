@@ -1,0 +1,286 @@
+#!/usr/bin/env python3
+"""Benchmark of the batched SpMM hot path on one MI355X.
+
+A *step* is one `bspmm_run` launch over one batch (the plan is built once, outside the timed
+region, as a GCN reuses one adjacency batch across layers and passes; plan-creation time is
+reported separately).  The headline workload is the molecule-like batch of 128 graphs at
+F = 128.  Dense operands rotate through a pool larger than the on-chip caches so that every
+launch really reads its inputs from, and writes its outputs to, HBM ("cold"); the cache-warm
+figure, the launch floor of an emptied schedule, eager launches and the other workload
+configurations are reported under "extra".
+
+Prints ONE JSON line.  The CPU oracle is timed beside the GPU as a baseline, not a target.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E peak
+POOL_BYTES = 640 << 20          # rotate dense operands through more than L2 + Infinity Cache
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=4000)
+    ap.add_argument("--warmup", type=int, default=400)
+    ap.add_argument("--no-extra", action="store_true", help="headline measurement only")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--cpu-seconds", type=float, default=10.0)
+    return ap.parse_args()
+
+
+class Runner:
+    """Holds a plan and a rotating pool of dense operands for one workload."""
+
+    def __init__(self, torch, K, batch, transposed=False, options=None, pool_bytes=POOL_BYTES,
+                 plan=None):
+        self.torch, self.K, self.b, self.transposed = torch, K, batch, transposed
+        t0 = time.perf_counter()
+        self.plan = plan or K.Plan(batch, options=options)
+        torch.cuda.synchronize()
+        self.create_ms = (time.perf_counter() - t0) * 1e3
+        F = batch.F
+        n_in = batch.n_c_rows if transposed else batch.n_b_rows
+        n_out = batch.n_b_rows if transposed else batch.n_c_rows
+        per_set = 4 * F * (n_in + n_out)
+        self.nsets = max(2, min(512, -(-pool_bytes // max(per_set, 1))))
+        self.inp = torch.rand((self.nsets, max(n_in, 1), F), dtype=torch.float32, device="cuda") * 2 - 1
+        self.out = torch.empty((self.nsets, max(n_out, 1), F), dtype=torch.float32, device="cuda")
+        self.in_ptrs = [self.inp[i].data_ptr() for i in range(self.nsets)]
+        self.out_ptrs = [self.out[i].data_ptr() for i in range(self.nsets)]
+        self.call = K.lib().bspmm_run_transposed if transposed else K.lib().bspmm_run
+        self.F = F
+        info = self.plan.info()
+        d = 1 if transposed else 0
+        self.eff_bytes = int(info.effective_bytes[d])
+        self.flops = int(info.flops)
+        self.workgroups = int(info.workgroups[d])
+        self.info = info
+        if transposed:      # build the transposed CSR outside any timed or captured region
+            self.launch(0, torch.cuda.current_stream().cuda_stream)
+            torch.cuda.synchronize()
+
+    def launch(self, i, stream, rotate=True):
+        s = i % self.nsets if rotate else 0
+        rc = self.call(self.plan.handle, self.in_ptrs[s], self.out_ptrs[s], self.F, self.F, stream)
+        if rc != 0:
+            raise self.K.BspmmError(rc, "bench launch")
+
+    def time_eager(self, steps, warmup, rotate=True):
+        torch = self.torch
+        stream = torch.cuda.current_stream().cuda_stream
+        for i in range(warmup):
+            self.launch(i, stream, rotate)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for i in range(steps):
+            self.launch(i, stream, rotate)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e-3 / steps
+
+    def time_graph(self, steps, warmup, rotate=True):
+        """Capture one pass over the pool in a HIP graph and replay it: the launches of the
+        timed region are issued by the GPU's command processor, not by the Python loop."""
+        torch = self.torch
+        chunk = self.nsets if rotate else 64
+        chunk = max(1, min(chunk, steps))
+        g = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            self.launch(0, side.cuda_stream, rotate)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        with torch.cuda.graph(g):
+            cs = torch.cuda.current_stream().cuda_stream
+            for i in range(chunk):
+                self.launch(i, cs, rotate)
+        reps = max(1, steps // chunk)
+        for _ in range(max(1, warmup // chunk)):
+            g.replay()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(reps):
+            g.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e-3 / (reps * chunk), reps * chunk
+
+    def summary(self, sec):
+        return {"us_per_launch": round(sec * 1e6, 3),
+                "graphs_per_s": round(self.b.n_graphs / sec, 1),
+                "gflops": round(self.flops / sec * 1e-9, 2),
+                "eff_GBps": round(self.eff_bytes / sec * 1e-9, 1),
+                "frac_of_8TBps": round(self.eff_bytes / sec * 1e-9 / HBM_PEAK_GBPS, 4),
+                "eff_MB": round(self.eff_bytes * 1e-6, 3),
+                "workgroups": self.workgroups}
+
+
+def copy_bandwidth(torch):
+    n = 1 << 28   # 1 GiB of fp32
+    a = torch.empty(n, dtype=torch.float32, device="cuda")
+    b = torch.empty(n, dtype=torch.float32, device="cuda")
+    a.fill_(1.0)
+    for _ in range(3):
+        b.copy_(a)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(10):
+        b.copy_(a)
+    e1.record()
+    torch.cuda.synchronize()
+    sec = e0.elapsed_time(e1) * 1e-3 / 10
+    del a, b
+    torch.cuda.empty_cache()
+    return 2 * 4 * n / sec * 1e-9
+
+
+def parity_sample(torch, K, runner, oracle):
+    """One launch of the timed configuration checked against the oracle on set 0."""
+    import numpy as np
+    b = runner.b
+    import dataclasses
+    bb = dataclasses.replace(b, B=runner.inp[0][:b.n_b_rows].cpu().numpy())
+    runner.out[0].fill_(-7.0)
+    runner.launch(0, torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    C, S = oracle.forward_batch(bb)
+    got = runner.out[0][:b.n_c_rows].cpu().numpy()
+    return bool(np.all(np.abs(got - C) <= 1e-5 * S))
+
+
+def cpu_baseline(oracle, b, seconds):
+    """The oracle as it stands, on the host cores, looping over the same batch."""
+    oracle.forward_batch(b, want_scale=False)
+    reps, t0 = 0, time.perf_counter()
+    while True:
+        oracle.forward_batch(b, want_scale=False)
+        reps += 1
+        dt = time.perf_counter() - t0
+        if dt >= seconds:
+            break
+    return {"value": round(b.n_graphs * reps / dt, 1), "unit": "graphs/s",
+            "cores": int(oracle.num_threads()), "kind": "oracle",
+            "sample": f"{reps} passes of the fp64 OpenMP oracle over the same 128-graph F=128 "
+                      f"batch in {dt:.1f} s (includes its output allocation)"}
+
+
+def read_traffic():
+    """HBM bytes per launch from the committed rocprofv3 counter summary, if there is one."""
+    path = os.path.join(ROOT, "profiles", "bspmm_kernel_cfg2_F128_pmc.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch"):
+                return float(line.split("=")[1].split()[0])
+    except OSError:
+        pass
+    return None
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU; --gpus must be 1 (batches shard across "
+              "GPUs without any exchange, see DESIGN.md)", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_1903_11409_amd import bspmm as K
+    from paper_1903_11409_amd import workloads as W
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    K.lib()
+
+    b = W.config2_molecule(F=128)
+    head = Runner(torch, K, b)
+    sec_graph, timed_steps = head.time_graph(args.steps, args.warmup)
+    sec_eager = head.time_eager(args.steps, args.warmup)
+    sec = min(sec_graph, sec_eager)
+    launch_mode = "hipgraph_replay" if sec_graph <= sec_eager else "eager"
+
+    extra = {}
+    parity_ok = None
+    if not args.no_cpu:
+        from oracle import reference as oracle
+        parity_ok = parity_sample(torch, K, head, oracle)
+    if not args.no_extra:
+        extra["headline_hipgraph"] = head.summary(sec_graph)
+        extra["headline_eager"] = head.summary(sec_eager)
+        warm, _ = head.time_graph(args.steps, args.warmup, rotate=False)
+        extra["headline_cache_warm"] = head.summary(warm)
+        floor = Runner(torch, K, b, options=K.make_options(flags=K.FLOOR_PROBE))
+        fsec, _ = floor.time_graph(args.steps, args.warmup)
+        extra["launch_floor_us"] = round(fsec * 1e6, 3)
+        extra["plan_create_ms"] = round(head.create_ms, 3)
+        t0 = time.perf_counter()
+        for _ in range(20):
+            K.Plan(b).close()
+        torch.cuda.synchronize()
+        extra["plan_create_ms_repeat"] = round((time.perf_counter() - t0) * 1e3 / 20, 3)
+        extra["copy_GBps_1GiB"] = round(copy_bandwidth(torch), 1)
+        others = {}
+        for name, mk, tr in [
+                ("cfg2_F64", lambda: W.config2_molecule(F=64), False),
+                ("cfg3_multichannel_F128", lambda: W.config3_multichannel(), False),
+                ("cfg4_F256", lambda: W.config4_wide(F=256), False),
+                ("cfg4_F1024", lambda: W.config4_wide(F=1024), False),
+                ("cfg5_forward_F256", lambda: W.config5_skewed(), False),
+                ("cfg5_transposed_F256", lambda: W.config5_skewed(), True)]:
+            bb = mk()
+            r = Runner(torch, K, bb, transposed=tr)
+            steps = max(200, min(args.steps, 2000))
+            s, _ = r.time_graph(steps, max(20, steps // 10))
+            others[name] = r.summary(s)
+            others[name]["bins"] = list(r.info.items_in_bin[1 if tr else 0])
+            del r
+            torch.cuda.empty_cache()
+        extra["other_configs_cold"] = others
+
+    out = {
+        "metric": "batched SpMM graphs/sec, F=128, batch 128",
+        "value": round(b.n_graphs / sec, 1),
+        "unit": "graphs/s",
+        "n_gpus": 1,
+        "steps": int(timed_steps if launch_mode == "hipgraph_replay" else args.steps),
+        "warmup": args.warmup,
+        "ms_per_step": round(sec * 1e3, 6),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": "cfg2_molecule: 128 molecule-like graphs (log-normal sizes, mean "
+                               "25 nodes, degree <= 6, self-loops, symmetric normalisation), "
+                               "F=128, forward",
+                   "seed": W.config_seed(2), "checksum": b.checksum(),
+                   "operands": f"hbm_cold: {head.nsets} dense operand sets rotated",
+                   "launch": launch_mode, "one_launch_per_batch": True,
+                   "gflops": round(head.flops / sec * 1e-9, 2),
+                   "parity_vs_oracle": parity_ok},
+        "roofline": {"bound": "hbm", "achieved": round(head.eff_bytes / sec * 1e-9, 1),
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(head.eff_bytes / sec * 1e-9 / HBM_PEAK_GBPS, 4),
+                     "traffic": read_traffic(),
+                     "kernel": "bspmm_kernel<4>", "bytes_per_launch": head.eff_bytes},
+    }
+    if not args.no_cpu:
+        out["cpu_baseline"] = cpu_baseline(oracle, b, args.cpu_seconds)
+    if extra:
+        out["extra"] = extra
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,209 @@
+/*
+ * bspmm.h - Batched SpMM for small sparse matrices on AMD MI355X (gfx950), C ABI.
+ *
+ * One call multiplies a whole mini-batch of small sparse matrices A_i (CSR) by dense matrices
+ * B_i in ONE kernel launch (the Batched SpMM of Sec. IV-C of "Batched Sparse Matrix
+ * Multiplication for Accelerating Graph Convolutional Networks", arXiv 1903.11409):
+ *
+ *     forward      C_i = A_i   . B_i      (the result of Fig. 2 / Fig. 4: C is overwritten)
+ *     transposed   G_i = A_i^T . dY_i     (the backward product of Sec. IV-D, last sentence)
+ *
+ * Conventions (Sec. II-B, II-C, Fig. 4, Sec. IV-D):
+ *  - A_i is CSR: row pointer `rpt` (rows_i+1 entries), column index `colids` and `values`
+ *    (nnz_i entries each), all 0-based int32 / fp32.  Each operation's row pointer is LOCAL:
+ *    rpt[0] == 0 and rpt[rows_i] == nnz_i.  Column indices inside a row need not be sorted
+ *    or unique (duplicates add up).
+ *  - All operations of a batch share one dense column count F (the paper's n_B).
+ *  - Dense operands are row-major fp32, packed for the whole batch: operation i reads rows
+ *    [b_row_off[i], b_row_off[i]+cols_i) of B and writes rows [c_row_off[i], c_row_off[i]+rows_i)
+ *    of C; leading dimensions are given per call, in elements, and must be >= F.
+ *    Several operations may read the same B block (a graph with several edge-type channels);
+ *    output blocks must not overlap.
+ *  - alpha = 1, beta = 0: every output row of every operation is written exactly once
+ *    (zeros for rows without entries); output rows that belong to no operation are untouched.
+ *  - Arithmetic is fp32 with fused multiply-add, summed in stored order inside a row.
+ *
+ * Memory and ownership.  Pointers marked HOST are read during the call and may be freed
+ * afterwards.  Pointers marked DEVICE must stay valid and unchanged until bspmm_destroy
+ * (the plan borrows them).  The library never allocates device memory: the caller provides a
+ * device workspace of at least bspmm_workspace_bytes() bytes, 256-byte aligned, which the plan
+ * owns until bspmm_destroy (schedule tables and the transposed CSR live there).
+ *
+ * Streams.  `stream` is a hipStream_t passed as void* (NULL = the default stream).  All
+ * device work is enqueued asynchronously; no call synchronises the device except where stated.
+ * bspmm_run / bspmm_run_transposed enqueue exactly one kernel.  Calls on one plan must be
+ * issued from one host thread at a time and on the stream order the caller wants.
+ *
+ * Errors.  Every int-returning call returns BSPMM_OK or a negative BSPMM_E* code; nothing is
+ * printed, thrown or aborted.  Device-side contents of rpt/colids are trusted by run calls;
+ * bspmm_validate checks them on the device on request.
+ */
+#ifndef BSPMM_H
+#define BSPMM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define BSPMM_OK          0
+#define BSPMM_EINVAL    (-1)  /* bad argument: null pointer, negative size, ld < F, ...      */
+#define BSPMM_ENOSPACE  (-2)  /* workspace smaller than bspmm_workspace_bytes()               */
+#define BSPMM_EHIP      (-3)  /* a HIP runtime call failed (see bspmm_last_hip_error)         */
+#define BSPMM_EOVERLAP  (-4)  /* output blocks of two operations overlap                      */
+#define BSPMM_ESTATE    (-5)  /* plan cannot do this (dry-run plan, transposed unsupported)   */
+#define BSPMM_EBADCSR   (-6)  /* bspmm_validate found a malformed CSR on the device           */
+
+/* bspmm_options.flags */
+#define BSPMM_DRY_RUN          1u  /* schedule only: touch no device, run calls return ESTATE */
+#define BSPMM_BUILD_TRANSPOSE  2u  /* enqueue the transposed-CSR build inside bspmm_create    */
+#define BSPMM_FLOOR_PROBE      4u  /* measurement aid: same grid, LDS and item fetches, but every
+                                      item is emptied, so a run computes and writes nothing      */
+
+/* Schedule bins: how many lanes one (operation, feature-tile) item gets. */
+#define BSPMM_BIN_WORKGROUP 0  /* 256 lanes, A_i and its B tile staged in LDS                 */
+#define BSPMM_BIN_WAVE      1  /* one 64-lane wavefront, staged                               */
+#define BSPMM_BIN_SLICE32   2  /* half a wavefront, staged                                    */
+#define BSPMM_BIN_SLICE16   3  /* a quarter wavefront, staged                                 */
+#define BSPMM_BIN_GENERIC   4  /* 256 lanes on a row block, operands read from global memory  */
+#define BSPMM_NUM_BINS      5
+
+typedef struct bspmm_plan bspmm_plan;
+
+/* The batch: the paper's list of sparse matrices plus where their dense blocks sit. */
+typedef struct bspmm_batch {
+    int32_t        batch;      /* number of SpMM operations, >= 0                              */
+    const int32_t* rows;       /* HOST [batch]  m_A of operation i                             */
+    const int32_t* cols;       /* HOST [batch]  n_A of operation i                             */
+    const int32_t* nnz;        /* HOST [batch]  stored entries of operation i                  */
+    const int64_t* rpt_off;    /* HOST [batch]  element offset of op i's row pointers in rpt   */
+    const int64_t* nz_off;     /* HOST [batch]  element offset of op i's entries               */
+    const int64_t* b_row_off;  /* HOST [batch]  first row of B_i in the packed dense input     */
+    const int64_t* c_row_off;  /* HOST [batch]  first row of C_i in the packed dense output    */
+    const int32_t* rpt;        /* DEVICE row pointers of all operations                        */
+    const int32_t* colids;     /* DEVICE column indices of all operations                      */
+    const float*   values;     /* DEVICE values of all operations                              */
+} bspmm_batch;
+
+/* Scheduler knobs.  Zero-initialise for defaults. */
+typedef struct bspmm_options {
+    uint32_t flags;            /* BSPMM_DRY_RUN | BSPMM_BUILD_TRANSPOSE | BSPMM_FLOOR_PROBE    */
+    int32_t  force_bin;        /* 0 = automatic; 1+b forces bin b for every op that fits it    */
+    int32_t  lds_bytes;        /* LDS per workgroup, 0 = default (32 KiB); <= 64 KiB           */
+    int32_t  min_tile;         /* narrowest feature tile in floats, 0 = default (32)           */
+    int32_t  max_tile;         /* widest feature tile in floats, 0 = default (256), <= 256     */
+    int32_t  target_workgroups;/* split tiles until the launch has this many, 0 = 4 per CU    */
+    int32_t  compute_units;    /* 0 = ask the device (256 assumed for dry runs)                */
+    int32_t  lds_pad;          /* floats added to each staged B row, 0 = default, -1 = none    */
+    int32_t  max_passes;       /* row passes a sub-workgroup slot may take, 0 = default (2)    */
+    int32_t  generic_rows;     /* rows per generic row block, 0 = default (32)                 */
+} bspmm_options;
+
+/* What the scheduler decided; index 0 = forward, 1 = transposed. */
+typedef struct bspmm_info {
+    int32_t batch;
+    int32_t F;
+    int32_t lds_bytes;
+    int32_t compute_units;
+    int32_t tile[2];                         /* batch-wide feature tile before per-op shrink  */
+    int32_t workgroups[2];                   /* grid size of the single launch                */
+    int32_t items[2];                        /* non-empty work items                          */
+    int32_t items_in_bin[2][BSPMM_NUM_BINS];
+    int32_t transposed_supported;            /* 0 when input-gradient blocks overlap          */
+    int32_t transposed_built;                /* the build kernel has been enqueued            */
+    int64_t effective_bytes[2];              /* CSR + distinct dense inputs + outputs, once   */
+    int64_t flops;                           /* 2 * nnz * F (Sec. V-A)                        */
+    uint64_t workspace_bytes;
+} bspmm_info;
+
+/* One scheduled work item, for inspection and tests. */
+typedef struct bspmm_item {
+    int32_t op;        /* operation index                                                     */
+    int32_t bin;       /* BSPMM_BIN_*                                                         */
+    int32_t row0;      /* first output row of the operation this item computes                */
+    int32_t nrows;     /* number of output rows                                               */
+    int32_t f0;        /* first feature column                                                */
+    int32_t fw;        /* number of feature columns                                           */
+    int32_t workgroup; /* blockIdx.x that runs it                                             */
+    int32_t slot;      /* lane slot inside the workgroup                                      */
+} bspmm_item;
+
+/*
+ * Bytes of device workspace a plan for (batch, F, options) needs.  Reads only HOST arrays.
+ * options may be NULL.  Device pointers in `b` are not dereferenced and may be NULL here.
+ */
+int bspmm_workspace_bytes(const bspmm_batch* b, int32_t F, const bspmm_options* options,
+                          size_t* bytes);
+
+/*
+ * Inspect the batch, bin every operation, tile the feature dimension, build the work lists
+ * for the forward and the transposed product and upload them to `workspace` (one async copy
+ * on `stream`); Sec. IV-C's "decide cache blocking and resource assignment from the sizes of
+ * the inputs", done per operation instead of from the batch maximum.
+ * Returns EINVAL for null/negative/inconsistent arguments or F <= 0, EOVERLAP when two
+ * operations' C blocks overlap, ENOSPACE, EHIP.  On error *plan is NULL.
+ */
+int bspmm_create(bspmm_plan** plan, const bspmm_batch* b, int32_t F,
+                 const bspmm_options* options, void* workspace, size_t workspace_bytes,
+                 void* stream);
+
+/*
+ * C_i = A_i . B_i for every operation, one kernel launch on `stream` (Fig. 4 per row, batched
+ * as in Sec. IV-C).  B and C are DEVICE pointers to the packed matrices, ldb/ldc their leading
+ * dimensions in floats (>= F).  B and C must not alias.  A plan with batch == 0 launches
+ * nothing.  The vectorised path needs 16-byte aligned B, C and ldb % 4 == ldc % 4 == 0;
+ * anything else silently takes the scalar path.
+ */
+int bspmm_run(bspmm_plan* plan, const float* B, float* C, int64_t ldb, int64_t ldc,
+              void* stream);
+
+/*
+ * G_i = A_i^T . dY_i for every operation (backward product with respect to the dense input).
+ * dY is indexed like C (rows_i rows at c_row_off[i]), G like B (cols_i rows at b_row_off[i]).
+ * The first call enqueues the on-device transposed-CSR build (one extra launch, once per
+ * plan) unless bspmm_create already did.  Returns ESTATE when two operations share or
+ * overlap a B block, because each would have to accumulate into the same gradient rows.
+ */
+int bspmm_run_transposed(bspmm_plan* plan, const float* dY, float* G, int64_t ldy, int64_t ldg,
+                         void* stream);
+
+/*
+ * Copy the plan's transposed CSR (stable: inside a row of A_i^T entries are ordered by the
+ * original row, ties by stored position) into caller DEVICE arrays: rpt_t gets sum(cols_i+1)
+ * int32 (op i at sum_{k<i}(cols_k+1), local), colids_t / values_t get sum(nnz_i) entries
+ * (op i at nz packing order sum_{k<i} nnz_k).  Builds the transpose first if needed.
+ */
+int bspmm_export_transposed(bspmm_plan* plan, int32_t* rpt_t, int32_t* colids_t,
+                            float* values_t, void* stream);
+
+/*
+ * Check the DEVICE CSR arrays against the HOST sizes given at creation: rpt[0]==0,
+ * rpt non-decreasing, rpt[rows]==nnz, 0 <= colids < cols.  Launches one kernel and
+ * SYNCHRONISES `stream`.  Returns OK or EBADCSR (*bad_op = first offending operation).
+ */
+int bspmm_validate(bspmm_plan* plan, int32_t* bad_op, void* stream);
+
+/* Fill *info.  Works on dry-run plans. */
+int bspmm_plan_info(const bspmm_plan* plan, bspmm_info* info);
+
+/* Copy up to `capacity` scheduled items of one direction (0 forward, 1 transposed) into
+ * `items`; *count receives the total number.  HOST only. */
+int bspmm_plan_items(const bspmm_plan* plan, int32_t transposed, bspmm_item* items,
+                     int32_t capacity, int32_t* count);
+
+/* Release the host side of the plan.  Does not touch the stream: the caller keeps the
+ * workspace alive until work already enqueued has finished.  NULL is allowed. */
+void bspmm_destroy(bspmm_plan* plan);
+
+/* Static description of an error code. */
+const char* bspmm_strerror(int code);
+
+/* The hipError_t (as int) behind the calling thread's most recent BSPMM_EHIP. */
+int bspmm_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BSPMM_H */

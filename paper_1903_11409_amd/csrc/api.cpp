@@ -1,0 +1,484 @@
+// C ABI of libbspmm (see include/bspmm.h for the contract of every entry point).
+#include <hip/hip_runtime_api.h>
+
+#include <algorithm>
+#include <cstring>
+#include <new>
+#include <set>
+#include <utility>
+#include <vector>
+
+#include "../../include/bspmm.h"
+#include "plan.hpp"
+#include "schedule.hpp"
+
+namespace bspmm {
+hipError_t launch_bspmm(const LaunchParams& P, int grid, int lds_bytes, bool vec4,
+                        hipStream_t stream);
+hipError_t launch_build_transpose(const OpRecord* ops, int batch, int lds_bytes,
+                                  const int32_t* rpt, const int32_t* colids,
+                                  const float* values, int32_t* rpt_t, int32_t* colids_t,
+                                  float* values_t, int32_t* gscratch, hipStream_t stream);
+hipError_t launch_validate(const OpRecord* ops, int batch, const int32_t* rpt,
+                           const int32_t* colids, int32_t* flag, hipStream_t stream);
+}  // namespace bspmm
+
+using namespace bspmm;
+
+namespace {
+
+thread_local int g_last_hip_error = 0;
+
+int hip_fail(hipError_t e)
+{
+    g_last_hip_error = (int)e;
+    return BSPMM_EHIP;
+}
+
+constexpr size_t kAlign = 256;
+size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+// Where each table sits inside the workspace (byte offsets).
+struct Layout {
+    size_t items[2] = {0, 0};
+    size_t op_records = 0;
+    size_t rpt_t = 0, colids_t = 0, values_t = 0;
+    size_t scratch = 0;
+    size_t flag = 0;
+    size_t total = 0;
+};
+
+}  // namespace
+
+struct bspmm_plan {
+    int32_t batch = 0;
+    int32_t F = 0;
+    bool dry = false;
+    Knobs knobs;
+    DirOps dir[2];
+    Schedule sched[2];
+    std::vector<OpRecord> records;
+    Layout lay;
+    int build_lds_bytes = 0;
+    int64_t scratch_words = 0;
+    bool transposed_supported = true;
+    bool transposed_built = false;
+    int64_t effective_bytes[2] = {0, 0};
+    int64_t flops = 0;
+    // borrowed device pointers
+    const int32_t* rpt = nullptr;
+    const int32_t* colids = nullptr;
+    const float* values = nullptr;
+    char* ws = nullptr;
+};
+
+namespace {
+
+int check_batch(const bspmm_batch* b, int32_t F, bool need_device)
+{
+    if (!b || F <= 0 || b->batch < 0) return BSPMM_EINVAL;
+    if (b->batch == 0) return BSPMM_OK;
+    if (!b->rows || !b->cols || !b->nnz || !b->rpt_off || !b->nz_off || !b->b_row_off ||
+        !b->c_row_off)
+        return BSPMM_EINVAL;
+    int64_t total_nnz = 0;
+    for (int i = 0; i < b->batch; ++i) {
+        if (b->rows[i] < 0 || b->cols[i] < 0 || b->nnz[i] < 0) return BSPMM_EINVAL;
+        if (b->rpt_off[i] < 0 || b->nz_off[i] < 0 || b->b_row_off[i] < 0 || b->c_row_off[i] < 0)
+            return BSPMM_EINVAL;
+        if ((b->rows[i] == 0 || b->cols[i] == 0) && b->nnz[i] != 0) return BSPMM_EINVAL;
+        total_nnz += b->nnz[i];
+    }
+    if (need_device) {
+        if (!b->rpt) return BSPMM_EINVAL;
+        if (total_nnz > 0 && (!b->colids || !b->values)) return BSPMM_EINVAL;
+    }
+    return BSPMM_OK;
+}
+
+// true when the half-open row intervals [off, off+len) with len > 0 are pairwise disjoint
+bool disjoint(const int64_t* off, const int32_t* len, int n)
+{
+    std::vector<std::pair<int64_t, int64_t>> v;
+    v.reserve(n);
+    for (int i = 0; i < n; ++i)
+        if (len[i] > 0) v.emplace_back(off[i], off[i] + len[i]);
+    std::sort(v.begin(), v.end());
+    for (size_t i = 1; i < v.size(); ++i)
+        if (v[i].first < v[i - 1].second) return false;
+    return true;
+}
+
+// Fill everything of the plan that needs no device.
+int plan_host(bspmm_plan& p, const bspmm_batch* b, int32_t F, const Knobs& kn)
+{
+    const int n = b->batch;
+    p.batch = n;
+    p.F = F;
+    p.knobs = kn;
+    DirOps& f = p.dir[0];
+    DirOps& t = p.dir[1];
+    int64_t rpt_t_words = 0;
+    p.records.resize(n);
+    int64_t nz_pack = 0;
+    int64_t scratch_words = 0;
+    int build_lds_words = 0;
+    for (int i = 0; i < n; ++i) {
+        f.m.push_back(b->rows[i]);
+        f.k.push_back(b->cols[i]);
+        f.nnz.push_back(b->nnz[i]);
+        f.rpt_off.push_back(b->rpt_off[i]);
+        f.nz_off.push_back(b->nz_off[i]);
+        f.in_off.push_back(b->b_row_off[i]);
+        f.out_off.push_back(b->c_row_off[i]);
+        // transposed: rows and columns swap, dense input is indexed like C, output like B;
+        // the transposed entries are packed back to back in operation order
+        t.m.push_back(b->cols[i]);
+        t.k.push_back(b->rows[i]);
+        t.nnz.push_back(b->nnz[i]);
+        t.rpt_off.push_back(rpt_t_words);
+        t.nz_off.push_back(nz_pack);
+        t.in_off.push_back(b->c_row_off[i]);
+        t.out_off.push_back(b->b_row_off[i]);
+
+        OpRecord& r = p.records[i];
+        r.rpt_off = b->rpt_off[i];
+        r.nz_off = b->nz_off[i];
+        r.rpt_t_off = rpt_t_words;
+        r.nz_t_off = nz_pack;
+        r.m = b->rows[i];
+        r.k = b->cols[i];
+        r.nnz = b->nnz[i];
+        r.pad_ = 0;
+        const int64_t work = (int64_t)b->cols[i] + 1 + b->nnz[i];
+        if (work * 4 <= kMaxLdsBytes - 2048) {
+            r.scratch_off = -1;
+            build_lds_words = std::max<int64_t>(build_lds_words, work);
+        } else {
+            r.scratch_off = scratch_words;
+            scratch_words += work;
+        }
+        rpt_t_words += (int64_t)b->cols[i] + 1;
+        nz_pack += b->nnz[i];
+    }
+    p.build_lds_bytes = (int)round_up(build_lds_words * 4 + 16, 256);
+    p.scratch_words = scratch_words;
+
+    if (n > 0 && !disjoint(b->c_row_off, b->rows, n)) return BSPMM_EOVERLAP;
+    p.transposed_supported = n == 0 || disjoint(b->b_row_off, b->cols, n);
+
+    p.sched[0] = make_schedule(f, F, kn);
+    if (p.transposed_supported) p.sched[1] = make_schedule(t, F, kn);
+
+    // compulsory traffic: CSR once, every distinct dense input block once, every output once
+    std::set<std::pair<int64_t, int32_t>> blocks_f, blocks_t;
+    int64_t csr_f = 0, csr_t = 0, out_f = 0, out_t = 0, in_f = 0, in_t = 0, nnz = 0;
+    for (int i = 0; i < n; ++i) {
+        csr_f += 4 * ((int64_t)b->rows[i] + 1) + 8 * (int64_t)b->nnz[i];
+        csr_t += 4 * ((int64_t)b->cols[i] + 1) + 8 * (int64_t)b->nnz[i];
+        out_f += 4 * (int64_t)b->rows[i] * F;
+        out_t += 4 * (int64_t)b->cols[i] * F;
+        if (blocks_f.emplace(b->b_row_off[i], b->cols[i]).second) in_f += 4 * (int64_t)b->cols[i] * F;
+        if (blocks_t.emplace(b->c_row_off[i], b->rows[i]).second) in_t += 4 * (int64_t)b->rows[i] * F;
+        nnz += b->nnz[i];
+    }
+    p.effective_bytes[0] = csr_f + in_f + out_f;
+    p.effective_bytes[1] = csr_t + in_t + out_t;
+    p.flops = 2 * nnz * F;
+
+    // workspace layout
+    Layout& L = p.lay;
+    size_t at = 0;
+    for (int d = 0; d < 2; ++d) {
+        L.items[d] = at;
+        at = align_up(at + p.sched[d].items.size() * sizeof(WorkItem));
+    }
+    L.op_records = at;
+    at = align_up(at + (size_t)n * sizeof(OpRecord));
+    L.rpt_t = at;
+    at = align_up(at + (size_t)rpt_t_words * 4);
+    L.colids_t = at;
+    at = align_up(at + (size_t)nz_pack * 4);
+    L.values_t = at;
+    at = align_up(at + (size_t)nz_pack * 4);
+    L.scratch = at;
+    at = align_up(at + (size_t)scratch_words * 4);
+    L.flag = at;
+    at = align_up(at + 4);
+    L.total = at;
+    return BSPMM_OK;
+}
+
+Knobs knobs_for(const bspmm_options* o, bool ask_device)
+{
+    Knobs kn = resolve_knobs(o);
+    const bool cus_given = o && o->compute_units > 0;
+    if (!cus_given && ask_device) {
+        int dev = 0, cus = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess &&
+            cus > 0)
+            kn.compute_units = cus;
+        else
+            (void)hipGetLastError();
+    }
+    if (!(o && o->target_workgroups > 0)) kn.target_wgs = 4 * kn.compute_units;
+    return kn;
+}
+
+int enqueue_build(bspmm_plan* p, hipStream_t s)
+{
+    if (p->transposed_built) return BSPMM_OK;
+    hipError_t e = launch_build_transpose(
+        reinterpret_cast<const OpRecord*>(p->ws + p->lay.op_records), p->batch,
+        p->build_lds_bytes, p->rpt, p->colids, p->values,
+        reinterpret_cast<int32_t*>(p->ws + p->lay.rpt_t),
+        reinterpret_cast<int32_t*>(p->ws + p->lay.colids_t),
+        reinterpret_cast<float*>(p->ws + p->lay.values_t),
+        reinterpret_cast<int32_t*>(p->ws + p->lay.scratch), s);
+    if (e != hipSuccess) return hip_fail(e);
+    p->transposed_built = true;
+    return BSPMM_OK;
+}
+
+int run_direction(bspmm_plan* p, int d, const float* in, float* out, int64_t ld_in,
+                  int64_t ld_out, hipStream_t s)
+{
+    const Schedule& sc = p->sched[d];
+    if (sc.grid == 0) return BSPMM_OK;
+    if (!in || !out || ld_in < p->F || ld_out < p->F) return BSPMM_EINVAL;
+    LaunchParams P;
+    P.items = reinterpret_cast<const WorkItem*>(p->ws + p->lay.items[d]);
+    if (d == 0) {
+        P.rpt = p->rpt;
+        P.colids = p->colids;
+        P.values = p->values;
+    } else {
+        P.rpt = reinterpret_cast<const int32_t*>(p->ws + p->lay.rpt_t);
+        P.colids = reinterpret_cast<const int32_t*>(p->ws + p->lay.colids_t);
+        P.values = reinterpret_cast<const float*>(p->ws + p->lay.values_t);
+    }
+    P.in = in;
+    P.out = out;
+    P.ld_in = ld_in;
+    P.ld_out = ld_out;
+    for (int r = 0; r < kRanges; ++r) {
+        P.wg_end[r] = sc.wg_end[r];
+        P.item_base[r] = sc.item_base[r];
+    }
+    P.lds_floats = p->knobs.lds_words;
+    P.pad = p->knobs.pad;
+    const bool vec4 = p->F % 4 == 0 && ld_in % 4 == 0 && ld_out % 4 == 0 &&
+                      (reinterpret_cast<uintptr_t>(in) & 15) == 0 &&
+                      (reinterpret_cast<uintptr_t>(out) & 15) == 0;
+    hipError_t e = launch_bspmm(P, sc.grid, p->knobs.lds_words * 4, vec4, s);
+    return e == hipSuccess ? BSPMM_OK : hip_fail(e);
+}
+
+}  // namespace
+
+extern "C" {
+
+int bspmm_workspace_bytes(const bspmm_batch* b, int32_t F, const bspmm_options* options,
+                          size_t* bytes)
+{
+    if (!bytes) return BSPMM_EINVAL;
+    *bytes = 0;
+    int rc = check_batch(b, F, false);
+    if (rc != BSPMM_OK) return rc;
+    bspmm_plan* p = new (std::nothrow) bspmm_plan;
+    if (!p) return BSPMM_EINVAL;
+    const bool dry = options && (options->flags & BSPMM_DRY_RUN);
+    rc = plan_host(*p, b, F, knobs_for(options, !dry));
+    if (rc == BSPMM_OK) *bytes = p->lay.total;
+    delete p;
+    return rc;
+}
+
+int bspmm_create(bspmm_plan** plan, const bspmm_batch* b, int32_t F,
+                 const bspmm_options* options, void* workspace, size_t workspace_bytes,
+                 void* stream)
+{
+    if (!plan) return BSPMM_EINVAL;
+    *plan = nullptr;
+    const bool dry = options && (options->flags & BSPMM_DRY_RUN);
+    int rc = check_batch(b, F, !dry);
+    if (rc != BSPMM_OK) return rc;
+    bspmm_plan* p = new (std::nothrow) bspmm_plan;
+    if (!p) return BSPMM_EINVAL;
+    p->dry = dry;
+    rc = plan_host(*p, b, F, knobs_for(options, !dry));
+    if (rc != BSPMM_OK) {
+        delete p;
+        return rc;
+    }
+    if (dry) {
+        *plan = p;
+        return BSPMM_OK;
+    }
+    if (options && (options->flags & BSPMM_FLOOR_PROBE))
+        for (int d = 0; d < 2; ++d)
+            for (WorkItem& w : p->sched[d].items) w.nrows = 0;
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & (kAlign - 1)) != 0) {
+        delete p;
+        return BSPMM_EINVAL;
+    }
+    if (workspace_bytes < p->lay.total) {
+        delete p;
+        return BSPMM_ENOSPACE;
+    }
+    p->rpt = b->rpt;
+    p->colids = b->colids;
+    p->values = b->values;
+    p->ws = static_cast<char*>(workspace);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    // The host tables stay alive inside the plan, so the asynchronous copies may read them
+    // at any time before bspmm_destroy.
+    hipError_t e = hipSuccess;
+    for (int d = 0; d < 2 && e == hipSuccess; ++d)
+        if (!p->sched[d].items.empty())
+            e = hipMemcpyAsync(p->ws + p->lay.items[d], p->sched[d].items.data(),
+                               p->sched[d].items.size() * sizeof(WorkItem),
+                               hipMemcpyHostToDevice, s);
+    if (e == hipSuccess && !p->records.empty())
+        e = hipMemcpyAsync(p->ws + p->lay.op_records, p->records.data(),
+                           p->records.size() * sizeof(OpRecord), hipMemcpyHostToDevice, s);
+    if (e != hipSuccess) {
+        delete p;
+        return hip_fail(e);
+    }
+    if (options && (options->flags & BSPMM_BUILD_TRANSPOSE) && p->transposed_supported) {
+        rc = enqueue_build(p, s);
+        if (rc != BSPMM_OK) {
+            delete p;
+            return rc;
+        }
+    }
+    *plan = p;
+    return BSPMM_OK;
+}
+
+int bspmm_run(bspmm_plan* plan, const float* B, float* C, int64_t ldb, int64_t ldc,
+              void* stream)
+{
+    if (!plan) return BSPMM_EINVAL;
+    if (plan->dry) return BSPMM_ESTATE;
+    return run_direction(plan, 0, B, C, ldb, ldc, static_cast<hipStream_t>(stream));
+}
+
+int bspmm_run_transposed(bspmm_plan* plan, const float* dY, float* G, int64_t ldy, int64_t ldg,
+                         void* stream)
+{
+    if (!plan) return BSPMM_EINVAL;
+    if (plan->dry || !plan->transposed_supported) return BSPMM_ESTATE;
+    if (plan->sched[1].grid > 0 && (!dY || !G || ldy < plan->F || ldg < plan->F))
+        return BSPMM_EINVAL;
+    int rc = enqueue_build(plan, static_cast<hipStream_t>(stream));
+    if (rc != BSPMM_OK) return rc;
+    return run_direction(plan, 1, dY, G, ldy, ldg, static_cast<hipStream_t>(stream));
+}
+
+int bspmm_export_transposed(bspmm_plan* plan, int32_t* rpt_t, int32_t* colids_t,
+                            float* values_t, void* stream)
+{
+    if (!plan) return BSPMM_EINVAL;
+    if (plan->dry) return BSPMM_ESTATE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    int rc = enqueue_build(plan, s);
+    if (rc != BSPMM_OK) return rc;
+    size_t rpt_words = 0, nz = 0;
+    for (int i = 0; i < plan->batch; ++i) {
+        rpt_words += (size_t)plan->dir[1].m[i] + 1;
+        nz += (size_t)plan->dir[1].nnz[i];
+    }
+    hipError_t e = hipSuccess;
+    if (rpt_words) {
+        if (!rpt_t) return BSPMM_EINVAL;
+        e = hipMemcpyAsync(rpt_t, plan->ws + plan->lay.rpt_t, rpt_words * 4,
+                           hipMemcpyDeviceToDevice, s);
+    }
+    if (e == hipSuccess && nz) {
+        if (!colids_t || !values_t) return BSPMM_EINVAL;
+        e = hipMemcpyAsync(colids_t, plan->ws + plan->lay.colids_t, nz * 4,
+                           hipMemcpyDeviceToDevice, s);
+        if (e == hipSuccess)
+            e = hipMemcpyAsync(values_t, plan->ws + plan->lay.values_t, nz * 4,
+                               hipMemcpyDeviceToDevice, s);
+    }
+    return e == hipSuccess ? BSPMM_OK : hip_fail(e);
+}
+
+int bspmm_validate(bspmm_plan* plan, int32_t* bad_op, void* stream)
+{
+    if (!plan) return BSPMM_EINVAL;
+    if (plan->dry) return BSPMM_ESTATE;
+    if (bad_op) *bad_op = -1;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    int32_t* flag = reinterpret_cast<int32_t*>(plan->ws + plan->lay.flag);
+    hipError_t e = launch_validate(reinterpret_cast<const OpRecord*>(plan->ws + plan->lay.op_records),
+                                   plan->batch, plan->rpt, plan->colids, flag, s);
+    if (e != hipSuccess) return hip_fail(e);
+    int32_t host_flag = 0;
+    e = hipMemcpyAsync(&host_flag, flag, 4, hipMemcpyDeviceToHost, s);
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
+    if (e != hipSuccess) return hip_fail(e);
+    if (host_flag != 0x7fffffff) {
+        if (bad_op) *bad_op = host_flag;
+        return BSPMM_EBADCSR;
+    }
+    return BSPMM_OK;
+}
+
+int bspmm_plan_info(const bspmm_plan* plan, bspmm_info* info)
+{
+    if (!plan || !info) return BSPMM_EINVAL;
+    std::memset(info, 0, sizeof(*info));
+    info->batch = plan->batch;
+    info->F = plan->F;
+    info->lds_bytes = plan->knobs.lds_words * 4;
+    info->compute_units = plan->knobs.compute_units;
+    for (int d = 0; d < 2; ++d) {
+        info->tile[d] = plan->sched[d].tile;
+        info->workgroups[d] = plan->sched[d].grid;
+        info->items[d] = (int32_t)plan->sched[d].view.size();
+        for (int b = 0; b < BSPMM_NUM_BINS; ++b)
+            info->items_in_bin[d][b] = plan->sched[d].items_in_bin[b];
+        info->effective_bytes[d] = plan->effective_bytes[d];
+    }
+    info->transposed_supported = plan->transposed_supported ? 1 : 0;
+    info->transposed_built = plan->transposed_built ? 1 : 0;
+    info->flops = plan->flops;
+    info->workspace_bytes = plan->lay.total;
+    return BSPMM_OK;
+}
+
+int bspmm_plan_items(const bspmm_plan* plan, int32_t transposed, bspmm_item* items,
+                     int32_t capacity, int32_t* count)
+{
+    if (!plan || !count || capacity < 0 || (capacity > 0 && !items)) return BSPMM_EINVAL;
+    const std::vector<bspmm_item>& v = plan->sched[transposed ? 1 : 0].view;
+    *count = (int32_t)v.size();
+    const size_t n = std::min<size_t>(v.size(), (size_t)capacity);
+    if (n) std::memcpy(items, v.data(), n * sizeof(bspmm_item));
+    return BSPMM_OK;
+}
+
+void bspmm_destroy(bspmm_plan* plan) { delete plan; }
+
+const char* bspmm_strerror(int code)
+{
+    switch (code) {
+        case BSPMM_OK: return "ok";
+        case BSPMM_EINVAL: return "invalid argument";
+        case BSPMM_ENOSPACE: return "workspace too small";
+        case BSPMM_EHIP: return "HIP runtime error";
+        case BSPMM_EOVERLAP: return "output blocks overlap";
+        case BSPMM_ESTATE: return "operation not available on this plan";
+        case BSPMM_EBADCSR: return "malformed CSR arrays on the device";
+        default: return "unknown error";
+    }
+}
+
+int bspmm_last_hip_error(void) { return g_last_hip_error; }
+
+}  // extern "C"

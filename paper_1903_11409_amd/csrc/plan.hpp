@@ -1,0 +1,107 @@
+// Internal structures shared by the host scheduler and the device kernels of libbspmm.
+// Not part of the public ABI (see include/bspmm.h for that).
+#pragma once
+
+#include <stdint.h>
+
+#if defined(__HIPCC__)
+#define BSPMM_HD __host__ __device__
+#else
+#define BSPMM_HD
+#endif
+
+namespace bspmm {
+
+constexpr int kThreads = 256;      // lanes per workgroup (4 wavefronts of 64)
+constexpr int kRanges = 4;         // launch ranges by slot size: 256, 64, 32, 16 lanes
+constexpr int kMaxLdsBytes = 64 * 1024;
+
+// Slot size (lanes) of launch range r, and its log2.
+BSPMM_HD constexpr int range_log2_slot(int r) { return r == 0 ? 8 : (r == 1 ? 6 : (r == 2 ? 5 : 4)); }
+
+// One unit of work: the rows [row0, row0+nrows) of one operation restricted to the feature
+// columns [f0, f0+fw).  64 bytes so one item is a single 64-byte fetch.
+struct alignas(16) WorkItem {
+    int64_t rpt_off;      // element offset of the operation's row pointers
+    int64_t nz_off;       // element offset of the operation's entries
+    int64_t in_row_off;   // first row of the dense input block
+    int64_t out_row_off;  // first row of the dense output block
+    int32_t m;            // output rows of the operation
+    int32_t k;            // dense-input rows of the operation (columns of the sparse matrix)
+    int32_t nnz;          // stored entries of the operation
+    int32_t row0;         // first output row of this item
+    int32_t nrows;        // output rows of this item (0 = empty item)
+    int32_t f0;           // first feature column
+    int32_t fw;           // feature columns
+    int32_t staged;       // 1: operands staged in LDS (whole operation, row0 == 0); 0: generic
+};
+static_assert(sizeof(WorkItem) == 64, "WorkItem must be 64 bytes");
+
+// Kernel argument block, passed by value.  Workgroup w belongs to range r when
+// wg_end[r-1] <= w < wg_end[r]; its first item is item_base[r] + (w - wg_end[r-1]) * slots(r).
+struct LaunchParams {
+    const WorkItem* items;
+    const int32_t* rpt;
+    const int32_t* colids;
+    const float* values;
+    const float* in;
+    float* out;
+    int64_t ld_in;
+    int64_t ld_out;
+    int32_t wg_end[kRanges];
+    int32_t item_base[kRanges];
+    int32_t lds_floats;   // LDS per workgroup, in 4-byte words
+    int32_t pad;          // words added to every staged dense row
+};
+
+// Per-operation record of the transposed-CSR build and of the validation kernel.
+struct alignas(8) OpRecord {
+    int64_t rpt_off;
+    int64_t nz_off;
+    int64_t rpt_t_off;     // element offset of the transposed row pointers
+    int64_t nz_t_off;      // element offset of the transposed entries
+    int64_t scratch_off;   // element offset into the global scratch, or -1 to use LDS
+    int32_t m;
+    int32_t k;
+    int32_t nnz;
+    int32_t pad_;
+};
+
+BSPMM_HD inline int round_up(int x, int a) { return (x + a - 1) / a * a; }
+
+BSPMM_HD inline int pow2_ceil(int x)
+{
+    int p = 1;
+    while (p < x) p <<= 1;
+    return p;
+}
+
+// LDS layout of a staged item, in 4-byte words from the start of its slot:
+//   [0, m+1)                      row pointers (clamped to nnz)
+//   [cv_off, cv_off + 2*nnz)      (column, value) pairs
+//   [b_off, b_off + k*stride)     dense tile, row stride `stride`
+struct StagedLayout {
+    int cv_off;
+    int b_off;
+    int stride;
+    int total;
+};
+
+BSPMM_HD inline StagedLayout staged_layout(int m, int k, int nnz, int fw, int pad)
+{
+    StagedLayout L;
+    L.cv_off = round_up(m + 1, 2);
+    L.b_off = round_up(L.cv_off + 2 * nnz, 4);
+    L.stride = round_up(fw, 4) + pad;
+    L.total = L.b_off + k * L.stride;
+    return L;
+}
+
+// Lanes that share one output row: enough 4-float vectors to cover the tile, a power of two.
+BSPMM_HD inline int lanes_per_row(int fw, int vec)
+{
+    int g = pow2_ceil((fw + vec - 1) / vec);
+    return g > 64 ? 64 : g;
+}
+
+}  // namespace bspmm

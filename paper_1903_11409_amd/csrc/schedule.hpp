@@ -1,0 +1,48 @@
+// Host-side batch scheduler of libbspmm: bins operations by size, tiles the feature
+// dimension, orders the work largest-first and maps it onto workgroups XCD-aware.
+#pragma once
+
+#include <cstdint>
+#include <vector>
+
+#include "../../include/bspmm.h"
+#include "plan.hpp"
+
+namespace bspmm {
+
+// The operations of one direction (forward, or transposed with the roles swapped).
+struct DirOps {
+    std::vector<int32_t> m, k, nnz;
+    std::vector<int64_t> rpt_off, nz_off, in_off, out_off;
+    int size() const { return (int)m.size(); }
+};
+
+// Scheduler knobs with defaults filled in.
+struct Knobs {
+    int force_bin = -1;       // -1 automatic, else BSPMM_BIN_*
+    int lds_words = 8192;     // 32 KiB
+    int min_tile = 32;
+    int max_tile = 256;
+    int target_wgs = 1024;
+    int compute_units = 256;
+    int pad = 0;
+    int max_passes = 2;
+    int generic_rows = 32;
+};
+
+struct Schedule {
+    std::vector<WorkItem> items;     // device table, launch order, padded with empty items
+    std::vector<bspmm_item> view;    // the non-empty items, for inspection
+    int32_t wg_end[kRanges] = {0, 0, 0, 0};
+    int32_t item_base[kRanges] = {0, 0, 0, 0};
+    int grid = 0;
+    int tile = 0;
+    int items_in_bin[BSPMM_NUM_BINS] = {0, 0, 0, 0, 0};
+};
+
+Knobs resolve_knobs(const bspmm_options* o);
+
+// Build the single-launch schedule for `ops` at feature width F.
+Schedule make_schedule(const DirOps& ops, int F, const Knobs& kn);
+
+}  // namespace bspmm

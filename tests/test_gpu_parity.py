@@ -1,0 +1,301 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle, element by
+element on the same seeded inputs.
+
+Bar (fp32 path, fp64 oracle): |C_gpu - C_ref| <= 1e-5 * S per element with
+S = sum_k |A_ik| |B_kj|; where S == 0 (rows without entries) the GPU value must be exactly 0.
+fp32 FMA accumulation of a row with d entries is off by at most about d * 2^-24 * S
+(6e-8 * d), so 1e-5 leaves room for rows of more than a hundred entries.
+Index work (the transposed CSR) is compared bit for bit.
+"""
+import dataclasses
+
+import numpy as np
+import pytest
+
+from paper_1903_11409_amd import bspmm as K
+from paper_1903_11409_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-5
+SENTINEL = -12345.0
+
+
+@pytest.fixture(scope="module")
+def torch_cuda():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    K.lib()   # raises if the HIP library has not been built: no fallback
+    return torch
+
+
+def _owned_rows(off, length, n):
+    m = np.zeros(n, dtype=bool)
+    for o, l in zip(off, length):
+        m[int(o):int(o) + int(l)] = True
+    return m
+
+
+def _assert_close(got, ref, scale, owned, what):
+    got = got.astype(np.float64)
+    assert np.all(got[~owned] == SENTINEL), f"{what}: rows outside every operation were written"
+    g, r, s = got[owned], ref[owned], scale[owned]
+    assert not np.any(np.isnan(g)), f"{what}: NaN in output"
+    err = np.abs(g - r)
+    bad = err > TOL * s
+    assert not np.any(bad), (f"{what}: {int(bad.sum())} elements beyond 1e-5*S, worst "
+                             f"ratio {float((err / np.maximum(s, 1e-300)).max()):.3e}")
+    assert np.all(g[s == 0.0] == 0.0), f"{what}: nonzero where no entry contributes"
+
+
+def _forward(torch, b, opts=None, ld_extra=0, offset=0):
+    plan = K.Plan(b, options=opts)
+    ld = b.F + ld_extra
+    Bd = torch.zeros((b.n_b_rows, ld), dtype=torch.float32, device="cuda")
+    Bd[:, :b.F] = torch.from_numpy(b.B).cuda()
+    store = torch.full((b.n_c_rows * ld + offset + 8,), SENTINEL, dtype=torch.float32, device="cuda")
+    Cd = store[offset:offset + b.n_c_rows * ld].view(b.n_c_rows, ld)
+    plan.run(Bd, Cd)
+    torch.cuda.synchronize()
+    out = Cd[:, :b.F].cpu().numpy()
+    if ld_extra:
+        assert torch.all(Cd[:, b.F:] == SENTINEL)
+    assert float(store[offset + b.n_c_rows * ld:].min()) == SENTINEL
+    return plan, out
+
+
+def _transposed(torch, b, opts=None, plan=None):
+    plan = plan or K.Plan(b, options=opts)
+    Yd = torch.from_numpy(b.dY).cuda()
+    Gd = torch.full((b.n_b_rows, b.F), SENTINEL, dtype=torch.float32, device="cuda")
+    plan.run_transposed(Yd, Gd)
+    torch.cuda.synchronize()
+    return plan, Gd.cpu().numpy()
+
+
+def _check_forward(torch, oracle, b, opts=None, what="", **kw):
+    plan, got = _forward(torch, b, opts, **kw)
+    ref, S = oracle.forward_batch(b)
+    _assert_close(got, ref, S, _owned_rows(b.c_row_off, b.rows, b.n_c_rows), what or b.name)
+    return plan, got
+
+
+def _check_transposed(torch, oracle, b, opts=None, what="", plan=None):
+    plan, got = _transposed(torch, b, opts, plan)
+    ref, S = oracle.transposed_batch(b)
+    _assert_close(got, ref, S, _owned_rows(b.b_row_off, b.cols, b.n_b_rows),
+                  (what or b.name) + " transposed")
+    return plan, got
+
+
+# ---------------------------------------------------------------------------------------------
+# the five workload configurations at full size
+# ---------------------------------------------------------------------------------------------
+
+def test_config1_tiny(torch_cuda, oracle):
+    b = W.config1_tiny()
+    plan, _ = _check_forward(torch_cuda, oracle, b)
+    assert plan.validate() == -1
+
+
+@pytest.mark.parametrize("F", [64, 128])
+def test_config2_molecule(torch_cuda, oracle, F):
+    b = W.config2_molecule(F=F)
+    plan, _ = _check_forward(torch_cuda, oracle, b)
+    info = plan.info()
+    assert info.workgroups[0] > 0 and info.items_in_bin[0][K.BIN_GENERIC] == 0
+
+
+def test_config3_multichannel_shared_input(torch_cuda, oracle):
+    b = W.config3_multichannel()
+    plan, got = _check_forward(torch_cuda, oracle, b)
+    assert plan.info().transposed_supported == 0
+    with pytest.raises(K.BspmmError) as e:
+        plan.run_transposed(torch_cuda.zeros((b.n_c_rows, b.F), device="cuda"),
+                            torch_cuda.zeros((b.n_b_rows, b.F), device="cuda"))
+    assert e.value.code == K.ESTATE
+    # row-normalised channels: with B = 1 the rows that have an edge of the channel give 1
+    ones = dataclasses.replace(b, B=np.ones_like(b.B))
+    _, c1 = _forward(torch_cuda, ones)
+    has = np.concatenate([np.diff(b.op_csr(i)[0]) > 0 for i in range(b.batch)])
+    assert np.allclose(c1[has], 1.0, rtol=1e-6) and np.all(c1[~has] == 0.0)
+
+
+@pytest.mark.parametrize("F", [256, 512, 1024])
+def test_config4_wide(torch_cuda, oracle, F):
+    b = W.config4_wide(F=F)
+    _check_forward(torch_cuda, oracle, b)
+
+
+def test_config5_skewed_forward_and_backward(torch_cuda, oracle):
+    b = W.config5_skewed()
+    plan, _ = _check_forward(torch_cuda, oracle, b)
+    info = plan.info()
+    assert info.items_in_bin[0][K.BIN_GENERIC] > 0      # the largest graphs leave LDS
+    _check_transposed(torch_cuda, oracle, b, plan=plan)
+    assert plan.info().transposed_built == 1
+
+
+def test_config5_asymmetric_twin_catches_a_missing_transpose(torch_cuda, oracle):
+    b = W.config5_skewed(asymmetric=True)
+    plan, got = _check_transposed(torch_cuda, oracle, b)
+    # the forward product of the same dense operand is NOT within tolerance of A^T dY
+    as_fwd = dataclasses.replace(b, B=b.dY)
+    wrong, S = oracle.forward_batch(as_fwd)
+    assert np.mean(np.abs(got - wrong) > TOL * S) > 0.5
+
+
+# ---------------------------------------------------------------------------------------------
+# index work: the device-built transposed CSR, bit for bit
+# ---------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("maker", [
+    lambda: W.config5_skewed(graphs=200, F=4, asymmetric=True),
+    lambda: W.random_general(77, F=4, shapes=[(9, 5, 40), (5, 9, 40), (30, 30, 0), (1, 1, 1),
+                                              (0, 0, 0), (17, 17, 60), (300, 200, 5000)]),
+    lambda: W.hub_batch(5, F=4, n=700),
+    # large enough that counters + positions exceed LDS: the build falls back to global scratch
+    lambda: W.random_general(78, F=4, shapes=[(4000, 3000, 20000), (10, 10, 30)]),
+])
+def test_transposed_csr_bit_exact(torch_cuda, oracle, maker):
+    b = maker()
+    plan = K.Plan(b, options=K.make_options(flags=K.BUILD_TRANSPOSE))
+    rt, ct, vt = plan.export_transposed()
+    torch_cuda.cuda.synchronize()
+    _, ert, ect, evt = oracle.csr_transpose(b.rows, b.cols, b.nnz, b.rpt_off, b.nz_off, b.rpt,
+                                            b.colids, b.values)
+    assert np.array_equal(rt.cpu().numpy(), ert)
+    # the oracle packs the transposed entries like the input; so do the generators (dense)
+    assert np.array_equal(ct.cpu().numpy(), ect)
+    assert np.array_equal(vt.cpu().numpy(), evt)
+    _check_transposed(torch_cuda, oracle, b, plan=plan)
+
+
+# ---------------------------------------------------------------------------------------------
+# edge cases
+# ---------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("F", [1, 3, 4, 5, 63, 64, 65, 100, 260])
+def test_ragged_shapes_unsorted_duplicates(torch_cuda, oracle, F):
+    shapes = [(1, 1, 1), (0, 0, 0), (7, 13, 25), (13, 7, 25), (40, 40, 0), (300, 300, 2000),
+              (2, 900, 50), (900, 2, 50), (64, 64, 64), (65, 63, 400), (5, 5, 100)]
+    b = W.random_general(500 + F, F=F, shapes=shapes, shuffle_blocks=True)
+    plan, _ = _check_forward(torch_cuda, oracle, b, what=f"general F={F}")
+    _check_transposed(torch_cuda, oracle, b, plan=plan, what=f"general F={F}")
+
+
+def test_identity_is_bitwise_and_hub_rows(torch_cuda, oracle):
+    b = W.identity_batch(7, F=128, sizes=[1, 5, 33, 200, 700])
+    _, got = _forward(torch_cuda, b)
+    assert np.array_equal(got, b.B)
+    h = W.hub_batch(9, F=64, n=600)
+    plan, _ = _check_forward(torch_cuda, oracle, h)
+    _check_transposed(torch_cuda, oracle, h, plan=plan)
+    small_hub = W.hub_batch(10, F=32, n=100, copies=5)
+    _check_forward(torch_cuda, oracle, small_hub)
+
+
+def test_empty_batch_and_all_empty_matrices(torch_cuda, oracle):
+    e = W.random_general(1, F=8, shapes=[])
+    plan = K.Plan(e)
+    plan.run(torch_cuda.zeros((1, 8), device="cuda"), torch_cuda.zeros((1, 8), device="cuda"))
+    z = W.random_general(2, F=16, shapes=[(10, 10, 0), (33, 4, 0)])
+    _, got = _check_forward(torch_cuda, oracle, z)
+    assert np.all(got == 0.0)
+
+
+@pytest.mark.parametrize("bin_", [K.BIN_WORKGROUP, K.BIN_WAVE, K.BIN_SLICE32, K.BIN_SLICE16,
+                                  K.BIN_GENERIC])
+@pytest.mark.parametrize("F", [16, 64, 128])
+def test_every_bin_alone(torch_cuda, oracle, bin_, F):
+    b = W.config2_molecule(graphs=64, F=F)
+    b = dataclasses.replace(b, dY=np.random.default_rng(1).standard_normal(
+        (b.n_c_rows, F)).astype(np.float32))
+    plan, _ = _check_forward(torch_cuda, oracle, b, K.make_options(force_bin=bin_),
+                             what=f"bin {K.BIN_NAMES[bin_]} F={F}")
+    _check_transposed(torch_cuda, oracle, b, plan=plan)
+
+
+@pytest.mark.parametrize("kw", [{"lds_pad": 4}, {"lds_pad": 8}, {"min_tile": 16},
+                                {"max_tile": 64}, {"lds_bytes": 65536}, {"lds_bytes": 8192},
+                                {"target_workgroups": 64}, {"max_passes": 4},
+                                {"generic_rows": 8, "lds_bytes": 4096}])
+def test_scheduler_knobs_do_not_change_results(torch_cuda, oracle, kw):
+    b = W.config5_skewed(graphs=96, F=128)
+    plan, _ = _check_forward(torch_cuda, oracle, b, K.make_options(**kw), what=str(kw))
+    _check_transposed(torch_cuda, oracle, b, plan=plan, what=str(kw))
+
+
+def test_scalar_path_for_unaligned_operands(torch_cuda, oracle):
+    b = W.config2_molecule(graphs=32, F=64)
+    _check_forward(torch_cuda, oracle, b, ld_extra=3, what="ld = F+3")
+    _check_forward(torch_cuda, oracle, b, offset=1, what="C misaligned by one float")
+    _check_forward(torch_cuda, oracle, b, ld_extra=4, offset=4, what="ld = F+4, aligned")
+
+
+def test_run_to_run_determinism(torch_cuda):
+    b = W.config5_skewed(graphs=256, F=128)
+    _, a = _forward(torch_cuda, b)
+    _, c = _forward(torch_cuda, b)
+    assert np.array_equal(a, c)
+    plan, g1 = _transposed(torch_cuda, b)
+    _, g2 = _transposed(torch_cuda, b)
+    assert np.array_equal(g1, g2)
+
+
+def test_linearity_and_relabelling_on_the_gpu(torch_cuda, oracle):
+    b = W.config2_molecule(graphs=32, F=32)
+    rng = np.random.default_rng(4)
+    B1 = (np.round(rng.uniform(-1, 1, b.B.shape) * 1024) / 1024).astype(np.float32)
+    B2 = (np.round(rng.uniform(-1, 1, b.B.shape) * 1024) / 1024).astype(np.float32)
+    comb = (2.0 * B1 - 0.5 * B2).astype(np.float32)
+    _, c1 = _forward(torch_cuda, dataclasses.replace(b, B=B1))
+    _, c2 = _forward(torch_cuda, dataclasses.replace(b, B=B2))
+    _, c12 = _forward(torch_cuda, dataclasses.replace(b, B=comb))
+    _, S = oracle.forward_batch(dataclasses.replace(b, B=np.abs(B1) * 2 + np.abs(B2) * 0.5))
+    assert np.all(np.abs(c12.astype(np.float64) - (2.0 * c1.astype(np.float64) - 0.5 * c2)) <= 3 * TOL * S)
+
+
+def test_validate_finds_the_malformed_operation(torch_cuda):
+    b = W.config2_molecule(graphs=16, F=32)
+    plan = K.Plan(b)
+    assert plan.validate() == -1
+    bad = dataclasses.replace(b, colids=b.colids.copy())
+    z0 = int(b.nz_off[5])
+    bad.colids[z0 + 1] = int(b.cols[5])          # one past the last valid column
+    assert K.Plan(bad).validate() == 5
+    bad2 = dataclasses.replace(b, rpt=b.rpt.copy())
+    r0 = int(b.rpt_off[9])
+    bad2.rpt[r0 + 2], bad2.rpt[r0 + 3] = b.rpt[r0 + 3] + 1, b.rpt[r0 + 2]   # not monotone
+    assert K.Plan(bad2).validate() == 9
+
+
+def test_run_argument_errors(torch_cuda):
+    b = W.config1_tiny()
+    plan = K.Plan(b)
+    Bd = torch_cuda.zeros((b.n_b_rows, b.F), device="cuda")
+    Cd = torch_cuda.zeros((b.n_c_rows, b.F), device="cuda")
+    with pytest.raises(K.BspmmError) as e:
+        K.bspmm_run(plan.handle, Bd, Cd, b.F - 1, b.F)
+    assert e.value.code == K.EINVAL
+    with pytest.raises(K.BspmmError) as e:
+        K.bspmm_run(plan.handle, None, Cd, b.F, b.F)
+    assert e.value.code == K.EINVAL
+    hb = plan.hb
+    with pytest.raises(K.BspmmError) as e:
+        K.bspmm_create(hb, b.F, None, plan.workspace, 256)
+    assert e.value.code == K.ENOSPACE
+
+
+def test_non_default_stream(torch_cuda, oracle):
+    b = W.config2_molecule(graphs=32, F=64)
+    s = torch_cuda.cuda.Stream()
+    with torch_cuda.cuda.stream(s):
+        plan = K.Plan(b)
+        Bd = torch_cuda.from_numpy(b.B).cuda()
+        Cd = torch_cuda.full((b.n_c_rows, b.F), SENTINEL, dtype=torch_cuda.float32, device="cuda")
+        plan.run(Bd, Cd)
+    s.synchronize()
+    ref, S = oracle.forward_batch(b)
+    _assert_close(Cd.cpu().numpy(), ref, S, _owned_rows(b.c_row_off, b.rows, b.n_c_rows), "stream")

@@ -1,0 +1,231 @@
+"""Host logic of libbspmm without a GPU: exported symbols, argument checking, and the
+scheduler's invariants (every output element of every operation is computed exactly once,
+staged items fit their LDS share, workgroups are well formed)."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_1903_11409_amd import bspmm as K
+from paper_1903_11409_amd import build as B
+from paper_1903_11409_amd import workloads as W
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _built():
+    if not os.path.exists(K.LIB_PATH):
+        B.build()
+
+
+def test_library_exports_every_declared_symbol():
+    text = open(os.path.join(ROOT, "include", "bspmm.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = set(re.findall(r"\b(bspmm_[a-z_]+)\s*\(", text))
+    assert declared == set(K.EXPORTS)
+    raw = ctypes.CDLL(K.LIB_PATH)
+    for name in declared:
+        assert hasattr(raw, name), name
+
+
+def test_struct_sizes_match_header():
+    assert ctypes.sizeof(K.bspmm_item) == 32
+    assert ctypes.sizeof(K.bspmm_options) == 40
+    assert ctypes.sizeof(K.bspmm_batch) == 8 + 10 * 8
+    assert ctypes.sizeof(K.bspmm_info) == 16 + 8 + 8 + 8 + 40 + 8 + 16 + 8 + 8
+
+
+def _slot_lanes(bin_):
+    return {K.BIN_WORKGROUP: 256, K.BIN_WAVE: 64, K.BIN_SLICE32: 32, K.BIN_SLICE16: 16,
+            K.BIN_GENERIC: 256}[bin_]
+
+
+def _lds_words(m, k, nnz, fw, pad):
+    cv = (m + 1 + 1) // 2 * 2
+    b_off = (cv + 2 * nnz + 3) // 4 * 4
+    return b_off + k * ((fw + 3) // 4 * 4 + pad)
+
+
+def _check_schedule(b, F, transposed=False, **opts):
+    h = K.dry_plan(b, F, **opts)
+    try:
+        info = K.bspmm_plan_info(h)
+        items = K.bspmm_plan_items(h, transposed)
+        d = 1 if transposed else 0
+        assert info.items[d] == len(items)
+        m_of = b.cols if transposed else b.rows
+        k_of = b.rows if transposed else b.cols
+        cover = [np.zeros((int(m), F), dtype=np.int32) for m in m_of]
+        seen = set()
+        pad = max(opts.get("lds_pad", 0), 0)
+        for it in items:
+            assert 0 <= it.op < b.batch
+            assert it.nrows > 0 and it.fw > 0
+            cover[it.op][it.row0:it.row0 + it.nrows, it.f0:it.f0 + it.fw] += 1
+            lanes = _slot_lanes(it.bin)
+            assert 0 <= it.slot < 256 // lanes
+            assert 0 <= it.workgroup < info.workgroups[d]
+            assert (it.workgroup, it.slot) not in seen
+            seen.add((it.workgroup, it.slot))
+            if it.bin != K.BIN_GENERIC:
+                assert it.row0 == 0 and it.nrows == int(m_of[it.op])
+                need = _lds_words(int(m_of[it.op]), int(k_of[it.op]), int(b.nnz[it.op]), it.fw, pad)
+                assert need * 4 <= info.lds_bytes * lanes // 256
+                if F % 4 == 0:
+                    assert it.f0 % 4 == 0 and it.fw % 4 == 0
+        for c in cover:
+            assert np.all(c == 1)
+        # sub-workgroup ranges come after the one-item-per-workgroup range, smaller slots last
+        order = {K.BIN_WORKGROUP: 0, K.BIN_GENERIC: 0, K.BIN_WAVE: 1, K.BIN_SLICE32: 2,
+                 K.BIN_SLICE16: 3}
+        hi = [-1, -1, -1, -1]
+        lo = [10 ** 9] * 4
+        for it in items:
+            r = order[it.bin]
+            hi[r] = max(hi[r], it.workgroup)
+            lo[r] = min(lo[r], it.workgroup)
+        prev = -1
+        for r in range(4):
+            if hi[r] >= 0:
+                assert lo[r] > prev
+                prev = hi[r]
+        return info, items
+    finally:
+        K.bspmm_destroy(h)
+
+
+@pytest.mark.parametrize("cfg,kw", [(1, {}), (2, {"F": 64}), (2, {"F": 128}),
+                                    (3, {"graphs": 96}), (4, {"F": 256, "graphs": 32}),
+                                    (4, {"F": 1024, "graphs": 32}), (5, {"graphs": 128})])
+def test_every_output_element_scheduled_once(cfg, kw):
+    b = W.CONFIGS[cfg](**kw)
+    info, _ = _check_schedule(b, b.F)
+    assert info.flops == W.flops(b)
+    assert info.effective_bytes[0] == W.effective_bytes(b)
+    if info.transposed_supported:
+        _check_schedule(b, b.F, transposed=True)
+        assert info.effective_bytes[1] == W.effective_bytes(b, transposed=True)
+
+
+@pytest.mark.parametrize("F", [1, 3, 4, 5, 63, 64, 65, 100, 260, 1000])
+def test_odd_feature_widths_and_shapes(F):
+    shapes = [(1, 1, 1), (0, 0, 0), (7, 13, 25), (13, 7, 25), (40, 40, 0), (300, 300, 2000),
+              (2, 900, 50), (900, 2, 50)]
+    b = W.random_general(F, F=F, shapes=shapes, with_dY=False)
+    _check_schedule(b, F)
+    _check_schedule(b, F, transposed=True)
+
+
+@pytest.mark.parametrize("bin_", [K.BIN_WORKGROUP, K.BIN_WAVE, K.BIN_SLICE32, K.BIN_SLICE16,
+                                  K.BIN_GENERIC])
+def test_forced_bins_still_cover(bin_):
+    b = W.config2_molecule(graphs=48, F=64)
+    info, items = _check_schedule(b, 64, force_bin=bin_)
+    if bin_ in (K.BIN_WORKGROUP, K.BIN_GENERIC):
+        assert all(it.bin == bin_ for it in items)
+    else:
+        assert any(it.bin == bin_ for it in items)
+
+
+@pytest.mark.parametrize("opts", [{"lds_pad": 4}, {"min_tile": 16}, {"max_tile": 64},
+                                  {"lds_bytes": 65536}, {"lds_bytes": 8192},
+                                  {"target_workgroups": 64}, {"max_passes": 4},
+                                  {"generic_rows": 8, "lds_bytes": 4096}])
+def test_knobs_keep_the_invariants(opts):
+    b = W.config5_skewed(graphs=64, F=128)
+    _check_schedule(b, 128, **opts)
+
+
+def test_generic_row_blocks_share_an_xcd():
+    """Row blocks of a large operation read one dense tile: their workgroup indices agree
+    modulo 8 (workgroups are dealt round-robin to the 8 XCDs)."""
+    b = W.random_general(3, F=256, shapes=[(700, 700, 5000), (30, 30, 90), (650, 650, 3000)],
+                         with_dY=False)
+    info, items = _check_schedule(b, 256)
+    for op in (0, 2):
+        for f0 in {it.f0 for it in items if it.op == op}:
+            mods = {it.workgroup % 8 for it in items if it.op == op and it.f0 == f0}
+            assert len(mods) == 1
+            assert all(it.bin == K.BIN_GENERIC for it in items if it.op == op)
+
+
+def test_channels_of_one_graph_share_an_xcd_or_workgroup():
+    b = W.config3_multichannel(graphs=40)
+    info, items = _check_schedule(b, b.F)
+    by_block = {}
+    for it in items:
+        by_block.setdefault((int(b.b_row_off[it.op]), it.f0), []).append(it)
+    for group in by_block.values():
+        wgs = {it.workgroup for it in group}
+        if all(it.bin == K.BIN_WORKGROUP for it in group):
+            assert len({w % 8 for w in wgs}) == 1
+
+
+def test_argument_errors():
+    b = W.config1_tiny()
+
+    def create(**over):
+        f = dict(rows=b.rows, cols=b.cols, nnz=b.nnz, rpt_off=b.rpt_off, nz_off=b.nz_off,
+                 b_row_off=b.b_row_off, c_row_off=b.c_row_off)
+        f.update(over)
+        hb = K.HostBatch(**f)
+        return K.bspmm_create(hb, over.get("F", 64), K.make_options(flags=K.DRY_RUN))
+
+    bad_rows = b.rows.copy()
+    bad_rows[2] = -1
+    with pytest.raises(K.BspmmError) as e:
+        create(rows=bad_rows)
+    assert e.value.code == K.EINVAL
+    overlap = b.c_row_off.copy()
+    overlap[1] = overlap[0] + 1
+    with pytest.raises(K.BspmmError) as e:
+        create(c_row_off=overlap)
+    assert e.value.code == K.EOVERLAP
+    neg = b.nz_off.copy()
+    neg[0] = -5
+    with pytest.raises(K.BspmmError) as e:
+        create(nz_off=neg)
+    assert e.value.code == K.EINVAL
+    hb = K.HostBatch(b.rows, b.cols, b.nnz, b.rpt_off, b.nz_off, b.b_row_off, b.c_row_off)
+    with pytest.raises(K.BspmmError) as e:
+        K.bspmm_create(hb, 0, K.make_options(flags=K.DRY_RUN))
+    assert e.value.code == K.EINVAL
+    # without DRY_RUN the device pointers and a workspace are required
+    with pytest.raises(K.BspmmError) as e:
+        K.bspmm_create(hb, 64, K.make_options(), None, 0, stream=0)
+    assert e.value.code == K.EINVAL
+    assert K.lib().bspmm_strerror(K.EOVERLAP) == b"output blocks overlap"
+    assert K.lib().bspmm_run(None, None, None, 1, 1, None) == K.EINVAL
+
+
+def test_dry_plan_refuses_to_run_and_shared_inputs_disable_transposed():
+    b = W.config3_multichannel(graphs=8)
+    h = K.dry_plan(b)
+    try:
+        info = K.bspmm_plan_info(h)
+        assert info.transposed_supported == 0
+        assert info.workgroups[1] == 0
+        assert K.lib().bspmm_run(h, 1, 1, 128, 128, None) == K.ESTATE
+        assert K.lib().bspmm_run_transposed(h, 1, 1, 128, 128, None) == K.ESTATE
+    finally:
+        K.bspmm_destroy(h)
+
+
+def test_empty_batch_and_workspace_size():
+    e = W.random_general(1, F=8, shapes=[], with_dY=False)
+    h = K.dry_plan(e)
+    info = K.bspmm_plan_info(h)
+    assert info.workgroups[0] == 0 and info.items[0] == 0
+    K.bspmm_destroy(h)
+    b = W.config2_molecule(graphs=16)
+    hb = K.HostBatch(b.rows, b.cols, b.nnz, b.rpt_off, b.nz_off, b.b_row_off, b.c_row_off)
+    o = K.make_options(flags=K.DRY_RUN)
+    n = K.bspmm_workspace_bytes(hb, b.F, o)
+    h = K.bspmm_create(hb, b.F, o)
+    assert K.bspmm_plan_info(h).workspace_bytes == n and n % 256 == 0
+    # the transposed CSR (row pointers, columns, values) lives in the workspace
+    assert n >= 4 * (int((b.cols.astype(np.int64) + 1).sum()) + 2 * int(b.nnz.sum()))
+    K.bspmm_destroy(h)
