@@ -99,6 +99,9 @@ typedef struct bspmm_options {
     int32_t  lds_pad;          /* floats added to each staged B row, 0 = default, -1 = none    */
     int32_t  max_passes;       /* row passes a sub-workgroup slot may take, 0 = default (2)    */
     int32_t  generic_rows;     /* rows per generic row block, 0 = default (32)                 */
+    int32_t  wg_passes;        /* row passes of a workgroup item before it is cut into row
+                                  ranges: 0 = cut only while the launch is short of
+                                  target_workgroups, N > 0 = always cap at N, -1 = never cut   */
 } bspmm_options;
 
 /* What the scheduler decided; index 0 = forward, 1 = transposed. */
@@ -122,7 +125,8 @@ typedef struct bspmm_info {
 typedef struct bspmm_item {
     int32_t op;        /* operation index                                                     */
     int32_t bin;       /* BSPMM_BIN_*                                                         */
-    int32_t row0;      /* first output row of the operation this item computes                */
+    int32_t row0;      /* first output row of the operation this item computes (a staged item
+                          still holds the whole operation in LDS)                              */
     int32_t nrows;     /* number of output rows                                               */
     int32_t f0;        /* first feature column                                                */
     int32_t fw;        /* number of feature columns                                           */

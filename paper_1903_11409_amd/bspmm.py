@@ -39,7 +39,8 @@ class bspmm_options(ctypes.Structure):
                 ("lds_bytes", ctypes.c_int32), ("min_tile", ctypes.c_int32),
                 ("max_tile", ctypes.c_int32), ("target_workgroups", ctypes.c_int32),
                 ("compute_units", ctypes.c_int32), ("lds_pad", ctypes.c_int32),
-                ("max_passes", ctypes.c_int32), ("generic_rows", ctypes.c_int32)]
+                ("max_passes", ctypes.c_int32), ("generic_rows", ctypes.c_int32),
+                ("wg_passes", ctypes.c_int32)]
 
 
 class bspmm_info(ctypes.Structure):

@@ -25,6 +25,11 @@ hipError_t launch_validate(const OpRecord* ops, int batch, const int32_t* rpt,
 
 using namespace bspmm;
 
+#ifdef BSPMM_TRACE
+static long long* g_trace = nullptr;
+extern "C" void bspmm_set_trace(void* p) { g_trace = static_cast<long long*>(p); }
+#endif
+
 namespace {
 
 thread_local int g_last_hip_error = 0;
@@ -268,6 +273,9 @@ int run_direction(bspmm_plan* p, int d, const float* in, float* out, int64_t ld_
     }
     P.lds_floats = p->knobs.lds_words;
     P.pad = p->knobs.pad;
+#ifdef BSPMM_TRACE
+    P.trace = g_trace;
+#endif
     const bool vec4 = p->F % 4 == 0 && ld_in % 4 == 0 && ld_out % 4 == 0 &&
                       (reinterpret_cast<uintptr_t>(in) & 15) == 0 &&
                       (reinterpret_cast<uintptr_t>(out) & 15) == 0;

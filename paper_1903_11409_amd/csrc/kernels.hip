@@ -73,51 +73,92 @@ struct Split {
 };
 
 // ---------------------------------------------------------------------------------------
-// staging: global -> LDS.  All three copies are independent of each other, so their loads
-// are in flight together; nothing here depends on the contents of the CSR arrays.
+// staging: global -> LDS.  The three copies (row pointers, entries, dense tile) do not depend
+// on each other, and none depends on the contents of the CSR arrays.  What decides the time
+// of a small item is the number of global-memory round trips on its critical path, so the
+// first trip of every copy is issued before anything is waited for: one round trip stages a
+// typical molecule-sized item completely; larger items finish in unrolled leftover loops.
 // ---------------------------------------------------------------------------------------
 template <int S, int VEC>
 __device__ __forceinline__ void stage_item(const LaunchParams& P, const WorkItem& it, int* sm,
                                            int lane)
 {
+    using VT = typename Vec<VEC>::type;
     const StagedLayout L = staged_layout(it.m, it.k, it.nnz, it.fw, P.pad);
-
     const int32_t* __restrict__ rp = P.rpt + it.rpt_off;
-    for (int i = lane; i <= it.m; i += S) {
-        int v = rp[i];
-        v = v < 0 ? 0 : v;
-        sm[i] = v > it.nnz ? it.nnz : v;   // a malformed row pointer cannot leave the slot
-    }
-
     const int32_t* __restrict__ ci = P.colids + it.nz_off;
     const float* __restrict__ va = P.values + it.nz_off;
     int2* cv = reinterpret_cast<int2*>(sm + L.cv_off);
-    for (int p = lane; p < it.nnz; p += S) {
-        int c = ci[p];
-        c = (unsigned)c < (unsigned)it.k ? c : 0;   // a malformed column cannot leave the tile
-        cv[p] = make_int2(c, __float_as_int(va[p]));
-    }
-
-    const Split<S, VEC> sp(it.fw, lane);
     float* bs = reinterpret_cast<float*>(sm + L.b_off);
     const float* __restrict__ src = P.in + it.in_row_off * P.ld_in + it.f0;
-    for (int v = sp.l; v < sp.nvec; v += sp.g_lanes) {
-        const int step = sp.groups;
-        int row = sp.g;
-        // four rows per trip so that four loads are outstanding before the first LDS write
-        for (; row + 3 * step < it.k; row += 4 * step) {
-            typename Vec<VEC>::type t0 = load_vec<VEC>(src + (int64_t)(row) * P.ld_in + v * VEC);
-            typename Vec<VEC>::type t1 = load_vec<VEC>(src + (int64_t)(row + step) * P.ld_in + v * VEC);
-            typename Vec<VEC>::type t2 = load_vec<VEC>(src + (int64_t)(row + 2 * step) * P.ld_in + v * VEC);
-            typename Vec<VEC>::type t3 = load_vec<VEC>(src + (int64_t)(row + 3 * step) * P.ld_in + v * VEC);
-            store_vec<VEC>(bs + (row) * L.stride + v * VEC, t0);
-            store_vec<VEC>(bs + (row + step) * L.stride + v * VEC, t1);
-            store_vec<VEC>(bs + (row + 2 * step) * L.stride + v * VEC, t2);
-            store_vec<VEC>(bs + (row + 3 * step) * L.stride + v * VEC, t3);
+    const Split<S, VEC> sp(it.fw, lane);
+    const int step = sp.groups;
+    const int m = it.m, nnz = it.nnz, k = it.k;
+
+    // ---- first trip of every copy: loads only
+    int rv = 0;
+    if (lane <= m) rv = rp[lane];
+    int c0 = 0, c1 = 0;
+    float a0 = 0.f, a1 = 0.f;
+    if (lane < nnz) {
+        c0 = ci[lane];
+        a0 = va[lane];
+    }
+    if (lane + S < nnz) {
+        c1 = ci[lane + S];
+        a1 = va[lane + S];
+    }
+    const bool col_ok = sp.l < sp.nvec;
+    const int r0 = sp.g, r1 = sp.g + step, r2 = sp.g + 2 * step, r3 = sp.g + 3 * step;
+    const float* colp = src + sp.l * VEC;
+    VT t0 = Vec<VEC>::zero(), t1 = Vec<VEC>::zero(), t2 = Vec<VEC>::zero(), t3 = Vec<VEC>::zero();
+    if (col_ok && r0 < k) t0 = load_vec<VEC>(colp + (int64_t)r0 * P.ld_in);
+    if (col_ok && r1 < k) t1 = load_vec<VEC>(colp + (int64_t)r1 * P.ld_in);
+    if (col_ok && r2 < k) t2 = load_vec<VEC>(colp + (int64_t)r2 * P.ld_in);
+    if (col_ok && r3 < k) t3 = load_vec<VEC>(colp + (int64_t)r3 * P.ld_in);
+
+    // ---- first trip: LDS writes.  Row pointers are clamped to [0, nnz] and columns to
+    // [0, k) so that malformed arrays cannot make a lane leave its slot.
+    if (lane <= m) sm[lane] = min(max(rv, 0), nnz);
+    if (lane < nnz) cv[lane] = make_int2((unsigned)c0 < (unsigned)k ? c0 : 0, __float_as_int(a0));
+    if (lane + S < nnz)
+        cv[lane + S] = make_int2((unsigned)c1 < (unsigned)k ? c1 : 0, __float_as_int(a1));
+    float* bcol = bs + sp.l * VEC;
+    if (col_ok && r0 < k) store_vec<VEC>(bcol + r0 * L.stride, t0);
+    if (col_ok && r1 < k) store_vec<VEC>(bcol + r1 * L.stride, t1);
+    if (col_ok && r2 < k) store_vec<VEC>(bcol + r2 * L.stride, t2);
+    if (col_ok && r3 < k) store_vec<VEC>(bcol + r3 * L.stride, t3);
+
+    // ---- leftovers of larger items
+    for (int i = lane + S; i <= m; i += S) sm[i] = min(max(rp[i], 0), nnz);
+    for (int p = lane + 2 * S; p < nnz; p += 2 * S) {
+        const int q = p + S;
+        const int cc0 = ci[p];
+        const float aa0 = va[p];
+        int cc1 = 0;
+        float aa1 = 0.f;
+        if (q < nnz) {
+            cc1 = ci[q];
+            aa1 = va[q];
         }
-        for (; row < it.k; row += step)
-            store_vec<VEC>(bs + row * L.stride + v * VEC,
-                           load_vec<VEC>(src + (int64_t)row * P.ld_in + v * VEC));
+        cv[p] = make_int2((unsigned)cc0 < (unsigned)k ? cc0 : 0, __float_as_int(aa0));
+        if (q < nnz) cv[q] = make_int2((unsigned)cc1 < (unsigned)k ? cc1 : 0, __float_as_int(aa1));
+    }
+    for (int v = sp.l; v < sp.nvec; v += sp.g_lanes) {
+        const float* cp = src + v * VEC;
+        float* bp = bs + v * VEC;
+        for (int row = (v == sp.l ? sp.g + 4 * step : sp.g); row < k; row += 4 * step) {
+            const int q1 = row + step, q2 = row + 2 * step, q3 = row + 3 * step;
+            VT u0 = load_vec<VEC>(cp + (int64_t)row * P.ld_in);
+            VT u1 = Vec<VEC>::zero(), u2 = Vec<VEC>::zero(), u3 = Vec<VEC>::zero();
+            if (q1 < k) u1 = load_vec<VEC>(cp + (int64_t)q1 * P.ld_in);
+            if (q2 < k) u2 = load_vec<VEC>(cp + (int64_t)q2 * P.ld_in);
+            if (q3 < k) u3 = load_vec<VEC>(cp + (int64_t)q3 * P.ld_in);
+            store_vec<VEC>(bp + row * L.stride, u0);
+            if (q1 < k) store_vec<VEC>(bp + q1 * L.stride, u1);
+            if (q2 < k) store_vec<VEC>(bp + q2 * L.stride, u2);
+            if (q3 < k) store_vec<VEC>(bp + q3 * L.stride, u3);
+        }
     }
 }
 
@@ -135,7 +176,8 @@ __device__ __forceinline__ void compute_staged(const LaunchParams& P, const Work
     const Split<S, VEC> sp(it.fw, lane);
     float* __restrict__ dst = P.out + it.out_row_off * P.ld_out + it.f0;
 
-    for (int r = sp.g; r < it.nrows; r += sp.groups) {
+    const int row_end = it.row0 + it.nrows;
+    for (int r = it.row0 + sp.g; r < row_end; r += sp.groups) {
         const int p0 = sm[r];
         const int p1 = sm[r + 1];
         for (int v = sp.l; v < sp.nvec; v += sp.g_lanes) {
@@ -220,21 +262,49 @@ __device__ __forceinline__ void run_slots(const LaunchParams& P, int* sm, int ra
     if (it.nrows > 0) compute_staged<S, VEC>(P, it, slot_sm, lane);
 }
 
+#ifdef BSPMM_TRACE
+#define BSPMM_STAMP(slot)                                                              \
+    do {                                                                               \
+        if (P.trace) {                                                                 \
+            asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");                \
+            if (threadIdx.x == 0) P.trace[(size_t)blockIdx.x * 8 + (slot)] = wall_clock64(); \
+        }                                                                              \
+    } while (0)
+#else
+#define BSPMM_STAMP(slot) do { } while (0)
+#endif
+
 template <int VEC>
 __global__ void __launch_bounds__(kThreads) bspmm_kernel(const LaunchParams P)
 {
     extern __shared__ __align__(16) int sm[];
     const int w = blockIdx.x;
+#ifdef BSPMM_TRACE
+    if (P.trace && threadIdx.x == 0) P.trace[(size_t)blockIdx.x * 8] = wall_clock64();
+#endif
     if (w < P.wg_end[0]) {
         const WorkItem it = P.items[P.item_base[0] + w];   // uniform address: scalar loads
         if (it.nrows <= 0) return;
+        BSPMM_STAMP(1);
         if (it.staged) {
             stage_item<kThreads, VEC>(P, it, sm, threadIdx.x);
             __syncthreads();
+            BSPMM_STAMP(2);
             compute_staged<kThreads, VEC>(P, it, sm, threadIdx.x);
         } else {
             compute_generic<VEC>(P, it, threadIdx.x);
         }
+        BSPMM_STAMP(3);
+#ifdef BSPMM_TRACE
+        if (P.trace && threadIdx.x == 0) {
+            P.trace[(size_t)blockIdx.x * 8 + 4] = it.nrows;
+            P.trace[(size_t)blockIdx.x * 8 + 5] = it.k;
+            P.trace[(size_t)blockIdx.x * 8 + 6] = it.nnz;
+            unsigned hw;
+            asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(hw));
+            P.trace[(size_t)blockIdx.x * 8 + 7] = hw;
+        }
+#endif
     } else if (w < P.wg_end[1]) {
         run_slots<6, VEC>(P, sm, 1, w - P.wg_end[0]);
     } else if (w < P.wg_end[2]) {

@@ -33,7 +33,7 @@ struct alignas(16) WorkItem {
     int32_t nrows;        // output rows of this item (0 = empty item)
     int32_t f0;           // first feature column
     int32_t fw;           // feature columns
-    int32_t staged;       // 1: operands staged in LDS (whole operation, row0 == 0); 0: generic
+    int32_t staged;       // 1: whole operation and its dense tile staged in LDS; 0: generic
 };
 static_assert(sizeof(WorkItem) == 64, "WorkItem must be 64 bytes");
 
@@ -52,6 +52,9 @@ struct LaunchParams {
     int32_t item_base[kRanges];
     int32_t lds_floats;   // LDS per workgroup, in 4-byte words
     int32_t pad;          // words added to every staged dense row
+#ifdef BSPMM_TRACE
+    long long* trace;     // development builds only: 8 timestamps per workgroup
+#endif
 };
 
 // Per-operation record of the transposed-CSR build and of the validation kernel.

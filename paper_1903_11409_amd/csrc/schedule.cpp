@@ -115,7 +115,9 @@ int64_t item_cost(const DirOps& o, int i, int nrows, int fw, bool staged)
            4 * (int64_t)nrows + 512;
 }
 
-void draft_op(const DirOps& o, int i, int F, const Choice& ch, const Knobs& kn,
+// `cap` > 0 cuts a workgroup item into row ranges of at most `cap` passes each (every range
+// stages the whole operation, so the cut costs on-chip traffic and buys parallelism).
+void draft_op(const DirOps& o, int i, int F, int vec, const Choice& ch, const Knobs& kn, int cap,
               std::map<std::pair<int64_t, int>, int>& groups, std::vector<Draft>& out)
 {
     if (o.m[i] <= 0) return;
@@ -131,7 +133,14 @@ void draft_op(const DirOps& o, int i, int F, const Choice& ch, const Knobs& kn,
         } else {
             gid = it->second;
         }
-        if (ch.bin != BSPMM_BIN_GENERIC) {
+        if (ch.bin == BSPMM_BIN_WORKGROUP && cap > 0) {
+            const int rows_per_pass = kThreads / lanes_per_row(fw, vec);
+            const int chunk = cap * rows_per_pass;
+            for (int r0 = 0; r0 < o.m[i]; r0 += chunk) {
+                const int nr = std::min(chunk, o.m[i] - r0);
+                out.push_back({i, ch.bin, r0, nr, f0, fw, 1, item_cost(o, i, nr, fw, true), gid});
+            }
+        } else if (ch.bin != BSPMM_BIN_GENERIC) {
             out.push_back({i, ch.bin, 0, o.m[i], f0, fw, 1, item_cost(o, i, o.m[i], fw, true), gid});
         } else {
             for (int r0 = 0; r0 < o.m[i]; r0 += kn.generic_rows) {
@@ -143,12 +152,12 @@ void draft_op(const DirOps& o, int i, int F, const Choice& ch, const Knobs& kn,
 }
 
 std::vector<Draft> draft_all(const DirOps& o, int F, int vec, const std::vector<int>& cand,
-                             size_t first, const Knobs& kn)
+                             size_t first, const Knobs& kn, int cap)
 {
     std::vector<Draft> d;
     std::map<std::pair<int64_t, int>, int> groups;
     for (int i = 0; i < o.size(); ++i)
-        draft_op(o, i, F, choose(o, i, F, vec, cand, first, kn), kn, groups, d);
+        draft_op(o, i, F, vec, choose(o, i, F, vec, cand, first, kn), kn, cap, groups, d);
     return d;
 }
 
@@ -208,6 +217,7 @@ Knobs resolve_knobs(const bspmm_options* o)
     if (o->lds_pad < 0) k.pad = 0;
     if (o->max_passes > 0) k.max_passes = o->max_passes;
     if (o->generic_rows > 0) k.generic_rows = o->generic_rows;
+    k.wg_passes = o->wg_passes;
     return k;
 }
 
@@ -222,14 +232,23 @@ Schedule make_schedule(const DirOps& ops, int F, const Knobs& kn_in)
     // widest batch-wide tile that still gives the launch enough workgroups
     std::vector<Draft> d;
     size_t chosen = cand.size() - 1;
+    const int fixed_cap = kn.wg_passes > 0 ? kn.wg_passes : 0;
     for (size_t c = 0; c < cand.size(); ++c) {
-        d = draft_all(ops, F, vec, cand, c, kn);
+        d = draft_all(ops, F, vec, cand, c, kn, fixed_cap);
         if (count_workgroups(d) >= kn.target_wgs || c + 1 == cand.size()) {
             chosen = c;
             break;
         }
     }
     s.tile = cand[chosen];
+    // still too few workgroups at the narrowest tile: the batch is small, its time is set by
+    // the slowest workgroup, so cut multi-pass workgroup items into row ranges
+    if (kn.wg_passes == 0 && count_workgroups(d) < kn.target_wgs) {
+        for (int cap = 4; cap >= 1; cap /= 2) {
+            d = draft_all(ops, F, vec, cand, chosen, kn, cap);
+            if (count_workgroups(d) >= kn.target_wgs) break;
+        }
+    }
 
     // group costs, for ordering and XCD placement
     int ngroups = 0;

@@ -28,6 +28,7 @@ struct Knobs {
     int pad = 0;
     int max_passes = 2;
     int generic_rows = 32;
+    int wg_passes = 0;        // 0 automatic, >0 cap on passes of a workgroup item, <0 never cut
 };
 
 struct Schedule {

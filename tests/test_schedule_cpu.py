@@ -33,7 +33,7 @@ def test_library_exports_every_declared_symbol():
 
 def test_struct_sizes_match_header():
     assert ctypes.sizeof(K.bspmm_item) == 32
-    assert ctypes.sizeof(K.bspmm_options) == 40
+    assert ctypes.sizeof(K.bspmm_options) == 44
     assert ctypes.sizeof(K.bspmm_batch) == 8 + 10 * 8
     assert ctypes.sizeof(K.bspmm_info) == 16 + 8 + 8 + 8 + 40 + 8 + 16 + 8 + 8
 
@@ -71,7 +71,8 @@ def _check_schedule(b, F, transposed=False, **opts):
             assert (it.workgroup, it.slot) not in seen
             seen.add((it.workgroup, it.slot))
             if it.bin != K.BIN_GENERIC:
-                assert it.row0 == 0 and it.nrows == int(m_of[it.op])
+                if it.bin != K.BIN_WORKGROUP:   # only workgroup items may be cut into row ranges
+                    assert it.row0 == 0 and it.nrows == int(m_of[it.op])
                 need = _lds_words(int(m_of[it.op]), int(k_of[it.op]), int(b.nnz[it.op]), it.fw, pad)
                 assert need * 4 <= info.lds_bytes * lanes // 256
                 if F % 4 == 0:
@@ -133,6 +134,7 @@ def test_forced_bins_still_cover(bin_):
 @pytest.mark.parametrize("opts", [{"lds_pad": 4}, {"min_tile": 16}, {"max_tile": 64},
                                   {"lds_bytes": 65536}, {"lds_bytes": 8192},
                                   {"target_workgroups": 64}, {"max_passes": 4},
+                                  {"wg_passes": 1}, {"wg_passes": -1, "target_workgroups": 4096},
                                   {"generic_rows": 8, "lds_bytes": 4096}])
 def test_knobs_keep_the_invariants(opts):
     b = W.config5_skewed(graphs=64, F=128)
