@@ -35,6 +35,9 @@ def parse_args():
     ap.add_argument("--no-extra", action="store_true", help="headline measurement only")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run a 256 MiB elementwise copy kernel of known traffic "
+                         "(scale reference for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     return ap.parse_args()
 
 
@@ -128,6 +131,20 @@ class Runner:
                 "workgroups": self.workgroups}
 
 
+_marker = None
+
+
+def phase_marker(torch, k):
+    """A one-element int16 fill between measurement phases: shows up in a kernel trace as a
+    FillFunctor<short> dispatch, so a profile of this script can be cut into its phases."""
+    global _marker
+    if _marker is None:
+        _marker = torch.empty(1, dtype=torch.int16, device="cuda")
+    torch.cuda.synchronize()
+    _marker.fill_(k)
+    torch.cuda.synchronize()
+
+
 def copy_bandwidth(torch):
     n = 1 << 28   # 1 GiB of fp32
     a = torch.empty(n, dtype=torch.float32, device="cuda")
@@ -205,13 +222,23 @@ def main():
 
     b = W.config2_molecule(F=128)
     head = Runner(torch, K, b)
+    phase_marker(torch, 1)          # phase 1: headline, HIP-graph replay, rotating operands
     sec_graph, timed_steps = head.time_graph(args.steps, args.warmup)
+    phase_marker(torch, 2)          # phase 2: headline, eager launches, rotating operands
     sec_eager = head.time_eager(args.steps, args.warmup)
+    phase_marker(torch, 3)          # phase 3: everything else
     sec = min(sec_graph, sec_eager)
     launch_mode = "hipgraph_replay" if sec_graph <= sec_eager else "eager"
 
     extra = {}
     parity_ok = None
+    if args.calib_copy:
+        a = torch.ones(1 << 26, dtype=torch.float32, device="cuda")
+        c = torch.empty_like(a)
+        for _ in range(3):
+            torch.mul(a, 1.0, out=c)      # reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
+        del a, c
     if not args.no_cpu:
         from oracle import reference as oracle
         parity_ok = parity_sample(torch, K, head, oracle)
