@@ -91,17 +91,19 @@ typedef struct bspmm_batch {
 typedef struct bspmm_options {
     uint32_t flags;            /* BSPMM_DRY_RUN | BSPMM_BUILD_TRANSPOSE | BSPMM_FLOOR_PROBE    */
     int32_t  force_bin;        /* 0 = automatic; 1+b forces bin b for every op that fits it    */
-    int32_t  lds_bytes;        /* LDS per workgroup, 0 = default (32 KiB); <= 64 KiB           */
+    int32_t  lds_bytes;        /* LDS per workgroup, 0 = default (24 KiB); <= 64 KiB           */
     int32_t  min_tile;         /* narrowest feature tile in floats, 0 = default (32)           */
     int32_t  max_tile;         /* widest feature tile in floats, 0 = default (256), <= 256     */
     int32_t  target_workgroups;/* split tiles until the launch has this many, 0 = 4 per CU    */
     int32_t  compute_units;    /* 0 = ask the device (256 assumed for dry runs)                */
     int32_t  lds_pad;          /* floats added to each staged B row, 0 = default, -1 = none    */
-    int32_t  max_passes;       /* row passes a sub-workgroup slot may take, 0 = default (2)    */
-    int32_t  generic_rows;     /* rows per generic row block, 0 = default (32)                 */
+    int32_t  max_passes;       /* row passes a sub-workgroup slot may take, 0 = default (1)    */
+    int32_t  generic_rows;     /* rows per generic row block, 0 = default (16)                 */
     int32_t  wg_passes;        /* row passes of a workgroup item before it is cut into row
                                   ranges: 0 = cut only while the launch is short of
                                   target_workgroups, N > 0 = always cap at N, -1 = never cut   */
+    int32_t  resident_workgroups; /* N > 0: persistent launch of N workgroups that stride
+                                  through the tasks; 0 = one workgroup per task (default)      */
 } bspmm_options;
 
 /* What the scheduler decided; index 0 = forward, 1 = transposed. */
@@ -112,6 +114,7 @@ typedef struct bspmm_info {
     int32_t compute_units;
     int32_t tile[2];                         /* batch-wide feature tile before per-op shrink  */
     int32_t workgroups[2];                   /* grid size of the single launch                */
+    int32_t tasks[2];                        /* workgroup-sized tasks the grid strides through */
     int32_t items[2];                        /* non-empty work items                          */
     int32_t items_in_bin[2][BSPMM_NUM_BINS];
     int32_t transposed_supported;            /* 0 when input-gradient blocks overlap          */
@@ -130,7 +133,7 @@ typedef struct bspmm_item {
     int32_t nrows;     /* number of output rows                                               */
     int32_t f0;        /* first feature column                                                */
     int32_t fw;        /* number of feature columns                                           */
-    int32_t workgroup; /* blockIdx.x that runs it                                             */
+    int32_t workgroup; /* task index; workgroup (task mod grid size) runs it                  */
     int32_t slot;      /* lane slot inside the workgroup                                      */
 } bspmm_item;
 

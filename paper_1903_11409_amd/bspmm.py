@@ -40,13 +40,14 @@ class bspmm_options(ctypes.Structure):
                 ("max_tile", ctypes.c_int32), ("target_workgroups", ctypes.c_int32),
                 ("compute_units", ctypes.c_int32), ("lds_pad", ctypes.c_int32),
                 ("max_passes", ctypes.c_int32), ("generic_rows", ctypes.c_int32),
-                ("wg_passes", ctypes.c_int32)]
+                ("wg_passes", ctypes.c_int32), ("resident_workgroups", ctypes.c_int32)]
 
 
 class bspmm_info(ctypes.Structure):
     _fields_ = [("batch", ctypes.c_int32), ("F", ctypes.c_int32),
                 ("lds_bytes", ctypes.c_int32), ("compute_units", ctypes.c_int32),
                 ("tile", ctypes.c_int32 * 2), ("workgroups", ctypes.c_int32 * 2),
+                ("tasks", ctypes.c_int32 * 2),
                 ("items", ctypes.c_int32 * 2),
                 ("items_in_bin", (ctypes.c_int32 * NUM_BINS) * 2),
                 ("transposed_supported", ctypes.c_int32),

@@ -13,12 +13,13 @@
 #include "schedule.hpp"
 
 namespace bspmm {
-hipError_t launch_bspmm(const LaunchParams& P, int grid, int lds_bytes, bool vec4,
+hipError_t launch_bspmm(const LaunchParams& P, int grid, int lds_bytes, bool vec4, bool slices,
                         hipStream_t stream);
 hipError_t launch_build_transpose(const OpRecord* ops, int batch, int lds_bytes,
                                   const int32_t* rpt, const int32_t* colids,
                                   const float* values, int32_t* rpt_t, int32_t* colids_t,
                                   float* values_t, int32_t* gscratch, hipStream_t stream);
+int bspmm_max_resident_workgroups(int lds_bytes, bool slices);
 hipError_t launch_validate(const OpRecord* ops, int batch, const int32_t* rpt,
                            const int32_t* colids, int32_t* flag, hipStream_t stream);
 }  // namespace bspmm
@@ -228,6 +229,10 @@ Knobs knobs_for(const bspmm_options* o, bool ask_device)
             (void)hipGetLastError();
     }
     if (!(o && o->target_workgroups > 0)) kn.target_wgs = 4 * kn.compute_units;
+    const int r = ask_device ? bspmm_max_resident_workgroups(kn.lds_words * 4, false) : 0;
+    const int rs = ask_device ? bspmm_max_resident_workgroups(kn.lds_words * 4, true) : 0;
+    kn.capacity_wgs = r > 0 ? r : 6 * kn.compute_units;
+    kn.capacity_wgs_slices = rs > 0 ? rs : 4 * kn.compute_units;
     return kn;
 }
 
@@ -271,6 +276,7 @@ int run_direction(bspmm_plan* p, int d, const float* in, float* out, int64_t ld_
         P.wg_end[r] = sc.wg_end[r];
         P.item_base[r] = sc.item_base[r];
     }
+    P.n_tasks = sc.grid;
     P.lds_floats = p->knobs.lds_words;
     P.pad = p->knobs.pad;
 #ifdef BSPMM_TRACE
@@ -279,7 +285,7 @@ int run_direction(bspmm_plan* p, int d, const float* in, float* out, int64_t ld_
     const bool vec4 = p->F % 4 == 0 && ld_in % 4 == 0 && ld_out % 4 == 0 &&
                       (reinterpret_cast<uintptr_t>(in) & 15) == 0 &&
                       (reinterpret_cast<uintptr_t>(out) & 15) == 0;
-    hipError_t e = launch_bspmm(P, sc.grid, p->knobs.lds_words * 4, vec4, s);
+    hipError_t e = launch_bspmm(P, sc.launch_grid, p->knobs.lds_words * 4, vec4, sc.has_slices, s);
     return e == hipSuccess ? BSPMM_OK : hip_fail(e);
 }
 
@@ -447,7 +453,8 @@ int bspmm_plan_info(const bspmm_plan* plan, bspmm_info* info)
     info->compute_units = plan->knobs.compute_units;
     for (int d = 0; d < 2; ++d) {
         info->tile[d] = plan->sched[d].tile;
-        info->workgroups[d] = plan->sched[d].grid;
+        info->workgroups[d] = plan->sched[d].launch_grid;
+        info->tasks[d] = plan->sched[d].grid;
         info->items[d] = (int32_t)plan->sched[d].view.size();
         for (int b = 0; b < BSPMM_NUM_BINS; ++b)
             info->items_in_bin[d][b] = plan->sched[d].items_in_bin[b];

@@ -49,6 +49,24 @@ __device__ __forceinline__ void store_vec(float* p, const typename Vec<VEC>::typ
     *reinterpret_cast<typename Vec<VEC>::type*>(p) = v;
 }
 
+// Output rows are written once and never read by this launch: a non-temporal store keeps
+// them from displacing the dense blocks that the generic bin re-reads out of L2.
+template <int VEC>
+__device__ __forceinline__ void store_out(float* p, const typename Vec<VEC>::type& v)
+{
+#ifdef BSPMM_NO_NT
+    store_vec<VEC>(p, v);
+#else
+    if constexpr (VEC == 4) {
+        typedef float native4 __attribute__((ext_vector_type(4)));
+        native4 n = {v.x, v.y, v.z, v.w};
+        __builtin_nontemporal_store(n, reinterpret_cast<native4*>(p));
+    } else {
+        __builtin_nontemporal_store(v, p);
+    }
+#endif
+}
+
 __device__ __forceinline__ int ilog2(int pow2) { return 31 - __clz(pow2); }
 
 // How the S lanes of a slot split into row groups for a tile of fw columns.
@@ -108,7 +126,33 @@ __device__ __forceinline__ void stage_item(const LaunchParams& P, const WorkItem
         c1 = ci[lane + S];
         a1 = va[lane + S];
     }
-    const bool col_ok = sp.l < sp.nvec;
+    // Dense tile.  Fast path: when a tile row is a power-of-two number of float4 and rows are
+    // packed without padding, whole wavefronts copy 1 KiB at a time straight from global
+    // memory into LDS (lane i lands at base + 16*i): no staging registers, and the entire
+    // tile is in flight at once instead of four rows per lane group.
+    const bool direct = VEC == 4 && S >= 64 && P.pad == 0 && (sp.nvec & (sp.nvec - 1)) == 0;
+    if (direct) {
+        const int sh = ilog2(sp.nvec);
+        const int total = k << sh;                       // float4 in the tile
+        const int wl = lane & 63;
+        for (int e0 = (lane >> 6) << 6; e0 < total; e0 += S) {
+            const int e = e0 + wl;
+            if (e < total) {
+                const float* gp = src + (int64_t)(e >> sh) * P.ld_in + ((e & (sp.nvec - 1)) << 2);
+                // a dense tile that no other item reads is streamed (non-temporal) so that it
+                // does not displace data other workgroups re-read from L2
+                if (it.staged & 2)
+                    __builtin_amdgcn_global_load_lds(
+                        (const void __attribute__((address_space(1)))*)gp,
+                        (void __attribute__((address_space(3)))*)(bs + (e0 << 2)), 16, 0, 2);
+                else
+                    __builtin_amdgcn_global_load_lds(
+                        (const void __attribute__((address_space(1)))*)gp,
+                        (void __attribute__((address_space(3)))*)(bs + (e0 << 2)), 16, 0, 0);
+            }
+        }
+    }
+    const bool col_ok = !direct && sp.l < sp.nvec;
     const int r0 = sp.g, r1 = sp.g + step, r2 = sp.g + 2 * step, r3 = sp.g + 3 * step;
     const float* colp = src + sp.l * VEC;
     VT t0 = Vec<VEC>::zero(), t1 = Vec<VEC>::zero(), t2 = Vec<VEC>::zero(), t3 = Vec<VEC>::zero();
@@ -144,7 +188,7 @@ __device__ __forceinline__ void stage_item(const LaunchParams& P, const WorkItem
         cv[p] = make_int2((unsigned)cc0 < (unsigned)k ? cc0 : 0, __float_as_int(aa0));
         if (q < nnz) cv[q] = make_int2((unsigned)cc1 < (unsigned)k ? cc1 : 0, __float_as_int(aa1));
     }
-    for (int v = sp.l; v < sp.nvec; v += sp.g_lanes) {
+    for (int v = sp.l; !direct && v < sp.nvec; v += sp.g_lanes) {
         const float* cp = src + v * VEC;
         float* bp = bs + v * VEC;
         for (int row = (v == sp.l ? sp.g + 4 * step : sp.g); row < k; row += 4 * step) {
@@ -199,118 +243,186 @@ __device__ __forceinline__ void compute_staged(const LaunchParams& P, const Work
                 const int2 e = cv[p];
                 V::fma(acc, __int_as_float(e.y), load_vec<VEC>(bcol + e.x * L.stride));
             }
-            store_vec<VEC>(dst + (int64_t)r * P.ld_out + v * VEC, acc);
+            store_out<VEC>(dst + (int64_t)r * P.ld_out + v * VEC, acc);
         }
     }
 }
 
-// Generic bin: nothing staged, every operand comes from global memory (L2 keeps the dense
-// block of a large operation while its row blocks run on the same XCD).
+// Generic bin: the operation's dense tile does not fit LDS, so a row block gathers it from
+// global memory (L2 keeps the block while the row blocks of one operation run on one XCD).
+// Only the block's slice of the CSR arrays is staged, in two dependent steps (row pointers,
+// then the entries they delimit); after that every gather of a row is independent and up to
+// four are in flight per lane (deeper
+// unrolling costs registers, hence occupancy, and measured slower).
 template <int VEC>
-__device__ __forceinline__ void compute_generic(const LaunchParams& P, const WorkItem& it,
-                                                int lane)
+__device__ __forceinline__ void run_generic(const LaunchParams& P, const WorkItem& it, int* sm,
+                                            int tid)
 {
     using V = Vec<VEC>;
-    const Split<kThreads, VEC> sp(it.fw, lane);
-    const int32_t* __restrict__ rp = P.rpt + it.rpt_off;
+    using VT = typename V::type;
+    const int32_t* __restrict__ rp = P.rpt + it.rpt_off + it.row0;
     const int32_t* __restrict__ ci = P.colids + it.nz_off;
     const float* __restrict__ va = P.values + it.nz_off;
-    const float* __restrict__ src = P.in + it.in_row_off * P.ld_in + it.f0;
-    float* __restrict__ dst = P.out + it.out_row_off * P.ld_out + it.f0;
+    const int nrows = it.nrows;
+    for (int i = tid; i <= nrows; i += kThreads) sm[i] = min(max(rp[i], 0), it.nnz);
+    __syncthreads();
+    const int pbeg = __builtin_amdgcn_readfirstlane(sm[0]);
+    const int cnt = max(__builtin_amdgcn_readfirstlane(sm[nrows]) - pbeg, 0);
+    const int cv_off = round_up(nrows + 1, 2);
+    const bool fits = cv_off + 2 * cnt <= P.lds_floats;
+    int2* cv = reinterpret_cast<int2*>(sm + cv_off);
+    if (fits) {
+        for (int p = tid; p < cnt; p += 2 * kThreads) {
+            const int q = p + kThreads;
+            const int c0 = ci[pbeg + p];
+            const float a0 = va[pbeg + p];
+            int c1 = 0;
+            float a1 = 0.f;
+            if (q < cnt) {
+                c1 = ci[pbeg + q];
+                a1 = va[pbeg + q];
+            }
+            cv[p] = make_int2((unsigned)c0 < (unsigned)it.k ? c0 : 0, __float_as_int(a0));
+            if (q < cnt) cv[q] = make_int2((unsigned)c1 < (unsigned)it.k ? c1 : 0, __float_as_int(a1));
+        }
+    }
+    __syncthreads();
 
-    for (int r = it.row0 + sp.g; r < it.row0 + it.nrows; r += sp.groups) {
-        const int p0 = rp[r];
-        const int p1 = rp[r + 1];
+    const Split<kThreads, VEC> sp(it.fw, tid);
+    const float* __restrict__ src = P.in + it.in_row_off * P.ld_in + it.f0;
+    float* __restrict__ dst = P.out + (it.out_row_off + it.row0) * P.ld_out + it.f0;
+    for (int i = sp.g; i < nrows; i += sp.groups) {
+        const int p0 = sm[i] - pbeg;
+        const int p1 = sm[i + 1] - pbeg;
         for (int v = sp.l; v < sp.nvec; v += sp.g_lanes) {
             const float* bcol = src + v * VEC;
-            typename V::type acc = V::zero();
-            int p = p0;
-            for (; p + 3 < p1; p += 4) {
-                const int c0 = ci[p], c1 = ci[p + 1], c2 = ci[p + 2], c3 = ci[p + 3];
-                const float a0 = va[p], a1 = va[p + 1], a2 = va[p + 2], a3 = va[p + 3];
-                const typename V::type b0 = load_vec<VEC>(bcol + (int64_t)c0 * P.ld_in);
-                const typename V::type b1 = load_vec<VEC>(bcol + (int64_t)c1 * P.ld_in);
-                const typename V::type b2 = load_vec<VEC>(bcol + (int64_t)c2 * P.ld_in);
-                const typename V::type b3 = load_vec<VEC>(bcol + (int64_t)c3 * P.ld_in);
-                V::fma(acc, a0, b0);
-                V::fma(acc, a1, b1);
-                V::fma(acc, a2, b2);
-                V::fma(acc, a3, b3);
+            VT acc = V::zero();
+            for (int p = p0; p < p1; p += 4) {
+                int cc[4];
+                float aa[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int q = min(p + u, p1 - 1);
+                    if (fits) {
+                        const int2 e = cv[q];
+                        cc[u] = e.x;
+                        aa[u] = __int_as_float(e.y);
+                    } else {
+                        const int c = ci[pbeg + q];
+                        cc[u] = (unsigned)c < (unsigned)it.k ? c : 0;
+                        aa[u] = va[pbeg + q];
+                    }
+                    if (p + u >= p1) aa[u] = 0.f;
+                }
+                VT b[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    b[u] = V::zero();
+                    if (p + u < p1) b[u] = load_vec<VEC>(bcol + (int64_t)cc[u] * P.ld_in);
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) V::fma(acc, aa[u], b[u]);
             }
-            for (; p < p1; ++p)
-                V::fma(acc, va[p], load_vec<VEC>(bcol + (int64_t)ci[p] * P.ld_in));
-            store_vec<VEC>(dst + (int64_t)r * P.ld_out + v * VEC, acc);
+            store_out<VEC>(dst + (int64_t)i * P.ld_out + v * VEC, acc);
         }
     }
 }
 
-// A workgroup of a sub-workgroup range: 256/S slots, one staged item each.
+// One task of a sub-workgroup range: 256/S slots, one staged item each.
 template <int LOG2S, int VEC>
-__device__ __forceinline__ void run_slots(const LaunchParams& P, int* sm, int range, int wrel)
+__device__ __forceinline__ void run_slots(const LaunchParams& P, int* sm, int first_item)
 {
     constexpr int S = 1 << LOG2S;
-    constexpr int SLOTS = kThreads / S;
     const int tid = threadIdx.x;
     const int slot = tid >> LOG2S;
     const int lane = tid & (S - 1);
-    int idx = P.item_base[range] + wrel * SLOTS + slot;
+    int idx = first_item + slot;
     if (LOG2S == 6) idx = __builtin_amdgcn_readfirstlane(idx);   // uniform inside a wavefront
     const WorkItem it = P.items[idx];
     int* slot_sm = sm + slot * (P.lds_floats >> (8 - LOG2S));
     if (it.nrows > 0) stage_item<S, VEC>(P, it, slot_sm, lane);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // direct-to-LDS loads landed
     __syncthreads();
     if (it.nrows > 0) compute_staged<S, VEC>(P, it, slot_sm, lane);
 }
 
 #ifdef BSPMM_TRACE
-#define BSPMM_STAMP(slot)                                                              \
+#define BSPMM_STAMP(task, slot)                                                        \
     do {                                                                               \
         if (P.trace) {                                                                 \
             asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");                \
-            if (threadIdx.x == 0) P.trace[(size_t)blockIdx.x * 8 + (slot)] = wall_clock64(); \
+            if (threadIdx.x == 0) P.trace[(size_t)(task) * 8 + (slot)] = wall_clock64(); \
         }                                                                              \
     } while (0)
 #else
-#define BSPMM_STAMP(slot) do { } while (0)
+#define BSPMM_STAMP(task, slot) do { } while (0)
 #endif
 
-template <int VEC>
+// One launch runs the whole schedule.  The grid is persistent: it has at most as many
+// workgroups as the chip holds at once, and workgroup w takes tasks w, w + gridDim.x, ...
+// of the task list (largest first), so a workgroup's stores drain and its next item arrives
+// while it already works on the following one.  Tasks below wg_end[0] are one item for the
+// whole workgroup (bins workgroup and generic); the next item's descriptor is fetched while
+// the current one is processed.  Later tasks hold 4, 8 or 16 items for 64-, 32- or 16-lane
+// slots.
+// SLICES = false leaves out the 32- and 16-lane slot code (per-lane item descriptors cost
+// registers, hence occupancy); the host launches it for schedules without such items.
+template <int VEC, bool SLICES>
 __global__ void __launch_bounds__(kThreads) bspmm_kernel(const LaunchParams P)
 {
     extern __shared__ __align__(16) int sm[];
-    const int w = blockIdx.x;
+    const int tid = threadIdx.x;
+    const int stride = gridDim.x;
+    int t = blockIdx.x;
+    if (t < P.wg_end[0]) {
+        WorkItem it = P.items[P.item_base[0] + t];   // uniform address: scalar loads
+        for (;;) {
+            const int tn = t + stride;
+            const bool more = tn < P.wg_end[0];
+            WorkItem nx = it;
+            if (more) nx = P.items[P.item_base[0] + tn];
 #ifdef BSPMM_TRACE
-    if (P.trace && threadIdx.x == 0) P.trace[(size_t)blockIdx.x * 8] = wall_clock64();
+            if (P.trace && tid == 0) P.trace[(size_t)t * 8] = wall_clock64();
 #endif
-    if (w < P.wg_end[0]) {
-        const WorkItem it = P.items[P.item_base[0] + w];   // uniform address: scalar loads
-        if (it.nrows <= 0) return;
-        BSPMM_STAMP(1);
-        if (it.staged) {
-            stage_item<kThreads, VEC>(P, it, sm, threadIdx.x);
-            __syncthreads();
-            BSPMM_STAMP(2);
-            compute_staged<kThreads, VEC>(P, it, sm, threadIdx.x);
-        } else {
-            compute_generic<VEC>(P, it, threadIdx.x);
-        }
-        BSPMM_STAMP(3);
+            if (it.nrows > 0) {
+                BSPMM_STAMP(t, 1);
+                if (it.staged) {
+                    stage_item<kThreads, VEC>(P, it, sm, tid);
+                    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // direct-to-LDS loads landed
+                    __syncthreads();
+                    BSPMM_STAMP(t, 2);
+                    compute_staged<kThreads, VEC>(P, it, sm, tid);
+                } else {
+                    run_generic<VEC>(P, it, sm, tid);
+                }
+                BSPMM_STAMP(t, 3);
 #ifdef BSPMM_TRACE
-        if (P.trace && threadIdx.x == 0) {
-            P.trace[(size_t)blockIdx.x * 8 + 4] = it.nrows;
-            P.trace[(size_t)blockIdx.x * 8 + 5] = it.k;
-            P.trace[(size_t)blockIdx.x * 8 + 6] = it.nnz;
-            unsigned hw;
-            asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(hw));
-            P.trace[(size_t)blockIdx.x * 8 + 7] = hw;
-        }
+                if (P.trace && tid == 0) {
+                    P.trace[(size_t)t * 8 + 4] = it.nrows;
+                    P.trace[(size_t)t * 8 + 5] = it.k;
+                    P.trace[(size_t)t * 8 + 6] = it.nnz;
+                    unsigned hw;
+                    asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(hw));
+                    P.trace[(size_t)t * 8 + 7] = hw;
+                }
 #endif
-    } else if (w < P.wg_end[1]) {
-        run_slots<6, VEC>(P, sm, 1, w - P.wg_end[0]);
-    } else if (w < P.wg_end[2]) {
-        run_slots<5, VEC>(P, sm, 2, w - P.wg_end[1]);
-    } else {
-        run_slots<4, VEC>(P, sm, 3, w - P.wg_end[2]);
+            }
+            t = tn;
+            if (!more) break;
+            __syncthreads();   // the next item overwrites the LDS this one was read from
+            it = nx;
+        }
+    }
+    for (; t < P.n_tasks; t += stride) {
+        __syncthreads();
+        if (t < P.wg_end[1]) {
+            run_slots<6, VEC>(P, sm, P.item_base[1] + (t - P.wg_end[0]) * 4);
+        } else if (SLICES) {
+            if (t < P.wg_end[2])
+                run_slots<5, VEC>(P, sm, P.item_base[2] + (t - P.wg_end[1]) * 8);
+            else
+                run_slots<4, VEC>(P, sm, P.item_base[3] + (t - P.wg_end[2]) * 16);
+        }
     }
 }
 
@@ -429,14 +541,43 @@ __global__ void fill_i32_kernel(int32_t* p, int32_t v, int n)
 // ---------------------------------------------------------------------------------------
 // host-side launchers (the only symbols the rest of the library sees)
 // ---------------------------------------------------------------------------------------
-hipError_t launch_bspmm(const LaunchParams& P, int grid, int lds_bytes, bool vec4,
+// Workgroups of bspmm_kernel the current device holds at once (0 if it cannot be asked).
+int bspmm_max_resident_workgroups(int lds_bytes, bool slices)
+{
+    int per_cu4 = 0, per_cu1 = 0, dev = 0, cus = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    if (e == hipSuccess)
+        e = slices ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu4, bspmm_kernel<4, true>,
+                                                                  kThreads, (size_t)lds_bytes)
+                   : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu4, bspmm_kernel<4, false>,
+                                                                  kThreads, (size_t)lds_bytes);
+    if (e == hipSuccess)
+        e = slices ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu1, bspmm_kernel<1, true>,
+                                                                  kThreads, (size_t)lds_bytes)
+                   : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu1, bspmm_kernel<1, false>,
+                                                                  kThreads, (size_t)lds_bytes);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        return 0;
+    }
+    const int per_cu = per_cu4 < per_cu1 ? per_cu4 : per_cu1;
+    return per_cu > 0 && cus > 0 ? per_cu * cus : 0;
+}
+
+hipError_t launch_bspmm(const LaunchParams& P, int grid, int lds_bytes, bool vec4, bool slices,
                         hipStream_t stream)
 {
     if (grid <= 0) return hipSuccess;
-    if (vec4)
-        hipLaunchKernelGGL(bspmm_kernel<4>, dim3(grid), dim3(kThreads), lds_bytes, stream, P);
+    const dim3 g(grid), b(kThreads);
+    if (vec4 && slices)
+        hipLaunchKernelGGL((bspmm_kernel<4, true>), g, b, lds_bytes, stream, P);
+    else if (vec4)
+        hipLaunchKernelGGL((bspmm_kernel<4, false>), g, b, lds_bytes, stream, P);
+    else if (slices)
+        hipLaunchKernelGGL((bspmm_kernel<1, true>), g, b, lds_bytes, stream, P);
     else
-        hipLaunchKernelGGL(bspmm_kernel<1>, dim3(grid), dim3(kThreads), lds_bytes, stream, P);
+        hipLaunchKernelGGL((bspmm_kernel<1, false>), g, b, lds_bytes, stream, P);
     return hipGetLastError();
 }
 

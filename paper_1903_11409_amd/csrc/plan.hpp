@@ -33,12 +33,15 @@ struct alignas(16) WorkItem {
     int32_t nrows;        // output rows of this item (0 = empty item)
     int32_t f0;           // first feature column
     int32_t fw;           // feature columns
-    int32_t staged;       // 1: whole operation and its dense tile staged in LDS; 0: generic
+    int32_t staged;       // bit 0: operation and dense tile staged in LDS (0 = generic bin);
+                          // bit 1: no other item reads this dense tile (stream it)
 };
 static_assert(sizeof(WorkItem) == 64, "WorkItem must be 64 bytes");
 
-// Kernel argument block, passed by value.  Workgroup w belongs to range r when
-// wg_end[r-1] <= w < wg_end[r]; its first item is item_base[r] + (w - wg_end[r-1]) * slots(r).
+// Kernel argument block, passed by value.  Task t belongs to range r when
+// wg_end[r-1] <= t < wg_end[r]; its first item is item_base[r] + (t - wg_end[r-1]) * slots(r).
+// The launch has min(n_tasks, resident workgroups) workgroups; workgroup w runs tasks
+// w, w + gridDim.x, ...
 struct LaunchParams {
     const WorkItem* items;
     const int32_t* rpt;
@@ -50,6 +53,7 @@ struct LaunchParams {
     int64_t ld_out;
     int32_t wg_end[kRanges];
     int32_t item_base[kRanges];
+    int32_t n_tasks;      // == wg_end[kRanges-1]
     int32_t lds_floats;   // LDS per workgroup, in 4-byte words
     int32_t pad;          // words added to every staged dense row
 #ifdef BSPMM_TRACE

@@ -88,7 +88,7 @@ bool fits_slot(const DirOps& o, int i, int tile, int F, int vec, int lanes, int 
 
 // Decide bin and tile of operation i given the batch-wide tile candidates from `first` on.
 Choice choose(const DirOps& o, int i, int F, int vec, const std::vector<int>& cand, size_t first,
-              const Knobs& kn)
+              const Knobs& kn, bool allow_small)
 {
     const int forced = kn.force_bin;
     if (forced == BSPMM_BIN_GENERIC) return {BSPMM_BIN_GENERIC, cand[0]};
@@ -100,7 +100,7 @@ Choice choose(const DirOps& o, int i, int F, int vec, const std::vector<int>& ca
     const int tile = cand[first];
     static const int small_bins[3] = {BSPMM_BIN_SLICE16, BSPMM_BIN_SLICE32, BSPMM_BIN_WAVE};
     for (int b : small_bins)
-        if (fits_slot(o, i, tile, F, vec, bin_slot_lanes(b), kn.max_passes, kn))
+        if (allow_small && fits_slot(o, i, tile, F, vec, bin_slot_lanes(b), kn.max_passes, kn))
             return {b, tile};
     for (size_t c = first; c < cand.size(); ++c)
         if (fits_slot(o, i, cand[c], F, vec, kThreads, 0, kn))
@@ -152,12 +152,13 @@ void draft_op(const DirOps& o, int i, int F, int vec, const Choice& ch, const Kn
 }
 
 std::vector<Draft> draft_all(const DirOps& o, int F, int vec, const std::vector<int>& cand,
-                             size_t first, const Knobs& kn, int cap)
+                             size_t first, const Knobs& kn, int cap, bool allow_small)
 {
     std::vector<Draft> d;
     std::map<std::pair<int64_t, int>, int> groups;
     for (int i = 0; i < o.size(); ++i)
-        draft_op(o, i, F, vec, choose(o, i, F, vec, cand, first, kn), kn, cap, groups, d);
+        draft_op(o, i, F, vec, choose(o, i, F, vec, cand, first, kn, allow_small), kn, cap, groups,
+                 d);
     return d;
 }
 
@@ -218,6 +219,7 @@ Knobs resolve_knobs(const bspmm_options* o)
     if (o->max_passes > 0) k.max_passes = o->max_passes;
     if (o->generic_rows > 0) k.generic_rows = o->generic_rows;
     k.wg_passes = o->wg_passes;
+    if (o->resident_workgroups > 0) k.persistent_wgs = o->resident_workgroups;
     return k;
 }
 
@@ -232,20 +234,29 @@ Schedule make_schedule(const DirOps& ops, int F, const Knobs& kn_in)
     // widest batch-wide tile that still gives the launch enough workgroups
     std::vector<Draft> d;
     size_t chosen = cand.size() - 1;
+    // Sub-workgroup slots pack several small items into one workgroup.  Measured on MI355X
+    // that only pays when the launch is over-subscribed (more workgroups than the chip holds
+    // at once); a launch that fits is latency-bound and every item is fastest with a whole
+    // workgroup staging it.  A forced bin overrides this.
     const int fixed_cap = kn.wg_passes > 0 ? kn.wg_passes : 0;
-    for (size_t c = 0; c < cand.size(); ++c) {
-        d = draft_all(ops, F, vec, cand, c, kn, fixed_cap);
-        if (count_workgroups(d) >= kn.target_wgs || c + 1 == cand.size()) {
-            chosen = c;
-            break;
+    bool allow_small = kn.force_bin >= 0;
+    for (int attempt = 0; attempt < 2; ++attempt) {
+        for (size_t c = 0; c < cand.size(); ++c) {
+            d = draft_all(ops, F, vec, cand, c, kn, fixed_cap, allow_small);
+            if (count_workgroups(d) >= kn.target_wgs || c + 1 == cand.size()) {
+                chosen = c;
+                break;
+            }
         }
+        if (allow_small || count_workgroups(d) <= kn.capacity_wgs) break;
+        allow_small = true;
     }
     s.tile = cand[chosen];
     // still too few workgroups at the narrowest tile: the batch is small, its time is set by
     // the slowest workgroup, so cut multi-pass workgroup items into row ranges
     if (kn.wg_passes == 0 && count_workgroups(d) < kn.target_wgs) {
         for (int cap = 4; cap >= 1; cap /= 2) {
-            d = draft_all(ops, F, vec, cand, chosen, kn, cap);
+            d = draft_all(ops, F, vec, cand, chosen, kn, cap, allow_small);
             if (count_workgroups(d) >= kn.target_wgs) break;
         }
     }
@@ -254,7 +265,13 @@ Schedule make_schedule(const DirOps& ops, int F, const Knobs& kn_in)
     int ngroups = 0;
     for (const Draft& x : d) ngroups = std::max(ngroups, x.group + 1);
     std::vector<int64_t> gcost(ngroups, 0);
-    for (const Draft& x : d) gcost[x.group] = std::max(gcost[x.group], x.cost);
+    std::vector<int> gsize(ngroups, 0);
+    for (const Draft& x : d) {
+        gcost[x.group] = std::max(gcost[x.group], x.cost);
+        ++gsize[x.group];
+    }
+    for (Draft& x : d)
+        if (x.staged && gsize[x.group] == 1) x.staged |= 2;   // nobody else reads this tile
 
     std::vector<std::vector<int>> by_range(kRanges);
     for (int idx = 0; idx < (int)d.size(); ++idx) by_range[bin_range(d[idx].bin)].push_back(idx);
@@ -288,6 +305,25 @@ Schedule make_schedule(const DirOps& ops, int F, const Knobs& kn_in)
     for (auto& l : xcd) longest = std::max(longest, l.size());
     const int grid0 = (int)(longest * kXcds);
 
+    // Optional persistent launch (off by default: the hardware dispatcher balances uneven
+    // tasks better than a static stride): W workgroups take tasks w, w+W, ...  With the lists
+    // sorted largest-first, every second round of W tasks is laid out backwards (in whole
+    // groups of eight, so a task keeps its XCD) and the workgroup that drew the largest task
+    // of one round draws the smallest of the next.
+    bool slices = false;
+    for (const Draft& x : d) slices = slices || x.bin == BSPMM_BIN_SLICE32 || x.bin == BSPMM_BIN_SLICE16;
+    s.has_slices = slices;
+    const int capacity = slices ? kn.capacity_wgs_slices : kn.capacity_wgs;
+    const int W = std::max(kXcds, (kn.persistent_wgs > 0 ? kn.persistent_wgs : capacity) / kXcds * kXcds);
+    const size_t per_round = (size_t)W / kXcds;
+    for (auto& l : xcd) {
+        l.resize(longest, -1);
+        for (size_t a = per_round; kn.persistent_wgs > 0 && a < longest; a += 2 * per_round) {
+            const size_t b = std::min(longest, a + per_round);
+            std::reverse(l.begin() + a, l.begin() + b);
+        }
+    }
+
     auto emit = [&](int draft_idx, int wg, int slot) {
         const Draft& x = d[draft_idx];
         s.items.push_back(to_item(ops, x));
@@ -298,7 +334,7 @@ Schedule make_schedule(const DirOps& ops, int F, const Knobs& kn_in)
     s.item_base[0] = 0;
     for (size_t pos = 0; pos < longest; ++pos)
         for (int x = 0; x < kXcds; ++x) {
-            if (pos < xcd[x].size())
+            if (xcd[x][pos] >= 0)
                 emit(xcd[x][pos], (int)(pos * kXcds + x), 0);
             else
                 s.items.push_back(empty_item());
@@ -317,6 +353,7 @@ Schedule make_schedule(const DirOps& ops, int F, const Knobs& kn_in)
         s.wg_end[r] = wg;
     }
     s.grid = wg;
+    s.launch_grid = kn.persistent_wgs > 0 ? std::min(wg, W) : wg;
     return s;
 }
 

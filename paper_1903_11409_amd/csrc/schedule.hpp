@@ -20,15 +20,18 @@ struct DirOps {
 // Scheduler knobs with defaults filled in.
 struct Knobs {
     int force_bin = -1;       // -1 automatic, else BSPMM_BIN_*
-    int lds_words = 8192;     // 32 KiB
+    int lds_words = 6144;     // 24 KiB: six workgroups per CU
     int min_tile = 32;
     int max_tile = 256;
     int target_wgs = 1024;
     int compute_units = 256;
     int pad = 0;
-    int max_passes = 2;
-    int generic_rows = 32;
+    int max_passes = 1;
+    int generic_rows = 16;
     int wg_passes = 0;        // 0 automatic, >0 cap on passes of a workgroup item, <0 never cut
+    int capacity_wgs = 1536;  // workgroups the chip holds at once (lean kernel variant)
+    int capacity_wgs_slices = 1024;   // same for the kernel variant with 32/16-lane slots
+    int persistent_wgs = 0;   // > 0: launch only this many workgroups and let them stride
 };
 
 struct Schedule {
@@ -36,7 +39,9 @@ struct Schedule {
     std::vector<bspmm_item> view;    // the non-empty items, for inspection
     int32_t wg_end[kRanges] = {0, 0, 0, 0};
     int32_t item_base[kRanges] = {0, 0, 0, 0};
-    int grid = 0;
+    int grid = 0;                    // number of tasks
+    int launch_grid = 0;             // workgroups of the persistent launch
+    bool has_slices = false;         // any 32- or 16-lane item: needs the larger kernel variant
     int tile = 0;
     int items_in_bin[BSPMM_NUM_BINS] = {0, 0, 0, 0, 0};
 };

@@ -221,6 +221,8 @@ def test_every_bin_alone(torch_cuda, oracle, bin_, F):
                                 {"max_tile": 64}, {"lds_bytes": 65536}, {"lds_bytes": 8192},
                                 {"target_workgroups": 64}, {"max_passes": 4},
                                 {"wg_passes": 1}, {"wg_passes": -1, "target_workgroups": 4096},
+                                {"resident_workgroups": 64}, {"resident_workgroups": 24},
+                                {"resident_workgroups": 8, "lds_bytes": 16384},
                                 {"generic_rows": 8, "lds_bytes": 4096}])
 def test_scheduler_knobs_do_not_change_results(torch_cuda, oracle, kw):
     b = W.config5_skewed(graphs=96, F=128)

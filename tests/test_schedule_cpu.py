@@ -33,9 +33,9 @@ def test_library_exports_every_declared_symbol():
 
 def test_struct_sizes_match_header():
     assert ctypes.sizeof(K.bspmm_item) == 32
-    assert ctypes.sizeof(K.bspmm_options) == 44
+    assert ctypes.sizeof(K.bspmm_options) == 48
     assert ctypes.sizeof(K.bspmm_batch) == 8 + 10 * 8
-    assert ctypes.sizeof(K.bspmm_info) == 16 + 8 + 8 + 8 + 40 + 8 + 16 + 8 + 8
+    assert ctypes.sizeof(K.bspmm_info) == 16 + 8 + 8 + 8 + 8 + 40 + 8 + 16 + 8 + 8
 
 
 def _slot_lanes(bin_):
@@ -67,7 +67,7 @@ def _check_schedule(b, F, transposed=False, **opts):
             cover[it.op][it.row0:it.row0 + it.nrows, it.f0:it.f0 + it.fw] += 1
             lanes = _slot_lanes(it.bin)
             assert 0 <= it.slot < 256 // lanes
-            assert 0 <= it.workgroup < info.workgroups[d]
+            assert 0 <= it.workgroup < info.tasks[d]
             assert (it.workgroup, it.slot) not in seen
             seen.add((it.workgroup, it.slot))
             if it.bin != K.BIN_GENERIC:
@@ -135,6 +135,7 @@ def test_forced_bins_still_cover(bin_):
                                   {"lds_bytes": 65536}, {"lds_bytes": 8192},
                                   {"target_workgroups": 64}, {"max_passes": 4},
                                   {"wg_passes": 1}, {"wg_passes": -1, "target_workgroups": 4096},
+                                  {"resident_workgroups": 64}, {"resident_workgroups": 24},
                                   {"generic_rows": 8, "lds_bytes": 4096}])
 def test_knobs_keep_the_invariants(opts):
     b = W.config5_skewed(graphs=64, F=128)
@@ -220,7 +221,7 @@ def test_empty_batch_and_workspace_size():
     e = W.random_general(1, F=8, shapes=[], with_dY=False)
     h = K.dry_plan(e)
     info = K.bspmm_plan_info(h)
-    assert info.workgroups[0] == 0 and info.items[0] == 0
+    assert info.workgroups[0] == 0 and info.tasks[0] == 0 and info.items[0] == 0
     K.bspmm_destroy(h)
     b = W.config2_molecule(graphs=16)
     hb = K.HostBatch(b.rows, b.cols, b.nnz, b.rpt_off, b.nz_off, b.b_row_off, b.c_row_off)
