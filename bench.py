@@ -268,8 +268,8 @@ def read_traffic():
 def main():
     args = parse_args()
     if args.gpus != 1:
-        print("bench.py: this build measures one GPU; --gpus must be 1 (batches shard across "
-              "GPUs without any exchange, see DESIGN.md)", file=sys.stderr)
+        print("bench.py: this build runs on one GPU only; --gpus must be 1 (a batch would shard "
+              "across GPUs by whole graphs, without any exchange)", file=sys.stderr)
         sys.exit(2)
     import torch
     from paper_1903_11409_amd import bspmm as K

@@ -59,6 +59,11 @@ extern "C" {
 /* bspmm_options.flags */
 #define BSPMM_DRY_RUN          1u  /* schedule only: touch no device, run calls return ESTATE */
 #define BSPMM_BUILD_TRANSPOSE  2u  /* enqueue the transposed-CSR build inside bspmm_create    */
+#define BSPMM_SPLIT_HUB_ROWS   8u  /* rows with >= 64 entries and >= 4x the operation's average are
+                                      split across all lanes of the workgroup and the partial
+                                      sums reduced (DPP / ds_swizzle inside a wavefront, LDS across
+                                      wavefronts).  For graphs with hub nodes; plain batches are a
+                                      few per cent faster without it                             */
 #define BSPMM_FLOOR_PROBE      4u  /* measurement aid: same grid, LDS and item fetches, but every
                                       item is emptied, so a run computes and writes nothing      */
 
@@ -89,7 +94,7 @@ typedef struct bspmm_batch {
 
 /* Scheduler knobs.  Zero-initialise for defaults. */
 typedef struct bspmm_options {
-    uint32_t flags;            /* BSPMM_DRY_RUN | BSPMM_BUILD_TRANSPOSE | BSPMM_FLOOR_PROBE    */
+    uint32_t flags;            /* BSPMM_DRY_RUN | BSPMM_BUILD_TRANSPOSE | BSPMM_SPLIT_HUB_ROWS */
     int32_t  force_bin;        /* 0 = automatic; 1+b forces bin b for every op that fits it    */
     int32_t  lds_bytes;        /* LDS per workgroup, 0 = default (24 KiB); <= 64 KiB           */
     int32_t  min_tile;         /* narrowest feature tile in floats, 0 = default (32)           */

@@ -14,12 +14,12 @@
 
 namespace bspmm {
 hipError_t launch_bspmm(const LaunchParams& P, int grid, int lds_bytes, bool vec4, bool slices,
-                        hipStream_t stream);
+                        bool hubs, hipStream_t stream);
 hipError_t launch_build_transpose(const OpRecord* ops, int batch, int lds_bytes,
                                   const int32_t* rpt, const int32_t* colids,
                                   const float* values, int32_t* rpt_t, int32_t* colids_t,
                                   float* values_t, int32_t* gscratch, hipStream_t stream);
-int bspmm_max_resident_workgroups(int lds_bytes, bool slices);
+int bspmm_max_resident_workgroups(int lds_bytes, bool slices, bool hubs);
 hipError_t launch_validate(const OpRecord* ops, int batch, const int32_t* rpt,
                            const int32_t* colids, int32_t* flag, hipStream_t stream);
 }  // namespace bspmm
@@ -229,8 +229,8 @@ Knobs knobs_for(const bspmm_options* o, bool ask_device)
             (void)hipGetLastError();
     }
     if (!(o && o->target_workgroups > 0)) kn.target_wgs = 4 * kn.compute_units;
-    const int r = ask_device ? bspmm_max_resident_workgroups(kn.lds_words * 4, false) : 0;
-    const int rs = ask_device ? bspmm_max_resident_workgroups(kn.lds_words * 4, true) : 0;
+    const int r = ask_device ? bspmm_max_resident_workgroups(kn.lds_words * 4, false, kn.hubs) : 0;
+    const int rs = ask_device ? bspmm_max_resident_workgroups(kn.lds_words * 4, true, kn.hubs) : 0;
     kn.capacity_wgs = r > 0 ? r : 6 * kn.compute_units;
     kn.capacity_wgs_slices = rs > 0 ? rs : 4 * kn.compute_units;
     return kn;
@@ -285,7 +285,8 @@ int run_direction(bspmm_plan* p, int d, const float* in, float* out, int64_t ld_
     const bool vec4 = p->F % 4 == 0 && ld_in % 4 == 0 && ld_out % 4 == 0 &&
                       (reinterpret_cast<uintptr_t>(in) & 15) == 0 &&
                       (reinterpret_cast<uintptr_t>(out) & 15) == 0;
-    hipError_t e = launch_bspmm(P, sc.launch_grid, p->knobs.lds_words * 4, vec4, sc.has_slices, s);
+    hipError_t e = launch_bspmm(P, sc.launch_grid, p->knobs.lds_words * 4, vec4, sc.has_slices,
+                                p->knobs.hubs, s);
     return e == hipSuccess ? BSPMM_OK : hip_fail(e);
 }
 

@@ -97,12 +97,13 @@ struct Split {
 // first trip of every copy is issued before anything is waited for: one round trip stages a
 // typical molecule-sized item completely; larger items finish in unrolled leftover loops.
 // ---------------------------------------------------------------------------------------
-template <int S, int VEC>
+template <int S, int VEC, bool HUBS>
 __device__ __forceinline__ void stage_item(const LaunchParams& P, const WorkItem& it, int* sm,
                                            int lane)
 {
     using VT = typename Vec<VEC>::type;
-    const StagedLayout L = staged_layout(it.m, it.k, it.nnz, it.fw, P.pad);
+    const StagedLayout L = staged_layout(it.m, it.k, it.nnz, it.fw, P.pad, HUBS && S == kThreads);
+    if (HUBS && S == kThreads && lane == 0) sm[L.hub_off] = 0;   // no hub row found yet
     const int32_t* __restrict__ rp = P.rpt + it.rpt_off;
     const int32_t* __restrict__ ci = P.colids + it.nz_off;
     const float* __restrict__ va = P.values + it.nz_off;
@@ -207,23 +208,120 @@ __device__ __forceinline__ void stage_item(const LaunchParams& P, const WorkItem
 }
 
 // ---------------------------------------------------------------------------------------
-// row gather-FMA from LDS and store
+// split-row reduce.  A hub row (hundreds of entries) would keep one lane group busy long after
+// the rest of the workgroup has finished, so its entries are dealt out to ALL lane groups of
+// the workgroup; each lane then holds a partial sum for its columns, and the partial sums of the
+// groups are added up: inside a wavefront with DPP row rotations (distance < 16),
+// ds_swizzle (16) and ds_bpermute (32), across the four wavefronts through one tile row of LDS
+// each, in a fixed order (the result does not depend on timing).
 // ---------------------------------------------------------------------------------------
-template <int S, int VEC>
-__device__ __forceinline__ void compute_staged(const LaunchParams& P, const WorkItem& it,
-                                               const int* sm, int lane)
+__device__ __forceinline__ float add_from_lane_xor(float v, int off)
+{
+    switch (off) {
+        case 1: return v + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x121, 0xf, 0xf, false));
+        case 2: return v + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x122, 0xf, 0xf, false));
+        case 4: return v + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x124, 0xf, 0xf, false));
+        case 8: return v + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x128, 0xf, 0xf, false));
+        case 16: return v + __int_as_float(__builtin_amdgcn_ds_swizzle(__float_as_int(v), (16 << 10) | 0x1f));
+        default: return v + __shfl_xor(v, 32);
+    }
+}
+
+// Sum over the lane groups of one wavefront: afterwards every lane holds the total of the
+// lanes that share its position inside a group (rotations by g, 2g, ... inside rows of 16
+// lanes visit every group of the row; 16 and 32 are true exchanges).
+template <int VEC>
+__device__ __forceinline__ void wave_group_sum(typename Vec<VEC>::type& a, int g_lanes)
+{
+    for (int off = g_lanes; off < 64; off <<= 1) {
+        if constexpr (VEC == 4) {
+            a.x = add_from_lane_xor(a.x, off);
+            a.y = add_from_lane_xor(a.y, off);
+            a.z = add_from_lane_xor(a.z, off);
+            a.w = add_from_lane_xor(a.w, off);
+        } else {
+            a = add_from_lane_xor(a, off);
+        }
+    }
+}
+
+// One hub row computed by the whole workgroup.  `load_entry(p)` yields (column, value) of entry
+// p, `bcol` addresses this lane's vector of dense row 0, `stride` is the dense row stride.
+// Contains two barriers: every lane of the workgroup must call it.
+template <int VEC, typename Entry>
+__device__ __forceinline__ void hub_row(int p0, int p1, Entry load_entry, const float* bcol,
+                                        int64_t stride, bool col_ok, int g_lanes, int groups,
+                                        int g, int l, float* scratch, int fwp, float* out_row)
 {
     using V = Vec<VEC>;
-    const StagedLayout L = staged_layout(it.m, it.k, it.nnz, it.fw, P.pad);
+    using VT = typename V::type;
+    VT acc = V::zero();
+    if (col_ok) {
+        int p = p0 + g;
+        for (; p + 3 * groups < p1; p += 4 * groups) {
+            const int2 e0 = load_entry(p), e1 = load_entry(p + groups),
+                       e2 = load_entry(p + 2 * groups), e3 = load_entry(p + 3 * groups);
+            const VT b0 = load_vec<VEC>(bcol + e0.x * stride);
+            const VT b1 = load_vec<VEC>(bcol + e1.x * stride);
+            const VT b2 = load_vec<VEC>(bcol + e2.x * stride);
+            const VT b3 = load_vec<VEC>(bcol + e3.x * stride);
+            V::fma(acc, __int_as_float(e0.y), b0);
+            V::fma(acc, __int_as_float(e1.y), b1);
+            V::fma(acc, __int_as_float(e2.y), b2);
+            V::fma(acc, __int_as_float(e3.y), b3);
+        }
+        for (; p < p1; p += groups) {
+            const int2 e = load_entry(p);
+            V::fma(acc, __int_as_float(e.y), load_vec<VEC>(bcol + e.x * stride));
+        }
+    }
+    wave_group_sum<VEC>(acc, g_lanes);
+    const int wave = threadIdx.x >> 6;
+    if ((threadIdx.x & 63) < g_lanes && col_ok) store_vec<VEC>(scratch + wave * fwp + l * VEC, acc);
+    __syncthreads();
+    if (threadIdx.x < g_lanes && col_ok) {
+        VT t = load_vec<VEC>(scratch + l * VEC);
+#pragma unroll
+        for (int w = 1; w < kThreads / 64; ++w) {
+            const VT u = load_vec<VEC>(scratch + w * fwp + l * VEC);
+            if constexpr (VEC == 4) {
+                t.x += u.x; t.y += u.y; t.z += u.z; t.w += u.w;
+            } else {
+                t += u;
+            }
+        }
+        store_out<VEC>(out_row + l * VEC, t);
+    }
+    __syncthreads();
+}
+
+// ---------------------------------------------------------------------------------------
+// row gather-FMA from LDS and store
+// ---------------------------------------------------------------------------------------
+template <int S, int VEC, bool HUBS>
+__device__ __forceinline__ void compute_staged(const LaunchParams& P, const WorkItem& it,
+                                               int* sm, int lane)
+{
+    using V = Vec<VEC>;
+    constexpr bool kHubs = HUBS && S == kThreads;
+    const StagedLayout L = staged_layout(it.m, it.k, it.nnz, it.fw, P.pad, kHubs);
     const int2* cv = reinterpret_cast<const int2*>(sm + L.cv_off);
     const float* bs = reinterpret_cast<const float*>(sm + L.b_off);
     const Split<S, VEC> sp(it.fw, lane);
     float* __restrict__ dst = P.out + it.out_row_off * P.ld_out + it.f0;
+    // hub rows need one vector per lane (always true on the float4 path)
+    const bool hubs_on = kHubs && sp.nvec <= sp.g_lanes;
+    const int hub_deg = max(kHubMin, kHubRatio * ((it.nnz + it.m - 1) / max(it.m, 1)));
+    int* hub = sm + L.hub_off;
 
     const int row_end = it.row0 + it.nrows;
     for (int r = it.row0 + sp.g; r < row_end; r += sp.groups) {
         const int p0 = sm[r];
         const int p1 = sm[r + 1];
+        if (hubs_on && p1 - p0 >= hub_deg) {
+            if (sp.l == 0) hub[1 + atomicAdd(&hub[0], 1)] = r;   // left to the whole workgroup
+            continue;
+        }
         for (int v = sp.l; v < sp.nvec; v += sp.g_lanes) {
             const float* bcol = bs + v * VEC;
             typename V::type acc = V::zero();
@@ -246,6 +344,19 @@ __device__ __forceinline__ void compute_staged(const LaunchParams& P, const Work
             store_out<VEC>(dst + (int64_t)r * P.ld_out + v * VEC, acc);
         }
     }
+    if constexpr (kHubs) {
+        if (!hubs_on) return;          // uniform: depends on the item only
+        __syncthreads();               // the hub list is complete
+        const int n_hub = hub[0];
+        const int fwp = round_up(it.fw, 4);
+        float* scratch = reinterpret_cast<float*>(hub + round_up(1 + it.nnz / kHubMin, 4));
+        for (int h = 0; h < n_hub; ++h) {
+            const int r = hub[1 + h];
+            hub_row<VEC>(sm[r], sm[r + 1], [cv](int p) { return cv[p]; }, bs + sp.l * VEC,
+                         (int64_t)L.stride, sp.l < sp.nvec, sp.g_lanes, sp.groups, sp.g, sp.l,
+                         scratch, fwp, dst + (int64_t)r * P.ld_out);
+        }
+    }
 }
 
 // Generic bin: the operation's dense tile does not fit LDS, so a row block gathers it from
@@ -254,7 +365,7 @@ __device__ __forceinline__ void compute_staged(const LaunchParams& P, const Work
 // then the entries they delimit); after that every gather of a row is independent and up to
 // four are in flight per lane (deeper
 // unrolling costs registers, hence occupancy, and measured slower).
-template <int VEC>
+template <int VEC, bool HUBS>
 __device__ __forceinline__ void run_generic(const LaunchParams& P, const WorkItem& it, int* sm,
                                             int tid)
 {
@@ -269,9 +380,12 @@ __device__ __forceinline__ void run_generic(const LaunchParams& P, const WorkIte
     const int pbeg = __builtin_amdgcn_readfirstlane(sm[0]);
     const int cnt = max(__builtin_amdgcn_readfirstlane(sm[nrows]) - pbeg, 0);
     const int cv_off = round_up(nrows + 1, 2);
-    const bool fits = cv_off + 2 * cnt <= P.lds_floats;
+    const int hub_off = round_up(cv_off + 2 * cnt, 4);
+    const bool fits = hub_off + (HUBS ? hub_words(nrows, it.fw) : 0) <= P.lds_floats;
     int2* cv = reinterpret_cast<int2*>(sm + cv_off);
+    int* hub = sm + hub_off;
     if (fits) {
+        if (HUBS && tid == 0) hub[0] = 0;
         for (int p = tid; p < cnt; p += 2 * kThreads) {
             const int q = p + kThreads;
             const int c0 = ci[pbeg + p];
@@ -291,9 +405,15 @@ __device__ __forceinline__ void run_generic(const LaunchParams& P, const WorkIte
     const Split<kThreads, VEC> sp(it.fw, tid);
     const float* __restrict__ src = P.in + it.in_row_off * P.ld_in + it.f0;
     float* __restrict__ dst = P.out + (it.out_row_off + it.row0) * P.ld_out + it.f0;
+    const bool hubs_on = HUBS && fits && sp.nvec <= sp.g_lanes;
+    const int hub_deg = HUBS ? max(kHubMin, kHubRatio * ((it.nnz + it.m - 1) / max(it.m, 1))) : 0;
     for (int i = sp.g; i < nrows; i += sp.groups) {
         const int p0 = sm[i] - pbeg;
         const int p1 = sm[i + 1] - pbeg;
+        if (hubs_on && p1 - p0 >= hub_deg) {
+            if (sp.l == 0) hub[1 + atomicAdd(&hub[0], 1)] = i;   // left to the whole workgroup
+            continue;
+        }
         for (int v = sp.l; v < sp.nvec; v += sp.g_lanes) {
             const float* bcol = src + v * VEC;
             VT acc = V::zero();
@@ -326,10 +446,21 @@ __device__ __forceinline__ void run_generic(const LaunchParams& P, const WorkIte
             store_out<VEC>(dst + (int64_t)i * P.ld_out + v * VEC, acc);
         }
     }
+    if (!HUBS || !hubs_on) return;     // uniform: depends on the item and its row pointers
+    __syncthreads();                   // the hub list is complete
+    const int n_hub = hub[0];
+    const int fwp = round_up(it.fw, 4);
+    float* scratch = reinterpret_cast<float*>(hub + round_up(1 + nrows, 4));
+    for (int h = 0; h < n_hub; ++h) {
+        const int i = hub[1 + h];
+        hub_row<VEC>(sm[i] - pbeg, sm[i + 1] - pbeg, [cv](int p) { return cv[p]; },
+                     src + sp.l * VEC, P.ld_in, sp.l < sp.nvec, sp.g_lanes, sp.groups, sp.g, sp.l,
+                     scratch, fwp, dst + (int64_t)i * P.ld_out);
+    }
 }
 
 // One task of a sub-workgroup range: 256/S slots, one staged item each.
-template <int LOG2S, int VEC>
+template <int LOG2S, int VEC, bool HUBS>
 __device__ __forceinline__ void run_slots(const LaunchParams& P, int* sm, int first_item)
 {
     constexpr int S = 1 << LOG2S;
@@ -340,10 +471,10 @@ __device__ __forceinline__ void run_slots(const LaunchParams& P, int* sm, int fi
     if (LOG2S == 6) idx = __builtin_amdgcn_readfirstlane(idx);   // uniform inside a wavefront
     const WorkItem it = P.items[idx];
     int* slot_sm = sm + slot * (P.lds_floats >> (8 - LOG2S));
-    if (it.nrows > 0) stage_item<S, VEC>(P, it, slot_sm, lane);
+    if (it.nrows > 0) stage_item<S, VEC, HUBS>(P, it, slot_sm, lane);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // direct-to-LDS loads landed
     __syncthreads();
-    if (it.nrows > 0) compute_staged<S, VEC>(P, it, slot_sm, lane);
+    if (it.nrows > 0) compute_staged<S, VEC, HUBS>(P, it, slot_sm, lane);
 }
 
 #ifdef BSPMM_TRACE
@@ -367,7 +498,9 @@ __device__ __forceinline__ void run_slots(const LaunchParams& P, int* sm, int fi
 // slots.
 // SLICES = false leaves out the 32- and 16-lane slot code (per-lane item descriptors cost
 // registers, hence occupancy); the host launches it for schedules without such items.
-template <int VEC, bool SLICES>
+// HUBS = true adds the split-row path for hub rows (an option of the plan: it costs a
+// register-limited occupancy step and LDS for the reduction, which plain batches do not need).
+template <int VEC, bool SLICES, bool HUBS>
 __global__ void __launch_bounds__(kThreads) bspmm_kernel(const LaunchParams P)
 {
     extern __shared__ __align__(16) int sm[];
@@ -387,13 +520,13 @@ __global__ void __launch_bounds__(kThreads) bspmm_kernel(const LaunchParams P)
             if (it.nrows > 0) {
                 BSPMM_STAMP(t, 1);
                 if (it.staged) {
-                    stage_item<kThreads, VEC>(P, it, sm, tid);
+                    stage_item<kThreads, VEC, HUBS>(P, it, sm, tid);
                     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // direct-to-LDS loads landed
                     __syncthreads();
                     BSPMM_STAMP(t, 2);
-                    compute_staged<kThreads, VEC>(P, it, sm, tid);
+                    compute_staged<kThreads, VEC, HUBS>(P, it, sm, tid);
                 } else {
-                    run_generic<VEC>(P, it, sm, tid);
+                    run_generic<VEC, HUBS>(P, it, sm, tid);
                 }
                 BSPMM_STAMP(t, 3);
 #ifdef BSPMM_TRACE
@@ -416,12 +549,12 @@ __global__ void __launch_bounds__(kThreads) bspmm_kernel(const LaunchParams P)
     for (; t < P.n_tasks; t += stride) {
         __syncthreads();
         if (t < P.wg_end[1]) {
-            run_slots<6, VEC>(P, sm, P.item_base[1] + (t - P.wg_end[0]) * 4);
+            run_slots<6, VEC, HUBS>(P, sm, P.item_base[1] + (t - P.wg_end[0]) * 4);
         } else if (SLICES) {
             if (t < P.wg_end[2])
-                run_slots<5, VEC>(P, sm, P.item_base[2] + (t - P.wg_end[1]) * 8);
+                run_slots<5, VEC, HUBS>(P, sm, P.item_base[2] + (t - P.wg_end[1]) * 8);
             else
-                run_slots<4, VEC>(P, sm, P.item_base[3] + (t - P.wg_end[2]) * 16);
+                run_slots<4, VEC, HUBS>(P, sm, P.item_base[3] + (t - P.wg_end[2]) * 16);
         }
     }
 }
@@ -541,22 +674,30 @@ __global__ void fill_i32_kernel(int32_t* p, int32_t v, int n)
 // ---------------------------------------------------------------------------------------
 // host-side launchers (the only symbols the rest of the library sees)
 // ---------------------------------------------------------------------------------------
+using KernelFn = void (*)(const LaunchParams);
+
+static KernelFn kernel_variant(bool vec4, bool slices, bool hubs)
+{
+    static const KernelFn table[8] = {
+        bspmm_kernel<1, false, false>, bspmm_kernel<1, false, true>,
+        bspmm_kernel<1, true, false>,  bspmm_kernel<1, true, true>,
+        bspmm_kernel<4, false, false>, bspmm_kernel<4, false, true>,
+        bspmm_kernel<4, true, false>,  bspmm_kernel<4, true, true>};
+    return table[(vec4 ? 4 : 0) + (slices ? 2 : 0) + (hubs ? 1 : 0)];
+}
+
 // Workgroups of bspmm_kernel the current device holds at once (0 if it cannot be asked).
-int bspmm_max_resident_workgroups(int lds_bytes, bool slices)
+int bspmm_max_resident_workgroups(int lds_bytes, bool slices, bool hubs)
 {
     int per_cu4 = 0, per_cu1 = 0, dev = 0, cus = 0;
     hipError_t e = hipGetDevice(&dev);
     if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
     if (e == hipSuccess)
-        e = slices ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu4, bspmm_kernel<4, true>,
-                                                                  kThreads, (size_t)lds_bytes)
-                   : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu4, bspmm_kernel<4, false>,
-                                                                  kThreads, (size_t)lds_bytes);
+        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu4, kernel_variant(true, slices, hubs),
+                                                         kThreads, (size_t)lds_bytes);
     if (e == hipSuccess)
-        e = slices ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu1, bspmm_kernel<1, true>,
-                                                                  kThreads, (size_t)lds_bytes)
-                   : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu1, bspmm_kernel<1, false>,
-                                                                  kThreads, (size_t)lds_bytes);
+        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu1, kernel_variant(false, slices, hubs),
+                                                         kThreads, (size_t)lds_bytes);
     if (e != hipSuccess) {
         (void)hipGetLastError();
         return 0;
@@ -566,18 +707,11 @@ int bspmm_max_resident_workgroups(int lds_bytes, bool slices)
 }
 
 hipError_t launch_bspmm(const LaunchParams& P, int grid, int lds_bytes, bool vec4, bool slices,
-                        hipStream_t stream)
+                        bool hubs, hipStream_t stream)
 {
     if (grid <= 0) return hipSuccess;
-    const dim3 g(grid), b(kThreads);
-    if (vec4 && slices)
-        hipLaunchKernelGGL((bspmm_kernel<4, true>), g, b, lds_bytes, stream, P);
-    else if (vec4)
-        hipLaunchKernelGGL((bspmm_kernel<4, false>), g, b, lds_bytes, stream, P);
-    else if (slices)
-        hipLaunchKernelGGL((bspmm_kernel<1, true>), g, b, lds_bytes, stream, P);
-    else
-        hipLaunchKernelGGL((bspmm_kernel<1, false>), g, b, lds_bytes, stream, P);
+    hipLaunchKernelGGL(kernel_variant(vec4, slices, hubs), dim3(grid), dim3(kThreads), lds_bytes,
+                       stream, P);
     return hipGetLastError();
 }
 

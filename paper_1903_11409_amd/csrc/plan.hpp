@@ -87,20 +87,35 @@ BSPMM_HD inline int pow2_ceil(int x)
 //   [0, m+1)                      row pointers (clamped to nnz)
 //   [cv_off, cv_off + 2*nnz)      (column, value) pairs
 //   [b_off, b_off + k*stride)     dense tile, row stride `stride`
+//   [hub_off, total)              workgroup items only: hub-row list and reduction scratch
 struct StagedLayout {
     int cv_off;
     int b_off;
     int stride;
+    int hub_off;
     int total;
 };
 
-BSPMM_HD inline StagedLayout staged_layout(int m, int k, int nnz, int fw, int pad)
+// A row is a hub when it has at least kHubMin entries and at least kHubRatio times the
+// average of its operation; its entries are then split across all lane groups.
+constexpr int kHubMin = 64;
+constexpr int kHubRatio = 4;
+
+// Words of the hub area: a counter, one slot per possible hub row, and one tile row per
+// wavefront for the cross-wavefront sum (16-byte aligned).
+BSPMM_HD inline int hub_words(int max_hubs, int fw)
+{
+    return round_up(1 + max_hubs, 4) + (kThreads / 64) * round_up(fw, 4);
+}
+
+BSPMM_HD inline StagedLayout staged_layout(int m, int k, int nnz, int fw, int pad, bool hub)
 {
     StagedLayout L;
     L.cv_off = round_up(m + 1, 2);
     L.b_off = round_up(L.cv_off + 2 * nnz, 4);
     L.stride = round_up(fw, 4) + pad;
-    L.total = L.b_off + k * L.stride;
+    L.hub_off = L.b_off + k * L.stride;
+    L.total = L.hub_off + (hub ? hub_words(nnz / kHubMin, fw) : 0);
     return L;
 }
 

@@ -82,7 +82,8 @@ bool fits_slot(const DirOps& o, int i, int tile, int F, int vec, int lanes, int 
     const int64_t lanes_wanted = (int64_t)o.m[i] * g;
     if (max_passes > 0 && (lanes_wanted + lanes - 1) / lanes > max_passes) return false;
     const int64_t head = (int64_t)round_up(o.m[i] + 1, 2) + 2 * (int64_t)o.nnz[i];
-    const int64_t need = (head + 3) / 4 * 4 + (int64_t)o.k[i] * (round_up(fw, 4) + kn.pad);
+    int64_t need = (head + 3) / 4 * 4 + (int64_t)o.k[i] * (round_up(fw, 4) + kn.pad);
+    if (kn.hubs && lanes == kThreads) need += hub_words(o.nnz[i] / kHubMin, fw);   // as staged_layout()
     return need <= (int64_t)kn.lds_words * lanes / kThreads;
 }
 
@@ -220,6 +221,7 @@ Knobs resolve_knobs(const bspmm_options* o)
     if (o->generic_rows > 0) k.generic_rows = o->generic_rows;
     k.wg_passes = o->wg_passes;
     if (o->resident_workgroups > 0) k.persistent_wgs = o->resident_workgroups;
+    k.hubs = (o->flags & BSPMM_SPLIT_HUB_ROWS) != 0;
     return k;
 }
 

@@ -31,6 +31,7 @@ struct Knobs {
     int wg_passes = 0;        // 0 automatic, >0 cap on passes of a workgroup item, <0 never cut
     int capacity_wgs = 1536;  // workgroups the chip holds at once (lean kernel variant)
     int capacity_wgs_slices = 1024;   // same for the kernel variant with 32/16-lane slots
+    bool hubs = false;        // split hub rows across the workgroup (reserves LDS for it)
     int persistent_wgs = 0;   // > 0: launch only this many workgroups and let them stride
 };
 

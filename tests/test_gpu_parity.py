@@ -196,6 +196,27 @@ def test_identity_is_bitwise_and_hub_rows(torch_cuda, oracle):
     _check_forward(torch_cuda, oracle, small_hub)
 
 
+@pytest.mark.parametrize("maker", [
+    lambda: W.hub_batch(21, F=32, n=100, copies=5),        # staged, 8 lanes per row
+    lambda: W.hub_batch(22, F=128, n=150, copies=3),       # staged, tile of 32 or more
+    lambda: W.hub_batch(23, F=256, n=90, copies=2),        # one wavefront per row
+    lambda: W.hub_batch(24, F=64, n=700),                  # generic bin
+    lambda: W.hub_batch(25, F=256, n=2000, copies=1),      # generic, wide tile
+    lambda: W.hub_batch(26, F=20, n=300),                  # 5 float4 per row: idle lanes
+    lambda: W.hub_batch(27, F=63, n=300),                  # scalar path
+    lambda: W.config5_skewed(graphs=64, F=128),            # no hub rows at all
+])
+def test_split_hub_rows(torch_cuda, oracle, maker):
+    """Rows with hundreds of entries are split across the workgroup and reduced; results stay
+    inside the same tolerance and are bitwise repeatable."""
+    b = maker()
+    opts = K.make_options(flags=K.SPLIT_HUB_ROWS)
+    plan, got = _check_forward(torch_cuda, oracle, b, opts, what=f"hub split {b.name} F={b.F}")
+    _check_transposed(torch_cuda, oracle, b, plan=plan, what=f"hub split {b.name} F={b.F}")
+    _, again = _forward(torch_cuda, b, opts)
+    assert np.array_equal(got, again)
+
+
 def test_empty_batch_and_all_empty_matrices(torch_cuda, oracle):
     e = W.random_general(1, F=8, shapes=[])
     plan = K.Plan(e)
@@ -235,6 +256,36 @@ def test_scalar_path_for_unaligned_operands(torch_cuda, oracle):
     _check_forward(torch_cuda, oracle, b, ld_extra=3, what="ld = F+3")
     _check_forward(torch_cuda, oracle, b, offset=1, what="C misaligned by one float")
     _check_forward(torch_cuda, oracle, b, ld_extra=4, offset=4, what="ld = F+4, aligned")
+
+
+def test_offsets_beyond_32_bits(torch_cuda, oracle):
+    """Leading dimensions of 2^20 floats put the later blocks more than 2^31 elements from
+    the base pointers: row offsets must be 64-bit all the way into the kernel."""
+    b = W.config2_molecule(graphs=96, F=64)
+    ld = 1 << 20
+    assert int(b.b_row_off.max()) * ld > 2 ** 31 and int(b.c_row_off.max()) * ld > 2 ** 31
+    plan = K.Plan(b)
+    Bd = torch_cuda.empty((b.n_b_rows, ld), dtype=torch_cuda.float32, device="cuda")
+    Cd = torch_cuda.empty((b.n_c_rows, ld), dtype=torch_cuda.float32, device="cuda")
+    Bd[:, :b.F] = torch_cuda.from_numpy(b.B).cuda()
+    Cd[:, :b.F + 4] = SENTINEL
+    plan.run(Bd, Cd)
+    gb = dataclasses.replace(b, dY=np.random.default_rng(2).standard_normal(
+        (b.n_c_rows, b.F)).astype(np.float32))
+    Cd2 = torch_cuda.empty((b.n_c_rows, ld), dtype=torch_cuda.float32, device="cuda")
+    Cd2[:, :b.F] = torch_cuda.from_numpy(gb.dY).cuda()
+    Gd = torch_cuda.empty((b.n_b_rows, ld), dtype=torch_cuda.float32, device="cuda")
+    Gd[:, :b.F + 4] = SENTINEL
+    plan.run_transposed(Cd2, Gd)
+    torch_cuda.cuda.synchronize()
+    ref, S = oracle.forward_batch(b)
+    own = np.ones(b.n_c_rows, dtype=bool)
+    _assert_close(Cd[:, :b.F].cpu().numpy(), ref, S, own, "ld = 2^20")
+    assert torch_cuda.all(Cd[:, b.F:b.F + 4] == SENTINEL)
+    refT, ST = oracle.transposed_batch(gb)
+    _assert_close(Gd[:, :b.F].cpu().numpy(), refT, ST, np.ones(b.n_b_rows, dtype=bool),
+                  "ld = 2^20 transposed")
+    assert torch_cuda.all(Gd[:, b.F:b.F + 4] == SENTINEL)
 
 
 def test_run_to_run_determinism(torch_cuda):

@@ -43,10 +43,13 @@ def _slot_lanes(bin_):
             K.BIN_GENERIC: 256}[bin_]
 
 
-def _lds_words(m, k, nnz, fw, pad):
+def _lds_words(m, k, nnz, fw, pad, lanes, hubs):
     cv = (m + 1 + 1) // 2 * 2
     b_off = (cv + 2 * nnz + 3) // 4 * 4
-    return b_off + k * ((fw + 3) // 4 * 4 + pad)
+    words = b_off + k * ((fw + 3) // 4 * 4 + pad)
+    if lanes == 256 and hubs:   # hub-row list and reduction scratch of workgroup items
+        words += (1 + nnz // 64 + 3) // 4 * 4 + 4 * ((fw + 3) // 4 * 4)
+    return words
 
 
 def _check_schedule(b, F, transposed=False, **opts):
@@ -73,7 +76,7 @@ def _check_schedule(b, F, transposed=False, **opts):
             if it.bin != K.BIN_GENERIC:
                 if it.bin != K.BIN_WORKGROUP:   # only workgroup items may be cut into row ranges
                     assert it.row0 == 0 and it.nrows == int(m_of[it.op])
-                need = _lds_words(int(m_of[it.op]), int(k_of[it.op]), int(b.nnz[it.op]), it.fw, pad)
+                need = _lds_words(int(m_of[it.op]), int(k_of[it.op]), int(b.nnz[it.op]), it.fw, pad, lanes, bool(opts.get('flags', 0) & K.SPLIT_HUB_ROWS))
                 assert need * 4 <= info.lds_bytes * lanes // 256
                 if F % 4 == 0:
                     assert it.f0 % 4 == 0 and it.fw % 4 == 0
@@ -136,6 +139,7 @@ def test_forced_bins_still_cover(bin_):
                                   {"target_workgroups": 64}, {"max_passes": 4},
                                   {"wg_passes": 1}, {"wg_passes": -1, "target_workgroups": 4096},
                                   {"resident_workgroups": 64}, {"resident_workgroups": 24},
+                                  {"flags": K.SPLIT_HUB_ROWS},
                                   {"generic_rows": 8, "lds_bytes": 4096}])
 def test_knobs_keep_the_invariants(opts):
     b = W.config5_skewed(graphs=64, F=128)
