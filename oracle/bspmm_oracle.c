@@ -9,6 +9,10 @@
  *   forward     C_i[r][j] = sum_{p = rpt_i[r]}^{rpt_i[r+1]-1} values_i[p] * B_i[colids_i[p]][j]
  *   transposed  G_i[c][j] = sum_{r} sum_{p in row r, colids_i[p] == c} values_i[p] * dY_i[r][j]
  *
+ * Several operations may name the SAME output block (the graph-convolution layer adds up the
+ * products of a graph's channels, Fig. 6 / Fig. 7 "ElementWiseAdd"): the block then holds the sum
+ * of their products.  Blocks are zeroed first, then every operation adds into its block.
+ *
  * The loops are the four nested loops of that definition (operation, row, stored entry,
  * column), in that order, with no blocking, fusion or reordering.  fp32 inputs are promoted
  * to fp64 and accumulated in fp64; the result stays fp64.  Beside the result the oracle
@@ -47,7 +51,18 @@ static int check_op(int32_t rows, int32_t cols, int32_t nnz, const int32_t* rp,
     return 1;
 }
 
-/* Forward product of every operation; C and S are fully overwritten on the operation's rows. */
+/* 1 when two operations name overlapping row ranges (then they are summed, one at a time). */
+static int shares_a_block(int32_t batch, const int64_t* off, const int32_t* len)
+{
+    for (int32_t i = 0; i < batch; ++i)
+        for (int32_t k = 0; k < i; ++k)
+            if (len[i] > 0 && len[k] > 0 && off[i] < off[k] + len[k] && off[k] < off[i] + len[i])
+                return 1;
+    return 0;
+}
+
+/* Forward product of every operation; C and S are fully overwritten on the operations' rows
+ * (operations that name the same block are added up). */
 int oracle_bspmm_forward(int32_t batch, const int32_t* rows, const int32_t* cols,
                          const int32_t* nnz, const int64_t* rpt_off, const int64_t* nz_off,
                          const int64_t* b_row_off, const int64_t* c_row_off,
@@ -58,7 +73,14 @@ int oracle_bspmm_forward(int32_t batch, const int32_t* rows, const int32_t* cols
     for (int32_t i = 0; i < batch; ++i)
         if (!check_op(rows[i], cols[i], nnz[i], rpt + rpt_off[i], colids + nz_off[i]))
             return -(i + 1);
-#pragma omp parallel for schedule(dynamic, 1)
+    for (int32_t i = 0; i < batch; ++i)
+        for (int32_t r = 0; r < rows[i]; ++r)
+            for (int32_t j = 0; j < F; ++j) {
+                C[(c_row_off[i] + r) * ldc + j] = 0.0;
+                if (S) S[(c_row_off[i] + r) * ldc + j] = 0.0;
+            }
+    const int shared = shares_a_block(batch, c_row_off, rows);
+#pragma omp parallel for schedule(dynamic, 1) if (!shared)
     for (int32_t i = 0; i < batch; ++i) {
         const int32_t* rp = rpt + rpt_off[i];
         const int32_t* ci = colids + nz_off[i];
@@ -66,10 +88,6 @@ int oracle_bspmm_forward(int32_t batch, const int32_t* rows, const int32_t* cols
         for (int32_t r = 0; r < rows[i]; ++r) {
             double* c = C + (c_row_off[i] + r) * ldc;
             double* s = S ? S + (c_row_off[i] + r) * ldc : NULL;
-            for (int32_t j = 0; j < F; ++j) {
-                c[j] = 0.0;
-                if (s) s[j] = 0.0;
-            }
             for (int32_t p = rp[r]; p < rp[r + 1]; ++p) {
                 const double v = (double)va[p];
                 const float* b = B + (b_row_off[i] + ci[p]) * ldb;
@@ -85,8 +103,8 @@ int oracle_bspmm_forward(int32_t batch, const int32_t* rows, const int32_t* cols
 
 /*
  * Transposed product G_i = A_i^T dY_i.  dY_i has rows[i] rows at dY + c_row_off[i]*ldy,
- * G_i has cols[i] rows at G + b_row_off[i]*ldg.  Output blocks of different operations must
- * not overlap (each is overwritten).
+ * G_i has cols[i] rows at G + b_row_off[i]*ldg.  Operations that name the same output block
+ * (channels reading one dense input in the forward direction) are added up.
  */
 int oracle_bspmm_transposed(int32_t batch, const int32_t* rows, const int32_t* cols,
                             const int32_t* nnz, const int64_t* rpt_off, const int64_t* nz_off,
@@ -98,16 +116,18 @@ int oracle_bspmm_transposed(int32_t batch, const int32_t* rows, const int32_t* c
     for (int32_t i = 0; i < batch; ++i)
         if (!check_op(rows[i], cols[i], nnz[i], rpt + rpt_off[i], colids + nz_off[i]))
             return -(i + 1);
-#pragma omp parallel for schedule(dynamic, 1)
-    for (int32_t i = 0; i < batch; ++i) {
-        const int32_t* rp = rpt + rpt_off[i];
-        const int32_t* ci = colids + nz_off[i];
-        const float* va = values + nz_off[i];
+    for (int32_t i = 0; i < batch; ++i)
         for (int32_t c = 0; c < cols[i]; ++c)
             for (int32_t j = 0; j < F; ++j) {
                 G[(b_row_off[i] + c) * ldg + j] = 0.0;
                 if (S) S[(b_row_off[i] + c) * ldg + j] = 0.0;
             }
+    const int shared = shares_a_block(batch, b_row_off, cols);
+#pragma omp parallel for schedule(dynamic, 1) if (!shared)
+    for (int32_t i = 0; i < batch; ++i) {
+        const int32_t* rp = rpt + rpt_off[i];
+        const int32_t* ci = colids + nz_off[i];
+        const float* va = values + nz_off[i];
         for (int32_t r = 0; r < rows[i]; ++r) {
             const float* y = dY + (c_row_off[i] + r) * ldy;
             for (int32_t p = rp[r]; p < rp[r + 1]; ++p) {

@@ -200,12 +200,13 @@ def row_normalised_csr(n: int, edges: np.ndarray, self_loops: bool):
 def assemble(name: str, F: int, ops: Sequence[Tuple[int, int, np.ndarray, np.ndarray, np.ndarray]],
              b_block_of_op: Sequence[int], b_block_rows: Sequence[int],
              rng: np.random.Generator, with_dY: bool = False, n_graphs: Optional[int] = None,
-             meta: Optional[dict] = None) -> Batch:
+             meta: Optional[dict] = None, c_block_of_op: Optional[Sequence[int]] = None) -> Batch:
     """Pack operations ``(rows, cols, rpt, colids, values)`` into one :class:`Batch`.
 
     ``b_block_of_op[i]`` names the dense-input block operation ``i`` reads (several operations
     may name the same block); ``b_block_rows[k]`` is the row count of block ``k``.  Output
-    blocks are laid out back to back in operation order.
+    blocks are laid out back to back in operation order, unless ``c_block_of_op`` names an
+    output block per operation (operations naming the same block are summed into it).
     """
     nb = len(ops)
     rows = np.array([o[0] for o in ops], dtype=np.int32).reshape(nb)
@@ -218,6 +219,17 @@ def assemble(name: str, F: int, ops: Sequence[Tuple[int, int, np.ndarray, np.nda
         rpt_off[1:] = np.cumsum(rows[:-1].astype(np.int64) + 1)
         nz_off[1:] = np.cumsum(nnz[:-1].astype(np.int64))
         c_row_off[1:] = np.cumsum(rows[:-1].astype(np.int64))
+    n_c_rows = int(rows.astype(np.int64).sum())
+    if c_block_of_op is not None:
+        nblk = (max(c_block_of_op) + 1) if nb else 0
+        blk_rows = np.zeros(nblk, dtype=np.int64)
+        for i in range(nb):
+            assert blk_rows[c_block_of_op[i]] in (0, int(rows[i]))
+            blk_rows[c_block_of_op[i]] = int(rows[i])
+        cstart = np.zeros(nblk + 1, dtype=np.int64)
+        cstart[1:] = np.cumsum(blk_rows)
+        c_row_off = np.array([cstart[k] for k in c_block_of_op], dtype=np.int64).reshape(nb)
+        n_c_rows = int(cstart[-1])
     blk_start = np.zeros(len(b_block_rows) + 1, dtype=np.int64)
     blk_start[1:] = np.cumsum(np.asarray(b_block_rows, dtype=np.int64))
     b_row_off = np.array([blk_start[k] for k in b_block_of_op], dtype=np.int64).reshape(nb)
@@ -230,7 +242,6 @@ def assemble(name: str, F: int, ops: Sequence[Tuple[int, int, np.ndarray, np.nda
     values = (np.concatenate([o[4] for o in ops]).astype(np.float32) if nb
               else np.zeros(0, dtype=np.float32))
     n_b_rows = int(blk_start[-1])
-    n_c_rows = int(rows.astype(np.int64).sum())
     B = rng.uniform(-1.0, 1.0, size=(n_b_rows, F)).astype(np.float32)
     dY = rng.standard_normal(size=(n_c_rows, F)).astype(np.float32) if with_dY else None
     return Batch(name=name, F=int(F), rows=rows, cols=cols, nnz=nnz, rpt_off=rpt_off,
@@ -279,27 +290,40 @@ def config2_molecule(seed: Optional[int] = None, F: int = 128, graphs: int = 128
 
 
 def config3_multichannel(seed: Optional[int] = None, F: int = 128, graphs: int = 512,
-                         channels: int = 4) -> Batch:
+                         channels: int = 4, accumulate: bool = False, own_inputs: bool = False,
+                         normalise: bool = True, with_dY: bool = False) -> Batch:
     """Each graph's edges are split at random into ``channels`` edge types.
 
     Every channel gives one CSR matrix without self-loops, row-normalised by its channel degree
     (rows without an edge of that type stay empty).  The ``channels`` operations of one graph
     read the same dense block; each writes its own output block.  Operation index =
     ``graph * channels + channel``.
+
+    Variants for the layer's channel sum (Fig. 6 / Fig. 7 of the paper): ``accumulate`` makes the
+    channels of a graph name ONE output block (their products are added), ``own_inputs`` gives
+    every channel its own dense block (the paper's ``B = X W[ch] + bias[ch]``),
+    ``normalise=False`` keeps the entries at 1.0 (the channel matrices then add up to the plain
+    adjacency matrix).
     """
     rng = np.random.default_rng(config_seed(3) if seed is None else seed)
     sizes = _lognormal_sizes(rng, graphs, mean=25.0, sigma=0.5, lo=3, hi=150)
-    ops, block_of_op, blocks = [], [], []
+    ops, block_of_op, blocks, c_block_of_op = [], [], [], []
     for g, n in enumerate(sizes):
         n = int(n)
         e = _molecule_edges(rng, n, float(rng.uniform(2.0, 4.0)), max_degree=6)
         ch = rng.integers(0, channels, size=e.shape[0])
         for k in range(channels):
-            ops.append((n, n) + row_normalised_csr(n, e[ch == k], self_loops=False))
-            block_of_op.append(g)
-        blocks.append(n)
-    return assemble("cfg3_multichannel", F, ops, block_of_op, blocks, rng, n_graphs=graphs,
-                    meta={"channels": channels})
+            rpt, ci, va = row_normalised_csr(n, e[ch == k], self_loops=False)
+            if not normalise:
+                va = np.ones_like(va)
+            ops.append((n, n, rpt, ci, va))
+            block_of_op.append(g * channels + k if own_inputs else g)
+            c_block_of_op.append(g)
+        blocks.extend([n] * (channels if own_inputs else 1))
+    name = "cfg3_multichannel" + ("_acc" if accumulate else "") + ("_own" if own_inputs else "")
+    return assemble(name, F, ops, block_of_op, blocks, rng, n_graphs=graphs,
+                    meta={"channels": channels}, with_dY=with_dY,
+                    c_block_of_op=c_block_of_op if accumulate else None)
 
 
 def config4_wide(seed: Optional[int] = None, F: int = 1024, graphs: int = 128) -> Batch:
@@ -416,7 +440,7 @@ def hub_batch(seed: int, F: int, n: int, copies: int = 2) -> Batch:
 
 def effective_bytes(b: Batch, transposed: bool = False) -> int:
     """Compulsory bytes one launch must move: CSR once, each distinct dense block once, each
-    output row once (fp32 dense, int32 indices).  For the transposed product the dense input
+    distinct output block once (fp32 dense, int32 indices).  For the transposed product the dense input
     is indexed like the forward output and vice versa."""
     rows = b.rows.astype(np.int64)
     cols = b.cols.astype(np.int64)
@@ -425,12 +449,14 @@ def effective_bytes(b: Batch, transposed: bool = False) -> int:
         csr = int((4 * (rows + 1) + 8 * nnz).sum())
         blocks = {(int(o), int(c)) for o, c in zip(b.b_row_off, cols)}
         dense_in = sum(4 * c * b.F for _, c in blocks)
-        dense_out = int((4 * rows * b.F).sum())
+        outs = {(int(o), int(r)) for o, r in zip(b.c_row_off, rows)}
+        dense_out = sum(4 * r * b.F for _, r in outs)
     else:
         csr = int((4 * (cols + 1) + 8 * nnz).sum())
         blocks = {(int(o), int(r)) for o, r in zip(b.c_row_off, rows)}
         dense_in = sum(4 * r * b.F for _, r in blocks)
-        dense_out = int((4 * cols * b.F).sum())
+        outs = {(int(o), int(c)) for o, c in zip(b.b_row_off, cols)}
+        dense_out = sum(4 * c * b.F for _, c in outs)
     return int(csr + dense_in + dense_out)
 
 

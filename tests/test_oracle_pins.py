@@ -309,3 +309,61 @@ def test_oracle_rejects_malformed(oracle):
 def test_flop_formula():
     b = W.config1_tiny()
     assert W.flops(b) == 2 * int(b.nnz.sum()) * b.F   # 2 * nnz_A * n_B (Sec. V-A)
+
+
+# ---------------------------------------------------------------------------------------------
+# channel sum: operations that name one output block are added up (Fig. 6 / Fig. 7,
+# "ElementWiseAdd" of the per-channel products)
+# ---------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("own_inputs", [False, True])
+def test_shared_output_blocks_are_summed(oracle, own_inputs):
+    b = W.config3_multichannel(graphs=12, F=6, accumulate=True, own_inputs=own_inputs,
+                               with_dY=True)
+    C, S = oracle.forward_batch(b)
+    G, SG = oracle.transposed_batch(b)
+    ch = b.meta["channels"]
+    refG = np.zeros((b.n_b_rows, b.F))
+    for g in range(b.n_graphs):
+        ops = range(g * ch, (g + 1) * ch)
+        n = int(b.rows[g * ch])
+        c0 = int(b.c_row_off[g * ch])
+        ref = np.zeros((n, b.F))
+        refS = np.zeros((n, b.F))
+        Y = b.dY[c0:c0 + n].astype(np.float64)
+        for i in ops:
+            assert int(b.c_row_off[i]) == c0
+            A = _dense_of(b, i)
+            Bi = b.B[int(b.b_row_off[i]):int(b.b_row_off[i]) + n].astype(np.float64)
+            ref += _brute(A, Bi)
+            refS += np.abs(A) @ np.abs(Bi)
+            refG[int(b.b_row_off[i]):int(b.b_row_off[i]) + n] += A.T @ Y
+        assert np.allclose(C[c0:c0 + n], ref, rtol=1e-12, atol=1e-14)
+        assert np.allclose(S[c0:c0 + n], refS, rtol=1e-12, atol=1e-14)
+    assert np.allclose(G, refG, rtol=1e-12, atol=1e-14)
+    # adjoint identity across the channel sum
+    lhs = float((C * b.dY.astype(np.float64)).sum())
+    rhs = float((b.B.astype(np.float64) * G).sum())
+    assert abs(lhs - rhs) <= 1e-11 * max(abs(lhs), 1.0)
+
+
+def test_unit_channels_sum_to_the_adjacency_matrix(oracle):
+    """With entries 1.0 the channel matrices of a graph partition its edges, so the summed
+    product is the plain neighbour sum: C[r] = sum of B over the neighbours of r."""
+    b = W.config3_multichannel(graphs=10, F=5, accumulate=True, normalise=False)
+    C, _ = oracle.forward_batch(b)
+    ch = b.meta["channels"]
+    for g in range(b.n_graphs):
+        n = int(b.rows[g * ch])
+        c0 = int(b.c_row_off[g * ch])
+        b0 = int(b.b_row_off[g * ch])
+        adj = np.zeros((n, n))
+        for i in range(g * ch, (g + 1) * ch):
+            rpt, ci, _ = b.op_csr(i)
+            r = np.repeat(np.arange(n), np.diff(rpt))
+            assert np.all(adj[r, ci] == 0)          # every edge belongs to exactly one channel
+            adj[r, ci] = 1.0
+        assert np.array_equal(adj, adj.T) and np.all(np.diag(adj) == 0)
+        Bg = b.B[b0:b0 + n].astype(np.float64)
+        ref = np.stack([Bg[adj[r] > 0].sum(axis=0) for r in range(n)])
+        assert np.allclose(C[c0:c0 + n], ref, rtol=1e-12, atol=1e-14)
