@@ -333,6 +333,20 @@ def main():
             del r
             torch.cuda.empty_cache()
         extra["other_configs_cold"] = others
+        # the layer's channel sum done inside the launch (BSPMM_ACCUMULATE): the 4 channel
+        # products of a graph go to ONE output block, 512 and 2048 graphs
+        acc = {}
+        for name, graphs in (("cfg3_channel_sum_512", 512), ("cfg3_channel_sum_2048", 2048)):
+            for label, mk, opts in (
+                    ("separate_outputs", lambda g=graphs: W.config3_multichannel(graphs=g), None),
+                    ("summed_in_launch", lambda g=graphs: W.config3_multichannel(graphs=g, accumulate=True),
+                     K.make_options(flags=K.ACCUMULATE))):
+                r = Runner(torch, K, mk(), options=opts)
+                s, _ = r.time_graph(1000, 100)
+                acc[f"{name}_{label}"] = r.summary(s)
+                del r
+                torch.cuda.empty_cache()
+        extra["channel_sum"] = acc
 
     out = {
         "metric": "batched SpMM graphs/sec, F=128, batch 128",

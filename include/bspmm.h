@@ -18,7 +18,8 @@
  *    [b_row_off[i], b_row_off[i]+cols_i) of B and writes rows [c_row_off[i], c_row_off[i]+rows_i)
  *    of C; leading dimensions are given per call, in elements, and must be >= F.
  *    Several operations may read the same B block (a graph with several edge-type channels);
- *    output blocks must not overlap.
+ *    output blocks must not overlap, except that with BSPMM_ACCUMULATE operations naming the
+ *    same output block are summed into it.
  *  - alpha = 1, beta = 0: every output row of every operation is written exactly once
  *    (zeros for rows without entries); output rows that belong to no operation are untouched.
  *  - Arithmetic is fp32 with fused multiply-add, summed in stored order inside a row.
@@ -55,6 +56,8 @@ extern "C" {
 #define BSPMM_EOVERLAP  (-4)  /* output blocks of two operations overlap                      */
 #define BSPMM_ESTATE    (-5)  /* plan cannot do this (dry-run plan, transposed unsupported)   */
 #define BSPMM_EBADCSR   (-6)  /* bspmm_validate found a malformed CSR on the device           */
+#define BSPMM_ETOOBIG   (-7)  /* operations summed into one block: more than 8 of them, or
+                                 their arrays do not fit the on-chip memory together           */
 
 /* bspmm_options.flags */
 #define BSPMM_DRY_RUN          1u  /* schedule only: touch no device, run calls return ESTATE */
@@ -64,6 +67,12 @@ extern "C" {
                                       sums reduced (DPP / ds_swizzle inside a wavefront, LDS across
                                       wavefronts).  For graphs with hub nodes; plain batches are a
                                       few per cent faster without it                             */
+#define BSPMM_ACCUMULATE       16u  /* operations that name the SAME output block (same first row,
+                                      same row count) are added up in one pass - the channel sum
+                                      of the graph-convolution layer (Fig. 6 / Fig. 7) - instead
+                                      of being rejected as overlapping.  Applies to C blocks in
+                                      bspmm_run and to B blocks (input gradients) in
+                                      bspmm_run_transposed                                       */
 #define BSPMM_FLOOR_PROBE      4u  /* measurement aid: same grid, LDS and item fetches, but every
                                       item is emptied, so a run computes and writes nothing      */
 
@@ -122,6 +131,7 @@ typedef struct bspmm_info {
     int32_t tasks[2];                        /* workgroup-sized tasks the grid strides through */
     int32_t items[2];                        /* non-empty work items                          */
     int32_t items_in_bin[2][BSPMM_NUM_BINS];
+    int32_t fused_tasks[2];                  /* tasks that add up several operations          */
     int32_t transposed_supported;            /* 0 when input-gradient blocks overlap          */
     int32_t transposed_built;                /* the build kernel has been enqueued            */
     int64_t effective_bytes[2];              /* CSR + distinct dense inputs + outputs, once   */
@@ -155,7 +165,8 @@ int bspmm_workspace_bytes(const bspmm_batch* b, int32_t F, const bspmm_options* 
  * on `stream`); Sec. IV-C's "decide cache blocking and resource assignment from the sizes of
  * the inputs", done per operation instead of from the batch maximum.
  * Returns EINVAL for null/negative/inconsistent arguments or F <= 0, EOVERLAP when two
- * operations' C blocks overlap, ENOSPACE, EHIP.  On error *plan is NULL.
+ * operations' C blocks overlap (with BSPMM_ACCUMULATE: overlap without being identical),
+ * ETOOBIG, ENOSPACE, EHIP.  On error *plan is NULL.
  */
 int bspmm_create(bspmm_plan** plan, const bspmm_batch* b, int32_t F,
                  const bspmm_options* options, void* workspace, size_t workspace_bytes,
@@ -176,7 +187,8 @@ int bspmm_run(bspmm_plan* plan, const float* B, float* C, int64_t ldb, int64_t l
  * dY is indexed like C (rows_i rows at c_row_off[i]), G like B (cols_i rows at b_row_off[i]).
  * The first call enqueues the on-device transposed-CSR build (one extra launch, once per
  * plan) unless bspmm_create already did.  Returns ESTATE when two operations share or
- * overlap a B block, because each would have to accumulate into the same gradient rows.
+ * overlap a B block and the plan was not created with BSPMM_ACCUMULATE (each would have to
+ * add into the same gradient rows), or when B blocks overlap without being identical.
  */
 int bspmm_run_transposed(bspmm_plan* plan, const float* dY, float* G, int64_t ldy, int64_t ldg,
                          void* stream);

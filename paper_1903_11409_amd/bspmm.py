@@ -15,8 +15,8 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libbspmm.so")
 
-OK, EINVAL, ENOSPACE, EHIP, EOVERLAP, ESTATE, EBADCSR = 0, -1, -2, -3, -4, -5, -6
-DRY_RUN, BUILD_TRANSPOSE, FLOOR_PROBE, SPLIT_HUB_ROWS = 1, 2, 4, 8
+OK, EINVAL, ENOSPACE, EHIP, EOVERLAP, ESTATE, EBADCSR, ETOOBIG = 0, -1, -2, -3, -4, -5, -6, -7
+DRY_RUN, BUILD_TRANSPOSE, FLOOR_PROBE, SPLIT_HUB_ROWS, ACCUMULATE = 1, 2, 4, 8, 16
 BIN_WORKGROUP, BIN_WAVE, BIN_SLICE32, BIN_SLICE16, BIN_GENERIC = 0, 1, 2, 3, 4
 NUM_BINS = 5
 BIN_NAMES = ["workgroup", "wave", "slice32", "slice16", "generic"]
@@ -50,6 +50,7 @@ class bspmm_info(ctypes.Structure):
                 ("tasks", ctypes.c_int32 * 2),
                 ("items", ctypes.c_int32 * 2),
                 ("items_in_bin", (ctypes.c_int32 * NUM_BINS) * 2),
+                ("fused_tasks", ctypes.c_int32 * 2),
                 ("transposed_supported", ctypes.c_int32),
                 ("transposed_built", ctypes.c_int32),
                 ("effective_bytes", ctypes.c_int64 * 2), ("flops", ctypes.c_int64),

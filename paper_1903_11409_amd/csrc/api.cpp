@@ -102,17 +102,23 @@ int check_batch(const bspmm_batch* b, int32_t F, bool need_device)
     return BSPMM_OK;
 }
 
-// true when the half-open row intervals [off, off+len) with len > 0 are pairwise disjoint
-bool disjoint(const int64_t* off, const int32_t* len, int n)
+// How the half-open row intervals [off, off+len) with len > 0 relate:
+// 0 = pairwise disjoint, 1 = some are identical but none overlaps otherwise, 2 = real overlap.
+int overlap_kind(const int64_t* off, const int32_t* len, int n)
 {
     std::vector<std::pair<int64_t, int64_t>> v;
     v.reserve(n);
     for (int i = 0; i < n; ++i)
         if (len[i] > 0) v.emplace_back(off[i], off[i] + len[i]);
     std::sort(v.begin(), v.end());
-    for (size_t i = 1; i < v.size(); ++i)
-        if (v[i].first < v[i - 1].second) return false;
-    return true;
+    int kind = 0;
+    for (size_t i = 1; i < v.size(); ++i) {
+        if (v[i] == v[i - 1])
+            kind = std::max(kind, 1);
+        else if (v[i].first < v[i - 1].second)
+            return 2;
+    }
+    return kind;
 }
 
 // Fill everything of the plan that needs no device.
@@ -170,11 +176,20 @@ int plan_host(bspmm_plan& p, const bspmm_batch* b, int32_t F, const Knobs& kn)
     p.build_lds_bytes = (int)round_up(build_lds_words * 4 + 16, 256);
     p.scratch_words = scratch_words;
 
-    if (n > 0 && !disjoint(b->c_row_off, b->rows, n)) return BSPMM_EOVERLAP;
-    p.transposed_supported = n == 0 || disjoint(b->b_row_off, b->cols, n);
+    const int ck = n > 0 ? overlap_kind(b->c_row_off, b->rows, n) : 0;
+    const int bk = n > 0 ? overlap_kind(b->b_row_off, b->cols, n) : 0;
+    if (ck == 2 || (ck == 1 && !kn.accumulate)) return BSPMM_EOVERLAP;
+    p.transposed_supported = bk == 0 || (bk == 1 && kn.accumulate);
 
     p.sched[0] = make_schedule(f, F, kn);
-    if (p.transposed_supported) p.sched[1] = make_schedule(t, F, kn);
+    if (p.sched[0].error) return p.sched[0].error;
+    if (p.transposed_supported) {
+        p.sched[1] = make_schedule(t, F, kn);
+        if (p.sched[1].error) {          // the forward product still works
+            p.sched[1] = Schedule();
+            p.transposed_supported = false;
+        }
+    }
 
     // compulsory traffic: CSR once, every distinct dense input block once, every output once
     std::set<std::pair<int64_t, int32_t>> blocks_f, blocks_t;
@@ -182,10 +197,16 @@ int plan_host(bspmm_plan& p, const bspmm_batch* b, int32_t F, const Knobs& kn)
     for (int i = 0; i < n; ++i) {
         csr_f += 4 * ((int64_t)b->rows[i] + 1) + 8 * (int64_t)b->nnz[i];
         csr_t += 4 * ((int64_t)b->cols[i] + 1) + 8 * (int64_t)b->nnz[i];
-        out_f += 4 * (int64_t)b->rows[i] * F;
-        out_t += 4 * (int64_t)b->cols[i] * F;
-        if (blocks_f.emplace(b->b_row_off[i], b->cols[i]).second) in_f += 4 * (int64_t)b->cols[i] * F;
-        if (blocks_t.emplace(b->c_row_off[i], b->rows[i]).second) in_t += 4 * (int64_t)b->rows[i] * F;
+        // a dense block counts once as an input and once as an output, however many
+        // operations read it or are summed into it
+        if (blocks_f.emplace(b->b_row_off[i], b->cols[i]).second) {
+            in_f += 4 * (int64_t)b->cols[i] * F;
+            out_t += 4 * (int64_t)b->cols[i] * F;
+        }
+        if (blocks_t.emplace(b->c_row_off[i], b->rows[i]).second) {
+            in_t += 4 * (int64_t)b->rows[i] * F;
+            out_f += 4 * (int64_t)b->rows[i] * F;
+        }
         nnz += b->nnz[i];
     }
     p.effective_bytes[0] = csr_f + in_f + out_f;
@@ -277,6 +298,7 @@ int run_direction(bspmm_plan* p, int d, const float* in, float* out, int64_t ld_
         P.item_base[r] = sc.item_base[r];
     }
     P.n_tasks = sc.grid;
+    P.fused_stride = sc.fused_stride;
     P.lds_floats = p->knobs.lds_words;
     P.pad = p->knobs.pad;
 #ifdef BSPMM_TRACE
@@ -460,6 +482,7 @@ int bspmm_plan_info(const bspmm_plan* plan, bspmm_info* info)
         for (int b = 0; b < BSPMM_NUM_BINS; ++b)
             info->items_in_bin[d][b] = plan->sched[d].items_in_bin[b];
         info->effective_bytes[d] = plan->effective_bytes[d];
+        info->fused_tasks[d] = plan->sched[d].fused_tasks;
     }
     info->transposed_supported = plan->transposed_supported ? 1 : 0;
     info->transposed_built = plan->transposed_built ? 1 : 0;
@@ -491,6 +514,7 @@ const char* bspmm_strerror(int code)
         case BSPMM_EOVERLAP: return "output blocks overlap";
         case BSPMM_ESTATE: return "operation not available on this plan";
         case BSPMM_EBADCSR: return "malformed CSR arrays on the device";
+        case BSPMM_ETOOBIG: return "operations summed into one block do not fit on chip together";
         default: return "unknown error";
     }
 }

@@ -459,6 +459,196 @@ __device__ __forceinline__ void run_generic(const LaunchParams& P, const WorkIte
     }
 }
 
+#ifdef BSPMM_TRACE
+#define BSPMM_STAMP(task, slot)                                                        \
+    do {                                                                               \
+        if (P.trace) {                                                                 \
+            asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");                \
+            if (threadIdx.x == 0) P.trace[(size_t)(task) * 8 + (slot)] = wall_clock64(); \
+        }                                                                              \
+    } while (0)
+#else
+#define BSPMM_STAMP(task, slot) do { } while (0)
+#endif
+
+// ---------------------------------------------------------------------------------------
+// Fused task: M operations with the same output rows whose products are added up (the channel
+// sum of the graph-convolution layer, Fig. 6 / Fig. 7) in registers, so the block is written
+// once instead of M times and never read back.  Every array of every member goes straight from
+// global memory into LDS (no staging registers: all of it is in flight at once); members that
+// read the same dense tile share one copy.
+// ---------------------------------------------------------------------------------------
+__device__ __forceinline__ void lds_copy_words(const void* src, int* dst_lds, int words, int tid)
+{
+    const int wl = tid & 63;
+    for (int e0 = (tid >> 6) << 6; e0 < words; e0 += kThreads) {
+        const int e = e0 + wl;
+        if (e < words)
+            __builtin_amdgcn_global_load_lds(
+                (const void __attribute__((address_space(1)))*)(static_cast<const int*>(src) + e),
+                (void __attribute__((address_space(3)))*)(dst_lds + e0), 4, 0, 0);
+    }
+}
+
+template <int VEC>
+__device__ __forceinline__ void run_fused(const LaunchParams& P, int* sm, int first_item,
+                                          int task)
+{
+    using V = Vec<VEC>;
+    using VT = typename V::type;
+    const int tid = threadIdx.x;
+    const WorkItem it0 = P.items[first_item];          // uniform: scalar loads
+    if (it0.nrows <= 0) return;
+#ifdef BSPMM_TRACE
+    if (P.trace && tid == 0) P.trace[(size_t)task * 8] = wall_clock64();
+#endif
+    BSPMM_STAMP(task, 1);
+    const int members = (it0.staged >> 8) & 0xff;
+    const int m = it0.m, fw = it0.fw;
+    const FusedLayout L = fused_layout(members, m);
+    const int stride = round_up(fw, 4);
+    const Split<kThreads, VEC> sp(fw, tid);
+    const bool direct = VEC == 4 && (sp.nvec & (sp.nvec - 1)) == 0;
+
+    // ---- member descriptors: lane j of every wavefront fetches member j's item, so all of
+    // them arrive in one round trip; the uniform loops below pick a member's fields out of
+    // the lanes with v_readlane (no scalar load and no LDS per member).
+    const int wl = tid & 63;
+    const WorkItem mine = P.items[first_item + min(wl, P.fused_stride - 1)];
+    auto lane_i32 = [](int v, int j) { return __builtin_amdgcn_readlane(v, j); };
+    auto lane_i64 = [](int64_t v, int j) {
+        const unsigned lo = __builtin_amdgcn_readlane((int)(v & 0xffffffff), j);
+        const unsigned hi = __builtin_amdgcn_readlane((int)(v >> 32), j);
+        return (int64_t)(((uint64_t)hi << 32) | lo);
+    };
+
+    // ---- stage every member: offsets are uniform, computed by everybody, tabled by lane 0
+    int off = L.cv_off;
+    int nnz_sum = 0;
+    for (int j = 0; j < members; ++j) {
+        const int nnz = lane_i32(mine.nnz, j);
+        const int64_t nz_off = lane_i64(mine.nz_off, j);
+        const int nz4 = round_up(nnz, 4);
+        if (tid == 0) {
+            sm[4 * j + 0] = off;
+            sm[4 * j + 1] = off + nz4;
+            sm[4 * j + 3] = nnz;
+        }
+        lds_copy_words(P.rpt + lane_i64(mine.rpt_off, j), sm + L.rpt_off + j * L.rs, m + 1, tid);
+        lds_copy_words(P.colids + nz_off, sm + off, nnz, tid);
+        lds_copy_words(P.values + nz_off, sm + off + nz4, nnz, tid);
+        off += 2 * nz4;
+        nnz_sum += nnz;
+    }
+    // merged CSR of the members (filled below): row pointers, then (dense row offset, value)
+    int* crpt = sm + off;
+    int2* cv = reinterpret_cast<int2*>(sm + off + L.rs);
+    int tile_off = off + L.rs + 2 * round_up(nnz_sum, 2);
+    int tile_of = 0;                                    // lane j: LDS offset of member j's tile
+    for (int j = 0; j < members; ++j) {
+        const int owner = (lane_i32(mine.staged, j) >> 16) & 0xff;
+        if (owner != j) {                               // shares the tile of an earlier member
+            const int shared = lane_i32(tile_of, owner);
+            tile_of = wl == j ? shared : tile_of;
+            if (tid == 0) sm[4 * j + 2] = shared;
+            continue;
+        }
+        tile_of = wl == j ? tile_off : tile_of;
+        if (tid == 0) sm[4 * j + 2] = tile_off;
+        const int k = lane_i32(mine.k, j);
+        float* bs = reinterpret_cast<float*>(sm + tile_off);
+        const float* __restrict__ src = P.in + lane_i64(mine.in_row_off, j) * P.ld_in + it0.f0;
+        if (direct) {
+            const int sh = ilog2(sp.nvec);
+            const int total = k << sh;
+            for (int e0 = (tid >> 6) << 6; e0 < total; e0 += kThreads) {
+                const int e = e0 + wl;
+                if (e < total)
+                    __builtin_amdgcn_global_load_lds(
+                        (const void __attribute__((address_space(1)))*)(
+                            src + (int64_t)(e >> sh) * P.ld_in + ((e & (sp.nvec - 1)) << 2)),
+                        (void __attribute__((address_space(3)))*)(bs + (e0 << 2)), 16, 0, 0);
+            }
+        } else {
+            for (int v = sp.l; v < sp.nvec; v += sp.g_lanes)
+                for (int row = sp.g; row < k; row += sp.groups)
+                    store_vec<VEC>(bs + row * stride + v * VEC,
+                                   load_vec<VEC>(src + (int64_t)row * P.ld_in + v * VEC));
+        }
+        tile_off += k * stride;
+    }
+    BSPMM_STAMP(task, 6);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // direct-to-LDS loads landed
+    __syncthreads();
+    BSPMM_STAMP(task, 7);
+
+    // ---- merge the members' rows into one CSR: row r of the sum is the concatenation of row r
+    // of every member, so its start is the sum of the members' starts; every entry already
+    // carries the LDS offset of the dense row it multiplies.  One lane per (row, member).
+    const int4* tab = reinterpret_cast<const int4*>(sm);
+    const int row_end = it0.row0 + it0.nrows;
+    const int pairs = it0.nrows * members;
+    for (int q = tid; q < pairs; q += kThreads) {
+        const int rl = q / members;
+        const int j = q - rl * members;
+        const int r = it0.row0 + rl;
+        int start = 0, before = 0, mine0 = 0, mine1 = 0;
+        for (int e = 0; e < members; ++e) {             // independent reads, all in flight
+            const int a = sm[L.rpt_off + e * L.rs + r];
+            const int b = sm[L.rpt_off + e * L.rs + r + 1];
+            start += a;
+            before += e < j ? b - a : 0;
+            mine0 = e == j ? a : mine0;
+            mine1 = e == j ? b : mine1;
+        }
+        const int4 tb = tab[j];
+        const int p1 = min(max(mine1, 0), tb.w);        // malformed pointers stay bounded
+        int pos = start + before;
+        for (int p = min(max(mine0, 0), p1); p < p1; ++p)
+            cv[pos++] = make_int2(tb.z + sm[tb.x + p] * stride, sm[tb.y + p]);
+        if (j == 0) crpt[r] = start;
+        if (j == members - 1 && r == row_end - 1) crpt[row_end] = pos;
+    }
+    __syncthreads();
+
+    BSPMM_STAMP(task, 2);
+    // ---- rows of the sum: the plain gather loop over the merged CSR, one store per row
+    float* __restrict__ dst = P.out + it0.out_row_off * P.ld_out + it0.f0;
+    const float* lds = reinterpret_cast<const float*>(sm);
+    for (int r = it0.row0 + sp.g; r < row_end; r += sp.groups) {
+        const int p0 = crpt[r];
+        const int p1 = crpt[r + 1];
+        for (int v = sp.l; v < sp.nvec; v += sp.g_lanes) {
+            const float* bcol = lds + v * VEC;
+            VT acc = V::zero();
+            int p = p0;
+            for (; p + 3 < p1; p += 4) {
+                const int2 e0 = cv[p], e1 = cv[p + 1], e2 = cv[p + 2], e3 = cv[p + 3];
+                const VT b0 = load_vec<VEC>(bcol + e0.x);
+                const VT b1 = load_vec<VEC>(bcol + e1.x);
+                const VT b2 = load_vec<VEC>(bcol + e2.x);
+                const VT b3 = load_vec<VEC>(bcol + e3.x);
+                V::fma(acc, __int_as_float(e0.y), b0);
+                V::fma(acc, __int_as_float(e1.y), b1);
+                V::fma(acc, __int_as_float(e2.y), b2);
+                V::fma(acc, __int_as_float(e3.y), b3);
+            }
+            for (; p < p1; ++p) {
+                const int2 e = cv[p];
+                V::fma(acc, __int_as_float(e.y), load_vec<VEC>(bcol + e.x));
+            }
+            store_out<VEC>(dst + (int64_t)r * P.ld_out + v * VEC, acc);
+        }
+    }
+    BSPMM_STAMP(task, 3);
+#ifdef BSPMM_TRACE
+    if (P.trace && tid == 0) {
+        P.trace[(size_t)task * 8 + 4] = it0.nrows;
+        P.trace[(size_t)task * 8 + 5] = it0.k;
+    }
+#endif
+}
+
 // One task of a sub-workgroup range: 256/S slots, one staged item each.
 template <int LOG2S, int VEC, bool HUBS>
 __device__ __forceinline__ void run_slots(const LaunchParams& P, int* sm, int first_item)
@@ -477,17 +667,6 @@ __device__ __forceinline__ void run_slots(const LaunchParams& P, int* sm, int fi
     if (it.nrows > 0) compute_staged<S, VEC, HUBS>(P, it, slot_sm, lane);
 }
 
-#ifdef BSPMM_TRACE
-#define BSPMM_STAMP(task, slot)                                                        \
-    do {                                                                               \
-        if (P.trace) {                                                                 \
-            asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");                \
-            if (threadIdx.x == 0) P.trace[(size_t)(task) * 8 + (slot)] = wall_clock64(); \
-        }                                                                              \
-    } while (0)
-#else
-#define BSPMM_STAMP(task, slot) do { } while (0)
-#endif
 
 // One launch runs the whole schedule.  The grid is persistent: it has at most as many
 // workgroups as the chip holds at once, and workgroup w takes tasks w, w + gridDim.x, ...
@@ -549,12 +728,14 @@ __global__ void __launch_bounds__(kThreads) bspmm_kernel(const LaunchParams P)
     for (; t < P.n_tasks; t += stride) {
         __syncthreads();
         if (t < P.wg_end[1]) {
-            run_slots<6, VEC, HUBS>(P, sm, P.item_base[1] + (t - P.wg_end[0]) * 4);
+            run_fused<VEC>(P, sm, P.item_base[1] + (t - P.wg_end[0]) * P.fused_stride, t);
+        } else if (t < P.wg_end[2]) {
+            run_slots<6, VEC, HUBS>(P, sm, P.item_base[2] + (t - P.wg_end[1]) * 4);
         } else if (SLICES) {
-            if (t < P.wg_end[2])
-                run_slots<5, VEC, HUBS>(P, sm, P.item_base[2] + (t - P.wg_end[1]) * 8);
+            if (t < P.wg_end[3])
+                run_slots<5, VEC, HUBS>(P, sm, P.item_base[3] + (t - P.wg_end[2]) * 8);
             else
-                run_slots<4, VEC, HUBS>(P, sm, P.item_base[3] + (t - P.wg_end[2]) * 16);
+                run_slots<4, VEC, HUBS>(P, sm, P.item_base[4] + (t - P.wg_end[3]) * 16);
         }
     }
 }

@@ -13,11 +13,12 @@
 namespace bspmm {
 
 constexpr int kThreads = 256;      // lanes per workgroup (4 wavefronts of 64)
-constexpr int kRanges = 4;         // launch ranges by slot size: 256, 64, 32, 16 lanes
+constexpr int kRanges = 5;         // launch ranges: 256 lanes, fused 256, then 64, 32, 16 lanes
+constexpr int kMaxMembers = 8;     // operations one fused task may add up
 constexpr int kMaxLdsBytes = 64 * 1024;
 
 // Slot size (lanes) of launch range r, and its log2.
-BSPMM_HD constexpr int range_log2_slot(int r) { return r == 0 ? 8 : (r == 1 ? 6 : (r == 2 ? 5 : 4)); }
+BSPMM_HD constexpr int range_log2_slot(int r) { return r <= 1 ? 8 : (r == 2 ? 6 : (r == 3 ? 5 : 4)); }
 
 // One unit of work: the rows [row0, row0+nrows) of one operation restricted to the feature
 // columns [f0, f0+fw).  64 bytes so one item is a single 64-byte fetch.
@@ -34,12 +35,15 @@ struct alignas(16) WorkItem {
     int32_t f0;           // first feature column
     int32_t fw;           // feature columns
     int32_t staged;       // bit 0: operation and dense tile staged in LDS (0 = generic bin);
-                          // bit 1: no other item reads this dense tile (stream it)
+                          // bit 1: no other item reads this dense tile (stream it);
+                          // fused tasks: bits 8-15 of the first member = number of members,
+                          // bits 16-23 of member j = the member whose dense tile j shares
 };
 static_assert(sizeof(WorkItem) == 64, "WorkItem must be 64 bytes");
 
 // Kernel argument block, passed by value.  Task t belongs to range r when
-// wg_end[r-1] <= t < wg_end[r]; its first item is item_base[r] + (t - wg_end[r-1]) * slots(r).
+// wg_end[r-1] <= t < wg_end[r]; its first item is item_base[r] + (t - wg_end[r-1]) * n(r) with
+// n = 1 (range 0), fused_stride (range 1: operations summed into one output block), 4, 8, 16.
 // The launch has min(n_tasks, resident workgroups) workgroups; workgroup w runs tasks
 // w, w + gridDim.x, ...
 struct LaunchParams {
@@ -54,6 +58,7 @@ struct LaunchParams {
     int32_t wg_end[kRanges];
     int32_t item_base[kRanges];
     int32_t n_tasks;      // == wg_end[kRanges-1]
+    int32_t fused_stride; // item slots per fused task
     int32_t lds_floats;   // LDS per workgroup, in 4-byte words
     int32_t pad;          // words added to every staged dense row
 #ifdef BSPMM_TRACE
@@ -116,6 +121,28 @@ BSPMM_HD inline StagedLayout staged_layout(int m, int k, int nnz, int fw, int pa
     L.stride = round_up(fw, 4) + pad;
     L.hub_off = L.b_off + k * L.stride;
     L.total = L.hub_off + (hub ? hub_words(nnz / kHubMin, fw) : 0);
+    return L;
+}
+
+// LDS layout of a fused task (M operations with the same output rows, summed), in words:
+//   [0, 4M)                       per member: column array, value array, dense tile, nnz
+//   [rpt_off + j*rs, ...)         row pointers of member j, rs = round_up(m+1, 4)
+//   then per member               column indices and values (round_up(nnz, 4) words each)
+//   then rs words                 row pointers of the merged CSR (row r = all members' row r)
+//   then 2*round_up(sum nnz, 2)   its entries: (LDS word offset of the dense row, value)
+//   then per distinct dense input its tile, k rows of round_up(fw, 4) words
+struct FusedLayout {
+    int rpt_off;
+    int rs;
+    int cv_off;     // first word after the row pointers
+};
+
+BSPMM_HD inline FusedLayout fused_layout(int members, int m)
+{
+    FusedLayout L;
+    L.rpt_off = round_up(4 * members, 4);
+    L.rs = round_up(m + 1, 4);
+    L.cv_off = L.rpt_off + members * L.rs;
     return L;
 }
 

@@ -33,6 +33,7 @@ struct Draft {           // one item before placement
     int staged;
     int64_t cost;
     int group;           // items with one group read the same dense tile
+    int fused;           // >= 0: index of the set of operations this task adds up
 };
 
 int bin_slot_lanes(int bin)
@@ -48,12 +49,14 @@ int bin_slot_lanes(int bin)
 int bin_range(int bin)
 {
     switch (bin) {
-        case BSPMM_BIN_WAVE: return 1;
-        case BSPMM_BIN_SLICE32: return 2;
-        case BSPMM_BIN_SLICE16: return 3;
+        case BSPMM_BIN_WAVE: return 2;
+        case BSPMM_BIN_SLICE32: return 3;
+        case BSPMM_BIN_SLICE16: return 4;
         default: return 0;
     }
 }
+
+int draft_range(const Draft& x) { return x.fused >= 0 ? 1 : bin_range(x.bin); }
 
 // Candidate tile widths, widest first.
 std::vector<int> tile_candidates(int F, const Knobs& kn)
@@ -139,36 +142,112 @@ void draft_op(const DirOps& o, int i, int F, int vec, const Choice& ch, const Kn
             const int chunk = cap * rows_per_pass;
             for (int r0 = 0; r0 < o.m[i]; r0 += chunk) {
                 const int nr = std::min(chunk, o.m[i] - r0);
-                out.push_back({i, ch.bin, r0, nr, f0, fw, 1, item_cost(o, i, nr, fw, true), gid});
+                out.push_back({i, ch.bin, r0, nr, f0, fw, 1, item_cost(o, i, nr, fw, true), gid, -1});
             }
         } else if (ch.bin != BSPMM_BIN_GENERIC) {
-            out.push_back({i, ch.bin, 0, o.m[i], f0, fw, 1, item_cost(o, i, o.m[i], fw, true), gid});
+            out.push_back({i, ch.bin, 0, o.m[i], f0, fw, 1, item_cost(o, i, o.m[i], fw, true), gid, -1});
         } else {
             for (int r0 = 0; r0 < o.m[i]; r0 += kn.generic_rows) {
                 const int nr = std::min(kn.generic_rows, o.m[i] - r0);
-                out.push_back({i, ch.bin, r0, nr, f0, fw, 0, item_cost(o, i, nr, fw, false), gid});
+                out.push_back({i, ch.bin, r0, nr, f0, fw, 0, item_cost(o, i, nr, fw, false), gid, -1});
             }
         }
     }
 }
 
+// LDS words a fused task needs: mirrors run_fused() in kernels.hip.
+int64_t fused_words(const DirOps& o, const std::vector<int>& members, int fw)
+{
+    const FusedLayout L = fused_layout((int)members.size(), o.m[members[0]]);
+    int64_t words = L.cv_off + L.rs;               // member tables, then merged row pointers
+    int64_t nnz_sum = 0;
+    for (int i : members) nnz_sum += o.nnz[i];
+    words += 2 * ((nnz_sum + 1) / 2 * 2);          // merged entries
+    for (size_t j = 0; j < members.size(); ++j) {
+        words += 2 * (int64_t)round_up(o.nnz[members[j]], 4);
+        bool owns = true;
+        for (size_t e = 0; e < j; ++e) owns = owns && o.in_off[members[e]] != o.in_off[members[j]];
+        if (owns) words += (int64_t)o.k[members[j]] * round_up(fw, 4);
+    }
+    return words;
+}
+
+// Tasks of one set of operations that are summed into one output block.  The tile is the
+// widest candidate (from `first` on, then 16, 8 and 4 floats) whose task fits LDS; returns false
+// when none does.
+bool draft_fused(const DirOps& o, const std::vector<int>& members, int fused_index, int F, int vec,
+                 const std::vector<int>& cand, size_t first, const Knobs& kn, int cap,
+                 std::vector<Draft>& out)
+{
+    std::vector<int> tiles(cand.begin() + first, cand.end());
+    for (int t : {16, 8, 4})
+        if (t < tiles.back()) tiles.push_back(t);
+    int tile = 0;
+    for (int t : tiles)
+        if (fused_words(o, members, std::min(t, F)) <= kn.lds_words) {
+            tile = t;
+            break;
+        }
+    if (!tile) return false;
+    const int m = o.m[members[0]];
+    for (int f0 = 0; f0 < F; f0 += tile) {
+        const int fw = std::min(tile, F - f0);
+        const int rows_per_pass = kThreads / lanes_per_row(fw, vec);
+        const int chunk = cap > 0 ? cap * rows_per_pass : m;
+        for (int r0 = 0; r0 < m; r0 += chunk) {
+            const int nr = std::min(chunk, m - r0);
+            int64_t cost = 0;
+            for (int i : members) cost += item_cost(o, i, nr, fw, true);
+            out.push_back({members[0], BSPMM_BIN_WORKGROUP, r0, nr, f0, fw, 1, cost, -1, fused_index});
+        }
+    }
+    return true;
+}
+
+// Operations grouped by the output block they name: a group of more than one is summed.
+std::vector<std::vector<int>> output_groups(const DirOps& o)
+{
+    std::map<std::pair<int64_t, int>, int> index;
+    std::vector<std::vector<int>> groups;
+    for (int i = 0; i < o.size(); ++i) {
+        if (o.m[i] <= 0) continue;
+        auto key = std::make_pair(o.out_off[i], o.m[i]);
+        auto it = index.find(key);
+        if (it == index.end()) {
+            index.emplace(key, (int)groups.size());
+            groups.push_back({i});
+        } else {
+            groups[it->second].push_back(i);
+        }
+    }
+    return groups;
+}
+
 std::vector<Draft> draft_all(const DirOps& o, int F, int vec, const std::vector<int>& cand,
-                             size_t first, const Knobs& kn, int cap, bool allow_small)
+                             size_t first, const Knobs& kn, int cap, bool allow_small,
+                             const std::vector<std::vector<int>>& outs, bool* fits)
 {
     std::vector<Draft> d;
     std::map<std::pair<int64_t, int>, int> groups;
-    for (int i = 0; i < o.size(); ++i)
-        draft_op(o, i, F, vec, choose(o, i, F, vec, cand, first, kn, allow_small), kn, cap, groups,
-                 d);
+    int nfused = 0;
+    for (const std::vector<int>& g : outs) {
+        if (g.size() == 1) {
+            const int i = g[0];
+            draft_op(o, i, F, vec, choose(o, i, F, vec, cand, first, kn, allow_small), kn, cap,
+                     groups, d);
+        } else if (!draft_fused(o, g, nfused++, F, vec, cand, first, kn, cap, d)) {
+            *fits = false;
+        }
+    }
     return d;
 }
 
 int count_workgroups(const std::vector<Draft>& d)
 {
-    int per_range[kRanges] = {0, 0, 0, 0};
-    for (const Draft& x : d) per_range[bin_range(x.bin)]++;
-    int wgs = per_range[0];
-    for (int r = 1; r < kRanges; ++r) {
+    int per_range[kRanges] = {0, 0, 0, 0, 0};
+    for (const Draft& x : d) per_range[draft_range(x)]++;
+    int wgs = per_range[0] + per_range[1];
+    for (int r = 2; r < kRanges; ++r) {
         const int slots = kThreads >> range_log2_slot(r);
         wgs += (per_range[r] + slots - 1) / slots;
     }
@@ -222,6 +301,7 @@ Knobs resolve_knobs(const bspmm_options* o)
     k.wg_passes = o->wg_passes;
     if (o->resident_workgroups > 0) k.persistent_wgs = o->resident_workgroups;
     k.hubs = (o->flags & BSPMM_SPLIT_HUB_ROWS) != 0;
+    k.accumulate = (o->flags & BSPMM_ACCUMULATE) != 0;
     return k;
 }
 
@@ -242,9 +322,17 @@ Schedule make_schedule(const DirOps& ops, int F, const Knobs& kn_in)
     // workgroup staging it.  A forced bin overrides this.
     const int fixed_cap = kn.wg_passes > 0 ? kn.wg_passes : 0;
     bool allow_small = kn.force_bin >= 0;
+    const std::vector<std::vector<int>> outs = output_groups(ops);
+    size_t most_members = 1;
+    for (const auto& g : outs) most_members = std::max(most_members, g.size());
+    if (most_members > (size_t)kMaxMembers) {
+        s.error = BSPMM_ETOOBIG;
+        return s;
+    }
+    bool fits = true;
     for (int attempt = 0; attempt < 2; ++attempt) {
         for (size_t c = 0; c < cand.size(); ++c) {
-            d = draft_all(ops, F, vec, cand, c, kn, fixed_cap, allow_small);
+            d = draft_all(ops, F, vec, cand, c, kn, fixed_cap, allow_small, outs, &fits);
             if (count_workgroups(d) >= kn.target_wgs || c + 1 == cand.size()) {
                 chosen = c;
                 break;
@@ -258,14 +346,20 @@ Schedule make_schedule(const DirOps& ops, int F, const Knobs& kn_in)
     // the slowest workgroup, so cut multi-pass workgroup items into row ranges
     if (kn.wg_passes == 0 && count_workgroups(d) < kn.target_wgs) {
         for (int cap = 4; cap >= 1; cap /= 2) {
-            d = draft_all(ops, F, vec, cand, chosen, kn, cap, allow_small);
+            d = draft_all(ops, F, vec, cand, chosen, kn, cap, allow_small, outs, &fits);
             if (count_workgroups(d) >= kn.target_wgs) break;
         }
+    }
+    if (!fits) {   // a set of summed operations does not fit LDS together even at 4 columns
+        s.error = BSPMM_ETOOBIG;
+        return s;
     }
 
     // group costs, for ordering and XCD placement
     int ngroups = 0;
     for (const Draft& x : d) ngroups = std::max(ngroups, x.group + 1);
+    for (Draft& x : d)
+        if (x.fused >= 0) x.group = ngroups++;                // fused tasks stand alone
     std::vector<int64_t> gcost(ngroups, 0);
     std::vector<int> gsize(ngroups, 0);
     for (const Draft& x : d) {
@@ -273,10 +367,10 @@ Schedule make_schedule(const DirOps& ops, int F, const Knobs& kn_in)
         ++gsize[x.group];
     }
     for (Draft& x : d)
-        if (x.staged && gsize[x.group] == 1) x.staged |= 2;   // nobody else reads this tile
+        if (x.fused < 0 && x.staged && gsize[x.group] == 1) x.staged |= 2;   // tile read once
 
     std::vector<std::vector<int>> by_range(kRanges);
-    for (int idx = 0; idx < (int)d.size(); ++idx) by_range[bin_range(d[idx].bin)].push_back(idx);
+    for (int idx = 0; idx < (int)d.size(); ++idx) by_range[draft_range(d[idx])].push_back(idx);
     auto big_first = [&](int a, int b) {
         const Draft &x = d[a], &y = d[b];
         if (gcost[x.group] != gcost[y.group]) return gcost[x.group] > gcost[y.group];
@@ -343,8 +437,39 @@ Schedule make_schedule(const DirOps& ops, int F, const Knobs& kn_in)
         }
     s.wg_end[0] = grid0;
 
+    // range 1: fused tasks, `fused_stride` item slots each (the members, then empty items)
     int wg = grid0;
-    for (int r = 1; r < kRanges; ++r) {
+    {
+        std::vector<std::vector<int>> fused_sets;
+        for (const auto& g : outs)
+            if (g.size() > 1) fused_sets.push_back(g);
+        s.fused_stride = (int)most_members;
+        s.item_base[1] = (int)s.items.size();
+        for (int idx : by_range[1]) {
+            const Draft& x = d[idx];
+            const std::vector<int>& mem = fused_sets[x.fused];
+            for (size_t j = 0; j < mem.size(); ++j) {
+                Draft y = x;
+                y.op = mem[j];
+                WorkItem w = to_item(ops, y);
+                size_t owner = j;
+                for (size_t e = 0; e < j; ++e)
+                    if (ops.in_off[mem[e]] == ops.in_off[mem[j]]) {
+                        owner = e;
+                        break;
+                    }
+                w.staged = 1 | (j == 0 ? (int)mem.size() << 8 : 0) | ((int)owner << 16);
+                s.items.push_back(w);
+                s.view.push_back({y.op, BSPMM_BIN_WORKGROUP, x.row0, x.nrows, x.f0, x.fw, wg, (int)j});
+                s.items_in_bin[BSPMM_BIN_WORKGROUP]++;
+            }
+            for (size_t j = mem.size(); j < most_members; ++j) s.items.push_back(empty_item());
+            ++wg;
+            ++s.fused_tasks;
+        }
+        s.wg_end[1] = wg;
+    }
+    for (int r = 2; r < kRanges; ++r) {
         const int slots = kThreads >> range_log2_slot(r);
         s.item_base[r] = (int)s.items.size();
         const std::vector<int>& v = by_range[r];

@@ -31,6 +31,7 @@ struct Knobs {
     int wg_passes = 0;        // 0 automatic, >0 cap on passes of a workgroup item, <0 never cut
     int capacity_wgs = 1536;  // workgroups the chip holds at once (lean kernel variant)
     int capacity_wgs_slices = 1024;   // same for the kernel variant with 32/16-lane slots
+    bool accumulate = false;  // operations naming one output block are summed (else an error)
     bool hubs = false;        // split hub rows across the workgroup (reserves LDS for it)
     int persistent_wgs = 0;   // > 0: launch only this many workgroups and let them stride
 };
@@ -38,8 +39,11 @@ struct Knobs {
 struct Schedule {
     std::vector<WorkItem> items;     // device table, launch order, padded with empty items
     std::vector<bspmm_item> view;    // the non-empty items, for inspection
-    int32_t wg_end[kRanges] = {0, 0, 0, 0};
-    int32_t item_base[kRanges] = {0, 0, 0, 0};
+    int32_t wg_end[kRanges] = {0, 0, 0, 0, 0};
+    int32_t item_base[kRanges] = {0, 0, 0, 0, 0};
+    int fused_stride = 1;            // item slots per fused task
+    int fused_tasks = 0;
+    int error = 0;                   // BSPMM_E* when the batch cannot be scheduled
     int grid = 0;                    // number of tasks
     int launch_grid = 0;             // workgroups of the persistent launch
     bool has_slices = false;         // any 32- or 16-lane item: needs the larger kernel variant

@@ -217,6 +217,44 @@ def test_split_hub_rows(torch_cuda, oracle, maker):
     assert np.array_equal(got, again)
 
 
+@pytest.mark.parametrize("F", [128, 32, 100, 63, 256])
+@pytest.mark.parametrize("own_inputs", [False, True])
+def test_channel_sum_in_one_pass(torch_cuda, oracle, F, own_inputs):
+    """BSPMM_ACCUMULATE: the channels of a graph name one output block and are summed in
+    registers (forward), and their transposed products are summed into the shared input
+    gradient (transposed)."""
+    b = W.config3_multichannel(graphs=96, F=F, accumulate=True, own_inputs=own_inputs,
+                               with_dY=True)
+    opts = K.make_options(flags=K.ACCUMULATE)
+    plan, got = _check_forward(torch_cuda, oracle, b, opts, what=f"channel sum F={F}")
+    info = plan.info()
+    assert info.fused_tasks[0] > 0 and info.transposed_supported == 1
+    _check_transposed(torch_cuda, oracle, b, plan=plan, what=f"channel sum F={F}")
+    _, again = _forward(torch_cuda, b, opts)
+    assert np.array_equal(got, again)
+
+
+def test_channel_sum_full_size_and_shared_input_gradient(torch_cuda, oracle):
+    b = W.config3_multichannel(accumulate=True, with_dY=True)
+    opts = K.make_options(flags=K.ACCUMULATE)
+    plan, _ = _check_forward(torch_cuda, oracle, b, opts)
+    _check_transposed(torch_cuda, oracle, b, plan=plan)
+    # the configuration as BASELINE states it (4 outputs per graph, one shared input): forward
+    # is unchanged, and the transposed product now sums the 4 channels into the shared block
+    c3 = W.config3_multichannel(with_dY=True)
+    plan3, _ = _check_forward(torch_cuda, oracle, c3, opts)
+    assert plan3.info().fused_tasks[0] == 0 and plan3.info().fused_tasks[1] > 0
+    _check_transposed(torch_cuda, oracle, c3, plan=plan3)
+    # unit entries: the channel matrices partition the edges, the sum is the neighbour sum
+    u = W.config3_multichannel(graphs=64, F=64, accumulate=True, normalise=False)
+    u = dataclasses.replace(u, B=np.ones_like(u.B))
+    _, ones = _forward(torch_cuda, u, opts)
+    ch = u.meta["channels"]
+    deg = np.concatenate([sum(np.diff(u.op_csr(g * ch + k)[0]) for k in range(ch))
+                          for g in range(u.n_graphs)])
+    assert np.array_equal(ones, np.repeat(deg[:, None], u.F, axis=1).astype(np.float32))
+
+
 def test_empty_batch_and_all_empty_matrices(torch_cuda, oracle):
     e = W.random_general(1, F=8, shapes=[])
     plan = K.Plan(e)

@@ -35,7 +35,7 @@ def test_struct_sizes_match_header():
     assert ctypes.sizeof(K.bspmm_item) == 32
     assert ctypes.sizeof(K.bspmm_options) == 48
     assert ctypes.sizeof(K.bspmm_batch) == 8 + 10 * 8
-    assert ctypes.sizeof(K.bspmm_info) == 16 + 8 + 8 + 8 + 8 + 40 + 8 + 16 + 8 + 8
+    assert ctypes.sizeof(K.bspmm_info) == 16 + 8 + 8 + 8 + 8 + 40 + 8 + 8 + 16 + 8 + 8
 
 
 def _slot_lanes(bin_):
@@ -63,17 +63,27 @@ def _check_schedule(b, F, transposed=False, **opts):
         k_of = b.rows if transposed else b.cols
         cover = [np.zeros((int(m), F), dtype=np.int32) for m in m_of]
         seen = set()
+        out_of = b.b_row_off if transposed else b.c_row_off
+        blocks = {}
+        for i in range(b.batch):
+            if int(m_of[i]) > 0:
+                blocks.setdefault((int(out_of[i]), int(m_of[i])), []).append(i)
+        summed = {i for ops in blocks.values() if len(ops) > 1 for i in ops}
         pad = max(opts.get("lds_pad", 0), 0)
         for it in items:
             assert 0 <= it.op < b.batch
             assert it.nrows > 0 and it.fw > 0
             cover[it.op][it.row0:it.row0 + it.nrows, it.f0:it.f0 + it.fw] += 1
             lanes = _slot_lanes(it.bin)
-            assert 0 <= it.slot < 256 // lanes
+            if it.op in summed:
+                assert 0 <= it.slot < 8          # member index inside the fused task
+            else:
+                assert 0 <= it.slot < 256 // lanes
             assert 0 <= it.workgroup < info.tasks[d]
             assert (it.workgroup, it.slot) not in seen
             seen.add((it.workgroup, it.slot))
-            if it.bin != K.BIN_GENERIC:
+            fused_member = it.op in summed
+            if it.bin != K.BIN_GENERIC and not fused_member:
                 if it.bin != K.BIN_WORKGROUP:   # only workgroup items may be cut into row ranges
                     assert it.row0 == 0 and it.nrows == int(m_of[it.op])
                 need = _lds_words(int(m_of[it.op]), int(k_of[it.op]), int(b.nnz[it.op]), it.fw, pad, lanes, bool(opts.get('flags', 0) & K.SPLIT_HUB_ROWS))
@@ -236,3 +246,60 @@ def test_empty_batch_and_workspace_size():
     # the transposed CSR (row pointers, columns, values) lives in the workspace
     assert n >= 4 * (int((b.cols.astype(np.int64) + 1).sum()) + 2 * int(b.nnz.sum()))
     K.bspmm_destroy(h)
+
+
+def test_summed_operations_share_one_task():
+    """With BSPMM_ACCUMULATE the channels of a graph (same output block) become members of
+    one fused task per (tile, row range); every member still covers its rows exactly once."""
+    for own in (False, True):
+        b = W.config3_multichannel(graphs=48, accumulate=True, own_inputs=own)
+        info, items = _check_schedule(b, b.F, flags=K.ACCUMULATE)
+        assert info.fused_tasks[0] > 0 and info.transposed_supported == 1
+        ch = b.meta["channels"]
+        by_task = {}
+        for it in items:
+            by_task.setdefault(it.workgroup, []).append(it)
+        for members in by_task.values():
+            assert len(members) == ch
+            assert len({m.op // ch for m in members}) == 1           # one graph
+            assert sorted(m.slot for m in members) == list(range(ch))
+            assert len({(m.row0, m.nrows, m.f0, m.fw) for m in members}) == 1
+        _check_schedule(b, b.F, transposed=True, flags=K.ACCUMULATE)
+        assert info.effective_bytes[0] == W.effective_bytes(b)
+    # shared inputs, separate outputs: the transposed product sums into the shared input block
+    b = W.config3_multichannel(graphs=16)
+    info, _ = _check_schedule(b, b.F, flags=K.ACCUMULATE)
+    assert info.fused_tasks[0] == 0 and info.transposed_supported == 1
+    info_t, _ = _check_schedule(b, b.F, transposed=True, flags=K.ACCUMULATE)
+    assert info_t.fused_tasks[1] > 0
+
+
+def test_summed_operations_need_the_flag_and_must_fit():
+    b = W.config3_multichannel(graphs=4, accumulate=True)
+    hb = K.HostBatch(b.rows, b.cols, b.nnz, b.rpt_off, b.nz_off, b.b_row_off, b.c_row_off)
+    with pytest.raises(K.BspmmError) as e:
+        K.bspmm_create(hb, b.F, K.make_options(flags=K.DRY_RUN))
+    assert e.value.code == K.EOVERLAP
+    # nine operations into one block: more members than a fused task holds
+    many = W.config3_multichannel(graphs=2, channels=9, accumulate=True)
+    hb = K.HostBatch(many.rows, many.cols, many.nnz, many.rpt_off, many.nz_off, many.b_row_off,
+                     many.c_row_off)
+    with pytest.raises(K.BspmmError) as e:
+        K.bspmm_create(hb, many.F, K.make_options(flags=K.DRY_RUN | K.ACCUMULATE))
+    assert e.value.code == K.ETOOBIG
+    # two large operations into one block: their arrays do not fit LDS together
+    big = W.random_general(5, F=64, shapes=[(3000, 3000, 9000), (3000, 3000, 9000)], with_dY=False)
+    big.c_row_off[1] = big.c_row_off[0]
+    hb = K.HostBatch(big.rows, big.cols, big.nnz, big.rpt_off, big.nz_off, big.b_row_off,
+                     big.c_row_off)
+    with pytest.raises(K.BspmmError) as e:
+        K.bspmm_create(hb, 64, K.make_options(flags=K.DRY_RUN | K.ACCUMULATE))
+    assert e.value.code == K.ETOOBIG
+    # partial overlap is an error with or without the flag
+    b2 = W.config1_tiny()
+    off = b2.c_row_off.copy()
+    off[1] = off[0] + 1
+    hb = K.HostBatch(b2.rows, b2.cols, b2.nnz, b2.rpt_off, b2.nz_off, b2.b_row_off, off)
+    with pytest.raises(K.BspmmError) as e:
+        K.bspmm_create(hb, 64, K.make_options(flags=K.DRY_RUN | K.ACCUMULATE))
+    assert e.value.code == K.EOVERLAP
