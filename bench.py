@@ -165,6 +165,28 @@ def copy_bandwidth(torch):
     return 2 * 4 * n / sec * 1e-9
 
 
+def paper_grid(torch, K, W):
+    """Batched against one launch per matrix on the random square matrices of the paper's
+    preliminary evaluation (Sec. V-A: batch 50/100, dim 50, 2-3 entries per row, n_B swept; and
+    the mixed batch with dim 32-256, 1-5 entries per row, n_B = 1024).  Cache-warm."""
+    rows = []
+    grid = [("batch50_dim50_nnz2", 50, 50, 2, (32, 64, 128, 256, 512)),
+            ("batch100_dim50_nnz3", 100, 50, 3, (64, 512)),
+            ("batch100_dim32-256_nnz1-5", 100, (32, 256), (1, 5), (1024,))]
+    for name, batch, dim, nz, widths in grid:
+        for F in widths:
+            b = W.random_square(W.config_seed(8) + F, F, batch, dim, nz)
+            r = Runner(torch, K, b, pool_bytes=1)
+            s, _ = r.time_graph(400, 40, rotate=False)
+            nb = non_batched(torch, K, b, s)
+            rows.append({"workload": name, "n_B": F, "batched_us": round(s * 1e6, 2),
+                         "gflops": round(r.flops / s * 1e-9, 1),
+                         "non_batched_us": min(nb["eager_us_per_batch"], nb["hipgraph_us_per_batch"]),
+                         "speedup": nb["batched_speedup"]})
+            del r
+    return rows
+
+
 def non_batched(torch, K, b, batched_sec):
     """The paper's comparison (Sec. V-A): the same graphs multiplied one launch per graph
     (a single-operation plan each, same kernel) against the one batched launch."""
@@ -347,6 +369,7 @@ def main():
                 del r
                 torch.cuda.empty_cache()
         extra["channel_sum"] = acc
+        extra["paper_grid_batched_vs_non_batched"] = paper_grid(torch, K, W)
 
     out = {
         "metric": "batched SpMM graphs/sec, F=128, batch 128",

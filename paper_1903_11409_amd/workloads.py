@@ -416,6 +416,26 @@ def random_general(seed: int, F: int, shapes: Sequence[Tuple[int, int, int]],
     return b
 
 
+def random_square(seed: int, F: int, batch: int, dim, nnz_per_row) -> Batch:
+    """The paper's preliminary workload (Sec. V-A): ``batch`` random square matrices, every
+    row holding ``nnz_per_row`` entries at distinct random columns (sorted), values U[-1,1).
+    ``dim`` and ``nnz_per_row`` are ints, or (lo, hi) pairs drawn per matrix for the mixed
+    batch of the last preliminary experiment."""
+    rng = np.random.default_rng(seed)
+    ops, blocks = [], []
+    for _ in range(batch):
+        n = int(dim if np.isscalar(dim) else rng.integers(dim[0], dim[1] + 1))
+        z = int(nnz_per_row if np.isscalar(nnz_per_row)
+                else rng.integers(nnz_per_row[0], nnz_per_row[1] + 1))
+        z = min(z, n)
+        cols = np.stack([np.sort(rng.choice(n, size=z, replace=False)) for _ in range(n)])
+        rpt = (np.arange(n + 1) * z).astype(np.int32)
+        vals = rng.uniform(-1.0, 1.0, size=n * z).astype(np.float32)
+        ops.append((n, n, rpt, cols.reshape(-1).astype(np.int32), vals))
+        blocks.append(n)
+    return assemble("random_square", F, ops, list(range(batch)), blocks, rng)
+
+
 def identity_batch(seed: int, F: int, sizes: Sequence[int]) -> Batch:
     """Every A_i is the identity matrix (values exactly 1.0)."""
     rng = np.random.default_rng(seed)
