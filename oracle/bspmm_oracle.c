@@ -30,7 +30,9 @@
  *
  * Pins (tests/test_oracle_pins.py): dense brute force, a library CSR product, A = I,
  * empty rows, linearity, node relabelling, the eigenvector of the symmetric normalisation,
- * row sums of the row normalisation, the adjoint identity <AB, dY> = <B, A^T dY>.
+ * row sums of the row normalisation, the adjoint identity <AB, dY> = <B, A^T dY>; for the COO
+ * functions a dense matrix assembled entry by entry, a library COO product, invariance under
+ * shuffling the entries, repeated pairs, and a library stable sort for the conversion.
  *
  * Returns 0, or a negative number naming the first malformed operation (-(i+1)).
  */
@@ -179,6 +181,92 @@ int oracle_csr_transpose(int32_t batch, const int32_t* rows, const int32_t* cols
                 ct[q] = r;
                 vt[q] = va[p];
             }
+    }
+    return 0;
+}
+
+/*
+ * COO / SparseTensor operands (Sec. II-B, Fig. 1: an entry is a (row, column) index pair and a
+ * value; Sec. IV: the entries are NOT sorted by row or column).  Op i holds nnz[i] entries:
+ * pair p at ids[2*(nz_off[i]+p)] = row, ids[2*(nz_off[i]+p)+1] = column, value at
+ * values[nz_off[i]+p].  The product is the loop nest of Fig. 2: set C to O, then for every
+ * stored entry in stored order and every column j, C[rid][j] += val * B[cid][j]; with
+ * `transposed` != 0 the roles of the two indices are swapped (G[cid][j] += val * dY[rid][j],
+ * dY at c_row_off with rows[i] rows, G at b_row_off with cols[i] rows).  Repeated (row, column)
+ * pairs are added up, as the loop nest does.  Operations naming one output block are summed.
+ */
+static int check_coo(int32_t rows, int32_t cols, int32_t nnz, const int32_t* id)
+{
+    if (rows < 0 || cols < 0 || nnz < 0) return 0;
+    for (int32_t p = 0; p < nnz; ++p)
+        if (id[2 * p] < 0 || id[2 * p] >= rows || id[2 * p + 1] < 0 || id[2 * p + 1] >= cols)
+            return 0;
+    return 1;
+}
+
+int oracle_coo_product(int32_t batch, int32_t transposed, const int32_t* rows,
+                       const int32_t* cols, const int32_t* nnz, const int64_t* nz_off,
+                       const int64_t* b_row_off, const int64_t* c_row_off, const int32_t* ids,
+                       const float* values, const float* X, int64_t ldx, int32_t F,
+                       double* Y, double* S, int64_t ldy)
+{
+    for (int32_t i = 0; i < batch; ++i)
+        if (!check_coo(rows[i], cols[i], nnz[i], ids + 2 * nz_off[i])) return -(i + 1);
+    const int64_t* in_off = transposed ? c_row_off : b_row_off;
+    const int64_t* out_off = transposed ? b_row_off : c_row_off;
+    const int32_t* out_rows = transposed ? cols : rows;
+    for (int32_t i = 0; i < batch; ++i)
+        for (int32_t r = 0; r < out_rows[i]; ++r)
+            for (int32_t j = 0; j < F; ++j) {
+                Y[(out_off[i] + r) * ldy + j] = 0.0;
+                if (S) S[(out_off[i] + r) * ldy + j] = 0.0;
+            }
+    for (int32_t i = 0; i < batch; ++i) {
+        const int32_t* id = ids + 2 * nz_off[i];
+        const float* va = values + nz_off[i];
+        for (int32_t p = 0; p < nnz[i]; ++p) {
+            const int32_t rid = transposed ? id[2 * p + 1] : id[2 * p];
+            const int32_t cid = transposed ? id[2 * p] : id[2 * p + 1];
+            const double val = (double)va[p];
+            const float* x = X + (in_off[i] + cid) * ldx;
+            double* y = Y + (out_off[i] + rid) * ldy;
+            double* s = S ? S + (out_off[i] + rid) * ldy : NULL;
+            for (int32_t j = 0; j < F; ++j) {
+                y[j] += val * (double)x[j];
+                if (s) s[j] += fabs(val) * fabs((double)x[j]);
+            }
+        }
+    }
+    return 0;
+}
+
+/*
+ * CSR of every COO operation by the textbook stable counting sort over rows: count the
+ * entries of each row, prefix-sum into row pointers, then walk the entries in stored order and
+ * append each to its row's list.  Inside a row the entries keep their stored order (repeated
+ * pairs stay separate entries).  Op i of the result has rows[i]+1 local row pointers at
+ * rpt_off[i]; its entries sit at nz_off[i] like the input's.
+ */
+int oracle_coo_to_csr(int32_t batch, const int32_t* rows, const int32_t* cols,
+                      const int32_t* nnz, const int64_t* nz_off, const int32_t* ids,
+                      const float* values, const int64_t* rpt_off, int32_t* rpt,
+                      int32_t* colids, float* csr_values, int32_t* cursor_scratch /* >= max rows */)
+{
+    for (int32_t i = 0; i < batch; ++i)
+        if (!check_coo(rows[i], cols[i], nnz[i], ids + 2 * nz_off[i])) return -(i + 1);
+    for (int32_t i = 0; i < batch; ++i) {
+        const int32_t* id = ids + 2 * nz_off[i];
+        const float* va = values + nz_off[i];
+        int32_t* rp = rpt + rpt_off[i];
+        for (int32_t r = 0; r <= rows[i]; ++r) rp[r] = 0;
+        for (int32_t p = 0; p < nnz[i]; ++p) rp[id[2 * p] + 1] += 1;
+        for (int32_t r = 0; r < rows[i]; ++r) rp[r + 1] += rp[r];
+        for (int32_t r = 0; r < rows[i]; ++r) cursor_scratch[r] = rp[r];
+        for (int32_t p = 0; p < nnz[i]; ++p) {
+            const int32_t q = cursor_scratch[id[2 * p]]++;
+            colids[nz_off[i] + q] = id[2 * p + 1];
+            csr_values[nz_off[i] + q] = va[p];
+        }
     }
     return 0;
 }

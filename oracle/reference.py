@@ -48,6 +48,13 @@ def _load():
         lib.oracle_csr_transpose.argtypes = [ctypes.c_int32, i32p, i32p, i32p, i64p, i64p,
                                              i32p, i32p, f32p, i64p, i32p, i32p, f32p, i32p]
         lib.oracle_csr_transpose.restype = ctypes.c_int
+        lib.oracle_coo_product.argtypes = [ctypes.c_int32, ctypes.c_int32, i32p, i32p, i32p,
+                                           i64p, i64p, i64p, i32p, f32p, f32p, ctypes.c_int64,
+                                           ctypes.c_int32, f64p, f64p, ctypes.c_int64]
+        lib.oracle_coo_product.restype = ctypes.c_int
+        lib.oracle_coo_to_csr.argtypes = [ctypes.c_int32, i32p, i32p, i32p, i64p, i32p, f32p,
+                                          i64p, i32p, i32p, f32p, i32p]
+        lib.oracle_coo_to_csr.restype = ctypes.c_int
         lib.oracle_num_threads.restype = ctypes.c_int
         lib.oracle_set_num_threads.argtypes = [ctypes.c_int]
         _lib = lib
@@ -146,6 +153,59 @@ def csr_transpose(rows, cols, nnz, rpt_off, nz_off, rpt, colids, values):
     if rc != 0:
         raise ValueError(f"oracle: malformed operation {-rc - 1}")
     return rpt_t_off, rpt_t, colids_t, values_t
+
+
+def coo_product(rows, cols, nnz, nz_off, b_row_off, c_row_off, ids, values, X: np.ndarray,
+                n_out_rows: int, transposed_: bool = False, want_scale: bool = True
+                ) -> Tuple[np.ndarray, Optional[np.ndarray]]:
+    """Product of every COO / SparseTensor operation (Fig. 2 loop nest): Y_i = A_i X_i, or
+    A_i^T X_i with ``transposed_``.  ``ids`` holds (row, column) pairs, op i at 2*nz_off[i]."""
+    lib = _load()
+    as_ = np.ascontiguousarray
+    rows, cols, nnz = (as_(x, dtype=np.int32) for x in (rows, cols, nnz))
+    nz_off, b_row_off, c_row_off = (as_(x, dtype=np.int64) for x in (nz_off, b_row_off, c_row_off))
+    ids = as_(ids, dtype=np.int32)
+    values = as_(values, dtype=np.float32)
+    X = as_(X, dtype=np.float32)
+    F = int(X.shape[1])
+    Y = np.full((int(n_out_rows), F), np.nan, dtype=np.float64)
+    S = np.full((int(n_out_rows), F), np.nan, dtype=np.float64) if want_scale else None
+    rc = lib.oracle_coo_product(
+        int(rows.shape[0]), 1 if transposed_ else 0, _p(rows, ctypes.c_int32),
+        _p(cols, ctypes.c_int32), _p(nnz, ctypes.c_int32), _p(nz_off, ctypes.c_int64),
+        _p(b_row_off, ctypes.c_int64), _p(c_row_off, ctypes.c_int64), _p(ids, ctypes.c_int32),
+        _p(values, ctypes.c_float), _p(X, ctypes.c_float), F, F, _p(Y, ctypes.c_double),
+        _p(S, ctypes.c_double) if S is not None else None, F)
+    if rc != 0:
+        raise ValueError(f"oracle: malformed operation {-rc - 1}")
+    return Y, S
+
+
+def coo_to_csr(rows, cols, nnz, nz_off, ids, values):
+    """Stable CSR of every COO operation.  Returns (rpt_off, rpt, colids, csr_values): op i has
+    rows[i]+1 local row pointers at rpt_off[i]; its entries sit at nz_off[i] like the input's."""
+    lib = _load()
+    as_ = np.ascontiguousarray
+    rows, cols, nnz = (as_(x, dtype=np.int32) for x in (rows, cols, nnz))
+    nz_off = as_(nz_off, dtype=np.int64)
+    ids = as_(ids, dtype=np.int32)
+    values = as_(values, dtype=np.float32)
+    nb = int(rows.shape[0])
+    rpt_off = np.zeros(nb, dtype=np.int64)
+    if nb:
+        rpt_off[1:] = np.cumsum(rows[:-1].astype(np.int64) + 1)
+    rpt = np.zeros(int((rows.astype(np.int64) + 1).sum()), dtype=np.int32)
+    colids = np.zeros(values.shape[0], dtype=np.int32)
+    csr_values = np.zeros(values.shape[0], dtype=np.float32)
+    scratch = np.zeros(max(int(rows.max()) if nb else 0, 1), dtype=np.int32)
+    rc = lib.oracle_coo_to_csr(
+        nb, _p(rows, ctypes.c_int32), _p(cols, ctypes.c_int32), _p(nnz, ctypes.c_int32),
+        _p(nz_off, ctypes.c_int64), _p(ids, ctypes.c_int32), _p(values, ctypes.c_float),
+        _p(rpt_off, ctypes.c_int64), _p(rpt, ctypes.c_int32), _p(colids, ctypes.c_int32),
+        _p(csr_values, ctypes.c_float), _p(scratch, ctypes.c_int32))
+    if rc != 0:
+        raise ValueError(f"oracle: malformed operation {-rc - 1}")
+    return rpt_off, rpt, colids, csr_values
 
 
 def forward_batch(b, want_scale: bool = True):

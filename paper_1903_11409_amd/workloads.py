@@ -458,6 +458,28 @@ def hub_batch(seed: int, F: int, n: int, copies: int = 2) -> Batch:
     return assemble("hub", F, ops, list(range(copies)), [n] * copies, rng, with_dY=True)
 
 
+def coo_view(b: Batch, seed: Optional[int] = None, shuffle: bool = True
+             ) -> Tuple[np.ndarray, np.ndarray]:
+    """The batch as SparseTensor / COO entries (Fig. 1): ``ids`` is int32 [2*sum(nnz)] with
+    the (row, column) pair of entry p of operation i at ``ids[2*(nz_off[i]+p)], [..+1]`` and the
+    matching ``values``.  With ``shuffle`` the entries of every operation are put in a seeded
+    random order (the paper assumes they are sorted neither by row nor by column, Sec. IV);
+    without it they keep the CSR's stored order."""
+    rng = np.random.default_rng(BASE_SEED if seed is None else seed)
+    ids = np.zeros(2 * int(b.colids.shape[0]), dtype=np.int32)
+    vals = np.zeros(b.values.shape[0], dtype=np.float32)
+    for i in range(b.batch):
+        rp, ci, va = b.op_csr(i)
+        n = int(b.nnz[i])
+        rid = np.repeat(np.arange(int(b.rows[i]), dtype=np.int32), np.diff(rp))
+        order = rng.permutation(n) if shuffle else np.arange(n)
+        z0 = int(b.nz_off[i])
+        ids[2 * z0:2 * (z0 + n):2] = rid[order]
+        ids[2 * z0 + 1:2 * (z0 + n):2] = ci[order]
+        vals[z0:z0 + n] = va[order]
+    return ids, vals
+
+
 def effective_bytes(b: Batch, transposed: bool = False) -> int:
     """Compulsory bytes one launch must move: CSR once, each distinct dense block once, each
     distinct output block once (fp32 dense, int32 indices).  For the transposed product the dense input

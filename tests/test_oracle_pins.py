@@ -367,3 +367,156 @@ def test_unit_channels_sum_to_the_adjacency_matrix(oracle):
         Bg = b.B[b0:b0 + n].astype(np.float64)
         ref = np.stack([Bg[adj[r] > 0].sum(axis=0) for r in range(n)])
         assert np.allclose(C[c0:c0 + n], ref, rtol=1e-12, atol=1e-14)
+
+
+# ---------------------------------------------------------------------------------------------
+# COO / SparseTensor operands (Sec. II-B, Fig. 1; the loop nest of Fig. 2; unsorted, Sec. IV)
+# ---------------------------------------------------------------------------------------------
+def _coo_dense(b, ids, vals, i):
+    """fp64 dense copy of COO operation i, assembled entry by entry (repeats add)."""
+    z0, n = int(b.nz_off[i]), int(b.nnz[i])
+    A = np.zeros((int(b.rows[i]), int(b.cols[i])), dtype=np.float64)
+    for p in range(n):
+        A[ids[2 * (z0 + p)], ids[2 * (z0 + p) + 1]] += float(vals[z0 + p])
+    return A
+
+
+def _coo_batches():
+    return [W.random_general(51, F=5, shapes=[(7, 13, 25), (13, 7, 25), (20, 20, 90), (1, 1, 3),
+                                              (0, 0, 0), (9, 9, 0)]),
+            W.config2_molecule(graphs=6, F=3),
+            W.config5_skewed(graphs=4, F=2)]
+
+
+@pytest.mark.parametrize("which", [0, 1, 2])
+@pytest.mark.parametrize("transposed", [False, True])
+def test_coo_product_dense_and_library(oracle, which, transposed):
+    """Against a dense matrix assembled one entry at a time, and scipy's COO product."""
+    b = _coo_batches()[which]
+    if b.dY is None:
+        b.dY = np.random.default_rng(3).standard_normal((b.n_c_rows, b.F)).astype(np.float32)
+    ids, vals = W.coo_view(b, seed=77)
+    X = b.dY if transposed else b.B
+    n_out = b.n_b_rows if transposed else b.n_c_rows
+    Y, S = oracle.coo_product(b.rows, b.cols, b.nnz, b.nz_off, b.b_row_off, b.c_row_off, ids,
+                              vals, X, n_out, transposed_=transposed)
+    for i in range(b.batch):
+        A = _coo_dense(b, ids, vals, i)
+        z0, n = int(b.nz_off[i]), int(b.nnz[i])
+        L = sp.coo_matrix((vals[z0:z0 + n].astype(np.float64),
+                           (ids[2 * z0:2 * (z0 + n):2], ids[2 * z0 + 1:2 * (z0 + n):2])),
+                          shape=A.shape)
+        if transposed:
+            A, L = A.T, L.T
+            xi = X[int(b.c_row_off[i]):int(b.c_row_off[i]) + int(b.rows[i])].astype(np.float64)
+            got = Y[int(b.b_row_off[i]):int(b.b_row_off[i]) + int(b.cols[i])]
+            sc = S[int(b.b_row_off[i]):int(b.b_row_off[i]) + int(b.cols[i])]
+        else:
+            xi = X[int(b.b_row_off[i]):int(b.b_row_off[i]) + int(b.cols[i])].astype(np.float64)
+            got = Y[int(b.c_row_off[i]):int(b.c_row_off[i]) + int(b.rows[i])]
+            sc = S[int(b.c_row_off[i]):int(b.c_row_off[i]) + int(b.rows[i])]
+        assert np.allclose(got, A @ xi, rtol=1e-12, atol=1e-14)
+        assert np.allclose(got, L @ xi, rtol=1e-12, atol=1e-14)
+        if A.shape[0] and A.shape[1] and not np.allclose(A, A.T if A.shape[0] == A.shape[1] else 0):
+            wrong = A.T @ xi if A.shape[0] == A.shape[1] else None
+            if wrong is not None:
+                assert not np.allclose(got, wrong, rtol=1e-3)   # swapped indices would show
+        assert np.all(sc >= np.abs(got) - 1e-12)
+
+
+def test_coo_brute_force_tiny(oracle):
+    """Pure-Python triple loop on a tiny operation with a repeated pair."""
+    rows, cols = 3, 4
+    ids = np.array([2, 1, 0, 3, 2, 1, 1, 0, 0, 0], dtype=np.int32)      # (2,1) twice
+    vals = np.array([0.5, -2.0, 0.25, 3.0, 1.5], dtype=np.float32)
+    Bm = np.arange(1, cols * 2 + 1, dtype=np.float32).reshape(cols, 2)
+    z = np.zeros(1, dtype=np.int64)
+    Y, S = oracle.coo_product([rows], [cols], [5], z, z, z, ids, vals, Bm, rows)
+    A = np.zeros((rows, cols))
+    A[2, 1] = 0.75; A[0, 3] = -2.0; A[1, 0] = 3.0; A[0, 0] = 1.5
+    assert np.array_equal(Y, _brute(A, Bm.astype(np.float64)))
+    absA = np.zeros((rows, cols))
+    absA[2, 1] = 0.75; absA[0, 3] = 2.0; absA[1, 0] = 3.0; absA[0, 0] = 1.5
+    assert np.array_equal(S, _brute(absA, np.abs(Bm).astype(np.float64)))
+    G, _ = oracle.coo_product([rows], [cols], [5], z, z, z, ids, vals,
+                              np.arange(1, rows * 2 + 1, dtype=np.float32).reshape(rows, 2), cols,
+                              transposed_=True)
+    assert np.array_equal(G, _brute(A.T, np.arange(1, rows * 2 + 1, dtype=np.float64).reshape(rows, 2)))
+
+
+def test_coo_in_stored_order_equals_csr_oracle_bitwise(oracle):
+    """A CSR batch read out entry by entry is a COO batch whose loop nest visits every output
+    element's terms in the same order: the two oracles must agree to the last bit."""
+    b = W.config3_multichannel(graphs=6, F=7, with_dY=True)
+    ids, vals = W.coo_view(b, shuffle=False)
+    C, S = oracle.forward_batch(b)
+    Y, T = oracle.coo_product(b.rows, b.cols, b.nnz, b.nz_off, b.b_row_off, b.c_row_off, ids,
+                              vals, b.B, b.n_c_rows)
+    assert np.array_equal(C, Y, equal_nan=True) and np.array_equal(S, T, equal_nan=True)
+    G, _ = oracle.transposed_batch(b)
+    H, _ = oracle.coo_product(b.rows, b.cols, b.nnz, b.nz_off, b.b_row_off, b.c_row_off, ids,
+                              vals, b.dY, b.n_b_rows, transposed_=True)
+    assert np.array_equal(G, H, equal_nan=True)
+
+
+def test_coo_entry_order_does_not_matter(oracle):
+    b = W.config5_skewed(graphs=3, F=4)
+    ref = None
+    for seed in (1, 2, 3):
+        ids, vals = W.coo_view(b, seed=seed)
+        Y, _ = oracle.coo_product(b.rows, b.cols, b.nnz, b.nz_off, b.b_row_off, b.c_row_off,
+                                  ids, vals, b.B, b.n_c_rows)
+        if ref is None:
+            ref = Y
+        assert np.allclose(Y, ref, rtol=1e-13, atol=1e-15, equal_nan=True)
+
+
+def test_coo_to_csr_is_stable_sort_by_row(oracle):
+    """Against numpy's stable argsort of the row ids, which defines the stable conversion, and
+    (unique sorted case) against scipy's conversion."""
+    b = W.random_general(34, F=1, shapes=[(9, 5, 40), (5, 9, 40), (30, 30, 0), (1, 1, 1),
+                                          (0, 0, 0), (17, 17, 60)], with_dY=False)
+    ids, vals = W.coo_view(b, seed=5)
+    off, rp, ci, va = oracle.coo_to_csr(b.rows, b.cols, b.nnz, b.nz_off, ids, vals)
+    assert np.array_equal(off, b.rpt_off)
+    for i in range(b.batch):
+        m, z, z0 = int(b.rows[i]), int(b.nnz[i]), int(b.nz_off[i])
+        r = ids[2 * z0:2 * (z0 + z):2]
+        c = ids[2 * z0 + 1:2 * (z0 + z):2]
+        order = np.argsort(r, kind="stable")
+        assert np.array_equal(ci[z0:z0 + z], c[order])
+        assert np.array_equal(va[z0:z0 + z], vals[z0:z0 + z][order])
+        exp = np.zeros(m + 1, dtype=np.int64)
+        exp[1:] = np.cumsum(np.bincount(r, minlength=m)) if z else 0
+        o = int(off[i])
+        assert np.array_equal(rp[o:o + m + 1], exp)
+    # unique entries: the row pointers and the per-row entry SETS are scipy's
+    b2 = W.config2_molecule(graphs=5, F=1)
+    ids2, vals2 = W.coo_view(b2, seed=9)
+    off2, rp2, ci2, va2 = oracle.coo_to_csr(b2.rows, b2.cols, b2.nnz, b2.nz_off, ids2, vals2)
+    for i in range(b2.batch):
+        m, n, z, z0 = int(b2.rows[i]), int(b2.cols[i]), int(b2.nnz[i]), int(b2.nz_off[i])
+        L = sp.coo_matrix((vals2[z0:z0 + z], (ids2[2 * z0:2 * (z0 + z):2],
+                                              ids2[2 * z0 + 1:2 * (z0 + z):2])), shape=(m, n)).tocsr()
+        L.sort_indices()
+        o = int(off2[i])
+        mine = sp.csr_matrix((va2[z0:z0 + z], ci2[z0:z0 + z], rp2[o:o + m + 1]), shape=(m, n))
+        mine.sort_indices()
+        assert np.array_equal(mine.indptr, L.indptr)
+        assert np.array_equal(mine.indices, L.indices) and np.array_equal(mine.data, L.data)
+        # and sorting the shuffled view by column inside rows gives back the batch's CSR
+        rpt, cc, vv = b2.op_csr(i)
+        assert np.array_equal(mine.indptr, rpt) and np.array_equal(mine.indices, cc)
+        assert np.array_equal(mine.data, vv)
+
+
+def test_coo_rejects_out_of_range(oracle):
+    z = np.zeros(1, dtype=np.int64)
+    Bm = np.zeros((3, 2), dtype=np.float32)
+    for bad in ([3, 0], [0, 3], [-1, 0], [0, -1]):
+        with pytest.raises(ValueError):
+            oracle.coo_product([3], [3], [1], z, z, z, np.array(bad, dtype=np.int32),
+                               np.ones(1, dtype=np.float32), Bm, 3)
+        with pytest.raises(ValueError):
+            oracle.coo_to_csr([3], [3], [1], z, np.array(bad, dtype=np.int32),
+                              np.ones(1, dtype=np.float32))
