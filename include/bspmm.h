@@ -101,6 +101,25 @@ typedef struct bspmm_batch {
     const float*   values;     /* DEVICE values of all operations                              */
 } bspmm_batch;
 
+/*
+ * The same batch with COO / SparseTensor operands (Sec. II-B, Fig. 1: every stored entry is a
+ * (row, column) index pair plus a value; Sec. IV: the entries are sorted neither by row nor by
+ * column).  Operation i owns nnz[i] entries starting at entry nz_off[i]: pair p sits at
+ * ids[2*(nz_off[i]+p)] (row) and ids[2*(nz_off[i]+p)+1] (column), its value at
+ * values[nz_off[i]+p].  Repeated pairs are added up, as the loop nest of Fig. 2 does.
+ */
+typedef struct bspmm_coo_batch {
+    int32_t        batch;      /* number of SpMM operations, >= 0                              */
+    const int32_t* rows;       /* HOST [batch]  m_A of operation i                             */
+    const int32_t* cols;       /* HOST [batch]  n_A of operation i                             */
+    const int32_t* nnz;        /* HOST [batch]  stored entries of operation i                  */
+    const int64_t* nz_off;     /* HOST [batch]  entry offset of op i in ids (pairs) and values */
+    const int64_t* b_row_off;  /* HOST [batch]  first row of B_i in the packed dense input     */
+    const int64_t* c_row_off;  /* HOST [batch]  first row of C_i in the packed dense output    */
+    const int32_t* ids;        /* DEVICE (row, column) pairs of all operations                 */
+    const float*   values;     /* DEVICE values of all operations                              */
+} bspmm_coo_batch;
+
 /* Scheduler knobs.  Zero-initialise for defaults. */
 typedef struct bspmm_options {
     uint32_t flags;            /* BSPMM_DRY_RUN | BSPMM_BUILD_TRANSPOSE | BSPMM_SPLIT_HUB_ROWS */
@@ -203,9 +222,37 @@ int bspmm_export_transposed(bspmm_plan* plan, int32_t* rpt_t, int32_t* colids_t,
                             float* values_t, void* stream);
 
 /*
+ * Plans for COO / SparseTensor operands (the batched product of Sec. IV-C for the data
+ * structure of Fig. 1 / Fig. 3).  bspmm_create_coo enqueues ONE extra launch on `stream`
+ * that sorts every operation's entries by row into CSR arrays inside the workspace (stable:
+ * entries of a row keep their stored order; one workgroup per operation, counting sort in
+ * LDS); afterwards the plan behaves exactly like a CSR plan of those arrays: bspmm_run,
+ * bspmm_run_transposed, bspmm_export_transposed and every option work unchanged, without
+ * atomics on the output and with bitwise reproducible results.  ids / values must stay valid
+ * and unchanged until that launch has finished; they are not read afterwards.  Entries whose
+ * indices fall outside their matrix are left out of the product (bspmm_validate reports
+ * them).  Arguments, workspace rules and error codes are those of bspmm_workspace_bytes /
+ * bspmm_create.
+ */
+int bspmm_workspace_bytes_coo(const bspmm_coo_batch* b, int32_t F, const bspmm_options* options,
+                              size_t* bytes);
+int bspmm_create_coo(bspmm_plan** plan, const bspmm_coo_batch* b, int32_t F,
+                     const bspmm_options* options, void* workspace, size_t workspace_bytes,
+                     void* stream);
+
+/*
+ * Copy the CSR arrays a COO plan built into caller DEVICE arrays: rpt gets sum(rows_i+1) int32
+ * (op i at sum_{k<i}(rows_k+1), local), colids / values get sum(nnz_i) entries (op i at
+ * sum_{k<i} nnz_k).  ESTATE for plans not made by bspmm_create_coo.
+ */
+int bspmm_export_csr(bspmm_plan* plan, int32_t* rpt, int32_t* colids, float* values,
+                     void* stream);
+
+/*
  * Check the DEVICE CSR arrays against the HOST sizes given at creation: rpt[0]==0,
  * rpt non-decreasing, rpt[rows]==nnz, 0 <= colids < cols.  Launches one kernel and
  * SYNCHRONISES `stream`.  Returns OK or EBADCSR (*bad_op = first offending operation).
+ * For a COO plan the index pairs are checked instead (0 <= row < rows, 0 <= column < cols).
  */
 int bspmm_validate(bspmm_plan* plan, int32_t* bad_op, void* stream);
 

@@ -34,6 +34,13 @@ class bspmm_batch(ctypes.Structure):
                 ("values", ctypes.c_void_p)]
 
 
+class bspmm_coo_batch(ctypes.Structure):
+    _fields_ = [("batch", ctypes.c_int32),
+                ("rows", _i32p), ("cols", _i32p), ("nnz", _i32p),
+                ("nz_off", _i64p), ("b_row_off", _i64p), ("c_row_off", _i64p),
+                ("ids", ctypes.c_void_p), ("values", ctypes.c_void_p)]
+
+
 class bspmm_options(ctypes.Structure):
     _fields_ = [("flags", ctypes.c_uint32), ("force_bin", ctypes.c_int32),
                 ("lds_bytes", ctypes.c_int32), ("min_tile", ctypes.c_int32),
@@ -65,7 +72,8 @@ class bspmm_item(ctypes.Structure):
 
 EXPORTS = ["bspmm_workspace_bytes", "bspmm_create", "bspmm_run", "bspmm_run_transposed",
            "bspmm_export_transposed", "bspmm_validate", "bspmm_plan_info", "bspmm_plan_items",
-           "bspmm_destroy", "bspmm_strerror", "bspmm_last_hip_error"]
+           "bspmm_destroy", "bspmm_strerror", "bspmm_last_hip_error",
+           "bspmm_workspace_bytes_coo", "bspmm_create_coo", "bspmm_export_csr"]
 
 _lib = None
 
@@ -99,6 +107,13 @@ def lib():
         L.bspmm_run_transposed.argtypes = [vp, vp, vp, ctypes.c_int64, ctypes.c_int64, vp]
         L.bspmm_export_transposed.argtypes = [vp, vp, vp, vp, vp]
         L.bspmm_validate.argtypes = [vp, _i32p, vp]
+        L.bspmm_workspace_bytes_coo.argtypes = [ctypes.POINTER(bspmm_coo_batch), ctypes.c_int32,
+                                                ctypes.POINTER(bspmm_options),
+                                                ctypes.POINTER(ctypes.c_size_t)]
+        L.bspmm_create_coo.argtypes = [ctypes.POINTER(vp), ctypes.POINTER(bspmm_coo_batch),
+                                       ctypes.c_int32, ctypes.POINTER(bspmm_options), vp,
+                                       ctypes.c_size_t, vp]
+        L.bspmm_export_csr.argtypes = [vp, vp, vp, vp, vp]
         L.bspmm_plan_info.argtypes = [vp, ctypes.POINTER(bspmm_info)]
         L.bspmm_plan_items.argtypes = [vp, ctypes.c_int32, ctypes.POINTER(bspmm_item),
                                        ctypes.c_int32, _i32p]
@@ -176,6 +191,56 @@ class HostBatch:
         self.struct = s
 
 
+class HostCooBatch:
+    """Keeps the numpy metadata arrays alive and exposes them as a ``bspmm_coo_batch``."""
+
+    def __init__(self, rows, cols, nnz, nz_off, b_row_off, c_row_off, ids_dev=None,
+                 values_dev=None):
+        as_ = np.ascontiguousarray
+        self.arrays = [as_(rows, dtype=np.int32), as_(cols, dtype=np.int32),
+                       as_(nnz, dtype=np.int32), as_(nz_off, dtype=np.int64),
+                       as_(b_row_off, dtype=np.int64), as_(c_row_off, dtype=np.int64)]
+        self.device = (ids_dev, values_dev)
+        s = bspmm_coo_batch()
+        a = self.arrays
+        s.batch = int(a[0].shape[0])
+        s.rows = a[0].ctypes.data_as(_i32p)
+        s.cols = a[1].ctypes.data_as(_i32p)
+        s.nnz = a[2].ctypes.data_as(_i32p)
+        s.nz_off = a[3].ctypes.data_as(_i64p)
+        s.b_row_off = a[4].ctypes.data_as(_i64p)
+        s.c_row_off = a[5].ctypes.data_as(_i64p)
+        s.ids = _ptr(ids_dev)
+        s.values = _ptr(values_dev)
+        self.struct = s
+
+
+def bspmm_workspace_bytes_coo(hb: HostCooBatch, F: int,
+                              options: Optional[bspmm_options] = None) -> int:
+    out = ctypes.c_size_t(0)
+    _check(lib().bspmm_workspace_bytes_coo(ctypes.byref(hb.struct), int(F),
+                                           ctypes.byref(options) if options is not None else None,
+                                           ctypes.byref(out)), "bspmm_workspace_bytes_coo")
+    return int(out.value)
+
+
+def bspmm_create_coo(hb: HostCooBatch, F: int, options: Optional[bspmm_options] = None,
+                     workspace=None, workspace_bytes: int = 0, stream=None) -> int:
+    """Returns the opaque plan handle (an integer address)."""
+    plan = ctypes.c_void_p(None)
+    dry = options is not None and (options.flags & DRY_RUN)
+    _check(lib().bspmm_create_coo(ctypes.byref(plan), ctypes.byref(hb.struct), int(F),
+                                  ctypes.byref(options) if options is not None else None,
+                                  _ptr(workspace), int(workspace_bytes),
+                                  None if dry else _stream_handle(stream)), "bspmm_create_coo")
+    return plan.value
+
+
+def bspmm_export_csr(plan: int, rpt, colids, values, stream=None) -> None:
+    _check(lib().bspmm_export_csr(plan, _ptr(rpt), _ptr(colids), _ptr(values),
+                                  _stream_handle(stream)), "bspmm_export_csr")
+
+
 def bspmm_workspace_bytes(hb: HostBatch, F: int, options: Optional[bspmm_options] = None) -> int:
     out = ctypes.c_size_t(0)
     _check(lib().bspmm_workspace_bytes(ctypes.byref(hb.struct), int(F),
@@ -250,12 +315,31 @@ class Plan:
     """
 
     def __init__(self, batch, F: Optional[int] = None, options: Optional[bspmm_options] = None,
-                 device="cuda:0", stream=None):
+                 device="cuda:0", stream=None, coo=None):
         import torch
         self.torch = torch
         self.F = int(F if F is not None else batch.F)
         self.device = torch.device(device)
         dev = self.device
+        self.options = options
+        self.rpt_len = int((np.asarray(batch.rows, dtype=np.int64) + 1).sum())
+        self.rpt_t_len = int((np.asarray(batch.cols, dtype=np.int64) + 1).sum())
+        self.nnz_total = int(np.asarray(batch.nnz, dtype=np.int64).sum())
+        if coo is not None:
+            # COO / SparseTensor operands: ``coo`` = (ids, values) numpy arrays laid out by the
+            # batch's nz_off; the batch's own CSR arrays are not used
+            ids, vals = coo
+            self.ids = torch.from_numpy(np.ascontiguousarray(ids, dtype=np.int32)).to(dev)
+            self.values = torch.from_numpy(np.ascontiguousarray(vals, dtype=np.float32)).to(dev)
+            self.hb = HostCooBatch(batch.rows, batch.cols, batch.nnz, batch.nz_off,
+                                   batch.b_row_off, batch.c_row_off,
+                                   self.ids if self.ids.numel() else None,
+                                   self.values if self.values.numel() else None)
+            nbytes = bspmm_workspace_bytes_coo(self.hb, self.F, options)
+            self.workspace = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=dev)
+            assert self.workspace.data_ptr() % 256 == 0
+            self.handle = bspmm_create_coo(self.hb, self.F, options, self.workspace, nbytes, stream)
+            return
         self.rpt = torch.from_numpy(np.ascontiguousarray(batch.rpt, dtype=np.int32)).to(dev)
         self.colids = torch.from_numpy(np.ascontiguousarray(batch.colids, dtype=np.int32)).to(dev)
         self.values = torch.from_numpy(np.ascontiguousarray(batch.values, dtype=np.float32)).to(dev)
@@ -266,13 +350,10 @@ class Plan:
                             batch.b_row_off, batch.c_row_off, self.rpt,
                             self.colids if self.colids.numel() else None,
                             self.values if self.values.numel() else None)
-        self.options = options
         nbytes = bspmm_workspace_bytes(self.hb, self.F, options)
         self.workspace = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=dev)
         assert self.workspace.data_ptr() % 256 == 0
         self.handle = bspmm_create(self.hb, self.F, options, self.workspace, nbytes, stream)
-        self.rpt_t_len = int((np.asarray(batch.cols, dtype=np.int64) + 1).sum())
-        self.nnz_total = int(np.asarray(batch.nnz, dtype=np.int64).sum())
 
     def run(self, B, C, stream=None):
         bspmm_run(self.handle, B, C, B.stride(0) if B.dim() == 2 else self.F,
@@ -290,6 +371,15 @@ class Plan:
         val_t = t.empty(max(self.nnz_total, 1), dtype=t.float32, device=self.device)
         bspmm_export_transposed(self.handle, rpt_t, col_t, val_t, stream)
         return rpt_t[:self.rpt_t_len], col_t[:self.nnz_total], val_t[:self.nnz_total]
+
+    def export_csr(self, stream=None):
+        """CSR arrays a COO plan built on the device (rpt, colids, values)."""
+        t = self.torch
+        rpt = t.empty(max(self.rpt_len, 1), dtype=t.int32, device=self.device)
+        col = t.empty(max(self.nnz_total, 1), dtype=t.int32, device=self.device)
+        val = t.empty(max(self.nnz_total, 1), dtype=t.float32, device=self.device)
+        bspmm_export_csr(self.handle, rpt, col, val, stream)
+        return rpt[:self.rpt_len], col[:self.nnz_total], val[:self.nnz_total]
 
     def validate(self, stream=None) -> int:
         return bspmm_validate(self.handle, stream)
@@ -316,7 +406,12 @@ def dry_plan(batch, F: Optional[int] = None, **option_kw) -> int:
     """Schedule-only plan (no device needed); free it with bspmm_destroy."""
     kw = dict(option_kw)
     flags = kw.pop("flags", 0) | DRY_RUN
+    coo = kw.pop("coo", False)
     opts = make_options(flags=flags, **kw)
+    if coo:
+        hc = HostCooBatch(batch.rows, batch.cols, batch.nnz, batch.nz_off, batch.b_row_off,
+                          batch.c_row_off)
+        return bspmm_create_coo(hc, int(F if F is not None else batch.F), opts)
     hb = HostBatch(batch.rows, batch.cols, batch.nnz, batch.rpt_off, batch.nz_off,
                    batch.b_row_off, batch.c_row_off)
     return bspmm_create(hb, int(F if F is not None else batch.F), opts)

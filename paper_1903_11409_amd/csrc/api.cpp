@@ -19,6 +19,11 @@ hipError_t launch_build_transpose(const OpRecord* ops, int batch, int lds_bytes,
                                   const int32_t* rpt, const int32_t* colids,
                                   const float* values, int32_t* rpt_t, int32_t* colids_t,
                                   float* values_t, int32_t* gscratch, hipStream_t stream);
+hipError_t launch_build_from_coo(const OpRecord* ops, int batch, int lds_bytes, const int32_t* ids,
+                                 const float* values, int32_t* rpt, int32_t* colids,
+                                 float* csr_values, int32_t* gscratch, hipStream_t stream);
+hipError_t launch_validate_coo(const OpRecord* ops, int batch, const int32_t* ids, int32_t* flag,
+                               hipStream_t stream);
 int bspmm_max_resident_workgroups(int lds_bytes, bool slices, bool hubs);
 hipError_t launch_validate(const OpRecord* ops, int batch, const int32_t* rpt,
                            const int32_t* colids, int32_t* flag, hipStream_t stream);
@@ -51,6 +56,10 @@ struct Layout {
     size_t rpt_t = 0, colids_t = 0, values_t = 0;
     size_t scratch = 0;
     size_t flag = 0;
+    // plans made from COO operands: the CSR arrays built on the device and what the build needs
+    size_t coo_records = 0;
+    size_t csr_rpt = 0, csr_colids = 0, csr_values = 0;
+    size_t coo_scratch = 0;
     size_t total = 0;
 };
 
@@ -76,6 +85,13 @@ struct bspmm_plan {
     const int32_t* colids = nullptr;
     const float* values = nullptr;
     char* ws = nullptr;
+    // COO / SparseTensor input: borrowed pair array and values, records of the conversion
+    bool from_coo = false;
+    const int32_t* ids = nullptr;
+    const float* coo_values = nullptr;
+    std::vector<OpRecord> coo_records;
+    int coo_build_lds_bytes = 0;
+    int64_t csr_rpt_words = 0, csr_nz = 0, coo_scratch_words = 0;
 };
 
 namespace {
@@ -312,6 +328,134 @@ int run_direction(bspmm_plan* p, int d, const float* in, float* out, int64_t ld_
     return e == hipSuccess ? BSPMM_OK : hip_fail(e);
 }
 
+int check_coo_batch(const bspmm_coo_batch* b, int32_t F, bool need_device)
+{
+    if (!b || F <= 0 || b->batch < 0) return BSPMM_EINVAL;
+    if (b->batch == 0) return BSPMM_OK;
+    if (!b->rows || !b->cols || !b->nnz || !b->nz_off || !b->b_row_off || !b->c_row_off)
+        return BSPMM_EINVAL;
+    int64_t total_nnz = 0;
+    for (int i = 0; i < b->batch; ++i) {
+        if (b->rows[i] < 0 || b->cols[i] < 0 || b->nnz[i] < 0) return BSPMM_EINVAL;
+        if (b->nz_off[i] < 0 || b->b_row_off[i] < 0 || b->c_row_off[i] < 0) return BSPMM_EINVAL;
+        if ((b->rows[i] == 0 || b->cols[i] == 0) && b->nnz[i] != 0) return BSPMM_EINVAL;
+        total_nnz += b->nnz[i];
+    }
+    if (need_device && total_nnz > 0 && (!b->ids || !b->values)) return BSPMM_EINVAL;
+    return BSPMM_OK;
+}
+
+// Plan for COO operands: the CSR arrays (row pointers and entries packed back to back in
+// operation order) are built inside the workspace, and everything else is the CSR plan of them.
+int plan_host_coo(bspmm_plan& p, const bspmm_coo_batch* b, int32_t F, const Knobs& kn)
+{
+    const int n = b->batch;
+    std::vector<int64_t> rpt_off(n), nz_pack(n);
+    int64_t rpt_words = 0, nz = 0, scratch_words = 0, lds_words = 0;
+    p.coo_records.resize(n);
+    for (int i = 0; i < n; ++i) {
+        rpt_off[i] = rpt_words;
+        nz_pack[i] = nz;
+        OpRecord& r = p.coo_records[i];
+        r.rpt_off = 0;
+        r.nz_off = b->nz_off[i];          // where the caller's pairs and values sit
+        r.rpt_t_off = rpt_words;          // where the built row pointers go
+        r.nz_t_off = nz;                  // where the built entries go
+        r.m = b->cols[i];                 // bound of the payload (column)
+        r.k = b->rows[i];                 // number of keys (rows)
+        r.nnz = b->nnz[i];
+        r.pad_ = 0;
+        const int64_t work = (int64_t)b->rows[i] + 1 + b->nnz[i];
+        if (work * 4 <= kMaxLdsBytes - 2048) {
+            r.scratch_off = -1;
+            lds_words = std::max(lds_words, work);
+        } else {
+            r.scratch_off = scratch_words;
+            scratch_words += work;
+        }
+        rpt_words += (int64_t)b->rows[i] + 1;
+        nz += b->nnz[i];
+    }
+    bspmm_batch ib;
+    ib.batch = n;
+    ib.rows = b->rows;
+    ib.cols = b->cols;
+    ib.nnz = b->nnz;
+    ib.rpt_off = rpt_off.data();
+    ib.nz_off = nz_pack.data();
+    ib.b_row_off = b->b_row_off;
+    ib.c_row_off = b->c_row_off;
+    ib.rpt = nullptr;
+    ib.colids = nullptr;
+    ib.values = nullptr;
+    const int rc = plan_host(p, &ib, F, kn);
+    if (rc != BSPMM_OK) return rc;
+    p.from_coo = true;
+    p.coo_build_lds_bytes = (int)round_up(lds_words * 4 + 16, 256);
+    p.csr_rpt_words = rpt_words;
+    p.csr_nz = nz;
+    p.coo_scratch_words = scratch_words;
+    Layout& L = p.lay;
+    size_t at = L.total;
+    L.coo_records = at;
+    at = align_up(at + (size_t)n * sizeof(OpRecord));
+    L.csr_rpt = at;
+    at = align_up(at + (size_t)rpt_words * 4);
+    L.csr_colids = at;
+    at = align_up(at + (size_t)nz * 4);
+    L.csr_values = at;
+    at = align_up(at + (size_t)nz * 4);
+    L.coo_scratch = at;
+    at = align_up(at + (size_t)scratch_words * 4);
+    L.total = at;
+    return BSPMM_OK;
+}
+
+// Device half of plan creation: tables to the workspace, conversions enqueued on `s`.
+int upload_plan(bspmm_plan* p, const bspmm_options* options, void* workspace,
+                size_t workspace_bytes, hipStream_t s)
+{
+    if (options && (options->flags & BSPMM_FLOOR_PROBE))
+        for (int d = 0; d < 2; ++d)
+            for (WorkItem& w : p->sched[d].items) w.nrows = 0;
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & (kAlign - 1)) != 0)
+        return BSPMM_EINVAL;
+    if (workspace_bytes < p->lay.total) return BSPMM_ENOSPACE;
+    p->ws = static_cast<char*>(workspace);
+    // The host tables stay alive inside the plan, so the asynchronous copies may read them
+    // at any time before bspmm_destroy.
+    hipError_t e = hipSuccess;
+    for (int d = 0; d < 2 && e == hipSuccess; ++d)
+        if (!p->sched[d].items.empty())
+            e = hipMemcpyAsync(p->ws + p->lay.items[d], p->sched[d].items.data(),
+                               p->sched[d].items.size() * sizeof(WorkItem),
+                               hipMemcpyHostToDevice, s);
+    if (e == hipSuccess && !p->records.empty())
+        e = hipMemcpyAsync(p->ws + p->lay.op_records, p->records.data(),
+                           p->records.size() * sizeof(OpRecord), hipMemcpyHostToDevice, s);
+    if (e == hipSuccess && p->from_coo) {
+        int32_t* rpt = reinterpret_cast<int32_t*>(p->ws + p->lay.csr_rpt);
+        int32_t* colids = reinterpret_cast<int32_t*>(p->ws + p->lay.csr_colids);
+        float* values = reinterpret_cast<float*>(p->ws + p->lay.csr_values);
+        p->rpt = rpt;
+        p->colids = colids;
+        p->values = values;
+        if (!p->coo_records.empty()) {
+            e = hipMemcpyAsync(p->ws + p->lay.coo_records, p->coo_records.data(),
+                               p->coo_records.size() * sizeof(OpRecord), hipMemcpyHostToDevice, s);
+            if (e == hipSuccess)
+                e = launch_build_from_coo(
+                    reinterpret_cast<const OpRecord*>(p->ws + p->lay.coo_records), p->batch,
+                    p->coo_build_lds_bytes, p->ids, p->coo_values, rpt, colids, values,
+                    reinterpret_cast<int32_t*>(p->ws + p->lay.coo_scratch), s);
+        }
+    }
+    if (e != hipSuccess) return hip_fail(e);
+    if (options && (options->flags & BSPMM_BUILD_TRANSPOSE) && p->transposed_supported)
+        return enqueue_build(p, s);
+    return BSPMM_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -345,54 +489,80 @@ int bspmm_create(bspmm_plan** plan, const bspmm_batch* b, int32_t F,
     if (!p) return BSPMM_EINVAL;
     p->dry = dry;
     rc = plan_host(*p, b, F, knobs_for(options, !dry));
+    if (rc == BSPMM_OK && !dry) {
+        p->rpt = b->rpt;
+        p->colids = b->colids;
+        p->values = b->values;
+        rc = upload_plan(p, options, workspace, workspace_bytes, static_cast<hipStream_t>(stream));
+    }
     if (rc != BSPMM_OK) {
         delete p;
         return rc;
     }
-    if (dry) {
-        *plan = p;
-        return BSPMM_OK;
+    *plan = p;
+    return BSPMM_OK;
+}
+
+int bspmm_workspace_bytes_coo(const bspmm_coo_batch* b, int32_t F, const bspmm_options* options,
+                              size_t* bytes)
+{
+    if (!bytes) return BSPMM_EINVAL;
+    *bytes = 0;
+    int rc = check_coo_batch(b, F, false);
+    if (rc != BSPMM_OK) return rc;
+    bspmm_plan* p = new (std::nothrow) bspmm_plan;
+    if (!p) return BSPMM_EINVAL;
+    const bool dry = options && (options->flags & BSPMM_DRY_RUN);
+    rc = plan_host_coo(*p, b, F, knobs_for(options, !dry));
+    if (rc == BSPMM_OK) *bytes = p->lay.total;
+    delete p;
+    return rc;
+}
+
+int bspmm_create_coo(bspmm_plan** plan, const bspmm_coo_batch* b, int32_t F,
+                     const bspmm_options* options, void* workspace, size_t workspace_bytes,
+                     void* stream)
+{
+    if (!plan) return BSPMM_EINVAL;
+    *plan = nullptr;
+    const bool dry = options && (options->flags & BSPMM_DRY_RUN);
+    int rc = check_coo_batch(b, F, !dry);
+    if (rc != BSPMM_OK) return rc;
+    bspmm_plan* p = new (std::nothrow) bspmm_plan;
+    if (!p) return BSPMM_EINVAL;
+    p->dry = dry;
+    rc = plan_host_coo(*p, b, F, knobs_for(options, !dry));
+    if (rc == BSPMM_OK && !dry) {
+        p->ids = b->ids;
+        p->coo_values = b->values;
+        rc = upload_plan(p, options, workspace, workspace_bytes, static_cast<hipStream_t>(stream));
     }
-    if (options && (options->flags & BSPMM_FLOOR_PROBE))
-        for (int d = 0; d < 2; ++d)
-            for (WorkItem& w : p->sched[d].items) w.nrows = 0;
-    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & (kAlign - 1)) != 0) {
+    if (rc != BSPMM_OK) {
         delete p;
-        return BSPMM_EINVAL;
-    }
-    if (workspace_bytes < p->lay.total) {
-        delete p;
-        return BSPMM_ENOSPACE;
-    }
-    p->rpt = b->rpt;
-    p->colids = b->colids;
-    p->values = b->values;
-    p->ws = static_cast<char*>(workspace);
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    // The host tables stay alive inside the plan, so the asynchronous copies may read them
-    // at any time before bspmm_destroy.
-    hipError_t e = hipSuccess;
-    for (int d = 0; d < 2 && e == hipSuccess; ++d)
-        if (!p->sched[d].items.empty())
-            e = hipMemcpyAsync(p->ws + p->lay.items[d], p->sched[d].items.data(),
-                               p->sched[d].items.size() * sizeof(WorkItem),
-                               hipMemcpyHostToDevice, s);
-    if (e == hipSuccess && !p->records.empty())
-        e = hipMemcpyAsync(p->ws + p->lay.op_records, p->records.data(),
-                           p->records.size() * sizeof(OpRecord), hipMemcpyHostToDevice, s);
-    if (e != hipSuccess) {
-        delete p;
-        return hip_fail(e);
-    }
-    if (options && (options->flags & BSPMM_BUILD_TRANSPOSE) && p->transposed_supported) {
-        rc = enqueue_build(p, s);
-        if (rc != BSPMM_OK) {
-            delete p;
-            return rc;
-        }
+        return rc;
     }
     *plan = p;
     return BSPMM_OK;
+}
+
+int bspmm_export_csr(bspmm_plan* plan, int32_t* rpt, int32_t* colids, float* values, void* stream)
+{
+    if (!plan) return BSPMM_EINVAL;
+    if (plan->dry || !plan->from_coo) return BSPMM_ESTATE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipError_t e = hipSuccess;
+    if (plan->csr_rpt_words) {
+        if (!rpt) return BSPMM_EINVAL;
+        e = hipMemcpyAsync(rpt, plan->rpt, (size_t)plan->csr_rpt_words * 4, hipMemcpyDeviceToDevice, s);
+    }
+    if (e == hipSuccess && plan->csr_nz) {
+        if (!colids || !values) return BSPMM_EINVAL;
+        e = hipMemcpyAsync(colids, plan->colids, (size_t)plan->csr_nz * 4, hipMemcpyDeviceToDevice, s);
+        if (e == hipSuccess)
+            e = hipMemcpyAsync(values, plan->values, (size_t)plan->csr_nz * 4,
+                               hipMemcpyDeviceToDevice, s);
+    }
+    return e == hipSuccess ? BSPMM_OK : hip_fail(e);
 }
 
 int bspmm_run(bspmm_plan* plan, const float* B, float* C, int64_t ldb, int64_t ldc,
@@ -452,8 +622,11 @@ int bspmm_validate(bspmm_plan* plan, int32_t* bad_op, void* stream)
     if (bad_op) *bad_op = -1;
     hipStream_t s = static_cast<hipStream_t>(stream);
     int32_t* flag = reinterpret_cast<int32_t*>(plan->ws + plan->lay.flag);
-    hipError_t e = launch_validate(reinterpret_cast<const OpRecord*>(plan->ws + plan->lay.op_records),
-                                   plan->batch, plan->rpt, plan->colids, flag, s);
+    hipError_t e = plan->from_coo
+        ? launch_validate_coo(reinterpret_cast<const OpRecord*>(plan->ws + plan->lay.coo_records),
+                              plan->batch, plan->ids, flag, s)
+        : launch_validate(reinterpret_cast<const OpRecord*>(plan->ws + plan->lay.op_records),
+                          plan->batch, plan->rpt, plan->colids, flag, s);
     if (e != hipSuccess) return hip_fail(e);
     int32_t host_flag = 0;
     e = hipMemcpyAsync(&host_flag, flag, 4, hipMemcpyDeviceToHost, s);

@@ -6,7 +6,8 @@
 //                   output row a group of lanes that accumulates its stored entries in
 //                   registers and writes the row once (the row-wise, atomic-free product of
 //                   Fig. 4, batched as in Sec. IV-C, with the column blocking of Fig. 5(d)).
-// build_transpose   stable CSR -> transposed CSR of every operation (counting sort by column).
+// build_sorted      stable CSR -> transposed CSR of every operation (counting sort by column),
+//                   and COO / SparseTensor -> CSR (the same sort by row).
 // validate_csr      structural check of the device CSR arrays.
 #include <hip/hip_runtime.h>
 
@@ -749,11 +750,17 @@ __global__ void __launch_bounds__(kThreads) bspmm_kernel(const LaunchParams P)
 // `work` is k+1 counters followed by nnz positions, in LDS when it fits, else in global
 // scratch (both reached through flat addressing).
 // ---------------------------------------------------------------------------------------
+// FROM_COO = true sorts a SparseTensor / COO operation (index pairs as in Fig. 2:
+// ids[2p] = row, ids[2p+1] = column, in any order) into CSR with the same machinery: the key is
+// the row, the payload the column; `colids` is then the pair array, o.k the number of rows,
+// o.m the number of columns, and the result is the stable sort by row (entries of a row keep
+// their stored order).
+template <bool FROM_COO>
 __global__ void __launch_bounds__(kThreads)
-build_transpose_kernel(const OpRecord* __restrict__ ops, const int32_t* __restrict__ rpt,
-                       const int32_t* __restrict__ colids, const float* __restrict__ values,
-                       int32_t* __restrict__ rpt_t, int32_t* __restrict__ colids_t,
-                       float* __restrict__ values_t, int32_t* gscratch)
+build_sorted_kernel(const OpRecord* __restrict__ ops, const int32_t* __restrict__ rpt,
+                    const int32_t* __restrict__ colids, const float* __restrict__ values,
+                    int32_t* __restrict__ rpt_t, int32_t* __restrict__ colids_t,
+                    float* __restrict__ values_t, int32_t* gscratch)
 {
     extern __shared__ __align__(16) int sm[];
     __shared__ int partial[kThreads];
@@ -762,15 +769,24 @@ build_transpose_kernel(const OpRecord* __restrict__ ops, const int32_t* __restri
     const int k = o.k, m = o.m, nnz = o.nnz;
     int* cnt = o.scratch_off >= 0 ? gscratch + o.scratch_off : sm;   // k+1 ints
     int* pos = cnt + (k + 1);                                          // nnz ints
-    const int32_t* ci = colids + o.nz_off;
+    const int32_t* ci = colids + (FROM_COO ? 2 * o.nz_off : o.nz_off);
     const int32_t* rp = rpt + o.rpt_off;
     int32_t* rt = rpt_t + o.rpt_t_off;
+    // key of entry p, or -1 when the entry is malformed and must be skipped
+    auto key_of = [&](int p) {
+        if (FROM_COO) {
+            const int r = ci[2 * p], c = ci[2 * p + 1];
+            return ((unsigned)r < (unsigned)k && (unsigned)c < (unsigned)m) ? r : -1;
+        }
+        const int c = ci[p];
+        return (unsigned)c < (unsigned)k ? c : -1;
+    };
 
     for (int c = tid; c <= k; c += kThreads) cnt[c] = 0;
     __syncthreads();
     for (int p = tid; p < nnz; p += kThreads) {
-        const int c = ci[p];
-        if ((unsigned)c < (unsigned)k) atomicAdd(&cnt[c + 1], 1);
+        const int c = key_of(p);
+        if (c >= 0) atomicAdd(&cnt[c + 1], 1);
     }
     __syncthreads();
 
@@ -798,28 +814,47 @@ build_transpose_kernel(const OpRecord* __restrict__ ops, const int32_t* __restri
 
     // scatter positions; cnt[c] ends as the first position of column c+1
     for (int p = tid; p < nnz; p += kThreads) {
-        const int c = ci[p];
-        if ((unsigned)c < (unsigned)k) pos[atomicAdd(&cnt[c], 1)] = p;
+        const int c = key_of(p);
+        if (c >= 0) pos[atomicAdd(&cnt[c], 1)] = p;
     }
     __syncthreads();
 
     const float* va = values + o.nz_off;
-    for (int q = tid; q < nnz; q += kThreads) {
+    const int placed = cnt[k];                      // entries that were not skipped
+    for (int q = tid; q < placed; q += kThreads) {
         const int p = pos[q];
-        const int c = ci[p];
+        const int c = key_of(p);
         const int beg = c > 0 ? cnt[c - 1] : 0;
         const int end = cnt[c];
         int rank = 0;
         for (int t = beg; t < end; ++t) rank += pos[t] < p ? 1 : 0;
-        // row of entry p: the last r with rp[r] <= p
-        int a = 0, b = m;   // invariant: rp[a] <= p, and (b == m or rp[b] > p) ... search (a, b]
-        while (b - a > 1) {
-            const int mid = (a + b) >> 1;
-            if (rp[mid] <= p) a = mid; else b = mid;
+        int a;
+        if (FROM_COO) {
+            a = ci[2 * p + 1];                        // the payload is the column
+        } else {
+            // row of entry p: the last r with rp[r] <= p
+            a = 0;
+            int b = m;   // invariant: rp[a] <= p, and (b == m or rp[b] > p)
+            while (b - a > 1) {
+                const int mid = (a + b) >> 1;
+                if (rp[mid] <= p) a = mid; else b = mid;
+            }
         }
         colids_t[o.nz_t_off + beg + rank] = a;
         values_t[o.nz_t_off + beg + rank] = va[p];
     }
+}
+
+// Index pairs of a COO operation inside their matrix?
+__global__ void __launch_bounds__(kThreads)
+validate_coo_kernel(const OpRecord* __restrict__ ops, const int32_t* __restrict__ ids, int32_t* flag)
+{
+    const OpRecord o = ops[blockIdx.x];
+    const int32_t* id = ids + 2 * o.nz_off;
+    bool bad = false;
+    for (int p = threadIdx.x; p < o.nnz; p += kThreads)
+        if ((unsigned)id[2 * p] >= (unsigned)o.k || (unsigned)id[2 * p + 1] >= (unsigned)o.m) bad = true;
+    if (bad) atomicMin(flag, (int)blockIdx.x);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -902,8 +937,29 @@ hipError_t launch_build_transpose(const OpRecord* ops, int batch, int lds_bytes,
                                   float* values_t, int32_t* gscratch, hipStream_t stream)
 {
     if (batch <= 0) return hipSuccess;
-    hipLaunchKernelGGL(build_transpose_kernel, dim3(batch), dim3(kThreads), lds_bytes, stream,
+    hipLaunchKernelGGL(build_sorted_kernel<false>, dim3(batch), dim3(kThreads), lds_bytes, stream,
                        ops, rpt, colids, values, rpt_t, colids_t, values_t, gscratch);
+    return hipGetLastError();
+}
+
+// COO (index pairs `ids`, values) -> CSR arrays of every operation.
+hipError_t launch_build_from_coo(const OpRecord* ops, int batch, int lds_bytes, const int32_t* ids,
+                                 const float* values, int32_t* rpt, int32_t* colids,
+                                 float* csr_values, int32_t* gscratch, hipStream_t stream)
+{
+    if (batch <= 0) return hipSuccess;
+    hipLaunchKernelGGL(build_sorted_kernel<true>, dim3(batch), dim3(kThreads), lds_bytes, stream,
+                       ops, static_cast<const int32_t*>(nullptr), ids, values, rpt, colids,
+                       csr_values, gscratch);
+    return hipGetLastError();
+}
+
+hipError_t launch_validate_coo(const OpRecord* ops, int batch, const int32_t* ids, int32_t* flag,
+                               hipStream_t stream)
+{
+    hipLaunchKernelGGL(fill_i32_kernel, dim3(1), dim3(64), 0, stream, flag, 0x7fffffff, 1);
+    if (batch > 0)
+        hipLaunchKernelGGL(validate_coo_kernel, dim3(batch), dim3(kThreads), 0, stream, ops, ids, flag);
     return hipGetLastError();
 }
 

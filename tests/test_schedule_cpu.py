@@ -303,3 +303,62 @@ def test_summed_operations_need_the_flag_and_must_fit():
     with pytest.raises(K.BspmmError) as e:
         K.bspmm_create(hb, 64, K.make_options(flags=K.DRY_RUN | K.ACCUMULATE))
     assert e.value.code == K.EOVERLAP
+
+
+# ---------------------------------------------------------------------------------------------
+# COO / SparseTensor plans: the schedule is the CSR plan's; the workspace also holds the CSR
+# ---------------------------------------------------------------------------------------------
+def test_coo_struct_size():
+    assert ctypes.sizeof(K.bspmm_coo_batch) == 8 + 8 * 8
+
+
+@pytest.mark.parametrize("maker", [lambda: W.config2_molecule(graphs=64, F=128),
+                                   lambda: W.config5_skewed(graphs=32, F=64),
+                                   lambda: W.random_general(5, F=20, shapes=[(7, 13, 25), (0, 0, 0),
+                                                                             (40, 3, 70)])])
+def test_coo_plan_schedules_like_the_csr_plan(maker):
+    b = maker()
+    hc = K.dry_plan(b, coo=True)
+    h = K.dry_plan(b)
+    try:
+        for t in (False, True):
+            a = [(i.op, i.bin, i.row0, i.nrows, i.f0, i.fw, i.workgroup, i.slot)
+                 for i in K.bspmm_plan_items(hc, t)]
+            c = [(i.op, i.bin, i.row0, i.nrows, i.f0, i.fw, i.workgroup, i.slot)
+                 for i in K.bspmm_plan_items(h, t)]
+            assert a == c
+        ic, i0 = K.bspmm_plan_info(hc), K.bspmm_plan_info(h)
+        assert ic.flops == i0.flops and list(ic.effective_bytes) == list(i0.effective_bytes)
+        # room for the built CSR: row pointers, column indices and values
+        extra = 4 * int((b.rows.astype(np.int64) + 1).sum()) + 8 * int(b.nnz.sum())
+        assert ic.workspace_bytes >= i0.workspace_bytes + extra
+        hb = K.HostCooBatch(b.rows, b.cols, b.nnz, b.nz_off, b.b_row_off, b.c_row_off)
+        assert K.bspmm_workspace_bytes_coo(hb, b.F, K.make_options(flags=K.DRY_RUN)) == ic.workspace_bytes
+    finally:
+        K.bspmm_destroy(hc)
+        K.bspmm_destroy(h)
+
+
+def test_coo_argument_errors():
+    b = W.config1_tiny()
+    opts = K.make_options(flags=K.DRY_RUN)
+    good = K.HostCooBatch(b.rows, b.cols, b.nnz, b.nz_off, b.b_row_off, b.c_row_off)
+    with pytest.raises(K.BspmmError) as e:
+        K.bspmm_create_coo(good, 0, opts)
+    assert e.value.code == K.EINVAL
+    neg = K.HostCooBatch(b.rows, b.cols, -b.nnz, b.nz_off, b.b_row_off, b.c_row_off)
+    with pytest.raises(K.BspmmError) as e:
+        K.bspmm_create_coo(neg, b.F, opts)
+    assert e.value.code == K.EINVAL
+    same_c = K.HostCooBatch(b.rows, b.cols, b.nnz, b.nz_off, b.b_row_off, np.zeros_like(b.c_row_off))
+    with pytest.raises(K.BspmmError) as e:
+        K.bspmm_create_coo(same_c, b.F, opts)
+    assert e.value.code == K.EOVERLAP
+    h = K.bspmm_create_coo(good, b.F, opts)
+    try:   # a dry plan has nothing on the device to export
+        rc = K.lib().bspmm_export_csr(h, None, None, None, None)
+        assert rc == K.ESTATE
+    finally:
+        K.bspmm_destroy(h)
+    raw = K.lib()
+    assert raw.bspmm_workspace_bytes_coo(None, 8, None, ctypes.byref(ctypes.c_size_t())) == K.EINVAL
