@@ -73,6 +73,16 @@ extern "C" {
                                       of being rejected as overlapping.  Applies to C blocks in
                                       bspmm_run and to B blocks (input gradients) in
                                       bspmm_run_transposed                                       */
+#define BSPMM_COO_DIRECT       32u  /* bspmm_create_coo only: no conversion to CSR.  Every run is one
+                                      launch of the kernel of Fig. 3 / Fig. 5(a,b): a group of lanes
+                                      per stored entry, products added with LDS floating-point
+                                      atomics into an output tile kept in LDS, column blocking
+                                      when the tile does not fit.  Cheapest when a batch is
+                                      multiplied once or twice; the order of the additions, and
+                                      with it the last bits of the result, vary from run to run.
+                                      The transposed product needs no build (the index roles
+                                      swap).  Not combined with BSPMM_ACCUMULATE or
+                                      BSPMM_SPLIT_HUB_ROWS (EINVAL)                              */
 #define BSPMM_FLOOR_PROBE      4u  /* measurement aid: same grid, LDS and item fetches, but every
                                       item is emptied, so a run computes and writes nothing      */
 
@@ -83,6 +93,7 @@ extern "C" {
 #define BSPMM_BIN_SLICE16   3  /* a quarter wavefront, staged                                 */
 #define BSPMM_BIN_GENERIC   4  /* 256 lanes on a row block, operands read from global memory  */
 #define BSPMM_NUM_BINS      5
+#define BSPMM_BIN_COO       5  /* items of a BSPMM_COO_DIRECT plan (not counted in items_in_bin) */
 
 typedef struct bspmm_plan bspmm_plan;
 
@@ -232,7 +243,9 @@ int bspmm_export_transposed(bspmm_plan* plan, int32_t* rpt_t, int32_t* colids_t,
  * and unchanged until that launch has finished; they are not read afterwards.  Entries whose
  * indices fall outside their matrix are left out of the product (bspmm_validate reports
  * them).  Arguments, workspace rules and error codes are those of bspmm_workspace_bytes /
- * bspmm_create.
+ * bspmm_create.  With BSPMM_COO_DIRECT nothing is converted: ids / values are read by every
+ * run and must stay valid for the life of the plan, bspmm_export_csr and
+ * bspmm_export_transposed return ESTATE, and out-of-range entries are skipped by the kernel.
  */
 int bspmm_workspace_bytes_coo(const bspmm_coo_batch* b, int32_t F, const bspmm_options* options,
                               size_t* bytes);

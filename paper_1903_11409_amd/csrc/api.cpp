@@ -22,6 +22,8 @@ hipError_t launch_build_transpose(const OpRecord* ops, int batch, int lds_bytes,
 hipError_t launch_build_from_coo(const OpRecord* ops, int batch, int lds_bytes, const int32_t* ids,
                                  const float* values, int32_t* rpt, int32_t* colids,
                                  float* csr_values, int32_t* gscratch, hipStream_t stream);
+hipError_t launch_bspmm_coo(const CooLaunchParams& P, int grid, int lds_bytes, bool vec4,
+                            hipStream_t stream);
 hipError_t launch_validate_coo(const OpRecord* ops, int batch, const int32_t* ids, int32_t* flag,
                                hipStream_t stream);
 int bspmm_max_resident_workgroups(int lds_bytes, bool slices, bool hubs);
@@ -92,6 +94,9 @@ struct bspmm_plan {
     std::vector<OpRecord> coo_records;
     int coo_build_lds_bytes = 0;
     int64_t csr_rpt_words = 0, csr_nz = 0, coo_scratch_words = 0;
+    // BSPMM_COO_DIRECT: no CSR at all, the runs launch the direct COO kernel
+    bool coo_direct = false;
+    CooSchedule coo_sched[2];
 };
 
 namespace {
@@ -291,6 +296,25 @@ int enqueue_build(bspmm_plan* p, hipStream_t s)
 int run_direction(bspmm_plan* p, int d, const float* in, float* out, int64_t ld_in,
                   int64_t ld_out, hipStream_t s)
 {
+    if (p->coo_direct) {
+        const CooSchedule& cs = p->coo_sched[d];
+        if (cs.items.empty()) return BSPMM_OK;
+        if (!in || !out || ld_in < p->F || ld_out < p->F) return BSPMM_EINVAL;
+        CooLaunchParams C;
+        C.items = reinterpret_cast<const CooItem*>(p->ws + p->lay.items[d]);
+        C.ids = p->ids;
+        C.values = p->coo_values;
+        C.in = in;
+        C.out = out;
+        C.ld_in = ld_in;
+        C.ld_out = ld_out;
+        C.transposed = d;
+        const bool v4 = p->F % 4 == 0 && ld_in % 4 == 0 && ld_out % 4 == 0 &&
+                        (reinterpret_cast<uintptr_t>(in) & 15) == 0 &&
+                        (reinterpret_cast<uintptr_t>(out) & 15) == 0;
+        hipError_t ce = launch_bspmm_coo(C, (int)cs.items.size(), p->knobs.lds_words * 4, v4, s);
+        return ce == hipSuccess ? BSPMM_OK : hip_fail(ce);
+    }
     const Schedule& sc = p->sched[d];
     if (sc.grid == 0) return BSPMM_OK;
     if (!in || !out || ld_in < p->F || ld_out < p->F) return BSPMM_EINVAL;
@@ -345,6 +369,62 @@ int check_coo_batch(const bspmm_coo_batch* b, int32_t F, bool need_device)
     return BSPMM_OK;
 }
 
+// Plan of the direct COO kernel: two item tables (forward, transposed), the validation
+// records and the flag word; no CSR, no build.
+int plan_host_coo_direct(bspmm_plan& p, const bspmm_coo_batch* b, int32_t F, const Knobs& kn)
+{
+    const int n = b->batch;
+    if (kn.accumulate || kn.hubs) return BSPMM_EINVAL;
+    p.batch = n;
+    p.F = F;
+    p.knobs = kn;
+    p.from_coo = true;
+    p.coo_direct = true;
+    DirOps& f = p.dir[0];
+    DirOps& t = p.dir[1];
+    int64_t nnz = 0, in_f = 0, out_f = 0;
+    std::set<std::pair<int64_t, int32_t>> blocks_b;
+    for (int i = 0; i < n; ++i) {
+        f.m.push_back(b->rows[i]);
+        f.k.push_back(b->cols[i]);
+        t.m.push_back(b->cols[i]);
+        t.k.push_back(b->rows[i]);
+        for (DirOps* d : {&f, &t}) {
+            d->nnz.push_back(b->nnz[i]);
+            d->rpt_off.push_back(0);
+            d->nz_off.push_back(b->nz_off[i]);
+        }
+        f.in_off.push_back(b->b_row_off[i]);
+        f.out_off.push_back(b->c_row_off[i]);
+        t.in_off.push_back(b->c_row_off[i]);
+        t.out_off.push_back(b->b_row_off[i]);
+        nnz += b->nnz[i];
+        if (blocks_b.emplace(b->b_row_off[i], b->cols[i]).second) in_f += 4 * (int64_t)b->cols[i] * F;
+        out_f += 4 * (int64_t)b->rows[i] * F;
+    }
+    if (n > 0 && overlap_kind(b->c_row_off, b->rows, n) != 0) return BSPMM_EOVERLAP;
+    p.transposed_supported = n == 0 || overlap_kind(b->b_row_off, b->cols, n) == 0;
+    p.coo_sched[0] = make_coo_schedule(f, F, kn);
+    if (p.transposed_supported) p.coo_sched[1] = make_coo_schedule(t, F, kn);
+    // compulsory traffic: every entry once (two indices and a value), distinct dense inputs
+    // once, outputs once
+    p.effective_bytes[0] = 12 * nnz + in_f + out_f;
+    p.effective_bytes[1] = 12 * nnz + out_f + in_f;
+    p.flops = 2 * nnz * F;
+    Layout& L = p.lay;
+    size_t at = 0;
+    for (int d = 0; d < 2; ++d) {
+        L.items[d] = at;
+        at = align_up(at + p.coo_sched[d].items.size() * sizeof(CooItem));
+    }
+    L.coo_records = at;
+    at = align_up(at + (size_t)n * sizeof(OpRecord));
+    L.flag = at;
+    at = align_up(at + 4);
+    L.total = at;
+    return BSPMM_OK;
+}
+
 // Plan for COO operands: the CSR arrays (row pointers and entries packed back to back in
 // operation order) are built inside the workspace, and everything else is the CSR plan of them.
 int plan_host_coo(bspmm_plan& p, const bspmm_coo_batch* b, int32_t F, const Knobs& kn)
@@ -376,6 +456,7 @@ int plan_host_coo(bspmm_plan& p, const bspmm_coo_batch* b, int32_t F, const Knob
         rpt_words += (int64_t)b->rows[i] + 1;
         nz += b->nnz[i];
     }
+    if (kn.coo_direct) return plan_host_coo_direct(p, b, F, kn);
     bspmm_batch ib;
     ib.batch = n;
     ib.rows = b->rows;
@@ -416,8 +497,10 @@ int upload_plan(bspmm_plan* p, const bspmm_options* options, void* workspace,
                 size_t workspace_bytes, hipStream_t s)
 {
     if (options && (options->flags & BSPMM_FLOOR_PROBE))
-        for (int d = 0; d < 2; ++d)
+        for (int d = 0; d < 2; ++d) {
             for (WorkItem& w : p->sched[d].items) w.nrows = 0;
+            for (CooItem& w : p->coo_sched[d].items) w.nrows = w.nnz = 0;
+        }
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & (kAlign - 1)) != 0)
         return BSPMM_EINVAL;
     if (workspace_bytes < p->lay.total) return BSPMM_ENOSPACE;
@@ -433,6 +516,17 @@ int upload_plan(bspmm_plan* p, const bspmm_options* options, void* workspace,
     if (e == hipSuccess && !p->records.empty())
         e = hipMemcpyAsync(p->ws + p->lay.op_records, p->records.data(),
                            p->records.size() * sizeof(OpRecord), hipMemcpyHostToDevice, s);
+    if (p->coo_direct) {
+        for (int d = 0; d < 2 && e == hipSuccess; ++d)
+            if (!p->coo_sched[d].items.empty())
+                e = hipMemcpyAsync(p->ws + p->lay.items[d], p->coo_sched[d].items.data(),
+                                   p->coo_sched[d].items.size() * sizeof(CooItem),
+                                   hipMemcpyHostToDevice, s);
+        if (e == hipSuccess && !p->coo_records.empty())
+            e = hipMemcpyAsync(p->ws + p->lay.coo_records, p->coo_records.data(),
+                               p->coo_records.size() * sizeof(OpRecord), hipMemcpyHostToDevice, s);
+        return e == hipSuccess ? BSPMM_OK : hip_fail(e);
+    }
     if (e == hipSuccess && p->from_coo) {
         int32_t* rpt = reinterpret_cast<int32_t*>(p->ws + p->lay.csr_rpt);
         int32_t* colids = reinterpret_cast<int32_t*>(p->ws + p->lay.csr_colids);
@@ -548,7 +642,7 @@ int bspmm_create_coo(bspmm_plan** plan, const bspmm_coo_batch* b, int32_t F,
 int bspmm_export_csr(bspmm_plan* plan, int32_t* rpt, int32_t* colids, float* values, void* stream)
 {
     if (!plan) return BSPMM_EINVAL;
-    if (plan->dry || !plan->from_coo) return BSPMM_ESTATE;
+    if (plan->dry || !plan->from_coo || plan->coo_direct) return BSPMM_ESTATE;
     hipStream_t s = static_cast<hipStream_t>(stream);
     hipError_t e = hipSuccess;
     if (plan->csr_rpt_words) {
@@ -578,6 +672,8 @@ int bspmm_run_transposed(bspmm_plan* plan, const float* dY, float* G, int64_t ld
 {
     if (!plan) return BSPMM_EINVAL;
     if (plan->dry || !plan->transposed_supported) return BSPMM_ESTATE;
+    if (plan->coo_direct)
+        return run_direction(plan, 1, dY, G, ldy, ldg, static_cast<hipStream_t>(stream));
     if (plan->sched[1].grid > 0 && (!dY || !G || ldy < plan->F || ldg < plan->F))
         return BSPMM_EINVAL;
     int rc = enqueue_build(plan, static_cast<hipStream_t>(stream));
@@ -589,7 +685,7 @@ int bspmm_export_transposed(bspmm_plan* plan, int32_t* rpt_t, int32_t* colids_t,
                             float* values_t, void* stream)
 {
     if (!plan) return BSPMM_EINVAL;
-    if (plan->dry) return BSPMM_ESTATE;
+    if (plan->dry || plan->coo_direct) return BSPMM_ESTATE;
     hipStream_t s = static_cast<hipStream_t>(stream);
     int rc = enqueue_build(plan, s);
     if (rc != BSPMM_OK) return rc;
@@ -656,6 +752,11 @@ int bspmm_plan_info(const bspmm_plan* plan, bspmm_info* info)
             info->items_in_bin[d][b] = plan->sched[d].items_in_bin[b];
         info->effective_bytes[d] = plan->effective_bytes[d];
         info->fused_tasks[d] = plan->sched[d].fused_tasks;
+        if (plan->coo_direct) {
+            info->tile[d] = plan->coo_sched[d].tile;
+            info->workgroups[d] = info->tasks[d] = info->items[d] =
+                (int32_t)plan->coo_sched[d].items.size();
+        }
     }
     info->transposed_supported = plan->transposed_supported ? 1 : 0;
     info->transposed_built = plan->transposed_built ? 1 : 0;
@@ -668,7 +769,8 @@ int bspmm_plan_items(const bspmm_plan* plan, int32_t transposed, bspmm_item* ite
                      int32_t capacity, int32_t* count)
 {
     if (!plan || !count || capacity < 0 || (capacity > 0 && !items)) return BSPMM_EINVAL;
-    const std::vector<bspmm_item>& v = plan->sched[transposed ? 1 : 0].view;
+    const std::vector<bspmm_item>& v = plan->coo_direct ? plan->coo_sched[transposed ? 1 : 0].view
+                                                        : plan->sched[transposed ? 1 : 0].view;
     *count = (int32_t)v.size();
     const size_t n = std::min<size_t>(v.size(), (size_t)capacity);
     if (n) std::memcpy(items, v.data(), n * sizeof(bspmm_item));

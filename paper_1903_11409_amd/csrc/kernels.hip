@@ -858,6 +858,162 @@ validate_coo_kernel(const OpRecord* __restrict__ ops, const int32_t* __restrict_
 }
 
 // ---------------------------------------------------------------------------------------
+// Direct product for COO / SparseTensor operands (Fig. 3 with the output staged on chip as in
+// Fig. 5(a,b)): the item's output tile lives in LDS; a group of L lanes takes one stored entry
+// at a time (L = the tile's vectors per row rounded up to a power of two, at most 64), reads
+// the dense row it names and adds value * row into the tile with LDS floating-point atomics;
+// the tile is then streamed out.  Entries outside the item's row range (or outside the
+// matrix) are skipped.  Four entries per group are in flight at once.
+// What the paper reads from global memory entry by entry - the index pairs, the values and
+// the dense rows - is first copied to LDS in bulk where the scheduler found room (item.mode):
+// a workgroup then pays one round trip to memory instead of one per entry.
+// ---------------------------------------------------------------------------------------
+template <int VEC>
+__global__ void __launch_bounds__(kThreads)
+bspmm_coo_kernel(const CooLaunchParams P)
+{
+    extern __shared__ __align__(16) float tile[];
+    using V = typename Vec<VEC>::type;
+    const CooItem it = P.items[blockIdx.x];
+    const int tid = threadIdx.x;
+    const int stride = round_up(it.fw, 4);
+    const int nvec = (it.fw + VEC - 1) / VEC;          // VEC == 4 implies fw % 4 == 0
+    const bool st_b = (it.mode & 1) != 0, st_e = (it.mode & 2) != 0;
+    float* bt = tile + it.nrows * stride;
+    int2* ent = reinterpret_cast<int2*>(bt + (st_b ? it.k * stride : 0));
+    float* ev = reinterpret_cast<float*>(ent + it.nnz);
+
+    int log2L = 0;
+    while ((1 << log2L) < nvec && log2L < 6) ++log2L;
+    const int L = 1 << log2L;
+    const int lane = tid & (L - 1);
+    const int grp = tid >> log2L;
+    const int G = kThreads >> log2L;
+    const int32_t* __restrict__ id = P.ids + 2 * it.nz_off;
+    const float* __restrict__ va = P.values + it.nz_off;
+    const int sel = P.transposed ? 1 : 0;
+    const float* __restrict__ in = P.in + it.in_row_off * P.ld_in + it.f0;
+
+    // ---- staging: every load is issued before anything is waited for
+    bool direct = false;
+    if (st_b) {
+        direct = VEC == 4 && (nvec & (nvec - 1)) == 0;      // then stride == fw: rows are packed
+        if (direct) {
+            const int sh = ilog2(nvec);
+            const int total = it.k << sh;                    // float4 in the tile
+            const int wl = tid & 63;
+            for (int e0 = (tid >> 6) << 6; e0 < total; e0 += kThreads) {
+                const int e = e0 + wl;
+                if (e < total) {
+                    const float* gp = in + (int64_t)(e >> sh) * P.ld_in + ((e & (nvec - 1)) << 2);
+                    __builtin_amdgcn_global_load_lds(
+                        (const void __attribute__((address_space(1)))*)gp,
+                        (void __attribute__((address_space(3)))*)(bt + (e0 << 2)), 16, 0, 0);
+                }
+            }
+        } else {
+            for (int r0 = grp; r0 < it.k; r0 += 4 * G)
+                for (int j = lane; j < nvec; j += L) {
+                    V t[4];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u)
+                        if (r0 + u * G < it.k)
+                            t[u] = load_vec<VEC>(in + (int64_t)(r0 + u * G) * P.ld_in + j * VEC);
+#pragma unroll
+                    for (int u = 0; u < 4; ++u)
+                        if (r0 + u * G < it.k) store_vec<VEC>(bt + (r0 + u * G) * stride + j * VEC, t[u]);
+                }
+        }
+    }
+    if (st_e) {
+        for (int p0 = tid; p0 < it.nnz; p0 += 2 * kThreads) {
+            int r[2], c[2];
+            float v[2];
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const int p = p0 + u * kThreads;
+                if (p < it.nnz) {
+                    r[u] = id[2 * p + sel] - it.row0;
+                    c[u] = id[2 * p + 1 - sel];
+                    v[u] = va[p];
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const int p = p0 + u * kThreads;
+                if (p < it.nnz) {
+                    const bool ok = (unsigned)r[u] < (unsigned)it.nrows && (unsigned)c[u] < (unsigned)it.k;
+                    ent[p] = make_int2(ok ? r[u] * stride : -1, st_b ? c[u] * stride : c[u]);
+                    ev[p] = v[u];
+                }
+            }
+        }
+    }
+    {
+        float4* t4 = reinterpret_cast<float4*>(tile);
+        const int n4 = it.nrows * (stride >> 2);
+        for (int i = tid; i < n4; i += kThreads) t4[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+    if (direct) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // direct-to-LDS loads landed
+    __syncthreads();
+
+    // ---- one lane group per entry
+    constexpr int U = 4;
+    for (int p0 = grp; p0 < it.nnz; p0 += U * G) {
+        int ro[U], co[U];
+        float v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int p = p0 + u * G;
+            ro[u] = -1;
+            co[u] = 0;
+            v[u] = 0.f;
+            if (p < it.nnz) {
+                if (st_e) {
+                    const int2 e = ent[p];
+                    ro[u] = e.x;
+                    co[u] = e.y;
+                    v[u] = ev[p];
+                } else {
+                    const int r = id[2 * p + sel] - it.row0;
+                    const int c = id[2 * p + 1 - sel];
+                    v[u] = va[p];
+                    if ((unsigned)r < (unsigned)it.nrows && (unsigned)c < (unsigned)it.k) {
+                        ro[u] = r * stride;
+                        co[u] = c;             // mode bit 0 is never set without bit 1
+                    }
+                }
+            }
+        }
+        for (int j = lane; j < nvec; j += L) {
+            V b[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                if (ro[u] >= 0)
+                    b[u] = st_b ? load_vec<VEC>(bt + co[u] + j * VEC)
+                                : load_vec<VEC>(in + (int64_t)co[u] * P.ld_in + j * VEC);
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                if (ro[u] >= 0) {
+                    float* dst = tile + ro[u] + j * VEC;
+                    const float* bf = reinterpret_cast<const float*>(&b[u]);
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e)
+                        __hip_atomic_fetch_add(dst + e, v[u] * bf[e], __ATOMIC_RELAXED,
+                                               __HIP_MEMORY_SCOPE_WORKGROUP);
+                }
+        }
+    }
+    __syncthreads();
+
+    float* out = P.out + (it.out_row_off + it.row0) * P.ld_out + it.f0;
+    for (int rr = grp; rr < it.nrows; rr += G)
+        for (int j = lane; j < nvec; j += L)
+            store_out<VEC>(out + (int64_t)rr * P.ld_out + j * VEC,
+                           load_vec<VEC>(tile + rr * stride + j * VEC));
+}
+
+// ---------------------------------------------------------------------------------------
 // structural check: *flag becomes the smallest index of a malformed operation.
 // ---------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(kThreads)
@@ -939,6 +1095,17 @@ hipError_t launch_build_transpose(const OpRecord* ops, int batch, int lds_bytes,
     if (batch <= 0) return hipSuccess;
     hipLaunchKernelGGL(build_sorted_kernel<false>, dim3(batch), dim3(kThreads), lds_bytes, stream,
                        ops, rpt, colids, values, rpt_t, colids_t, values_t, gscratch);
+    return hipGetLastError();
+}
+
+hipError_t launch_bspmm_coo(const CooLaunchParams& P, int grid, int lds_bytes, bool vec4,
+                            hipStream_t stream)
+{
+    if (grid <= 0) return hipSuccess;
+    if (vec4)
+        hipLaunchKernelGGL(bspmm_coo_kernel<4>, dim3(grid), dim3(kThreads), lds_bytes, stream, P);
+    else
+        hipLaunchKernelGGL(bspmm_coo_kernel<1>, dim3(grid), dim3(kThreads), lds_bytes, stream, P);
     return hipGetLastError();
 }
 

@@ -66,6 +66,39 @@ struct LaunchParams {
 #endif
 };
 
+// One unit of work of the direct COO kernel: the output rows [row0, row0+nrows) x feature
+// columns [f0, f0+fw) of one operation, accumulated in LDS from ALL of the operation's entries.
+// LDS, in words, with stride = round_up(fw, 4): output tile nrows*stride, then (mode bit 0)
+// the dense tile k*stride, then (mode bit 1) 2*nnz words of (output offset, input offset)
+// pairs and nnz values.
+struct alignas(16) CooItem {
+    int64_t nz_off;       // entry offset of the operation (its index pairs start at 2*nz_off)
+    int64_t in_row_off;   // first row of the dense input block
+    int64_t out_row_off;  // first row of the dense output block
+    int32_t nnz;          // stored entries of the operation
+    int32_t k;            // rows of the dense input block (bound of the gathered index)
+    int32_t row0;
+    int32_t nrows;
+    int32_t f0;
+    int32_t fw;
+    int32_t op;
+    int32_t mode;         // bit 0: the dense tile (k rows) is staged in LDS behind the output
+                          // tile; bit 1: the entries are staged in LDS behind that
+    int32_t pad_[2];
+};
+static_assert(sizeof(CooItem) == 64, "CooItem must be 64 bytes");
+
+struct CooLaunchParams {
+    const CooItem* items;
+    const int32_t* ids;   // (row, column) pairs
+    const float* values;
+    const float* in;
+    float* out;
+    int64_t ld_in;
+    int64_t ld_out;
+    int32_t transposed;   // 0: output row = pair[0], gathered row = pair[1]; 1: swapped
+};
+
 // Per-operation record of the transposed-CSR build and of the validation kernel.
 struct alignas(8) OpRecord {
     int64_t rpt_off;
@@ -80,6 +113,14 @@ struct alignas(8) OpRecord {
 };
 
 BSPMM_HD inline int round_up(int x, int a) { return (x + a - 1) / a * a; }
+
+// LDS words of a direct COO item (see CooItem).
+BSPMM_HD inline int64_t coo_lds_words(int nrows, int k, int nnz, int fw, int mode)
+{
+    const int64_t stride = round_up(fw, 4);
+    return (int64_t)nrows * stride + ((mode & 1) ? (int64_t)k * stride : 0) +
+           ((mode & 2) ? 3 * (int64_t)nnz + 1 : 0);
+}
 
 BSPMM_HD inline int pow2_ceil(int x)
 {

@@ -302,6 +302,7 @@ Knobs resolve_knobs(const bspmm_options* o)
     if (o->resident_workgroups > 0) k.persistent_wgs = o->resident_workgroups;
     k.hubs = (o->flags & BSPMM_SPLIT_HUB_ROWS) != 0;
     k.accumulate = (o->flags & BSPMM_ACCUMULATE) != 0;
+    k.coo_direct = (o->flags & BSPMM_COO_DIRECT) != 0;
     return k;
 }
 
@@ -481,6 +482,112 @@ Schedule make_schedule(const DirOps& ops, int F, const Knobs& kn_in)
     }
     s.grid = wg;
     s.launch_grid = kn.persistent_wgs > 0 ? std::min(wg, W) : wg;
+    return s;
+}
+
+// Direct COO kernel (the resource assignment of Sec. IV-C for SparseTensor operands, cases 1-3):
+// an item keeps its whole output tile in LDS.  Where they fit beside it, the operation's dense
+// tile and its entries are staged in LDS too (one bulk copy instead of one round trip to
+// memory per entry); an operation that is too large for that at the batch-wide tile takes a
+// narrower tile of its own, and one that fits at no width keeps only the output tile (and
+// the entries, if they fit) on chip and is cut into row ranges, each of which scans all of the
+// operation's entries and keeps its own (the paper falls back to atomics on global memory
+// there).  As for CSR, the batch-wide tile is the widest one that still gives the launch
+// enough workgroups.
+namespace {
+
+struct CooChoice {
+    int fw;      // tile width of this operation
+    int nr;      // rows per item
+    int mode;
+};
+
+CooChoice coo_choice(const DirOps& o, int i, int F, size_t first, const std::vector<int>& cand,
+                     const Knobs& kn)
+{
+    const int64_t W = kn.lds_words;
+    for (size_t c = first; c < cand.size(); ++c) {
+        const int fw = std::min(cand[c], F);
+        if (coo_lds_words(o.m[i], o.k[i], o.nnz[i], fw, 3) <= W) return {fw, o.m[i], 3};
+    }
+    const int fw = std::min(cand[first], F);
+    const int64_t stride = round_up(fw, 4);
+    const int64_t ent = 3 * (int64_t)o.nnz[i] + 1;
+    if (ent + 16 * stride <= W)
+        return {fw, (int)std::min<int64_t>(o.m[i], (W - ent) / stride), 2};
+    return {fw, (int)std::min<int64_t>(o.m[i], std::max<int64_t>(1, W / stride)), 0};
+}
+
+}  // namespace
+
+CooSchedule make_coo_schedule(const DirOps& ops, int F, const Knobs& kn_in)
+{
+    CooSchedule s;
+    Knobs kn = kn_in;
+    if (!kn.target_wgs) kn.target_wgs = 4 * kn.compute_units;
+    const std::vector<int> cand = tile_candidates(F, kn);
+    auto count = [&](size_t first) {
+        int64_t n = 0;
+        for (int i = 0; i < ops.size(); ++i)
+            if (ops.m[i] > 0) {
+                const CooChoice ch = coo_choice(ops, i, F, first, cand, kn);
+                n += (int64_t)((F + ch.fw - 1) / ch.fw) * ((ops.m[i] + ch.nr - 1) / ch.nr);
+            }
+        return n;
+    };
+    size_t first = cand.size() - 1;
+    for (size_t c = 0; c < cand.size(); ++c)
+        if (count(c) >= kn.target_wgs) {
+            first = c;
+            break;
+        }
+    s.tile = std::min(cand[first], F);
+    struct Key { int64_t work; int idx; };
+    std::vector<CooItem> raw;
+    for (int i = 0; i < ops.size(); ++i) {
+        if (ops.m[i] <= 0) continue;
+        const CooChoice ch = coo_choice(ops, i, F, first, cand, kn);
+        const int parts = (ops.m[i] + ch.nr - 1) / ch.nr;
+        const int per = (ops.m[i] + parts - 1) / parts;
+        for (int f0 = 0; f0 < F; f0 += ch.fw)
+            for (int r0 = 0; r0 < ops.m[i]; r0 += per) {
+                CooItem it{};
+                it.nz_off = ops.nz_off[i];
+                it.in_row_off = ops.in_off[i];
+                it.out_row_off = ops.out_off[i];
+                it.nnz = ops.nnz[i];
+                it.k = ops.k[i];
+                it.row0 = r0;
+                it.nrows = std::min(per, ops.m[i] - r0);
+                it.f0 = f0;
+                it.fw = std::min(ch.fw, F - f0);
+                it.op = i;
+                it.mode = ch.mode;
+                raw.push_back(it);
+            }
+    }
+    std::vector<Key> order(raw.size());
+    for (size_t j = 0; j < raw.size(); ++j)
+        order[j] = {(int64_t)raw[j].fw * ((int64_t)raw[j].nnz * ((raw[j].mode & 1) ? 1 : 4) +
+                                          2 * raw[j].nrows + raw[j].k), (int)j};
+    std::stable_sort(order.begin(), order.end(),
+                     [](const Key& a, const Key& b) { return a.work > b.work; });
+    s.items.reserve(raw.size());
+    s.view.reserve(raw.size());
+    for (const Key& kx : order) {
+        const CooItem& it = raw[kx.idx];
+        bspmm_item v;
+        v.op = it.op;
+        v.bin = BSPMM_BIN_COO;
+        v.row0 = it.row0;
+        v.nrows = it.nrows;
+        v.f0 = it.f0;
+        v.fw = it.fw;
+        v.workgroup = (int32_t)s.items.size();
+        v.slot = it.mode;
+        s.items.push_back(it);
+        s.view.push_back(v);
+    }
     return s;
 }
 

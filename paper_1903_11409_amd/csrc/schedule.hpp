@@ -33,6 +33,7 @@ struct Knobs {
     int capacity_wgs_slices = 1024;   // same for the kernel variant with 32/16-lane slots
     bool accumulate = false;  // operations naming one output block are summed (else an error)
     bool hubs = false;        // split hub rows across the workgroup (reserves LDS for it)
+    bool coo_direct = false;  // COO plans: run the direct kernel instead of converting to CSR
     int persistent_wgs = 0;   // > 0: launch only this many workgroups and let them stride
 };
 
@@ -51,7 +52,18 @@ struct Schedule {
     int items_in_bin[BSPMM_NUM_BINS] = {0, 0, 0, 0, 0};
 };
 
+// Schedule of the direct COO kernel: one workgroup per item, largest first.
+struct CooSchedule {
+    std::vector<CooItem> items;
+    std::vector<bspmm_item> view;
+    int tile = 0;
+    int error = 0;
+};
+
 Knobs resolve_knobs(const bspmm_options* o);
+
+// Items of the direct COO kernel for `ops` (rpt_off unused, nz_off = the caller's entry offsets).
+CooSchedule make_coo_schedule(const DirOps& ops, int F, const Knobs& kn);
 
 // Build the single-launch schedule for `ops` at feature width F.
 Schedule make_schedule(const DirOps& ops, int F, const Knobs& kn);

@@ -200,3 +200,101 @@ def test_export_csr_needs_a_coo_plan(torch_cuda):
     with pytest.raises(K.BspmmError) as e:
         plan.export_csr()
     assert e.value.code == K.ESTATE
+
+
+# ---------------------------------------------------------------------------------------------
+# BSPMM_COO_DIRECT: the kernel of Fig. 3 / Fig. 5(a,b), no conversion
+# ---------------------------------------------------------------------------------------------
+DIRECT = dict(flags=K.COO_DIRECT)
+
+
+@pytest.mark.parametrize("maker", [
+    lambda: W.config1_tiny(),
+    lambda: W.config2_molecule(),                                    # the headline batch
+    lambda: W.config4_wide(F=512),
+    lambda: W.config5_skewed(),
+    lambda: W.config5_skewed(graphs=200, F=64, asymmetric=True),
+])
+def test_direct_workload_configurations(torch_cuda, oracle, maker):
+    b = maker()
+    ids, vals = W.coo_view(b, seed=W.config_seed(9))
+    _check(torch_cuda, oracle, b, ids, vals, opts=K.make_options(**DIRECT), what=b.name + " direct",
+           csr=False)
+
+
+def test_direct_shared_inputs_forward_only(torch_cuda, oracle):
+    b = W.config3_multichannel()
+    ids, vals = W.coo_view(b, seed=12)
+    plan = _check(torch_cuda, oracle, b, ids, vals, opts=K.make_options(**DIRECT),
+                  what="cfg3 direct", csr=False, transposed=False)
+    Y = torch_cuda.zeros((b.n_c_rows, b.F), device="cuda")
+    G = torch_cuda.zeros((b.n_b_rows, b.F), device="cuda")
+    with pytest.raises(K.BspmmError) as e:
+        plan.run_transposed(Y, G)
+    assert e.value.code == K.ESTATE
+    with pytest.raises(K.BspmmError) as e:
+        plan.export_csr()
+    assert e.value.code == K.ESTATE
+
+
+@pytest.mark.parametrize("F", [1, 5, 64, 100, 260])
+def test_direct_ragged_repeated_pairs_and_empty_operations(torch_cuda, oracle, F):
+    b = W.random_general(92, F=F, shapes=[(9, 5, 40), (5, 9, 40), (30, 30, 0), (1, 1, 1),
+                                          (0, 0, 0), (17, 17, 60), (300, 200, 5000),
+                                          (1, 64, 64), (64, 1, 64)], shuffle_blocks=True)
+    ids, vals = W.coo_view(b, seed=F)
+    _check(torch_cuda, oracle, b, ids, vals, opts=K.make_options(**DIRECT), what=f"direct F={F}",
+           csr=False)
+
+
+@pytest.mark.parametrize("kw", [{"lds_bytes": 4096}, {"lds_bytes": 65536}, {"max_tile": 64},
+                                {"min_tile": 8, "target_workgroups": 5000},
+                                {"target_workgroups": 1}, {"wg_passes": -1}])
+def test_direct_row_ranges_and_knobs(torch_cuda, oracle, kw):
+    """Tiles that cannot hold all rows of an operation are cut into row ranges."""
+    b = W.random_general(93, F=96, shapes=[(4000, 3000, 20000), (10, 10, 30), (700, 700, 9000)])
+    ids, vals = W.coo_view(b, seed=3)
+    _check(torch_cuda, oracle, b, ids, vals, opts=K.make_options(**DIRECT, **kw),
+           what=f"direct {kw}", csr=False)
+
+
+def test_direct_hub_rows_and_skipped_pairs(torch_cuda, oracle):
+    torch = torch_cuda
+    b = W.hub_batch(5, F=64, n=700)
+    ids, vals = W.coo_view(b, seed=6)
+    _check(torch, oracle, b, ids, vals, opts=K.make_options(**DIRECT), what="hub direct", csr=False)
+    # out-of-range pairs are reported by validate and left out of the product
+    b = W.config2_molecule(graphs=16, F=32)
+    ids, vals = W.coo_view(b, seed=2)
+    bad = ids.copy()
+    z0 = int(b.nz_off[5])
+    bad[2 * (z0 + 1) + 1] = int(b.cols[5])
+    plan = K.Plan(b, coo=(bad, vals), options=K.make_options(**DIRECT))
+    assert plan.validate() == 5
+    good_ids, good_vals = ids.copy(), vals.copy()
+    good_vals[z0 + 1] = 0.0                            # same product as leaving the entry out
+    ref, S = oracle.coo_product(b.rows, b.cols, b.nnz, b.nz_off, b.b_row_off, b.c_row_off,
+                                good_ids, good_vals, b.B, b.n_c_rows)
+    Cd = torch.full((b.n_c_rows, b.F), SENTINEL, dtype=torch.float32, device="cuda")
+    plan.run(torch.from_numpy(b.B).cuda(), Cd)
+    torch.cuda.synchronize()
+    _assert_close(Cd.cpu().numpy(), ref, S, _owned(b.c_row_off, b.rows, b.n_c_rows), "direct skipped")
+
+
+def test_direct_scalar_path_for_unaligned_operands(torch_cuda, oracle):
+    torch = torch_cuda
+    b = W.config2_molecule(graphs=24, F=64)
+    ids, vals = W.coo_view(b, seed=2)
+    plan = K.Plan(b, coo=(ids, vals), options=K.make_options(**DIRECT))
+    ld = b.F + 3
+    Bd = torch.zeros((b.n_b_rows, ld), dtype=torch.float32, device="cuda")
+    Bd[:, :b.F] = torch.from_numpy(b.B).cuda()
+    store = torch.full((b.n_c_rows * ld + 9,), SENTINEL, dtype=torch.float32, device="cuda")
+    Cd = store[1:1 + b.n_c_rows * ld].view(b.n_c_rows, ld)
+    plan.run(Bd, Cd)
+    torch.cuda.synchronize()
+    ref, S = oracle.coo_product(b.rows, b.cols, b.nnz, b.nz_off, b.b_row_off, b.c_row_off, ids,
+                                vals, b.B, b.n_c_rows)
+    _assert_close(Cd[:, :b.F].cpu().numpy(), ref, S, _owned(b.c_row_off, b.rows, b.n_c_rows),
+                  "direct unaligned")
+    assert torch.all(Cd[:, b.F:] == SENTINEL) and float(store[0]) == SENTINEL

@@ -362,3 +362,65 @@ def test_coo_argument_errors():
         K.bspmm_destroy(h)
     raw = K.lib()
     assert raw.bspmm_workspace_bytes_coo(None, 8, None, ctypes.byref(ctypes.c_size_t())) == K.EINVAL
+
+
+@pytest.mark.parametrize("maker,F,kw", [
+    (lambda: W.config2_molecule(graphs=64, F=128), 128, {}),
+    (lambda: W.config5_skewed(graphs=64, F=256), 256, {}),
+    (lambda: W.config4_wide(graphs=16, F=1024), 1024, {}),
+    (lambda: W.random_general(5, F=1, shapes=[(7, 13, 25), (0, 0, 0), (40, 3, 70), (9, 9, 0)]), 63, {}),
+    # tiles that cannot hold all rows: row ranges
+    (lambda: W.random_general(6, F=1, shapes=[(5000, 40, 900), (3, 3, 3)]), 64, {"lds_bytes": 8192}),
+    (lambda: W.config2_molecule(graphs=8, F=1), 100, {"target_workgroups": 4000}),
+])
+@pytest.mark.parametrize("transposed", [False, True])
+def test_direct_coo_schedule_covers_every_element_once(maker, F, kw, transposed):
+    b = maker()
+    h = K.dry_plan(b, F, coo=True, flags=K.COO_DIRECT, **kw)
+    try:
+        info = K.bspmm_plan_info(h)
+        items = K.bspmm_plan_items(h, transposed)
+        d = 1 if transposed else 0
+        assert info.items[d] == info.workgroups[d] == len(items)
+        m_of = b.cols if transposed else b.rows
+        cover = [np.zeros((int(m), F), dtype=np.int32) for m in m_of]
+        for n, it in enumerate(items):
+            assert it.bin == K.BIN_COO and it.workgroup == n
+            assert it.nrows > 0 and it.fw > 0 and it.fw <= 256
+            assert F % 4 != 0 or (it.f0 % 4 == 0 and it.fw % 4 == 0)
+            # the output tile of the item, and whatever else it stages (slot = mode bits: 1 the
+            # dense tile, 2 the entries), sit in LDS together
+            k_of = b.rows if transposed else b.cols
+            stride = (it.fw + 3) // 4 * 4
+            words = it.nrows * stride
+            assert it.slot in (0, 2, 3)
+            if it.slot & 1:
+                words += int(k_of[it.op]) * stride
+            if it.slot & 2:
+                words += 3 * int(b.nnz[it.op]) + 1
+            assert words * 4 <= info.lds_bytes
+            cover[it.op][it.row0:it.row0 + it.nrows, it.f0:it.f0 + it.fw] += 1
+        for c in cover:
+            assert np.all(c == 1)
+        assert info.flops == 2 * int(b.nnz.sum()) * F
+    finally:
+        K.bspmm_destroy(h)
+
+
+def test_direct_coo_rejects_what_it_cannot_do():
+    b = W.config3_multichannel(graphs=4, F=32, accumulate=True)
+    hc = K.HostCooBatch(b.rows, b.cols, b.nnz, b.nz_off, b.b_row_off, b.c_row_off)
+    for flags in (K.COO_DIRECT | K.ACCUMULATE, K.COO_DIRECT | K.SPLIT_HUB_ROWS):
+        with pytest.raises(K.BspmmError) as e:
+            K.bspmm_create_coo(hc, 32, K.make_options(flags=K.DRY_RUN | flags))
+        assert e.value.code == K.EINVAL
+    with pytest.raises(K.BspmmError) as e:       # summed output blocks need the CSR route
+        K.bspmm_create_coo(hc, 32, K.make_options(flags=K.DRY_RUN | K.COO_DIRECT))
+    assert e.value.code == K.EOVERLAP
+    # inputs shared by several operations: forward works, the transposed product is refused
+    b2 = W.config3_multichannel(graphs=4, F=32)
+    h = K.dry_plan(b2, coo=True, flags=K.COO_DIRECT)
+    try:
+        assert K.bspmm_plan_info(h).transposed_supported == 0
+    finally:
+        K.bspmm_destroy(h)
