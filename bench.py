@@ -131,6 +131,44 @@ class Runner:
                 "workgroups": self.workgroups}
 
 
+def coo_operands(torch, K, W):
+    """COO / SparseTensor operands (unsorted index pairs): the conversion launch of
+    bspmm_create_coo, the product on the converted plan, and the direct LDS-atomic kernel
+    (BSPMM_COO_DIRECT), all HBM-cold."""
+    out = {}
+    for name, mk in (("cfg2_F128", lambda: W.config2_molecule(F=128)),
+                     ("cfg5_F256", lambda: W.config5_skewed())):
+        b = mk()
+        ids, vals = W.coo_view(b, seed=W.config_seed(9))
+        conv = K.Plan(b, coo=(ids, vals))
+        r = Runner(torch, K, b, plan=conv)
+        s_conv, _ = r.time_graph(1000, 100)
+        # device time of a plan creation: uploads of the tables plus the sort launch
+        ws, hb = conv.workspace, conv.hb
+        nbytes = K.bspmm_workspace_bytes_coo(hb, b.F, None)
+        stream = torch.cuda.current_stream().cuda_stream
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        reps = 20
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        e0.record()
+        for _ in range(reps):
+            K.bspmm_destroy(K.bspmm_create_coo(hb, b.F, None, ws, nbytes, stream))
+        e1.record()
+        torch.cuda.synchronize()
+        wall = (time.perf_counter() - t0) / reps
+        # the last creation left the workspace as the first did: conv is still valid
+        direct = K.Plan(b, coo=(ids, vals), options=K.make_options(flags=K.COO_DIRECT))
+        rd = Runner(torch, K, b, plan=direct)
+        s_dir, _ = rd.time_graph(400, 40)
+        out[name] = {"create_coo_wall_us": round(wall * 1e6, 1),
+                     "create_coo_stream_us": round(e0.elapsed_time(e1) * 1e3 / reps, 1),
+                     "converted_run": r.summary(s_conv), "direct_run": rd.summary(s_dir)}
+        del r, rd, conv, direct
+        torch.cuda.empty_cache()
+    return out
+
+
 _marker = None
 
 
@@ -370,6 +408,7 @@ def main():
                 torch.cuda.empty_cache()
         extra["channel_sum"] = acc
         extra["paper_grid_batched_vs_non_batched"] = paper_grid(torch, K, W)
+        extra["coo_operands"] = coo_operands(torch, K, W)
 
     out = {
         "metric": "batched SpMM graphs/sec, F=128, batch 128",

@@ -119,38 +119,67 @@ int64_t item_cost(const DirOps& o, int i, int nrows, int fw, bool staged)
            4 * (int64_t)nrows + 512;
 }
 
+// Where drafted items go.  Sizing the launch only needs to know how many items each launch
+// range would get, so the search over tiles and row cuts runs on a sink that counts; the one
+// draft that is kept is built with a sink that stores the items.
+struct Sink {
+    std::vector<Draft>* out = nullptr;     // null: count only
+    int per_range[kRanges] = {0, 0, 0, 0, 0};
+    const std::vector<int>* block_of_op = nullptr;   // dense-input block index of every operation
+    int tiles_per_block = 1;               // group id = block * tiles_per_block + f0 / tile_unit
+    int tile_unit = 4;
+    void add(const DirOps& o, int i, int bin, int row0, int nrows, int f0, int fw, int staged,
+             int fused)
+    {
+        per_range[fused >= 0 ? 1 : bin_range(bin)]++;
+        if (!out) return;
+        const int gid = fused >= 0 ? -1 : (*block_of_op)[i] * tiles_per_block + f0 / tile_unit;
+        out->push_back({i, bin, row0, nrows, f0, fw, staged,
+                        fused >= 0 ? 0 : item_cost(o, i, nrows, fw, staged != 0), gid, fused});
+    }
+    int workgroups() const
+    {
+        int wgs = per_range[0] + per_range[1];
+        for (int r = 2; r < kRanges; ++r) {
+            const int slots = kThreads >> range_log2_slot(r);
+            wgs += (per_range[r] + slots - 1) / slots;
+        }
+        return wgs;
+    }
+};
+
 // `cap` > 0 cuts a workgroup item into row ranges of at most `cap` passes each (every range
 // stages the whole operation, so the cut costs on-chip traffic and buys parallelism).
 void draft_op(const DirOps& o, int i, int F, int vec, const Choice& ch, const Knobs& kn, int cap,
-              std::map<std::pair<int64_t, int>, int>& groups, std::vector<Draft>& out)
+              Sink& sink)
 {
     if (o.m[i] <= 0) return;
     const int tile = ch.tile;
+    if (!sink.out) {    // counting: the same items in closed form
+        auto per_tile = [&](int fw) {
+            if (ch.bin == BSPMM_BIN_WORKGROUP && cap > 0) {
+                const int chunk = cap * (kThreads / lanes_per_row(fw, vec));
+                return (o.m[i] + chunk - 1) / chunk;
+            }
+            if (ch.bin != BSPMM_BIN_GENERIC) return 1;
+            return (o.m[i] + kn.generic_rows - 1) / kn.generic_rows;
+        };
+        const int full = F / tile, tail = F % tile;
+        sink.per_range[bin_range(ch.bin)] += (full ? full * per_tile(tile) : 0) + (tail ? per_tile(tail) : 0);
+        return;
+    }
     for (int f0 = 0; f0 < F; f0 += tile) {
         const int fw = std::min(tile, F - f0);
-        auto key = std::make_pair(o.in_off[i], f0);
-        auto it = groups.find(key);
-        int gid;
-        if (it == groups.end()) {
-            gid = (int)groups.size();
-            groups.emplace(key, gid);
-        } else {
-            gid = it->second;
-        }
         if (ch.bin == BSPMM_BIN_WORKGROUP && cap > 0) {
             const int rows_per_pass = kThreads / lanes_per_row(fw, vec);
             const int chunk = cap * rows_per_pass;
-            for (int r0 = 0; r0 < o.m[i]; r0 += chunk) {
-                const int nr = std::min(chunk, o.m[i] - r0);
-                out.push_back({i, ch.bin, r0, nr, f0, fw, 1, item_cost(o, i, nr, fw, true), gid, -1});
-            }
+            for (int r0 = 0; r0 < o.m[i]; r0 += chunk)
+                sink.add(o, i, ch.bin, r0, std::min(chunk, o.m[i] - r0), f0, fw, 1, -1);
         } else if (ch.bin != BSPMM_BIN_GENERIC) {
-            out.push_back({i, ch.bin, 0, o.m[i], f0, fw, 1, item_cost(o, i, o.m[i], fw, true), gid, -1});
+            sink.add(o, i, ch.bin, 0, o.m[i], f0, fw, 1, -1);
         } else {
-            for (int r0 = 0; r0 < o.m[i]; r0 += kn.generic_rows) {
-                const int nr = std::min(kn.generic_rows, o.m[i] - r0);
-                out.push_back({i, ch.bin, r0, nr, f0, fw, 0, item_cost(o, i, nr, fw, false), gid, -1});
-            }
+            for (int r0 = 0; r0 < o.m[i]; r0 += kn.generic_rows)
+                sink.add(o, i, ch.bin, r0, std::min(kn.generic_rows, o.m[i] - r0), f0, fw, 0, -1);
         }
     }
 }
@@ -177,7 +206,7 @@ int64_t fused_words(const DirOps& o, const std::vector<int>& members, int fw)
 // when none does.
 bool draft_fused(const DirOps& o, const std::vector<int>& members, int fused_index, int F, int vec,
                  const std::vector<int>& cand, size_t first, const Knobs& kn, int cap,
-                 std::vector<Draft>& out)
+                 Sink& sink)
 {
     std::vector<int> tiles(cand.begin() + first, cand.end());
     for (int t : {16, 8, 4})
@@ -196,62 +225,84 @@ bool draft_fused(const DirOps& o, const std::vector<int>& members, int fused_ind
         const int chunk = cap > 0 ? cap * rows_per_pass : m;
         for (int r0 = 0; r0 < m; r0 += chunk) {
             const int nr = std::min(chunk, m - r0);
-            int64_t cost = 0;
-            for (int i : members) cost += item_cost(o, i, nr, fw, true);
-            out.push_back({members[0], BSPMM_BIN_WORKGROUP, r0, nr, f0, fw, 1, cost, -1, fused_index});
+            sink.add(o, members[0], BSPMM_BIN_WORKGROUP, r0, nr, f0, fw, 1, fused_index);
+            if (sink.out) {
+                int64_t cost = 0;
+                for (int i : members) cost += item_cost(o, i, nr, fw, true);
+                sink.out->back().cost = cost;
+            }
         }
     }
     return true;
 }
 
 // Operations grouped by the output block they name: a group of more than one is summed.
+// Groups are listed in the order of their first operation, members in operation order.
 std::vector<std::vector<int>> output_groups(const DirOps& o)
 {
-    std::map<std::pair<int64_t, int>, int> index;
+    std::vector<int> idx;
+    idx.reserve(o.size());
+    for (int i = 0; i < o.size(); ++i)
+        if (o.m[i] > 0) idx.push_back(i);
+    std::vector<int> sorted = idx;
+    std::sort(sorted.begin(), sorted.end(), [&](int a, int b) {
+        if (o.out_off[a] != o.out_off[b]) return o.out_off[a] < o.out_off[b];
+        if (o.m[a] != o.m[b]) return o.m[a] < o.m[b];
+        return a < b;
+    });
+    // leader[i] = first operation (lowest index) naming the same block as i
+    std::vector<int> leader(o.size(), -1);
+    for (size_t a = 0; a < sorted.size();) {
+        size_t b = a;
+        while (b < sorted.size() && o.out_off[sorted[b]] == o.out_off[sorted[a]] &&
+               o.m[sorted[b]] == o.m[sorted[a]])
+            leader[sorted[b++]] = sorted[a];
+        a = b;
+    }
+    std::vector<int> group_of(o.size(), -1);
     std::vector<std::vector<int>> groups;
-    for (int i = 0; i < o.size(); ++i) {
-        if (o.m[i] <= 0) continue;
-        auto key = std::make_pair(o.out_off[i], o.m[i]);
-        auto it = index.find(key);
-        if (it == index.end()) {
-            index.emplace(key, (int)groups.size());
-            groups.push_back({i});
-        } else {
-            groups[it->second].push_back(i);
+    groups.reserve(idx.size());
+    for (int i : idx) {
+        const int l = leader[i];
+        if (group_of[l] < 0) {
+            group_of[l] = (int)groups.size();
+            groups.emplace_back();
         }
+        groups[group_of[l]].push_back(i);
     }
     return groups;
 }
 
-std::vector<Draft> draft_all(const DirOps& o, int F, int vec, const std::vector<int>& cand,
-                             size_t first, const Knobs& kn, int cap, bool allow_small,
-                             const std::vector<std::vector<int>>& outs, bool* fits)
+// Index of the dense-input block of every operation (operations reading the same first row
+// share an index).
+std::vector<int> input_blocks(const DirOps& o)
 {
-    std::vector<Draft> d;
-    std::map<std::pair<int64_t, int>, int> groups;
+    std::vector<int> order(o.size());
+    std::iota(order.begin(), order.end(), 0);
+    std::sort(order.begin(), order.end(),
+              [&](int a, int b) { return o.in_off[a] != o.in_off[b] ? o.in_off[a] < o.in_off[b] : a < b; });
+    std::vector<int> block(o.size(), 0);
+    int nb = -1;
+    for (size_t t = 0; t < order.size(); ++t) {
+        if (t == 0 || o.in_off[order[t]] != o.in_off[order[t - 1]]) ++nb;
+        block[order[t]] = nb;
+    }
+    return block;
+}
+
+void draft_all(const DirOps& o, int F, int vec, const std::vector<int>& cand, size_t first,
+               const Knobs& kn, int cap, bool allow_small,
+               const std::vector<std::vector<int>>& outs, bool* fits, Sink& sink)
+{
     int nfused = 0;
     for (const std::vector<int>& g : outs) {
         if (g.size() == 1) {
             const int i = g[0];
-            draft_op(o, i, F, vec, choose(o, i, F, vec, cand, first, kn, allow_small), kn, cap,
-                     groups, d);
-        } else if (!draft_fused(o, g, nfused++, F, vec, cand, first, kn, cap, d)) {
+            draft_op(o, i, F, vec, choose(o, i, F, vec, cand, first, kn, allow_small), kn, cap, sink);
+        } else if (!draft_fused(o, g, nfused++, F, vec, cand, first, kn, cap, sink)) {
             *fits = false;
         }
     }
-    return d;
-}
-
-int count_workgroups(const std::vector<Draft>& d)
-{
-    int per_range[kRanges] = {0, 0, 0, 0, 0};
-    for (const Draft& x : d) per_range[draft_range(x)]++;
-    int wgs = per_range[0] + per_range[1];
-    for (int r = 2; r < kRanges; ++r) {
-        const int slots = kThreads >> range_log2_slot(r);
-        wgs += (per_range[r] + slots - 1) / slots;
-    }
-    return wgs;
 }
 
 WorkItem to_item(const DirOps& o, const Draft& x)
@@ -331,34 +382,50 @@ Schedule make_schedule(const DirOps& ops, int F, const Knobs& kn_in)
         return s;
     }
     bool fits = true;
+    auto workgroups_of = [&](size_t first, int cap, bool small) {
+        Sink counter;
+        draft_all(ops, F, vec, cand, first, kn, cap, small, outs, &fits, counter);
+        return counter.workgroups();
+    };
+    int wgs = 0;
     for (int attempt = 0; attempt < 2; ++attempt) {
         for (size_t c = 0; c < cand.size(); ++c) {
-            d = draft_all(ops, F, vec, cand, c, kn, fixed_cap, allow_small, outs, &fits);
-            if (count_workgroups(d) >= kn.target_wgs || c + 1 == cand.size()) {
+            wgs = workgroups_of(c, fixed_cap, allow_small);
+            if (wgs >= kn.target_wgs || c + 1 == cand.size()) {
                 chosen = c;
                 break;
             }
         }
-        if (allow_small || count_workgroups(d) <= kn.capacity_wgs) break;
+        if (allow_small || wgs <= kn.capacity_wgs) break;
         allow_small = true;
     }
     s.tile = cand[chosen];
     // still too few workgroups at the narrowest tile: the batch is small, its time is set by
     // the slowest workgroup, so cut multi-pass workgroup items into row ranges
-    if (kn.wg_passes == 0 && count_workgroups(d) < kn.target_wgs) {
-        for (int cap = 4; cap >= 1; cap /= 2) {
-            d = draft_all(ops, F, vec, cand, chosen, kn, cap, allow_small, outs, &fits);
-            if (count_workgroups(d) >= kn.target_wgs) break;
+    int cap = fixed_cap;
+    if (kn.wg_passes == 0 && wgs < kn.target_wgs) {
+        for (cap = 4; cap >= 1; cap /= 2) {
+            wgs = workgroups_of(chosen, cap, allow_small);
+            if (wgs >= kn.target_wgs || cap == 1) break;
         }
     }
     if (!fits) {   // a set of summed operations does not fit LDS together even at 4 columns
         s.error = BSPMM_ETOOBIG;
         return s;
     }
+    // the draft that is kept
+    const std::vector<int> block_of_op = input_blocks(ops);
+    Sink keep;
+    keep.out = &d;
+    keep.block_of_op = &block_of_op;
+    keep.tile_unit = std::max(4, std::min(cand.back(), F));
+    keep.tiles_per_block = (F + keep.tile_unit - 1) / keep.tile_unit;
+    d.reserve((size_t)wgs * 4 + 16);
+    draft_all(ops, F, vec, cand, chosen, kn, cap, allow_small, outs, &fits, keep);
 
     // group costs, for ordering and XCD placement
     int ngroups = 0;
-    for (const Draft& x : d) ngroups = std::max(ngroups, x.group + 1);
+    for (int bi : block_of_op) ngroups = std::max(ngroups, (bi + 1) * keep.tiles_per_block);
     for (Draft& x : d)
         if (x.fused >= 0) x.group = ngroups++;                // fused tasks stand alone
     std::vector<int64_t> gcost(ngroups, 0);
@@ -370,16 +437,33 @@ Schedule make_schedule(const DirOps& ops, int F, const Knobs& kn_in)
     for (Draft& x : d)
         if (x.fused < 0 && x.staged && gsize[x.group] == 1) x.staged |= 2;   // tile read once
 
-    std::vector<std::vector<int>> by_range(kRanges);
-    for (int idx = 0; idx < (int)d.size(); ++idx) by_range[draft_range(d[idx])].push_back(idx);
-    auto big_first = [&](int a, int b) {
-        const Draft &x = d[a], &y = d[b];
-        if (gcost[x.group] != gcost[y.group]) return gcost[x.group] > gcost[y.group];
-        if (x.group != y.group) return x.group < y.group;
-        if (x.cost != y.cost) return x.cost > y.cost;
-        return a < b;
+    // largest group first, members of a group together, larger items first inside a group;
+    // the keys are copied next to the indices so that the sort touches one array only
+    struct SortKey {
+        int64_t gcost, cost;
+        int group, idx;
     };
-    for (auto& v : by_range) std::sort(v.begin(), v.end(), big_first);
+    std::vector<SortKey> keys[kRanges];
+    {
+        int n_in[kRanges] = {0, 0, 0, 0, 0};
+        for (const Draft& x : d) n_in[draft_range(x)]++;
+        for (int r = 0; r < kRanges; ++r) keys[r].reserve(n_in[r]);
+        for (int idx = 0; idx < (int)d.size(); ++idx) {
+            const Draft& x = d[idx];
+            keys[draft_range(x)].push_back({gcost[x.group], x.cost, x.group, idx});
+        }
+    }
+    std::vector<std::vector<int>> by_range(kRanges);
+    for (int r = 0; r < kRanges; ++r) {
+        std::sort(keys[r].begin(), keys[r].end(), [](const SortKey& a, const SortKey& b) {
+            if (a.gcost != b.gcost) return a.gcost > b.gcost;
+            if (a.group != b.group) return a.group < b.group;
+            if (a.cost != b.cost) return a.cost > b.cost;
+            return a.idx < b.idx;
+        });
+        by_range[r].reserve(keys[r].size());
+        for (const SortKey& k : keys[r]) by_range[r].push_back(k.idx);
+    }
 
     // range 0: one item per workgroup; groups dealt to the XCD with the least cost so far,
     // then the eight lists interleaved so that list x occupies workgroups x, x+8, x+16, ...
@@ -387,6 +471,7 @@ Schedule make_schedule(const DirOps& ops, int F, const Knobs& kn_in)
     {
         int64_t load[kXcds] = {0};
         const std::vector<int>& v = by_range[0];
+        for (auto& l : xcd) l.reserve(v.size() / kXcds + 64);
         size_t a = 0;
         while (a < v.size()) {
             size_t b = a;
@@ -428,6 +513,8 @@ Schedule make_schedule(const DirOps& ops, int F, const Knobs& kn_in)
         s.items_in_bin[x.bin]++;
     };
 
+    s.items.reserve(longest * kXcds + d.size() * (most_members > 1 ? most_members : 1) + 64);
+    s.view.reserve(d.size() * (most_members > 1 ? most_members : 1));
     s.item_base[0] = 0;
     for (size_t pos = 0; pos < longest; ++pos)
         for (int x = 0; x < kXcds; ++x) {
