@@ -104,6 +104,43 @@ int oracle_bspmm_forward(int32_t batch, const int32_t* rows, const int32_t* cols
 }
 
 /*
+ * The same forward product with an fp64 dense input (no scale output): the last step of the
+ * batched graph-convolution layer (Fig. 7: U = MatMul(Xr, W[ch]); B = Add(bias[ch], U);
+ * C[ch] = BatchedSpMM(A_list, B)), whose B the oracle keeps in fp64 instead of rounding it to
+ * fp32 between the steps.  `accumulate` != 0 adds to C instead of overwriting it (the
+ * ElementWiseAdd over channels taken one channel at a time).
+ */
+int oracle_bspmm_forward_f64(int32_t batch, const int32_t* rows, const int32_t* cols,
+                             const int32_t* nnz, const int64_t* rpt_off, const int64_t* nz_off,
+                             const int64_t* b_row_off, const int64_t* c_row_off,
+                             const int32_t* rpt, const int32_t* colids, const float* values,
+                             const double* B, int64_t ldb, int32_t F, int32_t accumulate,
+                             double* C, int64_t ldc)
+{
+    for (int32_t i = 0; i < batch; ++i)
+        if (!check_op(rows[i], cols[i], nnz[i], rpt + rpt_off[i], colids + nz_off[i]))
+            return -(i + 1);
+    if (!accumulate)
+        for (int32_t i = 0; i < batch; ++i)
+            for (int32_t r = 0; r < rows[i]; ++r)
+                for (int32_t j = 0; j < F; ++j) C[(c_row_off[i] + r) * ldc + j] = 0.0;
+    for (int32_t i = 0; i < batch; ++i) {
+        const int32_t* rp = rpt + rpt_off[i];
+        const int32_t* ci = colids + nz_off[i];
+        const float* va = values + nz_off[i];
+        for (int32_t r = 0; r < rows[i]; ++r) {
+            double* c = C + (c_row_off[i] + r) * ldc;
+            for (int32_t p = rp[r]; p < rp[r + 1]; ++p) {
+                const double v = (double)va[p];
+                const double* b = B + (b_row_off[i] + ci[p]) * ldb;
+                for (int32_t j = 0; j < F; ++j) c[j] += v * b[j];
+            }
+        }
+    }
+    return 0;
+}
+
+/*
  * Transposed product G_i = A_i^T dY_i.  dY_i has rows[i] rows at dY + c_row_off[i]*ldy,
  * G_i has cols[i] rows at G + b_row_off[i]*ldg.  Operations that name the same output block
  * (channels reading one dense input in the forward direction) are added up.

@@ -55,6 +55,11 @@ def _load():
         lib.oracle_coo_to_csr.argtypes = [ctypes.c_int32, i32p, i32p, i32p, i64p, i32p, f32p,
                                           i64p, i32p, i32p, f32p, i32p]
         lib.oracle_coo_to_csr.restype = ctypes.c_int
+        lib.oracle_bspmm_forward_f64.argtypes = [ctypes.c_int32, i32p, i32p, i32p, i64p, i64p,
+                                                 i64p, i64p, i32p, i32p, f32p, f64p,
+                                                 ctypes.c_int64, ctypes.c_int32, ctypes.c_int32,
+                                                 f64p, ctypes.c_int64]
+        lib.oracle_bspmm_forward_f64.restype = ctypes.c_int
         lib.oracle_num_threads.restype = ctypes.c_int
         lib.oracle_set_num_threads.argtypes = [ctypes.c_int]
         _lib = lib
@@ -206,6 +211,45 @@ def coo_to_csr(rows, cols, nnz, nz_off, ids, values):
     if rc != 0:
         raise ValueError(f"oracle: malformed operation {-rc - 1}")
     return rpt_off, rpt, colids, csr_values
+
+
+def _forward_f64(a, B64: np.ndarray, C: np.ndarray, accumulate: bool) -> None:
+    lib = _load()
+    F = int(B64.shape[1])
+    rc = lib.oracle_bspmm_forward_f64(
+        int(a[0].shape[0]), _p(a[0], ctypes.c_int32), _p(a[1], ctypes.c_int32),
+        _p(a[2], ctypes.c_int32), _p(a[3], ctypes.c_int64), _p(a[4], ctypes.c_int64),
+        _p(a[5], ctypes.c_int64), _p(a[6], ctypes.c_int64), _p(a[7], ctypes.c_int32),
+        _p(a[8], ctypes.c_int32), _p(a[9], ctypes.c_float), _p(B64, ctypes.c_double), F, F,
+        1 if accumulate else 0, _p(C, ctypes.c_double), F)
+    if rc != 0:
+        raise ValueError(f"oracle: malformed operation {-rc - 1}")
+
+
+def gcn_channel(b, X: np.ndarray, W: np.ndarray, bias: np.ndarray, Y=None, T=None):
+    """One channel of the batched graph-convolution layer (Fig. 7), step by step in fp64:
+    U = MatMul(Xr, W); B = Add(bias, U); C = BatchedSpMM(A_list, B).  ``X`` is the packed
+    feature matrix (row block i at ``b.b_row_off[i]``, ``b.cols[i]`` rows, n_X columns), ``W`` is
+    n_X x F, ``bias`` has F entries.  Returns (Y, T): with ``Y``/``T`` given the channel is added
+    to them (the ElementWiseAdd over channels).  T is the tolerance scale
+    sum_p |a_p| (sum_t |X[c_p][t]| |W[t][j]| + |bias[j]|)."""
+    a = _prep(b.rows, b.cols, b.nnz, b.rpt_off, b.nz_off, b.b_row_off, b.c_row_off, b.rpt,
+              b.colids, b.values)
+    X64 = np.asarray(X, dtype=np.float32).astype(np.float64)
+    W64 = np.asarray(W, dtype=np.float32).astype(np.float64)
+    bias64 = np.asarray(bias, dtype=np.float32).astype(np.float64)
+    U = X64 @ W64                                   # MatMul
+    B = np.ascontiguousarray(U + bias64[None, :])   # Add
+    Babs = np.ascontiguousarray(np.abs(X64) @ np.abs(W64) + np.abs(bias64)[None, :])
+    acc = Y is not None
+    if not acc:
+        Y = np.full((int(b.n_c_rows), B.shape[1]), np.nan, dtype=np.float64)
+        T = np.full((int(b.n_c_rows), B.shape[1]), np.nan, dtype=np.float64)
+    _forward_f64(a, B, Y, acc)                      # BatchedSpMM
+    absa = list(a)
+    absa[9] = np.abs(a[9])
+    _forward_f64(tuple(absa), Babs, T, acc)
+    return Y, T
 
 
 def forward_batch(b, want_scale: bool = True):

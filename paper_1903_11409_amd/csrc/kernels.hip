@@ -669,12 +669,12 @@ __device__ __forceinline__ void run_slots(const LaunchParams& P, int* sm, int fi
 }
 
 
-// One launch runs the whole schedule.  The grid is persistent: it has at most as many
-// workgroups as the chip holds at once, and workgroup w takes tasks w, w + gridDim.x, ...
-// of the task list (largest first), so a workgroup's stores drain and its next item arrives
-// while it already works on the following one.  Tasks below wg_end[0] are one item for the
-// whole workgroup (bins workgroup and generic); the next item's descriptor is fetched while
-// the current one is processed.  Later tasks hold 4, 8 or 16 items for 64-, 32- or 16-lane
+// One launch runs the whole schedule.  By default the grid has one workgroup per task (the
+// hardware dispatcher balances uneven tasks, largest first); when the plan asks for fewer
+// resident workgroups, workgroup w takes tasks w, w + gridDim.x, ... and fetches the next
+// item's descriptor while it processes the current one.  Tasks below wg_end[0] are one item
+// for the whole workgroup (bins workgroup and generic), tasks below wg_end[1] add up several
+// operations into one output block, later tasks hold 4, 8 or 16 items for 64-, 32- or 16-lane
 // slots.
 // SLICES = false leaves out the 32- and 16-lane slot code (per-lane item descriptors cost
 // registers, hence occupancy); the host launches it for schedules without such items.

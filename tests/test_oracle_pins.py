@@ -6,6 +6,7 @@ that any correct C = A B must satisfy (Sec. II-C definition; Fig. 2/3/4 all redu
 Each pin is chosen so that a plausible slip (dropped term, wrong index base, transposed
 operand, missing zero-initialisation, wrong offset) breaks at least one of them.
 """
+import dataclasses
 import os
 
 import numpy as np
@@ -520,3 +521,94 @@ def test_coo_rejects_out_of_range(oracle):
         with pytest.raises(ValueError):
             oracle.coo_to_csr([3], [3], [1], z, np.array(bad, dtype=np.int32),
                               np.ones(1, dtype=np.float32))
+
+
+# ---------------------------------------------------------------------------------------------
+# one channel of the batched graph-convolution layer (Fig. 7): MatMul, Add, BatchedSpMM
+# ---------------------------------------------------------------------------------------------
+def _layer_inputs(b, n_x, seed, integer=False):
+    rng = np.random.default_rng(seed)
+    if integer:   # small integers: every intermediate is exact in fp32 and fp64 alike
+        X = rng.integers(-3, 4, size=(b.n_b_rows, n_x)).astype(np.float32)
+        W = rng.integers(-2, 3, size=(n_x, b.F)).astype(np.float32)
+        bias = rng.integers(-2, 3, size=b.F).astype(np.float32)
+    else:
+        X = rng.uniform(-1, 1, size=(b.n_b_rows, n_x)).astype(np.float32)
+        W = rng.uniform(-1, 1, size=(n_x, b.F)).astype(np.float32)
+        bias = rng.uniform(-1, 1, size=b.F).astype(np.float32)
+    return X, W, bias
+
+
+@pytest.mark.parametrize("which", [0, 1])
+def test_gcn_channel_against_dense_algebra(oracle, which):
+    b = [W.config2_molecule(graphs=5, F=6), W.random_general(61, F=5, shapes=[(7, 13, 25), (13, 7, 25),
+                                                                              (4, 4, 0), (0, 0, 0)])][which]
+    X, Wt, bias = _layer_inputs(b, 9, 3)
+    Y, T = oracle.gcn_channel(b, X, Wt, bias)
+    for i in range(b.batch):
+        A = _dense_of(b, i)
+        xi = X[int(b.b_row_off[i]):int(b.b_row_off[i]) + int(b.cols[i])].astype(np.float64)
+        want = A @ (xi @ Wt.astype(np.float64) + bias.astype(np.float64))
+        got = Y[int(b.c_row_off[i]):int(b.c_row_off[i]) + int(b.rows[i])]
+        assert np.allclose(got, want, rtol=1e-12, atol=1e-13)
+        # a transposed weight matrix, a dropped bias or a bias added after the SpMM would show
+        assert not np.allclose(got, A @ (xi @ Wt.astype(np.float64)), rtol=1e-3) or A.size == 0 or not A.any()
+        # scale: every stored entry counts with its absolute value (repeated pairs do not cancel)
+        absA = _dense_of(dataclasses.replace(b, values=np.abs(b.values)), i)
+        want_T = absA @ (np.abs(xi) @ np.abs(Wt).astype(np.float64) + np.abs(bias).astype(np.float64))
+        assert np.allclose(T[int(b.c_row_off[i]):int(b.c_row_off[i]) + int(b.rows[i])], want_T,
+                           rtol=1e-12, atol=1e-13)
+
+
+def test_gcn_channel_bias_goes_through_the_adjacency(oracle):
+    """W = 0: every output row is (row sum of A) * bias, not bias itself."""
+    b = W.config5_skewed(graphs=3, F=4, asymmetric=True)
+    X, Wt, bias = _layer_inputs(b, 5, 4)
+    Y, _ = oracle.gcn_channel(b, X, np.zeros_like(Wt), bias)
+    for i in range(b.batch):
+        rs = _dense_of(b, i).sum(axis=1)
+        got = Y[int(b.c_row_off[i]):int(b.c_row_off[i]) + int(b.rows[i])]
+        assert np.allclose(got, rs[:, None] * bias[None, :].astype(np.float64), rtol=1e-12)
+
+
+def test_gcn_channel_identity_weights_reduce_to_the_plain_product(oracle):
+    """W = I, bias = 0: the layer is C = A X, bit for bit the forward oracle."""
+    b = W.config2_molecule(graphs=6, F=8)
+    Y, _ = oracle.gcn_channel(b, b.B, np.eye(8, dtype=np.float32), np.zeros(8, dtype=np.float32))
+    C, _ = oracle.forward_batch(b)
+    assert np.array_equal(Y, C, equal_nan=True)
+
+
+def test_gcn_channel_exact_integers_equal_the_three_step_pipeline(oracle):
+    """Integer-valued inputs: B = XW + bias is exact in fp32, so feeding it to the forward
+    oracle as an fp32 matrix gives the same bits as the fp64 pipeline."""
+    b = W.config3_multichannel(graphs=5, F=6, normalise=False)
+    X, Wt, bias = _layer_inputs(b, 7, 8, integer=True)
+    Y, _ = oracle.gcn_channel(b, X, Wt, bias)
+    B32 = (X @ Wt + bias[None, :]).astype(np.float32)
+    C, _ = oracle.forward(b.rows, b.cols, b.nnz, b.rpt_off, b.nz_off, b.b_row_off, b.c_row_off,
+                          b.rpt, b.colids, b.values, B32, b.n_c_rows)
+    assert np.array_equal(Y, C, equal_nan=True)
+
+
+def test_gcn_channels_accumulate_like_the_layer(oracle):
+    """Y = sum over channels of A_ch (X W_ch + bias_ch) (Fig. 7 last line), channel by channel."""
+    chans = 3
+    # the same graphs in every channel, with channel-specific edge weights
+    bs = [W.config2_molecule(seed=70, graphs=4, F=5) for _ in range(chans)]
+    rng = np.random.default_rng(5)
+    for c, bb in enumerate(bs):
+        bb.values = (bb.values * rng.uniform(0.5, 1.5, size=bb.values.shape)).astype(np.float32)
+    X = rng.uniform(-1, 1, size=(bs[0].n_b_rows, 6)).astype(np.float32)
+    Ws = [rng.uniform(-1, 1, size=(6, 5)).astype(np.float32) for _ in range(chans)]
+    biases = [rng.uniform(-1, 1, size=5).astype(np.float32) for _ in range(chans)]
+    Y = T = None
+    for c in range(chans):
+        Y, T = oracle.gcn_channel(bs[c], X, Ws[c], biases[c], Y, T)
+    b0 = bs[0]
+    for i in range(b0.batch):
+        xi = X[int(b0.b_row_off[i]):int(b0.b_row_off[i]) + int(b0.cols[i])].astype(np.float64)
+        want = sum(_dense_of(bs[c], i) @ (xi @ Ws[c].astype(np.float64) + biases[c].astype(np.float64))
+                   for c in range(chans))
+        got = Y[int(b0.c_row_off[i]):int(b0.c_row_off[i]) + int(b0.rows[i])]
+        assert np.allclose(got, want, rtol=1e-12, atol=1e-13)
