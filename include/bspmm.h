@@ -57,7 +57,9 @@ extern "C" {
 #define BSPMM_ESTATE    (-5)  /* plan cannot do this (dry-run plan, transposed unsupported)   */
 #define BSPMM_EBADCSR   (-6)  /* bspmm_validate found a malformed CSR on the device           */
 #define BSPMM_ETOOBIG   (-7)  /* operations summed into one block: more than 8 of them, or
-                                 their arrays do not fit the on-chip memory together           */
+                                 their arrays do not fit the on-chip memory together; with
+                                 front_features: an operation too large for a whole-workgroup
+                                 item                                                          */
 
 /* bspmm_options.flags */
 #define BSPMM_DRY_RUN          1u  /* schedule only: touch no device, run calls return ESTATE */
@@ -148,6 +150,13 @@ typedef struct bspmm_options {
                                   target_workgroups, N > 0 = always cap at N, -1 = never cut   */
     int32_t  resident_workgroups; /* N > 0: persistent launch of N workgroups that stride
                                   through the tasks; 0 = one workgroup per task (default)      */
+    int32_t  front_features;   /* n_X > 0: shape the forward schedule for bspmm_run_gcn with an
+                                  n_X-column layer input (whole workgroups, feature tiles in
+                                  multiples of 16); needs F % 16 == 0 and n_X % 4 == 0 (EINVAL),
+                                  not combined with BSPMM_ACCUMULATE, BSPMM_SPLIT_HUB_ROWS or
+                                  lds_pad (EINVAL); ETOOBIG when an operation and its dense tile
+                                  do not fit LDS at any tile width                              */
+    int32_t  reserved_;        /* 0 */
 } bspmm_options;
 
 /* What the scheduler decided; index 0 = forward, 1 = transposed. */
@@ -211,6 +220,21 @@ int bspmm_create(bspmm_plan** plan, const bspmm_batch* b, int32_t F,
  */
 int bspmm_run(bspmm_plan* plan, const float* B, float* C, int64_t ldb, int64_t ldc,
               void* stream);
+
+/*
+ * One channel of the batched graph-convolution layer in ONE launch (Fig. 7: U = MatMul(Xr, W),
+ * B = Add(bias, U), C = BatchedSpMM(A_list, B)):  Y_i = A_i . (X_i . W + bias), or with
+ * accumulate != 0  Y_i += A_i . (X_i . W + bias)  (the ElementWiseAdd over channels, one launch
+ * per channel, no intermediate U, B or C in memory).  X is the packed DEVICE feature matrix
+ * (cols_i rows of n_X = options.front_features floats at row b_row_off[i], leading dimension
+ * ldx >= n_X), W the DEVICE n_X x F weight matrix (leading dimension ldw >= F), bias F DEVICE
+ * floats, Y indexed like C.  The dense part runs on the matrix cores in fp32
+ * (v_mfma_f32_16x16x4_f32) and its result goes straight into LDS; B_i never leaves the chip.  X, W, Y must be
+ * 16-byte aligned with ldx, ldw, ldy multiples of 4 (EINVAL).  ESTATE for plans created
+ * without front_features.
+ */
+int bspmm_run_gcn(bspmm_plan* plan, const float* X, int64_t ldx, const float* W, int64_t ldw,
+                  const float* bias, float* Y, int64_t ldy, int32_t accumulate, void* stream);
 
 /*
  * G_i = A_i^T . dY_i for every operation (backward product with respect to the dense input).

@@ -48,7 +48,8 @@ class bspmm_options(ctypes.Structure):
                 ("max_tile", ctypes.c_int32), ("target_workgroups", ctypes.c_int32),
                 ("compute_units", ctypes.c_int32), ("lds_pad", ctypes.c_int32),
                 ("max_passes", ctypes.c_int32), ("generic_rows", ctypes.c_int32),
-                ("wg_passes", ctypes.c_int32), ("resident_workgroups", ctypes.c_int32)]
+                ("wg_passes", ctypes.c_int32), ("resident_workgroups", ctypes.c_int32),
+                ("front_features", ctypes.c_int32), ("reserved_", ctypes.c_int32)]
 
 
 class bspmm_info(ctypes.Structure):
@@ -74,7 +75,7 @@ class bspmm_item(ctypes.Structure):
 EXPORTS = ["bspmm_workspace_bytes", "bspmm_create", "bspmm_run", "bspmm_run_transposed",
            "bspmm_export_transposed", "bspmm_validate", "bspmm_plan_info", "bspmm_plan_items",
            "bspmm_destroy", "bspmm_strerror", "bspmm_last_hip_error",
-           "bspmm_workspace_bytes_coo", "bspmm_create_coo", "bspmm_export_csr"]
+           "bspmm_workspace_bytes_coo", "bspmm_create_coo", "bspmm_export_csr", "bspmm_run_gcn"]
 
 _lib = None
 
@@ -115,6 +116,8 @@ def lib():
                                        ctypes.c_int32, ctypes.POINTER(bspmm_options), vp,
                                        ctypes.c_size_t, vp]
         L.bspmm_export_csr.argtypes = [vp, vp, vp, vp, vp]
+        L.bspmm_run_gcn.argtypes = [vp, vp, ctypes.c_int64, vp, ctypes.c_int64, vp, vp,
+                                    ctypes.c_int64, ctypes.c_int32, vp]
         L.bspmm_plan_info.argtypes = [vp, ctypes.POINTER(bspmm_info)]
         L.bspmm_plan_items.argtypes = [vp, ctypes.c_int32, ctypes.POINTER(bspmm_item),
                                        ctypes.c_int32, _i32p]
@@ -267,6 +270,13 @@ def bspmm_run(plan: int, B, C, ldb: int, ldc: int, stream=None) -> None:
            "bspmm_run")
 
 
+def bspmm_run_gcn(plan: int, X, ldx: int, W, ldw: int, bias, Y, ldy: int, accumulate: bool = False,
+                  stream=None) -> None:
+    _check(lib().bspmm_run_gcn(plan, _ptr(X), int(ldx), _ptr(W), int(ldw), _ptr(bias), _ptr(Y),
+                               int(ldy), 1 if accumulate else 0, _stream_handle(stream)),
+           "bspmm_run_gcn")
+
+
 def bspmm_run_transposed(plan: int, dY, G, ldy: int, ldg: int, stream=None) -> None:
     _check(lib().bspmm_run_transposed(plan, _ptr(dY), _ptr(G), int(ldy), int(ldg),
                                       _stream_handle(stream)), "bspmm_run_transposed")
@@ -360,6 +370,12 @@ class Plan:
         bspmm_run(self.handle, B, C, B.stride(0) if B.dim() == 2 else self.F,
                   C.stride(0) if C.dim() == 2 else self.F, stream)
         return C
+
+    def run_gcn(self, X, W, bias, Y, accumulate: bool = False, stream=None):
+        """Y (+)= A (X W + bias) in one launch (plan created with ``front_features``)."""
+        bspmm_run_gcn(self.handle, X, X.stride(0), W, W.stride(0), bias, Y, Y.stride(0),
+                      accumulate, stream)
+        return Y
 
     def run_transposed(self, dY, G, stream=None):
         bspmm_run_transposed(self.handle, dY, G, dY.stride(0), G.stride(0), stream)

@@ -15,6 +15,8 @@
 namespace bspmm {
 hipError_t launch_bspmm(const LaunchParams& P, int grid, int lds_bytes, bool vec4, bool slices,
                         bool hubs, hipStream_t stream);
+hipError_t launch_bspmm_gcn(const LaunchParams& P, int grid, int lds_bytes, bool accumulate,
+                            hipStream_t stream);
 hipError_t launch_build_transpose(const OpRecord* ops, int batch, int lds_bytes,
                                   const int32_t* rpt, const int32_t* colids,
                                   const float* values, int32_t* rpt_t, int32_t* colids_t,
@@ -202,10 +204,14 @@ int plan_host(bspmm_plan& p, const bspmm_batch* b, int32_t F, const Knobs& kn)
     if (ck == 2 || (ck == 1 && !kn.accumulate)) return BSPMM_EOVERLAP;
     p.transposed_supported = bk == 0 || (bk == 1 && kn.accumulate);
 
+    if (kn.front > 0 && (F % 16 != 0 || kn.front % 4 != 0 || kn.accumulate || kn.hubs || kn.pad != 0))
+        return BSPMM_EINVAL;
     p.sched[0] = make_schedule(f, F, kn);
     if (p.sched[0].error) return p.sched[0].error;
     if (p.transposed_supported) {
-        p.sched[1] = make_schedule(t, F, kn);
+        Knobs kt = kn;
+        kt.front = 0;                     // the layer input is a forward-only guest
+        p.sched[1] = make_schedule(t, F, kt);
         if (p.sched[1].error) {          // the forward product still works
             p.sched[1] = Schedule();
             p.transposed_supported = false;
@@ -341,6 +347,11 @@ int run_direction(bspmm_plan* p, int d, const float* in, float* out, int64_t ld_
     P.fused_stride = sc.fused_stride;
     P.lds_floats = p->knobs.lds_words;
     P.pad = p->knobs.pad;
+    P.w = nullptr;
+    P.bias = nullptr;
+    P.ld_w = 0;
+    P.n_front = 0;
+    P.accumulate = 0;
 #ifdef BSPMM_TRACE
     P.trace = g_trace;
 #endif
@@ -550,6 +561,47 @@ int upload_plan(bspmm_plan* p, const bspmm_options* options, void* workspace,
     return BSPMM_OK;
 }
 
+// One channel of the graph-convolution layer: the forward schedule with the dense tile made
+// on chip from X_i, W and bias.
+int run_gcn(bspmm_plan* p, const float* X, int64_t ldx, const float* W, int64_t ldw,
+            const float* bias, float* Y, int64_t ldy, int accumulate, hipStream_t s)
+{
+    const Schedule& sc = p->sched[0];
+    if (sc.grid == 0) return BSPMM_OK;
+    const int nx = p->knobs.front;
+    auto misaligned = [](const void* q) { return (reinterpret_cast<uintptr_t>(q) & 15) != 0; };
+    if (!X || !W || !bias || !Y || ldx < nx || ldw < p->F || ldy < p->F) return BSPMM_EINVAL;
+    if (ldx % 4 || ldw % 4 || ldy % 4 || misaligned(X) || misaligned(W) || misaligned(Y))
+        return BSPMM_EINVAL;
+    LaunchParams P;
+    P.items = reinterpret_cast<const WorkItem*>(p->ws + p->lay.items[0]);
+    P.rpt = p->rpt;
+    P.colids = p->colids;
+    P.values = p->values;
+    P.in = X;
+    P.out = Y;
+    P.ld_in = ldx;
+    P.ld_out = ldy;
+    for (int r = 0; r < kRanges; ++r) {
+        P.wg_end[r] = sc.wg_end[r];
+        P.item_base[r] = sc.item_base[r];
+    }
+    P.n_tasks = sc.grid;
+    P.fused_stride = sc.fused_stride;
+    P.lds_floats = p->knobs.lds_words;
+    P.pad = 0;
+    P.w = W;
+    P.bias = bias;
+    P.ld_w = ldw;
+    P.n_front = nx;
+    P.accumulate = accumulate ? 1 : 0;
+#ifdef BSPMM_TRACE
+    P.trace = g_trace;
+#endif
+    hipError_t e = launch_bspmm_gcn(P, sc.grid, p->knobs.lds_words * 4, accumulate != 0, s);
+    return e == hipSuccess ? BSPMM_OK : hip_fail(e);
+}
+
 }  // namespace
 
 extern "C" {
@@ -665,6 +717,14 @@ int bspmm_run(bspmm_plan* plan, const float* B, float* C, int64_t ldb, int64_t l
     if (!plan) return BSPMM_EINVAL;
     if (plan->dry) return BSPMM_ESTATE;
     return run_direction(plan, 0, B, C, ldb, ldc, static_cast<hipStream_t>(stream));
+}
+
+int bspmm_run_gcn(bspmm_plan* plan, const float* X, int64_t ldx, const float* W, int64_t ldw,
+                  const float* bias, float* Y, int64_t ldy, int32_t accumulate, void* stream)
+{
+    if (!plan) return BSPMM_EINVAL;
+    if (plan->dry || plan->knobs.front <= 0 || plan->coo_direct) return BSPMM_ESTATE;
+    return run_gcn(plan, X, ldx, W, ldw, bias, Y, ldy, accumulate, static_cast<hipStream_t>(stream));
 }
 
 int bspmm_run_transposed(bspmm_plan* plan, const float* dY, float* G, int64_t ldy, int64_t ldg,
@@ -789,7 +849,7 @@ const char* bspmm_strerror(int code)
         case BSPMM_EOVERLAP: return "output blocks overlap";
         case BSPMM_ESTATE: return "operation not available on this plan";
         case BSPMM_EBADCSR: return "malformed CSR arrays on the device";
-        case BSPMM_ETOOBIG: return "operations summed into one block do not fit on chip together";
+        case BSPMM_ETOOBIG: return "operations do not fit on chip (those summed into one block together, or one with the fused front)";
         default: return "unknown error";
     }
 }

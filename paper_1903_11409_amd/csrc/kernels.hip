@@ -98,7 +98,7 @@ struct Split {
 // first trip of every copy is issued before anything is waited for: one round trip stages a
 // typical molecule-sized item completely; larger items finish in unrolled leftover loops.
 // ---------------------------------------------------------------------------------------
-template <int S, int VEC, bool HUBS>
+template <int S, int VEC, bool HUBS, bool WITH_TILE = true>
 __device__ __forceinline__ void stage_item(const LaunchParams& P, const WorkItem& it, int* sm,
                                            int lane)
 {
@@ -132,7 +132,7 @@ __device__ __forceinline__ void stage_item(const LaunchParams& P, const WorkItem
     // packed without padding, whole wavefronts copy 1 KiB at a time straight from global
     // memory into LDS (lane i lands at base + 16*i): no staging registers, and the entire
     // tile is in flight at once instead of four rows per lane group.
-    const bool direct = VEC == 4 && S >= 64 && P.pad == 0 && (sp.nvec & (sp.nvec - 1)) == 0;
+    const bool direct = WITH_TILE && VEC == 4 && S >= 64 && P.pad == 0 && (sp.nvec & (sp.nvec - 1)) == 0;
     if (direct) {
         const int sh = ilog2(sp.nvec);
         const int total = k << sh;                       // float4 in the tile
@@ -154,7 +154,7 @@ __device__ __forceinline__ void stage_item(const LaunchParams& P, const WorkItem
             }
         }
     }
-    const bool col_ok = !direct && sp.l < sp.nvec;
+    const bool col_ok = WITH_TILE && !direct && sp.l < sp.nvec;
     const int r0 = sp.g, r1 = sp.g + step, r2 = sp.g + 2 * step, r3 = sp.g + 3 * step;
     const float* colp = src + sp.l * VEC;
     VT t0 = Vec<VEC>::zero(), t1 = Vec<VEC>::zero(), t2 = Vec<VEC>::zero(), t3 = Vec<VEC>::zero();
@@ -190,7 +190,7 @@ __device__ __forceinline__ void stage_item(const LaunchParams& P, const WorkItem
         cv[p] = make_int2((unsigned)cc0 < (unsigned)k ? cc0 : 0, __float_as_int(aa0));
         if (q < nnz) cv[q] = make_int2((unsigned)cc1 < (unsigned)k ? cc1 : 0, __float_as_int(aa1));
     }
-    for (int v = sp.l; !direct && v < sp.nvec; v += sp.g_lanes) {
+    for (int v = sp.l; WITH_TILE && !direct && v < sp.nvec; v += sp.g_lanes) {
         const float* cp = src + v * VEC;
         float* bp = bs + v * VEC;
         for (int row = (v == sp.l ? sp.g + 4 * step : sp.g); row < k; row += 4 * step) {
@@ -299,15 +299,17 @@ __device__ __forceinline__ void hub_row(int p0, int p1, Entry load_entry, const 
 // ---------------------------------------------------------------------------------------
 // row gather-FMA from LDS and store
 // ---------------------------------------------------------------------------------------
-template <int S, int VEC, bool HUBS>
+// `tile_shift` moves the dense tile behind a guest that sits at its usual place (the layer
+// input of the fused front); ACC adds the sums to the output instead of overwriting it.
+template <int S, int VEC, bool HUBS, bool ACC = false>
 __device__ __forceinline__ void compute_staged(const LaunchParams& P, const WorkItem& it,
-                                               int* sm, int lane)
+                                               int* sm, int lane, int tile_shift = 0)
 {
     using V = Vec<VEC>;
     constexpr bool kHubs = HUBS && S == kThreads;
     const StagedLayout L = staged_layout(it.m, it.k, it.nnz, it.fw, P.pad, kHubs);
     const int2* cv = reinterpret_cast<const int2*>(sm + L.cv_off);
-    const float* bs = reinterpret_cast<const float*>(sm + L.b_off);
+    const float* bs = reinterpret_cast<const float*>(sm + L.b_off + tile_shift);
     const Split<S, VEC> sp(it.fw, lane);
     float* __restrict__ dst = P.out + it.out_row_off * P.ld_out + it.f0;
     // hub rows need one vector per lane (always true on the float4 path)
@@ -341,6 +343,14 @@ __device__ __forceinline__ void compute_staged(const LaunchParams& P, const Work
             for (; p < p1; ++p) {
                 const int2 e = cv[p];
                 V::fma(acc, __int_as_float(e.y), load_vec<VEC>(bcol + e.x * L.stride));
+            }
+            if constexpr (ACC) {
+                static_assert(VEC == 4, "accumulating stores are built for the float4 path");
+                const float4 old = load_vec<4>(dst + (int64_t)r * P.ld_out + v * VEC);
+                acc.x += old.x;
+                acc.y += old.y;
+                acc.z += old.z;
+                acc.w += old.w;
             }
             store_out<VEC>(dst + (int64_t)r * P.ld_out + v * VEC, acc);
         }
@@ -858,6 +868,95 @@ validate_coo_kernel(const OpRecord* __restrict__ ops, const int32_t* __restrict_
 }
 
 // ---------------------------------------------------------------------------------------
+// One channel of the batched graph-convolution layer in one launch (Fig. 7: MatMul, Add,
+// BatchedSpMM): Y_i (+)= A_i (X_i W + bias).  A workgroup stages A_i, computes the dense tile
+// B = X_i W[:, f0:f0+fw] + bias on the matrix cores straight into the tile's place in LDS, and
+// then runs the ordinary row gather over it: U, B and the per-channel C never exist in memory.
+// The dense part is v_mfma_f32_16x16x4_f32 (fp32 in, fp32 accumulate).  The tile is cut into
+// 16 x 16 blocks dealt to the four wavefronts.  Operand layout of the instruction: lane l
+// supplies A[l % 16][l / 16] and B[l / 16][l % 16] and receives rows 4*(l / 16) .. +3 of column
+// l % 16.  A lane reads four consecutive k of its X row with one 16-byte load and feeds them to
+// four instructions together with the weights of the same four k, so the k order inside a
+// step differs from memory order for both operands alike, which leaves the product unchanged.
+// Both operands come from global memory: X_i is read once per column tile, W by every
+// workgroup of a column tile (L2).  The loads of a wavefront's first block do not depend on
+// anything and are requested before the CSR staging is waited for.
+// Needs F % 16 == 0, n_front % 4 == 0 and 16-byte aligned operands (checked on the host).
+// ---------------------------------------------------------------------------------------
+template <bool ACC>
+__global__ void __launch_bounds__(kThreads) bspmm_gcn_kernel(const LaunchParams P)
+{
+    extern __shared__ __align__(16) int sm[];
+    typedef float mfma4 __attribute__((ext_vector_type(4)));
+    const int tid = threadIdx.x;
+    const WorkItem it = P.items[blockIdx.x];
+    if (it.nrows <= 0) return;
+    const int nx = P.n_front;
+    const int wave = tid >> 6, wl = tid & 63;
+    const int col = wl & 15, g = wl >> 4;
+    const int nb_count = it.fw >> 4;
+    const int blocks = ((it.k + 15) >> 4) * nb_count;
+    const float* wcol0 = P.w + it.f0 + col;
+    const float* x0 = P.in + it.in_row_off * P.ld_in + 4 * g;
+
+    // operands of 64 k of one block: 4 float4 of the lane's X row, 16 weights of its column
+    auto load_chunk = [&](int mb, int nb, int k0, float4 (&xa)[4], float (&wr)[16]) {
+        const int arow = min(16 * mb + col, it.k - 1);     // rows past the end repeat the last
+        const float* xrow = x0 + (int64_t)arow * P.ld_in + k0;
+        const float* wcol = wcol0 + 16 * nb;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int kk = k0 + 16 * j + 4 * g;
+            xa[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (kk < nx) xa[j] = *reinterpret_cast<const float4*>(xrow + 16 * j);
+#pragma unroll
+            for (int s4 = 0; s4 < 4; ++s4)
+                wr[4 * j + s4] = kk < nx ? wcol[(int64_t)(kk + s4) * P.ld_w] : 0.f;   // nx % 4 == 0
+        }
+    };
+
+    float4 xq[4];
+    float wq[16];
+    if (wave < blocks) load_chunk(wave / nb_count, wave % nb_count, 0, xq, wq);
+
+    stage_item<kThreads, 4, false, false>(P, it, sm, tid);    // A_i only: the tile is made here
+
+    const StagedLayout L = staged_layout(it.m, it.k, it.nnz, it.fw, 0, false);
+    float* bt = reinterpret_cast<float*>(sm + L.b_off);      // k x fw, row stride fw
+    for (int blk = wave; blk < blocks; blk += kThreads / 64) {
+        const int mb = blk / nb_count, nb = blk - mb * nb_count;
+        const float bv = P.bias[it.f0 + 16 * nb + col];
+        mfma4 acc = {bv, bv, bv, bv};
+        for (int k0 = 0; k0 < nx; k0 += 64) {
+            float4 xa[4];
+            float wr[16];
+            if (blk == wave && k0 == 0) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) xa[q] = xq[q];
+#pragma unroll
+                for (int q = 0; q < 16; ++q) wr[q] = wq[q];
+            } else {
+                load_chunk(mb, nb, k0, xa, wr);
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(xa[j].x, wr[4 * j + 0], acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(xa[j].y, wr[4 * j + 1], acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(xa[j].z, wr[4 * j + 2], acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(xa[j].w, wr[4 * j + 3], acc, 0, 0, 0);
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int row = 16 * mb + 4 * g + i;
+            if (row < it.k) bt[row * it.fw + 16 * nb + col] = acc[i];
+        }
+    }
+    __syncthreads();
+    compute_staged<kThreads, 4, false, ACC>(P, it, sm, tid);
+}
+
+// ---------------------------------------------------------------------------------------
 // Direct product for COO / SparseTensor operands (Fig. 3 with the output staged on chip as in
 // Fig. 5(a,b)): the item's output tile lives in LDS; a group of L lanes takes one stored entry
 // at a time (L = the tile's vectors per row rounded up to a power of two, at most 64), reads
@@ -1084,6 +1183,17 @@ hipError_t launch_bspmm(const LaunchParams& P, int grid, int lds_bytes, bool vec
     if (grid <= 0) return hipSuccess;
     hipLaunchKernelGGL(kernel_variant(vec4, slices, hubs), dim3(grid), dim3(kThreads), lds_bytes,
                        stream, P);
+    return hipGetLastError();
+}
+
+hipError_t launch_bspmm_gcn(const LaunchParams& P, int grid, int lds_bytes, bool accumulate,
+                            hipStream_t stream)
+{
+    if (grid <= 0) return hipSuccess;
+    if (accumulate)
+        hipLaunchKernelGGL(bspmm_gcn_kernel<true>, dim3(grid), dim3(kThreads), lds_bytes, stream, P);
+    else
+        hipLaunchKernelGGL(bspmm_gcn_kernel<false>, dim3(grid), dim3(kThreads), lds_bytes, stream, P);
     return hipGetLastError();
 }
 

@@ -61,6 +61,13 @@ struct LaunchParams {
     int32_t fused_stride; // item slots per fused task
     int32_t lds_floats;   // LDS per workgroup, in 4-byte words
     int32_t pad;          // words added to every staged dense row
+    // fused front of the graph-convolution layer (bspmm_run_gcn): `in` is then the layer input
+    // X with n_front columns, and the dense tile is X_i . W + bias computed on chip
+    const float* w;       // n_front x F weights
+    const float* bias;    // F floats
+    int64_t ld_w;
+    int32_t n_front;
+    int32_t accumulate;   // add to the output instead of overwriting it
 #ifdef BSPMM_TRACE
     long long* trace;     // development builds only: 8 timestamps per workgroup
 #endif

@@ -94,7 +94,7 @@ bool fits_slot(const DirOps& o, int i, int tile, int F, int vec, int lanes, int 
 Choice choose(const DirOps& o, int i, int F, int vec, const std::vector<int>& cand, size_t first,
               const Knobs& kn, bool allow_small)
 {
-    const int forced = kn.force_bin;
+    const int forced = kn.front > 0 ? BSPMM_BIN_WORKGROUP : kn.force_bin;   // the fused front runs on whole workgroups
     if (forced == BSPMM_BIN_GENERIC) return {BSPMM_BIN_GENERIC, cand[0]};
     if (forced >= 0) {
         for (size_t c = first; c < cand.size(); ++c)
@@ -125,6 +125,7 @@ int64_t item_cost(const DirOps& o, int i, int nrows, int fw, bool staged)
 struct Sink {
     std::vector<Draft>* out = nullptr;     // null: count only
     int per_range[kRanges] = {0, 0, 0, 0, 0};
+    int generic = 0;                       // items that read their operands from global memory
     const std::vector<int>* block_of_op = nullptr;   // dense-input block index of every operation
     int tiles_per_block = 1;               // group id = block * tiles_per_block + f0 / tile_unit
     int tile_unit = 4;
@@ -132,6 +133,7 @@ struct Sink {
              int fused)
     {
         per_range[fused >= 0 ? 1 : bin_range(bin)]++;
+        generic += bin == BSPMM_BIN_GENERIC;
         if (!out) return;
         const int gid = fused >= 0 ? -1 : (*block_of_op)[i] * tiles_per_block + f0 / tile_unit;
         out->push_back({i, bin, row0, nrows, f0, fw, staged,
@@ -165,7 +167,9 @@ void draft_op(const DirOps& o, int i, int F, int vec, const Choice& ch, const Kn
             return (o.m[i] + kn.generic_rows - 1) / kn.generic_rows;
         };
         const int full = F / tile, tail = F % tile;
-        sink.per_range[bin_range(ch.bin)] += (full ? full * per_tile(tile) : 0) + (tail ? per_tile(tail) : 0);
+        const int n = (full ? full * per_tile(tile) : 0) + (tail ? per_tile(tail) : 0);
+        sink.per_range[bin_range(ch.bin)] += n;
+        sink.generic += ch.bin == BSPMM_BIN_GENERIC ? n : 0;
         return;
     }
     for (int f0 = 0; f0 < F; f0 += tile) {
@@ -354,6 +358,11 @@ Knobs resolve_knobs(const bspmm_options* o)
     k.hubs = (o->flags & BSPMM_SPLIT_HUB_ROWS) != 0;
     k.accumulate = (o->flags & BSPMM_ACCUMULATE) != 0;
     k.coo_direct = (o->flags & BSPMM_COO_DIRECT) != 0;
+    if (o->front_features > 0) {   // the matrix-core blocks of the fused front are 16 columns wide
+        k.front = o->front_features;
+        k.max_tile = std::max(16, k.max_tile / 16 * 16);
+        k.min_tile = std::min(std::max(16, (k.min_tile + 15) / 16 * 16), k.max_tile);
+    }
     return k;
 }
 
@@ -373,7 +382,7 @@ Schedule make_schedule(const DirOps& ops, int F, const Knobs& kn_in)
     // at once); a launch that fits is latency-bound and every item is fastest with a whole
     // workgroup staging it.  A forced bin overrides this.
     const int fixed_cap = kn.wg_passes > 0 ? kn.wg_passes : 0;
-    bool allow_small = kn.force_bin >= 0;
+    bool allow_small = kn.force_bin >= 0 && kn.front == 0;
     const std::vector<std::vector<int>> outs = output_groups(ops);
     size_t most_members = 1;
     for (const auto& g : outs) most_members = std::max(most_members, g.size());
@@ -396,14 +405,14 @@ Schedule make_schedule(const DirOps& ops, int F, const Knobs& kn_in)
                 break;
             }
         }
-        if (allow_small || wgs <= kn.capacity_wgs) break;
+        if (allow_small || wgs <= kn.capacity_wgs || kn.front > 0) break;
         allow_small = true;
     }
     s.tile = cand[chosen];
     // still too few workgroups at the narrowest tile: the batch is small, its time is set by
     // the slowest workgroup, so cut multi-pass workgroup items into row ranges
     int cap = fixed_cap;
-    if (kn.wg_passes == 0 && wgs < kn.target_wgs) {
+    if (kn.wg_passes == 0 && wgs < kn.target_wgs && kn.front == 0) {
         for (cap = 4; cap >= 1; cap /= 2) {
             wgs = workgroups_of(chosen, cap, allow_small);
             if (wgs >= kn.target_wgs || cap == 1) break;
@@ -412,6 +421,14 @@ Schedule make_schedule(const DirOps& ops, int F, const Knobs& kn_in)
     if (!fits) {   // a set of summed operations does not fit LDS together even at 4 columns
         s.error = BSPMM_ETOOBIG;
         return s;
+    }
+    if (kn.front > 0) {   // every operation must hold its layer input on chip
+        Sink probe;
+        draft_all(ops, F, vec, cand, chosen, kn, cap, allow_small, outs, &fits, probe);
+        if (probe.per_range[1] || probe.generic) {
+            s.error = BSPMM_ETOOBIG;
+            return s;
+        }
     }
     // the draft that is kept
     const std::vector<int> block_of_op = input_blocks(ops);

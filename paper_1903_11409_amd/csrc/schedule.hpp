@@ -33,6 +33,8 @@ struct Knobs {
     int capacity_wgs_slices = 1024;   // same for the kernel variant with 32/16-lane slots
     bool accumulate = false;  // operations naming one output block are summed (else an error)
     bool hubs = false;        // split hub rows across the workgroup (reserves LDS for it)
+    int front = 0;            // > 0: columns of the layer input of bspmm_run_gcn (whole workgroups,
+                              // tiles in multiples of 16 columns)
     bool coo_direct = false;  // COO plans: run the direct kernel instead of converting to CSR
     int persistent_wgs = 0;   // > 0: launch only this many workgroups and let them stride
 };

@@ -1,0 +1,177 @@
+"""GPU parity for the fused front of the batched graph-convolution layer (Fig. 7: MatMul, Add,
+BatchedSpMM in one launch per channel): bspmm_run_gcn through the C ABI against the CPU oracle's
+three steps in fp64.
+
+Bar: |Y_gpu - Y_ref| <= tol * T per element with T = sum_p |a_p| (sum_t |X||W| + |bias|) and
+tol = max(1e-5, (n_X + d_max + 2) * 2^-23): an output element is a chain of n_X fused
+multiply-adds on the matrix cores, one add of the bias and d row-gather FMAs, each rounding to
+fp32 (2^-24 relative), so the worst case is (n_X + d + 1) * 2^-24 * T; the factor 2 covers the
+different association inside the matrix instruction.  Exactly 0 where T == 0.
+"""
+import numpy as np
+import pytest
+
+from paper_1903_11409_amd import bspmm as K
+from paper_1903_11409_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+SENTINEL = -12345.0
+
+
+@pytest.fixture(scope="module")
+def torch_cuda():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    K.lib()   # raises if the HIP library has not been built: no fallback
+    return torch
+
+
+def _layer(b, n_x, seed, channels=1):
+    rng = np.random.default_rng(seed)
+    X = rng.uniform(-1, 1, size=(b.n_b_rows, n_x)).astype(np.float32)
+    Ws = [rng.uniform(-1, 1, size=(n_x, b.F)).astype(np.float32) / np.float32(np.sqrt(n_x))
+          for _ in range(channels)]
+    biases = [rng.uniform(-1, 1, size=b.F).astype(np.float32) for _ in range(channels)]
+    return X, Ws, biases
+
+
+def _owned(off, length, n):
+    m = np.zeros(n, dtype=bool)
+    for o, l in zip(off, length):
+        m[int(o):int(o) + int(l)] = True
+    return m
+
+
+def _assert_close(got, ref, T, owned, tol, what):
+    got = got.astype(np.float64)
+    assert np.all(got[~owned] == SENTINEL), f"{what}: rows outside every operation were written"
+    g, r, t = got[owned], ref[owned], T[owned]
+    assert not np.any(np.isnan(g)), f"{what}: NaN in output"
+    err = np.abs(g - r)
+    bad = err > tol * t
+    assert not np.any(bad), (f"{what}: {int(bad.sum())} elements beyond {tol:.1e}*T, worst ratio "
+                             f"{float((err / np.maximum(t, 1e-300)).max()):.3e}")
+    assert np.all(g[t == 0.0] == 0.0), f"{what}: nonzero where nothing contributes"
+
+
+def _tol(b, n_x):
+    dmax = max((int(np.diff(b.op_csr(i)[0]).max()) if int(b.rows[i]) else 0) for i in range(b.batch))
+    return max(1e-5, (n_x + dmax + 2) * 2.0 ** -23)
+
+
+def _run_and_check(torch, oracle, b, n_x, seed=1, what="", **kw):
+    print(f"gcn case {what or b.name}: batch={b.batch} F={b.F} n_X={n_x} {kw}", flush=True)
+    X, Ws, biases = _layer(b, n_x, seed)
+    plan = K.Plan(b, options=K.make_options(front_features=n_x, **kw))
+    Xd, Wd, bd = (torch.from_numpy(a).cuda() for a in (X, Ws[0], biases[0]))
+    Yd = torch.full((b.n_c_rows, b.F), SENTINEL, dtype=torch.float32, device="cuda")
+    plan.run_gcn(Xd, Wd, bd, Yd)
+    torch.cuda.synchronize()
+    ref, T = oracle.gcn_channel(b, X, Ws[0], biases[0])
+    _assert_close(Yd.cpu().numpy(), ref, T, _owned(b.c_row_off, b.rows, b.n_c_rows), _tol(b, n_x),
+                  what or b.name)
+    return plan
+
+
+@pytest.mark.parametrize("maker,n_x", [
+    (lambda: W.config1_tiny(), 64),
+    (lambda: W.config2_molecule(), 64),             # the headline batch as a layer
+    (lambda: W.config2_molecule(F=64), 76),         # n_X not a multiple of 16 or 64
+    (lambda: W.config2_molecule(F=256), 128),
+    (lambda: W.config3_multichannel(), 32),         # channels sharing their input block
+    (lambda: W.config4_wide(F=512), 64),
+    (lambda: W.random_general(55, F=64, shapes=[(200, 180, 1500), (150, 150, 900), (12, 300, 80)] * 3), 16),
+])
+def test_layer_channel_configurations(torch_cuda, oracle, maker, n_x):
+    b = maker()
+    lds = {}
+    if b.name == "general":
+        lds = {"lds_bytes": 65536}                 # operations of a few hundred rows
+    _run_and_check(torch_cuda, oracle, b, n_x, **lds)
+
+
+@pytest.mark.parametrize("n_x", [4, 8, 20, 60, 64, 68, 132, 256])
+def test_input_widths_and_ragged_operations(torch_cuda, oracle, n_x):
+    b = W.random_general(101, F=48, shapes=[(9, 5, 40), (5, 9, 40), (30, 30, 0), (1, 1, 1),
+                                            (0, 0, 0), (17, 17, 60), (40, 33, 300), (1, 64, 64),
+                                            (64, 1, 64)], shuffle_blocks=True)
+    _run_and_check(torch_cuda, oracle, b, n_x, seed=n_x)
+
+
+@pytest.mark.parametrize("kw", [{"max_tile": 16}, {"max_tile": 64}, {"min_tile": 128, "lds_bytes": 65536},
+                                {"wg_passes": 1}, {"lds_bytes": 65536}, {"target_workgroups": 1}])
+def test_knobs_do_not_change_the_layer(torch_cuda, oracle, kw):
+    b = W.config2_molecule(graphs=48, F=128)
+    _run_and_check(torch_cuda, oracle, b, 64, what=f"knobs {kw}", **kw)
+
+
+def test_channels_accumulate_in_place(torch_cuda, oracle):
+    """Y = sum_ch A_ch (X W_ch + bias_ch): one launch per channel, the later ones adding."""
+    torch = torch_cuda
+    chans, n_x = 3, 64
+    bs = [W.config2_molecule(seed=70, graphs=64, F=128) for _ in range(chans)]
+    rng = np.random.default_rng(5)
+    for bb in bs:
+        bb.values = (bb.values * rng.uniform(0.5, 1.5, size=bb.values.shape)).astype(np.float32)
+    X, Ws, biases = _layer(bs[0], n_x, 9, channels=chans)
+    Xd = torch.from_numpy(X).cuda()
+    Yd = torch.full((bs[0].n_c_rows, 128), SENTINEL, dtype=torch.float32, device="cuda")
+    Y = T = None
+    plans = []
+    for c in range(chans):
+        plans.append(K.Plan(bs[c], options=K.make_options(front_features=n_x)))
+        plans[-1].run_gcn(Xd, torch.from_numpy(Ws[c]).cuda(), torch.from_numpy(biases[c]).cuda(), Yd,
+                          accumulate=c > 0)
+        Y, T = oracle.gcn_channel(bs[c], X, Ws[c], biases[c], Y, T)
+    torch.cuda.synchronize()
+    b0 = bs[0]
+    _assert_close(Yd.cpu().numpy(), Y, T, _owned(b0.c_row_off, b0.rows, b0.n_c_rows),
+                  max(1e-5, chans * (n_x + 10) * 2.0 ** -23), "channel accumulation")
+
+
+def test_identity_weights_give_the_plain_product_and_plan_still_runs_plain(torch_cuda, oracle):
+    """W = I, bias = 0: Y = A X, equal to bspmm_run on the same plan (matrix-core products with
+    a single non-zero term are exact)."""
+    torch = torch_cuda
+    b = W.config2_molecule(graphs=32, F=64)
+    plan = K.Plan(b, options=K.make_options(front_features=64))
+    Xd = torch.from_numpy(b.B).cuda()
+    Y1 = torch.empty((b.n_c_rows, 64), dtype=torch.float32, device="cuda")
+    Y2 = torch.empty_like(Y1)
+    plan.run_gcn(Xd, torch.eye(64, device="cuda"), torch.zeros(64, device="cuda"), Y1)
+    plan.run(Xd, Y2)
+    torch.cuda.synchronize()
+    assert torch.equal(Y1, Y2)
+
+
+def test_strided_operands_and_argument_errors(torch_cuda, oracle):
+    torch = torch_cuda
+    b = W.config2_molecule(graphs=24, F=64)
+    n_x = 32
+    X, Ws, biases = _layer(b, n_x, 4)
+    plan = K.Plan(b, options=K.make_options(front_features=n_x))
+    Xd = torch.zeros((b.n_b_rows, n_x + 8), dtype=torch.float32, device="cuda")
+    Xd[:, :n_x] = torch.from_numpy(X).cuda()
+    Wd = torch.zeros((n_x, 64 + 4), dtype=torch.float32, device="cuda")
+    Wd[:, :64] = torch.from_numpy(Ws[0]).cuda()
+    Yd = torch.full((b.n_c_rows, 64 + 12), SENTINEL, dtype=torch.float32, device="cuda")
+    bd = torch.from_numpy(biases[0]).cuda()
+    K.bspmm_run_gcn(plan.handle, Xd, n_x + 8, Wd, 68, bd, Yd, 76)
+    torch.cuda.synchronize()
+    ref, T = oracle.gcn_channel(b, X, Ws[0], biases[0])
+    _assert_close(Yd[:, :64].cpu().numpy(), ref, T, _owned(b.c_row_off, b.rows, b.n_c_rows),
+                  _tol(b, n_x), "strided")
+    assert torch.all(Yd[:, 64:] == SENTINEL)
+    for args in [(Xd, n_x - 4, Wd, 68, bd, Yd, 76),        # ldx < n_X
+                 (Xd, n_x + 8, Wd, 60, bd, Yd, 76),        # ldw < F
+                 (Xd, n_x + 7, Wd, 68, bd, Yd, 76),        # ldx not a multiple of 4
+                 (Xd, n_x + 8, Wd, 68, None, Yd, 76),      # no bias
+                 (Xd.data_ptr() + 4, n_x + 8, Wd, 68, bd, Yd, 76)]:   # misaligned X
+        with pytest.raises(K.BspmmError) as e:
+            K.bspmm_run_gcn(plan.handle, *args)
+        assert e.value.code == K.EINVAL
+    plain = K.Plan(b)
+    with pytest.raises(K.BspmmError) as e:
+        K.bspmm_run_gcn(plain.handle, Xd, n_x + 8, Wd, 68, bd, Yd, 76)
+    assert e.value.code == K.ESTATE

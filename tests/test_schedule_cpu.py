@@ -33,7 +33,7 @@ def test_library_exports_every_declared_symbol():
 
 def test_struct_sizes_match_header():
     assert ctypes.sizeof(K.bspmm_item) == 32
-    assert ctypes.sizeof(K.bspmm_options) == 48
+    assert ctypes.sizeof(K.bspmm_options) == 56
     assert ctypes.sizeof(K.bspmm_batch) == 8 + 10 * 8
     assert ctypes.sizeof(K.bspmm_info) == 16 + 8 + 8 + 8 + 8 + 40 + 8 + 8 + 16 + 8 + 8
 
@@ -87,6 +87,9 @@ def _check_schedule(b, F, transposed=False, **opts):
                 if it.bin != K.BIN_WORKGROUP:   # only workgroup items may be cut into row ranges
                     assert it.row0 == 0 and it.nrows == int(m_of[it.op])
                 need = _lds_words(int(m_of[it.op]), int(k_of[it.op]), int(b.nnz[it.op]), it.fw, pad, lanes, bool(opts.get('flags', 0) & K.SPLIT_HUB_ROWS))
+                front = opts.get("front_features", 0) if not transposed else 0
+                if front:   # whole workgroups, 16-column blocks for the matrix cores
+                    assert it.bin == K.BIN_WORKGROUP and it.fw % 16 == 0 and it.f0 % 16 == 0
                 assert need * 4 <= info.lds_bytes * lanes // 256
                 if F % 4 == 0:
                     assert it.f0 % 4 == 0 and it.fw % 4 == 0
@@ -422,5 +425,45 @@ def test_direct_coo_rejects_what_it_cannot_do():
     h = K.dry_plan(b2, coo=True, flags=K.COO_DIRECT)
     try:
         assert K.bspmm_plan_info(h).transposed_supported == 0
+    finally:
+        K.bspmm_destroy(h)
+
+
+# ---------------------------------------------------------------------------------------------
+# fused front of the layer (bspmm_run_gcn): the forward schedule also holds X_i in LDS
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("maker,F,nx", [
+    (lambda: W.config2_molecule(graphs=64, F=128), 128, 64),
+    (lambda: W.config2_molecule(graphs=64, F=64), 64, 76),
+    (lambda: W.config3_multichannel(graphs=32, F=128), 128, 32),
+    (lambda: W.config4_wide(graphs=16, F=512), 512, 128),
+])
+@pytest.mark.parametrize("transposed", [False, True])
+def test_front_schedule_invariants(maker, F, nx, transposed):
+    if transposed and nx == 32:
+        pytest.skip("channels share their input block: no transposed product without ACCUMULATE")
+    _check_schedule(maker(), F, transposed=transposed, front_features=nx)
+    _check_schedule(maker(), F, transposed=transposed, front_features=nx, min_tile=8, max_tile=100)
+
+
+def test_front_argument_errors():
+    b = W.config2_molecule(graphs=8, F=128)
+    for kw, code in [(dict(front_features=64, flags=K.ACCUMULATE), K.EINVAL),
+                     (dict(front_features=64, flags=K.SPLIT_HUB_ROWS), K.EINVAL),
+                     (dict(front_features=63), K.EINVAL),
+                     (dict(front_features=64, lds_pad=4), K.EINVAL)]:
+        with pytest.raises(K.BspmmError) as e:
+            K.dry_plan(b, 128, **kw)
+        assert e.value.code == code, kw
+    with pytest.raises(K.BspmmError) as e:      # F must be a multiple of 16
+        K.dry_plan(b, 100, front_features=64)
+    assert e.value.code == K.EINVAL
+    big = W.config5_skewed(graphs=64, F=128)     # graphs of hundreds of nodes need the generic bin
+    with pytest.raises(K.BspmmError) as e:
+        K.dry_plan(big, 128, front_features=128)
+    assert e.value.code == K.ETOOBIG
+    h = K.dry_plan(b, 128)                       # a plan without the front refuses the call
+    try:
+        assert K.lib().bspmm_run_gcn(h, None, 0, None, 0, None, None, 0, 0, None) == K.ESTATE
     finally:
         K.bspmm_destroy(h)
