@@ -169,6 +169,66 @@ def coo_operands(torch, K, W):
     return out
 
 
+def layer_front(torch, K, W, n_x=64):
+    """One channel of the graph-convolution layer on the headline batch, HBM-cold: the fused
+    launch (bspmm_run_gcn) against MatMul+Add by the BLAS library followed by bspmm_run."""
+    b = W.config2_molecule(F=128)
+    F = b.F
+    fused = K.Plan(b, options=K.make_options(front_features=n_x))
+    plain = K.Plan(b)
+    per_set = 4 * (b.n_b_rows * (n_x + F) + b.n_c_rows * F)
+    nsets = max(2, min(512, -(-POOL_BYTES // per_set)))
+    X = torch.rand((nsets, b.n_b_rows, n_x), device="cuda") * 2 - 1
+    Bm = torch.empty((nsets, b.n_b_rows, F), device="cuda")
+    Y = torch.empty((nsets, b.n_c_rows, F), device="cuda")
+    Wt = (torch.rand((n_x, F), device="cuda") * 2 - 1) / n_x ** 0.5
+    bias = torch.rand(F, device="cuda")
+
+    def run_fused(i, stream):
+        K.bspmm_run_gcn(fused.handle, X[i], n_x, Wt, F, bias, Y[i], F, False, stream)
+
+    def run_unfused(i, stream):
+        torch.addmm(bias, X[i], Wt, out=Bm[i])
+        K.bspmm_run(plain.handle, Bm[i], Y[i], F, F, stream)
+
+    def run_front_only(i, stream):
+        torch.addmm(bias, X[i], Wt, out=Bm[i])
+
+    def timed(fn):
+        g = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            fn(0, side)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        with torch.cuda.graph(g):
+            cs = torch.cuda.current_stream()
+            for i in range(nsets):
+                fn(i, cs)
+        for _ in range(2):
+            g.replay()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        reps = 4
+        for _ in range(reps):
+            g.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / (reps * nsets)
+
+    nnz = int(b.nnz.sum())
+    flops = 2 * b.n_b_rows * n_x * F + 2 * nnz * F
+    out = {"workload": f"cfg2_molecule, n_X={n_x}, F={F}, one channel", "operand_sets": nsets,
+           "fused_us": round(timed(run_fused), 3),
+           "blas_addmm_then_bspmm_run_us": round(timed(run_unfused), 3),
+           "blas_addmm_alone_us": round(timed(run_front_only), 3)}
+    out["fused_gflops"] = round(flops / out["fused_us"] * 1e-3, 1)
+    out["speedup"] = round(out["blas_addmm_then_bspmm_run_us"] / out["fused_us"], 2)
+    return out
+
+
 _marker = None
 
 
@@ -409,6 +469,7 @@ def main():
         extra["channel_sum"] = acc
         extra["paper_grid_batched_vs_non_batched"] = paper_grid(torch, K, W)
         extra["coo_operands"] = coo_operands(torch, K, W)
+        extra["layer_front"] = layer_front(torch, K, W)
 
     out = {
         "metric": "batched SpMM graphs/sec, F=128, batch 128",

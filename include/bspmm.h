@@ -151,11 +151,13 @@ typedef struct bspmm_options {
     int32_t  resident_workgroups; /* N > 0: persistent launch of N workgroups that stride
                                   through the tasks; 0 = one workgroup per task (default)      */
     int32_t  front_features;   /* n_X > 0: shape the forward schedule for bspmm_run_gcn with an
-                                  n_X-column layer input (whole workgroups, feature tiles in
-                                  multiples of 16); needs F % 16 == 0 and n_X % 4 == 0 (EINVAL),
-                                  not combined with BSPMM_ACCUMULATE, BSPMM_SPLIT_HUB_ROWS or
-                                  lds_pad (EINVAL); ETOOBIG when an operation and its dense tile
-                                  do not fit LDS at any tile width                              */
+                                  n_X-column layer input: whole workgroups, feature tiles in
+                                  multiples of 16, room in LDS for an n_X x tile block of weights
+                                  and at least 16 rows of X_i beside the operation (lds_bytes
+                                  then defaults to 64 KiB); needs F % 16 == 0 and n_X % 4 == 0
+                                  (EINVAL), not combined with BSPMM_ACCUMULATE,
+                                  BSPMM_SPLIT_HUB_ROWS or lds_pad (EINVAL); ETOOBIG when an
+                                  operation does not fit at any tile width                      */
     int32_t  reserved_;        /* 0 */
 } bspmm_options;
 
@@ -229,7 +231,7 @@ int bspmm_run(bspmm_plan* plan, const float* B, float* C, int64_t ldb, int64_t l
  * (cols_i rows of n_X = options.front_features floats at row b_row_off[i], leading dimension
  * ldx >= n_X), W the DEVICE n_X x F weight matrix (leading dimension ldw >= F), bias F DEVICE
  * floats, Y indexed like C.  The dense part runs on the matrix cores in fp32
- * (v_mfma_f32_16x16x4_f32) and its result goes straight into LDS; B_i never leaves the chip.  X, W, Y must be
+ * (v_mfma_f32_16x16x4_f32) from LDS to LDS; B_i never leaves the chip.  X, W, Y must be
  * 16-byte aligned with ldx, ldw, ldy multiples of 4 (EINVAL).  ESTATE for plans created
  * without front_features.
  */

@@ -276,7 +276,8 @@ Knobs knobs_for(const bspmm_options* o, bool ask_device)
         else
             (void)hipGetLastError();
     }
-    if (!(o && o->target_workgroups > 0)) kn.target_wgs = 4 * kn.compute_units;
+    // (the fused front stages more per workgroup: two per CU measured best)
+    if (!(o && o->target_workgroups > 0)) kn.target_wgs = (kn.front > 0 ? 2 : 4) * kn.compute_units;
     const int r = ask_device ? bspmm_max_resident_workgroups(kn.lds_words * 4, false, kn.hubs) : 0;
     const int rs = ask_device ? bspmm_max_resident_workgroups(kn.lds_words * 4, true, kn.hubs) : 0;
     kn.capacity_wgs = r > 0 ? r : 6 * kn.compute_units;
@@ -588,7 +589,7 @@ int run_gcn(bspmm_plan* p, const float* X, int64_t ldx, const float* W, int64_t 
     }
     P.n_tasks = sc.grid;
     P.fused_stride = sc.fused_stride;
-    P.lds_floats = p->knobs.lds_words;
+    P.lds_floats = sc.front_lds_words;     // what the launch gets: decides the rows of X_i per pass
     P.pad = 0;
     P.w = W;
     P.bias = bias;
@@ -598,7 +599,7 @@ int run_gcn(bspmm_plan* p, const float* X, int64_t ldx, const float* W, int64_t 
 #ifdef BSPMM_TRACE
     P.trace = g_trace;
 #endif
-    hipError_t e = launch_bspmm_gcn(P, sc.grid, p->knobs.lds_words * 4, accumulate != 0, s);
+    hipError_t e = launch_bspmm_gcn(P, sc.grid, sc.front_lds_words * 4, accumulate != 0, s);
     return e == hipSuccess ? BSPMM_OK : hip_fail(e);
 }
 

@@ -116,8 +116,9 @@ __device__ __forceinline__ void stage_item(const LaunchParams& P, const WorkItem
     const int m = it.m, nnz = it.nnz, k = it.k;
 
     // ---- first trip of every copy: loads only
-    int rv = 0;
-    if (lane <= m) rv = rp[lane];
+    // (unconditional, from a clamped index: a load inside a branch drags the first use of its
+    // value, and with it a wait for the whole round trip, in front of the loads that follow)
+    const int rv = rp[min(lane, m)];
     int c0 = 0, c1 = 0;
     float a0 = 0.f, a1 = 0.f;
     if (lane < nnz) {
@@ -869,20 +870,64 @@ validate_coo_kernel(const OpRecord* __restrict__ ops, const int32_t* __restrict_
 
 // ---------------------------------------------------------------------------------------
 // One channel of the batched graph-convolution layer in one launch (Fig. 7: MatMul, Add,
-// BatchedSpMM): Y_i (+)= A_i (X_i W + bias).  A workgroup stages A_i, computes the dense tile
-// B = X_i W[:, f0:f0+fw] + bias on the matrix cores straight into the tile's place in LDS, and
-// then runs the ordinary row gather over it: U, B and the per-channel C never exist in memory.
+// BatchedSpMM): Y_i (+)= A_i (X_i W + bias).  A workgroup stages A_i, the layer input X_i
+// (k x n_front), the weight tile W[:, f0:f0+fw] and the bias tile in LDS in ONE round trip to
+// memory (more when X_i does not fit at once), computes the dense tile B = X_i W + bias on the matrix cores out of LDS into the
+// tile's usual place, and then runs the ordinary row gather over it: U, B and the per-channel
+// C never exist in memory.
 // The dense part is v_mfma_f32_16x16x4_f32 (fp32 in, fp32 accumulate).  The tile is cut into
 // 16 x 16 blocks dealt to the four wavefronts.  Operand layout of the instruction: lane l
 // supplies A[l % 16][l / 16] and B[l / 16][l % 16] and receives rows 4*(l / 16) .. +3 of column
-// l % 16.  A lane reads four consecutive k of its X row with one 16-byte load and feeds them to
-// four instructions together with the weights of the same four k, so the k order inside a
-// step differs from memory order for both operands alike, which leaves the product unchanged.
-// Both operands come from global memory: X_i is read once per column tile, W by every
-// workgroup of a column tile (L2).  The loads of a wavefront's first block do not depend on
-// anything and are requested before the CSR staging is waited for.
+// l % 16.  A lane reads four consecutive k of its X row with one 16-byte LDS read and feeds
+// them to four instructions together with the weights of the same four k, so the k order
+// inside a step differs from memory order for both operands alike, which leaves the product
+// unchanged.
+// LDS, in words: the staged layout of the item (row pointers, entries, dense tile k x fw),
+// then the weight tile (n_front x fw), the bias tile (fw) and as many rows of X_i as fit
+// (a multiple of 16; operations with more rows take several passes).
 // Needs F % 16 == 0, n_front % 4 == 0 and 16-byte aligned operands (checked on the host).
 // ---------------------------------------------------------------------------------------
+
+// rows x (4 * nvec) floats, global (leading dimension ld) -> LDS (rows packed).  Whole
+// wavefronts copy 1 KiB per instruction straight into LDS when a row is a power-of-two number
+// of float4; otherwise through registers, four rows per lane group in flight.
+// `swz` != 0 (only with a power-of-two nvec, swz < nvec) stores the float4 with index v of row r
+// in slot v ^ (r & swz): rows that are a multiple of 64 words apart then no longer fall on the
+// same LDS banks when 16 lanes read the same column of 16 consecutive rows.
+__device__ __forceinline__ void stage_tile4(float* dst, const float* __restrict__ src, int64_t ld,
+                                            int rows, int nvec, int tid, int swz = 0)
+{
+    if ((nvec & (nvec - 1)) == 0) {
+        const int sh = ilog2(nvec);
+        const int total = rows << sh;
+        const int wl = tid & 63;
+        for (int e0 = (tid >> 6) << 6; e0 < total; e0 += kThreads) {
+            const int e = e0 + wl;
+            if (e < total) {
+                const int r = e >> sh;
+                const float* gp = src + (int64_t)r * ld + ((((e & (nvec - 1)) ^ (r & swz))) << 2);
+                __builtin_amdgcn_global_load_lds(
+                    (const void __attribute__((address_space(1)))*)gp,
+                    (void __attribute__((address_space(3)))*)(dst + (e0 << 2)), 16, 0, 0);
+            }
+        }
+    } else {
+        const int gl = min(64, pow2_ceil(nvec));
+        const int sh = ilog2(gl);
+        const int g = tid >> sh, l = tid & (gl - 1), G = kThreads >> sh;
+        if (l < nvec)
+            for (int r0 = g; r0 < rows; r0 += 4 * G) {
+                float4 t[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    t[u] = load_vec<4>(src + (int64_t)min(r0 + u * G, rows - 1) * ld + 4 * l);
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    if (r0 + u * G < rows) store_vec<4>(dst + (r0 + u * G) * (nvec << 2) + 4 * l, t[u]);
+            }
+    }
+}
+
 template <bool ACC>
 __global__ void __launch_bounds__(kThreads) bspmm_gcn_kernel(const LaunchParams P)
 {
@@ -892,67 +937,74 @@ __global__ void __launch_bounds__(kThreads) bspmm_gcn_kernel(const LaunchParams 
     const WorkItem it = P.items[blockIdx.x];
     if (it.nrows <= 0) return;
     const int nx = P.n_front;
-    const int wave = tid >> 6, wl = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), wl = tid & 63;
     const int col = wl & 15, g = wl >> 4;
     const int nb_count = it.fw >> 4;
-    const int blocks = ((it.k + 15) >> 4) * nb_count;
-    const float* wcol0 = P.w + it.f0 + col;
-    const float* x0 = P.in + it.in_row_off * P.ld_in + 4 * g;
-
-    // operands of 64 k of one block: 4 float4 of the lane's X row, 16 weights of its column
-    auto load_chunk = [&](int mb, int nb, int k0, float4 (&xa)[4], float (&wr)[16]) {
-        const int arow = min(16 * mb + col, it.k - 1);     // rows past the end repeat the last
-        const float* xrow = x0 + (int64_t)arow * P.ld_in + k0;
-        const float* wcol = wcol0 + 16 * nb;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int kk = k0 + 16 * j + 4 * g;
-            xa[j] = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (kk < nx) xa[j] = *reinterpret_cast<const float4*>(xrow + 16 * j);
-#pragma unroll
-            for (int s4 = 0; s4 < 4; ++s4)
-                wr[4 * j + s4] = kk < nx ? wcol[(int64_t)(kk + s4) * P.ld_w] : 0.f;   // nx % 4 == 0
-        }
-    };
-
-    float4 xq[4];
-    float wq[16];
-    if (wave < blocks) load_chunk(wave / nb_count, wave % nb_count, 0, xq, wq);
-
-    stage_item<kThreads, 4, false, false>(P, it, sm, tid);    // A_i only: the tile is made here
 
     const StagedLayout L = staged_layout(it.m, it.k, it.nnz, it.fw, 0, false);
-    float* bt = reinterpret_cast<float*>(sm + L.b_off);      // k x fw, row stride fw
-    for (int blk = wave; blk < blocks; blk += kThreads / 64) {
-        const int mb = blk / nb_count, nb = blk - mb * nb_count;
-        const float bv = P.bias[it.f0 + 16 * nb + col];
-        mfma4 acc = {bv, bv, bv, bv};
-        for (int k0 = 0; k0 < nx; k0 += 64) {
-            float4 xa[4];
-            float wr[16];
-            if (blk == wave && k0 == 0) {
-#pragma unroll
-                for (int q = 0; q < 4; ++q) xa[q] = xq[q];
-#pragma unroll
-                for (int q = 0; q < 16; ++q) wr[q] = wq[q];
-            } else {
-                load_chunk(mb, nb, k0, xa, wr);
+    float* bt = reinterpret_cast<float*>(sm + L.b_off);      // dense tile k x fw, made below
+    float* ws = bt + it.k * it.fw;                            // weight tile, nx x fw
+    float* bias_s = ws + nx * it.fw;                          // bias tile, fw
+    float* xs = bias_s + it.fw;                               // rows of X_i, R x nx
+    // X_i is taken R rows at a time (a 16 x 16 block needs 16 of its rows and all of their
+    // columns): as many as the rest of the LDS holds.  The host has made sure of 16.
+    const int R = min((it.k + 15) & ~15, ((P.lds_floats - (int)(xs - reinterpret_cast<float*>(sm))) / nx) & ~15);
+    const int xvec = nx >> 2;
+    const int swz = (xvec & (xvec - 1)) == 0 ? min(xvec, 16) - 1 : 0;
+    const float* xg = P.in + it.in_row_off * P.ld_in;
+
+    for (int r0 = 0; r0 < it.k; r0 += R) {
+        const int rows = min(R, it.k - r0);
+        // ---- everything read from memory, requested at once (first pass: also A_i, the
+        // weights and the bias)
+        stage_tile4(xs, xg + (int64_t)r0 * P.ld_in, P.ld_in, rows, xvec, tid, swz);
+        if (r0 == 0) {
+            stage_tile4(ws, P.w + it.f0, P.ld_w, nx, it.fw >> 2, tid);
+            float bias_v = 0.f;
+            if (tid < it.fw) bias_v = P.bias[it.f0 + tid];
+            stage_item<kThreads, 4, false, false>(P, it, sm, tid);    // A_i only
+            if (tid < it.fw) bias_s[tid] = bias_v;
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // direct-to-LDS loads landed
+        __syncthreads();
+
+        // ---- dense tile rows r0 .. r0+rows on the matrix cores, LDS -> LDS
+        const int blocks = ((rows + 15) >> 4) * nb_count;
+        for (int blk = wave; blk < blocks; blk += kThreads / 64) {
+            const int mb = blk / nb_count, nb = blk - mb * nb_count;
+            const float bv = bias_s[16 * nb + col];
+            // four independent accumulators (one per k of a lane's four): a chain of
+            // dependent matrix instructions would run at their latency, not their rate
+            mfma4 acc = {bv, bv, bv, bv};
+            mfma4 acc1 = {0.f, 0.f, 0.f, 0.f}, acc2 = acc1, acc3 = acc1;
+            const int arow = min(16 * mb + col, rows - 1);     // rows past the end repeat the last
+            const float* xrow = xs + arow * nx;
+            const int xs_swz = arow & swz;
+            const float* wcol = ws + 4 * g * it.fw + 16 * nb + col;
+            for (int k0 = 0; k0 < nx; k0 += 16) {
+                // every lane takes part in the matrix instruction: a lane group whose four k
+                // lie past the end (nx % 4 == 0: all four or none) reads the last valid ones
+                // instead and contributes zeros
+                const bool ok = k0 + 4 * g < nx;
+                const int kc = ok ? k0 : nx - 4 - 4 * g;
+                float4 a = *reinterpret_cast<const float4*>(xrow + ((((kc >> 2) + g) ^ xs_swz) << 2));
+                if (!ok) a = make_float4(0.f, 0.f, 0.f, 0.f);
+                const float* wk = wcol + kc * it.fw;
+                const float w0 = wk[0], w1 = wk[it.fw], w2 = wk[2 * it.fw], w3 = wk[3 * it.fw];
+                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a.x, w0, acc, 0, 0, 0);
+                acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(a.y, w1, acc1, 0, 0, 0);
+                acc2 = __builtin_amdgcn_mfma_f32_16x16x4f32(a.z, w2, acc2, 0, 0, 0);
+                acc3 = __builtin_amdgcn_mfma_f32_16x16x4f32(a.w, w3, acc3, 0, 0, 0);
             }
+            acc = (acc + acc1) + (acc2 + acc3);
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(xa[j].x, wr[4 * j + 0], acc, 0, 0, 0);
-                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(xa[j].y, wr[4 * j + 1], acc, 0, 0, 0);
-                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(xa[j].z, wr[4 * j + 2], acc, 0, 0, 0);
-                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(xa[j].w, wr[4 * j + 3], acc, 0, 0, 0);
+            for (int i = 0; i < 4; ++i) {
+                const int row = 16 * mb + 4 * g + i;
+                if (row < rows) bt[(r0 + row) * it.fw + 16 * nb + col] = acc[i];
             }
         }
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int row = 16 * mb + 4 * g + i;
-            if (row < it.k) bt[row * it.fw + 16 * nb + col] = acc[i];
-        }
+        __syncthreads();     // the rows of X_i may be replaced; after the last pass: tile complete
     }
-    __syncthreads();
     compute_staged<kThreads, 4, false, ACC>(P, it, sm, tid);
 }
 

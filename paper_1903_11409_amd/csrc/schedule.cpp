@@ -25,6 +25,7 @@ namespace bspmm {
 namespace {
 
 constexpr int kXcds = 8;
+constexpr int kFrontBlocks = 8;   // matrix-core blocks one workgroup of the fused front should make
 
 struct Draft {           // one item before placement
     int op;
@@ -87,6 +88,8 @@ bool fits_slot(const DirOps& o, int i, int tile, int F, int vec, int lanes, int 
     const int64_t head = (int64_t)round_up(o.m[i] + 1, 2) + 2 * (int64_t)o.nnz[i];
     int64_t need = (head + 3) / 4 * 4 + (int64_t)o.k[i] * (round_up(fw, 4) + kn.pad);
     if (kn.hubs && lanes == kThreads) need += hub_words(o.nnz[i] / kHubMin, fw);   // as staged_layout()
+    if (kn.front > 0)   // the weight tile, the bias tile and at least 16 rows of X_i ride along
+        need += 16 * (int64_t)kn.front + (int64_t)kn.front * round_up(fw, 4) + round_up(fw, 4);
     return need <= (int64_t)kn.lds_words * lanes / kThreads;
 }
 
@@ -97,9 +100,16 @@ Choice choose(const DirOps& o, int i, int F, int vec, const std::vector<int>& ca
     const int forced = kn.front > 0 ? BSPMM_BIN_WORKGROUP : kn.force_bin;   // the fused front runs on whole workgroups
     if (forced == BSPMM_BIN_GENERIC) return {BSPMM_BIN_GENERIC, cand[0]};
     if (forced >= 0) {
-        for (size_t c = first; c < cand.size(); ++c)
+        for (size_t c = first; c < cand.size(); ++c) {
+            // fused front: a workgroup makes its whole dense tile on the matrix cores before it
+            // can gather, and the launch lasts as long as its slowest workgroup, so a larger
+            // operation takes a narrower tile (at most kFrontBlocks 16 x 16 blocks each)
+            if (kn.front > 0 && c + 1 < cand.size() &&
+                ((o.k[i] + 15) / 16) * ((std::min(cand[c], F) + 15) / 16) > kFrontBlocks)
+                continue;
             if (fits_slot(o, i, cand[c], F, vec, bin_slot_lanes(forced), 0, kn))
                 return {forced, cand[c]};
+        }
     }
     const int tile = cand[first];
     static const int small_bins[3] = {BSPMM_BIN_SLICE16, BSPMM_BIN_SLICE32, BSPMM_BIN_WAVE};
@@ -348,7 +358,8 @@ Knobs resolve_knobs(const bspmm_options* o)
     if (o->max_tile > 0) k.max_tile = std::min(std::max(o->max_tile, 4), 256) / 4 * 4;
     if (o->min_tile > 0) k.min_tile = std::min(std::max(o->min_tile, 4), k.max_tile);
     if (o->compute_units > 0) k.compute_units = o->compute_units;
-    k.target_wgs = o->target_workgroups > 0 ? o->target_workgroups : 4 * k.compute_units;
+    k.target_wgs = o->target_workgroups > 0 ? o->target_workgroups
+                                            : (o->front_features > 0 ? 2 : 4) * k.compute_units;
     if (o->lds_pad > 0) k.pad = std::min(o->lds_pad, 64) / 4 * 4;
     if (o->lds_pad < 0) k.pad = 0;
     if (o->max_passes > 0) k.max_passes = o->max_passes;
@@ -360,8 +371,11 @@ Knobs resolve_knobs(const bspmm_options* o)
     k.coo_direct = (o->flags & BSPMM_COO_DIRECT) != 0;
     if (o->front_features > 0) {   // the matrix-core blocks of the fused front are 16 columns wide
         k.front = o->front_features;
+        // an item also holds X_i and a weight tile: take the whole 64 KiB unless told otherwise
+        // (the launch asks only for what its largest item needs)
+        if (o->lds_bytes <= 0) k.lds_words = kMaxLdsBytes / 4;
         k.max_tile = std::max(16, k.max_tile / 16 * 16);
-        k.min_tile = std::min(std::max(16, (k.min_tile + 15) / 16 * 16), k.max_tile);
+        k.min_tile = o->min_tile > 0 ? std::min(std::max(16, (k.min_tile + 15) / 16 * 16), k.max_tile) : 16;
     }
     return k;
 }
@@ -586,6 +600,16 @@ Schedule make_schedule(const DirOps& ops, int F, const Knobs& kn_in)
     }
     s.grid = wg;
     s.launch_grid = kn.persistent_wgs > 0 ? std::min(wg, W) : wg;
+    if (kn.front > 0) {
+        int64_t most = 0;
+        for (const WorkItem& w : s.items) {
+            if (w.nrows <= 0) continue;
+            const StagedLayout L = staged_layout(w.m, w.k, w.nnz, w.fw, 0, false);
+            most = std::max<int64_t>(most, (int64_t)L.total + (int64_t)round_up(w.k, 16) * kn.front +
+                                               (int64_t)kn.front * w.fw + w.fw);
+        }
+        s.front_lds_words = (int)std::min<int64_t>(kn.lds_words, round_up((int)most, 64));
+    }
     return s;
 }
 

@@ -51,6 +51,7 @@ struct Schedule {
     int launch_grid = 0;             // workgroups of the persistent launch
     bool has_slices = false;         // any 32- or 16-lane item: needs the larger kernel variant
     int tile = 0;
+    int front_lds_words = 0;         // LDS the fused-front launch asks for (its largest item)
     int items_in_bin[BSPMM_NUM_BINS] = {0, 0, 0, 0, 0};
 };
 

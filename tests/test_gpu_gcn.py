@@ -78,17 +78,15 @@ def _run_and_check(torch, oracle, b, n_x, seed=1, what="", **kw):
     (lambda: W.config1_tiny(), 64),
     (lambda: W.config2_molecule(), 64),             # the headline batch as a layer
     (lambda: W.config2_molecule(F=64), 76),         # n_X not a multiple of 16 or 64
-    (lambda: W.config2_molecule(F=256), 128),
+    (lambda: W.config2_molecule(F=256), 128),       # X_i of the larger graphs in several passes
     (lambda: W.config3_multichannel(), 32),         # channels sharing their input block
     (lambda: W.config4_wide(F=512), 64),
     (lambda: W.random_general(55, F=64, shapes=[(200, 180, 1500), (150, 150, 900), (12, 300, 80)] * 3), 16),
+    (lambda: W.config5_skewed(graphs=256, F=64, asymmetric=True), 64),   # up to 500 nodes: many passes
 ])
 def test_layer_channel_configurations(torch_cuda, oracle, maker, n_x):
     b = maker()
-    lds = {}
-    if b.name == "general":
-        lds = {"lds_bytes": 65536}                 # operations of a few hundred rows
-    _run_and_check(torch_cuda, oracle, b, n_x, **lds)
+    _run_and_check(torch_cuda, oracle, b, n_x)
 
 
 @pytest.mark.parametrize("n_x", [4, 8, 20, 60, 64, 68, 132, 256])
@@ -99,7 +97,7 @@ def test_input_widths_and_ragged_operations(torch_cuda, oracle, n_x):
     _run_and_check(torch_cuda, oracle, b, n_x, seed=n_x)
 
 
-@pytest.mark.parametrize("kw", [{"max_tile": 16}, {"max_tile": 64}, {"min_tile": 128, "lds_bytes": 65536},
+@pytest.mark.parametrize("kw", [{"max_tile": 16}, {"max_tile": 64}, {"min_tile": 32},
                                 {"wg_passes": 1}, {"lds_bytes": 65536}, {"target_workgroups": 1}])
 def test_knobs_do_not_change_the_layer(torch_cuda, oracle, kw):
     b = W.config2_molecule(graphs=48, F=128)

@@ -88,7 +88,9 @@ def _check_schedule(b, F, transposed=False, **opts):
                     assert it.row0 == 0 and it.nrows == int(m_of[it.op])
                 need = _lds_words(int(m_of[it.op]), int(k_of[it.op]), int(b.nnz[it.op]), it.fw, pad, lanes, bool(opts.get('flags', 0) & K.SPLIT_HUB_ROWS))
                 front = opts.get("front_features", 0) if not transposed else 0
-                if front:   # whole workgroups, 16-column blocks for the matrix cores
+                if front:   # 16 rows of X_i at least, the weight tile and the bias tile ride
+                    #          along; whole workgroups, 16-column blocks for the matrix cores
+                    need += 16 * front + front * it.fw + it.fw
                     assert it.bin == K.BIN_WORKGROUP and it.fw % 16 == 0 and it.f0 % 16 == 0
                 assert need * 4 <= info.lds_bytes * lanes // 256
                 if F % 4 == 0:
@@ -458,9 +460,9 @@ def test_front_argument_errors():
     with pytest.raises(K.BspmmError) as e:      # F must be a multiple of 16
         K.dry_plan(b, 100, front_features=64)
     assert e.value.code == K.EINVAL
-    big = W.config5_skewed(graphs=64, F=128)     # graphs of hundreds of nodes need the generic bin
+    big = W.config5_skewed(graphs=64, F=128)     # graphs of hundreds of nodes in 16 KiB: no room
     with pytest.raises(K.BspmmError) as e:
-        K.dry_plan(big, 128, front_features=128)
+        K.dry_plan(big, 128, front_features=128, lds_bytes=16384)
     assert e.value.code == K.ETOOBIG
     h = K.dry_plan(b, 128)                       # a plan without the front refuses the call
     try:
