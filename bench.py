@@ -469,7 +469,7 @@ def main():
         extra["channel_sum"] = acc
         extra["paper_grid_batched_vs_non_batched"] = paper_grid(torch, K, W)
         extra["coo_operands"] = coo_operands(torch, K, W)
-        extra["layer_front"] = layer_front(torch, K, W)
+        extra["layer_front"] = [layer_front(torch, K, W, n_x=n) for n in (32, 64, 128)]
 
     out = {
         "metric": "batched SpMM graphs/sec, F=128, batch 128",

@@ -953,22 +953,8 @@ __global__ void __launch_bounds__(kThreads) bspmm_gcn_kernel(const LaunchParams 
     const int swz = (xvec & (xvec - 1)) == 0 ? min(xvec, 16) - 1 : 0;
     const float* xg = P.in + it.in_row_off * P.ld_in;
 
-    for (int r0 = 0; r0 < it.k; r0 += R) {
-        const int rows = min(R, it.k - r0);
-        // ---- everything read from memory, requested at once (first pass: also A_i, the
-        // weights and the bias)
-        stage_tile4(xs, xg + (int64_t)r0 * P.ld_in, P.ld_in, rows, xvec, tid, swz);
-        if (r0 == 0) {
-            stage_tile4(ws, P.w + it.f0, P.ld_w, nx, it.fw >> 2, tid);
-            float bias_v = 0.f;
-            if (tid < it.fw) bias_v = P.bias[it.f0 + tid];
-            stage_item<kThreads, 4, false, false>(P, it, sm, tid);    // A_i only
-            if (tid < it.fw) bias_s[tid] = bias_v;
-        }
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // direct-to-LDS loads landed
-        __syncthreads();
-
-        // ---- dense tile rows r0 .. r0+rows on the matrix cores, LDS -> LDS
+    // dense tile rows r0 .. r0+rows on the matrix cores, LDS -> LDS
+    auto dense_rows = [&](int r0, int rows) {
         const int blocks = ((rows + 15) >> 4) * nb_count;
         for (int blk = wave; blk < blocks; blk += kThreads / 64) {
             const int mb = blk / nb_count, nb = blk - mb * nb_count;
@@ -1003,7 +989,28 @@ __global__ void __launch_bounds__(kThreads) bspmm_gcn_kernel(const LaunchParams 
                 if (row < rows) bt[(r0 + row) * it.fw + 16 * nb + col] = acc[i];
             }
         }
-        __syncthreads();     // the rows of X_i may be replaced; after the last pass: tile complete
+    };
+
+    // ---- first pass: everything read from memory is requested at once (the first rows of
+    // X_i, the weights, the bias, A_i)
+    stage_tile4(xs, xg, P.ld_in, min(R, it.k), xvec, tid, swz);
+    stage_tile4(ws, P.w + it.f0, P.ld_w, nx, it.fw >> 2, tid);
+    float bias_v = 0.f;
+    if (tid < it.fw) bias_v = P.bias[it.f0 + tid];
+    stage_item<kThreads, 4, false, false>(P, it, sm, tid);    // A_i only
+    if (tid < it.fw) bias_s[tid] = bias_v;
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");          // direct-to-LDS loads landed
+    __syncthreads();
+    dense_rows(0, min(R, it.k));
+    __syncthreads();         // the rows of X_i may be replaced; after the last pass: tile complete
+    // ---- operations with more rows than fit: further passes
+    for (int r0 = R; r0 < it.k; r0 += R) {
+        const int rows = min(R, it.k - r0);
+        stage_tile4(xs, xg + (int64_t)r0 * P.ld_in, P.ld_in, rows, xvec, tid, swz);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        dense_rows(r0, rows);
+        __syncthreads();
     }
     compute_staged<kThreads, 4, false, ACC>(P, it, sm, tid);
 }
