@@ -196,6 +196,9 @@ typedef struct bspmm_item {
 /*
  * Bytes of device workspace a plan for (batch, F, options) needs.  Reads only HOST arrays.
  * options may be NULL.  Device pointers in `b` are not dereferenced and may be NULL here.
+ * The size depends on the schedule, so this call schedules the batch; a bspmm_create on the
+ * same thread with the same batch contents, F and options takes that schedule over instead of
+ * making it again.
  */
 int bspmm_workspace_bytes(const bspmm_batch* b, int32_t F, const bspmm_options* options,
                           size_t* bytes);

@@ -4,6 +4,7 @@
 #include <algorithm>
 #include <cstring>
 #include <new>
+#include <memory>
 #include <set>
 #include <utility>
 #include <vector>
@@ -208,7 +209,22 @@ int plan_host(bspmm_plan& p, const bspmm_batch* b, int32_t F, const Knobs& kn)
         return BSPMM_EINVAL;
     p.sched[0] = make_schedule(f, F, kn);
     if (p.sched[0].error) return p.sched[0].error;
-    if (p.transposed_supported) {
+    // Square operations whose input and output blocks sit at the same rows (adjacency matrices
+    // of a GCN batch) have the same schedule in both directions: only the location of the
+    // CSR arrays differs.
+    bool same_shape = kn.front == 0;
+    for (int i = 0; i < n && same_shape; ++i)
+        same_shape = b->rows[i] == b->cols[i] && b->b_row_off[i] == b->c_row_off[i];
+    if (p.transposed_supported && same_shape) {
+        p.sched[1] = p.sched[0];
+        Schedule& st = p.sched[1];
+        for (size_t j = 0; j < st.items.size(); ++j) {
+            const int op = st.item_op[j];
+            if (op < 0) continue;
+            st.items[j].rpt_off = t.rpt_off[op];
+            st.items[j].nz_off = t.nz_off[op];
+        }
+    } else if (p.transposed_supported) {
         Knobs kt = kn;
         kt.front = 0;                     // the layer input is a forward-only guest
         p.sched[1] = make_schedule(t, F, kt);
@@ -263,23 +279,53 @@ int plan_host(bspmm_plan& p, const bspmm_batch* b, int32_t F, const Knobs& kn)
     return BSPMM_OK;
 }
 
+// What the device says about itself does not change between plans: asked once per
+// (device, LDS size, kernel variant) and thread.
+struct DeviceFacts {
+    int dev = -1, lds_bytes = 0;
+    bool hubs = false;
+    int cus = 0, resident = 0, resident_slices = 0;
+};
+
+const DeviceFacts& device_facts(int lds_bytes, bool hubs)
+{
+    thread_local DeviceFacts f;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) {
+        (void)hipGetLastError();
+        dev = -2;
+    }
+    if (f.dev != dev || f.lds_bytes != lds_bytes || f.hubs != hubs) {
+        f = DeviceFacts();
+        f.dev = dev;
+        f.lds_bytes = lds_bytes;
+        f.hubs = hubs;
+        if (dev >= 0) {
+            int cus = 0;
+            if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess)
+                f.cus = cus;
+            else
+                (void)hipGetLastError();
+            f.resident = bspmm_max_resident_workgroups(lds_bytes, false, hubs);
+            f.resident_slices = bspmm_max_resident_workgroups(lds_bytes, true, hubs);
+        }
+    }
+    return f;
+}
+
 Knobs knobs_for(const bspmm_options* o, bool ask_device)
 {
     Knobs kn = resolve_knobs(o);
     const bool cus_given = o && o->compute_units > 0;
-    if (!cus_given && ask_device) {
-        int dev = 0, cus = 0;
-        if (hipGetDevice(&dev) == hipSuccess &&
-            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess &&
-            cus > 0)
-            kn.compute_units = cus;
-        else
-            (void)hipGetLastError();
+    int r = 0, rs = 0;
+    if (ask_device) {
+        const DeviceFacts& f = device_facts(kn.lds_words * 4, kn.hubs);
+        if (!cus_given && f.cus > 0) kn.compute_units = f.cus;
+        r = f.resident;
+        rs = f.resident_slices;
     }
     // (the fused front stages more per workgroup: two per CU measured best)
     if (!(o && o->target_workgroups > 0)) kn.target_wgs = (kn.front > 0 ? 2 : 4) * kn.compute_units;
-    const int r = ask_device ? bspmm_max_resident_workgroups(kn.lds_words * 4, false, kn.hubs) : 0;
-    const int rs = ask_device ? bspmm_max_resident_workgroups(kn.lds_words * 4, true, kn.hubs) : 0;
     kn.capacity_wgs = r > 0 ? r : 6 * kn.compute_units;
     kn.capacity_wgs_slices = rs > 0 ? rs : 4 * kn.compute_units;
     return kn;
@@ -603,6 +649,73 @@ int run_gcn(bspmm_plan* p, const float* X, int64_t ldx, const float* W, int64_t 
     return e == hipSuccess ? BSPMM_OK : hip_fail(e);
 }
 
+// bspmm_workspace_bytes has to schedule the batch to know the size; a bspmm_create that follows
+// on the same thread with the same arguments takes that plan over instead of scheduling again.
+// The key holds the argument values and a hash of the host arrays' contents.
+struct PlanKey {
+    uint64_t hash = 0;
+    int32_t batch = -1, F = 0;
+    bool coo = false, has_options = false;
+    bspmm_options options;
+    bool operator==(const PlanKey& o) const
+    {
+        return hash == o.hash && batch == o.batch && F == o.F && coo == o.coo &&
+               has_options == o.has_options &&
+               (!has_options || std::memcmp(&options, &o.options, sizeof(options)) == 0);
+    }
+};
+
+uint64_t fnv(uint64_t h, const void* data, size_t bytes)
+{
+    const unsigned char* q = static_cast<const unsigned char*>(data);
+    // eight bytes at a time (the arrays are int32 / int64)
+    size_t i = 0;
+    for (; i + 8 <= bytes; i += 8) {
+        uint64_t w;
+        std::memcpy(&w, q + i, 8);
+        h = (h ^ w) * 0x100000001b3ull;
+    }
+    for (; i < bytes; ++i) h = (h ^ q[i]) * 0x100000001b3ull;
+    return h;
+}
+
+template <class Batch>
+PlanKey make_key(const Batch* b, int32_t F, const bspmm_options* o, bool coo, const int64_t* rpt_off)
+{
+    PlanKey k;
+    k.batch = b->batch;
+    k.F = F;
+    k.coo = coo;
+    k.has_options = o != nullptr;
+    if (o) k.options = *o;
+    uint64_t h = 0xcbf29ce484222325ull;
+    const size_t n = (size_t)b->batch;
+    h = fnv(h, b->rows, n * 4);
+    h = fnv(h, b->cols, n * 4);
+    h = fnv(h, b->nnz, n * 4);
+    if (rpt_off) h = fnv(h, rpt_off, n * 8);
+    h = fnv(h, b->nz_off, n * 8);
+    h = fnv(h, b->b_row_off, n * 8);
+    h = fnv(h, b->c_row_off, n * 8);
+    k.hash = h;
+    return k;
+}
+
+thread_local std::unique_ptr<bspmm_plan> t_memo;
+thread_local PlanKey t_memo_key;
+
+void remember(bspmm_plan* p, const PlanKey& k)
+{
+    t_memo.reset(p);
+    t_memo_key = k;
+}
+
+bspmm_plan* recall(const PlanKey& k)
+{
+    if (t_memo && t_memo_key == k) return t_memo.release();
+    return nullptr;
+}
+
 }  // namespace
 
 extern "C" {
@@ -618,9 +731,13 @@ int bspmm_workspace_bytes(const bspmm_batch* b, int32_t F, const bspmm_options* 
     if (!p) return BSPMM_EINVAL;
     const bool dry = options && (options->flags & BSPMM_DRY_RUN);
     rc = plan_host(*p, b, F, knobs_for(options, !dry));
-    if (rc == BSPMM_OK) *bytes = p->lay.total;
-    delete p;
-    return rc;
+    if (rc != BSPMM_OK) {
+        delete p;
+        return rc;
+    }
+    *bytes = p->lay.total;
+    remember(p, make_key(b, F, options, false, b->rpt_off));
+    return BSPMM_OK;
 }
 
 int bspmm_create(bspmm_plan** plan, const bspmm_batch* b, int32_t F,
@@ -632,10 +749,13 @@ int bspmm_create(bspmm_plan** plan, const bspmm_batch* b, int32_t F,
     const bool dry = options && (options->flags & BSPMM_DRY_RUN);
     int rc = check_batch(b, F, !dry);
     if (rc != BSPMM_OK) return rc;
-    bspmm_plan* p = new (std::nothrow) bspmm_plan;
-    if (!p) return BSPMM_EINVAL;
+    bspmm_plan* p = b->batch > 0 ? recall(make_key(b, F, options, false, b->rpt_off)) : nullptr;
+    if (!p) {
+        p = new (std::nothrow) bspmm_plan;
+        if (!p) return BSPMM_EINVAL;
+        rc = plan_host(*p, b, F, knobs_for(options, !dry));
+    }
     p->dry = dry;
-    rc = plan_host(*p, b, F, knobs_for(options, !dry));
     if (rc == BSPMM_OK && !dry) {
         p->rpt = b->rpt;
         p->colids = b->colids;
@@ -661,9 +781,13 @@ int bspmm_workspace_bytes_coo(const bspmm_coo_batch* b, int32_t F, const bspmm_o
     if (!p) return BSPMM_EINVAL;
     const bool dry = options && (options->flags & BSPMM_DRY_RUN);
     rc = plan_host_coo(*p, b, F, knobs_for(options, !dry));
-    if (rc == BSPMM_OK) *bytes = p->lay.total;
-    delete p;
-    return rc;
+    if (rc != BSPMM_OK) {
+        delete p;
+        return rc;
+    }
+    *bytes = p->lay.total;
+    remember(p, make_key(b, F, options, true, nullptr));
+    return BSPMM_OK;
 }
 
 int bspmm_create_coo(bspmm_plan** plan, const bspmm_coo_batch* b, int32_t F,
@@ -675,10 +799,13 @@ int bspmm_create_coo(bspmm_plan** plan, const bspmm_coo_batch* b, int32_t F,
     const bool dry = options && (options->flags & BSPMM_DRY_RUN);
     int rc = check_coo_batch(b, F, !dry);
     if (rc != BSPMM_OK) return rc;
-    bspmm_plan* p = new (std::nothrow) bspmm_plan;
-    if (!p) return BSPMM_EINVAL;
+    bspmm_plan* p = b->batch > 0 ? recall(make_key(b, F, options, true, nullptr)) : nullptr;
+    if (!p) {
+        p = new (std::nothrow) bspmm_plan;
+        if (!p) return BSPMM_EINVAL;
+        rc = plan_host_coo(*p, b, F, knobs_for(options, !dry));
+    }
     p->dry = dry;
-    rc = plan_host_coo(*p, b, F, knobs_for(options, !dry));
     if (rc == BSPMM_OK && !dry) {
         p->ids = b->ids;
         p->coo_values = b->values;

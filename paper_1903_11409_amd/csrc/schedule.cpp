@@ -539,7 +539,9 @@ Schedule make_schedule(const DirOps& ops, int F, const Knobs& kn_in)
 
     auto emit = [&](int draft_idx, int wg, int slot) {
         const Draft& x = d[draft_idx];
+        s.item_op.resize(s.items.size(), -1);      // empty items before this one
         s.items.push_back(to_item(ops, x));
+        s.item_op.push_back(x.op);
         s.view.push_back({x.op, x.bin, x.row0, x.nrows, x.f0, x.fw, wg, slot});
         s.items_in_bin[x.bin]++;
     };
@@ -578,7 +580,9 @@ Schedule make_schedule(const DirOps& ops, int F, const Knobs& kn_in)
                         break;
                     }
                 w.staged = 1 | (j == 0 ? (int)mem.size() << 8 : 0) | ((int)owner << 16);
+                s.item_op.resize(s.items.size(), -1);
                 s.items.push_back(w);
+                s.item_op.push_back(y.op);
                 s.view.push_back({y.op, BSPMM_BIN_WORKGROUP, x.row0, x.nrows, x.f0, x.fw, wg, (int)j});
                 s.items_in_bin[BSPMM_BIN_WORKGROUP]++;
             }
@@ -598,6 +602,7 @@ Schedule make_schedule(const DirOps& ops, int F, const Knobs& kn_in)
         wg += nwg;
         s.wg_end[r] = wg;
     }
+    s.item_op.resize(s.items.size(), -1);
     s.grid = wg;
     s.launch_grid = kn.persistent_wgs > 0 ? std::min(wg, W) : wg;
     if (kn.front > 0) {

@@ -41,6 +41,7 @@ struct Knobs {
 
 struct Schedule {
     std::vector<WorkItem> items;     // device table, launch order, padded with empty items
+    std::vector<int32_t> item_op;    // operation of every entry of `items` (-1: empty item)
     std::vector<bspmm_item> view;    // the non-empty items, for inspection
     int32_t wg_end[kRanges] = {0, 0, 0, 0, 0};
     int32_t item_base[kRanges] = {0, 0, 0, 0, 0};
