@@ -469,3 +469,47 @@ def test_front_argument_errors():
         assert K.lib().bspmm_run_gcn(h, None, 0, None, 0, None, None, 0, 0, None) == K.ESTATE
     finally:
         K.bspmm_destroy(h)
+
+
+def test_workspace_query_hands_its_schedule_to_create_only_for_the_same_batch():
+    """bspmm_workspace_bytes keeps its plan for the next bspmm_create on the thread; a batch
+    whose arrays changed in place (same addresses) must be scheduled afresh."""
+    b = W.config2_molecule(graphs=16, F=64)
+    hb = K.HostBatch(b.rows, b.cols, b.nnz, b.rpt_off, b.nz_off, b.b_row_off, b.c_row_off)
+    opts = K.make_options(flags=K.DRY_RUN)
+    n0 = K.bspmm_workspace_bytes(hb, 64, opts)
+    h = K.bspmm_create(hb, 64, opts)
+    flops0 = K.bspmm_plan_info(h).flops
+    assert K.bspmm_plan_info(h).workspace_bytes == n0
+    K.bspmm_destroy(h)
+    K.bspmm_workspace_bytes(hb, 64, opts)
+    hb.arrays[2][3] += 5                      # nnz of operation 3, edited in place
+    h = K.bspmm_create(hb, 64, opts)
+    try:
+        assert K.bspmm_plan_info(h).flops == flops0 + 2 * 5 * 64
+    finally:
+        K.bspmm_destroy(h)
+    # different F or options: no hand-over either
+    K.bspmm_workspace_bytes(hb, 64, opts)
+    h = K.bspmm_create(hb, 32, opts)
+    try:
+        assert K.bspmm_plan_info(h).F == 32
+    finally:
+        K.bspmm_destroy(h)
+    K.bspmm_workspace_bytes(hb, 64, opts)
+    h = K.bspmm_create(hb, 64, K.make_options(flags=K.DRY_RUN, max_tile=32))
+    try:
+        assert K.bspmm_plan_info(h).tile[0] <= 32
+    finally:
+        K.bspmm_destroy(h)
+
+
+def test_square_batches_share_the_schedule_of_both_directions():
+    b = W.config2_molecule(graphs=32, F=128)
+    h = K.dry_plan(b)
+    try:
+        f = [(i.op, i.bin, i.row0, i.nrows, i.f0, i.fw, i.workgroup, i.slot) for i in K.bspmm_plan_items(h, False)]
+        t = [(i.op, i.bin, i.row0, i.nrows, i.f0, i.fw, i.workgroup, i.slot) for i in K.bspmm_plan_items(h, True)]
+        assert f == t and len(f) > 0
+    finally:
+        K.bspmm_destroy(h)
