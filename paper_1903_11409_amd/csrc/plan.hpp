@@ -131,9 +131,13 @@ BSPMM_HD inline int64_t coo_lds_words(int nrows, int k, int nnz, int fw, int mod
 
 BSPMM_HD inline int pow2_ceil(int x)
 {
+#if defined(__HIP_DEVICE_COMPILE__)
+    return x <= 1 ? 1 : 1 << (32 - __builtin_clz((unsigned)(x - 1)));     // no loop on the device
+#else
     int p = 1;
     while (p < x) p <<= 1;
     return p;
+#endif
 }
 
 // LDS layout of a staged item, in 4-byte words from the start of its slot:
