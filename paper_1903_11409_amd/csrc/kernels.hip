@@ -167,9 +167,12 @@ __device__ __forceinline__ void stage_item(const LaunchParams& P, const WorkItem
     // ---- first trip: LDS writes.  Row pointers are clamped to [0, nnz] and columns to
     // [0, k) so that malformed arrays cannot make a lane leave its slot.
     if (lane <= m) sm[lane] = min(max(rv, 0), nnz);
-    if (lane < nnz) cv[lane] = make_int2((unsigned)c0 < (unsigned)k ? c0 : 0, __float_as_int(a0));
+    // (entries carry the word offset of their dense row in the tile, not the column itself:
+    // the multiplication is done once here instead of by every lane that gathers the entry)
+    if (lane < nnz)
+        cv[lane] = make_int2((unsigned)c0 < (unsigned)k ? c0 * L.stride : 0, __float_as_int(a0));
     if (lane + S < nnz)
-        cv[lane + S] = make_int2((unsigned)c1 < (unsigned)k ? c1 : 0, __float_as_int(a1));
+        cv[lane + S] = make_int2((unsigned)c1 < (unsigned)k ? c1 * L.stride : 0, __float_as_int(a1));
     float* bcol = bs + sp.l * VEC;
     if (col_ok && r0 < k) store_vec<VEC>(bcol + r0 * L.stride, t0);
     if (col_ok && r1 < k) store_vec<VEC>(bcol + r1 * L.stride, t1);
@@ -188,8 +191,9 @@ __device__ __forceinline__ void stage_item(const LaunchParams& P, const WorkItem
             cc1 = ci[q];
             aa1 = va[q];
         }
-        cv[p] = make_int2((unsigned)cc0 < (unsigned)k ? cc0 : 0, __float_as_int(aa0));
-        if (q < nnz) cv[q] = make_int2((unsigned)cc1 < (unsigned)k ? cc1 : 0, __float_as_int(aa1));
+        cv[p] = make_int2((unsigned)cc0 < (unsigned)k ? cc0 * L.stride : 0, __float_as_int(aa0));
+        if (q < nnz)
+            cv[q] = make_int2((unsigned)cc1 < (unsigned)k ? cc1 * L.stride : 0, __float_as_int(aa1));
     }
     for (int v = sp.l; WITH_TILE && !direct && v < sp.nvec; v += sp.g_lanes) {
         const float* cp = src + v * VEC;
@@ -332,10 +336,10 @@ __device__ __forceinline__ void compute_staged(const LaunchParams& P, const Work
             int p = p0;
             for (; p + 3 < p1; p += 4) {
                 const int2 e0 = cv[p], e1 = cv[p + 1], e2 = cv[p + 2], e3 = cv[p + 3];
-                const typename V::type b0 = load_vec<VEC>(bcol + e0.x * L.stride);
-                const typename V::type b1 = load_vec<VEC>(bcol + e1.x * L.stride);
-                const typename V::type b2 = load_vec<VEC>(bcol + e2.x * L.stride);
-                const typename V::type b3 = load_vec<VEC>(bcol + e3.x * L.stride);
+                const typename V::type b0 = load_vec<VEC>(bcol + e0.x);
+                const typename V::type b1 = load_vec<VEC>(bcol + e1.x);
+                const typename V::type b2 = load_vec<VEC>(bcol + e2.x);
+                const typename V::type b3 = load_vec<VEC>(bcol + e3.x);
                 V::fma(acc, __int_as_float(e0.y), b0);
                 V::fma(acc, __int_as_float(e1.y), b1);
                 V::fma(acc, __int_as_float(e2.y), b2);
@@ -343,7 +347,7 @@ __device__ __forceinline__ void compute_staged(const LaunchParams& P, const Work
             }
             for (; p < p1; ++p) {
                 const int2 e = cv[p];
-                V::fma(acc, __int_as_float(e.y), load_vec<VEC>(bcol + e.x * L.stride));
+                V::fma(acc, __int_as_float(e.y), load_vec<VEC>(bcol + e.x));
             }
             if constexpr (ACC) {
                 static_assert(VEC == 4, "accumulating stores are built for the float4 path");
@@ -365,7 +369,7 @@ __device__ __forceinline__ void compute_staged(const LaunchParams& P, const Work
         for (int h = 0; h < n_hub; ++h) {
             const int r = hub[1 + h];
             hub_row<VEC>(sm[r], sm[r + 1], [cv](int p) { return cv[p]; }, bs + sp.l * VEC,
-                         (int64_t)L.stride, sp.l < sp.nvec, sp.g_lanes, sp.groups, sp.g, sp.l,
+                         (int64_t)1 /* entries hold row offsets already */, sp.l < sp.nvec, sp.g_lanes, sp.groups, sp.g, sp.l,
                          scratch, fwp, dst + (int64_t)r * P.ld_out);
         }
     }

@@ -142,7 +142,8 @@ BSPMM_HD inline int pow2_ceil(int x)
 
 // LDS layout of a staged item, in 4-byte words from the start of its slot:
 //   [0, m+1)                      row pointers (clamped to nnz)
-//   [cv_off, cv_off + 2*nnz)      (column, value) pairs
+//   [cv_off, cv_off + 2*nnz)      (column * stride, value) pairs: the word offset of the entry's
+//                                 dense row inside the tile, and its value
 //   [b_off, b_off + k*stride)     dense tile, row stride `stride`
 //   [hub_off, total)              workgroup items only: hub-row list and reduction scratch
 struct StagedLayout {
