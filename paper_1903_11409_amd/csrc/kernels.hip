@@ -1045,8 +1045,7 @@ bspmm_coo_kernel(const CooLaunchParams P)
     int2* ent = reinterpret_cast<int2*>(bt + (st_b ? it.k * stride : 0));
     float* ev = reinterpret_cast<float*>(ent + it.nnz);
 
-    int log2L = 0;
-    while ((1 << log2L) < nvec && log2L < 6) ++log2L;
+    const int log2L = ilog2(min(64, pow2_ceil(nvec)));
     const int L = 1 << log2L;
     const int lane = tid & (L - 1);
     const int grp = tid >> log2L;
