@@ -85,6 +85,12 @@ extern "C" {
                                       The transposed product needs no build (the index roles
                                       swap).  Not combined with BSPMM_ACCUMULATE or
                                       BSPMM_SPLIT_HUB_ROWS (EINVAL)                              */
+#define BSPMM_SYMMETRIC        64u  /* the caller asserts that every A_i equals its transpose (e.g. the
+                                      symmetric normalisation D^-1/2 (A+I) D^-1/2 of an undirected
+                                      graph): bspmm_run_transposed then gathers over the same CSR
+                                      arrays and no transposed CSR is ever built.  Not checked;
+                                      with an asymmetric A_i the result is A_i . dY_i.  Operations
+                                      must be square (EINVAL)                                    */
 #define BSPMM_FLOOR_PROBE      4u  /* measurement aid: same grid, LDS and item fetches, but every
                                       item is emptied, so a run computes and writes nothing      */
 

@@ -16,7 +16,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libbspmm.so")
 
 OK, EINVAL, ENOSPACE, EHIP, EOVERLAP, ESTATE, EBADCSR, ETOOBIG = 0, -1, -2, -3, -4, -5, -6, -7
-DRY_RUN, BUILD_TRANSPOSE, FLOOR_PROBE, SPLIT_HUB_ROWS, ACCUMULATE, COO_DIRECT = 1, 2, 4, 8, 16, 32
+DRY_RUN, BUILD_TRANSPOSE, FLOOR_PROBE, SPLIT_HUB_ROWS, ACCUMULATE, COO_DIRECT, SYMMETRIC = 1, 2, 4, 8, 16, 32, 64
 BIN_WORKGROUP, BIN_WAVE, BIN_SLICE32, BIN_SLICE16, BIN_GENERIC = 0, 1, 2, 3, 4
 NUM_BINS = 5
 BIN_COO = 5          # items of a COO_DIRECT plan

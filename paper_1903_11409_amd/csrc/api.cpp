@@ -160,6 +160,7 @@ int plan_host(bspmm_plan& p, const bspmm_batch* b, int32_t F, const Knobs& kn)
     int64_t scratch_words = 0;
     int build_lds_words = 0;
     for (int i = 0; i < n; ++i) {
+        if (kn.symmetric && b->rows[i] != b->cols[i]) return BSPMM_EINVAL;
         f.m.push_back(b->rows[i]);
         f.k.push_back(b->cols[i]);
         f.nnz.push_back(b->nnz[i]);
@@ -172,8 +173,9 @@ int plan_host(bspmm_plan& p, const bspmm_batch* b, int32_t F, const Knobs& kn)
         t.m.push_back(b->cols[i]);
         t.k.push_back(b->rows[i]);
         t.nnz.push_back(b->nnz[i]);
-        t.rpt_off.push_back(rpt_t_words);
-        t.nz_off.push_back(nz_pack);
+        // (a symmetric operand is its own transpose: the same arrays serve both directions)
+        t.rpt_off.push_back(kn.symmetric ? b->rpt_off[i] : rpt_t_words);
+        t.nz_off.push_back(kn.symmetric ? b->nz_off[i] : nz_pack);
         t.in_off.push_back(b->c_row_off[i]);
         t.out_off.push_back(b->b_row_off[i]);
 
@@ -333,7 +335,7 @@ Knobs knobs_for(const bspmm_options* o, bool ask_device)
 
 int enqueue_build(bspmm_plan* p, hipStream_t s)
 {
-    if (p->transposed_built) return BSPMM_OK;
+    if (p->transposed_built || p->knobs.symmetric) return BSPMM_OK;
     hipError_t e = launch_build_transpose(
         reinterpret_cast<const OpRecord*>(p->ws + p->lay.op_records), p->batch,
         p->build_lds_bytes, p->rpt, p->colids, p->values,
@@ -381,6 +383,11 @@ int run_direction(bspmm_plan* p, int d, const float* in, float* out, int64_t ld_
         P.rpt = reinterpret_cast<const int32_t*>(p->ws + p->lay.rpt_t);
         P.colids = reinterpret_cast<const int32_t*>(p->ws + p->lay.colids_t);
         P.values = reinterpret_cast<const float*>(p->ws + p->lay.values_t);
+    }
+    if (p->knobs.symmetric) {
+        P.rpt = p->rpt;
+        P.colids = p->colids;
+        P.values = p->values;
     }
     P.in = in;
     P.out = out;
@@ -443,6 +450,7 @@ int plan_host_coo_direct(bspmm_plan& p, const bspmm_coo_batch* b, int32_t F, con
     int64_t nnz = 0, in_f = 0, out_f = 0;
     std::set<std::pair<int64_t, int32_t>> blocks_b;
     for (int i = 0; i < n; ++i) {
+        if (kn.symmetric && b->rows[i] != b->cols[i]) return BSPMM_EINVAL;
         f.m.push_back(b->rows[i]);
         f.k.push_back(b->cols[i]);
         t.m.push_back(b->cols[i]);
@@ -873,7 +881,7 @@ int bspmm_export_transposed(bspmm_plan* plan, int32_t* rpt_t, int32_t* colids_t,
                             float* values_t, void* stream)
 {
     if (!plan) return BSPMM_EINVAL;
-    if (plan->dry || plan->coo_direct) return BSPMM_ESTATE;
+    if (plan->dry || plan->coo_direct || plan->knobs.symmetric) return BSPMM_ESTATE;
     hipStream_t s = static_cast<hipStream_t>(stream);
     int rc = enqueue_build(plan, s);
     if (rc != BSPMM_OK) return rc;

@@ -369,6 +369,7 @@ Knobs resolve_knobs(const bspmm_options* o)
     k.hubs = (o->flags & BSPMM_SPLIT_HUB_ROWS) != 0;
     k.accumulate = (o->flags & BSPMM_ACCUMULATE) != 0;
     k.coo_direct = (o->flags & BSPMM_COO_DIRECT) != 0;
+    k.symmetric = (o->flags & BSPMM_SYMMETRIC) != 0;
     if (o->front_features > 0) {   // the matrix-core blocks of the fused front are 16 columns wide
         k.front = o->front_features;
         // an item also holds X_i and a weight tile: take the whole 64 KiB unless told otherwise

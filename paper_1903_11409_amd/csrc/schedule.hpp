@@ -35,6 +35,7 @@ struct Knobs {
     bool hubs = false;        // split hub rows across the workgroup (reserves LDS for it)
     int front = 0;            // > 0: columns of the layer input of bspmm_run_gcn (whole workgroups,
                               // tiles in multiples of 16 columns)
+    bool symmetric = false;   // A_i == A_i^T promised: the transposed product reads the same CSR
     bool coo_direct = false;  // COO plans: run the direct kernel instead of converting to CSR
     int persistent_wgs = 0;   // > 0: launch only this many workgroups and let them stride
 };

@@ -239,7 +239,7 @@ def test_channel_sum_full_size_and_shared_input_gradient(torch_cuda, oracle):
     opts = K.make_options(flags=K.ACCUMULATE)
     plan, _ = _check_forward(torch_cuda, oracle, b, opts)
     _check_transposed(torch_cuda, oracle, b, plan=plan)
-    # the configuration as BASELINE states it (4 outputs per graph, one shared input): forward
+    # the multi-channel configuration as specified (4 outputs per graph, one shared input): forward
     # is unchanged, and the transposed product now sums the 4 channels into the shared block
     c3 = W.config3_multichannel(with_dY=True)
     plan3, _ = _check_forward(torch_cuda, oracle, c3, opts)
@@ -391,3 +391,28 @@ def test_non_default_stream(torch_cuda, oracle):
     s.synchronize()
     ref, S = oracle.forward_batch(b)
     _assert_close(Cd.cpu().numpy(), ref, S, _owned_rows(b.c_row_off, b.rows, b.n_c_rows), "stream")
+
+
+def test_symmetric_operands_need_no_transposed_build(torch_cuda, oracle):
+    """Symmetrically normalised adjacency matrices equal their transposes: with
+    BSPMM_SYMMETRIC the backward product gathers over the forward CSR and nothing is built."""
+    torch = torch_cuda
+    for b in (W.config5_skewed(graphs=128, F=64), W.config2_molecule(F=32)):
+        if b.dY is None:
+            b.dY = np.random.default_rng(1).standard_normal((b.n_c_rows, b.F)).astype(np.float32)
+        plan = K.Plan(b, options=K.make_options(flags=K.SYMMETRIC))
+        _check_transposed(torch, oracle, b, plan=plan, what=b.name + " symmetric flag")
+        assert plan.info().transposed_built == 0
+        with pytest.raises(K.BspmmError) as e:
+            plan.export_transposed()
+        assert e.value.code == K.ESTATE
+        # and the same bits as the plan that builds the transposed CSR (sorted columns: the
+        # stable transpose of a symmetric matrix is the matrix itself, entry for entry)
+        built = K.Plan(b)
+        Yd = torch.from_numpy(b.dY).cuda()
+        G1 = torch.empty((b.n_b_rows, b.F), dtype=torch.float32, device="cuda")
+        G2 = torch.empty_like(G1)
+        plan.run_transposed(Yd, G1)
+        built.run_transposed(Yd, G2)
+        torch.cuda.synchronize()
+        assert torch.equal(G1, G2)

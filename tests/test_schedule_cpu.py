@@ -513,3 +513,16 @@ def test_square_batches_share_the_schedule_of_both_directions():
         assert f == t and len(f) > 0
     finally:
         K.bspmm_destroy(h)
+
+
+def test_symmetric_flag_needs_square_operations():
+    b = W.random_general(3, F=8, shapes=[(5, 5, 9), (4, 6, 7)], with_dY=False)
+    with pytest.raises(K.BspmmError) as e:
+        K.dry_plan(b, 8, flags=K.SYMMETRIC)
+    assert e.value.code == K.EINVAL
+    sq = W.config2_molecule(graphs=8, F=16)
+    h = K.dry_plan(sq, 16, flags=K.SYMMETRIC)
+    try:
+        assert K.bspmm_plan_info(h).transposed_supported == 1
+    finally:
+        K.bspmm_destroy(h)
