@@ -187,8 +187,11 @@ int plan_host(bspmm_plan& p, const bspmm_batch* b, int32_t F, const Knobs& kn)
         r.m = b->rows[i];
         r.k = b->cols[i];
         r.nnz = b->nnz[i];
-        r.pad_ = 0;
-        const int64_t work = (int64_t)b->cols[i] + 1 + b->nnz[i];
+        // small operations take the build kernel's register path (small = 1): at most four
+        // entries per lane, the input's row pointers in LDS as well
+        const int64_t work_small = (int64_t)b->cols[i] + 1 + b->nnz[i] + b->rows[i] + 1;
+        r.small = b->nnz[i] <= 4 * kThreads && work_small * 4 <= kMaxLdsBytes - 2048 ? 1 : 0;
+        const int64_t work = r.small ? work_small : (int64_t)b->cols[i] + 1 + b->nnz[i];
         if (work * 4 <= kMaxLdsBytes - 2048) {
             r.scratch_off = -1;
             build_lds_words = std::max<int64_t>(build_lds_words, work);
@@ -510,8 +513,8 @@ int plan_host_coo(bspmm_plan& p, const bspmm_coo_batch* b, int32_t F, const Knob
         r.m = b->cols[i];                 // bound of the payload (column)
         r.k = b->rows[i];                 // number of keys (rows)
         r.nnz = b->nnz[i];
-        r.pad_ = 0;
         const int64_t work = (int64_t)b->rows[i] + 1 + b->nnz[i];
+        r.small = b->nnz[i] <= 4 * kThreads && work * 4 <= kMaxLdsBytes - 2048 ? 1 : 0;   // register path
         if (work * 4 <= kMaxLdsBytes - 2048) {
             r.scratch_off = -1;
             lds_words = std::max(lds_words, work);

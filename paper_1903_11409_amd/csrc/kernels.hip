@@ -762,8 +762,9 @@ __global__ void __launch_bounds__(kThreads) bspmm_kernel(const LaunchParams P)
 //   entry positions with atomic cursors (arrival order is arbitrary) -> every entry finds its
 //   rank inside its column segment by counting the positions smaller than its own.
 // The result does not depend on the arrival order: it is the stable transpose.
-// `work` is k+1 counters followed by nnz positions, in LDS when it fits, else in global
-// scratch (both reached through flat addressing).
+// `work` is k+1 counters followed by nnz positions (and, for small operations, the input's
+// row pointers), in LDS when it fits, else in global scratch (both reached through flat
+// addressing).
 // ---------------------------------------------------------------------------------------
 // FROM_COO = true sorts a SparseTensor / COO operation (index pairs as in Fig. 2:
 // ids[2p] = row, ids[2p+1] = column, in any order) into CSR with the same machinery: the key is
@@ -796,6 +797,99 @@ build_sorted_kernel(const OpRecord* __restrict__ ops, const int32_t* __restrict_
         const int c = ci[p];
         return (unsigned)c < (unsigned)k ? c : -1;
     };
+
+    // ---- small operations (flagged by the host: everything in LDS, at most four entries per
+    // lane): one round trip to memory reads the operation into registers (and the row
+    // pointers into LDS, which turns the search for an entry's row into LDS reads), the scan
+    // runs on wavefront shuffles, and nothing is read twice.
+    if (o.small != 0) {
+        constexpr int E = 4;
+        int key[E], pay[E];
+        float val[E];
+        const float* va = values + o.nz_off;
+        int* rps = pos + nnz;                              // CSR input only: m+1 row pointers
+#pragma unroll
+        for (int u = 0; u < E; ++u) {
+            const int p = tid + u * kThreads;
+            key[u] = -1;
+            pay[u] = 0;
+            val[u] = 0.f;
+            if (p < nnz) {
+                if (FROM_COO) {
+                    const int r = ci[2 * p], c = ci[2 * p + 1];
+                    key[u] = ((unsigned)r < (unsigned)k && (unsigned)c < (unsigned)m) ? r : -1;
+                    pay[u] = c;
+                } else {
+                    const int c = ci[p];
+                    key[u] = (unsigned)c < (unsigned)k ? c : -1;
+                }
+                val[u] = va[p];
+            }
+        }
+        if (!FROM_COO)
+            for (int i = tid; i <= m; i += kThreads) rps[i] = rp[i];
+        for (int c = tid; c <= k; c += kThreads) cnt[c] = 0;
+        __syncthreads();
+#pragma unroll
+        for (int u = 0; u < E; ++u)
+            if (key[u] >= 0) atomicAdd(&cnt[key[u] + 1], 1);
+        __syncthreads();
+
+        // inclusive scan of cnt[0..k]: a lane sums its chunk, the wavefront scans the sums with
+        // shuffles, the four wavefront totals go through LDS
+        const int chunk = (k + 1 + kThreads - 1) / kThreads;
+        const int lo = tid * chunk;
+        const int hi = min(lo + chunk, k + 1);
+        int sum = 0;
+        for (int c = lo; c < hi; ++c) sum += cnt[c];
+        int incl = sum;
+        const int wl = tid & 63;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const int n = __shfl_up(incl, d);
+            if (wl >= d) incl += n;
+        }
+        if (wl == 63) partial[tid >> 6] = incl;
+        __syncthreads();
+        int run = incl - sum;
+        for (int w = 0; w < (tid >> 6); ++w) run += partial[w];
+        for (int c = lo; c < hi; ++c) {
+            run += cnt[c];
+            cnt[c] = run;
+            rt[c] = run;
+        }
+        __syncthreads();
+
+        // scatter positions; cnt[c] ends as the first position of column c+1
+#pragma unroll
+        for (int u = 0; u < E; ++u)
+            if (key[u] >= 0) pos[atomicAdd(&cnt[key[u]], 1)] = tid + u * kThreads;
+        __syncthreads();
+
+#pragma unroll
+        for (int u = 0; u < E; ++u) {
+            if (key[u] < 0) continue;
+            const int p = tid + u * kThreads;
+            const int c = key[u];
+            const int beg = c > 0 ? cnt[c - 1] : 0;
+            const int end = cnt[c];
+            int rank = 0;
+            for (int t = beg; t < end; ++t) rank += pos[t] < p ? 1 : 0;
+            int a = pay[u];
+            if (!FROM_COO) {
+                // row of entry p: the last r with rp[r] <= p
+                a = 0;
+                int b = m;
+                while (b - a > 1) {
+                    const int mid = (a + b) >> 1;
+                    if (rps[mid] <= p) a = mid; else b = mid;
+                }
+            }
+            colids_t[o.nz_t_off + beg + rank] = a;
+            values_t[o.nz_t_off + beg + rank] = val[u];
+        }
+        return;
+    }
 
     for (int c = tid; c <= k; c += kThreads) cnt[c] = 0;
     __syncthreads();

@@ -116,7 +116,7 @@ struct alignas(8) OpRecord {
     int32_t m;
     int32_t k;
     int32_t nnz;
-    int32_t pad_;
+    int32_t small;         // 1: the build kernel may take its register path (see there)
 };
 
 BSPMM_HD inline int round_up(int x, int a) { return (x + a - 1) / a * a; }
