@@ -35,6 +35,10 @@ def parse_args():
     ap.add_argument("--no-extra", action="store_true", help="headline measurement only")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
+    ap.add_argument("--only", default=None,
+                    choices=["cfg2", "cfg3", "cfg4_F1024", "cfg5", "cfg5_transposed"],
+                    help="run only this configuration, HBM-cold, eager launches, and print a "
+                         "short JSON line (for rocprofv3 counter runs per configuration)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run a 256 MiB elementwise copy kernel of known traffic "
                          "(scale reference for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
@@ -367,10 +371,21 @@ def cpu_baseline(oracle, b, seconds):
         dt = time.perf_counter() - t0
         if dt >= seconds:
             break
-    return {"value": round(b.n_graphs * reps / dt, 1), "unit": "graphs/s",
-            "cores": int(oracle.num_threads()), "kind": "oracle",
-            "sample": f"{reps} passes of the fp64 OpenMP oracle over the same 128-graph F=128 "
-                      f"batch in {dt:.1f} s (includes its output allocation)"}
+    out = {"value": round(b.n_graphs * reps / dt, 1), "unit": "graphs/s",
+           "cores": int(oracle.num_threads()), "kind": "oracle",
+           "sample": f"{reps} passes of the fp64 OpenMP oracle over the same 128-graph F=128 "
+                     f"batch in {dt:.1f} s (includes its output allocation)"}
+    # the same on one thread, 2 s
+    threads = oracle.num_threads()
+    oracle.set_num_threads(1)
+    reps1, t0 = 0, time.perf_counter()
+    while time.perf_counter() - t0 < 2.0:
+        oracle.forward_batch(b, want_scale=False)
+        reps1 += 1
+    dt1 = time.perf_counter() - t0
+    oracle.set_num_threads(threads)
+    out["one_thread_value"] = round(b.n_graphs * reps1 / dt1, 1)
+    return out
 
 
 def read_traffic():
@@ -397,6 +412,20 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     K.lib()
+
+    if args.only:
+        mk, tr = {"cfg2": (lambda: W.config2_molecule(F=128), False),
+                  "cfg3": (lambda: W.config3_multichannel(), False),
+                  "cfg4_F1024": (lambda: W.config4_wide(F=1024), False),
+                  "cfg5": (lambda: W.config5_skewed(), False),
+                  "cfg5_transposed": (lambda: W.config5_skewed(), True)}[args.only]
+        r = Runner(torch, K, mk(), transposed=tr)
+        steps = min(args.steps, 400)
+        sec = r.time_eager(steps, min(args.warmup, 40))
+        line = r.summary(sec)
+        line.update({"workload": args.only, "launches": steps, "mode": "eager, HBM-cold"})
+        print(json.dumps(line))
+        return
 
     b = W.config2_molecule(F=128)
     head = Runner(torch, K, b)
@@ -428,13 +457,35 @@ def main():
         floor = Runner(torch, K, b, options=K.make_options(flags=K.FLOOR_PROBE))
         fsec, _ = floor.time_graph(args.steps, args.warmup)
         extra["launch_floor_us"] = round(fsec * 1e6, 3)
+        reps = sorted(head.time_graph(args.steps, args.warmup)[0] for _ in range(5))
+        extra["headline_hipgraph_5_repeats_us"] = {"median": round(reps[2] * 1e6, 3),
+                                                   "min": round(reps[0] * 1e6, 3),
+                                                   "max": round(reps[4] * 1e6, 3)}
         extra["plan_create_ms"] = round(head.create_ms, 3)
+        # the paper's batched timings include handing the matrix list to the device: plan
+        # creation through the C ABI (schedule, upload) plus one product, device arrays in place
+        hb, ws = head.plan.hb, head.plan.workspace
+        stream = torch.cuda.current_stream().cuda_stream
+        nbytes = K.bspmm_workspace_bytes(hb, b.F, None)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(50):
+            K.bspmm_workspace_bytes(hb, b.F, None)
+            h = K.bspmm_create(hb, b.F, None, ws, nbytes, stream)
+            rc = K.lib().bspmm_run(h, head.in_ptrs[i % head.nsets], head.out_ptrs[i % head.nsets],
+                                   b.F, b.F, stream)
+            assert rc == 0
+            torch.cuda.synchronize()
+            K.bspmm_destroy(h)
+        extra["create_plus_run_us"] = round((time.perf_counter() - t0) / 50 * 1e6, 1)
         t0 = time.perf_counter()
         for _ in range(20):
             K.Plan(b).close()
         torch.cuda.synchronize()
         extra["plan_create_ms_repeat"] = round((time.perf_counter() - t0) * 1e3 / 20, 3)
         extra["copy_GBps_1GiB"] = round(copy_bandwidth(torch), 1)
+        extra["headline_frac_of_copy_bandwidth"] = round(
+            head.eff_bytes / sec * 1e-9 / extra["copy_GBps_1GiB"], 4)
         extra["non_batched"] = non_batched(torch, K, b, sec)
         others = {}
         for name, mk, tr in [
