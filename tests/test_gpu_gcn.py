@@ -173,3 +173,14 @@ def test_strided_operands_and_argument_errors(torch_cuda, oracle):
     with pytest.raises(K.BspmmError) as e:
         K.bspmm_run_gcn(plain.handle, Xd, n_x + 8, Wd, 68, bd, Yd, 76)
     assert e.value.code == K.ESTATE
+
+
+def test_empty_batch_launches_nothing(torch_cuda):
+    torch = torch_cuda
+    b = W.random_general(1, F=16, shapes=[], with_dY=False)
+    plan = K.Plan(b, options=K.make_options(front_features=8))
+    Y = torch.full((4, 16), SENTINEL, device="cuda")
+    plan.run_gcn(torch.zeros((4, 8), device="cuda"), torch.zeros((8, 16), device="cuda"),
+                 torch.zeros(16, device="cuda"), Y)
+    torch.cuda.synchronize()
+    assert torch.all(Y == SENTINEL)

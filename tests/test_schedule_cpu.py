@@ -526,3 +526,21 @@ def test_symmetric_flag_needs_square_operations():
         assert K.bspmm_plan_info(h).transposed_supported == 1
     finally:
         K.bspmm_destroy(h)
+
+
+def test_empty_batches_through_every_creation_path():
+    z32, z64 = np.zeros(0, dtype=np.int32), np.zeros(0, dtype=np.int64)
+    hc = K.HostCooBatch(z32, z32, z32, z64, z64, z64)
+    for flags in (K.DRY_RUN, K.DRY_RUN | K.COO_DIRECT, K.DRY_RUN | K.SYMMETRIC):
+        h = K.bspmm_create_coo(hc, 16, K.make_options(flags=flags))
+        try:
+            info = K.bspmm_plan_info(h)
+            assert info.batch == 0 and info.workgroups[0] == 0 and info.workgroups[1] == 0
+        finally:
+            K.bspmm_destroy(h)
+    hb = K.HostBatch(z32, z32, z32, z64, z64, z64, z64)
+    h = K.bspmm_create(hb, 16, K.make_options(flags=K.DRY_RUN, front_features=8))
+    try:
+        assert K.bspmm_plan_info(h).workgroups[0] == 0
+    finally:
+        K.bspmm_destroy(h)
