@@ -159,10 +159,12 @@ __device__ __forceinline__ void stage_item(const LaunchParams& P, const WorkItem
     const int r0 = sp.g, r1 = sp.g + step, r2 = sp.g + 2 * step, r3 = sp.g + 3 * step;
     const float* colp = src + sp.l * VEC;
     VT t0 = Vec<VEC>::zero(), t1 = Vec<VEC>::zero(), t2 = Vec<VEC>::zero(), t3 = Vec<VEC>::zero();
-    if (col_ok && r0 < k) t0 = load_vec<VEC>(colp + (int64_t)r0 * P.ld_in);
-    if (col_ok && r1 < k) t1 = load_vec<VEC>(colp + (int64_t)r1 * P.ld_in);
-    if (col_ok && r2 < k) t2 = load_vec<VEC>(colp + (int64_t)r2 * P.ld_in);
-    if (col_ok && r3 < k) t3 = load_vec<VEC>(colp + (int64_t)r3 * P.ld_in);
+    if (WITH_TILE && !direct) {     // the same for every lane: a scalar branch over the whole path
+        if (col_ok && r0 < k) t0 = load_vec<VEC>(colp + (int64_t)r0 * P.ld_in);
+        if (col_ok && r1 < k) t1 = load_vec<VEC>(colp + (int64_t)r1 * P.ld_in);
+        if (col_ok && r2 < k) t2 = load_vec<VEC>(colp + (int64_t)r2 * P.ld_in);
+        if (col_ok && r3 < k) t3 = load_vec<VEC>(colp + (int64_t)r3 * P.ld_in);
+    }
 
     // ---- first trip: LDS writes.  Row pointers are clamped to [0, nnz] and columns to
     // [0, k) so that malformed arrays cannot make a lane leave its slot.
@@ -174,13 +176,18 @@ __device__ __forceinline__ void stage_item(const LaunchParams& P, const WorkItem
     if (lane + S < nnz)
         cv[lane + S] = make_int2((unsigned)c1 < (unsigned)k ? c1 * L.stride : 0, __float_as_int(a1));
     float* bcol = bs + sp.l * VEC;
-    if (col_ok && r0 < k) store_vec<VEC>(bcol + r0 * L.stride, t0);
-    if (col_ok && r1 < k) store_vec<VEC>(bcol + r1 * L.stride, t1);
-    if (col_ok && r2 < k) store_vec<VEC>(bcol + r2 * L.stride, t2);
-    if (col_ok && r3 < k) store_vec<VEC>(bcol + r3 * L.stride, t3);
+    if (WITH_TILE && !direct) {
+        if (col_ok && r0 < k) store_vec<VEC>(bcol + r0 * L.stride, t0);
+        if (col_ok && r1 < k) store_vec<VEC>(bcol + r1 * L.stride, t1);
+        if (col_ok && r2 < k) store_vec<VEC>(bcol + r2 * L.stride, t2);
+        if (col_ok && r3 < k) store_vec<VEC>(bcol + r3 * L.stride, t3);
+    }
 
-    // ---- leftovers of larger items
-    for (int i = lane + S; i <= m; i += S) sm[i] = min(max(rp[i], 0), nnz);
+    // ---- leftovers of larger items (each behind a condition that is the same for every
+    // lane, so that a small item jumps over them instead of walking through masked-off code)
+    if (m >= S)
+        for (int i = lane + S; i <= m; i += S) sm[i] = min(max(rp[i], 0), nnz);
+    if (nnz > 2 * S)
     for (int p = lane + 2 * S; p < nnz; p += 2 * S) {
         const int q = p + S;
         const int cc0 = ci[p];
@@ -195,7 +202,8 @@ __device__ __forceinline__ void stage_item(const LaunchParams& P, const WorkItem
         if (q < nnz)
             cv[q] = make_int2((unsigned)cc1 < (unsigned)k ? cc1 * L.stride : 0, __float_as_int(aa1));
     }
-    for (int v = sp.l; WITH_TILE && !direct && v < sp.nvec; v += sp.g_lanes) {
+    if (WITH_TILE && !direct)
+    for (int v = sp.l; v < sp.nvec; v += sp.g_lanes) {
         const float* cp = src + v * VEC;
         float* bp = bs + v * VEC;
         for (int row = (v == sp.l ? sp.g + 4 * step : sp.g); row < k; row += 4 * step) {
