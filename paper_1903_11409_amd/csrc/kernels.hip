@@ -166,6 +166,10 @@ __device__ __forceinline__ void stage_item(const LaunchParams& P, const WorkItem
         if (col_ok && r3 < k) t3 = load_vec<VEC>(colp + (int64_t)r3 * P.ld_in);
     }
 
+    // No use of a loaded value may be scheduled above this line: the wait in front of it would
+    // hold back the loads that have not been issued yet and cost a second round trip.
+    __builtin_amdgcn_sched_barrier(0);
+
     // ---- first trip: LDS writes.  Row pointers are clamped to [0, nnz] and columns to
     // [0, k) so that malformed arrays cannot make a lane leave its slot.
     if (lane <= m) sm[lane] = min(max(rv, 0), nnz);
