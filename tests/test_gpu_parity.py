@@ -416,3 +416,21 @@ def test_symmetric_operands_need_no_transposed_build(torch_cuda, oracle):
         built.run_transposed(Yd, G2)
         torch.cuda.synchronize()
         assert torch.equal(G1, G2)
+
+
+def test_autograd_wrapper_backward_is_the_transposed_product(torch_cuda, oracle):
+    torch = torch_cuda
+    from paper_1903_11409_amd.autograd import batched_spmm
+    b = W.config5_skewed(graphs=64, F=32, asymmetric=True)
+    plan = K.Plan(b)
+    Bd = torch.from_numpy(b.B).cuda().requires_grad_(True)
+    C = batched_spmm(plan, Bd, b.n_c_rows)
+    Yd = torch.from_numpy(b.dY).cuda()
+    (C * Yd).sum().backward()
+    torch.cuda.synchronize()
+    ref, S = oracle.forward_batch(b)
+    own = _owned_rows(b.c_row_off, b.rows, b.n_c_rows)
+    assert np.all(np.abs(C.detach().cpu().numpy()[own] - ref[own]) <= TOL * S[own])
+    G, SG = oracle.transposed_batch(b)
+    own_b = _owned_rows(b.b_row_off, b.cols, b.n_b_rows)
+    assert np.all(np.abs(Bd.grad.cpu().numpy()[own_b] - G[own_b]) <= TOL * SG[own_b])
