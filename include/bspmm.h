@@ -226,7 +226,8 @@ int bspmm_create(bspmm_plan** plan, const bspmm_batch* b, int32_t F,
  * C_i = A_i . B_i for every operation, one kernel launch on `stream` (Fig. 4 per row, batched
  * as in Sec. IV-C).  B and C are DEVICE pointers to the packed matrices, ldb/ldc their leading
  * dimensions in floats (>= F).  B and C must not alias.  A plan with batch == 0 launches
- * nothing.  The vectorised path needs 16-byte aligned B, C and ldb % 4 == ldc % 4 == 0;
+ * nothing.  B may be NULL when it has no rows at all, that is when no operation has both
+ * rows and columns (nothing is read then; the same holds for dY of bspmm_run_transposed).  The vectorised path needs 16-byte aligned B, C and ldb % 4 == ldc % 4 == 0;
  * anything else silently takes the scalar path.
  */
 int bspmm_run(bspmm_plan* plan, const float* B, float* C, int64_t ldb, int64_t ldc,

@@ -147,6 +147,14 @@ def _ptr(t) -> Optional[int]:
     return t.data_ptr()
 
 
+def _ld(t, width: int) -> int:
+    """Leading dimension of a row-major matrix held in a tensor; a tensor with fewer than two
+    rows (torch gives an empty one strides of zero) has none of its own and takes its width."""
+    if t.dim() != 2 or t.shape[0] < 2:
+        return max(int(width), int(t.shape[-1]) if t.dim() else 0)
+    return int(t.stride(0))
+
+
 def _stream_handle(stream) -> Optional[int]:
     if stream is None:
         import torch
@@ -367,18 +375,17 @@ class Plan:
         self.handle = bspmm_create(self.hb, self.F, options, self.workspace, nbytes, stream)
 
     def run(self, B, C, stream=None):
-        bspmm_run(self.handle, B, C, B.stride(0) if B.dim() == 2 else self.F,
-                  C.stride(0) if C.dim() == 2 else self.F, stream)
+        bspmm_run(self.handle, B, C, _ld(B, self.F), _ld(C, self.F), stream)
         return C
 
     def run_gcn(self, X, W, bias, Y, accumulate: bool = False, stream=None):
         """Y (+)= A (X W + bias) in one launch (plan created with ``front_features``)."""
-        bspmm_run_gcn(self.handle, X, X.stride(0), W, W.stride(0), bias, Y, Y.stride(0),
+        bspmm_run_gcn(self.handle, X, _ld(X, X.shape[-1]), W, _ld(W, self.F), bias, Y, _ld(Y, self.F),
                       accumulate, stream)
         return Y
 
     def run_transposed(self, dY, G, stream=None):
-        bspmm_run_transposed(self.handle, dY, G, dY.stride(0), G.stride(0), stream)
+        bspmm_run_transposed(self.handle, dY, G, _ld(dY, self.F), _ld(G, self.F), stream)
         return G
 
     def export_transposed(self, stream=None):

@@ -85,6 +85,7 @@ struct bspmm_plan {
     bool transposed_built = false;
     int64_t effective_bytes[2] = {0, 0};
     int64_t flops = 0;
+    bool reads_dense = false;   // some operation has rows and columns: the runs read the dense input
     // borrowed device pointers
     const int32_t* rpt = nullptr;
     const int32_t* colids = nullptr;
@@ -256,6 +257,7 @@ int plan_host(bspmm_plan& p, const bspmm_batch* b, int32_t F, const Knobs& kn)
             out_f += 4 * (int64_t)b->rows[i] * F;
         }
         nnz += b->nnz[i];
+        if (b->rows[i] > 0 && b->cols[i] > 0) p.reads_dense = true;
     }
     p.effective_bytes[0] = csr_f + in_f + out_f;
     p.effective_bytes[1] = csr_t + in_t + out_t;
@@ -357,7 +359,7 @@ int run_direction(bspmm_plan* p, int d, const float* in, float* out, int64_t ld_
     if (p->coo_direct) {
         const CooSchedule& cs = p->coo_sched[d];
         if (cs.items.empty()) return BSPMM_OK;
-        if (!in || !out || ld_in < p->F || ld_out < p->F) return BSPMM_EINVAL;
+        if ((!in && p->reads_dense) || !out || ld_in < p->F || ld_out < p->F) return BSPMM_EINVAL;
         CooLaunchParams C;
         C.items = reinterpret_cast<const CooItem*>(p->ws + p->lay.items[d]);
         C.ids = p->ids;
@@ -375,7 +377,8 @@ int run_direction(bspmm_plan* p, int d, const float* in, float* out, int64_t ld_
     }
     const Schedule& sc = p->sched[d];
     if (sc.grid == 0) return BSPMM_OK;
-    if (!in || !out || ld_in < p->F || ld_out < p->F) return BSPMM_EINVAL;
+    // when no operation has both rows and columns nothing is read: the input may have no rows at all
+    if ((!in && p->reads_dense) || !out || ld_in < p->F || ld_out < p->F) return BSPMM_EINVAL;
     LaunchParams P;
     P.items = reinterpret_cast<const WorkItem*>(p->ws + p->lay.items[d]);
     if (d == 0) {
@@ -468,6 +471,7 @@ int plan_host_coo_direct(bspmm_plan& p, const bspmm_coo_batch* b, int32_t F, con
         t.in_off.push_back(b->c_row_off[i]);
         t.out_off.push_back(b->b_row_off[i]);
         nnz += b->nnz[i];
+        if (b->rows[i] > 0 && b->cols[i] > 0) p.reads_dense = true;
         if (blocks_b.emplace(b->b_row_off[i], b->cols[i]).second) in_f += 4 * (int64_t)b->cols[i] * F;
         out_f += 4 * (int64_t)b->rows[i] * F;
     }
@@ -873,7 +877,7 @@ int bspmm_run_transposed(bspmm_plan* plan, const float* dY, float* G, int64_t ld
     if (plan->dry || !plan->transposed_supported) return BSPMM_ESTATE;
     if (plan->coo_direct)
         return run_direction(plan, 1, dY, G, ldy, ldg, static_cast<hipStream_t>(stream));
-    if (plan->sched[1].grid > 0 && (!dY || !G || ldy < plan->F || ldg < plan->F))
+    if (plan->sched[1].grid > 0 && ((!dY && plan->reads_dense) || !G || ldy < plan->F || ldg < plan->F))
         return BSPMM_EINVAL;
     int rc = enqueue_build(plan, static_cast<hipStream_t>(stream));
     if (rc != BSPMM_OK) return rc;

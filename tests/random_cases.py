@@ -1,0 +1,79 @@
+"""Seeded random batches and scheduler options for the property tests.
+
+One seed gives one case: a mix of operation shapes (empty, tiny, molecule-sized, a few hundred
+rows, strongly rectangular), a feature width and a handful of scheduler knobs.  The CPU tests
+check the schedule of every case against the coverage and capacity invariants; the GPU tests
+run the same cases and compare with the oracle, so a corner of the scheduler that the
+workload configurations never reach is still exercised on both sides.
+"""
+import numpy as np
+
+from paper_1903_11409_amd import bspmm as K
+from paper_1903_11409_amd import workloads as W
+
+FEATURES = [1, 2, 4, 7, 8, 12, 16, 20, 32, 48, 64, 100, 128, 200, 256, 384]
+
+
+def _shape(rng, kind):
+    if kind == 0:   # nothing to do
+        return [(0, 0, 0), (0, 5, 0), (5, 0, 0), (4, 4, 0)][int(rng.integers(4))]
+    if kind == 1:   # a few rows
+        m, n = int(rng.integers(1, 9)), int(rng.integers(1, 9))
+    elif kind == 2:   # molecule-sized, square
+        m = n = int(rng.integers(10, 61))
+    elif kind == 3:   # a few hundred rows, square
+        m = n = int(rng.integers(61, 400))
+    elif kind == 4:   # short and wide / tall and narrow
+        m, n = int(rng.integers(1, 6)), int(rng.integers(200, 1500))
+        if rng.integers(2):
+            m, n = n, m
+    else:   # larger than any LDS budget at full width
+        m = n = int(rng.integers(400, 2500))
+    per_row = [0.3, 1.0, 2.5, 5.0, 20.0][int(rng.integers(5))]
+    return (m, n, int(min(per_row * m, 40000)))
+
+
+def random_case(seed, max_ops=200, max_nnz=250_000, with_dY=True):
+    """(batch, options as keyword dict) of one seed."""
+    rng = np.random.default_rng(0xB5B0 + seed)
+    batch = [1, 2, 5, 17, 60, max_ops][int(rng.integers(6))]
+    kinds_p = np.array([1, 3, 6, 2, 1, 0.5])
+    if batch > 60:
+        kinds_p[5] = 0.05
+    kinds = rng.choice(6, size=batch, p=kinds_p / kinds_p.sum())
+    shapes, total = [], 0
+    for kd in kinds:
+        s = _shape(rng, int(kd))
+        if total + s[2] > max_nnz:
+            s = (s[0], s[1], min(s[2], s[0]))
+        total += s[2]
+        shapes.append(s)
+    F = FEATURES[int(rng.integers(len(FEATURES)))]
+    b = W.random_general(1000 + seed, F=F, shapes=shapes, sort_columns=bool(rng.integers(2)),
+                         with_dY=with_dY, shuffle_blocks=bool(rng.integers(2)))
+    opts = {}
+    pick = lambda values: values[int(rng.integers(len(values)))]
+    if rng.random() < 0.4:
+        opts["lds_bytes"] = pick([4096, 8192, 16384, 32768, 65536])
+    if rng.random() < 0.3:
+        opts["min_tile"] = pick([4, 8, 16, 32])
+    if rng.random() < 0.3:
+        opts["max_tile"] = pick([32, 64, 128, 256])
+    if rng.random() < 0.4:
+        opts["target_workgroups"] = pick([1, 64, 512, 4096])
+    if rng.random() < 0.35:
+        opts["force_bin"] = pick([K.BIN_WORKGROUP, K.BIN_WAVE, K.BIN_SLICE32, K.BIN_SLICE16,
+                                  K.BIN_GENERIC])
+    if rng.random() < 0.3:
+        opts["wg_passes"] = pick([1, 2, -1])
+    if rng.random() < 0.25:
+        opts["max_passes"] = pick([1, 2, 4])
+    if rng.random() < 0.2:
+        opts["lds_pad"] = pick([4, 8])
+    if rng.random() < 0.2:
+        opts["flags"] = K.SPLIT_HUB_ROWS
+    if rng.random() < 0.2:
+        opts["resident_workgroups"] = pick([8, 64, 300])
+    if rng.random() < 0.2:
+        opts["generic_rows"] = pick([4, 8, 64])
+    return b, opts

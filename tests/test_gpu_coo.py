@@ -298,3 +298,22 @@ def test_direct_scalar_path_for_unaligned_operands(torch_cuda, oracle):
     _assert_close(Cd[:, :b.F].cpu().numpy(), ref, S, _owned(b.c_row_off, b.rows, b.n_c_rows),
                   "direct unaligned")
     assert torch.all(Cd[:, b.F:] == SENTINEL) and float(store[0]) == SENTINEL
+
+
+@pytest.mark.parametrize("block", range(4))
+def test_random_batches_and_knobs_from_coo(torch_cuda, oracle, block):
+    """Seeded random shapes, feature widths and knobs: the converted route with every knob,
+    the direct kernel on every third case with the knobs it knows."""
+    from random_cases import random_case
+    for seed in range(200 + 10 * block, 200 + 10 * block + 10):
+        b, kw = random_case(seed, max_ops=120, max_nnz=120_000)
+        ids, vals = W.coo_view(b, seed=seed)
+        flags = kw.pop("flags", 0)
+        force_bin = kw.pop("force_bin", None)
+        what = f"seed {seed} {kw} flags={flags} bin={force_bin}"
+        _check(torch_cuda, oracle, b, ids, vals, what=what,
+               opts=K.make_options(flags=flags, force_bin=force_bin, **kw))
+        if seed % 3 == 0:
+            few = {k: v for k, v in kw.items() if k in ("lds_bytes", "min_tile", "max_tile")}
+            _check(torch_cuda, oracle, b, ids, vals, what=what + " direct", csr=False,
+                   opts=K.make_options(flags=K.COO_DIRECT, **few))

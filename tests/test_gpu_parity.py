@@ -434,3 +434,19 @@ def test_autograd_wrapper_backward_is_the_transposed_product(torch_cuda, oracle)
     G, SG = oracle.transposed_batch(b)
     own_b = _owned_rows(b.b_row_off, b.cols, b.n_b_rows)
     assert np.all(np.abs(Bd.grad.cpu().numpy()[own_b] - G[own_b]) <= TOL * SG[own_b])
+
+
+@pytest.mark.parametrize("block", range(12))
+def test_random_batches_and_knobs(torch_cuda, oracle, block):
+    """The seeded random cases of the scheduler's property test, forward and transposed."""
+    from random_cases import random_case
+    for seed in range(16 * block, 16 * block + 16):
+        b, kw = random_case(seed)
+        what = f"seed {seed} F={b.F} batch={b.batch} {kw}"
+        print(what, flush=True)
+        flags = kw.pop("flags", 0)
+        force_bin = kw.pop("force_bin", None)
+        opts = K.make_options(flags=flags, force_bin=force_bin, **kw)
+        plan, _ = _check_forward(torch_cuda, oracle, b, opts, what=what)
+        if plan.info().transposed_supported:
+            _check_transposed(torch_cuda, oracle, b, plan=plan, what=what)

@@ -380,7 +380,10 @@ def test_coo_argument_errors():
 ])
 @pytest.mark.parametrize("transposed", [False, True])
 def test_direct_coo_schedule_covers_every_element_once(maker, F, kw, transposed):
-    b = maker()
+    _check_direct_coo_schedule(maker(), F, kw, transposed)
+
+
+def _check_direct_coo_schedule(b, F, kw, transposed):
     h = K.dry_plan(b, F, coo=True, flags=K.COO_DIRECT, **kw)
     try:
         info = K.bspmm_plan_info(h)
@@ -544,3 +547,28 @@ def test_empty_batches_through_every_creation_path():
         assert K.bspmm_plan_info(h).workgroups[0] == 0
     finally:
         K.bspmm_destroy(h)
+
+
+@pytest.mark.parametrize("block", range(16))
+def test_random_batches_and_knobs_keep_the_invariants(block):
+    """Seeded random mixes of shapes, feature widths and knobs, both directions."""
+    from random_cases import random_case
+    for seed in range(16 * block, 16 * block + 16):
+        b, opts = random_case(seed, with_dY=False)
+        try:
+            _check_schedule(b, b.F, **opts)
+            _check_schedule(b, b.F, transposed=True, **opts)
+        except AssertionError as e:
+            raise AssertionError(f"seed {seed} F={b.F} batch={b.batch} opts={opts}: {e}") from e
+
+
+def test_random_batches_through_the_direct_coo_schedule():
+    from random_cases import random_case
+    for seed in range(200, 240, 3):
+        b, kw = random_case(seed, max_ops=120, max_nnz=120_000, with_dY=False)
+        few = {k: v for k, v in kw.items() if k in ("lds_bytes", "min_tile", "max_tile")}
+        for transposed in (False, True):
+            try:
+                _check_direct_coo_schedule(b, b.F, few, transposed)
+            except AssertionError as e:
+                raise AssertionError(f"seed {seed} F={b.F} {few} transposed={transposed}: {e}") from e
