@@ -143,7 +143,9 @@ typedef struct bspmm_coo_batch {
 typedef struct bspmm_options {
     uint32_t flags;            /* BSPMM_DRY_RUN | BSPMM_BUILD_TRANSPOSE | BSPMM_SPLIT_HUB_ROWS */
     int32_t  force_bin;        /* 0 = automatic; 1+b forces bin b for every op that fits it    */
-    int32_t  lds_bytes;        /* LDS per workgroup, 0 = default (24 KiB); <= 64 KiB           */
+    int32_t  lds_bytes;        /* LDS per workgroup; <= 160 KiB (all of a CU's).  0 = 24 KiB,
+                                  and 64 KiB, then 160 KiB, are tried before a batch whose
+                                  summed operations need more is refused with ETOOBIG          */
     int32_t  min_tile;         /* narrowest feature tile in floats, 0 = default (32)           */
     int32_t  max_tile;         /* widest feature tile in floats, 0 = default (256), <= 256     */
     int32_t  target_workgroups;/* split tiles until the launch has this many, 0 = 4 per CU    */

@@ -191,9 +191,9 @@ int plan_host(bspmm_plan& p, const bspmm_batch* b, int32_t F, const Knobs& kn)
         // small operations take the build kernel's register path (small = 1): at most four
         // entries per lane, the input's row pointers in LDS as well
         const int64_t work_small = (int64_t)b->cols[i] + 1 + b->nnz[i] + b->rows[i] + 1;
-        r.small = b->nnz[i] <= 4 * kThreads && work_small * 4 <= kMaxLdsBytes - 2048 ? 1 : 0;
+        r.small = b->nnz[i] <= 4 * kThreads && work_small * 4 <= kBuildLdsBytes - 2048 ? 1 : 0;
         const int64_t work = r.small ? work_small : (int64_t)b->cols[i] + 1 + b->nnz[i];
-        if (work * 4 <= kMaxLdsBytes - 2048) {
+        if (work * 4 <= kBuildLdsBytes - 2048) {
             r.scratch_off = -1;
             build_lds_words = std::max<int64_t>(build_lds_words, work);
         } else {
@@ -235,6 +235,7 @@ int plan_host(bspmm_plan& p, const bspmm_batch* b, int32_t F, const Knobs& kn)
         kt.front = 0;                     // the layer input is a forward-only guest
         p.sched[1] = make_schedule(t, F, kt);
         if (p.sched[1].error) {          // the forward product still works
+            if (kn.need_both && p.sched[1].error == BSPMM_ETOOBIG) return BSPMM_ETOOBIG;
             p.sched[1] = Schedule();
             p.transposed_supported = false;
         }
@@ -336,6 +337,33 @@ Knobs knobs_for(const bspmm_options* o, bool ask_device)
     kn.capacity_wgs = r > 0 ? r : 6 * kn.compute_units;
     kn.capacity_wgs_slices = rs > 0 ? rs : 4 * kn.compute_units;
     return kn;
+}
+
+// Host planning with the LDS budget the caller gave.  When the caller left it open and the
+// batch does not fit the default (operations summed into one block share a workgroup's LDS),
+// larger budgets are tried before the batch is refused: first asking for both directions,
+// then for the forward product alone.
+template <class Batch, class PlanFn>
+int plan_with_budget(bspmm_plan& p, const Batch* b, int32_t F, const bspmm_options* options,
+                     bool dry, PlanFn plan_fn)
+{
+    const bool open = !(options && (options->lds_bytes > 0 || options->front_features > 0));
+    Knobs kn = knobs_for(options, !dry);
+    kn.need_both = open;
+    int rc = plan_fn(p, b, F, kn);
+    if (rc != BSPMM_ETOOBIG || !open) return rc;
+    static const struct { int bytes; bool both; } attempts[] = {
+        {kFrontLdsBytes, true}, {kMaxLdsBytes, true}, {0, false}, {kFrontLdsBytes, false}, {kMaxLdsBytes, false}};
+    for (const auto& a : attempts) {
+        bspmm_options o = options ? *options : bspmm_options{};
+        o.lds_bytes = a.bytes;
+        kn = knobs_for(&o, !dry);
+        kn.need_both = a.both;
+        p = bspmm_plan();
+        rc = plan_fn(p, b, F, kn);
+        if (rc != BSPMM_ETOOBIG) return rc;
+    }
+    return rc;
 }
 
 int enqueue_build(bspmm_plan* p, hipStream_t s)
@@ -518,8 +546,8 @@ int plan_host_coo(bspmm_plan& p, const bspmm_coo_batch* b, int32_t F, const Knob
         r.k = b->rows[i];                 // number of keys (rows)
         r.nnz = b->nnz[i];
         const int64_t work = (int64_t)b->rows[i] + 1 + b->nnz[i];
-        r.small = b->nnz[i] <= 4 * kThreads && work * 4 <= kMaxLdsBytes - 2048 ? 1 : 0;   // register path
-        if (work * 4 <= kMaxLdsBytes - 2048) {
+        r.small = b->nnz[i] <= 4 * kThreads && work * 4 <= kBuildLdsBytes - 2048 ? 1 : 0;   // register path
+        if (work * 4 <= kBuildLdsBytes - 2048) {
             r.scratch_off = -1;
             lds_words = std::max(lds_words, work);
         } else {
@@ -745,7 +773,7 @@ int bspmm_workspace_bytes(const bspmm_batch* b, int32_t F, const bspmm_options* 
     bspmm_plan* p = new (std::nothrow) bspmm_plan;
     if (!p) return BSPMM_EINVAL;
     const bool dry = options && (options->flags & BSPMM_DRY_RUN);
-    rc = plan_host(*p, b, F, knobs_for(options, !dry));
+    rc = plan_with_budget(*p, b, F, options, dry, plan_host);
     if (rc != BSPMM_OK) {
         delete p;
         return rc;
@@ -768,7 +796,7 @@ int bspmm_create(bspmm_plan** plan, const bspmm_batch* b, int32_t F,
     if (!p) {
         p = new (std::nothrow) bspmm_plan;
         if (!p) return BSPMM_EINVAL;
-        rc = plan_host(*p, b, F, knobs_for(options, !dry));
+        rc = plan_with_budget(*p, b, F, options, dry, plan_host);
     }
     p->dry = dry;
     if (rc == BSPMM_OK && !dry) {
@@ -795,7 +823,7 @@ int bspmm_workspace_bytes_coo(const bspmm_coo_batch* b, int32_t F, const bspmm_o
     bspmm_plan* p = new (std::nothrow) bspmm_plan;
     if (!p) return BSPMM_EINVAL;
     const bool dry = options && (options->flags & BSPMM_DRY_RUN);
-    rc = plan_host_coo(*p, b, F, knobs_for(options, !dry));
+    rc = plan_with_budget(*p, b, F, options, dry, plan_host_coo);
     if (rc != BSPMM_OK) {
         delete p;
         return rc;
@@ -818,7 +846,7 @@ int bspmm_create_coo(bspmm_plan** plan, const bspmm_coo_batch* b, int32_t F,
     if (!p) {
         p = new (std::nothrow) bspmm_plan;
         if (!p) return BSPMM_EINVAL;
-        rc = plan_host_coo(*p, b, F, knobs_for(options, !dry));
+        rc = plan_with_budget(*p, b, F, options, dry, plan_host_coo);
     }
     p->dry = dry;
     if (rc == BSPMM_OK && !dry) {

@@ -374,7 +374,7 @@ Knobs resolve_knobs(const bspmm_options* o)
         k.front = o->front_features;
         // an item also holds X_i and a weight tile: take the whole 64 KiB unless told otherwise
         // (the launch asks only for what its largest item needs)
-        if (o->lds_bytes <= 0) k.lds_words = kMaxLdsBytes / 4;
+        if (o->lds_bytes <= 0) k.lds_words = kFrontLdsBytes / 4;
         k.max_tile = std::max(16, k.max_tile / 16 * 16);
         k.min_tile = o->min_tile > 0 ? std::min(std::max(16, (k.min_tile + 15) / 16 * 16), k.max_tile) : 16;
     }

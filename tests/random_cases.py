@@ -77,3 +77,57 @@ def random_case(seed, max_ops=200, max_nnz=250_000, with_dY=True):
     if rng.random() < 0.2:
         opts["generic_rows"] = pick([4, 8, 64])
     return b, opts
+
+
+def _random_csr(rng, m, n, z, sort_columns):
+    r = rng.integers(0, max(m, 1), size=z)
+    c = rng.integers(0, max(n, 1), size=z)
+    v = rng.uniform(-1.0, 1.0, size=z)
+    order = np.lexsort((c, r)) if sort_columns else np.argsort(r, kind="stable")
+    r, c, v = r[order], c[order], v[order]
+    rpt = np.zeros(m + 1, dtype=np.int32)
+    rpt[1:] = np.cumsum(np.bincount(r, minlength=m) if z else np.zeros(m, dtype=np.int64))
+    return rpt, c.astype(np.int32), v.astype(np.float32)
+
+
+def random_summed_case(seed, with_dY=True):
+    """Groups of one to eight operations that are added into one output block (the layer's
+    channel sum with BSPMM_ACCUMULATE): the members of a group share the row count; they read
+    one shared dense block (same column count) or a block each (any column counts)."""
+    rng = np.random.default_rng(0x5B77 + seed)
+    groups = [1, 3, 12, 50][int(rng.integers(4))]
+    ops, b_block_of_op, b_block_rows, c_block_of_op = [], [], [], []
+    for g in range(groups):
+        m = int(rng.integers(1, 140)) if rng.random() < 0.9 else int(rng.integers(140, 600))
+        members = int(rng.integers(1, 9))
+        shared = bool(rng.integers(2))
+        n_shared = m if rng.integers(2) else int(rng.integers(1, 140))
+        if shared:
+            b_block_rows.append(n_shared)
+        for _ in range(members):
+            n = n_shared if shared else int(rng.integers(1, 140))
+            per_row = [0.0, 0.3, 1.0, 3.0, 8.0][int(rng.integers(5))]
+            rpt, ci, va = _random_csr(rng, m, n, int(per_row * m), bool(rng.integers(2)))
+            ops.append((m, n, rpt, ci, va))
+            if not shared:
+                b_block_rows.append(n)
+            b_block_of_op.append(len(b_block_rows) - 1)
+            c_block_of_op.append(g)
+    F = [1, 4, 8, 20, 32, 63, 64, 100, 128, 256][int(rng.integers(10))]
+    b = W.assemble("summed", F, ops, b_block_of_op, b_block_rows, rng, with_dY=with_dY,
+                   n_graphs=groups, c_block_of_op=c_block_of_op)
+    opts = {"flags": K.ACCUMULATE}
+    pick = lambda values: values[int(rng.integers(len(values)))]
+    if rng.random() < 0.3:
+        opts["lds_bytes"] = pick([16384, 32768, 65536])
+    if rng.random() < 0.3:
+        opts["min_tile"] = pick([4, 8, 16])
+    if rng.random() < 0.3:
+        opts["max_tile"] = pick([32, 64, 128])
+    if rng.random() < 0.3:
+        opts["target_workgroups"] = pick([1, 64, 4096])
+    if rng.random() < 0.2:
+        opts["resident_workgroups"] = pick([8, 64])
+    if rng.random() < 0.2:
+        opts["lds_pad"] = 4
+    return b, opts

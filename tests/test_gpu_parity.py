@@ -278,6 +278,7 @@ def test_every_bin_alone(torch_cuda, oracle, bin_, F):
 
 @pytest.mark.parametrize("kw", [{"lds_pad": 4}, {"lds_pad": 8}, {"min_tile": 16},
                                 {"max_tile": 64}, {"lds_bytes": 65536}, {"lds_bytes": 8192},
+                                {"lds_bytes": 163840}, {"lds_bytes": 131072, "min_tile": 256},
                                 {"target_workgroups": 64}, {"max_passes": 4},
                                 {"wg_passes": 1}, {"wg_passes": -1, "target_workgroups": 4096},
                                 {"resident_workgroups": 64}, {"resident_workgroups": 24},
@@ -450,3 +451,50 @@ def test_random_batches_and_knobs(torch_cuda, oracle, block):
         plan, _ = _check_forward(torch_cuda, oracle, b, opts, what=what)
         if plan.info().transposed_supported:
             _check_transposed(torch_cuda, oracle, b, plan=plan, what=what)
+
+
+@pytest.mark.parametrize("block", range(4))
+def test_random_summed_groups(torch_cuda, oracle, block):
+    """Random groups of one to eight operations added into one block (rectangular members,
+    shared or own inputs, any feature width), forward and transposed; groups that do not fit
+    on chip are refused at plan creation and skipped here."""
+    from random_cases import random_summed_case
+    ran = 0
+    for seed in range(15 * block, 15 * block + 15):
+        b, kw = random_summed_case(seed)
+        what = f"summed seed {seed} F={b.F} batch={b.batch} {kw}"
+        print(what, flush=True)
+        opts = K.make_options(**kw)
+        try:
+            plan, _ = _check_forward(torch_cuda, oracle, b, opts, what=what)
+        except K.BspmmError as e:
+            assert e.code == K.ETOOBIG, what
+            continue
+        ran += 1
+        if plan.info().transposed_supported:
+            _check_transposed(torch_cuda, oracle, b, plan=plan, what=what)
+    assert ran >= 5
+
+
+def test_summed_groups_take_a_larger_lds_budget_when_they_need_it(torch_cuda, oracle):
+    """Four channels of 400-node graphs do not fit the default 24 KiB together: with lds_bytes
+    left open the plan moves to 64 KiB, then to the CU's whole 160 KiB, instead of refusing."""
+    from random_cases import _random_csr
+    rng = np.random.default_rng(5)
+    for m, per_row, want in [(150, 2, 65536), (400, 5, 163840)]:
+        ops, blocks = [], []
+        for g in range(3):
+            for _ in range(4):
+                rpt, ci, va = _random_csr(rng, m, m, per_row * m, True)
+                ops.append((m, m, rpt, ci, va))
+                blocks.append(g)
+        b = W.assemble("big_summed", 64, ops, blocks, [m] * 3, rng, with_dY=True, n_graphs=3,
+                       c_block_of_op=blocks)
+        plan, _ = _check_forward(torch_cuda, oracle, b, K.make_options(flags=K.ACCUMULATE),
+                                 what=f"summed m={m}")
+        info = plan.info()
+        assert info.lds_bytes == want and info.fused_tasks[0] > 0 and info.transposed_supported
+        _check_transposed(torch_cuda, oracle, b, plan=plan, what=f"summed m={m}")
+        with pytest.raises(K.BspmmError) as e:      # a budget the caller fixed is kept
+            K.Plan(b, options=K.make_options(flags=K.ACCUMULATE, lds_bytes=24576))
+        assert e.value.code == K.ETOOBIG

@@ -150,7 +150,7 @@ def test_forced_bins_still_cover(bin_):
 
 
 @pytest.mark.parametrize("opts", [{"lds_pad": 4}, {"min_tile": 16}, {"max_tile": 64},
-                                  {"lds_bytes": 65536}, {"lds_bytes": 8192},
+                                  {"lds_bytes": 65536}, {"lds_bytes": 8192}, {"lds_bytes": 163840},
                                   {"target_workgroups": 64}, {"max_passes": 4},
                                   {"wg_passes": 1}, {"wg_passes": -1, "target_workgroups": 4096},
                                   {"resident_workgroups": 64}, {"resident_workgroups": 24},
@@ -572,3 +572,22 @@ def test_random_batches_through_the_direct_coo_schedule():
                 _check_direct_coo_schedule(b, b.F, few, transposed)
             except AssertionError as e:
                 raise AssertionError(f"seed {seed} F={b.F} {few} transposed={transposed}: {e}") from e
+
+
+def test_random_summed_groups_keep_the_invariants():
+    """Random groups of operations added into one block, both directions; a group that does
+    not fit on chip at any tile width is refused as a whole."""
+    from random_cases import random_summed_case
+    fitted = 0
+    for seed in range(60):
+        b, opts = random_summed_case(seed, with_dY=False)
+        try:
+            info, _ = _check_schedule(b, b.F, **opts)
+            if info.transposed_supported:
+                _check_schedule(b, b.F, transposed=True, **opts)
+            fitted += 1
+        except K.BspmmError as e:
+            assert e.code == K.ETOOBIG, f"seed {seed}: {e}"
+        except AssertionError as e:
+            raise AssertionError(f"seed {seed} F={b.F} batch={b.batch} opts={opts}: {e}") from e
+    assert fitted >= 30
