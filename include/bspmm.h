@@ -162,7 +162,8 @@ typedef struct bspmm_options {
                                   n_X-column layer input: whole workgroups, feature tiles in
                                   multiples of 16, room in LDS for an n_X x tile block of weights
                                   and at least 16 rows of X_i beside the operation (lds_bytes
-                                  then defaults to 64 KiB); needs F % 16 == 0 and n_X % 4 == 0
+                                  then defaults to 64 KiB, 160 KiB if that is too little); needs
+                                  F % 16 == 0 and n_X % 4 == 0
                                   (EINVAL), not combined with BSPMM_ACCUMULATE,
                                   BSPMM_SPLIT_HUB_ROWS or lds_pad (EINVAL); ETOOBIG when an
                                   operation does not fit at any tile width                      */

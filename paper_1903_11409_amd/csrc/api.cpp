@@ -340,21 +340,24 @@ Knobs knobs_for(const bspmm_options* o, bool ask_device)
 }
 
 // Host planning with the LDS budget the caller gave.  When the caller left it open and the
-// batch does not fit the default (operations summed into one block share a workgroup's LDS),
-// larger budgets are tried before the batch is refused: first asking for both directions,
-// then for the forward product alone.
+// batch does not fit the default (operations summed into one block share a workgroup's LDS; an
+// operation of the fused front shares it with its layer input), larger budgets are tried
+// before the batch is refused: first asking for both directions, then for the forward product
+// alone.
 template <class Batch, class PlanFn>
 int plan_with_budget(bspmm_plan& p, const Batch* b, int32_t F, const bspmm_options* options,
                      bool dry, PlanFn plan_fn)
 {
-    const bool open = !(options && (options->lds_bytes > 0 || options->front_features > 0));
+    const bool open = !(options && options->lds_bytes > 0);
+    const bool front = options && options->front_features > 0;   // its default is 64 KiB already
     Knobs kn = knobs_for(options, !dry);
-    kn.need_both = open;
+    kn.need_both = open && !front;
     int rc = plan_fn(p, b, F, kn);
     if (rc != BSPMM_ETOOBIG || !open) return rc;
     static const struct { int bytes; bool both; } attempts[] = {
         {kFrontLdsBytes, true}, {kMaxLdsBytes, true}, {0, false}, {kFrontLdsBytes, false}, {kMaxLdsBytes, false}};
     for (const auto& a : attempts) {
+        if (front && !(a.bytes == kMaxLdsBytes && !a.both)) continue;
         bspmm_options o = options ? *options : bspmm_options{};
         o.lds_bytes = a.bytes;
         kn = knobs_for(&o, !dry);

@@ -184,3 +184,30 @@ def test_empty_batch_launches_nothing(torch_cuda):
                  torch.zeros(16, device="cuda"), Y)
     torch.cuda.synchronize()
     assert torch.all(Y == SENTINEL)
+
+
+@pytest.mark.parametrize("block", range(4))
+def test_random_batches_and_knobs_through_the_front(torch_cuda, oracle, block):
+    """The seeded random shapes of the scheduler's property test as layer channels: random
+    input width, output width a multiple of 16, the knobs the front honours.  A batch with an
+    operation that does not fit on chip beside its layer input is refused and skipped."""
+    import dataclasses
+    from random_cases import random_case
+    ran = 0
+    for seed in range(300 + 10 * block, 300 + 10 * block + 10):
+        b, kw = random_case(seed, max_ops=60, max_nnz=60_000, with_dY=False)
+        rng = np.random.default_rng(seed)
+        F = [16, 32, 48, 64, 128, 256][int(rng.integers(6))]
+        n_x = [4, 8, 20, 32, 64, 100, 128][int(rng.integers(7))]
+        if b.n_b_rows == 0 or b.n_c_rows == 0:
+            continue
+        b = dataclasses.replace(b, F=F, B=np.zeros((b.n_b_rows, F), dtype=np.float32))
+        few = {k: v for k, v in kw.items() if k in ("lds_bytes", "target_workgroups", "wg_passes")}
+        if "max_tile" in kw:
+            few["max_tile"] = max(16, kw["max_tile"])
+        try:
+            _run_and_check(torch_cuda, oracle, b, n_x, seed=seed, what=f"seed {seed}", **few)
+            ran += 1
+        except K.BspmmError as e:
+            assert e.code == K.ETOOBIG, f"seed {seed}: {e}"
+    assert ran >= 4
