@@ -1056,9 +1056,11 @@ __global__ void __launch_bounds__(kThreads) bspmm_gcn_kernel(const LaunchParams 
     float* ws = bt + it.k * it.fw;                            // weight tile, nx x fw
     float* bias_s = ws + nx * it.fw;                          // bias tile, fw
     float* xs = bias_s + it.fw;                               // rows of X_i, R x nx
-    // X_i is taken R rows at a time (a 16 x 16 block needs 16 of its rows and all of their
-    // columns): as many as the rest of the LDS holds.  The host has made sure of 16.
-    const int R = min((it.k + 15) & ~15, ((P.lds_floats - (int)(xs - reinterpret_cast<float*>(sm))) / nx) & ~15);
+    // X_i is taken R rows at a time: all of them when the rest of the LDS holds them, else a
+    // multiple of 16 (a 16 x 16 block needs 16 rows of X_i and all of their columns).  The
+    // host has made sure of 16.
+    const int x_room = (P.lds_floats - (int)(xs - reinterpret_cast<float*>(sm))) / nx;
+    const int R = it.k <= x_room ? it.k : x_room & ~15;
     const int xvec = nx >> 2;
     const int swz = (xvec & (xvec - 1)) == 0 ? min(xvec, 16) - 1 : 0;
     const float* xg = P.in + it.in_row_off * P.ld_in;
@@ -1077,20 +1079,45 @@ __global__ void __launch_bounds__(kThreads) bspmm_gcn_kernel(const LaunchParams 
             const float* xrow = xs + arow * nx;
             const int xs_swz = arow & swz;
             const float* wcol = ws + 4 * g * it.fw + 16 * nb + col;
-            for (int k0 = 0; k0 < nx; k0 += 16) {
-                // every lane takes part in the matrix instruction: a lane group whose four k
-                // lie past the end (nx % 4 == 0: all four or none) reads the last valid ones
-                // instead and contributes zeros
-                const bool ok = k0 + 4 * g < nx;
-                const int kc = ok ? k0 : nx - 4 - 4 * g;
-                float4 a = *reinterpret_cast<const float4*>(xrow + ((((kc >> 2) + g) ^ xs_swz) << 2));
-                if (!ok) a = make_float4(0.f, 0.f, 0.f, 0.f);
-                const float* wk = wcol + kc * it.fw;
-                const float w0 = wk[0], w1 = wk[it.fw], w2 = wk[2 * it.fw], w3 = wk[3 * it.fw];
+            // Sixteen k per trip (four per lane group, one matrix instruction each).  The
+            // operands of the next trip are read from LDS before the instructions of this one
+            // are issued: read latency then hides behind the matrix pipeline instead of
+            // adding to every trip.
+            const int nfull = nx & ~15;
+            float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
+            float w0 = 0.f, w1 = 0.f, w2 = 0.f, w3 = 0.f;
+            if (nfull > 0) {
+                a = *reinterpret_cast<const float4*>(xrow + ((g ^ xs_swz) << 2));
+                w0 = wcol[0], w1 = wcol[it.fw], w2 = wcol[2 * it.fw], w3 = wcol[3 * it.fw];
+            }
+            for (int k0 = 0; k0 < nfull; k0 += 16) {
+                float4 an = a;
+                float v0 = w0, v1 = w1, v2 = w2, v3 = w3;
+                if (k0 + 16 < nfull) {
+                    an = *reinterpret_cast<const float4*>(xrow + (((((k0 + 16) >> 2) + g) ^ xs_swz) << 2));
+                    const float* wk = wcol + (k0 + 16) * it.fw;
+                    v0 = wk[0], v1 = wk[it.fw], v2 = wk[2 * it.fw], v3 = wk[3 * it.fw];
+                }
                 acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a.x, w0, acc, 0, 0, 0);
                 acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(a.y, w1, acc1, 0, 0, 0);
                 acc2 = __builtin_amdgcn_mfma_f32_16x16x4f32(a.z, w2, acc2, 0, 0, 0);
                 acc3 = __builtin_amdgcn_mfma_f32_16x16x4f32(a.w, w3, acc3, 0, 0, 0);
+                a = an;
+                w0 = v0, w1 = v1, w2 = v2, w3 = v3;
+            }
+            if (nfull < nx) {
+                // the last, partial trip: every lane takes part in the matrix instruction; a
+                // lane group whose four k lie past the end (nx % 4 == 0: all four or none)
+                // reads the last valid ones instead and contributes zeros
+                const bool ok = nfull + 4 * g < nx;
+                const int kc = ok ? nfull : nx - 4 - 4 * g;
+                float4 at = *reinterpret_cast<const float4*>(xrow + ((((kc >> 2) + g) ^ xs_swz) << 2));
+                if (!ok) at = make_float4(0.f, 0.f, 0.f, 0.f);
+                const float* wk = wcol + kc * it.fw;
+                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(at.x, wk[0], acc, 0, 0, 0);
+                acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(at.y, wk[it.fw], acc1, 0, 0, 0);
+                acc2 = __builtin_amdgcn_mfma_f32_16x16x4f32(at.z, wk[2 * it.fw], acc2, 0, 0, 0);
+                acc3 = __builtin_amdgcn_mfma_f32_16x16x4f32(at.w, wk[3 * it.fw], acc3, 0, 0, 0);
             }
             acc = (acc + acc1) + (acc2 + acc3);
 #pragma unroll

@@ -611,7 +611,7 @@ Schedule make_schedule(const DirOps& ops, int F, const Knobs& kn_in)
         for (const WorkItem& w : s.items) {
             if (w.nrows <= 0) continue;
             const StagedLayout L = staged_layout(w.m, w.k, w.nnz, w.fw, 0, false);
-            most = std::max<int64_t>(most, (int64_t)L.total + (int64_t)round_up(w.k, 16) * kn.front +
+            most = std::max<int64_t>(most, (int64_t)L.total + (int64_t)w.k * kn.front +
                                                (int64_t)kn.front * w.fw + w.fw);
         }
         s.front_lds_words = (int)std::min<int64_t>(kn.lds_words, round_up((int)most, 64));
