@@ -144,7 +144,7 @@ typedef struct bspmm_options {
     uint32_t flags;            /* BSPMM_DRY_RUN | BSPMM_BUILD_TRANSPOSE | BSPMM_SPLIT_HUB_ROWS */
     int32_t  force_bin;        /* 0 = automatic; 1+b forces bin b for every op that fits it    */
     int32_t  lds_bytes;        /* LDS per workgroup; <= 160 KiB (all of a CU's).  0 = 24 KiB,
-                                  and 64 KiB, then 160 KiB, are tried before a batch whose
+                                  and 80 KiB, then 160 KiB, are tried before a batch whose
                                   summed operations need more is refused with ETOOBIG          */
     int32_t  min_tile;         /* narrowest feature tile in floats, 0 = default (32)           */
     int32_t  max_tile;         /* widest feature tile in floats, 0 = default (256), <= 256     */
@@ -162,7 +162,7 @@ typedef struct bspmm_options {
                                   n_X-column layer input: whole workgroups, feature tiles in
                                   multiples of 16, room in LDS for an n_X x tile block of weights
                                   and at least 16 rows of X_i beside the operation (lds_bytes
-                                  then defaults to 64 KiB, 160 KiB if that is too little); needs
+                                  then defaults to 80 KiB, 160 KiB if that is too little); needs
                                   F % 16 == 0 and n_X % 4 == 0
                                   (EINVAL), not combined with BSPMM_ACCUMULATE,
                                   BSPMM_SPLIT_HUB_ROWS or lds_pad (EINVAL); ETOOBIG when an

@@ -4,8 +4,8 @@
 #include <algorithm>
 #include <cstring>
 #include <new>
-#include <memory>
 #include <set>
+#include <memory>
 #include <utility>
 #include <vector>
 
@@ -131,6 +131,14 @@ int check_batch(const bspmm_batch* b, int32_t F, bool need_device)
 // 0 = pairwise disjoint, 1 = some are identical but none overlaps otherwise, 2 = real overlap.
 int overlap_kind(const int64_t* off, const int32_t* len, int n)
 {
+    bool in_order = true;   // the usual case: blocks back to back in operation order
+    int64_t end = 0;
+    for (int i = 0; i < n && in_order; ++i) {
+        if (len[i] <= 0) continue;
+        in_order = off[i] >= end;
+        end = off[i] + len[i];
+    }
+    if (in_order) return 0;
     std::vector<std::pair<int64_t, int64_t>> v;
     v.reserve(n);
     for (int i = 0; i < n; ++i)
@@ -160,6 +168,10 @@ int plan_host(bspmm_plan& p, const bspmm_batch* b, int32_t F, const Knobs& kn)
     int64_t nz_pack = 0;
     int64_t scratch_words = 0;
     int build_lds_words = 0;
+    for (DirOps* o : {&f, &t}) {
+        o->m.reserve(n), o->k.reserve(n), o->nnz.reserve(n), o->rpt_off.reserve(n);
+        o->nz_off.reserve(n), o->in_off.reserve(n), o->out_off.reserve(n);
+    }
     for (int i = 0; i < n; ++i) {
         if (kn.symmetric && b->rows[i] != b->cols[i]) return BSPMM_EINVAL;
         f.m.push_back(b->rows[i]);
@@ -242,21 +254,31 @@ int plan_host(bspmm_plan& p, const bspmm_batch* b, int32_t F, const Knobs& kn)
     }
 
     // compulsory traffic: CSR once, every distinct dense input block once, every output once
-    std::set<std::pair<int64_t, int32_t>> blocks_f, blocks_t;
     int64_t csr_f = 0, csr_t = 0, out_f = 0, out_t = 0, in_f = 0, in_t = 0, nnz = 0;
+    // a dense block counts once as an input and once as an output, however many operations
+    // read it or are summed into it
+    auto distinct_rows = [n](const int64_t* off, const int32_t* len) {
+        bool increasing = true;        // the usual case: blocks back to back in operation order
+        for (int i = 1; i < n && increasing; ++i) increasing = off[i] >= off[i - 1] + len[i - 1];
+        int64_t rows = 0;
+        if (increasing) {
+            for (int i = 0; i < n; ++i) rows += len[i];
+            return rows;
+        }
+        std::vector<std::pair<int64_t, int32_t>> v(n);
+        for (int i = 0; i < n; ++i) v[i] = {off[i], len[i]};
+        std::sort(v.begin(), v.end());
+        for (int i = 0; i < n; ++i)
+            if (i == 0 || v[i] != v[i - 1]) rows += v[i].second;
+        return rows;
+    };
+    const int64_t b_rows = distinct_rows(b->b_row_off, b->cols);
+    const int64_t c_rows = distinct_rows(b->c_row_off, b->rows);
+    in_f = out_t = 4 * b_rows * F;
+    in_t = out_f = 4 * c_rows * F;
     for (int i = 0; i < n; ++i) {
         csr_f += 4 * ((int64_t)b->rows[i] + 1) + 8 * (int64_t)b->nnz[i];
         csr_t += 4 * ((int64_t)b->cols[i] + 1) + 8 * (int64_t)b->nnz[i];
-        // a dense block counts once as an input and once as an output, however many
-        // operations read it or are summed into it
-        if (blocks_f.emplace(b->b_row_off[i], b->cols[i]).second) {
-            in_f += 4 * (int64_t)b->cols[i] * F;
-            out_t += 4 * (int64_t)b->cols[i] * F;
-        }
-        if (blocks_t.emplace(b->c_row_off[i], b->rows[i]).second) {
-            in_t += 4 * (int64_t)b->rows[i] * F;
-            out_f += 4 * (int64_t)b->rows[i] * F;
-        }
         nnz += b->nnz[i];
         if (b->rows[i] > 0 && b->cols[i] > 0) p.reads_dense = true;
     }
@@ -349,13 +371,13 @@ int plan_with_budget(bspmm_plan& p, const Batch* b, int32_t F, const bspmm_optio
                      bool dry, PlanFn plan_fn)
 {
     const bool open = !(options && options->lds_bytes > 0);
-    const bool front = options && options->front_features > 0;   // its default is 64 KiB already
+    const bool front = options && options->front_features > 0;   // its default is 80 KiB already
     Knobs kn = knobs_for(options, !dry);
     kn.need_both = open && !front;
     int rc = plan_fn(p, b, F, kn);
     if (rc != BSPMM_ETOOBIG || !open) return rc;
     static const struct { int bytes; bool both; } attempts[] = {
-        {kFrontLdsBytes, true}, {kMaxLdsBytes, true}, {0, false}, {kFrontLdsBytes, false}, {kMaxLdsBytes, false}};
+        {kHalfLdsBytes, true}, {kMaxLdsBytes, true}, {0, false}, {kHalfLdsBytes, false}, {kMaxLdsBytes, false}};
     for (const auto& a : attempts) {
         if (front && !(a.bytes == kMaxLdsBytes && !a.both)) continue;
         bspmm_options o = options ? *options : bspmm_options{};
@@ -486,6 +508,10 @@ int plan_host_coo_direct(bspmm_plan& p, const bspmm_coo_batch* b, int32_t F, con
     DirOps& t = p.dir[1];
     int64_t nnz = 0, in_f = 0, out_f = 0;
     std::set<std::pair<int64_t, int32_t>> blocks_b;
+    for (DirOps* o : {&f, &t}) {
+        o->m.reserve(n), o->k.reserve(n), o->nnz.reserve(n), o->rpt_off.reserve(n);
+        o->nz_off.reserve(n), o->in_off.reserve(n), o->out_off.reserve(n);
+    }
     for (int i = 0; i < n; ++i) {
         if (kn.symmetric && b->rows[i] != b->cols[i]) return BSPMM_EINVAL;
         f.m.push_back(b->rows[i]);

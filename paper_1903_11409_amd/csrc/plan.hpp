@@ -17,7 +17,7 @@ constexpr int kRanges = 5;         // launch ranges: 256 lanes, fused 256, then 
 constexpr int kMaxMembers = 8;     // operations one fused task may add up
 constexpr int kMaxLdsBytes = 160 * 1024;    // LDS one workgroup can have on gfx950 (the whole CU's)
 constexpr int kBuildLdsBytes = 64 * 1024;   // most the transpose / conversion kernels take
-constexpr int kFrontLdsBytes = 80 * 1024;   // default budget of the fused front: two workgroups per CU
+constexpr int kHalfLdsBytes = 80 * 1024;    // half a CU's LDS (two workgroups per CU): default of the fused front
 
 // Slot size (lanes) of launch range r, and its log2.
 BSPMM_HD constexpr int range_log2_slot(int r) { return r <= 1 ? 8 : (r == 2 ? 6 : (r == 3 ? 5 : 4)); }

@@ -251,12 +251,43 @@ bool draft_fused(const DirOps& o, const std::vector<int>& members, int fused_ind
 }
 
 // Operations grouped by the output block they name: a group of more than one is summed.
-// Groups are listed in the order of their first operation, members in operation order.
-std::vector<std::vector<int>> output_groups(const DirOps& o)
+// Groups are listed in the order of their first operation, members in operation order; group g
+// is member[start[g]] .. member[start[g + 1] - 1].
+struct Groups {
+    std::vector<int> start, member;
+    int size() const { return (int)start.size() - 1; }
+    int count(int g) const { return start[g + 1] - start[g]; }
+    const int* begin(int g) const { return member.data() + start[g]; }
+    std::vector<int> members(int g) const { return std::vector<int>(begin(g), begin(g) + count(g)); }
+};
+
+Groups output_groups(const DirOps& o)
 {
+    Groups out;
+    const int n = o.size();
+    out.member.reserve(n);
+    out.start.reserve(n + 1);
+    // the usual case: every operation has an output block of its own, later operations at
+    // higher rows - nothing to sort
+    bool separate = true;
+    int64_t end = -1;
+    for (int i = 0; i < n && separate; ++i) {
+        if (o.m[i] <= 0) continue;
+        separate = o.out_off[i] >= end;
+        end = o.out_off[i] + o.m[i];
+    }
+    if (separate) {
+        for (int i = 0; i < n; ++i)
+            if (o.m[i] > 0) {
+                out.start.push_back((int)out.member.size());
+                out.member.push_back(i);
+            }
+        out.start.push_back((int)out.member.size());
+        return out;
+    }
     std::vector<int> idx;
-    idx.reserve(o.size());
-    for (int i = 0; i < o.size(); ++i)
+    idx.reserve(n);
+    for (int i = 0; i < n; ++i)
         if (o.m[i] > 0) idx.push_back(i);
     std::vector<int> sorted = idx;
     std::sort(sorted.begin(), sorted.end(), [&](int a, int b) {
@@ -264,27 +295,29 @@ std::vector<std::vector<int>> output_groups(const DirOps& o)
         if (o.m[a] != o.m[b]) return o.m[a] < o.m[b];
         return a < b;
     });
-    // leader[i] = first operation (lowest index) naming the same block as i
-    std::vector<int> leader(o.size(), -1);
+    // leader[i] = first operation (lowest index) naming the same block as i; size[l] = members
+    std::vector<int> leader(n, -1), size(n, 0);
     for (size_t a = 0; a < sorted.size();) {
         size_t b = a;
         while (b < sorted.size() && o.out_off[sorted[b]] == o.out_off[sorted[a]] &&
                o.m[sorted[b]] == o.m[sorted[a]])
             leader[sorted[b++]] = sorted[a];
+        size[sorted[a]] = (int)(b - a);
         a = b;
     }
-    std::vector<int> group_of(o.size(), -1);
-    std::vector<std::vector<int>> groups;
-    groups.reserve(idx.size());
-    for (int i : idx) {
-        const int l = leader[i];
-        if (group_of[l] < 0) {
-            group_of[l] = (int)groups.size();
-            groups.emplace_back();
+    // groups in the order of their leaders; a group's slots are filled in operation order
+    std::vector<int> at(n, -1);
+    int total = 0;
+    for (int i : idx)
+        if (leader[i] == i) {
+            out.start.push_back(total);
+            at[i] = total;
+            total += size[i];
         }
-        groups[group_of[l]].push_back(i);
-    }
-    return groups;
+    out.start.push_back(total);
+    out.member.resize(total);
+    for (int i : idx) out.member[at[leader[i]]++] = i;
+    return out;
 }
 
 // Index of the dense-input block of every operation (operations reading the same first row
@@ -306,14 +339,14 @@ std::vector<int> input_blocks(const DirOps& o)
 
 void draft_all(const DirOps& o, int F, int vec, const std::vector<int>& cand, size_t first,
                const Knobs& kn, int cap, bool allow_small,
-               const std::vector<std::vector<int>>& outs, bool* fits, Sink& sink)
+               const Groups& outs, bool* fits, Sink& sink)
 {
     int nfused = 0;
-    for (const std::vector<int>& g : outs) {
-        if (g.size() == 1) {
-            const int i = g[0];
+    for (int g = 0; g < outs.size(); ++g) {
+        if (outs.count(g) == 1) {
+            const int i = *outs.begin(g);
             draft_op(o, i, F, vec, choose(o, i, F, vec, cand, first, kn, allow_small), kn, cap, sink);
-        } else if (!draft_fused(o, g, nfused++, F, vec, cand, first, kn, cap, sink)) {
+        } else if (!draft_fused(o, outs.members(g), nfused++, F, vec, cand, first, kn, cap, sink)) {
             *fits = false;
         }
     }
@@ -372,9 +405,9 @@ Knobs resolve_knobs(const bspmm_options* o)
     k.symmetric = (o->flags & BSPMM_SYMMETRIC) != 0;
     if (o->front_features > 0) {   // the matrix-core blocks of the fused front are 16 columns wide
         k.front = o->front_features;
-        // an item also holds X_i and a weight tile: take the whole 64 KiB unless told otherwise
+        // an item also holds X_i and a weight tile: take half the CU's LDS unless told otherwise
         // (the launch asks only for what its largest item needs)
-        if (o->lds_bytes <= 0) k.lds_words = kFrontLdsBytes / 4;
+        if (o->lds_bytes <= 0) k.lds_words = kHalfLdsBytes / 4;
         k.max_tile = std::max(16, k.max_tile / 16 * 16);
         k.min_tile = o->min_tile > 0 ? std::min(std::max(16, (k.min_tile + 15) / 16 * 16), k.max_tile) : 16;
     }
@@ -398,9 +431,9 @@ Schedule make_schedule(const DirOps& ops, int F, const Knobs& kn_in)
     // workgroup staging it.  A forced bin overrides this.
     const int fixed_cap = kn.wg_passes > 0 ? kn.wg_passes : 0;
     bool allow_small = kn.force_bin >= 0 && kn.front == 0;
-    const std::vector<std::vector<int>> outs = output_groups(ops);
+    const Groups outs = output_groups(ops);
     size_t most_members = 1;
-    for (const auto& g : outs) most_members = std::max(most_members, g.size());
+    for (int g = 0; g < outs.size(); ++g) most_members = std::max<size_t>(most_members, outs.count(g));
     if (most_members > (size_t)kMaxMembers) {
         s.error = BSPMM_ETOOBIG;
         return s;
@@ -469,32 +502,77 @@ Schedule make_schedule(const DirOps& ops, int F, const Knobs& kn_in)
     for (Draft& x : d)
         if (x.fused < 0 && x.staged && gsize[x.group] == 1) x.staged |= 2;   // tile read once
 
-    // largest group first, members of a group together, larger items first inside a group;
-    // the keys are copied next to the indices so that the sort touches one array only
-    struct SortKey {
-        int64_t gcost, cost;
-        int group, idx;
-    };
-    std::vector<SortKey> keys[kRanges];
+    // Largest group first, members of a group together, larger items first inside a group,
+    // equal keys in draft order.  The order only steers the greedy placement below, so costs
+    // are compared in 15 and 16 bits (scaled to the largest): the three keys then pack into one
+    // 55-bit word and a stable radix sort (11-bit digits: the counters stay in L1; digits that
+    // are equal in every key are skipped) replaces the comparison sort, which was the most
+    // expensive step of planning a large batch.
+    std::vector<std::vector<int>> by_range(kRanges);
     {
-        int n_in[kRanges] = {0, 0, 0, 0, 0};
+        int64_t top = 1;
+        for (int64_t c : gcost) top = std::max(top, c);
+        int shift = 0;
+        while ((top >> shift) > 0x7fff) ++shift;
+        size_t n_in[kRanges] = {0, 0, 0, 0, 0};
         for (const Draft& x : d) n_in[draft_range(x)]++;
-        for (int r = 0; r < kRanges; ++r) keys[r].reserve(n_in[r]);
+        std::vector<uint64_t> key[kRanges], key_tmp;
+        std::vector<int> idx_tmp;
+        for (int r = 0; r < kRanges; ++r) {
+            key[r].reserve(n_in[r]);
+            by_range[r].reserve(n_in[r]);
+        }
+        const bool packable = ngroups < (1 << 24);
         for (int idx = 0; idx < (int)d.size(); ++idx) {
             const Draft& x = d[idx];
-            keys[draft_range(x)].push_back({gcost[x.group], x.cost, x.group, idx});
+            const int r = draft_range(x);
+            const uint64_t g15 = 0x7fff - (uint64_t)(gcost[x.group] >> shift);
+            const uint64_t c16 = 0xffff - (uint64_t)(std::min(x.cost, gcost[x.group]) >> shift << 1);
+            key[r].push_back(g15 << 40 | (uint64_t)x.group << 16 | c16);
+            by_range[r].push_back(idx);
         }
-    }
-    std::vector<std::vector<int>> by_range(kRanges);
-    for (int r = 0; r < kRanges; ++r) {
-        std::sort(keys[r].begin(), keys[r].end(), [](const SortKey& a, const SortKey& b) {
-            if (a.gcost != b.gcost) return a.gcost > b.gcost;
-            if (a.group != b.group) return a.group < b.group;
-            if (a.cost != b.cost) return a.cost > b.cost;
-            return a.idx < b.idx;
-        });
-        by_range[r].reserve(keys[r].size());
-        for (const SortKey& k : keys[r]) by_range[r].push_back(k.idx);
+        uint32_t count[1 << 11];
+        for (int r = 0; r < kRanges; ++r) {
+            std::vector<uint64_t>& k = key[r];
+            std::vector<int>& v = by_range[r];
+            const size_t n = k.size();
+            if (n < 2) continue;
+            if (!packable || n < 128) {   // few items (or more groups than the key holds): compare
+                std::vector<int> order(n);
+                std::iota(order.begin(), order.end(), 0);
+                std::stable_sort(order.begin(), order.end(), [&](int a, int b) {
+                    const Draft &x = d[v[a]], &y = d[v[b]];
+                    if ((k[a] >> 40) != (k[b] >> 40)) return k[a] < k[b];
+                    if (x.group != y.group) return x.group < y.group;
+                    return (k[a] & 0xffff) < (k[b] & 0xffff);
+                });
+                std::vector<int> sorted(n);
+                for (size_t t = 0; t < n; ++t) sorted[t] = v[order[t]];
+                v.swap(sorted);
+                continue;
+            }
+            key_tmp.resize(n);
+            idx_tmp.resize(n);
+            for (int pass = 0; pass < 5; ++pass) {
+                const int sh = 11 * pass;
+                std::fill(count, count + (1 << 11), 0u);
+                for (size_t t = 0; t < n; ++t) ++count[(k[t] >> sh) & 0x7ff];
+                if (count[(k[0] >> sh) & 0x7ff] == n) continue;   // one digit everywhere
+                uint32_t run = 0;
+                for (uint32_t& c : count) {
+                    const uint32_t here = c;
+                    c = run;
+                    run += here;
+                }
+                for (size_t t = 0; t < n; ++t) {
+                    const uint32_t at = count[(k[t] >> sh) & 0x7ff]++;
+                    key_tmp[at] = k[t];
+                    idx_tmp[at] = v[t];
+                }
+                k.swap(key_tmp);
+                v.swap(idx_tmp);
+            }
+        }
     }
 
     // range 0: one item per workgroup; groups dealt to the XCD with the least cost so far,
@@ -563,8 +641,8 @@ Schedule make_schedule(const DirOps& ops, int F, const Knobs& kn_in)
     int wg = grid0;
     {
         std::vector<std::vector<int>> fused_sets;
-        for (const auto& g : outs)
-            if (g.size() > 1) fused_sets.push_back(g);
+        for (int g = 0; g < outs.size(); ++g)
+            if (outs.count(g) > 1) fused_sets.push_back(outs.members(g));
         s.fused_stride = (int)most_members;
         s.item_base[1] = (int)s.items.size();
         for (int idx : by_range[1]) {
