@@ -485,6 +485,10 @@ Schedule make_schedule(const DirOps& ops, int F, const Knobs& kn_in)
     keep.block_of_op = &block_of_op;
     keep.tile_unit = std::max(4, std::min(cand.back(), F));
     keep.tiles_per_block = (F + keep.tile_unit - 1) / keep.tile_unit;
+    if (kn.front > 0) {   // every feature tile of an operation reads the whole of X_i: one group
+        keep.tile_unit = std::max(4, F);
+        keep.tiles_per_block = 1;
+    }
     d.reserve((size_t)wgs * 4 + 16);
     draft_all(ops, F, vec, cand, chosen, kn, cap, allow_small, outs, &fits, keep);
 
