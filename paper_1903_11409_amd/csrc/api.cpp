@@ -354,8 +354,7 @@ Knobs knobs_for(const bspmm_options* o, bool ask_device)
         r = f.resident;
         rs = f.resident_slices;
     }
-    // (the fused front stages more per workgroup: two per CU measured best)
-    if (!(o && o->target_workgroups > 0)) kn.target_wgs = (kn.front > 0 ? 2 : 4) * kn.compute_units;
+    if (!(o && o->target_workgroups > 0)) kn.target_wgs = workgroups_per_cu(kn.front) * kn.compute_units;
     kn.capacity_wgs = r > 0 ? r : 6 * kn.compute_units;
     kn.capacity_wgs_slices = rs > 0 ? rs : 4 * kn.compute_units;
     return kn;

@@ -381,6 +381,14 @@ WorkItem empty_item()
 
 }  // namespace
 
+// Workgroups per CU a launch aims for.  Plain products: four (their time is latency).  The
+// fused front stages X_i again for every feature tile, so it wants fewer, wider tiles the
+// wider the layer input is: two per CU measured best up to 64 input columns, one from 128 on.
+int workgroups_per_cu(int front)
+{
+    return front <= 0 ? 4 : (front < 128 ? 2 : 1);
+}
+
 Knobs resolve_knobs(const bspmm_options* o)
 {
     Knobs k;
@@ -392,7 +400,7 @@ Knobs resolve_knobs(const bspmm_options* o)
     if (o->min_tile > 0) k.min_tile = std::min(std::max(o->min_tile, 4), k.max_tile);
     if (o->compute_units > 0) k.compute_units = o->compute_units;
     k.target_wgs = o->target_workgroups > 0 ? o->target_workgroups
-                                            : (o->front_features > 0 ? 2 : 4) * k.compute_units;
+                                            : workgroups_per_cu(o->front_features) * k.compute_units;
     if (o->lds_pad > 0) k.pad = std::min(o->lds_pad, 64) / 4 * 4;
     if (o->lds_pad < 0) k.pad = 0;
     if (o->max_passes > 0) k.max_passes = o->max_passes;

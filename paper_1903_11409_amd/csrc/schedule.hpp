@@ -66,6 +66,7 @@ struct CooSchedule {
     int error = 0;
 };
 
+int workgroups_per_cu(int front_features);
 Knobs resolve_knobs(const bspmm_options* o);
 
 // Items of the direct COO kernel for `ops` (rpt_off unused, nz_off = the caller's entry offsets).
