@@ -506,10 +506,10 @@ __device__ __forceinline__ void run_generic(const LaunchParams& P, const WorkIte
 // global memory into LDS (no staging registers: all of it is in flight at once); members that
 // read the same dense tile share one copy.
 // ---------------------------------------------------------------------------------------
-__device__ __forceinline__ void lds_copy_words(const void* src, int* dst_lds, int words, int tid)
+// `words` 32-bit words global -> LDS by one wavefront (lane wl of 64), 256 bytes per instruction.
+__device__ __forceinline__ void wave_copy_words(const void* src, int* dst_lds, int words, int wl)
 {
-    const int wl = tid & 63;
-    for (int e0 = (tid >> 6) << 6; e0 < words; e0 += kThreads) {
+    for (int e0 = 0; e0 < words; e0 += 64) {
         const int e = e0 + wl;
         if (e < words)
             __builtin_amdgcn_global_load_lds(
@@ -525,8 +525,29 @@ __device__ __forceinline__ void run_fused(const LaunchParams& P, int* sm, int fi
     using V = Vec<VEC>;
     using VT = typename V::type;
     const int tid = threadIdx.x;
-    const WorkItem it0 = P.items[first_item];          // uniform: scalar loads
+    // ---- member descriptors: lane j of every wavefront fetches member j's item, so all of
+    // them arrive in one round trip; the uniform code below picks a member's fields out of
+    // the lanes with v_readlane (no scalar load and no LDS per member).  The task's own
+    // fields are member 0's.
+    const int wl = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const WorkItem mine = P.items[first_item + min(wl, P.fused_stride - 1)];
+    auto lane_i32 = [](int v, int j) { return __builtin_amdgcn_readlane(v, j); };
+    auto lane_i64 = [](int64_t v, int j) {
+        const unsigned lo = __builtin_amdgcn_readlane((int)(v & 0xffffffff), j);
+        const unsigned hi = __builtin_amdgcn_readlane((int)(v >> 32), j);
+        return (int64_t)(((uint64_t)hi << 32) | lo);
+    };
+    WorkItem it0;
+    it0.nrows = lane_i32(mine.nrows, 0);
     if (it0.nrows <= 0) return;
+    it0.staged = lane_i32(mine.staged, 0);
+    it0.m = lane_i32(mine.m, 0);
+    it0.k = lane_i32(mine.k, 0);
+    it0.fw = lane_i32(mine.fw, 0);
+    it0.f0 = lane_i32(mine.f0, 0);
+    it0.row0 = lane_i32(mine.row0, 0);
+    it0.out_row_off = lane_i64(mine.out_row_off, 0);
 #ifdef BSPMM_TRACE
     if (P.trace && tid == 0) P.trace[(size_t)task * 8] = wall_clock64();
 #endif
@@ -538,33 +559,26 @@ __device__ __forceinline__ void run_fused(const LaunchParams& P, int* sm, int fi
     const Split<kThreads, VEC> sp(fw, tid);
     const bool direct = VEC == 4 && (sp.nvec & (sp.nvec - 1)) == 0;
 
-    // ---- member descriptors: lane j of every wavefront fetches member j's item, so all of
-    // them arrive in one round trip; the uniform loops below pick a member's fields out of
-    // the lanes with v_readlane (no scalar load and no LDS per member).
-    const int wl = tid & 63;
-    const WorkItem mine = P.items[first_item + min(wl, P.fused_stride - 1)];
-    auto lane_i32 = [](int v, int j) { return __builtin_amdgcn_readlane(v, j); };
-    auto lane_i64 = [](int64_t v, int j) {
-        const unsigned lo = __builtin_amdgcn_readlane((int)(v & 0xffffffff), j);
-        const unsigned hi = __builtin_amdgcn_readlane((int)(v >> 32), j);
-        return (int64_t)(((uint64_t)hi << 32) | lo);
-    };
-
-    // ---- stage every member: offsets are uniform, computed by everybody, tabled by lane 0
+    // ---- stage the CSR arrays: member j is copied by wavefront j % 4 alone (the arrays of a
+    // molecule-sized member are one instruction each; four wavefronts walking every member
+    // would spend their time on address arithmetic).  Offsets are uniform; lane 0 of the
+    // copying wavefront tables them.
     int off = L.cv_off;
     int nnz_sum = 0;
     for (int j = 0; j < members; ++j) {
         const int nnz = lane_i32(mine.nnz, j);
-        const int64_t nz_off = lane_i64(mine.nz_off, j);
         const int nz4 = round_up(nnz, 4);
-        if (tid == 0) {
-            sm[4 * j + 0] = off;
-            sm[4 * j + 1] = off + nz4;
-            sm[4 * j + 3] = nnz;
+        if ((j & (kThreads / 64 - 1)) == wave) {
+            const int64_t nz_off = lane_i64(mine.nz_off, j);
+            if (wl == 0) {
+                sm[4 * j + 0] = off;
+                sm[4 * j + 1] = off + nz4;
+                sm[4 * j + 3] = nnz;
+            }
+            wave_copy_words(P.rpt + lane_i64(mine.rpt_off, j), sm + L.rpt_off + j * L.rs, m + 1, wl);
+            wave_copy_words(P.colids + nz_off, sm + off, nnz, wl);
+            wave_copy_words(P.values + nz_off, sm + off + nz4, nnz, wl);
         }
-        lds_copy_words(P.rpt + lane_i64(mine.rpt_off, j), sm + L.rpt_off + j * L.rs, m + 1, tid);
-        lds_copy_words(P.colids + nz_off, sm + off, nnz, tid);
-        lds_copy_words(P.values + nz_off, sm + off + nz4, nnz, tid);
         off += 2 * nz4;
         nnz_sum += nnz;
     }
