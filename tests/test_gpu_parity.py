@@ -498,3 +498,15 @@ def test_summed_groups_take_a_larger_lds_budget_when_they_need_it(torch_cuda, or
         with pytest.raises(K.BspmmError) as e:      # a budget the caller fixed is kept
             K.Plan(b, options=K.make_options(flags=K.ACCUMULATE, lds_bytes=24576))
         assert e.value.code == K.ETOOBIG
+
+
+def test_large_batch_of_small_graphs(torch_cuda, oracle):
+    """16384 molecule graphs in one launch (many times what the chip holds at once: the
+    scheduler packs several small items into a workgroup), forward and transposed."""
+    b = W.config2_molecule(seed=77, graphs=16384, F=64)
+    b = dataclasses.replace(b, dY=np.random.default_rng(2).standard_normal(
+        (b.n_c_rows, b.F)).astype(np.float32))
+    plan, _ = _check_forward(torch_cuda, oracle, b, what="16384 graphs")
+    info = plan.info()
+    assert info.items[0] >= 16384 and info.workgroups[0] < info.items[0]
+    _check_transposed(torch_cuda, oracle, b, plan=plan, what="16384 graphs")
