@@ -494,7 +494,9 @@ def main():
                 ("cfg4_F256", lambda: W.config4_wide(F=256), False),
                 ("cfg4_F1024", lambda: W.config4_wide(F=1024), False),
                 ("cfg5_forward_F256", lambda: W.config5_skewed(), False),
-                ("cfg5_transposed_F256", lambda: W.config5_skewed(), True)]:
+                ("cfg5_transposed_F256", lambda: W.config5_skewed(), True),
+                # throughput regime: the headline's molecule graphs, 128 times as many
+                ("cfg2_molecule_16384_graphs_F128", lambda: W.config2_molecule(graphs=16384), False)]:
             bb = mk()
             r = Runner(torch, K, bb, transposed=tr)
             steps = max(200, min(args.steps, 2000))
