@@ -136,6 +136,7 @@ struct Sink {
     std::vector<Draft>* out = nullptr;     // null: count only
     int per_range[kRanges] = {0, 0, 0, 0, 0};
     int generic = 0;                       // items that read their operands from global memory
+    int64_t tile_words = 0;                // counting only: dense-tile words the staged items copy
     const std::vector<int>* block_of_op = nullptr;   // dense-input block index of every operation
     int tiles_per_block = 1;               // group id = block * tiles_per_block + f0 / tile_unit
     int tile_unit = 4;
@@ -177,9 +178,12 @@ void draft_op(const DirOps& o, int i, int F, int vec, const Choice& ch, const Kn
             return (o.m[i] + kn.generic_rows - 1) / kn.generic_rows;
         };
         const int full = F / tile, tail = F % tile;
-        const int n = (full ? full * per_tile(tile) : 0) + (tail ? per_tile(tail) : 0);
+        const int n_full = full ? per_tile(tile) : 0, n_tail = tail ? per_tile(tail) : 0;
+        const int n = full * n_full + n_tail;
         sink.per_range[bin_range(ch.bin)] += n;
         sink.generic += ch.bin == BSPMM_BIN_GENERIC ? n : 0;
+        if (ch.bin != BSPMM_BIN_GENERIC)   // every piece of a cut item copies the whole tile
+            sink.tile_words += (int64_t)o.k[i] * ((int64_t)full * n_full * tile + (int64_t)n_tail * tail);
         return;
     }
     for (int f0 = 0; f0 < F; f0 += tile) {
@@ -447,9 +451,11 @@ Schedule make_schedule(const DirOps& ops, int F, const Knobs& kn_in)
         return s;
     }
     bool fits = true;
+    int64_t counted_tile_words = 0;
     auto workgroups_of = [&](size_t first, int cap, bool small) {
         Sink counter;
         draft_all(ops, F, vec, cand, first, kn, cap, small, outs, &fits, counter);
+        counted_tile_words = counter.tile_words;
         return counter.workgroups();
     };
     int wgs = 0;
@@ -467,11 +473,34 @@ Schedule make_schedule(const DirOps& ops, int F, const Knobs& kn_in)
     s.tile = cand[chosen];
     // still too few workgroups at the narrowest tile: the batch is small, its time is set by
     // the slowest workgroup, so cut multi-pass workgroup items into row ranges
+    // Likewise while the launch still fits the chip at once: the workgroups with several passes
+    // are its critical path, and cutting them pays as long as no workgroup has to wait for a
+    // free slot and the pieces, each of which copies the whole dense tile again, do not add
+    // more than 60 % to the tile traffic (measured: 256 molecule graphs 4.9 -> 4.3 us, 512
+    // graphs 5.9 -> 4.8 us; cut beyond what the chip holds, 384 graphs go from 4.9 to 5.9 us;
+    // wide tiles of 100-row graphs cut to four rows each, 8.2 -> 9.2 us).
     int cap = fixed_cap;
-    if (kn.wg_passes == 0 && wgs < kn.target_wgs && kn.front == 0) {
-        for (cap = 4; cap >= 1; cap /= 2) {
-            wgs = workgroups_of(chosen, cap, allow_small);
-            if (wgs >= kn.target_wgs || cap == 1) break;
+    if (kn.wg_passes == 0 && kn.front == 0) {
+        const int uncut = workgroups_of(chosen, fixed_cap, allow_small);
+        const int64_t uncut_words = counted_tile_words;
+        bool done = false;
+        // (a launch that moves more than about 28 MB is bound by bandwidth, not by its slowest
+        // workgroup: there the extra copies only cost)
+        const bool latency_bound = uncut_words <= 3500000;
+        for (int c = 1; c <= 4 && uncut <= kn.capacity_wgs && latency_bound; c *= 2) {
+            const int w = workgroups_of(chosen, c, allow_small);
+            if (w <= kn.capacity_wgs && 5 * (counted_tile_words - uncut_words) <= 3 * uncut_words) {
+                cap = c;
+                wgs = w;
+                done = true;
+                break;
+            }
+        }
+        if (!done && uncut < kn.target_wgs) {
+            for (cap = 4; cap >= 1; cap /= 2) {
+                wgs = workgroups_of(chosen, cap, allow_small);
+                if (wgs >= kn.target_wgs || cap == 1) break;
+            }
         }
     }
     if (!fits) {   // a set of summed operations does not fit LDS together even at 4 columns
