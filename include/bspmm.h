@@ -28,11 +28,13 @@
  * afterwards.  Pointers marked DEVICE must stay valid and unchanged until bspmm_destroy
  * (the plan borrows them).  The library never allocates device memory: the caller provides a
  * device workspace of at least bspmm_workspace_bytes() bytes, 256-byte aligned, which the plan
- * owns until bspmm_destroy (schedule tables and the transposed CSR live there).
+ * owns until bspmm_destroy (schedule tables, the transposed CSR and the merged CSR of summed
+ * operations live there).
  *
  * Streams.  `stream` is a hipStream_t passed as void* (NULL = the default stream).  All
  * device work is enqueued asynchronously; no call synchronises the device except where stated.
- * bspmm_run / bspmm_run_transposed enqueue exactly one kernel.  Calls on one plan must be
+ * bspmm_run / bspmm_run_transposed enqueue exactly one kernel (the first call of a direction
+ * also the one-off device builds named under BSPMM_BUILD_TRANSPOSE).  Calls on one plan must be
  * issued from one host thread at a time and on the stream order the caller wants.
  *
  * Errors.  Every int-returning call returns BSPMM_OK or a negative BSPMM_E* code; nothing is
@@ -63,7 +65,10 @@ extern "C" {
 
 /* bspmm_options.flags */
 #define BSPMM_DRY_RUN          1u  /* schedule only: touch no device, run calls return ESTATE */
-#define BSPMM_BUILD_TRANSPOSE  2u  /* enqueue the transposed-CSR build inside bspmm_create    */
+#define BSPMM_BUILD_TRANSPOSE  2u  /* enqueue the one-off device builds (the transposed CSR; with
+                                      BSPMM_ACCUMULATE the merged CSR of every summed set, both
+                                      directions) inside bspmm_create instead of in the first run
+                                      that needs them - e.g. before a HIP-graph capture          */
 #define BSPMM_SPLIT_HUB_ROWS   8u  /* rows with >= 64 entries and >= 4x the operation's average are
                                       split across all lanes of the workgroup and the partial
                                       sums reduced (DPP / ds_swizzle inside a wavefront, LDS across
@@ -74,7 +79,9 @@ extern "C" {
                                       of the graph-convolution layer (Fig. 6 / Fig. 7) - instead
                                       of being rejected as overlapping.  Applies to C blocks in
                                       bspmm_run and to B blocks (input gradients) in
-                                      bspmm_run_transposed                                       */
+                                      bspmm_run_transposed.  The first run of a direction also
+                                      enqueues a kernel that merges the CSR arrays of every such
+                                      set into the workspace (once per plan)                     */
 #define BSPMM_COO_DIRECT       32u  /* bspmm_create_coo only: no conversion to CSR.  Every run is one
                                       launch of the kernel of Fig. 3 / Fig. 5(a,b): a group of lanes
                                       per stored entry, products added with LDS floating-point

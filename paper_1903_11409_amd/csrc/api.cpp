@@ -27,6 +27,9 @@ hipError_t launch_build_from_coo(const OpRecord* ops, int batch, int lds_bytes, 
                                  float* csr_values, int32_t* gscratch, hipStream_t stream);
 hipError_t launch_bspmm_coo(const CooLaunchParams& P, int grid, int lds_bytes, bool vec4,
                             hipStream_t stream);
+hipError_t launch_merge_sets(const SetRecord* sets, int count, const int32_t* rpt,
+                             const int32_t* colids, const float* values, int32_t* merged,
+                             hipStream_t stream);
 hipError_t launch_validate_coo(const OpRecord* ops, int batch, const int32_t* ids, int32_t* flag,
                                hipStream_t stream);
 int bspmm_max_resident_workgroups(int lds_bytes, bool slices, bool hubs);
@@ -61,6 +64,9 @@ struct Layout {
     size_t rpt_t = 0, colids_t = 0, values_t = 0;
     size_t scratch = 0;
     size_t flag = 0;
+    // summed sets (BSPMM_ACCUMULATE), per direction: their records and their merged CSR arrays
+    size_t sets[2] = {0, 0};
+    size_t merged[2] = {0, 0};
     // plans made from COO operands: the CSR arrays built on the device and what the build needs
     size_t coo_records = 0;
     size_t csr_rpt = 0, csr_colids = 0, csr_values = 0;
@@ -83,6 +89,9 @@ struct bspmm_plan {
     int64_t scratch_words = 0;
     bool transposed_supported = true;
     bool transposed_built = false;
+    std::vector<SetRecord> set_records[2];   // summed sets of the forward / transposed schedule
+    int64_t merged_words[2] = {0, 0};
+    bool merged_built[2] = {false, false};
     int64_t effective_bytes[2] = {0, 0};
     int64_t flops = 0;
     bool reads_dense = false;   // some operation has rows and columns: the runs read the dense input
@@ -152,6 +161,60 @@ int overlap_kind(const int64_t* off, const int32_t* len, int n)
             return 2;
     }
     return kind;
+}
+
+// The sets of summed operations of direction d: one record per set for the kernel that merges
+// their CSR arrays, room for the merged arrays, and the location of those in the first item of
+// every task of the set (its rpt_off, nz_off and nnz then describe the merged CSR).
+void describe_sets(bspmm_plan& p, int d)
+{
+    Schedule& sc = p.sched[d];
+    const DirOps& o = p.dir[d];
+    std::vector<SetRecord>& recs = p.set_records[d];
+    recs.clear();
+    int64_t words = 0;
+    std::vector<int32_t> nnz_sum(sc.fused_sets.size(), 0);
+    for (size_t si = 0; si < sc.fused_sets.size(); ++si) {
+        const std::vector<int>& mem = sc.fused_sets[si];
+        SetRecord r;
+        std::memset(&r, 0, sizeof r);
+        r.members = (int32_t)mem.size();
+        r.m = o.m[mem[0]];
+        int32_t rows = 0;
+        for (size_t j = 0; j < mem.size(); ++j) {
+            r.rpt_off[j] = o.rpt_off[mem[j]];
+            r.nz_off[j] = o.nz_off[mem[j]];
+            r.nnz[j] = o.nnz[mem[j]];
+            r.k[j] = o.k[mem[j]];
+            size_t owner = j;
+            for (size_t e = 0; e < j; ++e)
+                if (o.in_off[mem[e]] == o.in_off[mem[j]]) {
+                    owner = e;
+                    break;
+                }
+            if (owner == j) {
+                r.tile_row[j] = rows;
+                rows += o.k[mem[j]];
+            } else {
+                r.tile_row[j] = r.tile_row[owner];
+            }
+            nnz_sum[si] += o.nnz[mem[j]];
+        }
+        const FusedLayout L = fused_layout(r.m, nnz_sum[si]);
+        r.merged_rpt_off = words;
+        words += L.rs;
+        r.merged_nz_off = words;
+        words += L.entry_words;
+        recs.push_back(r);
+    }
+    p.merged_words[d] = words;
+    for (size_t t = 0; t < sc.task_set.size(); ++t) {
+        const int si = sc.task_set[t];
+        WorkItem& w = sc.items[(size_t)sc.item_base[1] + t * sc.fused_stride];
+        w.rpt_off = recs[si].merged_rpt_off;
+        w.nz_off = recs[si].merged_nz_off;
+        w.nnz = nnz_sum[si];
+    }
 }
 
 // Fill everything of the plan that needs no device.
@@ -305,6 +368,13 @@ int plan_host(bspmm_plan& p, const bspmm_batch* b, int32_t F, const Knobs& kn)
     at = align_up(at + (size_t)scratch_words * 4);
     L.flag = at;
     at = align_up(at + 4);
+    for (int d = 0; d < 2; ++d) {
+        describe_sets(p, d);
+        L.sets[d] = at;
+        at = align_up(at + p.set_records[d].size() * sizeof(SetRecord));
+        L.merged[d] = at;
+        at = align_up(at + (size_t)p.merged_words[d] * 4);
+    }
     L.total = at;
     return BSPMM_OK;
 }
@@ -405,6 +475,23 @@ int enqueue_build(bspmm_plan* p, hipStream_t s)
     return BSPMM_OK;
 }
 
+// The merged CSR of the summed sets of direction d (once per plan; for d = 1 after the
+// transposed CSR has been built).
+int enqueue_merge(bspmm_plan* p, int d, hipStream_t s)
+{
+    if (p->merged_built[d] || p->set_records[d].empty()) return BSPMM_OK;
+    const bool own = d == 0 || p->knobs.symmetric;
+    const int32_t* rpt = own ? p->rpt : reinterpret_cast<const int32_t*>(p->ws + p->lay.rpt_t);
+    const int32_t* colids = own ? p->colids : reinterpret_cast<const int32_t*>(p->ws + p->lay.colids_t);
+    const float* values = own ? p->values : reinterpret_cast<const float*>(p->ws + p->lay.values_t);
+    hipError_t e = launch_merge_sets(reinterpret_cast<const SetRecord*>(p->ws + p->lay.sets[d]),
+                                     (int)p->set_records[d].size(), rpt, colids, values,
+                                     reinterpret_cast<int32_t*>(p->ws + p->lay.merged[d]), s);
+    if (e != hipSuccess) return hip_fail(e);
+    p->merged_built[d] = true;
+    return BSPMM_OK;
+}
+
 int run_direction(bspmm_plan* p, int d, const float* in, float* out, int64_t ld_in,
                   int64_t ld_out, hipStream_t s)
 {
@@ -431,6 +518,8 @@ int run_direction(bspmm_plan* p, int d, const float* in, float* out, int64_t ld_
     if (sc.grid == 0) return BSPMM_OK;
     // when no operation has both rows and columns nothing is read: the input may have no rows at all
     if ((!in && p->reads_dense) || !out || ld_in < p->F || ld_out < p->F) return BSPMM_EINVAL;
+    const int mrc = enqueue_merge(p, d, s);
+    if (mrc != BSPMM_OK) return mrc;
     LaunchParams P;
     P.items = reinterpret_cast<const WorkItem*>(p->ws + p->lay.items[d]);
     if (d == 0) {
@@ -457,6 +546,7 @@ int run_direction(bspmm_plan* p, int d, const float* in, float* out, int64_t ld_
     }
     P.n_tasks = sc.grid;
     P.fused_stride = sc.fused_stride;
+    P.merged = reinterpret_cast<const int32_t*>(p->ws + p->lay.merged[d]);
     P.lds_floats = p->knobs.lds_words;
     P.pad = p->knobs.pad;
     P.w = nullptr;
@@ -645,6 +735,10 @@ int upload_plan(bspmm_plan* p, const bspmm_options* options, void* workspace,
     if (e == hipSuccess && !p->records.empty())
         e = hipMemcpyAsync(p->ws + p->lay.op_records, p->records.data(),
                            p->records.size() * sizeof(OpRecord), hipMemcpyHostToDevice, s);
+    for (int d = 0; d < 2 && e == hipSuccess; ++d)
+        if (!p->set_records[d].empty())
+            e = hipMemcpyAsync(p->ws + p->lay.sets[d], p->set_records[d].data(),
+                               p->set_records[d].size() * sizeof(SetRecord), hipMemcpyHostToDevice, s);
     if (p->coo_direct) {
         for (int d = 0; d < 2 && e == hipSuccess; ++d)
             if (!p->coo_sched[d].items.empty())
@@ -674,8 +768,12 @@ int upload_plan(bspmm_plan* p, const bspmm_options* options, void* workspace,
         }
     }
     if (e != hipSuccess) return hip_fail(e);
-    if (options && (options->flags & BSPMM_BUILD_TRANSPOSE) && p->transposed_supported)
-        return enqueue_build(p, s);
+    if (options && (options->flags & BSPMM_BUILD_TRANSPOSE)) {
+        int rc = enqueue_merge(p, 0, s);
+        if (rc == BSPMM_OK && p->transposed_supported) rc = enqueue_build(p, s);
+        if (rc == BSPMM_OK && p->transposed_supported) rc = enqueue_merge(p, 1, s);
+        return rc;
+    }
     return BSPMM_OK;
 }
 
@@ -706,6 +804,7 @@ int run_gcn(bspmm_plan* p, const float* X, int64_t ldx, const float* W, int64_t 
     }
     P.n_tasks = sc.grid;
     P.fused_stride = sc.fused_stride;
+    P.merged = nullptr;
     P.lds_floats = sc.front_lds_words;     // what the launch gets: decides the rows of X_i per pass
     P.pad = 0;
     P.w = W;

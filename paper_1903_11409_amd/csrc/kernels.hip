@@ -502,19 +502,21 @@ __device__ __forceinline__ void run_generic(const LaunchParams& P, const WorkIte
 // ---------------------------------------------------------------------------------------
 // Fused task: M operations with the same output rows whose products are added up (the channel
 // sum of the graph-convolution layer, Fig. 6 / Fig. 7) in registers, so the block is written
-// once instead of M times and never read back.  Every array of every member goes straight from
-// global memory into LDS (no staging registers: all of it is in flight at once); members that
-// read the same dense tile share one copy.
+// once instead of M times and never read back.  The set runs from its merged CSR (built once
+// per plan by merge_sets_kernel below): the task is then an ordinary staged item whose dense
+// tile is the members' tiles laid end to end.  Everything goes straight from global memory
+// into LDS, 16 bytes per lane (the merged arrays are the library's own: aligned and padded).
 // ---------------------------------------------------------------------------------------
-// `words` 32-bit words global -> LDS by one wavefront (lane wl of 64), 256 bytes per instruction.
-__device__ __forceinline__ void wave_copy_words(const void* src, int* dst_lds, int words, int wl)
+// `vecs` 16-byte vectors global -> LDS by the whole workgroup, 1 KiB per wavefront instruction.
+__device__ __forceinline__ void wg_copy_vec4(const int32_t* src, int* dst_lds, int vecs, int wave,
+                                             int wl)
 {
-    for (int e0 = 0; e0 < words; e0 += 64) {
+    for (int e0 = wave << 6; e0 < vecs; e0 += kThreads) {
         const int e = e0 + wl;
-        if (e < words)
+        if (e < vecs)
             __builtin_amdgcn_global_load_lds(
-                (const void __attribute__((address_space(1)))*)(static_cast<const int*>(src) + e),
-                (void __attribute__((address_space(3)))*)(dst_lds + e0), 4, 0, 0);
+                (const void __attribute__((address_space(1)))*)(src + 4 * e),
+                (void __attribute__((address_space(3)))*)(dst_lds + 4 * e0), 16, 0, 0);
     }
 }
 
@@ -528,7 +530,7 @@ __device__ __forceinline__ void run_fused(const LaunchParams& P, int* sm, int fi
     // ---- member descriptors: lane j of every wavefront fetches member j's item, so all of
     // them arrive in one round trip; the uniform code below picks a member's fields out of
     // the lanes with v_readlane (no scalar load and no LDS per member).  The task's own
-    // fields are member 0's.
+    // fields are member 0's; its rpt_off, nz_off and nnz describe the merged CSR of the set.
     const int wl = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const WorkItem mine = P.items[first_item + min(wl, P.fused_stride - 1)];
@@ -538,72 +540,40 @@ __device__ __forceinline__ void run_fused(const LaunchParams& P, int* sm, int fi
         const unsigned hi = __builtin_amdgcn_readlane((int)(v >> 32), j);
         return (int64_t)(((uint64_t)hi << 32) | lo);
     };
-    WorkItem it0;
-    it0.nrows = lane_i32(mine.nrows, 0);
-    if (it0.nrows <= 0) return;
-    it0.staged = lane_i32(mine.staged, 0);
-    it0.m = lane_i32(mine.m, 0);
-    it0.k = lane_i32(mine.k, 0);
-    it0.fw = lane_i32(mine.fw, 0);
-    it0.f0 = lane_i32(mine.f0, 0);
-    it0.row0 = lane_i32(mine.row0, 0);
-    it0.out_row_off = lane_i64(mine.out_row_off, 0);
+    const int nrows = lane_i32(mine.nrows, 0);
+    if (nrows <= 0) return;
+    const int staged0 = lane_i32(mine.staged, 0);
+    const int m = lane_i32(mine.m, 0);
+    const int fw = lane_i32(mine.fw, 0);
+    const int f0 = lane_i32(mine.f0, 0);
+    const int row0 = lane_i32(mine.row0, 0);
+    const int nnz_sum = lane_i32(mine.nnz, 0);
+    const int64_t out_row_off = lane_i64(mine.out_row_off, 0);
 #ifdef BSPMM_TRACE
     if (P.trace && tid == 0) P.trace[(size_t)task * 8] = wall_clock64();
 #endif
     BSPMM_STAMP(task, 1);
-    const int members = (it0.staged >> 8) & 0xff;
-    const int m = it0.m, fw = it0.fw;
-    const FusedLayout L = fused_layout(members, m);
+    const int members = (staged0 >> 8) & 0xff;
+    const FusedLayout L = fused_layout(m, nnz_sum);
     const int stride = round_up(fw, 4);
     const Split<kThreads, VEC> sp(fw, tid);
     const bool direct = VEC == 4 && (sp.nvec & (sp.nvec - 1)) == 0;
 
-    // ---- stage the CSR arrays: member j is copied by wavefront j % 4 alone (the arrays of a
-    // molecule-sized member are one instruction each; four wavefronts walking every member
-    // would spend their time on address arithmetic).  Offsets are uniform; lane 0 of the
-    // copying wavefront tables them.
-    int off = L.cv_off;
-    int nnz_sum = 0;
-    for (int j = 0; j < members; ++j) {
-        const int nnz = lane_i32(mine.nnz, j);
-        const int nz4 = round_up(nnz, 4);
-        if ((j & (kThreads / 64 - 1)) == wave) {
-            const int64_t nz_off = lane_i64(mine.nz_off, j);
-            if (wl == 0) {
-                sm[4 * j + 0] = off;
-                sm[4 * j + 1] = off + nz4;
-                sm[4 * j + 3] = nnz;
-            }
-            wave_copy_words(P.rpt + lane_i64(mine.rpt_off, j), sm + L.rpt_off + j * L.rs, m + 1, wl);
-            wave_copy_words(P.colids + nz_off, sm + off, nnz, wl);
-            wave_copy_words(P.values + nz_off, sm + off + nz4, nnz, wl);
-        }
-        off += 2 * nz4;
-        nnz_sum += nnz;
-    }
-    // merged CSR of the members (filled below): row pointers, then (dense row offset, value)
-    int* crpt = sm + off;
-    int2* cv = reinterpret_cast<int2*>(sm + off + L.rs);
-    int tile_off = off + L.rs + 2 * round_up(nnz_sum, 2);
-    int tile_of = 0;                                    // lane j: LDS offset of member j's tile
+    // ---- stage the merged CSR
+    wg_copy_vec4(P.merged + lane_i64(mine.rpt_off, 0), sm, L.rs >> 2, wave, wl);
+    wg_copy_vec4(P.merged + lane_i64(mine.nz_off, 0), sm + L.rs, L.entry_words >> 2, wave, wl);
+    // ---- and the dense tile of every member that does not share an earlier member's
+    int tile_off = L.tile_off;
     for (int j = 0; j < members; ++j) {
         const int owner = (lane_i32(mine.staged, j) >> 16) & 0xff;
-        if (owner != j) {                               // shares the tile of an earlier member
-            const int shared = lane_i32(tile_of, owner);
-            tile_of = wl == j ? shared : tile_of;
-            if (tid == 0) sm[4 * j + 2] = shared;
-            continue;
-        }
-        tile_of = wl == j ? tile_off : tile_of;
-        if (tid == 0) sm[4 * j + 2] = tile_off;
+        if (owner != j) continue;
         const int k = lane_i32(mine.k, j);
         float* bs = reinterpret_cast<float*>(sm + tile_off);
-        const float* __restrict__ src = P.in + lane_i64(mine.in_row_off, j) * P.ld_in + it0.f0;
+        const float* __restrict__ src = P.in + lane_i64(mine.in_row_off, j) * P.ld_in + f0;
         if (direct) {
             const int sh = ilog2(sp.nvec);
             const int total = k << sh;
-            for (int e0 = (tid >> 6) << 6; e0 < total; e0 += kThreads) {
+            for (int e0 = wave << 6; e0 < total; e0 += kThreads) {
                 const int e = e0 + wl;
                 if (e < total)
                     __builtin_amdgcn_global_load_lds(
@@ -622,54 +592,27 @@ __device__ __forceinline__ void run_fused(const LaunchParams& P, int* sm, int fi
     BSPMM_STAMP(task, 6);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // direct-to-LDS loads landed
     __syncthreads();
-    BSPMM_STAMP(task, 7);
-
-    // ---- merge the members' rows into one CSR: row r of the sum is the concatenation of row r
-    // of every member, so its start is the sum of the members' starts; every entry already
-    // carries the LDS offset of the dense row it multiplies.  One lane per (row, member).
-    const int4* tab = reinterpret_cast<const int4*>(sm);
-    const int row_end = it0.row0 + it0.nrows;
-    const int pairs = it0.nrows * members;
-    for (int q = tid; q < pairs; q += kThreads) {
-        const int rl = q / members;
-        const int j = q - rl * members;
-        const int r = it0.row0 + rl;
-        int start = 0, before = 0, mine0 = 0, mine1 = 0;
-        for (int e = 0; e < members; ++e) {             // independent reads, all in flight
-            const int a = sm[L.rpt_off + e * L.rs + r];
-            const int b = sm[L.rpt_off + e * L.rs + r + 1];
-            start += a;
-            before += e < j ? b - a : 0;
-            mine0 = e == j ? a : mine0;
-            mine1 = e == j ? b : mine1;
-        }
-        const int4 tb = tab[j];
-        const int p1 = min(max(mine1, 0), tb.w);        // malformed pointers stay bounded
-        int pos = start + before;
-        for (int p = min(max(mine0, 0), p1); p < p1; ++p)
-            cv[pos++] = make_int2(tb.z + sm[tb.x + p] * stride, sm[tb.y + p]);
-        if (j == 0) crpt[r] = start;
-        if (j == members - 1 && r == row_end - 1) crpt[row_end] = pos;
-    }
-    __syncthreads();
-
     BSPMM_STAMP(task, 2);
+
     // ---- rows of the sum: the plain gather loop over the merged CSR, one store per row
-    float* __restrict__ dst = P.out + it0.out_row_off * P.ld_out + it0.f0;
-    const float* lds = reinterpret_cast<const float*>(sm);
-    for (int r = it0.row0 + sp.g; r < row_end; r += sp.groups) {
-        const int p0 = crpt[r];
-        const int p1 = crpt[r + 1];
+    const int* crpt = sm;
+    const int2* cv = reinterpret_cast<const int2*>(sm + L.rs);
+    const int row_end = row0 + nrows;
+    float* __restrict__ dst = P.out + out_row_off * P.ld_out + f0;
+    const float* tiles = reinterpret_cast<const float*>(sm + L.tile_off);
+    for (int r = row0 + sp.g; r < row_end; r += sp.groups) {
+        const int p1 = min(max(crpt[r + 1], 0), nnz_sum);     // malformed pointers stay bounded
+        const int p0 = min(max(crpt[r], 0), p1);
         for (int v = sp.l; v < sp.nvec; v += sp.g_lanes) {
-            const float* bcol = lds + v * VEC;
+            const float* bcol = tiles + v * VEC;
             VT acc = V::zero();
             int p = p0;
             for (; p + 3 < p1; p += 4) {
                 const int2 e0 = cv[p], e1 = cv[p + 1], e2 = cv[p + 2], e3 = cv[p + 3];
-                const VT b0 = load_vec<VEC>(bcol + e0.x);
-                const VT b1 = load_vec<VEC>(bcol + e1.x);
-                const VT b2 = load_vec<VEC>(bcol + e2.x);
-                const VT b3 = load_vec<VEC>(bcol + e3.x);
+                const VT b0 = load_vec<VEC>(bcol + e0.x * stride);
+                const VT b1 = load_vec<VEC>(bcol + e1.x * stride);
+                const VT b2 = load_vec<VEC>(bcol + e2.x * stride);
+                const VT b3 = load_vec<VEC>(bcol + e3.x * stride);
                 V::fma(acc, __int_as_float(e0.y), b0);
                 V::fma(acc, __int_as_float(e1.y), b1);
                 V::fma(acc, __int_as_float(e2.y), b2);
@@ -677,7 +620,7 @@ __device__ __forceinline__ void run_fused(const LaunchParams& P, int* sm, int fi
             }
             for (; p < p1; ++p) {
                 const int2 e = cv[p];
-                V::fma(acc, __int_as_float(e.y), load_vec<VEC>(bcol + e.x));
+                V::fma(acc, __int_as_float(e.y), load_vec<VEC>(bcol + e.x * stride));
             }
             store_out<VEC>(dst + (int64_t)r * P.ld_out + v * VEC, acc);
         }
@@ -685,10 +628,66 @@ __device__ __forceinline__ void run_fused(const LaunchParams& P, int* sm, int fi
     BSPMM_STAMP(task, 3);
 #ifdef BSPMM_TRACE
     if (P.trace && tid == 0) {
-        P.trace[(size_t)task * 8 + 4] = it0.nrows;
-        P.trace[(size_t)task * 8 + 5] = it0.k;
+        P.trace[(size_t)task * 8 + 4] = nrows;
+        P.trace[(size_t)task * 8 + 5] = lane_i32(mine.k, 0);
     }
 #endif
+}
+
+// Merged CSR of one set of summed operations (one workgroup per set, once per plan and
+// direction): row r of the set = row r of member 0, then of member 1, ...; an entry becomes
+// (row of the concatenated dense tiles, value).  Row pointers are clamped to the member's entry
+// count and columns outside a member's tile point at its row 0, so malformed input cannot make
+// the product leave its LDS.
+__global__ void __launch_bounds__(kThreads)
+merge_sets_kernel(const SetRecord* __restrict__ sets, const int32_t* __restrict__ rpt,
+                  const int32_t* __restrict__ colids, const float* __restrict__ values,
+                  int32_t* __restrict__ merged)
+{
+    __shared__ int partial[kThreads];
+    const SetRecord& g = sets[blockIdx.x];
+    const int tid = threadIdx.x;
+    const int m = g.m, members = g.members;
+    const int per = (m + kThreads - 1) / kThreads;
+    const int r0 = min(m, tid * per), r1 = min(m, r0 + per);
+    auto row_range = [&](int j, int r, int& a, int& b) {
+        const int32_t* rp = rpt + g.rpt_off[j];
+        b = min(max(rp[r + 1], 0), g.nnz[j]);
+        a = min(max(rp[r], 0), b);
+    };
+    int sum = 0;
+    for (int r = r0; r < r1; ++r)
+        for (int j = 0; j < members; ++j) {
+            int a, b;
+            row_range(j, r, a, b);
+            sum += b - a;
+        }
+    partial[tid] = sum;
+    __syncthreads();
+    for (int off = 1; off < kThreads; off <<= 1) {     // inclusive scan over the lanes' sums
+        const int add = tid >= off ? partial[tid - off] : 0;
+        __syncthreads();
+        partial[tid] += add;
+        __syncthreads();
+    }
+    int pos = partial[tid] - sum;
+    int32_t* mr = merged + g.merged_rpt_off;
+    int2* mc = reinterpret_cast<int2*>(merged + g.merged_nz_off);
+    for (int r = r0; r < r1; ++r) {
+        mr[r] = pos;
+        for (int j = 0; j < members; ++j) {
+            int a, b;
+            row_range(j, r, a, b);
+            const int32_t* ci = colids + g.nz_off[j];
+            const float* va = values + g.nz_off[j];
+            for (int p = a; p < b; ++p) {
+                const int c = ci[p];
+                mc[pos++] = make_int2(g.tile_row[j] + ((unsigned)c < (unsigned)g.k[j] ? c : 0),
+                                      __float_as_int(va[p]));
+            }
+        }
+    }
+    if (tid == kThreads - 1) mr[m] = pos;
 }
 
 // One task of a sub-workgroup range: 256/S slots, one staged item each.
@@ -1414,6 +1413,16 @@ hipError_t launch_build_transpose(const OpRecord* ops, int batch, int lds_bytes,
     if (batch <= 0) return hipSuccess;
     hipLaunchKernelGGL(build_sorted_kernel<false>, dim3(batch), dim3(kThreads), lds_bytes, stream,
                        ops, rpt, colids, values, rpt_t, colids_t, values_t, gscratch);
+    return hipGetLastError();
+}
+
+hipError_t launch_merge_sets(const SetRecord* sets, int count, const int32_t* rpt,
+                             const int32_t* colids, const float* values, int32_t* merged,
+                             hipStream_t stream)
+{
+    if (count <= 0) return hipSuccess;
+    hipLaunchKernelGGL(merge_sets_kernel, dim3(count), dim3(kThreads), 0, stream, sets, rpt, colids,
+                       values, merged);
     return hipGetLastError();
 }
 

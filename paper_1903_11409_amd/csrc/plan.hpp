@@ -70,6 +70,7 @@ struct LaunchParams {
     int64_t ld_w;
     int32_t n_front;
     int32_t accumulate;   // add to the output instead of overwriting it
+    const int32_t* merged; // merged CSR arrays of the summed sets of this direction
 #ifdef BSPMM_TRACE
     long long* trace;     // development builds only: 8 timestamps per workgroup
 #endif
@@ -179,27 +180,44 @@ BSPMM_HD inline StagedLayout staged_layout(int m, int k, int nnz, int fw, int pa
     return L;
 }
 
-// LDS layout of a fused task (M operations with the same output rows, summed), in words:
-//   [0, 4M)                       per member: column array, value array, dense tile, nnz
-//   [rpt_off + j*rs, ...)         row pointers of member j, rs = round_up(m+1, 4)
-//   then per member               column indices and values (round_up(nnz, 4) words each)
-//   then rs words                 row pointers of the merged CSR (row r = all members' row r)
-//   then 2*round_up(sum nnz, 2)   its entries: (LDS word offset of the dense row, value)
-//   then per distinct dense input its tile, k rows of round_up(fw, 4) words
+// Operations that are summed into one output block ("a set") run from a merged CSR that a device
+// kernel builds once per plan and direction: row r of the set is row r of every member, one
+// after the other in member order, and an entry names a row of the members' dense tiles laid
+// end to end (members that read the same dense block share one tile).  Per set, in the
+// workspace: round_up(m+1, 4) row pointers, then round_up(sum nnz, 2) entries of two words
+// (tile row, value).
+//
+// LDS layout of a fused task, in words:
+//   [0, rs)                            merged row pointers, rs = round_up(m+1, 4)
+//   [rs, rs + 2*round_up(sum nnz, 2))  merged entries
+//   then per distinct dense input      its tile, k rows of round_up(fw, 4) words
 struct FusedLayout {
-    int rpt_off;
     int rs;
-    int cv_off;     // first word after the row pointers
+    int entry_words;
+    int tile_off;
 };
 
-BSPMM_HD inline FusedLayout fused_layout(int members, int m)
+BSPMM_HD inline FusedLayout fused_layout(int m, int nnz_sum)
 {
     FusedLayout L;
-    L.rpt_off = round_up(4 * members, 4);
     L.rs = round_up(m + 1, 4);
-    L.cv_off = L.rpt_off + members * L.rs;
+    L.entry_words = 2 * round_up(nnz_sum, 2);
+    L.tile_off = L.rs + L.entry_words;
     return L;
 }
+
+// What the kernel that merges a set needs (one record per set and direction).
+struct alignas(8) SetRecord {
+    int64_t rpt_off[kMaxMembers];   // the members' row pointers and entries in the CSR arrays
+    int64_t nz_off[kMaxMembers];
+    int64_t merged_rpt_off;         // word offsets of the set's merged arrays
+    int64_t merged_nz_off;
+    int32_t nnz[kMaxMembers];
+    int32_t k[kMaxMembers];         // dense-input rows of the members (bound of their columns)
+    int32_t tile_row[kMaxMembers];  // first row of member j's dense tile in the concatenation
+    int32_t members;
+    int32_t m;
+};
 
 // Lanes that share one output row: enough 4-float vectors to cover the tile, a power of two.
 BSPMM_HD inline int lanes_per_row(int fw, int vec)

@@ -205,13 +205,10 @@ void draft_op(const DirOps& o, int i, int F, int vec, const Choice& ch, const Kn
 // LDS words a fused task needs: mirrors run_fused() in kernels.hip.
 int64_t fused_words(const DirOps& o, const std::vector<int>& members, int fw)
 {
-    const FusedLayout L = fused_layout((int)members.size(), o.m[members[0]]);
-    int64_t words = L.cv_off + L.rs;               // member tables, then merged row pointers
     int64_t nnz_sum = 0;
     for (int i : members) nnz_sum += o.nnz[i];
-    words += 2 * ((nnz_sum + 1) / 2 * 2);          // merged entries
+    int64_t words = round_up(o.m[members[0]] + 1, 4) + 2 * ((nnz_sum + 1) / 2 * 2);
     for (size_t j = 0; j < members.size(); ++j) {
-        words += 2 * (int64_t)round_up(o.nnz[members[j]], 4);
         bool owns = true;
         for (size_t e = 0; e < j; ++e) owns = owns && o.in_off[members[e]] != o.in_off[members[j]];
         if (owns) words += (int64_t)o.k[members[j]] * round_up(fw, 4);
@@ -681,7 +678,7 @@ Schedule make_schedule(const DirOps& ops, int F, const Knobs& kn_in)
     // range 1: fused tasks, `fused_stride` item slots each (the members, then empty items)
     int wg = grid0;
     {
-        std::vector<std::vector<int>> fused_sets;
+        std::vector<std::vector<int>>& fused_sets = s.fused_sets;
         for (int g = 0; g < outs.size(); ++g)
             if (outs.count(g) > 1) fused_sets.push_back(outs.members(g));
         s.fused_stride = (int)most_members;
@@ -707,6 +704,7 @@ Schedule make_schedule(const DirOps& ops, int F, const Knobs& kn_in)
                 s.items_in_bin[BSPMM_BIN_WORKGROUP]++;
             }
             for (size_t j = mem.size(); j < most_members; ++j) s.items.push_back(empty_item());
+            s.task_set.push_back(x.fused);
             ++wg;
             ++s.fused_tasks;
         }

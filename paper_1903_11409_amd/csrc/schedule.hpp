@@ -49,6 +49,8 @@ struct Schedule {
     int32_t item_base[kRanges] = {0, 0, 0, 0, 0};
     int fused_stride = 1;            // item slots per fused task
     int fused_tasks = 0;
+    std::vector<std::vector<int>> fused_sets;   // the sets of summed operations (members in order)
+    std::vector<int> task_set;       // set of every fused task, in task order
     int error = 0;                   // BSPMM_E* when the batch cannot be scheduled
     int grid = 0;                    // number of tasks
     int launch_grid = 0;             // workgroups of the persistent launch

@@ -477,11 +477,12 @@ def test_random_summed_groups(torch_cuda, oracle, block):
 
 
 def test_summed_groups_take_a_larger_lds_budget_when_they_need_it(torch_cuda, oracle):
-    """Four channels of 400-node graphs do not fit the default 24 KiB together: with lds_bytes
-    left open the plan moves to 80 KiB, then to the CU's whole 160 KiB, instead of refusing."""
+    """Four channels of graphs with many hundred nodes do not fit the default 24 KiB together:
+    with lds_bytes left open the plan moves to 80 KiB, then to the CU's whole 160 KiB, instead
+    of refusing."""
     from random_cases import _random_csr
     rng = np.random.default_rng(5)
-    for m, per_row, want in [(150, 2, 81920), (400, 5, 163840)]:
+    for m, per_row, want in [(800, 2, 81920), (1800, 2, 163840)]:
         ops, blocks = [], []
         for g in range(3):
             for _ in range(4):
