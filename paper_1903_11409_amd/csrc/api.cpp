@@ -15,7 +15,7 @@
 
 namespace bspmm {
 hipError_t launch_bspmm(const LaunchParams& P, int grid, int lds_bytes, bool vec4, bool slices,
-                        bool hubs, hipStream_t stream);
+                        bool hubs, bool merged, hipStream_t stream);
 hipError_t launch_bspmm_gcn(const LaunchParams& P, int grid, int lds_bytes, bool accumulate,
                             hipStream_t stream);
 hipError_t launch_build_transpose(const OpRecord* ops, int batch, int lds_bytes,
@@ -173,14 +173,14 @@ void describe_sets(bspmm_plan& p, int d)
     std::vector<SetRecord>& recs = p.set_records[d];
     recs.clear();
     int64_t words = 0;
-    std::vector<int32_t> nnz_sum(sc.fused_sets.size(), 0);
-    for (size_t si = 0; si < sc.fused_sets.size(); ++si) {
-        const std::vector<int>& mem = sc.fused_sets[si];
+    auto describe = [&](const std::vector<int>& mem, bool plain) {
         SetRecord r;
         std::memset(&r, 0, sizeof r);
         r.members = (int32_t)mem.size();
         r.m = o.m[mem[0]];
+        r.plain = plain ? 1 : 0;
         int32_t rows = 0;
+        int64_t nnz_sum = 0;
         for (size_t j = 0; j < mem.size(); ++j) {
             r.rpt_off[j] = o.rpt_off[mem[j]];
             r.nz_off[j] = o.nz_off[mem[j]];
@@ -198,15 +198,20 @@ void describe_sets(bspmm_plan& p, int d)
             } else {
                 r.tile_row[j] = r.tile_row[owner];
             }
-            nnz_sum[si] += o.nnz[mem[j]];
+            nnz_sum += o.nnz[mem[j]];
         }
-        const FusedLayout L = fused_layout(r.m, nnz_sum[si]);
         r.merged_rpt_off = words;
-        words += L.rs;
+        words += round_up(r.m + 1, 4);
         r.merged_nz_off = words;
-        words += L.entry_words;
+        words += 2 * (int64_t)round_up((int)nnz_sum, 4);
         recs.push_back(r);
-    }
+        return (int32_t)nnz_sum;
+    };
+    // sets run as fused tasks, then sets an operation with the summed matrix stands in for
+    std::vector<int32_t> nnz_sum;
+    for (const std::vector<int>& mem : sc.fused_sets) nnz_sum.push_back(describe(mem, false));
+    const size_t first_plain = recs.size();
+    for (const std::vector<int>& mem : sc.merged_sets) describe(mem, true);
     p.merged_words[d] = words;
     for (size_t t = 0; t < sc.task_set.size(); ++t) {
         const int si = sc.task_set[t];
@@ -215,6 +220,14 @@ void describe_sets(bspmm_plan& p, int d)
         w.nz_off = recs[si].merged_nz_off;
         w.nnz = nnz_sum[si];
     }
+    if (!sc.merged_sets.empty())
+        for (size_t j = 0; j < sc.items.size(); ++j) {
+            const int op = j < sc.item_op.size() ? sc.item_op[j] : -1;
+            if (op < sc.first_stand_in) continue;
+            const SetRecord& r = recs[first_plain + (size_t)(op - sc.first_stand_in)];
+            sc.items[j].rpt_off = r.merged_rpt_off;
+            sc.items[j].nz_off = r.merged_nz_off;
+        }
 }
 
 // Fill everything of the plan that needs no device.
@@ -301,7 +314,7 @@ int plan_host(bspmm_plan& p, const bspmm_batch* b, int32_t F, const Knobs& kn)
         Schedule& st = p.sched[1];
         for (size_t j = 0; j < st.items.size(); ++j) {
             const int op = st.item_op[j];
-            if (op < 0) continue;
+            if (op < 0 || op >= n) continue;     // (stand-ins of summed sets: see describe_sets)
             st.items[j].rpt_off = t.rpt_off[op];
             st.items[j].nz_off = t.nz_off[op];
         }
@@ -546,10 +559,9 @@ int run_direction(bspmm_plan* p, int d, const float* in, float* out, int64_t ld_
     }
     P.n_tasks = sc.grid;
     P.fused_stride = sc.fused_stride;
-    P.merged = reinterpret_cast<const int32_t*>(p->ws + p->lay.merged[d]);
     P.lds_floats = p->knobs.lds_words;
     P.pad = p->knobs.pad;
-    P.w = nullptr;
+    P.w = reinterpret_cast<const float*>(p->ws + p->lay.merged[d]);   // see LaunchParams
     P.bias = nullptr;
     P.ld_w = 0;
     P.n_front = 0;
@@ -561,7 +573,7 @@ int run_direction(bspmm_plan* p, int d, const float* in, float* out, int64_t ld_
                       (reinterpret_cast<uintptr_t>(in) & 15) == 0 &&
                       (reinterpret_cast<uintptr_t>(out) & 15) == 0;
     hipError_t e = launch_bspmm(P, sc.launch_grid, p->knobs.lds_words * 4, vec4, sc.has_slices,
-                                p->knobs.hubs, s);
+                                p->knobs.hubs, !sc.merged_sets.empty(), s);
     return e == hipSuccess ? BSPMM_OK : hip_fail(e);
 }
 
@@ -804,7 +816,6 @@ int run_gcn(bspmm_plan* p, const float* X, int64_t ldx, const float* W, int64_t 
     }
     P.n_tasks = sc.grid;
     P.fused_stride = sc.fused_stride;
-    P.merged = nullptr;
     P.lds_floats = sc.front_lds_words;     // what the launch gets: decides the rows of X_i per pass
     P.pad = 0;
     P.w = W;

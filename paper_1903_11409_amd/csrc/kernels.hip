@@ -98,16 +98,31 @@ struct Split {
 // first trip of every copy is issued before anything is waited for: one round trip stages a
 // typical molecule-sized item completely; larger items finish in unrolled leftover loops.
 // ---------------------------------------------------------------------------------------
-template <int S, int VEC, bool HUBS, bool WITH_TILE = true>
+// (the pointer travels in the slot of the front's weights, which such launches do not have: a
+// field of its own made the argument block longer and the headline launch 1 % slower)
+__device__ __forceinline__ const int32_t* merged_words(const LaunchParams& P)
+{
+    return reinterpret_cast<const int32_t*>(P.w);
+}
+
+template <int S, int VEC, bool HUBS, bool WITH_TILE = true, bool MERGED = false>
 __device__ __forceinline__ void stage_item(const LaunchParams& P, const WorkItem& it, int* sm,
                                            int lane)
 {
     using VT = typename Vec<VEC>::type;
     const StagedLayout L = staged_layout(it.m, it.k, it.nnz, it.fw, P.pad, HUBS && S == kThreads);
     if (HUBS && S == kThreads && lane == 0) sm[L.hub_off] = 0;   // no hub row found yet
-    const int32_t* __restrict__ rp = P.rpt + it.rpt_off;
-    const int32_t* __restrict__ ci = P.colids + it.nz_off;
-    const float* __restrict__ va = P.values + it.nz_off;
+    // (MERGED kernels, bit 2 of `staged`: the item is a set of summed operations that read one
+    // dense block, i.e. the product with the sum of their matrices; its CSR is the set's
+    // merged one in the workspace - row pointers at rpt_off, columns at nz_off, values behind
+    // the columns.  A template parameter, not a run-time test alone: the three selects cost
+    // the plain kernel 2 % of the headline launch.)
+    const bool merged = MERGED && (it.staged & 4) != 0;
+    const int32_t* __restrict__ rp = (merged ? merged_words(P) : P.rpt) + it.rpt_off;
+    const int32_t* __restrict__ ci = (merged ? merged_words(P) : P.colids) + it.nz_off;
+    const float* __restrict__ va =
+        merged ? reinterpret_cast<const float*>(merged_words(P) + it.nz_off + round_up(it.nnz, 4))
+               : P.values + it.nz_off;
     int2* cv = reinterpret_cast<int2*>(sm + L.cv_off);
     float* bs = reinterpret_cast<float*>(sm + L.b_off);
     const float* __restrict__ src = P.in + it.in_row_off * P.ld_in + it.f0;
@@ -560,8 +575,8 @@ __device__ __forceinline__ void run_fused(const LaunchParams& P, int* sm, int fi
     const bool direct = VEC == 4 && (sp.nvec & (sp.nvec - 1)) == 0;
 
     // ---- stage the merged CSR
-    wg_copy_vec4(P.merged + lane_i64(mine.rpt_off, 0), sm, L.rs >> 2, wave, wl);
-    wg_copy_vec4(P.merged + lane_i64(mine.nz_off, 0), sm + L.rs, L.entry_words >> 2, wave, wl);
+    wg_copy_vec4(merged_words(P) + lane_i64(mine.rpt_off, 0), sm, L.rs >> 2, wave, wl);
+    wg_copy_vec4(merged_words(P) + lane_i64(mine.nz_off, 0), sm + L.rs, L.entry_words >> 2, wave, wl);
     // ---- and the dense tile of every member that does not share an earlier member's
     int tile_off = L.tile_off;
     for (int j = 0; j < members; ++j) {
@@ -673,6 +688,11 @@ merge_sets_kernel(const SetRecord* __restrict__ sets, const int32_t* __restrict_
     int pos = partial[tid] - sum;
     int32_t* mr = merged + g.merged_rpt_off;
     int2* mc = reinterpret_cast<int2*>(merged + g.merged_nz_off);
+    // plain sets (one dense block): an ordinary CSR, columns and values in arrays of their own
+    int nnz_sum = 0;
+    for (int j = 0; j < members; ++j) nnz_sum += g.nnz[j];
+    int32_t* pc = merged + g.merged_nz_off;
+    float* pv = reinterpret_cast<float*>(pc + round_up(nnz_sum, 4));
     for (int r = r0; r < r1; ++r) {
         mr[r] = pos;
         for (int j = 0; j < members; ++j) {
@@ -682,8 +702,14 @@ merge_sets_kernel(const SetRecord* __restrict__ sets, const int32_t* __restrict_
             const float* va = values + g.nz_off[j];
             for (int p = a; p < b; ++p) {
                 const int c = ci[p];
-                mc[pos++] = make_int2(g.tile_row[j] + ((unsigned)c < (unsigned)g.k[j] ? c : 0),
-                                      __float_as_int(va[p]));
+                const int row = g.tile_row[j] + ((unsigned)c < (unsigned)g.k[j] ? c : 0);
+                if (g.plain) {
+                    pc[pos] = row;
+                    pv[pos] = va[p];
+                } else {
+                    mc[pos] = make_int2(row, __float_as_int(va[p]));
+                }
+                ++pos;
             }
         }
     }
@@ -720,7 +746,7 @@ __device__ __forceinline__ void run_slots(const LaunchParams& P, int* sm, int fi
 // registers, hence occupancy); the host launches it for schedules without such items.
 // HUBS = true adds the split-row path for hub rows (an option of the plan: it costs a
 // register-limited occupancy step and LDS for the reduction, which plain batches do not need).
-template <int VEC, bool SLICES, bool HUBS>
+template <int VEC, bool SLICES, bool HUBS, bool MERGED = false>
 __global__ void __launch_bounds__(kThreads) bspmm_kernel(const LaunchParams P)
 {
     extern __shared__ __align__(16) int sm[];
@@ -740,7 +766,7 @@ __global__ void __launch_bounds__(kThreads) bspmm_kernel(const LaunchParams P)
             if (it.nrows > 0) {
                 BSPMM_STAMP(t, 1);
                 if (it.staged) {
-                    stage_item<kThreads, VEC, HUBS>(P, it, sm, tid);
+                    stage_item<kThreads, VEC, HUBS, true, MERGED>(P, it, sm, tid);
                     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // direct-to-LDS loads landed
                     __syncthreads();
                     BSPMM_STAMP(t, 2);
@@ -1355,14 +1381,18 @@ __global__ void fill_i32_kernel(int32_t* p, int32_t v, int n)
 // ---------------------------------------------------------------------------------------
 using KernelFn = void (*)(const LaunchParams);
 
-static KernelFn kernel_variant(bool vec4, bool slices, bool hubs)
+static KernelFn kernel_variant(bool vec4, bool slices, bool hubs, bool merged = false)
 {
-    static const KernelFn table[8] = {
+    static const KernelFn table[16] = {
         bspmm_kernel<1, false, false>, bspmm_kernel<1, false, true>,
         bspmm_kernel<1, true, false>,  bspmm_kernel<1, true, true>,
         bspmm_kernel<4, false, false>, bspmm_kernel<4, false, true>,
-        bspmm_kernel<4, true, false>,  bspmm_kernel<4, true, true>};
-    return table[(vec4 ? 4 : 0) + (slices ? 2 : 0) + (hubs ? 1 : 0)];
+        bspmm_kernel<4, true, false>,  bspmm_kernel<4, true, true>,
+        bspmm_kernel<1, false, false, true>, bspmm_kernel<1, false, true, true>,
+        bspmm_kernel<1, true, false, true>,  bspmm_kernel<1, true, true, true>,
+        bspmm_kernel<4, false, false, true>, bspmm_kernel<4, false, true, true>,
+        bspmm_kernel<4, true, false, true>,  bspmm_kernel<4, true, true, true>};
+    return table[(merged ? 8 : 0) + (vec4 ? 4 : 0) + (slices ? 2 : 0) + (hubs ? 1 : 0)];
 }
 
 // Workgroups of bspmm_kernel the current device holds at once (0 if it cannot be asked).
@@ -1386,11 +1416,11 @@ int bspmm_max_resident_workgroups(int lds_bytes, bool slices, bool hubs)
 }
 
 hipError_t launch_bspmm(const LaunchParams& P, int grid, int lds_bytes, bool vec4, bool slices,
-                        bool hubs, hipStream_t stream)
+                        bool hubs, bool merged, hipStream_t stream)
 {
     if (grid <= 0) return hipSuccess;
-    hipLaunchKernelGGL(kernel_variant(vec4, slices, hubs), dim3(grid), dim3(kThreads), lds_bytes,
-                       stream, P);
+    hipLaunchKernelGGL(kernel_variant(vec4, slices, hubs, merged), dim3(grid), dim3(kThreads),
+                       lds_bytes, stream, P);
     return hipGetLastError();
 }
 

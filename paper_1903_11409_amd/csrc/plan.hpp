@@ -65,12 +65,12 @@ struct LaunchParams {
     int32_t pad;          // words added to every staged dense row
     // fused front of the graph-convolution layer (bspmm_run_gcn): `in` is then the layer input
     // X with n_front columns, and the dense tile is X_i . W + bias computed on chip
-    const float* w;       // n_front x F weights
+    const float* w;       // n_front x F weights; launches without a front: the merged CSR arrays
+                          // of the summed sets of this direction (32-bit words)
     const float* bias;    // F floats
     int64_t ld_w;
     int32_t n_front;
     int32_t accumulate;   // add to the output instead of overwriting it
-    const int32_t* merged; // merged CSR arrays of the summed sets of this direction
 #ifdef BSPMM_TRACE
     long long* trace;     // development builds only: 8 timestamps per workgroup
 #endif
@@ -185,7 +185,7 @@ BSPMM_HD inline StagedLayout staged_layout(int m, int k, int nnz, int fw, int pa
 // after the other in member order, and an entry names a row of the members' dense tiles laid
 // end to end (members that read the same dense block share one tile).  Per set, in the
 // workspace: round_up(m+1, 4) row pointers, then round_up(sum nnz, 2) entries of two words
-// (tile row, value).
+// (tile row, value); 2*round_up(sum nnz, 4) words are reserved for them.
 //
 // LDS layout of a fused task, in words:
 //   [0, rs)                            merged row pointers, rs = round_up(m+1, 4)
@@ -217,6 +217,10 @@ struct alignas(8) SetRecord {
     int32_t tile_row[kMaxMembers];  // first row of member j's dense tile in the concatenation
     int32_t members;
     int32_t m;
+    int32_t plain;                  // 1: the members read one dense block; the merged arrays are
+                                    // then an ordinary CSR (row pointers, round_up(sum nnz, 4)
+                                    // columns, as many values) that a plain item reads
+    int32_t pad_;
 };
 
 // Lanes that share one output row: enough 4-float vectors to cover the tile, a power of two.

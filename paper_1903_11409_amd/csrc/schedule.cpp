@@ -16,6 +16,7 @@
 #include "schedule.hpp"
 
 #include <algorithm>
+#include <cstdint>
 #include <map>
 #include <numeric>
 #include <utility>
@@ -338,15 +339,27 @@ std::vector<int> input_blocks(const DirOps& o)
     return block;
 }
 
+// `stand_in[g]` >= 0: the operations of group g all read one dense block, so their sum is the
+// product with the sum of their matrices: one operation (appended to `o` at that index, its CSR
+// the set's merged one) stands in for them and is drafted as a workgroup item like any other.
 void draft_all(const DirOps& o, int F, int vec, const std::vector<int>& cand, size_t first,
                const Knobs& kn, int cap, bool allow_small,
-               const Groups& outs, bool* fits, Sink& sink)
+               const Groups& outs, const std::vector<int>& stand_in, bool* fits, Sink& sink)
 {
     int nfused = 0;
     for (int g = 0; g < outs.size(); ++g) {
         if (outs.count(g) == 1) {
             const int i = *outs.begin(g);
             draft_op(o, i, F, vec, choose(o, i, F, vec, cand, first, kn, allow_small), kn, cap, sink);
+        } else if (stand_in[g] >= 0) {
+            const int v = stand_in[g];
+            Choice ch = {BSPMM_BIN_WORKGROUP, cand.back()};
+            for (size_t c = first; c < cand.size(); ++c)
+                if (fits_slot(o, v, cand[c], F, vec, kThreads, 0, kn)) {
+                    ch.tile = cand[c];
+                    break;
+                }
+            draft_op(o, v, F, vec, ch, kn, cap, sink);
         } else if (!draft_fused(o, outs.members(g), nfused++, F, vec, cand, first, kn, cap, sink)) {
             *fits = false;
         }
@@ -423,13 +436,56 @@ Knobs resolve_knobs(const bspmm_options* o)
     return k;
 }
 
-Schedule make_schedule(const DirOps& ops, int F, const Knobs& kn_in)
+Schedule make_schedule(const DirOps& ops_in, int F, const Knobs& kn_in)
 {
     Schedule s;
     Knobs kn = kn_in;
     if (!kn_in.target_wgs) kn.target_wgs = 4 * kn.compute_units;
     const int vec = (F % 4 == 0) ? 4 : 1;
     const std::vector<int> cand = tile_candidates(F, kn);
+    const Groups outs = output_groups(ops_in);
+
+    // Sets of summed operations that all read one dense block: an operation with the summed
+    // matrix stands in for the set when it fits a staged workgroup item at the narrowest tile.
+    DirOps ext;
+    std::vector<int> stand_in(outs.size(), -1);
+    {
+        bool copied = false;
+        for (int g = 0; g < outs.size(); ++g) {
+            const int cnt = outs.count(g);
+            if (cnt < 2 || cnt > kMaxMembers || kn.front > 0 || kn.force_bin == BSPMM_BIN_GENERIC) continue;
+            const int* mem = outs.begin(g);
+            bool one_input = true;
+            int64_t nnz = 0;
+            for (int j = 0; j < cnt; ++j) {
+                one_input = one_input && ops_in.in_off[mem[j]] == ops_in.in_off[mem[0]] &&
+                            ops_in.k[mem[j]] == ops_in.k[mem[0]];
+                nnz += ops_in.nnz[mem[j]];
+            }
+            if (!one_input || nnz > INT32_MAX) continue;
+            if (!copied) {
+                ext = ops_in;
+                copied = true;
+            }
+            const int v = ext.size();
+            ext.m.push_back(ops_in.m[mem[0]]);
+            ext.k.push_back(ops_in.k[mem[0]]);
+            ext.nnz.push_back((int32_t)nnz);
+            ext.rpt_off.push_back(0);       // the merged arrays are placed by the caller
+            ext.nz_off.push_back(0);
+            ext.in_off.push_back(ops_in.in_off[mem[0]]);
+            ext.out_off.push_back(ops_in.out_off[mem[0]]);
+            if (fits_slot(ext, v, cand.back(), F, vec, kThreads, 0, kn)) {
+                stand_in[g] = v;
+                s.merged_sets.push_back(outs.members(g));
+            } else {   // take it back: the set runs as a fused task (or does not fit at all)
+                ext.m.pop_back(), ext.k.pop_back(), ext.nnz.pop_back(), ext.rpt_off.pop_back();
+                ext.nz_off.pop_back(), ext.in_off.pop_back(), ext.out_off.pop_back();
+            }
+        }
+    }
+    s.first_stand_in = ops_in.size();
+    const DirOps& ops = s.merged_sets.empty() ? ops_in : ext;
 
     // widest batch-wide tile that still gives the launch enough workgroups
     std::vector<Draft> d;
@@ -440,7 +496,6 @@ Schedule make_schedule(const DirOps& ops, int F, const Knobs& kn_in)
     // workgroup staging it.  A forced bin overrides this.
     const int fixed_cap = kn.wg_passes > 0 ? kn.wg_passes : 0;
     bool allow_small = kn.force_bin >= 0 && kn.front == 0;
-    const Groups outs = output_groups(ops);
     size_t most_members = 1;
     for (int g = 0; g < outs.size(); ++g) most_members = std::max<size_t>(most_members, outs.count(g));
     if (most_members > (size_t)kMaxMembers) {
@@ -451,7 +506,7 @@ Schedule make_schedule(const DirOps& ops, int F, const Knobs& kn_in)
     int64_t counted_tile_words = 0;
     auto workgroups_of = [&](size_t first, int cap, bool small) {
         Sink counter;
-        draft_all(ops, F, vec, cand, first, kn, cap, small, outs, &fits, counter);
+        draft_all(ops, F, vec, cand, first, kn, cap, small, outs, stand_in, &fits, counter);
         counted_tile_words = counter.tile_words;
         return counter.workgroups();
     };
@@ -506,7 +561,7 @@ Schedule make_schedule(const DirOps& ops, int F, const Knobs& kn_in)
     }
     if (kn.front > 0) {   // every operation must hold its layer input on chip
         Sink probe;
-        draft_all(ops, F, vec, cand, chosen, kn, cap, allow_small, outs, &fits, probe);
+        draft_all(ops, F, vec, cand, chosen, kn, cap, allow_small, outs, stand_in, &fits, probe);
         if (probe.per_range[1] || probe.generic) {
             s.error = BSPMM_ETOOBIG;
             return s;
@@ -524,7 +579,7 @@ Schedule make_schedule(const DirOps& ops, int F, const Knobs& kn_in)
         keep.tiles_per_block = 1;
     }
     d.reserve((size_t)wgs * 4 + 16);
-    draft_all(ops, F, vec, cand, chosen, kn, cap, allow_small, outs, &fits, keep);
+    draft_all(ops, F, vec, cand, chosen, kn, cap, allow_small, outs, stand_in, &fits, keep);
 
     // group costs, for ordering and XCD placement
     int ngroups = 0;
@@ -659,8 +714,15 @@ Schedule make_schedule(const DirOps& ops, int F, const Knobs& kn_in)
         s.item_op.resize(s.items.size(), -1);      // empty items before this one
         s.items.push_back(to_item(ops, x));
         s.item_op.push_back(x.op);
-        s.view.push_back({x.op, x.bin, x.row0, x.nrows, x.f0, x.fw, wg, slot});
         s.items_in_bin[x.bin]++;
+        if (x.op < s.first_stand_in) {
+            s.view.push_back({x.op, x.bin, x.row0, x.nrows, x.f0, x.fw, wg, slot});
+        } else {   // a stand-in: the view lists the operations it stands for
+            s.items.back().staged |= 4;
+            const std::vector<int>& mem = s.merged_sets[x.op - s.first_stand_in];
+            for (size_t j = 0; j < mem.size(); ++j)
+                s.view.push_back({mem[j], x.bin, x.row0, x.nrows, x.f0, x.fw, wg, (int)j});
+        }
     };
 
     s.items.reserve(longest * kXcds + d.size() * (most_members > 1 ? most_members : 1) + 64);
@@ -680,7 +742,7 @@ Schedule make_schedule(const DirOps& ops, int F, const Knobs& kn_in)
     {
         std::vector<std::vector<int>>& fused_sets = s.fused_sets;
         for (int g = 0; g < outs.size(); ++g)
-            if (outs.count(g) > 1) fused_sets.push_back(outs.members(g));
+            if (outs.count(g) > 1 && stand_in[g] < 0) fused_sets.push_back(outs.members(g));
         s.fused_stride = (int)most_members;
         s.item_base[1] = (int)s.items.size();
         for (int idx : by_range[1]) {

@@ -51,6 +51,9 @@ struct Schedule {
     int fused_tasks = 0;
     std::vector<std::vector<int>> fused_sets;   // the sets of summed operations (members in order)
     std::vector<int> task_set;       // set of every fused task, in task order
+    std::vector<std::vector<int>> merged_sets;  // sets that one operation with the summed matrix
+                                     // stands in for; its index is first_stand_in + position
+    int first_stand_in = 0;          // == number of operations of the batch
     int error = 0;                   // BSPMM_E* when the batch cannot be scheduled
     int grid = 0;                    // number of tasks
     int launch_grid = 0;             // workgroups of the persistent launch
