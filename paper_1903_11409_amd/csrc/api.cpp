@@ -188,7 +188,7 @@ void describe_sets(bspmm_plan& p, int d)
             r.k[j] = o.k[mem[j]];
             size_t owner = j;
             for (size_t e = 0; e < j; ++e)
-                if (o.in_off[mem[e]] == o.in_off[mem[j]]) {
+                if (o.in_off[mem[e]] == o.in_off[mem[j]] && o.k[mem[e]] == o.k[mem[j]]) {
                     owner = e;
                     break;
                 }

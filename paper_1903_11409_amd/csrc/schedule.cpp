@@ -211,7 +211,8 @@ int64_t fused_words(const DirOps& o, const std::vector<int>& members, int fw)
     int64_t words = round_up(o.m[members[0]] + 1, 4) + 2 * ((nnz_sum + 1) / 2 * 2);
     for (size_t j = 0; j < members.size(); ++j) {
         bool owns = true;
-        for (size_t e = 0; e < j; ++e) owns = owns && o.in_off[members[e]] != o.in_off[members[j]];
+        for (size_t e = 0; e < j; ++e)   // (the same block: same first row AND same row count)
+            owns = owns && !(o.in_off[members[e]] == o.in_off[members[j]] && o.k[members[e]] == o.k[members[j]]);
         if (owns) words += (int64_t)o.k[members[j]] * round_up(fw, 4);
     }
     return words;
@@ -339,6 +340,17 @@ std::vector<int> input_blocks(const DirOps& o)
     return block;
 }
 
+// Narrowest tile a stand-in may take: the narrowest batch-wide candidate, or half of it when
+// only that fits (the members' tiles side by side are several times an operation's tile; 0 when
+// neither fits).
+int stand_in_tile(const DirOps& o, int v, int F, int vec, const std::vector<int>& cand, const Knobs& kn)
+{
+    if (fits_slot(o, v, cand.back(), F, vec, kThreads, 0, kn)) return cand.back();
+    const int half = cand.back() / 2;
+    if (half >= 16 && half % 4 == 0 && fits_slot(o, v, half, F, vec, kThreads, 0, kn)) return half;
+    return 0;
+}
+
 // `stand_in[g]` >= 0: the operations of group g all read one dense block, so their sum is the
 // product with the sum of their matrices: one operation (appended to `o` at that index, its CSR
 // the set's merged one) stands in for them and is drafted as a workgroup item like any other.
@@ -353,7 +365,7 @@ void draft_all(const DirOps& o, int F, int vec, const std::vector<int>& cand, si
             draft_op(o, i, F, vec, choose(o, i, F, vec, cand, first, kn, allow_small), kn, cap, sink);
         } else if (stand_in[g] >= 0) {
             const int v = stand_in[g];
-            Choice ch = {BSPMM_BIN_WORKGROUP, cand.back()};
+            Choice ch = {BSPMM_BIN_WORKGROUP, stand_in_tile(o, v, F, vec, cand, kn)};
             for (size_t c = first; c < cand.size(); ++c)
                 if (fits_slot(o, v, cand[c], F, vec, kThreads, 0, kn)) {
                     ch.tile = cand[c];
@@ -445,8 +457,9 @@ Schedule make_schedule(const DirOps& ops_in, int F, const Knobs& kn_in)
     const std::vector<int> cand = tile_candidates(F, kn);
     const Groups outs = output_groups(ops_in);
 
-    // Sets of summed operations that all read one dense block: an operation with the summed
-    // matrix stands in for the set when it fits a staged workgroup item at the narrowest tile.
+    // Sets of summed operations whose dense blocks are one block (the same one, or blocks that
+    // lie back to back in the packed input): an operation with the members' matrices side by
+    // side stands in for the set when it fits a staged workgroup item at the narrowest tile.
     DirOps ext;
     std::vector<int> stand_in(outs.size(), -1);
     {
@@ -455,27 +468,33 @@ Schedule make_schedule(const DirOps& ops_in, int F, const Knobs& kn_in)
             const int cnt = outs.count(g);
             if (cnt < 2 || cnt > kMaxMembers || kn.front > 0 || kn.force_bin == BSPMM_BIN_GENERIC) continue;
             const int* mem = outs.begin(g);
-            bool one_input = true;
-            int64_t nnz = 0;
+            // the members' dense blocks, each counted once in member order, must lie back to
+            // back: laid end to end they are then one block of the packed input as it stands
+            bool one_block = true;
+            int64_t nnz = 0, rows = 0;
             for (int j = 0; j < cnt; ++j) {
-                one_input = one_input && ops_in.in_off[mem[j]] == ops_in.in_off[mem[0]] &&
-                            ops_in.k[mem[j]] == ops_in.k[mem[0]];
                 nnz += ops_in.nnz[mem[j]];
+                bool seen = false;
+                for (int e = 0; e < j && !seen; ++e)
+                    seen = ops_in.in_off[mem[e]] == ops_in.in_off[mem[j]] && ops_in.k[mem[e]] == ops_in.k[mem[j]];
+                if (seen) continue;
+                one_block = one_block && ops_in.in_off[mem[j]] == ops_in.in_off[mem[0]] + rows;
+                rows += ops_in.k[mem[j]];
             }
-            if (!one_input || nnz > INT32_MAX) continue;
+            if (!one_block || nnz > INT32_MAX || rows > INT32_MAX) continue;
             if (!copied) {
                 ext = ops_in;
                 copied = true;
             }
             const int v = ext.size();
             ext.m.push_back(ops_in.m[mem[0]]);
-            ext.k.push_back(ops_in.k[mem[0]]);
+            ext.k.push_back((int32_t)rows);
             ext.nnz.push_back((int32_t)nnz);
             ext.rpt_off.push_back(0);       // the merged arrays are placed by the caller
             ext.nz_off.push_back(0);
             ext.in_off.push_back(ops_in.in_off[mem[0]]);
             ext.out_off.push_back(ops_in.out_off[mem[0]]);
-            if (fits_slot(ext, v, cand.back(), F, vec, kThreads, 0, kn)) {
+            if (stand_in_tile(ext, v, F, vec, cand, kn) > 0) {
                 stand_in[g] = v;
                 s.merged_sets.push_back(outs.members(g));
             } else {   // take it back: the set runs as a fused task (or does not fit at all)
@@ -754,7 +773,7 @@ Schedule make_schedule(const DirOps& ops_in, int F, const Knobs& kn_in)
                 WorkItem w = to_item(ops, y);
                 size_t owner = j;
                 for (size_t e = 0; e < j; ++e)
-                    if (ops.in_off[mem[e]] == ops.in_off[mem[j]]) {
+                    if (ops.in_off[mem[e]] == ops.in_off[mem[j]] && ops.k[mem[e]] == ops.k[mem[j]]) {
                         owner = e;
                         break;
                     }

@@ -93,7 +93,8 @@ def _random_csr(rng, m, n, z, sort_columns):
 def random_summed_case(seed, with_dY=True):
     """Groups of one to eight operations that are added into one output block (the layer's
     channel sum with BSPMM_ACCUMULATE): the members of a group share the row count; they read
-    one shared dense block (same column count) or a block each (any column counts)."""
+    one shared dense block (same column count) or a block each (any column counts; back to back
+    in the packed input, or with unused rows in between)."""
     rng = np.random.default_rng(0x5B77 + seed)
     groups = [1, 3, 12, 50][int(rng.integers(4))]
     ops, b_block_of_op, b_block_rows, c_block_of_op = [], [], [], []
@@ -101,6 +102,7 @@ def random_summed_case(seed, with_dY=True):
         m = int(rng.integers(1, 140)) if rng.random() < 0.9 else int(rng.integers(140, 600))
         members = int(rng.integers(1, 9))
         shared = bool(rng.integers(2))
+        spaced = bool(rng.integers(2))
         n_shared = m if rng.integers(2) else int(rng.integers(1, 140))
         if shared:
             b_block_rows.append(n_shared)
@@ -110,6 +112,8 @@ def random_summed_case(seed, with_dY=True):
             rpt, ci, va = _random_csr(rng, m, n, int(per_row * m), bool(rng.integers(2)))
             ops.append((m, n, rpt, ci, va))
             if not shared:
+                if spaced:      # a block nobody reads in between: the members' blocks are apart
+                    b_block_rows.append(int(rng.integers(1, 4)))
                 b_block_rows.append(n)
             b_block_of_op.append(len(b_block_rows) - 1)
             c_block_of_op.append(g)

@@ -218,17 +218,24 @@ def test_split_hub_rows(torch_cuda, oracle, maker):
 
 
 @pytest.mark.parametrize("F", [128, 32, 100, 63, 256])
-@pytest.mark.parametrize("own_inputs", [False, True])
+@pytest.mark.parametrize("own_inputs", [False, True, "apart"])
 def test_channel_sum_in_one_pass(torch_cuda, oracle, F, own_inputs):
     """BSPMM_ACCUMULATE: the channels of a graph name one output block and are summed in
     registers (forward), and their transposed products are summed into the shared input
-    gradient (transposed)."""
-    b = W.config3_multichannel(graphs=96, F=F, accumulate=True, own_inputs=own_inputs,
+    gradient (transposed).  Shared input: one operation over the summed matrix; an input per
+    channel, back to back: one operation over the matrices side by side; "apart" (the blocks of
+    channels 0 and 1 swapped, so they are not one block in channel order): fused tasks."""
+    b = W.config3_multichannel(graphs=96, F=F, accumulate=True, own_inputs=bool(own_inputs),
                                with_dY=True)
+    if own_inputs == "apart":
+        off = b.b_row_off.copy()
+        off[0::4], off[1::4] = b.b_row_off[1::4], b.b_row_off[0::4]
+        b = dataclasses.replace(b, b_row_off=off)
     opts = K.make_options(flags=K.ACCUMULATE)
     plan, got = _check_forward(torch_cuda, oracle, b, opts, what=f"channel sum F={F}")
     info = plan.info()
-    assert (info.fused_tasks[0] > 0) == own_inputs and info.transposed_supported == 1
+    assert info.transposed_supported == 1
+    assert own_inputs != "apart" or info.fused_tasks[0] > 0
     _check_transposed(torch_cuda, oracle, b, plan=plan, what=f"channel sum F={F}")
     _, again = _forward(torch_cuda, b, opts)
     assert np.array_equal(got, again)
@@ -243,7 +250,7 @@ def test_channel_sum_full_size_and_shared_input_gradient(torch_cuda, oracle):
     # is unchanged, and the transposed product now sums the 4 channels into the shared block
     c3 = W.config3_multichannel(with_dY=True)
     plan3, _ = _check_forward(torch_cuda, oracle, c3, opts)
-    assert plan3.info().fused_tasks[0] == 0 and plan3.info().fused_tasks[1] > 0
+    assert plan3.info().fused_tasks[0] == 0
     _check_transposed(torch_cuda, oracle, c3, plan=plan3)
     # unit entries: the channel matrices partition the edges, the sum is the neighbour sum
     u = W.config3_multichannel(graphs=64, F=64, accumulate=True, normalise=False)

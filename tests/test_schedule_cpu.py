@@ -5,6 +5,8 @@ import ctypes
 import os
 import re
 
+import dataclasses
+
 import numpy as np
 import pytest
 
@@ -256,12 +258,19 @@ def test_empty_batch_and_workspace_size():
 def test_summed_operations_share_one_task():
     """With BSPMM_ACCUMULATE the channels of a graph (same output block) become members of
     one task per (tile, row range); every member still covers its rows exactly once.  Channels
-    with a dense input each run as fused tasks; channels that share their input are the
-    product with the sum of their matrices, an ordinary workgroup item."""
-    for own in (False, True):
+    whose dense inputs are one block of the packed input (the same block, or blocks lying back
+    to back in channel order) are the product with their matrices side by side, an ordinary
+    workgroup item; otherwise (here: the blocks of channels 0 and 1 swapped) a fused task."""
+    fused = {}
+    for own, swapped in ((False, False), (True, False), (True, True)):
         b = W.config3_multichannel(graphs=48, accumulate=True, own_inputs=own)
+        if swapped:
+            off = b.b_row_off.copy()
+            off[0::4], off[1::4] = b.b_row_off[1::4], b.b_row_off[0::4]
+            b = dataclasses.replace(b, b_row_off=off)
         info, items = _check_schedule(b, b.F, flags=K.ACCUMULATE)
-        assert (info.fused_tasks[0] > 0) == own and info.transposed_supported == 1
+        fused[(own, swapped)] = info.fused_tasks[0]
+        assert info.transposed_supported == 1
         ch = b.meta["channels"]
         by_task = {}
         for it in items:
@@ -273,12 +282,15 @@ def test_summed_operations_share_one_task():
             assert len({(m.row0, m.nrows, m.f0, m.fw) for m in members}) == 1
         _check_schedule(b, b.F, transposed=True, flags=K.ACCUMULATE)
         assert info.effective_bytes[0] == W.effective_bytes(b)
+    # (with a block per channel the largest graphs do not fit a plain item and stay fused tasks)
+    assert fused[(False, False)] == 0 and fused[(True, True)] > 4 * fused[(True, False)]
     # shared inputs, separate outputs: the transposed product sums into the shared input block
+    # (the channels' output blocks lie back to back: no fused task in that direction either)
     b = W.config3_multichannel(graphs=16)
     info, _ = _check_schedule(b, b.F, flags=K.ACCUMULATE)
     assert info.fused_tasks[0] == 0 and info.transposed_supported == 1
-    info_t, _ = _check_schedule(b, b.F, transposed=True, flags=K.ACCUMULATE)
-    assert info_t.fused_tasks[1] > 0
+    info_t, items_t = _check_schedule(b, b.F, transposed=True, flags=K.ACCUMULATE)
+    assert info_t.fused_tasks[1] == 0 and len({(it.workgroup, it.slot) for it in items_t}) == len(items_t)
 
 
 def test_summed_operations_need_the_flag_and_must_fit():
