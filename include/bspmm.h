@@ -81,7 +81,10 @@ extern "C" {
                                       bspmm_run and to B blocks (input gradients) in
                                       bspmm_run_transposed.  The first run of a direction also
                                       enqueues a kernel that merges the CSR arrays of every such
-                                      set into the workspace (once per plan)                     */
+                                      set into the workspace (once per plan).  Fastest when the
+                                      dense blocks the members of a set read are one block of the
+                                      packed input: the same block, or blocks that follow each
+                                      other in member order without a gap                        */
 #define BSPMM_COO_DIRECT       32u  /* bspmm_create_coo only: no conversion to CSR.  Every run is one
                                       launch of the kernel of Fig. 3 / Fig. 5(a,b): a group of lanes
                                       per stored entry, products added with LDS floating-point
