@@ -518,3 +518,61 @@ def test_large_batch_of_small_graphs(torch_cuda, oracle):
     info = plan.info()
     assert info.items[0] >= 16384 and info.workgroups[0] < info.items[0]
     _check_transposed(torch_cuda, oracle, b, plan=plan, what="16384 graphs")
+
+
+def test_runs_replayed_from_a_hip_graph(torch_cuda, oracle):
+    """Forward, transposed and channel-sum runs captured in one HIP graph (the one-off device
+    builds done at plan creation with BSPMM_BUILD_TRANSPOSE, so that the capture holds the
+    products only) and replayed with new operands, eager work and synchronisation in between:
+    every replay equals the eager result bit for bit and meets the oracle."""
+    torch = torch_cuda
+    b = W.config5_skewed(graphs=64, F=64, asymmetric=True)
+    c = W.config3_multichannel(graphs=48, F=64, accumulate=True, own_inputs=True, with_dY=True)
+    pb = K.Plan(b, options=K.make_options(flags=K.BUILD_TRANSPOSE))
+    pc = K.Plan(c, options=K.make_options(flags=K.BUILD_TRANSPOSE | K.ACCUMULATE))
+    torch.cuda.synchronize()
+    Bb = torch.zeros((b.n_b_rows, 64), device="cuda")
+    Cb = torch.empty((b.n_c_rows, 64), device="cuda")
+    Yb = torch.zeros((b.n_c_rows, 64), device="cuda")
+    Gb = torch.empty((b.n_b_rows, 64), device="cuda")
+    Bc = torch.zeros((c.n_b_rows, 64), device="cuda")
+    Cc = torch.empty((c.n_c_rows, 64), device="cuda")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(g, stream=side):
+            s = torch.cuda.current_stream().cuda_stream
+            pb.run(Bb, Cb, stream=s)
+            pb.run_transposed(Yb, Gb, stream=s)
+            pc.run(Bc, Cc, stream=s)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(31)
+    for rep in range(3):
+        nb = rng.uniform(-1, 1, size=b.B.shape).astype(np.float32)
+        ny = rng.standard_normal(size=b.dY.shape).astype(np.float32)
+        nc = rng.uniform(-1, 1, size=c.B.shape).astype(np.float32)
+        Bb.copy_(torch.from_numpy(nb).cuda())
+        Yb.copy_(torch.from_numpy(ny).cuda())
+        Bc.copy_(torch.from_numpy(nc).cuda())
+        for t in (Cb, Gb, Cc):
+            t.fill_(SENTINEL)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        got = [t.cpu().numpy() for t in (Cb, Gb, Cc)]
+        eager = [torch.empty_like(t) for t in (Cb, Gb, Cc)]      # eager work between replays
+        pb.run(Bb, eager[0])
+        pb.run_transposed(Yb, eager[1])
+        pc.run(Bc, eager[2])
+        torch.cuda.synchronize()
+        for a, e in zip(got, eager):
+            assert np.array_equal(a, e.cpu().numpy()), f"replay {rep} differs from the eager run"
+        b2 = dataclasses.replace(b, B=nb, dY=ny)
+        ref, S = oracle.forward_batch(b2)
+        _assert_close(got[0], ref, S, _owned_rows(b.c_row_off, b.rows, b.n_c_rows), f"replay {rep}")
+        ref, S = oracle.transposed_batch(b2)
+        _assert_close(got[1], ref, S, _owned_rows(b.b_row_off, b.cols, b.n_b_rows), f"replay {rep} transposed")
+        ref, S = oracle.forward_batch(dataclasses.replace(c, B=nc))
+        _assert_close(got[2], ref, S, _owned_rows(c.c_row_off, c.rows, c.n_c_rows), f"replay {rep} channel sum")
