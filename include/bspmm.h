@@ -174,8 +174,9 @@ typedef struct bspmm_options {
                                   and at least 16 rows of X_i beside the operation (lds_bytes
                                   then defaults to 80 KiB, 160 KiB if that is too little); needs
                                   F % 16 == 0 and n_X % 4 == 0
-                                  (EINVAL), not combined with BSPMM_ACCUMULATE,
-                                  BSPMM_SPLIT_HUB_ROWS or lds_pad (EINVAL); ETOOBIG when an
+                                  (EINVAL), not combined with
+                                  BSPMM_SPLIT_HUB_ROWS or lds_pad (EINVAL); with
+                                  BSPMM_ACCUMULATE see bspmm_run_gcn; ETOOBIG when an
                                   operation does not fit at any tile width                      */
     int32_t  reserved_;        /* 0 */
 } bspmm_options;
@@ -257,6 +258,14 @@ int bspmm_run(bspmm_plan* plan, const float* B, float* C, int64_t ldb, int64_t l
  * (v_mfma_f32_16x16x4_f32) from LDS to LDS; B_i never leaves the chip.  X, W, Y must be
  * 16-byte aligned with ldx, ldw, ldy multiples of 4 (EINVAL).  ESTATE for plans created
  * without front_features.
+ *
+ * The whole layer in one launch: a plan created with front_features AND BSPMM_ACCUMULATE, in
+ * which every operation is one of M channels of a graph - the M channel operations of a graph
+ * read the same X block and name the same output block, M the same for all graphs (EINVAL
+ * otherwise) - computes  Y_i = sum_ch A_i^ch . (X_i . W[ch] + bias[ch])  (Fig. 7 including the
+ * ElementWiseAdd) with X_i staged once for all channels.  W is then the M weight matrices one
+ * under the other (M * n_X rows, channel ch at row ch * n_X) and bias M rows of F floats; the
+ * channels of a graph are taken in the order of their operations.
  */
 int bspmm_run_gcn(bspmm_plan* plan, const float* X, int64_t ldx, const float* W, int64_t ldw,
                   const float* bias, float* Y, int64_t ldy, int32_t accumulate, void* stream);

@@ -17,7 +17,7 @@ namespace bspmm {
 hipError_t launch_bspmm(const LaunchParams& P, int grid, int lds_bytes, bool vec4, bool slices,
                         bool hubs, bool merged, hipStream_t stream);
 hipError_t launch_bspmm_gcn(const LaunchParams& P, int grid, int lds_bytes, bool accumulate,
-                            hipStream_t stream);
+                            bool sets, hipStream_t stream);
 hipError_t launch_build_transpose(const OpRecord* ops, int batch, int lds_bytes,
                                   const int32_t* rpt, const int32_t* colids,
                                   const float* values, int32_t* rpt_t, int32_t* colids_t,
@@ -92,6 +92,7 @@ struct bspmm_plan {
     std::vector<SetRecord> set_records[2];   // summed sets of the forward / transposed schedule
     int64_t merged_words[2] = {0, 0};
     bool merged_built[2] = {false, false};
+    int front_channels = 1;   // fused front with BSPMM_ACCUMULATE: channels per output block
     int64_t effective_bytes[2] = {0, 0};
     int64_t flops = 0;
     bool reads_dense = false;   // some operation has rows and columns: the runs read the dense input
@@ -192,7 +193,7 @@ void describe_sets(bspmm_plan& p, int d)
                     owner = e;
                     break;
                 }
-            if (owner == j) {
+            if (owner == j || (plain && d == 0 && p.knobs.front > 0)) {   // (front: a tile per channel)
                 r.tile_row[j] = rows;
                 rows += o.k[mem[j]];
             } else {
@@ -299,10 +300,23 @@ int plan_host(bspmm_plan& p, const bspmm_batch* b, int32_t F, const Knobs& kn)
     if (ck == 2 || (ck == 1 && !kn.accumulate)) return BSPMM_EOVERLAP;
     p.transposed_supported = bk == 0 || (bk == 1 && kn.accumulate);
 
-    if (kn.front > 0 && (F % 16 != 0 || kn.front % 4 != 0 || kn.accumulate || kn.hubs || kn.pad != 0))
+    if (kn.front > 0 && (F % 16 != 0 || kn.front % 4 != 0 || kn.hubs || kn.pad != 0))
         return BSPMM_EINVAL;
     p.sched[0] = make_schedule(f, F, kn);
     if (p.sched[0].error) return p.sched[0].error;
+    if (kn.front > 0 && kn.accumulate) {
+        // the whole layer in one launch: every operation must be a channel of a set, all sets
+        // with the same number of channels, the channels of a set sharing the layer input
+        const Schedule& sc = p.sched[0];
+        size_t in_sets = 0, with_rows = 0;
+        for (const auto& mem : sc.merged_sets) {
+            if (mem.size() != sc.merged_sets[0].size()) return BSPMM_EINVAL;
+            in_sets += mem.size();
+        }
+        for (int i = 0; i < n; ++i) with_rows += b->rows[i] > 0;
+        if (in_sets != with_rows) return sc.fused_tasks > 0 ? BSPMM_ETOOBIG : BSPMM_EINVAL;
+        p.front_channels = sc.merged_sets.empty() ? 1 : (int)sc.merged_sets[0].size();
+    }
     // Square operations whose input and output blocks sit at the same rows (adjacency matrices
     // of a GCN batch) have the same schedule in both directions: only the location of the
     // CSR arrays differs.
@@ -801,9 +815,15 @@ int run_gcn(bspmm_plan* p, const float* X, int64_t ldx, const float* W, int64_t 
     if (!X || !W || !bias || !Y || ldx < nx || ldw < p->F || ldy < p->F) return BSPMM_EINVAL;
     if (ldx % 4 || ldw % 4 || ldy % 4 || misaligned(X) || misaligned(W) || misaligned(Y))
         return BSPMM_EINVAL;
+    const bool sets = !sc.merged_sets.empty();
+    if (sets) {
+        const int mrc = enqueue_merge(p, 0, s);
+        if (mrc != BSPMM_OK) return mrc;
+    }
     LaunchParams P;
     P.items = reinterpret_cast<const WorkItem*>(p->ws + p->lay.items[0]);
-    P.rpt = p->rpt;
+    // (channel sets: every item reads the merged CSR of its set; P.rpt carries its base)
+    P.rpt = sets ? reinterpret_cast<const int32_t*>(p->ws + p->lay.merged[0]) : p->rpt;
     P.colids = p->colids;
     P.values = p->values;
     P.in = X;
@@ -815,7 +835,7 @@ int run_gcn(bspmm_plan* p, const float* X, int64_t ldx, const float* W, int64_t 
         P.item_base[r] = sc.item_base[r];
     }
     P.n_tasks = sc.grid;
-    P.fused_stride = sc.fused_stride;
+    P.fused_stride = p->F;                 // this launch: floats between the channels' bias rows
     P.lds_floats = sc.front_lds_words;     // what the launch gets: decides the rows of X_i per pass
     P.pad = 0;
     P.w = W;
@@ -826,7 +846,7 @@ int run_gcn(bspmm_plan* p, const float* X, int64_t ldx, const float* W, int64_t 
 #ifdef BSPMM_TRACE
     P.trace = g_trace;
 #endif
-    hipError_t e = launch_bspmm_gcn(P, sc.grid, sc.front_lds_words * 4, accumulate != 0, s);
+    hipError_t e = launch_bspmm_gcn(P, sc.grid, sc.front_lds_words * 4, accumulate != 0, sets, s);
     return e == hipSuccess ? BSPMM_OK : hip_fail(e);
 }
 

@@ -1077,7 +1077,13 @@ __device__ __forceinline__ void stage_tile4(float* dst, const float* __restrict_
     }
 }
 
-template <bool ACC>
+// SETS = true: every item stands in for a set of M channel operations that share the layer
+// input X_i and are summed into one output block (the whole layer of Fig. 7 in one launch):
+// the dense tile is [X_i W[0] + bias[0]; ...; X_i W[M-1] + bias[M-1]] (M x kx rows), the CSR is
+// the set's merged one, whose entries of channel c name rows c*kx ... of that tile; W is the M
+// weight matrices one under the other (M*nx rows), bias M rows of P.fused_stride floats apart, and
+// P.rpt is the base of the merged arrays.
+template <bool ACC, bool SETS>
 __global__ void __launch_bounds__(kThreads) bspmm_gcn_kernel(const LaunchParams P)
 {
     extern __shared__ __align__(16) int sm[];
@@ -1089,27 +1095,32 @@ __global__ void __launch_bounds__(kThreads) bspmm_gcn_kernel(const LaunchParams 
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), wl = tid & 63;
     const int col = wl & 15, g = wl >> 4;
     const int nb_count = it.fw >> 4;
+    const int M = SETS ? max(1, (it.staged >> 8) & 0xff) : 1;   // channels
+    const int kx = SETS ? it.k / M : it.k;                       // rows of X_i
 
     const StagedLayout L = staged_layout(it.m, it.k, it.nnz, it.fw, 0, false);
     float* bt = reinterpret_cast<float*>(sm + L.b_off);      // dense tile k x fw, made below
-    float* ws = bt + it.k * it.fw;                            // weight tile, nx x fw
-    float* bias_s = ws + nx * it.fw;                          // bias tile, fw
-    float* xs = bias_s + it.fw;                               // rows of X_i, R x nx
+    float* ws = bt + it.k * it.fw;                            // weight tiles, M x (nx x fw)
+    float* bias_s = ws + M * nx * it.fw;                      // bias tiles, M x fw
+    float* xs = bias_s + M * it.fw;                           // rows of X_i, R x nx
     // X_i is taken R rows at a time: all of them when the rest of the LDS holds them, else a
     // multiple of 16 (a 16 x 16 block needs 16 rows of X_i and all of their columns).  The
     // host has made sure of 16.
     const int x_room = (P.lds_floats - (int)(xs - reinterpret_cast<float*>(sm))) / nx;
-    const int R = it.k <= x_room ? it.k : x_room & ~15;
+    const int R = kx <= x_room ? kx : x_room & ~15;
     const int xvec = nx >> 2;
     const int swz = (xvec & (xvec - 1)) == 0 ? min(xvec, 16) - 1 : 0;
     const float* xg = P.in + it.in_row_off * P.ld_in;
 
     // dense tile rows r0 .. r0+rows on the matrix cores, LDS -> LDS
     auto dense_rows = [&](int r0, int rows) {
-        const int blocks = ((rows + 15) >> 4) * nb_count;
+        const int per_channel = ((rows + 15) >> 4) * nb_count;
+        const int blocks = per_channel * M;
         for (int blk = wave; blk < blocks; blk += kThreads / 64) {
-            const int mb = blk / nb_count, nb = blk - mb * nb_count;
-            const float bv = bias_s[16 * nb + col];
+            const int c = SETS ? blk / per_channel : 0;
+            const int rem = blk - c * per_channel;
+            const int mb = rem / nb_count, nb = rem - mb * nb_count;
+            const float bv = bias_s[c * it.fw + 16 * nb + col];
             // four independent accumulators (one per k of a lane's four): a chain of
             // dependent matrix instructions would run at their latency, not their rate
             mfma4 acc = {bv, bv, bv, bv};
@@ -1117,7 +1128,7 @@ __global__ void __launch_bounds__(kThreads) bspmm_gcn_kernel(const LaunchParams 
             const int arow = min(16 * mb + col, rows - 1);     // rows past the end repeat the last
             const float* xrow = xs + arow * nx;
             const int xs_swz = arow & swz;
-            const float* wcol = ws + 4 * g * it.fw + 16 * nb + col;
+            const float* wcol = ws + (c * nx + 4 * g) * it.fw + 16 * nb + col;
             // Sixteen k per trip (four per lane group, one matrix instruction each).  The
             // operands of the next trip are read from LDS before the instructions of this one
             // are issued: read latency then hides behind the matrix pipeline instead of
@@ -1162,26 +1173,36 @@ __global__ void __launch_bounds__(kThreads) bspmm_gcn_kernel(const LaunchParams 
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const int row = 16 * mb + 4 * g + i;
-                if (row < rows) bt[(r0 + row) * it.fw + 16 * nb + col] = acc[i];
+                if (row < rows) bt[(c * kx + r0 + row) * it.fw + 16 * nb + col] = acc[i];
             }
         }
     };
 
     // ---- first pass: everything read from memory is requested at once (the first rows of
     // X_i, the weights, the bias, A_i)
-    stage_tile4(xs, xg, P.ld_in, min(R, it.k), xvec, tid, swz);
-    stage_tile4(ws, P.w + it.f0, P.ld_w, nx, it.fw >> 2, tid);
+    stage_tile4(xs, xg, P.ld_in, min(R, kx), xvec, tid, swz);
+    stage_tile4(ws, P.w + it.f0, P.ld_w, M * nx, it.fw >> 2, tid);
     float bias_v = 0.f;
     if (tid < it.fw) bias_v = P.bias[it.f0 + tid];
-    stage_item<kThreads, 4, false, false>(P, it, sm, tid);    // A_i only
+    if (SETS) {
+        LaunchParams Q = P;                                   // CSR from the merged arrays
+        Q.w = reinterpret_cast<const float*>(P.rpt);
+        stage_item<kThreads, 4, false, false, true>(Q, it, sm, tid);
+        for (int e = tid + it.fw; e < M * it.fw; e += kThreads) {   // the other channels' bias
+            const int c = e / it.fw;
+            bias_s[e] = P.bias[(int64_t)c * P.fused_stride + it.f0 + (e - c * it.fw)];
+        }
+    } else {
+        stage_item<kThreads, 4, false, false>(P, it, sm, tid);    // A_i only
+    }
     if (tid < it.fw) bias_s[tid] = bias_v;
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");          // direct-to-LDS loads landed
     __syncthreads();
-    dense_rows(0, min(R, it.k));
+    dense_rows(0, min(R, kx));
     __syncthreads();         // the rows of X_i may be replaced; after the last pass: tile complete
     // ---- operations with more rows than fit: further passes
-    for (int r0 = R; r0 < it.k; r0 += R) {
-        const int rows = min(R, it.k - r0);
+    for (int r0 = R; r0 < kx; r0 += R) {
+        const int rows = min(R, kx - r0);
         stage_tile4(xs, xg + (int64_t)r0 * P.ld_in, P.ld_in, rows, xvec, tid, swz);
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
@@ -1425,13 +1446,14 @@ hipError_t launch_bspmm(const LaunchParams& P, int grid, int lds_bytes, bool vec
 }
 
 hipError_t launch_bspmm_gcn(const LaunchParams& P, int grid, int lds_bytes, bool accumulate,
-                            hipStream_t stream)
+                            bool sets, hipStream_t stream)
 {
     if (grid <= 0) return hipSuccess;
-    if (accumulate)
-        hipLaunchKernelGGL(bspmm_gcn_kernel<true>, dim3(grid), dim3(kThreads), lds_bytes, stream, P);
-    else
-        hipLaunchKernelGGL(bspmm_gcn_kernel<false>, dim3(grid), dim3(kThreads), lds_bytes, stream, P);
+    using Fn = void (*)(const LaunchParams);
+    static const Fn table[4] = {bspmm_gcn_kernel<false, false>, bspmm_gcn_kernel<true, false>,
+                                bspmm_gcn_kernel<false, true>, bspmm_gcn_kernel<true, true>};
+    hipLaunchKernelGGL(table[(sets ? 2 : 0) + (accumulate ? 1 : 0)], dim3(grid), dim3(kThreads),
+                       lds_bytes, stream, P);
     return hipGetLastError();
 }
 

@@ -60,7 +60,8 @@ struct LaunchParams {
     int32_t wg_end[kRanges];
     int32_t item_base[kRanges];
     int32_t n_tasks;      // == wg_end[kRanges-1]
-    int32_t fused_stride; // item slots per fused task
+    int32_t fused_stride; // item slots per fused task (fused-front launches: floats between the
+                          // bias rows of the channels)
     int32_t lds_floats;   // LDS per workgroup, in 4-byte words
     int32_t pad;          // words added to every staged dense row
     // fused front of the graph-convolution layer (bspmm_run_gcn): `in` is then the layer input

@@ -89,8 +89,9 @@ bool fits_slot(const DirOps& o, int i, int tile, int F, int vec, int lanes, int 
     const int64_t head = (int64_t)round_up(o.m[i] + 1, 2) + 2 * (int64_t)o.nnz[i];
     int64_t need = (head + 3) / 4 * 4 + (int64_t)o.k[i] * (round_up(fw, 4) + kn.pad);
     if (kn.hubs && lanes == kThreads) need += hub_words(o.nnz[i] / kHubMin, fw);   // as staged_layout()
-    if (kn.front > 0)   // the weight tile, the bias tile and at least 16 rows of X_i ride along
-        need += 16 * (int64_t)kn.front + (int64_t)kn.front * round_up(fw, 4) + round_up(fw, 4);
+    if (kn.front > 0)   // a weight tile and a bias tile per channel and at least 16 rows of X_i ride along
+        need += 16 * (int64_t)kn.front +
+                o.channels(i) * ((int64_t)kn.front * round_up(fw, 4) + round_up(fw, 4));
     return need <= (int64_t)kn.lds_words * lanes / kThreads;
 }
 
@@ -466,7 +467,7 @@ Schedule make_schedule(const DirOps& ops_in, int F, const Knobs& kn_in)
         bool copied = false;
         for (int g = 0; g < outs.size(); ++g) {
             const int cnt = outs.count(g);
-            if (cnt < 2 || cnt > kMaxMembers || kn.front > 0 || kn.force_bin == BSPMM_BIN_GENERIC) continue;
+            if (cnt < 2 || cnt > kMaxMembers || kn.force_bin == BSPMM_BIN_GENERIC) continue;
             const int* mem = outs.begin(g);
             // the members' dense blocks, each counted once in member order, must lie back to
             // back: laid end to end they are then one block of the packed input as it stands
@@ -477,6 +478,14 @@ Schedule make_schedule(const DirOps& ops_in, int F, const Knobs& kn_in)
                 bool seen = false;
                 for (int e = 0; e < j && !seen; ++e)
                     seen = ops_in.in_off[mem[e]] == ops_in.in_off[mem[j]] && ops_in.k[mem[e]] == ops_in.k[mem[j]];
+                if (kn.front > 0) {
+                    // fused front: the channels of a set share the layer input X_i, and each
+                    // makes a dense tile of its own from it (X_i W[ch] + bias[ch]) on chip:
+                    // the tiles are side by side by construction
+                    one_block = one_block && (j == 0 || seen);
+                    rows += ops_in.k[mem[j]];
+                    continue;
+                }
                 if (seen) continue;
                 one_block = one_block && ops_in.in_off[mem[j]] == ops_in.in_off[mem[0]] + rows;
                 rows += ops_in.k[mem[j]];
@@ -494,12 +503,17 @@ Schedule make_schedule(const DirOps& ops_in, int F, const Knobs& kn_in)
             ext.nz_off.push_back(0);
             ext.in_off.push_back(ops_in.in_off[mem[0]]);
             ext.out_off.push_back(ops_in.out_off[mem[0]]);
+            if (kn.front > 0) {
+                ext.chan.resize(ext.size(), 1);
+                ext.chan.back() = cnt;
+            }
             if (stand_in_tile(ext, v, F, vec, cand, kn) > 0) {
                 stand_in[g] = v;
                 s.merged_sets.push_back(outs.members(g));
             } else {   // take it back: the set runs as a fused task (or does not fit at all)
                 ext.m.pop_back(), ext.k.pop_back(), ext.nnz.pop_back(), ext.rpt_off.pop_back();
                 ext.nz_off.pop_back(), ext.in_off.pop_back(), ext.out_off.pop_back();
+                if (!ext.chan.empty()) ext.chan.pop_back();
             }
         }
     }
@@ -737,7 +751,7 @@ Schedule make_schedule(const DirOps& ops_in, int F, const Knobs& kn_in)
         if (x.op < s.first_stand_in) {
             s.view.push_back({x.op, x.bin, x.row0, x.nrows, x.f0, x.fw, wg, slot});
         } else {   // a stand-in: the view lists the operations it stands for
-            s.items.back().staged |= 4;
+            s.items.back().staged |= 4 | (kn.front > 0 ? ops.channels(x.op) << 8 : 0);
             const std::vector<int>& mem = s.merged_sets[x.op - s.first_stand_in];
             for (size_t j = 0; j < mem.size(); ++j)
                 s.view.push_back({mem[j], x.bin, x.row0, x.nrows, x.f0, x.fw, wg, (int)j});
@@ -809,8 +823,9 @@ Schedule make_schedule(const DirOps& ops_in, int F, const Knobs& kn_in)
         for (const WorkItem& w : s.items) {
             if (w.nrows <= 0) continue;
             const StagedLayout L = staged_layout(w.m, w.k, w.nnz, w.fw, 0, false);
-            most = std::max<int64_t>(most, (int64_t)L.total + (int64_t)w.k * kn.front +
-                                               (int64_t)kn.front * w.fw + w.fw);
+            const int ch = std::max(1, (w.staged >> 8) & 0xff);     // channels of a stand-in
+            most = std::max<int64_t>(most, (int64_t)L.total + (int64_t)(w.k / ch) * kn.front +
+                                               ch * ((int64_t)kn.front * w.fw + w.fw));
         }
         s.front_lds_words = (int)std::min<int64_t>(kn.lds_words, round_up((int)most, 64));
     }

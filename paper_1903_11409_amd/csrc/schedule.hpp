@@ -14,6 +14,9 @@ namespace bspmm {
 struct DirOps {
     std::vector<int32_t> m, k, nnz;
     std::vector<int64_t> rpt_off, nz_off, in_off, out_off;
+    std::vector<int32_t> chan;   // empty, or per operation: channels of the fused front it carries
+                                 // (an operation standing in for a set of summed channels)
+    int channels(int i) const { return chan.empty() ? 1 : chan[i]; }
     int size() const { return (int)m.size(); }
 };
 

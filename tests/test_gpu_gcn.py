@@ -211,3 +211,48 @@ def test_random_batches_and_knobs_through_the_front(torch_cuda, oracle, block):
         except K.BspmmError as e:
             assert e.code == K.ETOOBIG, f"seed {seed}: {e}"
     assert ran >= 4
+
+
+def _channel(b, c, chans):
+    """Sub-batch of channel c of a multichannel batch (operation index = graph * chans + c)."""
+    import dataclasses
+    sel = slice(c, None, chans)
+    return dataclasses.replace(b, rows=b.rows[sel], cols=b.cols[sel], nnz=b.nnz[sel],
+                               rpt_off=b.rpt_off[sel], nz_off=b.nz_off[sel],
+                               b_row_off=b.b_row_off[sel], c_row_off=b.c_row_off[sel])
+
+
+@pytest.mark.parametrize("graphs,F,n_x,chans", [(64, 128, 64, 4), (48, 64, 32, 4), (40, 48, 20, 3),
+                                                 (24, 256, 128, 2), (128, 128, 64, 4)])
+def test_whole_layer_in_one_launch(torch_cuda, oracle, graphs, F, n_x, chans):
+    """Y = sum_ch A_ch (X W_ch + bias_ch) (Fig. 7 with the ElementWiseAdd over the channels) in
+    ONE launch: a plan with front_features and BSPMM_ACCUMULATE whose channel operations share
+    the layer input and the output block; W is the channels' weight matrices one under the
+    other, bias one row per channel."""
+    torch = torch_cuda
+    b = W.config3_multichannel(seed=500 + graphs, graphs=graphs, F=F, channels=chans, accumulate=True)
+    X, Ws, biases = _layer(b, n_x, 11, channels=chans)
+    print(f"layer case: graphs={graphs} F={F} n_X={n_x} channels={chans}", flush=True)
+    plan = K.Plan(b, options=K.make_options(flags=K.ACCUMULATE, front_features=n_x))
+    info = plan.info()
+    assert info.fused_tasks[0] == 0
+    Xd = torch.from_numpy(X).cuda()
+    Wd = torch.from_numpy(np.concatenate(Ws, axis=0)).cuda()
+    bd = torch.from_numpy(np.stack(biases)).cuda()
+    Yd = torch.full((b.n_c_rows, F), SENTINEL, dtype=torch.float32, device="cuda")
+    plan.run_gcn(Xd, Wd, bd, Yd)
+    torch.cuda.synchronize()
+    Y = T = None
+    dmax = 0
+    for c in range(chans):
+        bc = _channel(b, c, chans)
+        Y, T = oracle.gcn_channel(bc, X, Ws[c], biases[c], Y, T)
+        dmax += max(int(np.diff(bc.op_csr(i)[0]).max()) if int(bc.rows[i]) else 0 for i in range(bc.batch))
+    tol = max(1e-5, chans * (n_x + 2) * 2.0 ** -23 + dmax * 2.0 ** -23)
+    # rows no channel writes keep the oracle's NaN marker only where no operation owns them
+    owned = _owned(b.c_row_off, b.rows, b.n_c_rows)
+    _assert_close(Yd.cpu().numpy(), Y, T, owned, tol, "whole layer")
+    again = torch.empty_like(Yd)
+    plan.run_gcn(Xd, Wd, bd, again)
+    torch.cuda.synchronize()
+    assert torch.equal(Yd, again)

@@ -605,3 +605,28 @@ def test_random_summed_groups_keep_the_invariants():
         except AssertionError as e:
             raise AssertionError(f"seed {seed} F={b.F} batch={b.batch} opts={opts}: {e}") from e
     assert fitted >= 30
+
+
+def test_whole_layer_plans_need_uniform_channel_sets():
+    """front_features with BSPMM_ACCUMULATE: the channels of a graph (shared layer input, one
+    output block) become one item per (tile, row range); every operation must be a channel of
+    a set and all sets must have the same number of channels."""
+    b = W.config3_multichannel(graphs=40, F=64, channels=4, accumulate=True)
+    info, items = _check_schedule(b, 64, flags=K.ACCUMULATE, front_features=32)
+    assert info.fused_tasks[0] == 0 and all(it.bin == K.BIN_WORKGROUP for it in items)
+    by_task = {}
+    for it in items:
+        by_task.setdefault(it.workgroup, []).append(it)
+    assert all(sorted(m.slot for m in mem) == [0, 1, 2, 3] for mem in by_task.values())
+    # channels with an input block each do not share the layer input
+    own = W.config3_multichannel(graphs=8, F=64, channels=4, accumulate=True, own_inputs=True)
+    # one graph with three channels among graphs with four
+    c_off = b.c_row_off.copy()
+    c_off[3] = int(b.c_row_off.max()) + int(b.rows.max()) + 7
+    odd = dataclasses.replace(b, c_row_off=c_off)
+    for bad in (own, odd):
+        hb = K.HostBatch(bad.rows, bad.cols, bad.nnz, bad.rpt_off, bad.nz_off, bad.b_row_off,
+                         bad.c_row_off)
+        with pytest.raises(K.BspmmError) as e:
+            K.bspmm_create(hb, 64, K.make_options(flags=K.DRY_RUN | K.ACCUMULATE, front_features=32))
+        assert e.value.code in (K.EINVAL, K.ETOOBIG)
