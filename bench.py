@@ -233,6 +233,82 @@ def layer_front(torch, K, W, n_x=64):
     return out
 
 
+def layer_whole(torch, K, W, n_x=64, channels=4, graphs=128):
+    """The whole graph-convolution layer Y = sum_ch A_ch (X W_ch + bias_ch), HBM-cold, on config
+    3's structure (the channels of a graph share the layer input and one output block): one
+    launch (front_features with BSPMM_ACCUMULATE), one fused launch per channel, and the BLAS
+    library's addmm per channel followed by the summed product."""
+    import dataclasses
+    F = 128
+    b = W.config3_multichannel(graphs=graphs, F=F, channels=channels, accumulate=True)
+    whole = K.Plan(b, options=K.make_options(flags=K.ACCUMULATE, front_features=n_x))
+    sel = [slice(c, None, channels) for c in range(channels)]
+    per_ch = [K.Plan(dataclasses.replace(b, rows=b.rows[q], cols=b.cols[q], nnz=b.nnz[q],
+                                         rpt_off=b.rpt_off[q], nz_off=b.nz_off[q],
+                                         b_row_off=b.b_row_off[q], c_row_off=b.c_row_off[q]),
+                     options=K.make_options(front_features=n_x)) for q in sel]
+    bo = W.config3_multichannel(graphs=graphs, F=F, channels=channels, accumulate=True,
+                                own_inputs=True)
+    summed = K.Plan(bo, options=K.make_options(flags=K.ACCUMULATE))
+    per_set = 4 * (b.n_b_rows * n_x + b.n_c_rows * F)
+    nsets = max(2, min(128, -(-POOL_BYTES // per_set)))
+    X = torch.rand((nsets, b.n_b_rows, n_x), device="cuda") * 2 - 1
+    Y = torch.empty((nsets, b.n_c_rows, F), device="cuda")
+    Wt = (torch.rand((channels * n_x, F), device="cuda") * 2 - 1) / n_x ** 0.5
+    bias = torch.rand((channels, F), device="cuda")
+    Ws = [Wt[c * n_x:(c + 1) * n_x] for c in range(channels)]
+    # dense blocks per (graph, channel) as the summed product reads them; the library calls below
+    # write full-size matrices per channel instead (a strided batched GEMM would be needed to
+    # put them there), which costs the same arithmetic and traffic
+    Bm = torch.empty((min(nsets, 16), bo.n_b_rows, F), device="cuda")
+    U = torch.empty((channels, b.n_b_rows, F), device="cuda")
+
+    def run_whole(i, stream):
+        K.bspmm_run_gcn(whole.handle, X[i], n_x, Wt, F, bias, Y[i], F, False, stream)
+
+    def run_per_channel(i, stream):
+        for c in range(channels):
+            K.bspmm_run_gcn(per_ch[c].handle, X[i], n_x, Ws[c], F, bias[c], Y[i], F, c > 0, stream)
+
+    def run_unfused(i, stream):
+        for c in range(channels):
+            torch.addmm(bias[c], X[i], Ws[c], out=U[c])
+        K.bspmm_run(summed.handle, Bm[i % Bm.shape[0]], Y[i], F, F, stream)
+
+    def timed(fn):
+        g = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            fn(0, side.cuda_stream)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        with torch.cuda.graph(g):
+            cs = torch.cuda.current_stream().cuda_stream
+            for i in range(nsets):
+                fn(i, cs)
+        for _ in range(2):
+            g.replay()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(4):
+            g.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / (4 * nsets)
+
+    nnz = int(b.nnz.sum())
+    flops = channels * 2 * b.n_b_rows * n_x * F + 2 * nnz * F
+    out = {"workload": f"cfg3 structure, {graphs} graphs, {channels} channels, n_X={n_x}, F={F}",
+           "operand_sets": nsets,
+           "one_launch_us": round(timed(run_whole), 3),
+           "one_fused_launch_per_channel_us": round(timed(run_per_channel), 3),
+           "blas_addmm_per_channel_then_summed_product_us": round(timed(run_unfused), 3)}
+    out["one_launch_gflops"] = round(flops / out["one_launch_us"] * 1e-3, 1)
+    return out
+
+
 _marker = None
 
 
@@ -523,6 +599,7 @@ def main():
         extra["paper_grid_batched_vs_non_batched"] = paper_grid(torch, K, W)
         extra["coo_operands"] = coo_operands(torch, K, W)
         extra["layer_front"] = [layer_front(torch, K, W, n_x=n) for n in (32, 64, 128)]
+        extra["layer_whole"] = [layer_whole(torch, K, W, n_x=n) for n in (32, 64)]
 
     out = {
         "metric": "batched SpMM graphs/sec, F=128, batch 128",

@@ -27,6 +27,7 @@ struct Knobs {
     int min_tile = 32;
     int max_tile = 256;
     int target_wgs = 1024;
+    bool target_given = false;   // the caller fixed target_wgs
     int compute_units = 256;
     int pad = 0;
     int max_passes = 1;
