@@ -256,3 +256,12 @@ def test_whole_layer_in_one_launch(torch_cuda, oracle, graphs, F, n_x, chans):
     plan.run_gcn(Xd, Wd, bd, again)
     torch.cuda.synchronize()
     assert torch.equal(Yd, again)
+    # accumulate != 0 adds the layer onto what the output holds
+    base = np.random.default_rng(3).uniform(-1, 1, size=(b.n_c_rows, F)).astype(np.float32)
+    onto = torch.from_numpy(base).cuda()
+    plan.run_gcn(Xd, Wd, bd, onto, accumulate=True)
+    torch.cuda.synchronize()
+    got = onto.cpu().numpy()
+    assert np.array_equal(got[~owned], base[~owned])
+    _assert_close(np.where(owned[:, None], got, SENTINEL), Y + base.astype(np.float64),
+                  T + np.abs(base.astype(np.float64)), owned, tol, "whole layer, accumulated")
