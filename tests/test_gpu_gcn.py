@@ -265,3 +265,50 @@ def test_whole_layer_in_one_launch(torch_cuda, oracle, graphs, F, n_x, chans):
     assert np.array_equal(got[~owned], base[~owned])
     _assert_close(np.where(owned[:, None], got, SENTINEL), Y + base.astype(np.float64),
                   T + np.abs(base.astype(np.float64)), owned, tol, "whole layer, accumulated")
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_random_whole_layers(torch_cuda, oracle, seed):
+    """Random layers: 2 to 8 channels, rectangular channel matrices (the layer input has its own
+    row count), empty channels, odd input widths, graphs from one node to a few hundred."""
+    from random_cases import _random_csr
+    torch = torch_cuda
+    rng = np.random.default_rng(900 + seed)
+    chans = int(rng.integers(2, 9))
+    F = [16, 32, 48, 64, 128][int(rng.integers(5))]
+    n_x = [4, 12, 20, 32, 64, 100][int(rng.integers(6))]
+    graphs = [1, 3, 20, 60][int(rng.integers(4))]
+    ops, b_block_of_op, b_block_rows, c_block_of_op = [], [], [], []
+    for g in range(graphs):
+        m = int(rng.integers(1, 90)) if rng.random() < 0.9 else int(rng.integers(90, 260))
+        k = m if rng.integers(2) else int(rng.integers(1, 90))
+        b_block_rows.append(k)
+        for _ in range(chans):
+            per_row = [0.0, 0.5, 1.5, 4.0][int(rng.integers(4))]
+            rpt, ci, va = _random_csr(rng, m, k, int(per_row * m), bool(rng.integers(2)))
+            ops.append((m, k, rpt, ci, va))
+            b_block_of_op.append(g)
+            c_block_of_op.append(g)
+    b = W.assemble("layer", F, ops, b_block_of_op, b_block_rows, rng, n_graphs=graphs,
+                   c_block_of_op=c_block_of_op)
+    X, Ws, biases = _layer(b, n_x, seed, channels=chans)
+    print(f"random layer {seed}: graphs={graphs} channels={chans} F={F} n_X={n_x}", flush=True)
+    try:
+        plan = K.Plan(b, options=K.make_options(flags=K.ACCUMULATE, front_features=n_x))
+    except K.BspmmError as e:
+        assert e.code == K.ETOOBIG
+        pytest.skip("a set does not fit on chip beside its layer input")
+    Xd = torch.from_numpy(X).cuda()
+    Wd = torch.from_numpy(np.concatenate(Ws, axis=0)).cuda()
+    bd = torch.from_numpy(np.stack(biases)).cuda()
+    Yd = torch.full((b.n_c_rows, F), SENTINEL, dtype=torch.float32, device="cuda")
+    plan.run_gcn(Xd, Wd, bd, Yd)
+    torch.cuda.synchronize()
+    Y = T = None
+    dsum = 0
+    for c in range(chans):
+        bc = _channel(b, c, chans)
+        Y, T = oracle.gcn_channel(bc, X, Ws[c], biases[c], Y, T)
+        dsum += max(int(np.diff(bc.op_csr(i)[0]).max()) if int(bc.rows[i]) else 0 for i in range(bc.batch))
+    tol = max(1e-5, (chans * (n_x + 2) + dsum) * 2.0 ** -23)
+    _assert_close(Yd.cpu().numpy(), Y, T, _owned(b.c_row_off, b.rows, b.n_c_rows), tol, f"random layer {seed}")
