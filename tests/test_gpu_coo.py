@@ -317,3 +317,26 @@ def test_random_batches_and_knobs_from_coo(torch_cuda, oracle, block):
             few = {k: v for k, v in kw.items() if k in ("lds_bytes", "min_tile", "max_tile")}
             _check(torch_cuda, oracle, b, ids, vals, what=what + " direct", csr=False,
                    opts=K.make_options(flags=K.COO_DIRECT, **few))
+
+
+@pytest.mark.parametrize("own_inputs", [False, True])
+def test_channel_sum_from_coo(torch_cuda, oracle, own_inputs):
+    """BSPMM_ACCUMULATE on a plan made from COO operands: the summed sets are merged from the CSR
+    arrays the conversion built in the workspace."""
+    torch = torch_cuda
+    b = W.config3_multichannel(graphs=64, F=64, accumulate=True, own_inputs=own_inputs, with_dY=True)
+    ids, vals = W.coo_view(b, seed=12)
+    plan = K.Plan(b, options=K.make_options(flags=K.ACCUMULATE), coo=(ids, vals))
+    Bd = torch.from_numpy(b.B).cuda()
+    Cd = torch.full((b.n_c_rows, b.F), SENTINEL, dtype=torch.float32, device="cuda")
+    plan.run(Bd, Cd)
+    torch.cuda.synchronize()
+    ref, S = oracle.forward_batch(b)       # same entries, summed per output block
+    _assert_close(Cd.cpu().numpy(), ref, S, _owned(b.c_row_off, b.rows, b.n_c_rows), "coo channel sum")
+    Yd = torch.from_numpy(b.dY).cuda()
+    Gd = torch.full((b.n_b_rows, b.F), SENTINEL, dtype=torch.float32, device="cuda")
+    plan.run_transposed(Yd, Gd)
+    torch.cuda.synchronize()
+    ref, S = oracle.transposed_batch(b)
+    _assert_close(Gd.cpu().numpy(), ref, S, _owned(b.b_row_off, b.cols, b.n_b_rows),
+                  "coo channel sum transposed")
