@@ -572,7 +572,7 @@ Schedule make_schedule(const DirOps& ops_in, int F, const Knobs& kn_in)
     // wide tiles of 100-row graphs cut to four rows each, 8.2 -> 9.2 us).
     int cap = fixed_cap;
     if (kn.wg_passes == 0 && kn.front == 0) {
-        const int uncut = workgroups_of(chosen, fixed_cap, allow_small);
+        const int uncut = wgs;                         // (the tile search ended on this very count)
         const int64_t uncut_words = counted_tile_words;
         bool done = false;
         // (a launch that moves more than about 28 MB is bound by bandwidth, not by its slowest
@@ -669,7 +669,14 @@ Schedule make_schedule(const DirOps& ops_in, int F, const Knobs& kn_in)
             std::vector<int>& v = by_range[r];
             const size_t n = k.size();
             if (n < 2) continue;
-            if (!packable || n < 128) {   // few items (or more groups than the key holds): compare
+            if (packable && n < 4096) {   // few items: the counters of a radix pass would outweigh them
+                std::vector<std::pair<uint64_t, int>> kv(n);
+                for (size_t t = 0; t < n; ++t) kv[t] = {k[t], v[t]};
+                std::sort(kv.begin(), kv.end());     // (equal keys: by draft index, as the stable sort)
+                for (size_t t = 0; t < n; ++t) v[t] = kv[t].second;
+                continue;
+            }
+            if (!packable) {   // more groups than the key holds: compare
                 std::vector<int> order(n);
                 std::iota(order.begin(), order.end(), 0);
                 std::stable_sort(order.begin(), order.end(), [&](int a, int b) {
