@@ -113,17 +113,28 @@ class Runner:
             cs = torch.cuda.current_stream().cuda_stream
             for i in range(chunk):
                 self.launch(i, cs, rotate)
-        reps = max(1, steps // chunk)
+        reps, rest = divmod(steps, chunk)
+        tail = None
+        if rest:            # exactly `steps` launches: a second graph holds what one pass leaves over
+            tail = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(tail):
+                cs = torch.cuda.current_stream().cuda_stream
+                for i in range(rest):
+                    self.launch(i, cs, rotate)
         for _ in range(max(1, warmup // chunk)):
             g.replay()
+        if tail is not None:
+            tail.replay()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         torch.cuda.synchronize()
         e0.record()
         for _ in range(reps):
             g.replay()
+        if tail is not None:
+            tail.replay()
         e1.record()
         torch.cuda.synchronize()
-        return e0.elapsed_time(e1) * 1e-3 / (reps * chunk), reps * chunk
+        return e0.elapsed_time(e1) * 1e-3 / steps, steps
 
     def summary(self, sec):
         return {"us_per_launch": round(sec * 1e6, 3),
