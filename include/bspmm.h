@@ -34,7 +34,9 @@
  * Streams.  `stream` is a hipStream_t passed as void* (NULL = the default stream).  All
  * device work is enqueued asynchronously; no call synchronises the device except where stated.
  * bspmm_run / bspmm_run_transposed enqueue exactly one kernel (the first call of a direction
- * also the one-off device builds named under BSPMM_BUILD_TRANSPOSE).  Calls on one plan must be
+ * also the one-off device builds named under BSPMM_BUILD_TRANSPOSE; a build recorded into a
+ * stream capture runs with the graph and is not counted as done, so plans used in HIP graphs
+ * are best created with that flag or run once before the capture).  Calls on one plan must be
  * issued from one host thread at a time and on the stream order the caller wants.
  *
  * Errors.  Every int-returning call returns BSPMM_OK or a negative BSPMM_E* code; nothing is

@@ -487,6 +487,18 @@ int plan_with_budget(bspmm_plan& p, const Batch* b, int32_t F, const bspmm_optio
     return rc;
 }
 
+// A one-off build recorded into a stream capture runs when the graph is replayed, not now: the
+// plan must not count it as done (a later eager run builds again; the graph keeps its copy).
+bool capturing(hipStream_t s)
+{
+    hipStreamCaptureStatus st = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(s, &st) != hipSuccess) {
+        (void)hipGetLastError();
+        return false;
+    }
+    return st == hipStreamCaptureStatusActive;
+}
+
 int enqueue_build(bspmm_plan* p, hipStream_t s)
 {
     if (p->transposed_built || p->knobs.symmetric) return BSPMM_OK;
@@ -498,7 +510,7 @@ int enqueue_build(bspmm_plan* p, hipStream_t s)
         reinterpret_cast<float*>(p->ws + p->lay.values_t),
         reinterpret_cast<int32_t*>(p->ws + p->lay.scratch), s);
     if (e != hipSuccess) return hip_fail(e);
-    p->transposed_built = true;
+    p->transposed_built = !capturing(s);
     return BSPMM_OK;
 }
 
@@ -515,7 +527,7 @@ int enqueue_merge(bspmm_plan* p, int d, hipStream_t s)
                                      (int)p->set_records[d].size(), rpt, colids, values,
                                      reinterpret_cast<int32_t*>(p->ws + p->lay.merged[d]), s);
     if (e != hipSuccess) return hip_fail(e);
-    p->merged_built[d] = true;
+    p->merged_built[d] = !capturing(s);
     return BSPMM_OK;
 }
 

@@ -576,3 +576,44 @@ def test_runs_replayed_from_a_hip_graph(torch_cuda, oracle):
         _assert_close(got[1], ref, S, _owned_rows(b.b_row_off, b.cols, b.n_b_rows), f"replay {rep} transposed")
         ref, S = oracle.forward_batch(dataclasses.replace(c, B=nc))
         _assert_close(got[2], ref, S, _owned_rows(c.c_row_off, c.rows, c.n_c_rows), f"replay {rep} channel sum")
+
+
+def test_first_run_inside_a_stream_capture(torch_cuda, oracle):
+    """A plan whose first runs are recorded into a HIP graph: the one-off builds (transposed CSR,
+    merged CSR of summed sets) are recorded with them and do not count as done, so an eager run
+    before the first replay is still correct, and so is every replay."""
+    torch = torch_cuda
+    c = W.config3_multichannel(graphs=40, F=64, accumulate=True, own_inputs=True, with_dY=True)
+    plan = K.Plan(c, options=K.make_options(flags=K.ACCUMULATE))
+    Bd = torch.from_numpy(c.B).cuda()
+    Yd = torch.from_numpy(c.dY).cuda()
+    Cg = torch.full((c.n_c_rows, 64), SENTINEL, device="cuda")
+    Gg = torch.full((c.n_b_rows, 64), SENTINEL, device="cuda")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(g, stream=side):
+            s = torch.cuda.current_stream().cuda_stream
+            plan.run(Bd, Cg, stream=s)
+            plan.run_transposed(Yd, Gg, stream=s)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    assert plan.info().transposed_built == 0
+    refC, SC = oracle.forward_batch(c)
+    refG, SG = oracle.transposed_batch(c)
+    ownC = _owned_rows(c.c_row_off, c.rows, c.n_c_rows)
+    ownG = _owned_rows(c.b_row_off, c.cols, c.n_b_rows)
+    Ce = torch.full_like(Cg, SENTINEL)
+    Ge = torch.full_like(Gg, SENTINEL)
+    plan.run(Bd, Ce)                    # eager, before the graph has ever run
+    plan.run_transposed(Yd, Ge)
+    torch.cuda.synchronize()
+    _assert_close(Ce.cpu().numpy(), refC, SC, ownC, "eager before the first replay")
+    _assert_close(Ge.cpu().numpy(), refG, SG, ownG, "eager transposed before the first replay")
+    for rep in range(2):
+        Cg.fill_(SENTINEL)
+        Gg.fill_(SENTINEL)
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(Cg, Ce) and torch.equal(Gg, Ge), f"replay {rep}"
