@@ -6,8 +6,13 @@
 //                   output row a group of lanes that accumulates its stored entries in
 //                   registers and writes the row once (the row-wise, atomic-free product of
 //                   Fig. 4, batched as in Sec. IV-C, with the column blocking of Fig. 5(d)).
+// bspmm_gcn_kernel  the fused front of the graph-convolution layer (Fig. 7): the dense tile is
+//                   made on the matrix cores from the layer input and the weights, for one
+//                   channel or for all channels of the layer, and gathered as above.
+// bspmm_coo_kernel  the direct product for COO / SparseTensor operands (Fig. 3, Fig. 5(a,b)).
 // build_sorted      stable CSR -> transposed CSR of every operation (counting sort by column),
 //                   and COO / SparseTensor -> CSR (the same sort by row).
+// merge_sets        merged CSR of operations that are summed into one output block.
 // validate_csr      structural check of the device CSR arrays.
 #include <hip/hip_runtime.h>
 
