@@ -84,6 +84,7 @@ struct bspmm_plan {
     DirOps dir[2];
     Schedule sched[2];
     std::vector<OpRecord> records;
+    std::vector<char> tables;   // host image of the workspace's front: item tables and records
     Layout lay;
     int build_lds_bytes = 0;
     int64_t scratch_words = 0;
@@ -765,14 +766,22 @@ int upload_plan(bspmm_plan* p, const bspmm_options* options, void* workspace,
     // The host tables stay alive inside the plan, so the asynchronous copies may read them
     // at any time before bspmm_destroy.
     hipError_t e = hipSuccess;
-    for (int d = 0; d < 2 && e == hipSuccess; ++d)
-        if (!p->sched[d].items.empty())
-            e = hipMemcpyAsync(p->ws + p->lay.items[d], p->sched[d].items.data(),
-                               p->sched[d].items.size() * sizeof(WorkItem),
-                               hipMemcpyHostToDevice, s);
-    if (e == hipSuccess && !p->records.empty())
-        e = hipMemcpyAsync(p->ws + p->lay.op_records, p->records.data(),
-                           p->records.size() * sizeof(OpRecord), hipMemcpyHostToDevice, s);
+    if (!p->coo_direct) {
+        // The item tables of both directions and the operation records sit back to back at the
+        // front of the workspace: one copy from one host image of that stretch (every copy from
+        // pageable memory costs several microseconds of host time, whatever its size).
+        const size_t bytes = p->lay.op_records + p->records.size() * sizeof(OpRecord);
+        p->tables.assign(bytes, 0);
+        for (int d = 0; d < 2; ++d)
+            if (!p->sched[d].items.empty())
+                std::memcpy(p->tables.data() + p->lay.items[d], p->sched[d].items.data(),
+                            p->sched[d].items.size() * sizeof(WorkItem));
+        if (!p->records.empty())
+            std::memcpy(p->tables.data() + p->lay.op_records, p->records.data(),
+                        p->records.size() * sizeof(OpRecord));
+        if (bytes > 0)
+            e = hipMemcpyAsync(p->ws, p->tables.data(), bytes, hipMemcpyHostToDevice, s);
+    }
     for (int d = 0; d < 2 && e == hipSuccess; ++d)
         if (!p->set_records[d].empty())
             e = hipMemcpyAsync(p->ws + p->lay.sets[d], p->set_records[d].data(),
