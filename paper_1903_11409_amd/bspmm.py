@@ -329,8 +329,10 @@ def bspmm_destroy(plan: Optional[int]) -> None:
 class Plan:
     """Owns a plan handle plus the torch tensors it borrows (CSR arrays and workspace).
 
-    ``batch`` is a :class:`workloads.Batch`-like object with numpy members; the CSR arrays are
-    copied to ``device`` once.  Dense operands are passed per call as torch tensors.
+    ``batch`` is a :class:`workloads.Batch`-like object: the per-operation sizes and offsets are
+    host arrays; the CSR arrays (``rpt``, ``colids``, ``values``) are numpy arrays, copied to
+    ``device`` once, or tensors already there, borrowed in place.  Dense operands are passed per
+    call as torch tensors.
     """
 
     def __init__(self, batch, F: Optional[int] = None, options: Optional[bspmm_options] = None,
@@ -344,12 +346,20 @@ class Plan:
         self.rpt_len = int((np.asarray(batch.rows, dtype=np.int64) + 1).sum())
         self.rpt_t_len = int((np.asarray(batch.cols, dtype=np.int64) + 1).sum())
         self.nnz_total = int(np.asarray(batch.nnz, dtype=np.int64).sum())
+        def on_device(a, dtype):
+            # numpy arrays are copied over; tensors that already sit on the device with the
+            # right type and layout are borrowed as they are
+            if isinstance(a, torch.Tensor):
+                return a.to(device=dev, dtype=dtype).contiguous()
+            np_type = np.int32 if dtype == torch.int32 else np.float32
+            return torch.from_numpy(np.ascontiguousarray(a, dtype=np_type)).to(dev)
+
         if coo is not None:
-            # COO / SparseTensor operands: ``coo`` = (ids, values) numpy arrays laid out by the
-            # batch's nz_off; the batch's own CSR arrays are not used
+            # COO / SparseTensor operands: ``coo`` = (ids, values), numpy arrays or tensors, laid
+            # out by the batch's nz_off; the batch's own CSR arrays are not used
             ids, vals = coo
-            self.ids = torch.from_numpy(np.ascontiguousarray(ids, dtype=np.int32)).to(dev)
-            self.values = torch.from_numpy(np.ascontiguousarray(vals, dtype=np.float32)).to(dev)
+            self.ids = on_device(ids, torch.int32)
+            self.values = on_device(vals, torch.float32)
             self.hb = HostCooBatch(batch.rows, batch.cols, batch.nnz, batch.nz_off,
                                    batch.b_row_off, batch.c_row_off,
                                    self.ids if self.ids.numel() else None,
@@ -359,9 +369,9 @@ class Plan:
             assert self.workspace.data_ptr() % 256 == 0
             self.handle = bspmm_create_coo(self.hb, self.F, options, self.workspace, nbytes, stream)
             return
-        self.rpt = torch.from_numpy(np.ascontiguousarray(batch.rpt, dtype=np.int32)).to(dev)
-        self.colids = torch.from_numpy(np.ascontiguousarray(batch.colids, dtype=np.int32)).to(dev)
-        self.values = torch.from_numpy(np.ascontiguousarray(batch.values, dtype=np.float32)).to(dev)
+        self.rpt = on_device(batch.rpt, torch.int32)
+        self.colids = on_device(batch.colids, torch.int32)
+        self.values = on_device(batch.values, torch.float32)
         # zero-length tensors have a null data_ptr; give the library something addressable
         if self.rpt.numel() == 0:
             self.rpt = torch.zeros(1, dtype=torch.int32, device=dev)

@@ -401,6 +401,27 @@ def test_non_default_stream(torch_cuda, oracle):
     _assert_close(Cd.cpu().numpy(), ref, S, _owned_rows(b.c_row_off, b.rows, b.n_c_rows), "stream")
 
 
+def test_plan_borrows_csr_tensors_that_are_already_on_the_device(torch_cuda, oracle):
+    """The Python wrapper takes the CSR arrays as device tensors too (a pipeline that builds its
+    adjacency lists on the GPU): they are used in place, not copied."""
+    import dataclasses
+    torch = torch_cuda
+    b = W.config5_skewed(graphs=64, F=64, asymmetric=True)
+    dev = dataclasses.replace(b, rpt=torch.from_numpy(b.rpt).cuda(),
+                              colids=torch.from_numpy(b.colids).cuda(),
+                              values=torch.from_numpy(b.values).cuda())
+    plan = K.Plan(dev)
+    assert plan.rpt.data_ptr() == dev.rpt.data_ptr() and plan.values.data_ptr() == dev.values.data_ptr()
+    Bd = torch.from_numpy(b.B).cuda()
+    Cd = torch.full((b.n_c_rows, b.F), SENTINEL, dtype=torch.float32, device="cuda")
+    plan.run(Bd, Cd)
+    torch.cuda.synchronize()
+    ref, S = oracle.forward_batch(b)
+    _assert_close(Cd.cpu().numpy(), ref, S, _owned_rows(b.c_row_off, b.rows, b.n_c_rows), "device csr")
+    _check_transposed(torch, oracle, b, plan=plan, what="device csr")
+    assert plan.validate() == -1
+
+
 def test_symmetric_operands_need_no_transposed_build(torch_cuda, oracle):
     """Symmetrically normalised adjacency matrices equal their transposes: with
     BSPMM_SYMMETRIC the backward product gathers over the forward CSR and nothing is built."""
