@@ -1183,6 +1183,87 @@ __global__ void __launch_bounds__(kThreads) bspmm_gcn_kernel(const LaunchParams 
         }
     };
 
+    // The same on 32 x 32 blocks (channel sets whose tile is a multiple of 32 columns wide, where
+    // the host asks for it with bit 3 of `staged`): a
+    // block-trip of 16 k is eight matrix instructions of 64 cycles each fed by two 16-byte
+    // reads of X_i and eight reads of W per lane - half the LDS reads per flop of the 16 x 16
+    // form, and four times the matrix time per trip to hide their latency behind.  The
+    // instruction sums over k in any order: lane half h takes k0 + 8h ... k0 + 8h + 7, which
+    // are contiguous in the row of X_i.
+    auto dense_rows32 = [&](int r0, int rows) {
+        typedef float mfma16 __attribute__((ext_vector_type(16)));
+        const int nb32 = it.fw >> 5;
+        const int per_channel = ((rows + 31) >> 5) * nb32;
+        const int blocks = per_channel * M;
+        const int c32 = wl & 31, h = wl >> 5;
+        for (int blk = wave; blk < blocks; blk += kThreads / 64) {
+            const int c = blk / per_channel;
+            const int rem = blk - c * per_channel;
+            const int mb = rem / nb32, nb = rem - mb * nb32;
+            const float bv = bias_s[c * it.fw + 32 * nb + c32];
+            mfma16 acc;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[i] = bv;
+            const int arow = min(32 * mb + c32, rows - 1);     // rows past the end repeat the last
+            const float* xrow = xs + arow * nx;
+            const int xs_swz = arow & swz;
+            const float* wcol = ws + (c * nx + 8 * h) * it.fw + 32 * nb + c32;
+            const int nfull = nx & ~15;
+            float4 a0 = make_float4(0.f, 0.f, 0.f, 0.f), a1 = a0;
+            float w[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+            if (nfull > 0) {
+                a0 = *reinterpret_cast<const float4*>(xrow + (((2 * h) ^ xs_swz) << 2));
+                a1 = *reinterpret_cast<const float4*>(xrow + (((2 * h + 1) ^ xs_swz) << 2));
+#pragma unroll
+                for (int j = 0; j < 8; ++j) w[j] = wcol[j * it.fw];
+            }
+            for (int k0 = 0; k0 < nfull; k0 += 16) {
+                float4 n0 = a0, n1 = a1;
+                float v[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) v[j] = w[j];
+                if (k0 + 16 < nfull) {      // the next trip's operands, before this trip's instructions
+                    const int q = ((k0 + 16) >> 2) + 2 * h;
+                    n0 = *reinterpret_cast<const float4*>(xrow + ((q ^ xs_swz) << 2));
+                    n1 = *reinterpret_cast<const float4*>(xrow + (((q + 1) ^ xs_swz) << 2));
+                    const float* wk = wcol + (k0 + 16) * it.fw;
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) v[j] = wk[j * it.fw];
+                }
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a0.x, w[0], acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a0.y, w[1], acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a0.z, w[2], acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a0.w, w[3], acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a1.x, w[4], acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a1.y, w[5], acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a1.z, w[6], acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a1.w, w[7], acc, 0, 0, 0);
+                a0 = n0, a1 = n1;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) w[j] = v[j];
+            }
+            if (nfull < nx) {
+                // the last, partial trip (4, 8 or 12 k): a lane whose k lies past the end reads
+                // the row's first element instead and contributes zero
+                const int left = nx - nfull;
+                for (int j = 0; j < min(8, left); ++j) {
+                    const bool ok = 8 * h + j < left;
+                    const int k = ok ? nfull + 8 * h + j : 0;
+                    float av = xrow[(((k >> 2) ^ xs_swz) << 2) + (k & 3)];
+                    if (!ok) av = 0.f;
+                    const float wv = ws[(c * nx + k) * it.fw + 32 * nb + c32];
+                    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av, wv, acc, 0, 0, 0);
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int row = 32 * mb + 8 * (i >> 2) + 4 * h + (i & 3);
+                if (row < rows) bt[(c * kx + r0 + row) * it.fw + 32 * nb + c32] = acc[i];
+            }
+        }
+    };
+    const bool blocks32 = SETS && (it.staged & 8) != 0 && (it.fw & 31) == 0;
+
     // ---- first pass: everything read from memory is requested at once (the first rows of
     // X_i, the weights, the bias, A_i)
     stage_tile4(xs, xg, P.ld_in, min(R, kx), xvec, tid, swz);
@@ -1203,7 +1284,10 @@ __global__ void __launch_bounds__(kThreads) bspmm_gcn_kernel(const LaunchParams 
     if (tid < it.fw) bias_s[tid] = bias_v;
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");          // direct-to-LDS loads landed
     __syncthreads();
-    dense_rows(0, min(R, kx));
+    if (blocks32)
+        dense_rows32(0, min(R, kx));
+    else
+        dense_rows(0, min(R, kx));
     __syncthreads();         // the rows of X_i may be replaced; after the last pass: tile complete
     // ---- operations with more rows than fit: further passes
     for (int r0 = R; r0 < kx; r0 += R) {
@@ -1211,7 +1295,10 @@ __global__ void __launch_bounds__(kThreads) bspmm_gcn_kernel(const LaunchParams 
         stage_tile4(xs, xg + (int64_t)r0 * P.ld_in, P.ld_in, rows, xvec, tid, swz);
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
-        dense_rows(r0, rows);
+        if (blocks32)
+            dense_rows32(r0, rows);
+        else
+            dense_rows(r0, rows);
         __syncthreads();
     }
     compute_staged<kThreads, 4, false, ACC>(P, it, sm, tid);

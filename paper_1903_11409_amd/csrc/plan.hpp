@@ -38,6 +38,8 @@ struct alignas(16) WorkItem {
     int32_t fw;           // feature columns
     int32_t staged;       // bit 0: operation and dense tile staged in LDS (0 = generic bin);
                           // bit 1: no other item reads this dense tile (stream it);
+                          // bit 2: the item stands in for a set of summed operations and reads
+                          // the set's merged CSR; bit 3 (fused front): dense tile in 32 x 32 blocks;
                           // fused tasks: bits 8-15 of the first member = number of members,
                           // bits 16-23 of member j = the member whose dense tile j shares
 };

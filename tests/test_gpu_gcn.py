@@ -229,11 +229,29 @@ def test_whole_layer_in_one_launch(torch_cuda, oracle, graphs, F, n_x, chans):
     ONE launch: a plan with front_features and BSPMM_ACCUMULATE whose channel operations share
     the layer input and the output block; W is the channels' weight matrices one under the
     other, bias one row per channel."""
-    torch = torch_cuda
+    _whole_layer_case(torch_cuda, oracle, graphs, F, n_x, chans)
+
+
+@pytest.mark.parametrize("graphs,F,n_x,chans,kw", [
+    # a launch of several rounds of workgroups makes its dense tiles in 32 x 32 blocks: for real
+    # (512 graphs), and on small batches by telling the scheduler that the chip has four CUs
+    (512, 128, 32, 4, {}),
+    (64, 128, 64, 4, {"compute_units": 4}),
+    (48, 64, 32, 4, {"compute_units": 4}),
+    (40, 64, 20, 3, {"compute_units": 4}),       # 20 = 16 + a partial trip of 4
+    (40, 128, 44, 2, {"compute_units": 4}),      # 44 = 32 + a partial trip of 12
+    (30, 96, 8, 2, {"compute_units": 4}),        # a partial trip only; 96 columns = three blocks
+    (24, 64, 32, 8, {"compute_units": 4, "lds_bytes": 163840}),
+])
+def test_whole_layer_in_wide_blocks(torch_cuda, oracle, graphs, F, n_x, chans, kw):
+    _whole_layer_case(torch_cuda, oracle, graphs, F, n_x, chans, **kw)
+
+
+def _whole_layer_case(torch, oracle, graphs, F, n_x, chans, **kw):
     b = W.config3_multichannel(seed=500 + graphs, graphs=graphs, F=F, channels=chans, accumulate=True)
     X, Ws, biases = _layer(b, n_x, 11, channels=chans)
-    print(f"layer case: graphs={graphs} F={F} n_X={n_x} channels={chans}", flush=True)
-    plan = K.Plan(b, options=K.make_options(flags=K.ACCUMULATE, front_features=n_x))
+    print(f"layer case: graphs={graphs} F={F} n_X={n_x} channels={chans} {kw}", flush=True)
+    plan = K.Plan(b, options=K.make_options(flags=K.ACCUMULATE, front_features=n_x, **kw))
     info = plan.info()
     assert info.fused_tasks[0] == 0
     Xd = torch.from_numpy(X).cuda()
