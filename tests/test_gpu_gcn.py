@@ -286,7 +286,7 @@ def _whole_layer_case(torch, oracle, graphs, F, n_x, chans, **kw):
 
 
 @pytest.mark.parametrize("seed", range(8))
-def test_random_whole_layers(torch_cuda, oracle, seed):
+def test_random_whole_layers(torch_cuda, oracle, seed, **kw):
     """Random layers: 2 to 8 channels, rectangular channel matrices (the layer input has its own
     row count), empty channels, odd input widths, graphs from one node to a few hundred."""
     from random_cases import _random_csr
@@ -312,7 +312,7 @@ def test_random_whole_layers(torch_cuda, oracle, seed):
     X, Ws, biases = _layer(b, n_x, seed, channels=chans)
     print(f"random layer {seed}: graphs={graphs} channels={chans} F={F} n_X={n_x}", flush=True)
     try:
-        plan = K.Plan(b, options=K.make_options(flags=K.ACCUMULATE, front_features=n_x))
+        plan = K.Plan(b, options=K.make_options(flags=K.ACCUMULATE, front_features=n_x, **kw))
     except K.BspmmError as e:
         assert e.code == K.ETOOBIG
         pytest.skip("a set does not fit on chip beside its layer input")
@@ -330,3 +330,12 @@ def test_random_whole_layers(torch_cuda, oracle, seed):
         dsum += max(int(np.diff(bc.op_csr(i)[0]).max()) if int(bc.rows[i]) else 0 for i in range(bc.batch))
     tol = max(1e-5, (chans * (n_x + 2) + dsum) * 2.0 ** -23)
     _assert_close(Yd.cpu().numpy(), Y, T, _owned(b.c_row_off, b.rows, b.n_c_rows), tol, f"random layer {seed}")
+
+
+@pytest.mark.parametrize("seed", range(20, 32))
+def test_random_whole_layers_in_several_rounds(torch_cuda, oracle, seed):
+    """The same random layers with the scheduler told that the chip has one CU: launches of
+    more than six workgroups then count as several rounds and (up to 64 input features, tiles
+    of 32 columns or a multiple) make their dense tiles in 32 x 32 blocks."""
+    test_random_whole_layers(torch_cuda, oracle, seed, compute_units=1)
+
