@@ -257,7 +257,8 @@ int bspmm_run(bspmm_plan* plan, const float* B, float* C, int64_t ldb, int64_t l
  * (cols_i rows of n_X = options.front_features floats at row b_row_off[i], leading dimension
  * ldx >= n_X), W the DEVICE n_X x F weight matrix (leading dimension ldw >= F), bias F DEVICE
  * floats, Y indexed like C.  The dense part runs on the matrix cores in fp32
- * (v_mfma_f32_16x16x4_f32) from LDS to LDS; B_i never leaves the chip.  X, W, Y must be
+ * (v_mfma_f32_16x16x4_f32; whole layers in large launches: v_mfma_f32_32x32x2_f32) from LDS
+ * to LDS; B_i never leaves the chip.  X, W, Y must be
  * 16-byte aligned with ldx, ldw, ldy multiples of 4 (EINVAL).  ESTATE for plans created
  * without front_features.
  *

@@ -1036,6 +1036,8 @@ validate_coo_kernel(const OpRecord* __restrict__ ops, const int32_t* __restrict_
 // them to four instructions together with the weights of the same four k, so the k order
 // inside a step differs from memory order for both operands alike, which leaves the product
 // unchanged.
+// (Whole layers in launches of several rounds use v_mfma_f32_32x32x2_f32 on 32 x 32 blocks
+// instead; see dense_rows32 in the kernel.)
 // LDS, in words: the staged layout of the item (row pointers, entries, dense tile k x fw),
 // then the weight tile (n_front x fw), the bias tile (fw) and as many rows of X_i as fit
 // (a multiple of 16; operations with more rows take several passes).
