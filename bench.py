@@ -613,6 +613,8 @@ def main():
         extra["coo_operands"] = coo_operands(torch, K, W)
         extra["layer_front"] = [layer_front(torch, K, W, n_x=n) for n in (32, 64, 128)]
         extra["layer_whole"] = [layer_whole(torch, K, W, n_x=n) for n in (32, 64)]
+        # a launch of several rounds of workgroups (32 x 32 matrix-core blocks)
+        extra["layer_whole"].append(layer_whole(torch, K, W, n_x=32, graphs=512))
 
     out = {
         "metric": "batched SpMM graphs/sec, F=128, batch 128",
