@@ -174,7 +174,9 @@ typedef struct bspmm_options {
                                   n_X-column layer input: whole workgroups, feature tiles in
                                   multiples of 16, room in LDS for an n_X x tile block of weights
                                   and at least 16 rows of X_i beside the operation (lds_bytes
-                                  then defaults to 80 KiB, 160 KiB if that is too little); needs
+                                  then defaults to 80 KiB, 160 KiB if that is too little; for
+                                  batches of 1.5 graphs per CU and more, 24 to 52 KiB first:
+                                  more workgroups per CU); needs
                                   F % 16 == 0 and n_X % 4 == 0
                                   (EINVAL), not combined with
                                   BSPMM_SPLIT_HUB_ROWS or lds_pad (EINVAL); with

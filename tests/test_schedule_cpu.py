@@ -630,3 +630,25 @@ def test_whole_layer_plans_need_uniform_channel_sets():
         with pytest.raises(K.BspmmError) as e:
             K.bspmm_create(hb, 64, K.make_options(flags=K.DRY_RUN | K.ACCUMULATE, front_features=32))
         assert e.value.code in (K.EINVAL, K.ETOOBIG)
+
+
+def test_large_front_batches_take_a_smaller_lds_budget():
+    """A fused-front launch of several rounds of workgroups is planned with a smaller LDS budget
+    first (more workgroups per CU); small batches, budgets that do not hold the batch and
+    budgets the caller gives are not touched."""
+    for graphs, nx, want in [(128, 32, 81920), (300, 64, 81920), (1024, 32, 24576), (1024, 48, 24576),
+                             (1024, 64, 40960), (1024, 128, 40960)]:
+        b = W.config2_molecule(graphs=graphs, F=128)
+        info, _ = _check_schedule(b, 128, front_features=nx)
+        assert info.lds_bytes == want, (graphs, nx, info.lds_bytes)
+    b = W.config2_molecule(graphs=1024, F=128)
+    info, _ = _check_schedule(b, 128, front_features=32, lds_bytes=65536)
+    assert info.lds_bytes == 65536
+    layer = W.config3_multichannel(graphs=512, F=128, channels=4, accumulate=True)
+    info, _ = _check_schedule(layer, 128, flags=K.ACCUMULATE, front_features=32)
+    assert info.lds_bytes == 53248
+    info, _ = _check_schedule(layer, 128, flags=K.ACCUMULATE, front_features=64)
+    assert info.lds_bytes == 81920      # nothing smaller holds four weight tiles beside a graph
+    small = W.config3_multichannel(graphs=256, F=128, channels=4, accumulate=True)
+    info, _ = _check_schedule(small, 128, flags=K.ACCUMULATE, front_features=32)
+    assert info.lds_bytes == 81920
