@@ -70,6 +70,12 @@ MUTANTS = [
     # graph-convolution layer (Fig. 7: MatMul, Add, BatchedSpMM, ElementWiseAdd)
     ("layer_product_drops_the_value", "c", "c[j] += v * b[j];", "c[j] += b[j];", 0),
     ("layer_channels_overwrite_each_other", "c", "if (!accumulate)", "if (1)", 0),
+    ("layer_matmul_drops_the_last_input_feature", "py",
+     "U = X64 @ W64 ", "U = X64[:, :-1] @ W64[:-1] ", 0),
+    ("layer_matmul_pairs_features_with_the_wrong_weight_rows", "py",
+     "U = X64 @ W64 ", "U = X64[:, ::-1] @ np.roll(W64[::-1], 1, axis=0) ", 0),
+    ("layer_matmul_is_elementwise_times_a_row_sum", "py",
+     "U = X64 @ W64 ", "U = X64.sum(axis=1, keepdims=True) * W64.mean(axis=0, keepdims=True) ", 0),
     ("layer_without_bias", "py",
      "B = np.ascontiguousarray(U + bias64[None, :])", "B = np.ascontiguousarray(U)", 0),
     ("layer_bias_added_twice", "py",

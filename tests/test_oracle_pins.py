@@ -548,14 +548,17 @@ def test_gcn_channel_against_dense_algebra(oracle, which):
     for i in range(b.batch):
         A = _dense_of(b, i)
         xi = X[int(b.b_row_off[i]):int(b.b_row_off[i]) + int(b.cols[i])].astype(np.float64)
-        want = A @ (xi @ Wt.astype(np.float64) + bias.astype(np.float64))
+        # every product of the expected value is the pure-Python triple loop: the oracle's
+        # MatMul step is a library routine, and calling that routine again would pin nothing
+        W64, bias64 = Wt.astype(np.float64), bias.astype(np.float64)
+        want = _brute(A, _brute(xi, W64) + bias64)
         got = Y[int(b.c_row_off[i]):int(b.c_row_off[i]) + int(b.rows[i])]
         assert np.allclose(got, want, rtol=1e-12, atol=1e-13)
         # a transposed weight matrix, a dropped bias or a bias added after the SpMM would show
-        assert not np.allclose(got, A @ (xi @ Wt.astype(np.float64)), rtol=1e-3) or A.size == 0 or not A.any()
+        assert not np.allclose(got, _brute(A, _brute(xi, W64)), rtol=1e-3) or A.size == 0 or not A.any()
         # scale: every stored entry counts with its absolute value (repeated pairs do not cancel)
         absA = _dense_of(dataclasses.replace(b, values=np.abs(b.values)), i)
-        want_T = absA @ (np.abs(xi) @ np.abs(Wt).astype(np.float64) + np.abs(bias).astype(np.float64))
+        want_T = _brute(absA, _brute(np.abs(xi), np.abs(W64)) + np.abs(bias64))
         assert np.allclose(T[int(b.c_row_off[i]):int(b.c_row_off[i]) + int(b.rows[i])], want_T,
                            rtol=1e-12, atol=1e-13)
 
@@ -608,7 +611,8 @@ def test_gcn_channels_accumulate_like_the_layer(oracle):
     b0 = bs[0]
     for i in range(b0.batch):
         xi = X[int(b0.b_row_off[i]):int(b0.b_row_off[i]) + int(b0.cols[i])].astype(np.float64)
-        want = sum(_dense_of(bs[c], i) @ (xi @ Ws[c].astype(np.float64) + biases[c].astype(np.float64))
+        want = sum(_brute(_dense_of(bs[c], i),
+                          _brute(xi, Ws[c].astype(np.float64)) + biases[c].astype(np.float64))
                    for c in range(chans))
         got = Y[int(b0.c_row_off[i]):int(b0.c_row_off[i]) + int(b0.rows[i])]
         assert np.allclose(got, want, rtol=1e-12, atol=1e-13)
