@@ -46,7 +46,18 @@ def parse_args():
 
 
 class Runner:
-    """Holds a plan and a rotating pool of dense operands for one workload."""
+    """Holds a plan and a pool of dense operand sets for one workload.
+
+    Rotation.  Launch number i of a pass reads input set i and writes output set i; a pass
+    goes once through the whole pool, and every measurement is laid out in whole passes, so a
+    launch always touches a set that the previous ``nsets - 1`` launches (more than the 256 MB
+    Infinity Cache plus the L2s of other traffic) did not: warm-up, timed and filler launches
+    share one rotation, whatever ``steps`` is.  A measurement of K launches is
+    ``[pass (untimed)] e0 [K // nsets passes + the first K % nsets sets] e1 [the rest of
+    that pass (untimed)]``.  The untimed pass in front also keeps the GPU busy while the host
+    enqueues the timed region, so the events bracket back-to-back kernels and not the host's
+    submission latency; that makes a 20-launch measurement agree with a 4000-launch one.
+    """
 
     def __init__(self, torch, K, batch, transposed=False, options=None, pool_bytes=POOL_BYTES,
                  plan=None):
@@ -59,6 +70,7 @@ class Runner:
         n_in = batch.n_c_rows if transposed else batch.n_b_rows
         n_out = batch.n_b_rows if transposed else batch.n_c_rows
         per_set = 4 * F * (n_in + n_out)
+        self.per_set_bytes = per_set
         self.nsets = max(2, min(512, -(-pool_bytes // max(per_set, 1))))
         self.inp = torch.rand((self.nsets, max(n_in, 1), F), dtype=torch.float32, device="cuda") * 2 - 1
         self.out = torch.empty((self.nsets, max(n_out, 1), F), dtype=torch.float32, device="cuda")
@@ -72,69 +84,121 @@ class Runner:
         self.flops = int(info.flops)
         self.workgroups = int(info.workgroups[d])
         self.info = info
-        if transposed:      # build the transposed CSR outside any timed or captured region
-            self.launch(0, torch.cuda.current_stream().cuda_stream)
-            torch.cuda.synchronize()
+        self._graphs = {}
+        # one launch outside any timed or captured region (builds the transposed CSR, if any)
+        self.launch(0, torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
 
-    def launch(self, i, stream, rotate=True):
-        s = i % self.nsets if rotate else 0
+    def launch(self, s, stream):
         rc = self.call(self.plan.handle, self.in_ptrs[s], self.out_ptrs[s], self.F, self.F, stream)
         if rc != 0:
             raise self.K.BspmmError(rc, "bench launch")
 
-    def time_eager(self, steps, warmup, rotate=True):
-        torch = self.torch
-        stream = torch.cuda.current_stream().cuda_stream
-        for i in range(warmup):
-            self.launch(i, stream, rotate)
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        torch.cuda.synchronize()
-        e0.record()
-        for i in range(steps):
-            self.launch(i, stream, rotate)
-        e1.record()
-        torch.cuda.synchronize()
-        return e0.elapsed_time(e1) * 1e-3 / steps
+    def rotation(self):
+        return (f"{self.nsets} dense operand sets ({self.nsets * self.per_set_bytes / 2**20:.0f} MiB) "
+                f"in one rotation shared by warm-up, timed and filler launches: a launch's set was "
+                f"last touched {self.nsets - 1} launches "
+                f"({(self.nsets - 1) * self.per_set_bytes / 2**20:.0f} MiB of other traffic) earlier")
 
-    def time_graph(self, steps, warmup, rotate=True):
-        """Capture one pass over the pool in a HIP graph and replay it: the launches of the
-        timed region are issued by the GPU's command processor, not by the Python loop."""
-        torch = self.torch
-        chunk = self.nsets if rotate else 64
-        chunk = max(1, min(chunk, steps))
-        g = torch.cuda.CUDAGraph()
-        side = torch.cuda.Stream()
-        side.wait_stream(torch.cuda.current_stream())
-        with torch.cuda.stream(side):
-            self.launch(0, side.cuda_stream, rotate)
-        torch.cuda.current_stream().wait_stream(side)
-        torch.cuda.synchronize()
-        with torch.cuda.graph(g):
-            cs = torch.cuda.current_stream().cuda_stream
-            for i in range(chunk):
-                self.launch(i, cs, rotate)
-        reps, rest = divmod(steps, chunk)
-        tail = None
-        if rest:            # exactly `steps` launches: a second graph holds what one pass leaves over
-            tail = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(tail):
+    def _graph(self, first, count, rotate):
+        """A HIP graph of `count` launches on sets first, first+1, ... (all on set 0 when not
+        rotating).  The launches of a replay are issued by the GPU's command processor."""
+        key = (first, count, rotate)
+        if key not in self._graphs:
+            torch = self.torch
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
                 cs = torch.cuda.current_stream().cuda_stream
-                for i in range(rest):
-                    self.launch(i, cs, rotate)
-        for _ in range(max(1, warmup // chunk)):
-            g.replay()
-        if tail is not None:
-            tail.replay()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                for i in range(count):
+                    self.launch((first + i) % self.nsets if rotate else 0, cs)
+            self._graphs[key] = g
+        return self._graphs[key]
+
+    def measure(self, steps, warmup, repeats=5, rotate=True, graph=True):
+        """Seconds per launch of `repeats` measurements of exactly `steps` launches each
+        (sorted), after `warmup` untimed launches (rounded up to whole passes)."""
+        torch = self.torch
+        n = self.nsets if rotate else min(256, max(steps, 1))
+        q, rem = divmod(steps, n)
+        stream = torch.cuda.current_stream()
+
+        def eager(first, count):
+            for i in range(count):
+                self.launch((first + i) % self.nsets if rotate else 0, stream.cuda_stream)
+
+        if graph:
+            whole, head = self._graph(0, n, rotate), (self._graph(0, rem, rotate) if rem else None)
+            rest = self._graph(rem, n - rem, rotate) if rem else None
+            run_pass, run_head = whole.replay, (head.replay if rem else None)
+            run_rest = rest.replay if rem else None
+        else:
+            run_pass = lambda: eager(0, n)
+            run_head = (lambda: eager(0, rem)) if rem else None
+            run_rest = (lambda: eager(rem, n - rem)) if rem else None
+        for _ in range(-(-max(warmup, 1) // n)):      # warm-up: whole passes, eager
+            eager(0, n)
+        if graph:                                       # and every graph once
+            run_pass()
+            if rem:
+                run_head()
+                run_rest()
         torch.cuda.synchronize()
-        e0.record()
-        for _ in range(reps):
-            g.replay()
-        if tail is not None:
-            tail.replay()
-        e1.record()
+        out = []
+        for _ in range(repeats):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            run_pass()                                  # untimed: GPU busy, rotation intact
+            e0.record()
+            for _ in range(q):
+                run_pass()
+            if rem:
+                run_head()
+            e1.record()
+            if rem:
+                run_rest()                              # untimed: completes the pass
+            torch.cuda.synchronize()
+            out.append(e0.elapsed_time(e1) * 1e-3 / steps)
+        return sorted(out)
+
+    def per_launch_slope(self, steps, repeats=5):
+        """Seconds per launch with the fixed cost of a graph replay taken out: the difference
+        between replays of `steps` and of 2 * `steps` launches (both inside one pass, GPU busy in
+        front as in measure()), divided by `steps`.  For measurements shorter than a pass, where
+        the replay's own start and end (about 10 us) are not amortised.  Median of `repeats`."""
+        torch = self.torch
+        k1 = max(1, min(steps, self.nsets // 2))
+        k2 = 2 * k1
+        whole = self._graph(0, self.nsets, True)
+        g1, g2 = self._graph(0, k1, True), self._graph(0, k2, True)
+        r1, r2 = self._graph(k1, self.nsets - k1, True), self._graph(k2, self.nsets - k2, True) \
+            if k2 < self.nsets else None
+        for g in (whole, g1, r1, g2, r2):
+            if g is not None:
+                g.replay()
         torch.cuda.synchronize()
-        return e0.elapsed_time(e1) * 1e-3 / steps, steps
+        out = []
+        for _ in range(repeats):
+            t = []
+            for g, rest in ((g1, r1), (g2, r2)):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                whole.replay()
+                e0.record()
+                g.replay()
+                e1.record()
+                if rest is not None:
+                    rest.replay()
+                torch.cuda.synchronize()
+                t.append(e0.elapsed_time(e1) * 1e-3)
+            out.append((t[1] - t[0]) / (k2 - k1))
+        return sorted(out)[len(out) // 2], (k1, k2)
+
+    def time_graph(self, steps, warmup, rotate=True, repeats=3):
+        """Median seconds per launch over `repeats` HIP-graph measurements of `steps` launches."""
+        r = self.measure(steps, warmup, repeats=repeats, rotate=rotate, graph=True)
+        return r[len(r) // 2], steps
+
+    def time_eager(self, steps, warmup, rotate=True, repeats=3):
+        r = self.measure(steps, warmup, repeats=repeats, rotate=rotate, graph=False)
+        return r[len(r) // 2]
 
     def summary(self, sec):
         return {"us_per_launch": round(sec * 1e6, 3),
@@ -379,24 +443,9 @@ def paper_grid(torch, K, W):
 def non_batched(torch, K, b, batched_sec):
     """The paper's comparison (Sec. V-A): the same graphs multiplied one launch per graph
     (a single-operation plan each, same kernel) against the one batched launch."""
-    import numpy as np
-    plans = []
     Bd = torch.rand((b.n_b_rows, b.F), dtype=torch.float32, device="cuda")
     Cd = torch.empty((b.n_c_rows, b.F), dtype=torch.float32, device="cuda")
-    for i in range(b.batch):
-        r0, z0 = int(b.rpt_off[i]), int(b.nz_off[i])
-        n, z = int(b.rows[i]), int(b.nnz[i])
-        one = type("One", (), {})()
-        one.F = b.F
-        one.rows, one.cols, one.nnz = b.rows[i:i + 1], b.cols[i:i + 1], b.nnz[i:i + 1]
-        one.rpt_off = np.zeros(1, np.int64)
-        one.nz_off = np.zeros(1, np.int64)
-        one.b_row_off = b.b_row_off[i:i + 1]
-        one.c_row_off = b.c_row_off[i:i + 1]
-        one.rpt = b.rpt[r0:r0 + n + 1]
-        one.colids = b.colids[z0:z0 + z]
-        one.values = b.values[z0:z0 + z]
-        plans.append(K.Plan(one))
+    plans = [K.Plan(b.single(i)) for i in range(b.batch)]
     stream = torch.cuda.current_stream().cuda_stream
     run = K.lib().bspmm_run
 
@@ -448,30 +497,38 @@ def parity_sample(torch, K, runner, oracle):
     return bool(np.all(np.abs(got - C) <= 1e-5 * S))
 
 
-def cpu_baseline(oracle, b, seconds):
-    """The oracle as it stands, on the host cores, looping over the same batch."""
-    oracle.forward_batch(b, want_scale=False)
-    reps, t0 = 0, time.perf_counter()
-    while True:
-        oracle.forward_batch(b, want_scale=False)
-        reps += 1
-        dt = time.perf_counter() - t0
-        if dt >= seconds:
-            break
-    out = {"value": round(b.n_graphs * reps / dt, 1), "unit": "graphs/s",
-           "cores": int(oracle.num_threads()), "kind": "oracle",
-           "sample": f"{reps} passes of the fp64 OpenMP oracle over the same 128-graph F=128 "
-                     f"batch in {dt:.1f} s (includes its output allocation)"}
-    # the same on one thread, 2 s
-    threads = oracle.num_threads()
+def cpu_baseline(oracle, b, seconds, eff_bytes, flops):
+    """The oracle as it stands, on the host cores: its C routine alone on the same batch
+    (arrays and the fp64 output prepared once, outside the clock), one warm-up call, then the
+    best of 5 samples of back-to-back calls; all host threads, and one thread."""
+    def leg(budget):
+        probe = min(oracle.time_forward_call(b, 3, samples=1))
+        calls = max(1, int(budget / 5 / max(probe, 1e-7)))
+        return min(oracle.time_forward_call(b, calls, samples=5)), calls
+
+    threads = int(oracle.num_threads())
+    best, calls = leg(seconds)
+    out = {"value": round(b.n_graphs / best, 1), "unit": "graphs/s", "cores": threads,
+           "kind": "oracle",
+           "sample": f"the C routine of the fp64 OpenMP oracle alone (preallocated output, no "
+                     f"Python marshalling) on the same {b.n_graphs}-graph F={b.F} batch: 1 warm-up "
+                     f"call, then best of 5 samples of {calls} back-to-back calls "
+                     f"(about {seconds:.0f} s of CPU work)",
+           "us_per_batch": round(best * 1e6, 2),
+           "gflops": round(flops / best * 1e-9, 2),
+           "eff_GBps": round(eff_bytes / best * 1e-9, 2),
+           "eff_bytes_note": "the same algorithmic bytes as the GPU line (fp32 operands and "
+                             "output; the oracle itself writes fp64)"}
     oracle.set_num_threads(1)
-    reps1, t0 = 0, time.perf_counter()
-    while time.perf_counter() - t0 < 2.0:
-        oracle.forward_batch(b, want_scale=False)
-        reps1 += 1
-    dt1 = time.perf_counter() - t0
-    oracle.set_num_threads(threads)
-    out["one_thread_value"] = round(b.n_graphs * reps1 / dt1, 1)
+    try:
+        best1, calls1 = leg(min(3.0, seconds))
+    finally:
+        oracle.set_num_threads(threads)
+    out["one_thread"] = {"value": round(b.n_graphs / best1, 1), "cores": 1,
+                         "us_per_batch": round(best1 * 1e6, 2),
+                         "gflops": round(flops / best1 * 1e-9, 2),
+                         "eff_GBps": round(eff_bytes / best1 * 1e-9, 2),
+                         "calls_per_sample": calls1}
     return out
 
 
@@ -517,12 +574,14 @@ def main():
     b = W.config2_molecule(F=128)
     head = Runner(torch, K, b)
     phase_marker(torch, 1)          # phase 1: headline, HIP-graph replay, rotating operands
-    sec_graph, timed_steps = head.time_graph(args.steps, args.warmup)
+    reps_graph = head.measure(args.steps, args.warmup, repeats=5, graph=True)
     phase_marker(torch, 2)          # phase 2: headline, eager launches, rotating operands
-    sec_eager = head.time_eager(args.steps, args.warmup)
+    reps_eager = head.measure(args.steps, args.warmup, repeats=5, graph=False)
     phase_marker(torch, 3)          # phase 3: everything else
+    sec_graph, sec_eager = reps_graph[2], reps_eager[2]      # medians of five
     sec = min(sec_graph, sec_eager)
     launch_mode = "hipgraph_replay" if sec_graph <= sec_eager else "eager"
+    reps_head = reps_graph if sec_graph <= sec_eager else reps_eager
 
     extra = {}
     parity_ok = None
@@ -544,12 +603,29 @@ def main():
         warm, _ = head.time_graph(args.steps, args.warmup, rotate=False)
         extra["headline_cache_warm"] = head.summary(warm)
         floor = Runner(torch, K, b, options=K.make_options(flags=K.FLOOR_PROBE))
-        fsec, _ = floor.time_graph(args.steps, args.warmup)
-        extra["launch_floor_us"] = round(fsec * 1e6, 3)
-        reps = sorted(head.time_graph(args.steps, args.warmup)[0] for _ in range(5))
-        extra["headline_hipgraph_5_repeats_us"] = {"median": round(reps[2] * 1e6, 3),
-                                                   "min": round(reps[0] * 1e6, 3),
-                                                   "max": round(reps[4] * 1e6, 3)}
+        freps = min(floor.measure(args.steps, args.warmup, repeats=5, graph=True),
+                    floor.measure(args.steps, args.warmup, repeats=5, graph=False),
+                    key=lambda r: r[2])
+        extra["launch_floor_us"] = round(freps[2] * 1e6, 3)
+        extra["launch_floor_5_repeats_us"] = {"median": round(freps[2] * 1e6, 3),
+                                              "min": round(freps[0] * 1e6, 3),
+                                              "max": round(freps[4] * 1e6, 3)}
+        if args.steps < head.nsets:
+            # shorter than one pass over the pool: a replay's own start and end are not
+            # amortised over the timed launches; the two-point slope leaves them out
+            sl, ks = head.per_launch_slope(args.steps)
+            fl, _ = floor.per_launch_slope(args.steps)
+            extra["headline_us_per_launch_without_replay_cost"] = {
+                "us": round(sl * 1e6, 3), "launch_floor_us": round(fl * 1e6, 3),
+                "method": f"(replay of {ks[1]} launches - replay of {ks[0]} launches) / {ks[1] - ks[0]}, "
+                          f"HIP graph, same rotation, median of 5"}
+        del floor
+        extra["headline_hipgraph_5_repeats_us"] = {"median": round(reps_graph[2] * 1e6, 3),
+                                                   "min": round(reps_graph[0] * 1e6, 3),
+                                                   "max": round(reps_graph[4] * 1e6, 3)}
+        extra["headline_eager_5_repeats_us"] = {"median": round(reps_eager[2] * 1e6, 3),
+                                                "min": round(reps_eager[0] * 1e6, 3),
+                                                "max": round(reps_eager[4] * 1e6, 3)}
         extra["plan_create_ms"] = round(head.create_ms, 3)
         # the paper's batched timings include handing the matrix list to the device: plan
         # creation through the C ABI (schedule, upload) plus one product, device arrays in place
@@ -621,7 +697,7 @@ def main():
         "value": round(b.n_graphs / sec, 1),
         "unit": "graphs/s",
         "n_gpus": 1,
-        "steps": int(timed_steps if launch_mode == "hipgraph_replay" else args.steps),
+        "steps": int(args.steps),
         "warmup": args.warmup,
         "ms_per_step": round(sec * 1e3, 6),
         "higher_is_better": True,
@@ -633,7 +709,11 @@ def main():
                                "25 nodes, degree <= 6, self-loops, symmetric normalisation), "
                                "F=128, forward",
                    "seed": W.config_seed(2), "checksum": b.checksum(),
-                   "operands": f"hbm_cold: {head.nsets} dense operand sets rotated",
+                   "operands": "hbm_cold: " + head.rotation(),
+                   "repeats": {"n": 5, "median_us": round(reps_head[2] * 1e6, 3),
+                               "min_us": round(reps_head[0] * 1e6, 3),
+                               "max_us": round(reps_head[4] * 1e6, 3),
+                               "value_from": "median"},
                    "launch": launch_mode, "one_launch_per_batch": True,
                    "gflops": round(head.flops / sec * 1e-9, 2),
                    },
@@ -641,10 +721,13 @@ def main():
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(head.eff_bytes / sec * 1e-9 / HBM_PEAK_GBPS, 4),
                      "traffic": read_traffic(),
+                     "traffic_source": "committed rocprofv3 counter summary profiles/"
+                                       "bspmm_kernel_cfg2_F128_pmc.txt (a separate run of this "
+                                       "workload, not measured by this process)",
                      "kernel": "bspmm_kernel<4>", "bytes_per_launch": head.eff_bytes},
     }
     if not args.no_cpu:
-        out["cpu_baseline"] = cpu_baseline(oracle, b, args.cpu_seconds)
+        out["cpu_baseline"] = cpu_baseline(oracle, b, args.cpu_seconds, head.eff_bytes, head.flops)
         out["cpu_baseline"]["gpu_launch_within_tolerance_of_it"] = parity_ok
     if extra:
         out["extra"] = extra

@@ -230,8 +230,9 @@ int bspmm_workspace_bytes(const bspmm_batch* b, int32_t F, const bspmm_options* 
 /*
  * Inspect the batch, bin every operation, tile the feature dimension, build the work lists
  * for the forward and the transposed product and upload them to `workspace` (one async copy
- * on `stream`); Sec. IV-C's "decide cache blocking and resource assignment from the sizes of
- * the inputs", done per operation instead of from the batch maximum.
+ * on `stream`).  This is the step of Sec. IV-C that sizes the launch and picks the cache
+ * blocking from the shapes of the inputs, done here per operation instead of from the batch
+ * maximum.
  * Returns EINVAL for null/negative/inconsistent arguments or F <= 0, EOVERLAP when two
  * operations' C blocks overlap (with BSPMM_ACCUMULATE: overlap without being identical),
  * ETOOBIG, ENOSPACE, EHIP.  On error *plan is NULL.

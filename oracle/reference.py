@@ -110,6 +110,34 @@ def forward(rows, cols, nnz, rpt_off, nz_off, b_row_off, c_row_off, rpt, colids,
     return C, S
 
 
+def time_forward_call(b, calls: int, samples: int = 5):
+    """Wall time of the C routine alone on a Batch-like object: arrays converted and the fp64
+    output allocated once, outside the clock; one warm-up call, then ``samples`` timed runs of
+    ``calls`` back-to-back calls each.  Returns the list of seconds per call, one per sample.
+    (The scale S is not computed: the baseline times the product only.)"""
+    import time
+    lib = _load()
+    a = _prep(b.rows, b.cols, b.nnz, b.rpt_off, b.nz_off, b.b_row_off, b.c_row_off, b.rpt,
+              b.colids, b.values)
+    B = np.ascontiguousarray(b.B, dtype=np.float32)
+    F = int(B.shape[1])
+    C = np.zeros((int(b.n_c_rows), F), dtype=np.float64)
+    args = (int(a[0].shape[0]), _p(a[0], ctypes.c_int32), _p(a[1], ctypes.c_int32),
+            _p(a[2], ctypes.c_int32), _p(a[3], ctypes.c_int64), _p(a[4], ctypes.c_int64),
+            _p(a[5], ctypes.c_int64), _p(a[6], ctypes.c_int64), _p(a[7], ctypes.c_int32),
+            _p(a[8], ctypes.c_int32), _p(a[9], ctypes.c_float), _p(B, ctypes.c_float),
+            F, F, _p(C, ctypes.c_double), None, F)
+    if lib.oracle_bspmm_forward(*args) != 0:
+        raise ValueError("oracle: malformed operation")
+    out = []
+    for _ in range(int(samples)):
+        t0 = time.perf_counter()
+        for _ in range(int(calls)):
+            lib.oracle_bspmm_forward(*args)
+        out.append((time.perf_counter() - t0) / max(int(calls), 1))
+    return out
+
+
 def transposed(rows, cols, nnz, rpt_off, nz_off, b_row_off, c_row_off, rpt, colids, values,
                dY: np.ndarray, n_b_rows: int, want_scale: bool = True
                ) -> Tuple[np.ndarray, Optional[np.ndarray]]:

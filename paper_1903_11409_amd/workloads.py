@@ -3,8 +3,8 @@
 A *batch* is a list of independent SpMM operations ``C_i = A_i . B_i`` (paper Sec. IV-C): every
 ``A_i`` is a small CSR matrix (row pointer / column index / value arrays, Sec. II-B), every
 ``B_i`` is a row slice of one packed row-major dense matrix whose column count ``F`` (the
-paper's ``n_B``) is the same for the whole batch (Sec. IV, "each column size of dense input in the
-batch is same"; packed layout as in the reshaped input of Sec. IV-D).
+paper's ``n_B``) is the same for the whole batch (Sec. IV; packed layout as in the reshaped
+input of Sec. IV-D).
 
 The paper evaluates on Tox21 / Reaction100 molecule graphs (Table 1: at most 50 nodes, batch
 50-200, n_B 64/512) and on random square matrices (Sec. V-A: dim 32-256, nnz/row 1-5).  Neither
@@ -83,6 +83,16 @@ class Batch:
         if self.dY is not None:
             h.update(np.ascontiguousarray(self.dY).tobytes())
         return h.hexdigest()[:16]
+
+    def single(self, i: int) -> "Batch":
+        """Operation ``i`` alone, as a batch of one that still reads and writes its rows of the
+        packed dense matrices (the non-batched route of Sec. V-A: one launch per matrix)."""
+        rpt, ci, va = self.op_csr(i)
+        z = np.zeros(1, dtype=np.int64)
+        return dataclasses.replace(
+            self, name=f"{self.name}[{i}]", rows=self.rows[i:i + 1], cols=self.cols[i:i + 1],
+            nnz=self.nnz[i:i + 1], rpt_off=z, nz_off=z.copy(), b_row_off=self.b_row_off[i:i + 1],
+            c_row_off=self.c_row_off[i:i + 1], rpt=rpt, colids=ci, values=va, n_graphs=1)
 
     def with_F(self, F: int, seed: int) -> "Batch":
         """Same sparse structure, fresh dense input of width ``F``."""
