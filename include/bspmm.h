@@ -242,6 +242,24 @@ int bspmm_create(bspmm_plan** plan, const bspmm_batch* b, int32_t F,
                  void* stream);
 
 /*
+ * bspmm_create for callers that cannot allocate device memory (code under HIP-graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc): the same plan, but its workspace is an
+ * array of BSPMM_STATIC_WORKSPACE_BYTES bytes that is part of the library's device code on every
+ * GPU, so the caller passes none and the call allocates no device memory.  The GPU is the
+ * calling thread's current device; `stream` must belong to it.
+ *  - ENOSPACE when the plan needs more than BSPMM_STATIC_WORKSPACE_BYTES (bspmm_workspace_bytes
+ *    tells in advance); BSPMM_DRY_RUN is EINVAL; otherwise arguments and errors as bspmm_create.
+ *  - All such plans of a GPU share the one array, which keeps what the last one wrote.  Nothing
+ *    in it has to start at zero: every table is written in full before it is read.  Only the
+ *    latest static plan of a GPU is valid; run, export and validate calls on an earlier one
+ *    return ESTATE.  The caller orders the streams: work of the earlier plan that is still
+ *    running when the next bspmm_create_static uploads its tables races with that upload.
+ */
+#define BSPMM_STATIC_WORKSPACE_BYTES (8 * 1024 * 1024)
+int bspmm_create_static(bspmm_plan** plan, const bspmm_batch* b, int32_t F,
+                        const bspmm_options* options, void* stream);
+
+/*
  * C_i = A_i . B_i for every operation, one kernel launch on `stream` (Fig. 4 per row, batched
  * as in Sec. IV-C).  B and C are DEVICE pointers to the packed matrices, ldb/ldc their leading
  * dimensions in floats (>= F).  B and C must not alias.  A plan with batch == 0 launches

@@ -75,7 +75,9 @@ class bspmm_item(ctypes.Structure):
 EXPORTS = ["bspmm_workspace_bytes", "bspmm_create", "bspmm_run", "bspmm_run_transposed",
            "bspmm_export_transposed", "bspmm_validate", "bspmm_plan_info", "bspmm_plan_items",
            "bspmm_destroy", "bspmm_strerror", "bspmm_last_hip_error",
-           "bspmm_workspace_bytes_coo", "bspmm_create_coo", "bspmm_export_csr", "bspmm_run_gcn"]
+           "bspmm_workspace_bytes_coo", "bspmm_create_coo", "bspmm_export_csr", "bspmm_run_gcn",
+           "bspmm_create_static"]
+STATIC_WORKSPACE_BYTES = 8 * 1024 * 1024
 
 _lib = None
 
@@ -105,6 +107,8 @@ def lib():
         L.bspmm_create.argtypes = [ctypes.POINTER(vp), ctypes.POINTER(bspmm_batch),
                                    ctypes.c_int32, ctypes.POINTER(bspmm_options), vp,
                                    ctypes.c_size_t, vp]
+        L.bspmm_create_static.argtypes = [ctypes.POINTER(vp), ctypes.POINTER(bspmm_batch),
+                                          ctypes.c_int32, ctypes.POINTER(bspmm_options), vp]
         L.bspmm_run.argtypes = [vp, vp, vp, ctypes.c_int64, ctypes.c_int64, vp]
         L.bspmm_run_transposed.argtypes = [vp, vp, vp, ctypes.c_int64, ctypes.c_int64, vp]
         L.bspmm_export_transposed.argtypes = [vp, vp, vp, vp, vp]
@@ -270,6 +274,16 @@ def bspmm_create(hb: HostBatch, F: int, options: Optional[bspmm_options] = None,
                               ctypes.byref(options) if options is not None else None,
                               _ptr(workspace), int(workspace_bytes),
                               None if dry else _stream_handle(stream)), "bspmm_create")
+    return plan.value
+
+
+def bspmm_create_static(hb: HostBatch, F: int, options: Optional[bspmm_options] = None,
+                        stream=None) -> int:
+    """Plan whose workspace is the library's static device array; returns the plan handle."""
+    plan = ctypes.c_void_p(None)
+    _check(lib().bspmm_create_static(ctypes.byref(plan), ctypes.byref(hb.struct), int(F),
+                                     ctypes.byref(options) if options is not None else None,
+                                     _stream_handle(stream)), "bspmm_create_static")
     return plan.value
 
 

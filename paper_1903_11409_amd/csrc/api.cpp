@@ -1,8 +1,11 @@
 // C ABI of libbspmm (see include/bspmm.h for the contract of every entry point).
+#include <hip/hip_runtime.h>
 #include <hip/hip_runtime_api.h>
 
 #include <algorithm>
+#include <atomic>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <set>
 #include <memory>
@@ -44,6 +47,12 @@ static long long* g_trace = nullptr;
 extern "C" void bspmm_set_trace(void* p) { g_trace = static_cast<long long*>(p); }
 #endif
 
+// Workspace of plans made by bspmm_create_static: device memory that belongs to the library's
+// code object, so no allocation is needed to get it.  Every GPU the library runs on holds its own
+// copy at its own address until the process ends.  In host code this name is only a handle for
+// hipGetSymbolAddress (see static_workspace below); it is never passed to a kernel or a copy.
+static __device__ __align__(256) unsigned char scratch[BSPMM_STATIC_WORKSPACE_BYTES];
+
 namespace {
 
 thread_local int g_last_hip_error = 0;
@@ -77,6 +86,8 @@ struct Layout {
 }  // namespace
 
 struct bspmm_plan {
+    int static_device = -1;         // >= 0: the workspace is that device's static array ...
+    uint64_t static_generation = 0; // ... as handed out by this call of bspmm_create_static
     int32_t batch = 0;
     int32_t F = 0;
     bool dry = false;
@@ -902,6 +913,41 @@ int run_gcn(bspmm_plan* p, const float* X, int64_t ldx, const float* W, int64_t 
     return e == hipSuccess ? BSPMM_OK : hip_fail(e);
 }
 
+// The static workspace of the current device.  Its device address is asked for once per device
+// (with that device current) and kept; every later use goes through the kept pointer.  The
+// generation counts the plans handed out on a device: only the latest owns the array.
+constexpr int kMaxDevices = 64;
+std::mutex g_static_mutex;
+void* g_static_ptr[kMaxDevices] = {};
+std::atomic<uint64_t> g_static_generation[kMaxDevices];
+
+int static_workspace(int* device, void** ptr)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e);
+    if (dev < 0 || dev >= kMaxDevices) return BSPMM_EINVAL;
+    std::lock_guard<std::mutex> lock(g_static_mutex);
+    if (!g_static_ptr[dev]) {
+        void* q = nullptr;
+        e = hipGetSymbolAddress(&q, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return hip_fail(e);
+        if (!q || (reinterpret_cast<uintptr_t>(q) & (kAlign - 1)) != 0) return BSPMM_EINVAL;
+        g_static_ptr[dev] = q;
+    }
+    *device = dev;
+    *ptr = g_static_ptr[dev];
+    return BSPMM_OK;
+}
+
+// A plan made by bspmm_create_static that a later one on the same device has displaced must
+// not run: the tables it points at are no longer its own.
+bool displaced(const bspmm_plan* p)
+{
+    return p->static_device >= 0 &&
+           g_static_generation[p->static_device].load(std::memory_order_acquire) != p->static_generation;
+}
+
 // bspmm_workspace_bytes has to schedule the batch to know the size; a bspmm_create that follows
 // on the same thread with the same arguments takes that plan over instead of scheduling again.
 // The key holds the argument values and a hash of the host arrays' contents.
@@ -1023,6 +1069,42 @@ int bspmm_create(bspmm_plan** plan, const bspmm_batch* b, int32_t F,
     return BSPMM_OK;
 }
 
+int bspmm_create_static(bspmm_plan** plan, const bspmm_batch* b, int32_t F,
+                        const bspmm_options* options, void* stream)
+{
+    if (!plan) return BSPMM_EINVAL;
+    *plan = nullptr;
+    if (options && (options->flags & BSPMM_DRY_RUN)) return BSPMM_EINVAL;
+    int rc = check_batch(b, F, true);
+    if (rc != BSPMM_OK) return rc;
+    int dev = -1;
+    void* ws = nullptr;
+    rc = static_workspace(&dev, &ws);
+    if (rc != BSPMM_OK) return rc;
+    bspmm_plan* p = new (std::nothrow) bspmm_plan;
+    if (!p) return BSPMM_EINVAL;
+    rc = plan_with_budget(*p, b, F, options, false, plan_host);
+    if (rc == BSPMM_OK && p->lay.total > (size_t)BSPMM_STATIC_WORKSPACE_BYTES) rc = BSPMM_ENOSPACE;
+    if (rc == BSPMM_OK) {
+        p->rpt = b->rpt;
+        p->colids = b->colids;
+        p->values = b->values;
+        // from here on the array belongs to this plan: earlier static plans of the device are
+        // displaced before anything is written over their tables
+        p->static_device = dev;
+        p->static_generation =
+            g_static_generation[dev].fetch_add(1, std::memory_order_acq_rel) + 1;
+        rc = upload_plan(p, options, ws, (size_t)BSPMM_STATIC_WORKSPACE_BYTES,
+                         static_cast<hipStream_t>(stream));
+    }
+    if (rc != BSPMM_OK) {
+        delete p;
+        return rc;
+    }
+    *plan = p;
+    return BSPMM_OK;
+}
+
 int bspmm_workspace_bytes_coo(const bspmm_coo_batch* b, int32_t F, const bspmm_options* options,
                               size_t* bytes)
 {
@@ -1096,7 +1178,7 @@ int bspmm_run(bspmm_plan* plan, const float* B, float* C, int64_t ldb, int64_t l
               void* stream)
 {
     if (!plan) return BSPMM_EINVAL;
-    if (plan->dry) return BSPMM_ESTATE;
+    if (plan->dry || displaced(plan)) return BSPMM_ESTATE;
     return run_direction(plan, 0, B, C, ldb, ldc, static_cast<hipStream_t>(stream));
 }
 
@@ -1104,7 +1186,7 @@ int bspmm_run_gcn(bspmm_plan* plan, const float* X, int64_t ldx, const float* W,
                   const float* bias, float* Y, int64_t ldy, int32_t accumulate, void* stream)
 {
     if (!plan) return BSPMM_EINVAL;
-    if (plan->dry || plan->knobs.front <= 0 || plan->coo_direct) return BSPMM_ESTATE;
+    if (plan->dry || plan->knobs.front <= 0 || plan->coo_direct || displaced(plan)) return BSPMM_ESTATE;
     return run_gcn(plan, X, ldx, W, ldw, bias, Y, ldy, accumulate, static_cast<hipStream_t>(stream));
 }
 
@@ -1112,7 +1194,7 @@ int bspmm_run_transposed(bspmm_plan* plan, const float* dY, float* G, int64_t ld
                          void* stream)
 {
     if (!plan) return BSPMM_EINVAL;
-    if (plan->dry || !plan->transposed_supported) return BSPMM_ESTATE;
+    if (plan->dry || !plan->transposed_supported || displaced(plan)) return BSPMM_ESTATE;
     if (plan->coo_direct)
         return run_direction(plan, 1, dY, G, ldy, ldg, static_cast<hipStream_t>(stream));
     if (plan->sched[1].grid > 0 && ((!dY && plan->reads_dense) || !G || ldy < plan->F || ldg < plan->F))
@@ -1126,7 +1208,7 @@ int bspmm_export_transposed(bspmm_plan* plan, int32_t* rpt_t, int32_t* colids_t,
                             float* values_t, void* stream)
 {
     if (!plan) return BSPMM_EINVAL;
-    if (plan->dry || plan->coo_direct || plan->knobs.symmetric) return BSPMM_ESTATE;
+    if (plan->dry || plan->coo_direct || plan->knobs.symmetric || displaced(plan)) return BSPMM_ESTATE;
     hipStream_t s = static_cast<hipStream_t>(stream);
     int rc = enqueue_build(plan, s);
     if (rc != BSPMM_OK) return rc;
@@ -1155,7 +1237,7 @@ int bspmm_export_transposed(bspmm_plan* plan, int32_t* rpt_t, int32_t* colids_t,
 int bspmm_validate(bspmm_plan* plan, int32_t* bad_op, void* stream)
 {
     if (!plan) return BSPMM_EINVAL;
-    if (plan->dry) return BSPMM_ESTATE;
+    if (plan->dry || displaced(plan)) return BSPMM_ESTATE;
     if (bad_op) *bad_op = -1;
     hipStream_t s = static_cast<hipStream_t>(stream);
     int32_t* flag = reinterpret_cast<int32_t*>(plan->ws + plan->lay.flag);
