@@ -199,6 +199,9 @@ typedef struct bspmm_info {
     int32_t fused_tasks[2];                  /* tasks that add up several operations          */
     int32_t transposed_supported;            /* 0 when input-gradient blocks overlap          */
     int32_t transposed_built;                /* the build kernel has been enqueued            */
+    int32_t lean[2];                         /* 1: every task is one staged workgroup item with a
+                                                power-of-two tile, so runs with 16-byte aligned
+                                                operands launch the lean kernel                */
     int64_t effective_bytes[2];              /* CSR + distinct dense inputs + outputs, once   */
     int64_t flops;                           /* 2 * nnz * F (Sec. V-A)                        */
     uint64_t workspace_bytes;

@@ -62,6 +62,7 @@ class bspmm_info(ctypes.Structure):
                 ("fused_tasks", ctypes.c_int32 * 2),
                 ("transposed_supported", ctypes.c_int32),
                 ("transposed_built", ctypes.c_int32),
+                ("lean", ctypes.c_int32 * 2),
                 ("effective_bytes", ctypes.c_int64 * 2), ("flops", ctypes.c_int64),
                 ("workspace_bytes", ctypes.c_uint64)]
 

@@ -28,6 +28,11 @@ def build(verbose: bool = False) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           # kernels whose arguments are plain pointers and integers get them in SGPRs when a
+           # wavefront starts (the command processor fills up to 16 of them): their first
+           # dependent fetch, the work item, goes out at once instead of after a kernel-argument
+           # load
+           "-mllvm", "-amdgpu-kernarg-preload-count=16",
            "-Wall", "-Wno-unused-command-line-argument",
            "-x", "hip", os.path.join(CSRC, "kernels.hip"),
            "-x", "hip", os.path.join(CSRC, "schedule.cpp"),

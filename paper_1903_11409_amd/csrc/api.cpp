@@ -19,6 +19,8 @@
 namespace bspmm {
 hipError_t launch_bspmm(const LaunchParams& P, int grid, int lds_bytes, bool vec4, bool slices,
                         bool hubs, bool merged, hipStream_t stream);
+hipError_t launch_bspmm_lean(const LeanItem* items, const LaunchParams& P, int grid, int lds_bytes,
+                             hipStream_t stream);
 hipError_t launch_bspmm_gcn(const LaunchParams& P, int grid, int lds_bytes, bool accumulate,
                             bool sets, hipStream_t stream);
 hipError_t launch_build_transpose(const OpRecord* ops, int batch, int lds_bytes,
@@ -42,10 +44,6 @@ hipError_t launch_validate(const OpRecord* ops, int batch, const int32_t* rpt,
 
 using namespace bspmm;
 
-#ifdef BSPMM_TRACE
-static long long* g_trace = nullptr;
-extern "C" void bspmm_set_trace(void* p) { g_trace = static_cast<long long*>(p); }
-#endif
 
 // Workspace of plans made by bspmm_create_static: device memory that belongs to the library's
 // code object, so no allocation is needed to get it.  Every GPU the library runs on holds its own
@@ -69,6 +67,7 @@ size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 // Where each table sits inside the workspace (byte offsets).
 struct Layout {
     size_t items[2] = {0, 0};
+    size_t lean[2] = {0, 0};     // item tables of the lean kernel (empty when a direction is not lean)
     size_t op_records = 0;
     size_t rpt_t = 0, colids_t = 0, values_t = 0;
     size_t scratch = 0;
@@ -95,6 +94,9 @@ struct bspmm_plan {
     DirOps dir[2];
     Schedule sched[2];
     std::vector<OpRecord> records;
+    std::vector<LeanItem> lean_items[2];   // per direction: the items again, for the lean kernel
+    int32_t lean_rows[2] = {0, 0};         // most input rows / output rows of an operation: bounds
+    int32_t lean_out_rows[2] = {0, 0};     // of the 32-bit offsets the lean kernel forms per call
     std::vector<char> tables;   // host image of the workspace's front: item tables and records
     Layout lay;
     int build_lds_bytes = 0;
@@ -241,6 +243,48 @@ void describe_sets(bspmm_plan& p, int d)
             sc.items[j].rpt_off = r.merged_rpt_off;
             sc.items[j].nz_off = r.merged_nz_off;
         }
+}
+
+// The item table of the lean kernel for direction d, when the schedule is lean and every offset
+// fits the table's 32-bit fields (else the direction keeps the general kernel).
+void make_lean_items(bspmm_plan& p, int d)
+{
+    const Schedule& sc = p.sched[d];
+    std::vector<LeanItem>& out = p.lean_items[d];
+    out.clear();
+    if (!sc.lean) return;
+    out.reserve(sc.items.size());
+    constexpr int64_t kLimit = (int64_t)1 << 31;
+    int32_t most_k = 0, most_m = 0;
+    for (const WorkItem& w : sc.items) {
+        LeanItem t;
+        std::memset(&t, 0, sizeof t);
+        if (w.nrows > 0) {
+            if (w.rpt_off >= kLimit || w.nz_off >= kLimit || w.in_row_off >= kLimit ||
+                w.out_row_off >= kLimit) {
+                out.clear();
+                return;
+            }
+            const StagedLayout L = staged_layout(w.m, w.k, w.nnz, w.fw, 0, false);
+            int sh = 0;
+            while ((4 << sh) < w.fw) ++sh;
+            t.rpt_off = (uint32_t)w.rpt_off;
+            t.nz_off = (uint32_t)w.nz_off;
+            t.in_row = (uint32_t)w.in_row_off;
+            t.out_row = (uint32_t)w.out_row_off;
+            t.m = w.m, t.k = w.k, t.nnz = w.nnz, t.row0 = w.row0, t.nrows = w.nrows, t.f0 = w.f0;
+            t.sh = sh;
+            t.stream = (w.staged & 2) ? 1 : 0;
+            t.cv_byte = 4 * L.cv_off;
+            t.b_byte = 4 * L.b_off;
+            t.tile_vecs = w.k << sh;
+            most_k = std::max(most_k, w.k);
+            most_m = std::max(most_m, w.m);
+        }
+        out.push_back(t);
+    }
+    p.lean_rows[d] = most_k;
+    p.lean_out_rows[d] = most_m;
 }
 
 // Fill everything of the plan that needs no device.
@@ -394,6 +438,11 @@ int plan_host(bspmm_plan& p, const bspmm_batch* b, int32_t F, const Knobs& kn)
     for (int d = 0; d < 2; ++d) {
         L.items[d] = at;
         at = align_up(at + p.sched[d].items.size() * sizeof(WorkItem));
+    }
+    for (int d = 0; d < 2; ++d) {
+        make_lean_items(p, d);
+        L.lean[d] = at;
+        at = align_up(at + p.lean_items[d].size() * sizeof(LeanItem));
     }
     L.op_records = at;
     at = align_up(at + (size_t)n * sizeof(OpRecord));
@@ -635,14 +684,20 @@ int run_direction(bspmm_plan* p, int d, const float* in, float* out, int64_t ld_
     P.ld_w = 0;
     P.n_front = 0;
     P.accumulate = 0;
-#ifdef BSPMM_TRACE
-    P.trace = g_trace;
-#endif
     const bool vec4 = p->F % 4 == 0 && ld_in % 4 == 0 && ld_out % 4 == 0 &&
                       (reinterpret_cast<uintptr_t>(in) & 15) == 0 &&
                       (reinterpret_cast<uintptr_t>(out) & 15) == 0;
-    hipError_t e = launch_bspmm(P, sc.launch_grid, p->knobs.lds_words * 4, vec4, sc.has_slices,
-                                p->knobs.hubs, !sc.merged_sets.empty(), s);
+    // the lean kernel forms 32-bit byte offsets inside an operation's dense blocks and multiplies
+    // in 24 bits: leading dimensions below 4 Mi floats, blocks below 4 GiB
+    constexpr int64_t kMul24 = (int64_t)1 << 22, kOff32 = (int64_t)1 << 30;
+    const bool lean = vec4 && !p->lean_items[d].empty() && ld_in < kMul24 && ld_out < kMul24 &&
+                      (int64_t)p->lean_rows[d] * ld_in < kOff32 &&
+                      (int64_t)p->lean_out_rows[d] * ld_out < kOff32;
+    hipError_t e = lean
+        ? launch_bspmm_lean(reinterpret_cast<const LeanItem*>(p->ws + p->lay.lean[d]), P,
+                            sc.launch_grid, p->knobs.lds_words * 4, s)
+        : launch_bspmm(P, sc.launch_grid, p->knobs.lds_words * 4, vec4, sc.has_slices,
+                       p->knobs.hubs, !sc.merged_sets.empty(), s);
     return e == hipSuccess ? BSPMM_OK : hip_fail(e);
 }
 
@@ -798,7 +853,8 @@ int upload_plan(bspmm_plan* p, const bspmm_options* options, void* workspace,
 {
     if (options && (options->flags & BSPMM_FLOOR_PROBE))
         for (int d = 0; d < 2; ++d) {
-            for (WorkItem& w : p->sched[d].items) w.nrows = 0;
+            for (WorkItem& w : p->sched[d].items) w.nrows = w.m = w.k = w.nnz = 0;
+            for (LeanItem& w : p->lean_items[d]) w.nrows = w.m = w.k = w.nnz = w.tile_vecs = 0;
             for (CooItem& w : p->coo_sched[d].items) w.nrows = w.nnz = 0;
         }
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & (kAlign - 1)) != 0)
@@ -818,6 +874,10 @@ int upload_plan(bspmm_plan* p, const bspmm_options* options, void* workspace,
             if (!p->sched[d].items.empty())
                 std::memcpy(p->tables.data() + p->lay.items[d], p->sched[d].items.data(),
                             p->sched[d].items.size() * sizeof(WorkItem));
+        for (int d = 0; d < 2; ++d)
+            if (!p->lean_items[d].empty())
+                std::memcpy(p->tables.data() + p->lay.lean[d], p->lean_items[d].data(),
+                            p->lean_items[d].size() * sizeof(LeanItem));
         if (!p->records.empty())
             std::memcpy(p->tables.data() + p->lay.op_records, p->records.data(),
                         p->records.size() * sizeof(OpRecord));
@@ -906,9 +966,6 @@ int run_gcn(bspmm_plan* p, const float* X, int64_t ldx, const float* W, int64_t 
     P.ld_w = ldw;
     P.n_front = nx;
     P.accumulate = accumulate ? 1 : 0;
-#ifdef BSPMM_TRACE
-    P.trace = g_trace;
-#endif
     hipError_t e = launch_bspmm_gcn(P, sc.grid, sc.front_lds_words * 4, accumulate != 0, sets, s);
     return e == hipSuccess ? BSPMM_OK : hip_fail(e);
 }
@@ -1283,6 +1340,7 @@ int bspmm_plan_info(const bspmm_plan* plan, bspmm_info* info)
     }
     info->transposed_supported = plan->transposed_supported ? 1 : 0;
     info->transposed_built = plan->transposed_built ? 1 : 0;
+    for (int d = 0; d < 2; ++d) info->lean[d] = plan->lean_items[d].empty() ? 0 : 1;
     info->flops = plan->flops;
     info->workspace_bytes = plan->lay.total;
     return BSPMM_OK;

@@ -60,9 +60,6 @@ __device__ __forceinline__ void store_vec(float* p, const typename Vec<VEC>::typ
 template <int VEC>
 __device__ __forceinline__ void store_out(float* p, const typename Vec<VEC>::type& v)
 {
-#ifdef BSPMM_NO_NT
-    store_vec<VEC>(p, v);
-#else
     if constexpr (VEC == 4) {
         typedef float native4 __attribute__((ext_vector_type(4)));
         native4 n = {v.x, v.y, v.z, v.w};
@@ -70,7 +67,6 @@ __device__ __forceinline__ void store_out(float* p, const typename Vec<VEC>::typ
     } else {
         __builtin_nontemporal_store(v, p);
     }
-#endif
 }
 
 __device__ __forceinline__ int ilog2(int pow2) { return 31 - __clz(pow2); }
@@ -507,17 +503,6 @@ __device__ __forceinline__ void run_generic(const LaunchParams& P, const WorkIte
     }
 }
 
-#ifdef BSPMM_TRACE
-#define BSPMM_STAMP(task, slot)                                                        \
-    do {                                                                               \
-        if (P.trace) {                                                                 \
-            asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");                \
-            if (threadIdx.x == 0) P.trace[(size_t)(task) * 8 + (slot)] = wall_clock64(); \
-        }                                                                              \
-    } while (0)
-#else
-#define BSPMM_STAMP(task, slot) do { } while (0)
-#endif
 
 // ---------------------------------------------------------------------------------------
 // Fused task: M operations with the same output rows whose products are added up (the channel
@@ -569,10 +554,6 @@ __device__ __forceinline__ void run_fused(const LaunchParams& P, int* sm, int fi
     const int row0 = lane_i32(mine.row0, 0);
     const int nnz_sum = lane_i32(mine.nnz, 0);
     const int64_t out_row_off = lane_i64(mine.out_row_off, 0);
-#ifdef BSPMM_TRACE
-    if (P.trace && tid == 0) P.trace[(size_t)task * 8] = wall_clock64();
-#endif
-    BSPMM_STAMP(task, 1);
     const int members = (staged0 >> 8) & 0xff;
     const FusedLayout L = fused_layout(m, nnz_sum);
     const int stride = round_up(fw, 4);
@@ -609,10 +590,8 @@ __device__ __forceinline__ void run_fused(const LaunchParams& P, int* sm, int fi
         }
         tile_off += k * stride;
     }
-    BSPMM_STAMP(task, 6);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // direct-to-LDS loads landed
     __syncthreads();
-    BSPMM_STAMP(task, 2);
 
     // ---- rows of the sum: the plain gather loop over the merged CSR, one store per row
     const int* crpt = sm;
@@ -645,13 +624,6 @@ __device__ __forceinline__ void run_fused(const LaunchParams& P, int* sm, int fi
             store_out<VEC>(dst + (int64_t)r * P.ld_out + v * VEC, acc);
         }
     }
-    BSPMM_STAMP(task, 3);
-#ifdef BSPMM_TRACE
-    if (P.trace && tid == 0) {
-        P.trace[(size_t)task * 8 + 4] = nrows;
-        P.trace[(size_t)task * 8 + 5] = lane_i32(mine.k, 0);
-    }
-#endif
 }
 
 // Merged CSR of one set of summed operations (one workgroup per set, once per plan and
@@ -765,31 +737,15 @@ __global__ void __launch_bounds__(kThreads) bspmm_kernel(const LaunchParams P)
             const bool more = tn < P.wg_end[0];
             WorkItem nx = it;
             if (more) nx = P.items[P.item_base[0] + tn];
-#ifdef BSPMM_TRACE
-            if (P.trace && tid == 0) P.trace[(size_t)t * 8] = wall_clock64();
-#endif
             if (it.nrows > 0) {
-                BSPMM_STAMP(t, 1);
                 if (it.staged) {
                     stage_item<kThreads, VEC, HUBS, true, MERGED>(P, it, sm, tid);
                     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // direct-to-LDS loads landed
                     __syncthreads();
-                    BSPMM_STAMP(t, 2);
                     compute_staged<kThreads, VEC, HUBS>(P, it, sm, tid);
                 } else {
                     run_generic<VEC, HUBS>(P, it, sm, tid);
                 }
-                BSPMM_STAMP(t, 3);
-#ifdef BSPMM_TRACE
-                if (P.trace && tid == 0) {
-                    P.trace[(size_t)t * 8 + 4] = it.nrows;
-                    P.trace[(size_t)t * 8 + 5] = it.k;
-                    P.trace[(size_t)t * 8 + 6] = it.nnz;
-                    unsigned hw;
-                    asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(hw));
-                    P.trace[(size_t)t * 8 + 7] = hw;
-                }
-#endif
             }
             t = tn;
             if (!more) break;
@@ -810,6 +766,150 @@ __global__ void __launch_bounds__(kThreads) bspmm_kernel(const LaunchParams P)
                 run_slots<4, VEC, HUBS>(P, sm, P.item_base[4] + (t - P.wg_end[3]) * 16);
         }
     }
+}
+
+// ---------------------------------------------------------------------------------------
+// Lean launch.  When every task of a schedule is one staged workgroup item whose dense tile is
+// a power-of-two number of float4 wide (molecule-sized batches: the launch fits the chip at
+// once and its time is the life of a workgroup, a chain of short latencies), the launch runs
+// this kernel instead of bspmm_kernel: the same staging and the same gather (Fig. 4 per row,
+// batched as in Sec. IV-C, column blocking of Fig. 5(d)), with nothing on the path that such
+// an item does not need.  The dense tile is requested first (it is the part that comes from
+// HBM), every lane group asks for the row pointers of its own first row directly, so the first
+// pass over the rows starts from registers instead of a dependent LDS read, and the address
+// arithmetic of the copies is scalar wherever the item decides it.
+// Results are bit for bit those of bspmm_kernel: same order of the additions inside a row.
+// ---------------------------------------------------------------------------------------
+__device__ __forceinline__ float4 gather_row(const int2* cv, const char* bcol, int p0, int p1)
+{
+    using V = Vec<4>;
+    float4 acc = V::zero();
+    // Four entries per trip, all their LDS reads in flight together, also on the last trip of
+    // a row: an entry past the end reads the row's last one and counts with value zero (the
+    // sum starts at +0 and can never become -0, so adding 0 * b leaves its bits unchanged).
+    const int last = p1 - 1;
+    for (int p = p0; p < p1; p += 4) {
+        const int2 e0 = cv[p], e1 = cv[min(p + 1, last)], e2 = cv[min(p + 2, last)],
+                   e3 = cv[min(p + 3, last)];
+        const float4 b0 = *reinterpret_cast<const float4*>(bcol + e0.x);
+        const float4 b1 = *reinterpret_cast<const float4*>(bcol + e1.x);
+        const float4 b2 = *reinterpret_cast<const float4*>(bcol + e2.x);
+        const float4 b3 = *reinterpret_cast<const float4*>(bcol + e3.x);
+        V::fma(acc, __int_as_float(e0.y), b0);
+        V::fma(acc, p + 1 < p1 ? __int_as_float(e1.y) : 0.f, b1);
+        V::fma(acc, p + 2 < p1 ? __int_as_float(e2.y) : 0.f, b2);
+        V::fma(acc, p + 3 < p1 ? __int_as_float(e3.y) : 0.f, b3);
+    }
+    return acc;
+}
+
+__global__ void __launch_bounds__(kThreads)
+bspmm_lean_kernel(const LeanItem* __restrict__ items, const int32_t* __restrict__ rpt,
+                  const int32_t* __restrict__ colids, const float* __restrict__ values,
+                  const float* __restrict__ in, float* __restrict__ out, uint32_t ld_in,
+                  uint32_t ld_out)
+{
+    extern __shared__ __align__(16) int sm[];
+    const uint32_t tid = threadIdx.x;
+    // One clause of scalar loads fetches the whole item; there is no early exit for an empty
+    // item (all its sizes are zero, so nothing below has a trip): a branch on one field would
+    // split the fetch into two dependent round trips.  The output arguments are pulled in here
+    // as well, not after the barrier where they are first used.
+    const LeanItem it = items[blockIdx.x];
+    asm volatile("" ::"s"(out), "s"(ld_out));
+    const int m = it.m, k = it.k, nnz = it.nnz;
+    const int sh = it.sh;
+    const uint32_t nvec = 1u << sh;                  // float4 per tile row, <= 64
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6), wl = tid & 63;
+    char* lds = reinterpret_cast<char*>(sm);
+
+    // ---- dense tile, straight from global memory into LDS, 1 KiB per wavefront instruction
+    // (lane i lands at base + 16*i); a tile no other item reads is streamed.  Offsets inside
+    // the item's block are 32-bit (the host launches this kernel only when they fit).
+    {
+        const char* __restrict__ src =
+            reinterpret_cast<const char*>(in + ((uint64_t)it.in_row * ld_in + (uint32_t)it.f0));
+        const uint32_t row_bytes = ld_in << 2;
+        const uint32_t total = (uint32_t)it.tile_vecs;
+        char* bs = lds + it.b_byte;
+        if (it.stream) {
+            for (uint32_t e0 = wave << 6; e0 < total; e0 += kThreads) {
+                const uint32_t e = e0 + wl;
+                if (e < total)
+                    __builtin_amdgcn_global_load_lds(
+                        (const void __attribute__((address_space(1)))*)(
+                            src + (__umul24(e >> sh, row_bytes) + ((e & (nvec - 1)) << 4))),
+                        (void __attribute__((address_space(3)))*)(bs + (e0 << 4)), 16, 0, 2);
+            }
+        } else {
+            for (uint32_t e0 = wave << 6; e0 < total; e0 += kThreads) {
+                const uint32_t e = e0 + wl;
+                if (e < total)
+                    __builtin_amdgcn_global_load_lds(
+                        (const void __attribute__((address_space(1)))*)(
+                            src + (__umul24(e >> sh, row_bytes) + ((e & (nvec - 1)) << 4))),
+                        (void __attribute__((address_space(3)))*)(bs + (e0 << 4)), 16, 0, 0);
+            }
+        }
+    }
+    // ---- CSR: the row pointers of this lane group's first row (they stay in registers), all
+    // row pointers and the entries (on their way to LDS).  Indices are clamped instead of
+    // predicated: a lane past the end reads, and later writes, what the last lane does.
+    const int32_t* __restrict__ rp = rpt + it.rpt_off;
+    const int32_t* __restrict__ ci = colids + it.nz_off;
+    const float* __restrict__ va = values + it.nz_off;
+    const uint32_t r_first = (uint32_t)it.row0 + (tid >> sh);
+    const uint32_t um = (uint32_t)m;
+    const int q0 = rp[min(r_first, um)];
+    const int q1 = rp[min(r_first + 1, um)];
+    const uint32_t ri = min(tid, um);
+    const int rv = rp[ri];
+    const uint32_t last = (uint32_t)max(nnz - 1, 0);
+    const uint32_t i0 = min(tid, last), i1 = min(tid + kThreads, last);
+    int c0 = 0, c1 = 0;
+    float a0 = 0.f, a1 = 0.f;
+    if (nnz > 0) {               // (the same for every lane: a scalar branch)
+        c0 = ci[i0];
+        a0 = va[i0];
+    }
+    if (nnz > kThreads) {
+        c1 = ci[i1];
+        a1 = va[i1];
+    }
+    // No use of a loaded value above this line (its wait would hold back later loads).
+    __builtin_amdgcn_sched_barrier(0);
+
+    // ---- LDS writes.  Row pointers are clamped to [0, nnz] and columns to [0, k): malformed
+    // arrays cannot make a lane leave the item's LDS.  An entry carries the byte offset of its
+    // dense row inside the tile.
+    const int lsh = sh + 4;                          // log2 of the tile's row stride in bytes
+    int2* cv = reinterpret_cast<int2*>(lds + it.cv_byte);
+    sm[ri] = min(max(rv, 0), nnz);
+    if (nnz > 0) cv[i0] = make_int2((unsigned)c0 < (unsigned)k ? c0 << lsh : 0, __float_as_int(a0));
+    if (nnz > kThreads) cv[i1] = make_int2((unsigned)c1 < (unsigned)k ? c1 << lsh : 0, __float_as_int(a1));
+    if (m >= kThreads)
+        for (int i = tid + kThreads; i <= m; i += kThreads) sm[i] = min(max(rp[i], 0), nnz);
+    if (nnz > 2 * kThreads)
+        for (int p = tid + 2 * kThreads; p < nnz; p += kThreads) {
+            const int c = ci[p];
+            cv[p] = make_int2((unsigned)c < (unsigned)k ? c << lsh : 0, __float_as_int(va[p]));
+        }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // direct-to-LDS loads landed
+    __syncthreads();
+
+    // ---- rows: the first pass from the registers, later passes from the staged row pointers
+    const uint32_t l = tid & (nvec - 1);
+    const char* bcol = lds + it.b_byte + (l << 4);
+    char* __restrict__ dst = reinterpret_cast<char*>(out + ((uint64_t)it.out_row * ld_out + (uint32_t)it.f0));
+    const uint32_t out_row_bytes = ld_out << 2;
+    const uint32_t row_end = (uint32_t)(it.row0 + it.nrows);
+    const uint32_t groups = kThreads >> sh;          // rows in flight
+    if (r_first < row_end)
+        store_out<4>(reinterpret_cast<float*>(dst + (__umul24(r_first, out_row_bytes) + (l << 4))),
+                     gather_row(cv, bcol, min(max(q0, 0), nnz), min(max(q1, 0), nnz)));
+    for (uint32_t r = r_first + groups; r < row_end; r += groups)
+        store_out<4>(reinterpret_cast<float*>(dst + (__umul24(r, out_row_bytes) + (l << 4))),
+                     gather_row(cv, bcol, sm[r], sm[r + 1]));
 }
 
 // ---------------------------------------------------------------------------------------
@@ -1536,6 +1636,16 @@ hipError_t launch_bspmm(const LaunchParams& P, int grid, int lds_bytes, bool vec
     if (grid <= 0) return hipSuccess;
     hipLaunchKernelGGL(kernel_variant(vec4, slices, hubs, merged), dim3(grid), dim3(kThreads),
                        lds_bytes, stream, P);
+    return hipGetLastError();
+}
+
+hipError_t launch_bspmm_lean(const LeanItem* items, const LaunchParams& P, int grid, int lds_bytes,
+                             hipStream_t stream)
+{
+    if (grid <= 0) return hipSuccess;
+    hipLaunchKernelGGL(bspmm_lean_kernel, dim3(grid), dim3(kThreads), lds_bytes, stream, items,
+                       P.rpt, P.colids, P.values, P.in, P.out, (uint32_t)P.ld_in,
+                       (uint32_t)P.ld_out);
     return hipGetLastError();
 }
 

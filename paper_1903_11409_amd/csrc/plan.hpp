@@ -45,6 +45,26 @@ struct alignas(16) WorkItem {
 };
 static_assert(sizeof(WorkItem) == 64, "WorkItem must be 64 bytes");
 
+// The same unit of work for the lean kernel (launches made only of staged workgroup items with
+// a direct tile): 32-bit offsets, and everything the host can derive - LDS placement, tile
+// shape - already derived, so that a workgroup's scalar preamble is a handful of instructions.
+struct alignas(16) LeanItem {
+    uint32_t rpt_off;     // element offset of the operation's row pointers
+    uint32_t nz_off;      // element offset of the operation's entries
+    uint32_t in_row;      // first row of the dense input block
+    uint32_t out_row;     // first row of the dense output block
+    int32_t m, k, nnz;    // as WorkItem
+    int32_t row0, nrows;  // output rows of this item
+    int32_t f0;           // first feature column
+    int32_t sh;           // log2 of the float4 per tile row (tile width = 4 << sh floats)
+    int32_t stream;       // 1: no other item reads this dense tile
+    int32_t cv_byte;      // LDS byte offset of the (row offset, value) pairs
+    int32_t b_byte;       // LDS byte offset of the dense tile
+    int32_t tile_vecs;    // float4 in the tile: k << sh
+    int32_t pad_;
+};
+static_assert(sizeof(LeanItem) == 64, "LeanItem must be 64 bytes");
+
 // Kernel argument block, passed by value.  Task t belongs to range r when
 // wg_end[r-1] <= t < wg_end[r]; its first item is item_base[r] + (t - wg_end[r-1]) * n(r) with
 // n = 1 (range 0), fused_stride (range 1: operations summed into one output block), 4, 8, 16.
@@ -74,9 +94,6 @@ struct LaunchParams {
     int64_t ld_w;
     int32_t n_front;
     int32_t accumulate;   // add to the output instead of overwriting it
-#ifdef BSPMM_TRACE
-    long long* trace;     // development builds only: 8 timestamps per workgroup
-#endif
 };
 
 // One unit of work of the direct COO kernel: the output rows [row0, row0+nrows) x feature

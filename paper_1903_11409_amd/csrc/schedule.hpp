@@ -61,6 +61,8 @@ struct Schedule {
     int error = 0;                   // BSPMM_E* when the batch cannot be scheduled
     int grid = 0;                    // number of tasks
     int launch_grid = 0;             // workgroups of the persistent launch
+    bool lean = false;               // every task is one staged workgroup item with a direct
+                                     // tile: the launch may take the lean kernel
     bool has_slices = false;         // any 32- or 16-lane item: needs the larger kernel variant
     int tile = 0;
     int front_lds_words = 0;         // LDS the fused-front launch asks for (its largest item)

@@ -334,6 +334,59 @@ def test_offsets_beyond_32_bits(torch_cuda, oracle):
     assert torch_cuda.all(Gd[:, b.F:b.F + 4] == SENTINEL)
 
 
+@pytest.mark.parametrize("case", ["molecule_F128", "molecule_F64_transposed", "tall_narrow", "edgeless",
+                                  "wide_rows"])
+def test_lean_launch_matches_the_general_kernel_bit_for_bit(torch_cuda, oracle, case):
+    """Launches made only of staged workgroup items take the lean kernel; the same batch planned
+    with resident workgroups (which the lean kernel does not do) takes the general one.  Same
+    order of additions inside a row, so the outputs agree in every bit, and both meet the
+    oracle.  Shapes: the headline batch; a transposed product of rectangular operations with
+    unsorted, repeated entries and shuffled output blocks; graphs of 300-700 nodes at
+    F = 8 (row pointers and entries beyond one trip of the staging code, several row passes);
+    operations without any entry; rows of 40-90 entries (several trips of the gather loop)."""
+    torch = torch_cuda
+    transposed = False
+    kw = {}
+    if case == "molecule_F128":
+        b = W.config2_molecule(F=128)
+    elif case == "molecule_F64_transposed":
+        rng = np.random.default_rng(31)
+        shapes = [(int(rng.integers(1, 90)), int(rng.integers(1, 90)), int(rng.integers(0, 500)))
+                  for _ in range(48)]
+        b = W.random_general(78, F=64, shapes=shapes, shuffle_blocks=True)
+        transposed = True
+    elif case == "tall_narrow":
+        b = W.random_square(W.config_seed(7), 8, 6, (300, 700), (2, 4))
+        kw = {"lds_bytes": 160 * 1024}
+    elif case == "edgeless":
+        b = W.random_general(77, F=32, shapes=[(20, 20, 0), (5, 9, 0), (9, 5, 17), (0, 0, 0), (31, 31, 0)])
+    else:
+        b = W.random_square(W.config_seed(7) + 1, 16, 10, (90, 120), (40, 90))
+        kw = {"lds_bytes": 160 * 1024}
+    lean = K.Plan(b, options=K.make_options(**kw))
+    general = K.Plan(b, options=K.make_options(resident_workgroups=4096, **kw))
+    d = 1 if transposed else 0
+    assert lean.info().lean[d] == 1 and general.info().lean[d] == 0
+    if transposed:
+        _, got = _transposed(torch, b, plan=lean)
+        _, ref_gpu = _transposed(torch, b, plan=general)
+        ref, S = oracle.transposed_batch(b)
+        own = _owned_rows(b.b_row_off, b.cols, b.n_b_rows)
+    else:
+        Bd = torch.from_numpy(b.B).cuda()
+        outs = []
+        for plan in (lean, general):
+            Cd = torch.full((b.n_c_rows, b.F), SENTINEL, dtype=torch.float32, device="cuda")
+            plan.run(Bd, Cd)
+            torch.cuda.synchronize()
+            outs.append(Cd.cpu().numpy())
+        got, ref_gpu = outs
+        ref, S = oracle.forward_batch(b)
+        own = _owned_rows(b.c_row_off, b.rows, b.n_c_rows)
+    assert np.array_equal(got.view(np.uint32), ref_gpu.view(np.uint32)), f"{case}: kernels differ"
+    _assert_close(got, ref, S, own, f"lean kernel, {case}")
+
+
 def test_run_to_run_determinism(torch_cuda):
     b = W.config5_skewed(graphs=256, F=128)
     _, a = _forward(torch_cuda, b)

@@ -37,7 +37,7 @@ def test_struct_sizes_match_header():
     assert ctypes.sizeof(K.bspmm_item) == 32
     assert ctypes.sizeof(K.bspmm_options) == 56
     assert ctypes.sizeof(K.bspmm_batch) == 8 + 10 * 8
-    assert ctypes.sizeof(K.bspmm_info) == 16 + 8 + 8 + 8 + 8 + 40 + 8 + 8 + 16 + 8 + 8
+    assert ctypes.sizeof(K.bspmm_info) == 16 + 8 + 8 + 8 + 8 + 40 + 8 + 8 + 8 + 16 + 8 + 8
 
 
 def _slot_lanes(bin_):
