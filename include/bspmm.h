@@ -69,8 +69,10 @@ extern "C" {
 #define BSPMM_DRY_RUN          1u  /* schedule only: touch no device, run calls return ESTATE */
 #define BSPMM_BUILD_TRANSPOSE  2u  /* enqueue the one-off device builds (the transposed CSR; with
                                       BSPMM_ACCUMULATE the merged CSR of every summed set, both
-                                      directions) inside bspmm_create instead of in the first run
-                                      that needs them - e.g. before a HIP-graph capture          */
+                                      directions; for operations too large for on-chip memory,
+                                      the entry ranges of their row blocks) inside bspmm_create
+                                      instead of in the first run that needs them - e.g. before
+                                      a HIP-graph capture                                        */
 #define BSPMM_SPLIT_HUB_ROWS   8u  /* rows with >= 64 entries and >= 4x the operation's average are
                                       split across all lanes of the workgroup and the partial
                                       sums reduced (DPP / ds_swizzle inside a wavefront, LDS across
@@ -164,7 +166,7 @@ typedef struct bspmm_options {
     int32_t  compute_units;    /* 0 = ask the device (256 assumed for dry runs)                */
     int32_t  lds_pad;          /* floats added to each staged B row, 0 = default, -1 = none    */
     int32_t  max_passes;       /* row passes a sub-workgroup slot may take, 0 = default (1)    */
-    int32_t  generic_rows;     /* rows per generic row block, 0 = default (16)                 */
+    int32_t  generic_rows;     /* rows per generic row block, 0 = default (8)                   */
     int32_t  wg_passes;        /* row passes of a workgroup item before it is cut into row
                                   ranges: 0 = cut only while the launch is short of
                                   target_workgroups, N > 0 = always cap at N, -1 = never cut   */

@@ -21,6 +21,7 @@ hipError_t launch_bspmm(const LaunchParams& P, int grid, int lds_bytes, bool vec
                         bool hubs, bool merged, hipStream_t stream);
 hipError_t launch_bspmm_lean(const LeanItem* items, const LaunchParams& P, int grid, int lds_bytes,
                              hipStream_t stream);
+hipError_t launch_lean_hints(LeanItem* items, int n, const int32_t* rpt, hipStream_t stream);
 hipError_t launch_bspmm_gcn(const LaunchParams& P, int grid, int lds_bytes, bool accumulate,
                             bool sets, hipStream_t stream);
 hipError_t launch_build_transpose(const OpRecord* ops, int batch, int lds_bytes,
@@ -97,6 +98,8 @@ struct bspmm_plan {
     std::vector<LeanItem> lean_items[2];   // per direction: the items again, for the lean kernel
     int32_t lean_rows[2] = {0, 0};         // most input rows / output rows of an operation: bounds
     int32_t lean_out_rows[2] = {0, 0};     // of the 32-bit offsets the lean kernel forms per call
+    bool lean_blocks[2] = {false, false};  // the lean table has row blocks of the generic bin ...
+    bool lean_hints_built[2] = {false, false};   // ... and the device has filled in their entry ranges
     std::vector<char> tables;   // host image of the workspace's front: item tables and records
     Layout lay;
     int build_lds_bytes = 0;
@@ -252,6 +255,7 @@ void make_lean_items(bspmm_plan& p, int d)
     const Schedule& sc = p.sched[d];
     std::vector<LeanItem>& out = p.lean_items[d];
     out.clear();
+    p.lean_blocks[d] = false;
     if (!sc.lean) return;
     out.reserve(sc.items.size());
     constexpr int64_t kLimit = (int64_t)1 << 31;
@@ -265,7 +269,6 @@ void make_lean_items(bspmm_plan& p, int d)
                 out.clear();
                 return;
             }
-            const StagedLayout L = staged_layout(w.m, w.k, w.nnz, w.fw, 0, false);
             int sh = 0;
             while ((4 << sh) < w.fw) ++sh;
             t.rpt_off = (uint32_t)w.rpt_off;
@@ -274,10 +277,16 @@ void make_lean_items(bspmm_plan& p, int d)
             t.out_row = (uint32_t)w.out_row_off;
             t.m = w.m, t.k = w.k, t.nnz = w.nnz, t.row0 = w.row0, t.nrows = w.nrows, t.f0 = w.f0;
             t.sh = sh;
-            t.stream = (w.staged & 2) ? 1 : 0;
-            t.cv_byte = 4 * L.cv_off;
-            t.b_byte = 4 * L.b_off;
-            t.tile_vecs = w.k << sh;
+            if (w.staged & 1) {
+                const StagedLayout L = staged_layout(w.m, w.k, w.nnz, w.fw, 0, false);
+                t.flags = (w.staged & 2) ? 1 : 0;
+                t.cv_byte = 4 * L.cv_off;
+                t.b_byte = 4 * L.b_off;
+                t.tile_vecs = w.k << sh;
+            } else {
+                t.flags = 2;    // a row block: its entry range is filled in on the device
+                p.lean_blocks[d] = true;
+            }
             most_k = std::max(most_k, w.k);
             most_m = std::max(most_m, w.m);
         }
@@ -623,6 +632,37 @@ int enqueue_merge(bspmm_plan* p, int d, hipStream_t s)
     return BSPMM_OK;
 }
 
+// CSR arrays a run of direction d reads.
+void csr_of_direction(const bspmm_plan* p, int d, const int32_t** rpt, const int32_t** colids,
+                      const float** values)
+{
+    if (d == 0 || p->knobs.symmetric) {
+        *rpt = p->rpt;
+        *colids = p->colids;
+        *values = p->values;
+    } else {
+        *rpt = reinterpret_cast<const int32_t*>(p->ws + p->lay.rpt_t);
+        *colids = reinterpret_cast<const int32_t*>(p->ws + p->lay.colids_t);
+        *values = reinterpret_cast<const float*>(p->ws + p->lay.values_t);
+    }
+}
+
+// Row blocks of the generic bin in a lean table: the device writes each block's entry range
+// into its item (once per plan and direction; for d = 1 after the transposed CSR is built).
+int enqueue_hints(bspmm_plan* p, int d, hipStream_t s)
+{
+    if (p->lean_hints_built[d] || !p->lean_blocks[d] || p->lean_items[d].empty()) return BSPMM_OK;
+    const int32_t* rpt;
+    const int32_t* colids;
+    const float* values;
+    csr_of_direction(p, d, &rpt, &colids, &values);
+    hipError_t e = launch_lean_hints(reinterpret_cast<LeanItem*>(p->ws + p->lay.lean[d]),
+                                     (int)p->lean_items[d].size(), rpt, s);
+    if (e != hipSuccess) return hip_fail(e);
+    p->lean_hints_built[d] = !capturing(s);
+    return BSPMM_OK;
+}
+
 int run_direction(bspmm_plan* p, int d, const float* in, float* out, int64_t ld_in,
                   int64_t ld_out, hipStream_t s)
 {
@@ -653,20 +693,7 @@ int run_direction(bspmm_plan* p, int d, const float* in, float* out, int64_t ld_
     if (mrc != BSPMM_OK) return mrc;
     LaunchParams P;
     P.items = reinterpret_cast<const WorkItem*>(p->ws + p->lay.items[d]);
-    if (d == 0) {
-        P.rpt = p->rpt;
-        P.colids = p->colids;
-        P.values = p->values;
-    } else {
-        P.rpt = reinterpret_cast<const int32_t*>(p->ws + p->lay.rpt_t);
-        P.colids = reinterpret_cast<const int32_t*>(p->ws + p->lay.colids_t);
-        P.values = reinterpret_cast<const float*>(p->ws + p->lay.values_t);
-    }
-    if (p->knobs.symmetric) {
-        P.rpt = p->rpt;
-        P.colids = p->colids;
-        P.values = p->values;
-    }
+    csr_of_direction(p, d, &P.rpt, &P.colids, &P.values);
     P.in = in;
     P.out = out;
     P.ld_in = ld_in;
@@ -693,6 +720,10 @@ int run_direction(bspmm_plan* p, int d, const float* in, float* out, int64_t ld_
     const bool lean = vec4 && !p->lean_items[d].empty() && ld_in < kMul24 && ld_out < kMul24 &&
                       (int64_t)p->lean_rows[d] * ld_in < kOff32 &&
                       (int64_t)p->lean_out_rows[d] * ld_out < kOff32;
+    if (lean) {
+        const int hrc = enqueue_hints(p, d, s);
+        if (hrc != BSPMM_OK) return hrc;
+    }
     hipError_t e = lean
         ? launch_bspmm_lean(reinterpret_cast<const LeanItem*>(p->ws + p->lay.lean[d]), P,
                             sc.launch_grid, p->knobs.lds_words * 4, s)
@@ -854,7 +885,8 @@ int upload_plan(bspmm_plan* p, const bspmm_options* options, void* workspace,
     if (options && (options->flags & BSPMM_FLOOR_PROBE))
         for (int d = 0; d < 2; ++d) {
             for (WorkItem& w : p->sched[d].items) w.nrows = w.m = w.k = w.nnz = 0;
-            for (LeanItem& w : p->lean_items[d]) w.nrows = w.m = w.k = w.nnz = w.tile_vecs = 0;
+            for (LeanItem& w : p->lean_items[d])
+                w.nrows = w.m = w.k = w.nnz = w.tile_vecs = w.count = w.flags = w.b_byte = 0;
             for (CooItem& w : p->coo_sched[d].items) w.nrows = w.nnz = 0;
         }
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & (kAlign - 1)) != 0)
@@ -921,6 +953,8 @@ int upload_plan(bspmm_plan* p, const bspmm_options* options, void* workspace,
         int rc = enqueue_merge(p, 0, s);
         if (rc == BSPMM_OK && p->transposed_supported) rc = enqueue_build(p, s);
         if (rc == BSPMM_OK && p->transposed_supported) rc = enqueue_merge(p, 1, s);
+        if (rc == BSPMM_OK) rc = enqueue_hints(p, 0, s);
+        if (rc == BSPMM_OK && p->transposed_supported) rc = enqueue_hints(p, 1, s);
         return rc;
     }
     return BSPMM_OK;
@@ -1007,58 +1041,28 @@ bool displaced(const bspmm_plan* p)
 
 // bspmm_workspace_bytes has to schedule the batch to know the size; a bspmm_create that follows
 // on the same thread with the same arguments takes that plan over instead of scheduling again.
-// The key holds the argument values and a hash of the host arrays' contents.
+// "The same" is checked on the values themselves: F, the options, and every host array of the
+// batch against what the remembered plan was made from.
 struct PlanKey {
-    uint64_t hash = 0;
     int32_t batch = -1, F = 0;
     bool coo = false, has_options = false;
     bspmm_options options;
-    bool operator==(const PlanKey& o) const
-    {
-        return hash == o.hash && batch == o.batch && F == o.F && coo == o.coo &&
-               has_options == o.has_options &&
-               (!has_options || std::memcmp(&options, &o.options, sizeof(options)) == 0);
-    }
 };
-
-uint64_t fnv(uint64_t h, const void* data, size_t bytes)
-{
-    const unsigned char* q = static_cast<const unsigned char*>(data);
-    // eight bytes at a time (the arrays are int32 / int64)
-    size_t i = 0;
-    for (; i + 8 <= bytes; i += 8) {
-        uint64_t w;
-        std::memcpy(&w, q + i, 8);
-        h = (h ^ w) * 0x100000001b3ull;
-    }
-    for (; i < bytes; ++i) h = (h ^ q[i]) * 0x100000001b3ull;
-    return h;
-}
-
-template <class Batch>
-PlanKey make_key(const Batch* b, int32_t F, const bspmm_options* o, bool coo, const int64_t* rpt_off)
-{
-    PlanKey k;
-    k.batch = b->batch;
-    k.F = F;
-    k.coo = coo;
-    k.has_options = o != nullptr;
-    if (o) k.options = *o;
-    uint64_t h = 0xcbf29ce484222325ull;
-    const size_t n = (size_t)b->batch;
-    h = fnv(h, b->rows, n * 4);
-    h = fnv(h, b->cols, n * 4);
-    h = fnv(h, b->nnz, n * 4);
-    if (rpt_off) h = fnv(h, rpt_off, n * 8);
-    h = fnv(h, b->nz_off, n * 8);
-    h = fnv(h, b->b_row_off, n * 8);
-    h = fnv(h, b->c_row_off, n * 8);
-    k.hash = h;
-    return k;
-}
 
 thread_local std::unique_ptr<bspmm_plan> t_memo;
 thread_local PlanKey t_memo_key;
+
+PlanKey make_key(int32_t batch, int32_t F, const bspmm_options* o, bool coo)
+{
+    PlanKey k;
+    k.batch = batch;
+    k.F = F;
+    k.coo = coo;
+    k.has_options = o != nullptr;
+    std::memset(&k.options, 0, sizeof(k.options));
+    if (o) k.options = *o;
+    return k;
+}
 
 void remember(bspmm_plan* p, const PlanKey& k)
 {
@@ -1066,10 +1070,33 @@ void remember(bspmm_plan* p, const PlanKey& k)
     t_memo_key = k;
 }
 
-bspmm_plan* recall(const PlanKey& k)
+// The remembered plan, if it was made from exactly this batch.  `rpt_off` is null for COO batches
+// (their plans keep the row-pointer offsets the library chose itself).
+template <class Batch>
+bspmm_plan* recall(const PlanKey& k, const Batch* b, const int64_t* rpt_off)
 {
-    if (t_memo && t_memo_key == k) return t_memo.release();
-    return nullptr;
+    if (!t_memo) return nullptr;
+    const PlanKey& m = t_memo_key;
+    if (m.batch != k.batch || m.F != k.F || m.coo != k.coo || m.has_options != k.has_options ||
+        std::memcmp(&m.options, &k.options, sizeof(k.options)) != 0)
+        return nullptr;
+    const bspmm_plan& p = *t_memo;
+    const DirOps& f = p.dir[0];
+    const size_t n = (size_t)k.batch;
+    if (p.batch != k.batch || f.m.size() != n) return nullptr;
+    auto same = [n](const auto& kept, const auto* given) {
+        return std::memcmp(kept.data(), given, n * sizeof(*given)) == 0;
+    };
+    if (!same(f.m, b->rows) || !same(f.k, b->cols) || !same(f.nnz, b->nnz) ||
+        !same(f.in_off, b->b_row_off) || !same(f.out_off, b->c_row_off))
+        return nullptr;
+    if (rpt_off) {
+        if (!same(f.rpt_off, rpt_off) || !same(f.nz_off, b->nz_off)) return nullptr;
+    } else {
+        for (size_t i = 0; i < n; ++i)
+            if (p.coo_records[i].nz_off != b->nz_off[i]) return nullptr;
+    }
+    return t_memo.release();
 }
 
 }  // namespace
@@ -1092,7 +1119,7 @@ int bspmm_workspace_bytes(const bspmm_batch* b, int32_t F, const bspmm_options* 
         return rc;
     }
     *bytes = p->lay.total;
-    remember(p, make_key(b, F, options, false, b->rpt_off));
+    remember(p, make_key(b->batch, F, options, false));
     return BSPMM_OK;
 }
 
@@ -1105,7 +1132,7 @@ int bspmm_create(bspmm_plan** plan, const bspmm_batch* b, int32_t F,
     const bool dry = options && (options->flags & BSPMM_DRY_RUN);
     int rc = check_batch(b, F, !dry);
     if (rc != BSPMM_OK) return rc;
-    bspmm_plan* p = b->batch > 0 ? recall(make_key(b, F, options, false, b->rpt_off)) : nullptr;
+    bspmm_plan* p = b->batch > 0 ? recall(make_key(b->batch, F, options, false), b, b->rpt_off) : nullptr;
     if (!p) {
         p = new (std::nothrow) bspmm_plan;
         if (!p) return BSPMM_EINVAL;
@@ -1178,7 +1205,7 @@ int bspmm_workspace_bytes_coo(const bspmm_coo_batch* b, int32_t F, const bspmm_o
         return rc;
     }
     *bytes = p->lay.total;
-    remember(p, make_key(b, F, options, true, nullptr));
+    remember(p, make_key(b->batch, F, options, true));
     return BSPMM_OK;
 }
 
@@ -1191,7 +1218,7 @@ int bspmm_create_coo(bspmm_plan** plan, const bspmm_coo_batch* b, int32_t F,
     const bool dry = options && (options->flags & BSPMM_DRY_RUN);
     int rc = check_coo_batch(b, F, !dry);
     if (rc != BSPMM_OK) return rc;
-    bspmm_plan* p = b->batch > 0 ? recall(make_key(b, F, options, true, nullptr)) : nullptr;
+    bspmm_plan* p = b->batch > 0 ? recall(make_key(b->batch, F, options, true), b, static_cast<const int64_t*>(nullptr)) : nullptr;
     if (!p) {
         p = new (std::nothrow) bspmm_plan;
         if (!p) return BSPMM_EINVAL;

@@ -355,7 +355,14 @@ __device__ __forceinline__ void compute_staged(const LaunchParams& P, const Work
         const int p0 = sm[r];
         const int p1 = sm[r + 1];
         if (hubs_on && p1 - p0 >= hub_deg) {
-            if (sp.l == 0) hub[1 + atomicAdd(&hub[0], 1)] = r;   // left to the whole workgroup
+            // left to the whole workgroup.  The list has room for nnz / kHubMin rows, which is
+            // all there can be when the row pointers are monotone; malformed ones (clamped, but
+            // going up and down) could name more: those rows stay out of the list, and so
+            // inside the item's LDS (their output is not written; the arrays were malformed).
+            if (sp.l == 0) {
+                const int slot = atomicAdd(&hub[0], 1);
+                if (slot < it.nnz / kHubMin) hub[1 + slot] = r;
+            }
             continue;
         }
         for (int v = sp.l; v < sp.nvec; v += sp.g_lanes) {
@@ -391,7 +398,7 @@ __device__ __forceinline__ void compute_staged(const LaunchParams& P, const Work
     if constexpr (kHubs) {
         if (!hubs_on) return;          // uniform: depends on the item only
         __syncthreads();               // the hub list is complete
-        const int n_hub = hub[0];
+        const int n_hub = min(hub[0], it.nnz / kHubMin);
         const int fwp = round_up(it.fw, 4);
         float* scratch = reinterpret_cast<float*>(hub + round_up(1 + it.nnz / kHubMin, 4));
         for (int h = 0; h < n_hub; ++h) {
@@ -803,11 +810,145 @@ __device__ __forceinline__ float4 gather_row(const int2* cv, const char* bcol, i
     return acc;
 }
 
+// The same sum with the dense rows gathered from global memory (L2): `cv` holds (byte offset
+// of the dense row inside the operation's block, value), `src_l` addresses this lane's float4 of
+// the block's first row.  Four independent gathers are in flight per lane (eight measured the
+// same: the gathers of a large operation are bound by what the L2 delivers, not by latency).
+__device__ __forceinline__ float4 gather_row_global(const int2* cv, const char* __restrict__ src_l,
+                                                    int p0, int p1)
+{
+    using V = Vec<4>;
+    float4 acc = V::zero();
+    const int last = p1 - 1;
+    for (int p = p0; p < p1; p += 4) {
+        int2 e[4];
+        float4 b[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) e[u] = cv[min(p + u, last)];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) b[u] = *reinterpret_cast<const float4*>(src_l + (uint32_t)e[u].x);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) V::fma(acc, p + u < p1 ? __int_as_float(e[u].y) : 0.f, b[u]);
+    }
+    return acc;
+}
+
+// Row block of the generic bin in a lean launch.  ONE round trip to memory brings the block's
+// row pointers and its entries: their position comes with the item (lean_hints_kernel wrote it
+// there once), where bspmm_kernel needs the row pointers before it can ask for the entries.
+// (Fetching the block's share of the dense rows into L2 ahead of the gathers was measured and
+// changed nothing: the gathers are bound by L2 throughput.)
+__device__ __forceinline__ void lean_row_block(const LeanItem& it, int* sm,
+                                               const int32_t* __restrict__ rpt,
+                                               const int32_t* __restrict__ colids,
+                                               const float* __restrict__ values,
+                                               const float* __restrict__ in, float* __restrict__ out,
+                                               uint32_t ld_in, uint32_t ld_out, uint32_t lds_words)
+{
+    const uint32_t tid = threadIdx.x;
+    const int nrows = it.nrows, k = it.k, nnz = it.nnz;
+    const int sh = it.sh;
+    const uint32_t nvec = 1u << sh;
+    const uint32_t l = tid & (nvec - 1), g = tid >> sh, groups = kThreads >> sh;
+    const int pbeg = min(max(it.tile_vecs, 0), nnz);
+    const int cnt = min(max(it.count, 0), nnz - pbeg);
+    const uint32_t row_bytes = ld_in << 2;
+    const char* __restrict__ src =
+        reinterpret_cast<const char*>(in + ((uint64_t)it.in_row * ld_in + (uint32_t)it.f0));
+    const int32_t* __restrict__ rp = rpt + it.rpt_off + (uint32_t)it.row0;
+    const int32_t* __restrict__ ci = colids + it.nz_off + (uint32_t)pbeg;
+    const float* __restrict__ va = values + it.nz_off + (uint32_t)pbeg;
+    const uint32_t cv_off = (uint32_t)round_up(nrows + 1, 2);
+    const bool fits = cv_off + 2u * (uint32_t)cnt <= lds_words;   // entries of the block in LDS
+    int2* cv = reinterpret_cast<int2*>(sm + cv_off);
+
+    // ---- requests
+    const uint32_t ri = min(tid, (uint32_t)nrows);
+    const int rv = rp[ri];
+    const uint32_t last = (uint32_t)max(cnt - 1, 0);
+    const uint32_t i0 = min(tid, last), i1 = min(tid + kThreads, last);
+    int c0 = 0, c1 = 0;
+    float a0 = 0.f, a1 = 0.f;
+    if (fits && cnt > 0) {
+        c0 = ci[i0];
+        a0 = va[i0];
+    }
+    if (fits && cnt > kThreads) {
+        c1 = ci[i1];
+        a1 = va[i1];
+    }
+    __builtin_amdgcn_sched_barrier(0);
+
+    // ---- LDS writes (clamped as in the staged path)
+    sm[ri] = min(max(rv, 0), nnz);
+    if (fits && cnt > 0)
+        cv[i0] = make_int2((unsigned)c0 < (unsigned)k ? (int)__umul24((uint32_t)c0, row_bytes) : 0, __float_as_int(a0));
+    if (fits && cnt > kThreads)
+        cv[i1] = make_int2((unsigned)c1 < (unsigned)k ? (int)__umul24((uint32_t)c1, row_bytes) : 0, __float_as_int(a1));
+    if (fits && cnt > 2 * kThreads)
+        for (int p = tid + 2 * kThreads; p < cnt; p += kThreads) {
+            const int c = ci[p];
+            cv[p] = make_int2((unsigned)c < (unsigned)k ? (int)__umul24((uint32_t)c, row_bytes) : 0,
+                              __float_as_int(va[p]));
+        }
+    __syncthreads();
+
+    // ---- rows
+    const char* src_l = src + (l << 4);
+    char* __restrict__ dst = reinterpret_cast<char*>(
+        out + (((uint64_t)it.out_row + (uint32_t)it.row0) * ld_out + (uint32_t)it.f0));
+    const uint32_t out_row_bytes = ld_out << 2;
+    for (uint32_t i = g; i < (uint32_t)nrows; i += groups) {
+        const int p1 = min(max(sm[i + 1] - pbeg, 0), cnt);
+        const int p0 = min(max(sm[i] - pbeg, 0), p1);
+        float4 acc;
+        if (fits) {
+            acc = gather_row_global(cv, src_l, p0, p1);
+        } else {
+            // a block whose entries do not fit LDS (rows of thousands of entries): entry by
+            // entry from global memory, four gathers in flight
+            acc = Vec<4>::zero();
+            for (int p = p0; p < p1; p += 4) {
+                int cc[4];
+                float aa[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int q = min(p + u, p1 - 1);
+                    const int c = ci[q];
+                    cc[u] = (unsigned)c < (unsigned)k ? c : 0;
+                    aa[u] = p + u < p1 ? va[q] : 0.f;
+                }
+                float4 b[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    b[u] = *reinterpret_cast<const float4*>(src_l + __umul24((uint32_t)cc[u], row_bytes));
+#pragma unroll
+                for (int u = 0; u < 4; ++u) Vec<4>::fma(acc, aa[u], b[u]);
+            }
+        }
+        store_out<4>(reinterpret_cast<float*>(dst + (__umul24(i, out_row_bytes) + (l << 4))), acc);
+    }
+}
+
+// Once per plan and direction: the position of every row block's entries goes into its item.
+__global__ void lean_hints_kernel(LeanItem* items, int n, const int32_t* __restrict__ rpt)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    LeanItem& it = items[i];
+    if ((it.flags & 2) == 0 || it.nrows <= 0) return;
+    const int32_t* rp = rpt + it.rpt_off;
+    const int a = min(max(rp[it.row0], 0), it.nnz);
+    const int b = min(max(rp[it.row0 + it.nrows], 0), it.nnz);
+    it.tile_vecs = a;
+    it.count = max(b - a, 0);
+}
+
 __global__ void __launch_bounds__(kThreads)
 bspmm_lean_kernel(const LeanItem* __restrict__ items, const int32_t* __restrict__ rpt,
                   const int32_t* __restrict__ colids, const float* __restrict__ values,
                   const float* __restrict__ in, float* __restrict__ out, uint32_t ld_in,
-                  uint32_t ld_out)
+                  uint32_t ld_out, uint32_t lds_words)
 {
     extern __shared__ __align__(16) int sm[];
     const uint32_t tid = threadIdx.x;
@@ -817,6 +958,10 @@ bspmm_lean_kernel(const LeanItem* __restrict__ items, const int32_t* __restrict_
     // as well, not after the barrier where they are first used.
     const LeanItem it = items[blockIdx.x];
     asm volatile("" ::"s"(out), "s"(ld_out));
+    if (it.flags & 2) {        // (the same for the whole workgroup)
+        lean_row_block(it, sm, rpt, colids, values, in, out, ld_in, ld_out, lds_words);
+        return;
+    }
     const int m = it.m, k = it.k, nnz = it.nnz;
     const int sh = it.sh;
     const uint32_t nvec = 1u << sh;                  // float4 per tile row, <= 64
@@ -832,7 +977,7 @@ bspmm_lean_kernel(const LeanItem* __restrict__ items, const int32_t* __restrict_
         const uint32_t row_bytes = ld_in << 2;
         const uint32_t total = (uint32_t)it.tile_vecs;
         char* bs = lds + it.b_byte;
-        if (it.stream) {
+        if (it.flags & 1) {
             for (uint32_t e0 = wave << 6; e0 < total; e0 += kThreads) {
                 const uint32_t e = e0 + wl;
                 if (e < total)
@@ -1645,7 +1790,14 @@ hipError_t launch_bspmm_lean(const LeanItem* items, const LaunchParams& P, int g
     if (grid <= 0) return hipSuccess;
     hipLaunchKernelGGL(bspmm_lean_kernel, dim3(grid), dim3(kThreads), lds_bytes, stream, items,
                        P.rpt, P.colids, P.values, P.in, P.out, (uint32_t)P.ld_in,
-                       (uint32_t)P.ld_out);
+                       (uint32_t)P.ld_out, (uint32_t)(lds_bytes / 4));
+    return hipGetLastError();
+}
+
+hipError_t launch_lean_hints(LeanItem* items, int n, const int32_t* rpt, hipStream_t stream)
+{
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(lean_hints_kernel, dim3((n + 255) / 256), dim3(256), 0, stream, items, n, rpt);
     return hipGetLastError();
 }
 

@@ -45,9 +45,13 @@ struct alignas(16) WorkItem {
 };
 static_assert(sizeof(WorkItem) == 64, "WorkItem must be 64 bytes");
 
-// The same unit of work for the lean kernel (launches made only of staged workgroup items with
-// a direct tile): 32-bit offsets, and everything the host can derive - LDS placement, tile
+// The same unit of work for the lean kernel (launches made only of whole-workgroup items with a
+// power-of-two tile): 32-bit offsets, and everything the host can derive - LDS placement, tile
 // shape - already derived, so that a workgroup's scalar preamble is a handful of instructions.
+// Two kinds: staged items (the operation and its dense tile in LDS) and row blocks of the
+// generic bin (operations too large for LDS: the dense rows are gathered from L2).  For a row
+// block the position of its entries is filled in on the device, once per plan, so that a run
+// requests row pointers, entries and dense rows in ONE round trip instead of three.
 struct alignas(16) LeanItem {
     uint32_t rpt_off;     // element offset of the operation's row pointers
     uint32_t nz_off;      // element offset of the operation's entries
@@ -57,11 +61,14 @@ struct alignas(16) LeanItem {
     int32_t row0, nrows;  // output rows of this item
     int32_t f0;           // first feature column
     int32_t sh;           // log2 of the float4 per tile row (tile width = 4 << sh floats)
-    int32_t stream;       // 1: no other item reads this dense tile
-    int32_t cv_byte;      // LDS byte offset of the (row offset, value) pairs
-    int32_t b_byte;       // LDS byte offset of the dense tile
-    int32_t tile_vecs;    // float4 in the tile: k << sh
-    int32_t pad_;
+    int32_t flags;        // bit 0: no other item reads this dense tile; bit 1: row block of the
+                          // generic bin
+    int32_t cv_byte;      // staged: LDS byte offset of the (row offset, value) pairs
+    int32_t b_byte;       // staged: LDS byte offset of the dense tile
+    int32_t tile_vecs;    // staged: float4 in the tile, k << sh
+                          // row block: its first entry, rpt[row0] (filled on the device)
+    int32_t count;        // row block: its entries, rpt[row0 + nrows] - rpt[row0] (filled on the
+                          // device)
 };
 static_assert(sizeof(LeanItem) == 64, "LeanItem must be 64 bytes");
 

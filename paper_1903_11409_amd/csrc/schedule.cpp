@@ -837,15 +837,16 @@ Schedule make_schedule(const DirOps& ops_in, int F, const Knobs& kn_in)
     s.item_op.resize(s.items.size(), -1);
     s.grid = wg;
     s.launch_grid = kn.persistent_wgs > 0 ? std::min(wg, W) : wg;
-    // The lean kernel serves launches made only of staged workgroup items on the float4 path
-    // whose tile rows are a power-of-two number of float4, copied straight into LDS.
+    // The lean kernel serves launches made only of whole-workgroup items (staged operations and
+    // row blocks of the generic bin) on the float4 path whose tile rows are a power-of-two number
+    // of float4.
     s.lean = vec == 4 && kn.pad == 0 && !kn.hubs && kn.front == 0 && kn.persistent_wgs == 0 &&
              s.merged_sets.empty() && s.wg_end[0] == wg && wg > 0;
     for (const WorkItem& w : s.items) {
         if (!s.lean) break;
         if (w.nrows <= 0) continue;
         const int nvec = w.fw >> 2;
-        s.lean = (w.staged & 1) != 0 && (w.fw & 3) == 0 && nvec > 0 && (nvec & (nvec - 1)) == 0 && nvec <= 64;
+        s.lean = (w.fw & 3) == 0 && nvec > 0 && (nvec & (nvec - 1)) == 0 && nvec <= 64;
     }
     if (kn.front > 0) {
         int64_t most = 0;

@@ -31,7 +31,7 @@ struct Knobs {
     int compute_units = 256;
     int pad = 0;
     int max_passes = 1;
-    int generic_rows = 16;
+    int generic_rows = 8;
     int wg_passes = 0;        // 0 automatic, >0 cap on passes of a workgroup item, <0 never cut
     int capacity_wgs = 1536;  // workgroups the chip holds at once (lean kernel variant)
     int capacity_wgs_slices = 1024;   // same for the kernel variant with 32/16-lane slots

@@ -652,3 +652,39 @@ def test_large_front_batches_take_a_smaller_lds_budget():
     small = W.config3_multichannel(graphs=256, F=128, channels=4, accumulate=True)
     info, _ = _check_schedule(small, 128, flags=K.ACCUMULATE, front_features=32)
     assert info.lds_bytes == 81920
+
+
+def test_a_plan_is_handed_from_workspace_bytes_to_create_only_for_the_same_batch():
+    """bspmm_workspace_bytes keeps the plan it had to make; bspmm_create takes it over when its
+    batch has the same contents, and plans afresh when any host array differs (same sizes, other
+    output blocks; same everything, other operation sizes)."""
+    import dataclasses
+    b1 = W.config2_molecule(graphs=12, F=64)
+    opts = K.make_options(flags=K.DRY_RUN)
+
+    def hb(b):
+        return K.HostBatch(b.rows, b.cols, b.nnz, b.rpt_off, b.nz_off, b.b_row_off, b.c_row_off)
+
+    def items_of(b_sized, b_created):
+        K.bspmm_workspace_bytes(hb(b_sized), 64, opts)
+        h = K.bspmm_create(hb(b_created), 64, opts)
+        got = sorted((it.op, it.row0, it.nrows, it.f0, it.fw) for it in K.bspmm_plan_items(h))
+        info = K.bspmm_plan_info(h)
+        K.bspmm_destroy(h)
+        return got, int(info.effective_bytes[0])
+
+    def fresh(b):
+        h = K.bspmm_create(hb(b), 64, opts)
+        got = sorted((it.op, it.row0, it.nrows, it.f0, it.fw) for it in K.bspmm_plan_items(h))
+        info = K.bspmm_plan_info(h)
+        K.bspmm_destroy(h)
+        return got, int(info.effective_bytes[0])
+
+    assert items_of(b1, b1) == fresh(b1)
+    # the same operations with their output blocks in reverse order
+    off = np.concatenate([[0], np.cumsum(b1.rows[::-1][:-1])])[::-1].astype(np.int64)
+    b2 = dataclasses.replace(b1, c_row_off=np.ascontiguousarray(off))
+    assert items_of(b1, b2) == fresh(b2)
+    # another batch of the same length
+    b3 = W.config2_molecule(seed=5, graphs=12, F=64)
+    assert items_of(b1, b3) == fresh(b3) and fresh(b3) != fresh(b1)
