@@ -24,13 +24,15 @@ hipError_t launch_bspmm_lean(const LeanItem* items, const LaunchParams& P, int g
 hipError_t launch_lean_hints(LeanItem* items, int n, const int32_t* rpt, hipStream_t stream);
 hipError_t launch_bspmm_gcn(const LaunchParams& P, int grid, int lds_bytes, bool accumulate,
                             bool sets, hipStream_t stream);
-hipError_t launch_build_transpose(const OpRecord* ops, int batch, int lds_bytes,
+hipError_t launch_build_transpose(const OpRecord* ops, int batch, int threads, int lds_bytes,
                                   const int32_t* rpt, const int32_t* colids,
                                   const float* values, int32_t* rpt_t, int32_t* colids_t,
-                                  float* values_t, int32_t* gscratch, hipStream_t stream);
-hipError_t launch_build_from_coo(const OpRecord* ops, int batch, int lds_bytes, const int32_t* ids,
+                                  float* values_t, int32_t* gscratch, const int32_t* order,
+                                  hipStream_t stream);
+hipError_t launch_build_from_coo(const OpRecord* ops, int batch, int threads, int lds_bytes, const int32_t* ids,
                                  const float* values, int32_t* rpt, int32_t* colids,
-                                 float* csr_values, int32_t* gscratch, hipStream_t stream);
+                                 float* csr_values, int32_t* gscratch, const int32_t* order,
+                                 hipStream_t stream);
 hipError_t launch_bspmm_coo(const CooLaunchParams& P, int grid, int lds_bytes, bool vec4,
                             hipStream_t stream);
 hipError_t launch_merge_sets(const SetRecord* sets, int count, const int32_t* rpt,
@@ -70,6 +72,7 @@ struct Layout {
     size_t items[2] = {0, 0};
     size_t lean[2] = {0, 0};     // item tables of the lean kernel (empty when a direction is not lean)
     size_t op_records = 0;
+    size_t build_order = 0;
     size_t rpt_t = 0, colids_t = 0, values_t = 0;
     size_t scratch = 0;
     size_t flag = 0;
@@ -95,6 +98,8 @@ struct bspmm_plan {
     DirOps dir[2];
     Schedule sched[2];
     std::vector<OpRecord> records;
+    std::vector<int32_t> build_order;      // operations, most entries first: the order the build
+                                           // kernels take them in
     std::vector<LeanItem> lean_items[2];   // per direction: the items again, for the lean kernel
     int32_t lean_rows[2] = {0, 0};         // most input rows / output rows of an operation: bounds
     int32_t lean_out_rows[2] = {0, 0};     // of the 32-bit offsets the lean kernel forms per call
@@ -103,6 +108,7 @@ struct bspmm_plan {
     std::vector<char> tables;   // host image of the workspace's front: item tables and records
     Layout lay;
     int build_lds_bytes = 0;
+    int build_threads = kThreads;          // lanes per workgroup of the build kernels
     int64_t scratch_words = 0;
     bool transposed_supported = true;
     bool transposed_built = false;
@@ -296,6 +302,33 @@ void make_lean_items(bspmm_plan& p, int d)
     p.lean_out_rows[d] = most_m;
 }
 
+// How the build kernel sorts an operation of `keys` key values, `nnz` entries and payloads below
+// `payloads` (rows of a CSR operand, columns of a COO one); `with_rpt` when the input's row
+// pointers come along.  Sets r.small and r.scratch_off and returns the LDS words it needs
+// (0 when the operation works in global scratch, whose words are added to *scratch_words).
+int64_t classify_build(OpRecord& r, int64_t keys, int64_t payloads, int64_t nnz, bool with_rpt,
+                       int threads, int64_t* scratch_words)
+{
+    const int64_t budget = (kBuildLdsBytes - 2048) / 4;
+    const int64_t base = keys + 1 + nnz;                     // counters and positions
+    const int64_t reg_path = base + (with_rpt ? payloads + 1 : 0);
+    auto bits = [](int64_t v) { int b = 0; while (v > 0) { ++b; v >>= 1; } return b; };
+    r.scratch_off = -1;
+    if (nnz <= (int64_t)build_entries_per_lane(threads) * threads && reg_path <= budget) {
+        r.small = 1;     // register path: a few entries per lane, row pointers in LDS too
+        return reg_path;
+    }
+    if (base + nnz <= budget && bits(keys) + bits(std::max<int64_t>(payloads - 1, 0)) <= 32) {
+        r.small = 2;     // key and payload of every entry packed into one more LDS word
+        return base + nnz;
+    }
+    r.small = 0;
+    if (base <= budget) return base;
+    r.scratch_off = *scratch_words;
+    *scratch_words += base;
+    return 0;
+}
+
 // Fill everything of the plan that needs no device.
 int plan_host(bspmm_plan& p, const bspmm_batch* b, int32_t F, const Knobs& kn)
 {
@@ -307,6 +340,9 @@ int plan_host(bspmm_plan& p, const bspmm_batch* b, int32_t F, const Knobs& kn)
     DirOps& t = p.dir[1];
     int64_t rpt_t_words = 0;
     p.records.resize(n);
+    p.build_threads = kThreads;
+    for (int i = 0; i < n; ++i)
+        if (b->nnz[i] > 4 * kThreads) p.build_threads = kBuildThreadsLarge;
     int64_t nz_pack = 0;
     int64_t scratch_words = 0;
     int build_lds_words = 0;
@@ -342,18 +378,9 @@ int plan_host(bspmm_plan& p, const bspmm_batch* b, int32_t F, const Knobs& kn)
         r.m = b->rows[i];
         r.k = b->cols[i];
         r.nnz = b->nnz[i];
-        // small operations take the build kernel's register path (small = 1): at most four
-        // entries per lane, the input's row pointers in LDS as well
-        const int64_t work_small = (int64_t)b->cols[i] + 1 + b->nnz[i] + b->rows[i] + 1;
-        r.small = b->nnz[i] <= 4 * kThreads && work_small * 4 <= kBuildLdsBytes - 2048 ? 1 : 0;
-        const int64_t work = r.small ? work_small : (int64_t)b->cols[i] + 1 + b->nnz[i];
-        if (work * 4 <= kBuildLdsBytes - 2048) {
-            r.scratch_off = -1;
-            build_lds_words = std::max<int64_t>(build_lds_words, work);
-        } else {
-            r.scratch_off = scratch_words;
-            scratch_words += work;
-        }
+        build_lds_words = std::max<int64_t>(
+            build_lds_words,
+            classify_build(r, b->cols[i], b->rows[i], b->nnz[i], true, p.build_threads, &scratch_words));
         rpt_t_words += (int64_t)b->cols[i] + 1;
         nz_pack += b->nnz[i];
     }
@@ -455,6 +482,12 @@ int plan_host(bspmm_plan& p, const bspmm_batch* b, int32_t F, const Knobs& kn)
     }
     L.op_records = at;
     at = align_up(at + (size_t)n * sizeof(OpRecord));
+    L.build_order = at;
+    at = align_up(at + (size_t)n * sizeof(int32_t));
+    p.build_order.resize(n);
+    for (int i = 0; i < n; ++i) p.build_order[i] = i;
+    std::stable_sort(p.build_order.begin(), p.build_order.end(),
+                     [b](int32_t x, int32_t y) { return b->nnz[x] > b->nnz[y]; });
     L.rpt_t = at;
     at = align_up(at + (size_t)rpt_t_words * 4);
     L.colids_t = at;
@@ -605,11 +638,12 @@ int enqueue_build(bspmm_plan* p, hipStream_t s)
     if (p->transposed_built || p->knobs.symmetric) return BSPMM_OK;
     hipError_t e = launch_build_transpose(
         reinterpret_cast<const OpRecord*>(p->ws + p->lay.op_records), p->batch,
-        p->build_lds_bytes, p->rpt, p->colids, p->values,
+        p->build_threads, p->build_lds_bytes, p->rpt, p->colids, p->values,
         reinterpret_cast<int32_t*>(p->ws + p->lay.rpt_t),
         reinterpret_cast<int32_t*>(p->ws + p->lay.colids_t),
         reinterpret_cast<float*>(p->ws + p->lay.values_t),
-        reinterpret_cast<int32_t*>(p->ws + p->lay.scratch), s);
+        reinterpret_cast<int32_t*>(p->ws + p->lay.scratch),
+        reinterpret_cast<const int32_t*>(p->ws + p->lay.build_order), s);
     if (e != hipSuccess) return hip_fail(e);
     p->transposed_built = !capturing(s);
     return BSPMM_OK;
@@ -819,6 +853,9 @@ int plan_host_coo(bspmm_plan& p, const bspmm_coo_batch* b, int32_t F, const Knob
     std::vector<int64_t> rpt_off(n), nz_pack(n);
     int64_t rpt_words = 0, nz = 0, scratch_words = 0, lds_words = 0;
     p.coo_records.resize(n);
+    int threads = kThreads;
+    for (int i = 0; i < n; ++i)
+        if (b->nnz[i] > 4 * kThreads) threads = kBuildThreadsLarge;
     for (int i = 0; i < n; ++i) {
         rpt_off[i] = rpt_words;
         nz_pack[i] = nz;
@@ -830,15 +867,8 @@ int plan_host_coo(bspmm_plan& p, const bspmm_coo_batch* b, int32_t F, const Knob
         r.m = b->cols[i];                 // bound of the payload (column)
         r.k = b->rows[i];                 // number of keys (rows)
         r.nnz = b->nnz[i];
-        const int64_t work = (int64_t)b->rows[i] + 1 + b->nnz[i];
-        r.small = b->nnz[i] <= 4 * kThreads && work * 4 <= kBuildLdsBytes - 2048 ? 1 : 0;   // register path
-        if (work * 4 <= kBuildLdsBytes - 2048) {
-            r.scratch_off = -1;
-            lds_words = std::max(lds_words, work);
-        } else {
-            r.scratch_off = scratch_words;
-            scratch_words += work;
-        }
+        lds_words = std::max(lds_words, classify_build(r, b->rows[i], b->cols[i], b->nnz[i], false,
+                                                       threads, &scratch_words));
         rpt_words += (int64_t)b->rows[i] + 1;
         nz += b->nnz[i];
     }
@@ -900,7 +930,7 @@ int upload_plan(bspmm_plan* p, const bspmm_options* options, void* workspace,
         // The item tables of both directions and the operation records sit back to back at the
         // front of the workspace: one copy from one host image of that stretch (every copy from
         // pageable memory costs several microseconds of host time, whatever its size).
-        const size_t bytes = p->lay.op_records + p->records.size() * sizeof(OpRecord);
+        const size_t bytes = p->lay.build_order + p->build_order.size() * sizeof(int32_t);
         p->tables.assign(bytes, 0);
         for (int d = 0; d < 2; ++d)
             if (!p->sched[d].items.empty())
@@ -913,6 +943,9 @@ int upload_plan(bspmm_plan* p, const bspmm_options* options, void* workspace,
         if (!p->records.empty())
             std::memcpy(p->tables.data() + p->lay.op_records, p->records.data(),
                         p->records.size() * sizeof(OpRecord));
+        if (!p->build_order.empty())
+            std::memcpy(p->tables.data() + p->lay.build_order, p->build_order.data(),
+                        p->build_order.size() * sizeof(int32_t));
         if (bytes > 0)
             e = hipMemcpyAsync(p->ws, p->tables.data(), bytes, hipMemcpyHostToDevice, s);
     }
@@ -944,8 +977,9 @@ int upload_plan(bspmm_plan* p, const bspmm_options* options, void* workspace,
             if (e == hipSuccess)
                 e = launch_build_from_coo(
                     reinterpret_cast<const OpRecord*>(p->ws + p->lay.coo_records), p->batch,
-                    p->coo_build_lds_bytes, p->ids, p->coo_values, rpt, colids, values,
-                    reinterpret_cast<int32_t*>(p->ws + p->lay.coo_scratch), s);
+                    p->build_threads, p->coo_build_lds_bytes, p->ids, p->coo_values, rpt, colids, values,
+                    reinterpret_cast<int32_t*>(p->ws + p->lay.coo_scratch),
+                    reinterpret_cast<const int32_t*>(p->ws + p->lay.build_order), s);
         }
     }
     if (e != hipSuccess) return hip_fail(e);

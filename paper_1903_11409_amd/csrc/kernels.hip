@@ -1072,16 +1072,18 @@ bspmm_lean_kernel(const LeanItem* __restrict__ items, const int32_t* __restrict_
 // the row, the payload the column; `colids` is then the pair array, o.k the number of rows,
 // o.m the number of columns, and the result is the stable sort by row (entries of a row keep
 // their stored order).
-template <bool FROM_COO>
-__global__ void __launch_bounds__(kThreads)
+template <bool FROM_COO, int T>
+__global__ void __launch_bounds__(T)
 build_sorted_kernel(const OpRecord* __restrict__ ops, const int32_t* __restrict__ rpt,
                     const int32_t* __restrict__ colids, const float* __restrict__ values,
                     int32_t* __restrict__ rpt_t, int32_t* __restrict__ colids_t,
-                    float* __restrict__ values_t, int32_t* gscratch)
+                    float* __restrict__ values_t, int32_t* gscratch,
+                    const int32_t* __restrict__ order)
 {
     extern __shared__ __align__(16) int sm[];
-    __shared__ int partial[kThreads];
-    const OpRecord o = ops[blockIdx.x];
+    __shared__ int partial[T];
+    // (operations are taken largest first: the launch lasts as long as its slowest workgroup)
+    const OpRecord o = ops[order[blockIdx.x]];
     const int tid = threadIdx.x;
     const int k = o.k, m = o.m, nnz = o.nnz;
     int* cnt = o.scratch_off >= 0 ? gscratch + o.scratch_off : sm;   // k+1 ints
@@ -1103,15 +1105,15 @@ build_sorted_kernel(const OpRecord* __restrict__ ops, const int32_t* __restrict_
     // lane): one round trip to memory reads the operation into registers (and the row
     // pointers into LDS, which turns the search for an entry's row into LDS reads), the scan
     // runs on wavefront shuffles, and nothing is read twice.
-    if (o.small != 0) {
-        constexpr int E = 4;
+    if (o.small == 1) {
+        constexpr int E = build_entries_per_lane(T);
         int key[E], pay[E];
         float val[E];
         const float* va = values + o.nz_off;
         int* rps = pos + nnz;                              // CSR input only: m+1 row pointers
 #pragma unroll
         for (int u = 0; u < E; ++u) {
-            const int p = tid + u * kThreads;
+            const int p = tid + u * T;
             key[u] = -1;
             pay[u] = 0;
             val[u] = 0.f;
@@ -1128,8 +1130,8 @@ build_sorted_kernel(const OpRecord* __restrict__ ops, const int32_t* __restrict_
             }
         }
         if (!FROM_COO)
-            for (int i = tid; i <= m; i += kThreads) rps[i] = rp[i];
-        for (int c = tid; c <= k; c += kThreads) cnt[c] = 0;
+            for (int i = tid; i <= m; i += T) rps[i] = rp[i];
+        for (int c = tid; c <= k; c += T) cnt[c] = 0;
         __syncthreads();
 #pragma unroll
         for (int u = 0; u < E; ++u)
@@ -1138,7 +1140,7 @@ build_sorted_kernel(const OpRecord* __restrict__ ops, const int32_t* __restrict_
 
         // inclusive scan of cnt[0..k]: a lane sums its chunk, the wavefront scans the sums with
         // shuffles, the four wavefront totals go through LDS
-        const int chunk = (k + 1 + kThreads - 1) / kThreads;
+        const int chunk = (k + 1 + T - 1) / T;
         const int lo = tid * chunk;
         const int hi = min(lo + chunk, k + 1);
         int sum = 0;
@@ -1164,13 +1166,13 @@ build_sorted_kernel(const OpRecord* __restrict__ ops, const int32_t* __restrict_
         // scatter positions; cnt[c] ends as the first position of column c+1
 #pragma unroll
         for (int u = 0; u < E; ++u)
-            if (key[u] >= 0) pos[atomicAdd(&cnt[key[u]], 1)] = tid + u * kThreads;
+            if (key[u] >= 0) pos[atomicAdd(&cnt[key[u]], 1)] = tid + u * T;
         __syncthreads();
 
 #pragma unroll
         for (int u = 0; u < E; ++u) {
             if (key[u] < 0) continue;
-            const int p = tid + u * kThreads;
+            const int p = tid + u * T;
             const int c = key[u];
             const int beg = c > 0 ? cnt[c - 1] : 0;
             const int end = cnt[c];
@@ -1192,23 +1194,121 @@ build_sorted_kernel(const OpRecord* __restrict__ ops, const int32_t* __restrict_
         return;
     }
 
-    for (int c = tid; c <= k; c += kThreads) cnt[c] = 0;
+    // ---- operations of more than a thousand entries that still fit LDS (flagged 2 by the
+    // host): every entry is read from memory ONCE, in order, with all loads of a lane in flight
+    // together; its key and its payload - for CSR input the row, which a pass over the row
+    // pointers ORs in - are packed into one LDS word, so the histogram, the scatter and the
+    // ranking run out of LDS, and the last pass walks the entries in stored order again
+    // (coalesced value loads; the scattered side is the stores, which nothing waits for).
+    if (o.small == 2) {
+        const int kb = 32 - __clz(k);                     // bits of a key; the value k marks a skipped entry
+        const unsigned kmask = (1u << kb) - 1u;
+        unsigned* keyrow = reinterpret_cast<unsigned*>(pos + nnz);
+        for (int c = tid; c <= k; c += T) cnt[c] = 0;
+        __syncthreads();
+        for (int p0 = tid; p0 < nnz; p0 += 4 * T) {
+            int key[4], pay[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int p = p0 + u * T;
+                key[u] = k;
+                pay[u] = 0;
+                if (p < nnz) {
+                    if (FROM_COO) {
+                        const int r = ci[2 * p], c = ci[2 * p + 1];
+                        if ((unsigned)r < (unsigned)k && (unsigned)c < (unsigned)m) key[u] = r;
+                        pay[u] = c;
+                    } else {
+                        const int c = ci[p];
+                        if ((unsigned)c < (unsigned)k) key[u] = c;
+                    }
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int p = p0 + u * T;
+                if (p < nnz) {
+                    keyrow[p] = (unsigned)key[u] | (key[u] < k ? (unsigned)pay[u] << kb : 0u);
+                    if (key[u] < k) atomicAdd(&cnt[key[u] + 1], 1);
+                }
+            }
+        }
+        if (!FROM_COO) {
+            __syncthreads();          // keys in place before the rows are ORed in
+            for (int r = tid; r < m; r += T) {
+                const int b = min(max(rp[r + 1], 0), nnz);
+                const int a = min(max(rp[r], 0), b);
+                for (int p = a; p < b; ++p) atomicOr(&keyrow[p], (unsigned)r << kb);
+            }
+        }
+        __syncthreads();
+
+        // inclusive scan of cnt[0..k] (as below)
+        const int chunk = (k + 1 + T - 1) / T;
+        const int lo = tid * chunk;
+        const int hi = min(lo + chunk, k + 1);
+        int sum = 0;
+        for (int c = lo; c < hi; ++c) sum += cnt[c];
+        int incl = sum;
+        const int wl = tid & 63;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const int n = __shfl_up(incl, d);
+            if (wl >= d) incl += n;
+        }
+        if (wl == 63) partial[tid >> 6] = incl;
+        __syncthreads();
+        int run = incl - sum;
+        for (int w = 0; w < (tid >> 6); ++w) run += partial[w];
+        for (int c = lo; c < hi; ++c) {
+            run += cnt[c];
+            cnt[c] = run;
+            rt[c] = run;
+        }
+        __syncthreads();
+
+        // scatter positions; cnt[c] ends as the first position of key c+1
+        for (int p = tid; p < nnz; p += T) {
+            const int c = (int)(keyrow[p] & kmask);
+            if (c < k) pos[atomicAdd(&cnt[c], 1)] = p;
+        }
+        __syncthreads();
+
+        const float* va = values + o.nz_off;
+        float v_next = tid < nnz ? va[tid] : 0.f;
+        for (int p = tid; p < nnz; p += T) {
+            const float v = v_next;
+            if (p + T < nnz) v_next = va[p + T];     // in flight during this trip
+            const unsigned kr = keyrow[p];
+            const int c = (int)(kr & kmask);
+            if (c >= k) continue;
+            const int beg = c > 0 ? cnt[c - 1] : 0;
+            const int end = cnt[c];
+            int rank = 0;
+            for (int t = beg; t < end; ++t) rank += pos[t] < p ? 1 : 0;
+            colids_t[o.nz_t_off + beg + rank] = (int)(kr >> kb);
+            values_t[o.nz_t_off + beg + rank] = v;
+        }
+        return;
+    }
+
+    for (int c = tid; c <= k; c += T) cnt[c] = 0;
     __syncthreads();
-    for (int p = tid; p < nnz; p += kThreads) {
+    for (int p = tid; p < nnz; p += T) {
         const int c = key_of(p);
         if (c >= 0) atomicAdd(&cnt[c + 1], 1);
     }
     __syncthreads();
 
     // inclusive scan of cnt[0..k]: afterwards cnt[c] = first position of column c
-    const int chunk = (k + 1 + kThreads - 1) / kThreads;
+    const int chunk = (k + 1 + T - 1) / T;
     const int lo = tid * chunk;
     const int hi = lo + chunk < k + 1 ? lo + chunk : k + 1;
     int sum = 0;
     for (int c = lo; c < hi; ++c) sum += cnt[c];
     partial[tid] = sum;
     __syncthreads();
-    for (int d = 1; d < kThreads; d <<= 1) {
+    for (int d = 1; d < T; d <<= 1) {
         const int add = tid >= d ? partial[tid - d] : 0;
         __syncthreads();
         partial[tid] += add;
@@ -1223,7 +1323,7 @@ build_sorted_kernel(const OpRecord* __restrict__ ops, const int32_t* __restrict_
     __syncthreads();
 
     // scatter positions; cnt[c] ends as the first position of column c+1
-    for (int p = tid; p < nnz; p += kThreads) {
+    for (int p = tid; p < nnz; p += T) {
         const int c = key_of(p);
         if (c >= 0) pos[atomicAdd(&cnt[c], 1)] = p;
     }
@@ -1231,7 +1331,7 @@ build_sorted_kernel(const OpRecord* __restrict__ ops, const int32_t* __restrict_
 
     const float* va = values + o.nz_off;
     const int placed = cnt[k];                      // entries that were not skipped
-    for (int q = tid; q < placed; q += kThreads) {
+    for (int q = tid; q < placed; q += T) {
         const int p = pos[q];
         const int c = key_of(p);
         const int beg = c > 0 ? cnt[c - 1] : 0;
@@ -1813,14 +1913,21 @@ hipError_t launch_bspmm_gcn(const LaunchParams& P, int grid, int lds_bytes, bool
     return hipGetLastError();
 }
 
-hipError_t launch_build_transpose(const OpRecord* ops, int batch, int lds_bytes,
+hipError_t launch_build_transpose(const OpRecord* ops, int batch, int threads, int lds_bytes,
                                   const int32_t* rpt, const int32_t* colids,
                                   const float* values, int32_t* rpt_t, int32_t* colids_t,
-                                  float* values_t, int32_t* gscratch, hipStream_t stream)
+                                  float* values_t, int32_t* gscratch, const int32_t* order,
+                                  hipStream_t stream)
 {
     if (batch <= 0) return hipSuccess;
-    hipLaunchKernelGGL(build_sorted_kernel<false>, dim3(batch), dim3(kThreads), lds_bytes, stream,
-                       ops, rpt, colids, values, rpt_t, colids_t, values_t, gscratch);
+    if (threads == kBuildThreadsLarge)
+        hipLaunchKernelGGL((build_sorted_kernel<false, kBuildThreadsLarge>), dim3(batch),
+                           dim3(kBuildThreadsLarge), lds_bytes, stream, ops, rpt, colids, values,
+                           rpt_t, colids_t, values_t, gscratch, order);
+    else
+        hipLaunchKernelGGL((build_sorted_kernel<false, kThreads>), dim3(batch), dim3(kThreads),
+                           lds_bytes, stream, ops, rpt, colids, values, rpt_t, colids_t, values_t,
+                           gscratch, order);
     return hipGetLastError();
 }
 
@@ -1846,14 +1953,21 @@ hipError_t launch_bspmm_coo(const CooLaunchParams& P, int grid, int lds_bytes, b
 }
 
 // COO (index pairs `ids`, values) -> CSR arrays of every operation.
-hipError_t launch_build_from_coo(const OpRecord* ops, int batch, int lds_bytes, const int32_t* ids,
+hipError_t launch_build_from_coo(const OpRecord* ops, int batch, int threads, int lds_bytes, const int32_t* ids,
                                  const float* values, int32_t* rpt, int32_t* colids,
-                                 float* csr_values, int32_t* gscratch, hipStream_t stream)
+                                 float* csr_values, int32_t* gscratch, const int32_t* order,
+                                 hipStream_t stream)
 {
     if (batch <= 0) return hipSuccess;
-    hipLaunchKernelGGL(build_sorted_kernel<true>, dim3(batch), dim3(kThreads), lds_bytes, stream,
-                       ops, static_cast<const int32_t*>(nullptr), ids, values, rpt, colids,
-                       csr_values, gscratch);
+    if (threads == kBuildThreadsLarge)
+        hipLaunchKernelGGL((build_sorted_kernel<true, kBuildThreadsLarge>), dim3(batch),
+                           dim3(kBuildThreadsLarge), lds_bytes, stream, ops,
+                           static_cast<const int32_t*>(nullptr), ids, values, rpt, colids,
+                           csr_values, gscratch, order);
+    else
+        hipLaunchKernelGGL((build_sorted_kernel<true, kThreads>), dim3(batch), dim3(kThreads),
+                           lds_bytes, stream, ops, static_cast<const int32_t*>(nullptr), ids,
+                           values, rpt, colids, csr_values, gscratch, order);
     return hipGetLastError();
 }
 

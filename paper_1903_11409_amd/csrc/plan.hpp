@@ -17,6 +17,12 @@ constexpr int kRanges = 5;         // launch ranges: 256 lanes, fused 256, then 
 constexpr int kMaxMembers = 8;     // operations one fused task may add up
 constexpr int kMaxLdsBytes = 160 * 1024;    // LDS one workgroup can have on gfx950 (the whole CU's)
 constexpr int kBuildLdsBytes = 64 * 1024;   // most the transpose / conversion kernels take
+// The transpose / conversion kernels run one workgroup per operation: 256 lanes, or 1024 when
+// the batch has an operation of more than a thousand entries (the launch lasts as long as its
+// largest operation).  Operations of up to build_entries_per_lane(T) * T entries keep their
+// entries in registers.
+constexpr int kBuildThreadsLarge = 1024;
+BSPMM_HD constexpr int build_entries_per_lane(int threads) { return threads == kThreads ? 4 : 5; }
 constexpr int kHalfLdsBytes = 80 * 1024;    // half a CU's LDS (two workgroups per CU): default of the fused front
 
 // Slot size (lanes) of launch range r, and its log2.
