@@ -36,9 +36,12 @@ def parse_args():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
     ap.add_argument("--only", default=None,
-                    choices=["cfg2", "cfg3", "cfg4_F1024", "cfg5", "cfg5_transposed"],
+                    choices=["cfg2", "cfg2_F64", "cfg3", "cfg4_F256", "cfg4_F1024", "cfg5",
+                             "cfg5_transposed", "cfg5_staged_ops", "cfg5_row_block_ops"],
                     help="run only this configuration, HBM-cold, eager launches, and print a "
                          "short JSON line (for rocprofv3 counter runs per configuration)")
+    ap.add_argument("--no-graph", action="store_true",
+                    help="with --only: eager launches only (counter passes)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run a 256 MiB elementwise copy kernel of known traffic "
                          "(scale reference for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
@@ -386,6 +389,19 @@ def layer_whole(torch, K, W, n_x=64, channels=4, graphs=128):
     return out
 
 
+def kernel_resources(K, lds_bytes):
+    """Registers, LDS and workgroups per CU of the library's kernels (bspmm_kernel_info)."""
+    out = {}
+    for i, name in enumerate(K.KERNEL_NAMES):
+        dyn = lds_bytes if name in ("lean", "general", "general_scalar", "coo") else 0
+        r = K.bspmm_kernel_info(i, dyn)
+        out[name] = {"vgprs": r.vgprs, "static_lds_bytes": r.static_lds_bytes,
+                     "scratch_bytes": r.scratch_bytes, "lanes_per_workgroup": r.threads,
+                     "dynamic_lds_bytes_assumed": dyn, "workgroups_per_cu": r.workgroups_per_cu,
+                     "compute_units": r.compute_units}
+    return out
+
+
 _marker = None
 
 
@@ -536,7 +552,7 @@ def cpu_baseline(oracle, b, seconds, eff_bytes, flops):
 
 def read_traffic():
     """HBM bytes per launch from the committed rocprofv3 counter summary, if there is one."""
-    path = os.path.join(ROOT, "profiles", "bspmm_kernel_cfg2_F128_pmc.txt")
+    path = os.path.join(ROOT, "profiles", "bspmm_lean_kernel_cfg2_F128_pmc.txt")
     try:
         for line in open(path):
             if line.startswith("traffic_bytes_per_launch"):
@@ -560,16 +576,46 @@ def main():
     K.lib()
 
     if args.only:
+        def cfg5_part(generic):
+            # config 5 cut in two by what the scheduler does with an operation: staged in LDS, or
+            # too large for it and cut into row blocks that gather from L2 (per-bin evidence)
+            b5 = W.config5_skewed()
+            h = K.dry_plan(b5)
+            blocks = {it.op for it in K.bspmm_plan_items(h) if it.bin == K.BIN_GENERIC}
+            K.bspmm_destroy(h)
+            ops = [i for i in range(b5.batch) if (i in blocks) == generic]
+            return b5.subset(ops, name="cfg5_row_block_ops" if generic else "cfg5_staged_ops")
+
         mk, tr = {"cfg2": (lambda: W.config2_molecule(F=128), False),
+                  "cfg2_F64": (lambda: W.config2_molecule(F=64), False),
                   "cfg3": (lambda: W.config3_multichannel(), False),
+                  "cfg4_F256": (lambda: W.config4_wide(F=256), False),
                   "cfg4_F1024": (lambda: W.config4_wide(F=1024), False),
                   "cfg5": (lambda: W.config5_skewed(), False),
-                  "cfg5_transposed": (lambda: W.config5_skewed(), True)}[args.only]
+                  "cfg5_transposed": (lambda: W.config5_skewed(), True),
+                  "cfg5_staged_ops": (lambda: cfg5_part(False), False),
+                  "cfg5_row_block_ops": (lambda: cfg5_part(True), False)}[args.only]
+        if args.calib_copy:
+            a = torch.ones(1 << 26, dtype=torch.float32, device="cuda")
+            c = torch.empty_like(a)
+            for _ in range(3):
+                torch.mul(a, 1.0, out=c)      # reads 256 MiB, writes 256 MiB
+            torch.cuda.synchronize()
+            del a, c
         r = Runner(torch, K, mk(), transposed=tr)
         steps = min(args.steps, 400)
         sec = r.time_eager(steps, min(args.warmup, 40))
+        sec_graph = sec if args.no_graph else r.time_graph(steps, min(args.warmup, 40))[0]
+        d = 1 if tr else 0
         line = r.summary(sec)
-        line.update({"workload": args.only, "launches": steps, "mode": "eager, HBM-cold"})
+        line.update({"workload": args.only, "launches": steps, "mode": "eager, HBM-cold",
+                     **({} if args.no_graph else {
+                         "us_per_launch_hipgraph": round(sec_graph * 1e6, 3),
+                         "eff_GBps_hipgraph": round(r.eff_bytes / sec_graph * 1e-9, 1)}),
+                     "lean": int(r.info.lean[d]), "bins": list(r.info.items_in_bin[d]),
+                     "dynamic_lds_bytes": int(r.info.lds_bytes),
+                     "kernel": kernel_resources(K, int(r.info.lds_bytes))[
+                         "lean" if r.info.lean[d] else "general"]})
         print(json.dumps(line))
         return
 
@@ -641,6 +687,10 @@ def main():
         extra["headline_eager_5_repeats_us"] = {"median": round(reps_eager[2] * 1e6, 3),
                                                 "min": round(reps_eager[0] * 1e6, 3),
                                                 "max": round(reps_eager[4] * 1e6, 3)}
+        extra["kernel_resources"] = kernel_resources(K, int(head.info.lds_bytes))
+        extra["headline_launch"] = {"kernel": "bspmm_lean_kernel" if head.info.lean[0] else "bspmm_kernel<4>",
+                                    "workgroups": head.workgroups,
+                                    "dynamic_lds_bytes": int(head.info.lds_bytes)}
         extra["plan_create_ms"] = round(head.create_ms, 3)
         # the paper's batched timings include handing the matrix list to the device: plan
         # creation through the C ABI (schedule, upload) plus one product, device arrays in place
@@ -738,9 +788,10 @@ def main():
                      "frac": round(head.eff_bytes / sec * 1e-9 / HBM_PEAK_GBPS, 4),
                      "traffic": read_traffic(),
                      "traffic_source": "committed rocprofv3 counter summary profiles/"
-                                       "bspmm_kernel_cfg2_F128_pmc.txt (a separate run of this "
+                                       "bspmm_lean_kernel_cfg2_F128_pmc.txt (a separate run of this "
                                        "workload, not measured by this process)",
-                     "kernel": "bspmm_kernel<4>", "bytes_per_launch": head.eff_bytes},
+                     "kernel": "bspmm_lean_kernel" if head.info.lean[0] else "bspmm_kernel<4>",
+                     "bytes_per_launch": head.eff_bytes},
     }
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(oracle, b, args.cpu_seconds, head.eff_bytes, head.flops)

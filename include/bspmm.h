@@ -356,6 +356,33 @@ int bspmm_export_csr(bspmm_plan* plan, int32_t* rpt, int32_t* colids, float* val
  */
 int bspmm_validate(bspmm_plan* plan, int32_t* bad_op, void* stream);
 
+/*
+ * What a kernel of the library needs on the current device (for profiles and occupancy
+ * arguments; asks the HIP runtime, launches nothing): vector and scalar registers per lane /
+ * wavefront, LDS the kernel declares itself (the launch adds `dynamic_lds_bytes`), and how many
+ * of its workgroups a compute unit holds at once with that much dynamic LDS.
+ * kernel: BSPMM_KERNEL_*.  EINVAL for an unknown kernel, EHIP when the runtime cannot tell.
+ */
+#define BSPMM_KERNEL_LEAN      0  /* bspmm_run / bspmm_run_transposed, lean launches               */
+#define BSPMM_KERNEL_GENERAL   1  /* the same, every other launch (float4 path, no slots, no hubs) */
+#define BSPMM_KERNEL_GENERAL_S 2  /* the general kernel's scalar path                              */
+#define BSPMM_KERNEL_FRONT     3  /* bspmm_run_gcn, one channel                                    */
+#define BSPMM_KERNEL_LAYER     4  /* bspmm_run_gcn, whole layer                                    */
+#define BSPMM_KERNEL_BUILD     5  /* transposed-CSR build, 256 lanes                               */
+#define BSPMM_KERNEL_BUILD_L   6  /* transposed-CSR build, 1024 lanes                              */
+#define BSPMM_KERNEL_COO       7  /* direct COO product                                            */
+typedef struct bspmm_kernel_resources {
+    int32_t vgprs;              /* vector registers per lane                                   */
+    int32_t sgprs;              /* scalar registers per wavefront (0: the runtime does not say)*/
+    int32_t static_lds_bytes;   /* LDS declared in the kernel                                  */
+    int32_t scratch_bytes;      /* private (spill) memory per lane                             */
+    int32_t threads;            /* lanes per workgroup the kernel is launched with             */
+    int32_t workgroups_per_cu;  /* resident workgroups per CU at dynamic_lds_bytes             */
+    int32_t compute_units;
+    int32_t reserved_;
+} bspmm_kernel_resources;
+int bspmm_kernel_info(int32_t kernel, int32_t dynamic_lds_bytes, bspmm_kernel_resources* out);
+
 /* Fill *info.  Works on dry-run plans. */
 int bspmm_plan_info(const bspmm_plan* plan, bspmm_info* info);
 

@@ -67,6 +67,13 @@ class bspmm_info(ctypes.Structure):
                 ("workspace_bytes", ctypes.c_uint64)]
 
 
+class bspmm_kernel_resources(ctypes.Structure):
+    _fields_ = [("vgprs", ctypes.c_int32), ("sgprs", ctypes.c_int32),
+                ("static_lds_bytes", ctypes.c_int32), ("scratch_bytes", ctypes.c_int32),
+                ("threads", ctypes.c_int32), ("workgroups_per_cu", ctypes.c_int32),
+                ("compute_units", ctypes.c_int32), ("reserved_", ctypes.c_int32)]
+
+
 class bspmm_item(ctypes.Structure):
     _fields_ = [("op", ctypes.c_int32), ("bin", ctypes.c_int32), ("row0", ctypes.c_int32),
                 ("nrows", ctypes.c_int32), ("f0", ctypes.c_int32), ("fw", ctypes.c_int32),
@@ -77,7 +84,8 @@ EXPORTS = ["bspmm_workspace_bytes", "bspmm_create", "bspmm_run", "bspmm_run_tran
            "bspmm_export_transposed", "bspmm_validate", "bspmm_plan_info", "bspmm_plan_items",
            "bspmm_destroy", "bspmm_strerror", "bspmm_last_hip_error",
            "bspmm_workspace_bytes_coo", "bspmm_create_coo", "bspmm_export_csr", "bspmm_run_gcn",
-           "bspmm_create_static"]
+           "bspmm_create_static", "bspmm_kernel_info"]
+KERNEL_NAMES = ["lean", "general", "general_scalar", "front", "layer", "build", "build_large", "coo"]
 STATIC_WORKSPACE_BYTES = 8 * 1024 * 1024
 
 _lib = None
@@ -123,6 +131,8 @@ def lib():
         L.bspmm_export_csr.argtypes = [vp, vp, vp, vp, vp]
         L.bspmm_run_gcn.argtypes = [vp, vp, ctypes.c_int64, vp, ctypes.c_int64, vp, vp,
                                     ctypes.c_int64, ctypes.c_int32, vp]
+        L.bspmm_kernel_info.argtypes = [ctypes.c_int32, ctypes.c_int32,
+                                        ctypes.POINTER(bspmm_kernel_resources)]
         L.bspmm_plan_info.argtypes = [vp, ctypes.POINTER(bspmm_info)]
         L.bspmm_plan_items.argtypes = [vp, ctypes.c_int32, ctypes.POINTER(bspmm_item),
                                        ctypes.c_int32, _i32p]
@@ -318,6 +328,13 @@ def bspmm_validate(plan: int, stream=None) -> int:
         return int(bad.value)
     _check(rc, "bspmm_validate")
     return -1
+
+
+def bspmm_kernel_info(kernel: int, dynamic_lds_bytes: int = 0) -> bspmm_kernel_resources:
+    out = bspmm_kernel_resources()
+    _check(lib().bspmm_kernel_info(int(kernel), int(dynamic_lds_bytes), ctypes.byref(out)),
+           "bspmm_kernel_info")
+    return out
 
 
 def bspmm_plan_info(plan: int) -> bspmm_info:

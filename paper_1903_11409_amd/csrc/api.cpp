@@ -41,6 +41,7 @@ hipError_t launch_merge_sets(const SetRecord* sets, int count, const int32_t* rp
 hipError_t launch_validate_coo(const OpRecord* ops, int batch, const int32_t* ids, int32_t* flag,
                                hipStream_t stream);
 int bspmm_max_resident_workgroups(int lds_bytes, bool slices, bool hubs);
+hipError_t kernel_resources(int which, int lds_bytes, int out[7]);
 hipError_t launch_validate(const OpRecord* ops, int batch, const int32_t* rpt,
                            const int32_t* colids, int32_t* flag, hipStream_t stream);
 }  // namespace bspmm
@@ -1373,6 +1374,26 @@ int bspmm_validate(bspmm_plan* plan, int32_t* bad_op, void* stream)
         if (bad_op) *bad_op = host_flag;
         return BSPMM_EBADCSR;
     }
+    return BSPMM_OK;
+}
+
+int bspmm_kernel_info(int32_t kernel, int32_t dynamic_lds_bytes, bspmm_kernel_resources* out)
+{
+    if (!out || kernel < 0 || kernel > BSPMM_KERNEL_COO || dynamic_lds_bytes < 0) return BSPMM_EINVAL;
+    int v[7] = {0, 0, 0, 0, 0, 0, 0};
+    const hipError_t e = kernel_resources(kernel, dynamic_lds_bytes, v);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        return hip_fail(e);
+    }
+    out->vgprs = v[0];
+    out->sgprs = v[1];
+    out->static_lds_bytes = v[2];
+    out->scratch_bytes = v[3];
+    out->threads = v[4];
+    out->workgroups_per_cu = v[5];
+    out->compute_units = v[6];
+    out->reserved_ = 0;
     return BSPMM_OK;
 }
 

@@ -1875,6 +1875,45 @@ int bspmm_max_resident_workgroups(int lds_bytes, bool slices, bool hubs)
     return per_cu > 0 && cus > 0 ? per_cu * cus : 0;
 }
 
+// Registers, LDS and occupancy of kernel `which` (BSPMM_KERNEL_* of the public header) on the
+// current device.  out: vgprs, sgprs, static LDS, scratch, lanes per workgroup, workgroups per CU
+// at `lds_bytes` of dynamic LDS, compute units.
+hipError_t kernel_resources(int which, int lds_bytes, int out[7])
+{
+    const void* fn = nullptr;
+    int threads = kThreads;
+    switch (which) {
+        case 0: fn = reinterpret_cast<const void*>(&bspmm_lean_kernel); break;
+        case 1: fn = reinterpret_cast<const void*>(&bspmm_kernel<4, false, false, false>); break;
+        case 2: fn = reinterpret_cast<const void*>(&bspmm_kernel<1, false, false, false>); break;
+        case 3: fn = reinterpret_cast<const void*>(&bspmm_gcn_kernel<false, false>); break;
+        case 4: fn = reinterpret_cast<const void*>(&bspmm_gcn_kernel<false, true>); break;
+        case 5: fn = reinterpret_cast<const void*>(&build_sorted_kernel<false, kThreads>); break;
+        case 6:
+            fn = reinterpret_cast<const void*>(&build_sorted_kernel<false, kBuildThreadsLarge>);
+            threads = kBuildThreadsLarge;
+            break;
+        case 7: fn = reinterpret_cast<const void*>(&bspmm_coo_kernel<4>); break;
+        default: return hipErrorInvalidValue;
+    }
+    hipFuncAttributes a;
+    hipError_t e = hipFuncGetAttributes(&a, fn);
+    if (e != hipSuccess) return e;
+    int per_cu = 0, dev = 0, cus = 0;
+    e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, threads, (size_t)lds_bytes);
+    if (e == hipSuccess) e = hipGetDevice(&dev);
+    if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    if (e != hipSuccess) return e;
+    out[0] = a.numRegs;
+    out[1] = 0;
+    out[2] = (int)a.sharedSizeBytes;
+    out[3] = (int)a.localSizeBytes;
+    out[4] = threads;
+    out[5] = per_cu;
+    out[6] = cus;
+    return hipSuccess;
+}
+
 hipError_t launch_bspmm(const LaunchParams& P, int grid, int lds_bytes, bool vec4, bool slices,
                         bool hubs, bool merged, hipStream_t stream)
 {

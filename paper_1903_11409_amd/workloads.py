@@ -94,6 +94,38 @@ class Batch:
             nnz=self.nnz[i:i + 1], rpt_off=z, nz_off=z.copy(), b_row_off=self.b_row_off[i:i + 1],
             c_row_off=self.c_row_off[i:i + 1], rpt=rpt, colids=ci, values=va, n_graphs=1)
 
+    def subset(self, ops: Sequence[int], name: Optional[str] = None) -> "Batch":
+        """The operations ``ops`` alone, repacked: CSR arrays, dense input rows and output rows
+        back to back in the order given (operations that read one dense block keep sharing
+        it only if it is listed once: every operation gets a block of its own here)."""
+        ops = np.asarray(list(ops), dtype=np.int64)
+        rows, cols, nnz = self.rows[ops], self.cols[ops], self.nnz[ops]
+        parts = [self.op_csr(int(i)) for i in ops]
+
+        def cat(j, dtype):
+            return (np.concatenate([p[j] for p in parts]).astype(dtype) if len(parts)
+                    else np.zeros(0, dtype=dtype))
+
+        def starts(lengths):
+            out = np.zeros(len(lengths), dtype=np.int64)
+            if len(lengths) > 1:
+                out[1:] = np.cumsum(np.asarray(lengths[:-1], dtype=np.int64))
+            return out
+
+        b_off, c_off = starts(cols), starts(rows)
+        B = (np.concatenate([self.B[int(self.b_row_off[i]):int(self.b_row_off[i]) + int(self.cols[i])]
+                             for i in ops]) if len(ops) else np.zeros((0, self.F), np.float32))
+        dY = None
+        if self.dY is not None:
+            dY = (np.concatenate([self.dY[int(self.c_row_off[i]):int(self.c_row_off[i]) + int(self.rows[i])]
+                                  for i in ops]) if len(ops) else np.zeros((0, self.F), np.float32))
+        return dataclasses.replace(
+            self, name=name or f"{self.name}[{len(ops)} ops]", rows=rows, cols=cols, nnz=nnz,
+            rpt_off=starts(rows.astype(np.int64) + 1), nz_off=starts(nnz), b_row_off=b_off,
+            c_row_off=c_off, rpt=cat(0, np.int32), colids=cat(1, np.int32), values=cat(2, np.float32),
+            B=np.ascontiguousarray(B), dY=None if dY is None else np.ascontiguousarray(dY),
+            n_b_rows=int(cols.sum()), n_c_rows=int(rows.sum()), n_graphs=int(len(ops)))
+
     def with_F(self, F: int, seed: int) -> "Batch":
         """Same sparse structure, fresh dense input of width ``F``."""
         rng = np.random.default_rng(seed)
