@@ -688,3 +688,53 @@ def test_a_plan_is_handed_from_workspace_bytes_to_create_only_for_the_same_batch
     # another batch of the same length
     b3 = W.config2_molecule(seed=5, graphs=12, F=64)
     assert items_of(b1, b3) == fresh(b3) and fresh(b3) != fresh(b1)
+
+
+def _lean_of(b, F=None, **opts):
+    h = K.dry_plan(b, F if F is not None else b.F, **opts)
+    try:
+        info = K.bspmm_plan_info(h)
+        return [int(info.lean[0]), int(info.lean[1])], info, K.bspmm_plan_items(h)
+    finally:
+        K.bspmm_destroy(h)
+
+
+@pytest.mark.parametrize("maker,kw", [(W.config2_molecule, {"F": 64}), (W.config2_molecule, {}),
+                                      (W.config4_wide, {"F": 256}), (W.config4_wide, {}),
+                                      (W.config5_skewed, {})])
+def test_whole_workgroup_launches_take_the_lean_kernel(maker, kw):
+    """The benchmark's launches (molecule graphs, wide features, the skewed training batch) are
+    made only of whole-workgroup items, staged operations and row blocks of the generic bin, with
+    tile rows of a power-of-two number of float4: both directions are marked for the lean
+    kernel."""
+    b = maker(**kw)
+    lean, info, items = _lean_of(b)
+    assert lean == [1, 1]
+    assert all(it.bin in (K.BIN_WORKGROUP, K.BIN_GENERIC) for it in items)
+    for it in items:
+        nvec = it.fw // 4
+        assert it.fw % 4 == 0 and nvec & (nvec - 1) == 0 and 0 < nvec <= 64
+
+
+@pytest.mark.parametrize("why,maker,F,opts", [
+    ("odd width: scalar path", W.config2_molecule, 63, {}),
+    ("tile rows not a power of two", W.config2_molecule, 96, {"min_tile": 96, "max_tile": 96}),
+    ("hub rows", W.config2_molecule, 128, {"flags": K.SPLIT_HUB_ROWS}),
+    ("padding", W.config2_molecule, 128, {"lds_pad": 4}),
+    ("resident workgroups", W.config2_molecule, 128, {"resident_workgroups": 64}),
+    ("sub-workgroup slots", W.config2_molecule, 128, {"force_bin": K.BIN_WAVE}),
+])
+def test_what_the_lean_kernel_does_not_do_keeps_the_general_one(why, maker, F, opts):
+    b = maker(F=F)
+    lean, _, _ = _lean_of(b, F, **opts)
+    assert lean == [0, 0], why
+
+
+def test_summed_channels_and_fused_fronts_keep_the_general_kernel():
+    c = W.config3_multichannel(graphs=32, accumulate=True)
+    assert _lean_of(c, flags=K.ACCUMULATE)[0] == [0, 0]
+    assert _lean_of(c, flags=K.ACCUMULATE, front_features=32)[0][0] == 0
+    # the same channels as separate outputs are plain whole-workgroup items (their transposed
+    # products would be sums into the shared input block: not planned without the flag)
+    lean, info, _ = _lean_of(W.config3_multichannel(graphs=32))
+    assert lean == [1, 0] and not info.transposed_supported
