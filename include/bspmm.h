@@ -105,6 +105,10 @@ extern "C" {
                                       arrays and no transposed CSR is ever built.  Not checked;
                                       with an asymmetric A_i the result is A_i . dY_i.  Operations
                                       must be square (EINVAL)                                    */
+#define BSPMM_ONE_FRONT_LAUNCH 128u /* whole-layer plans (front_features with BSPMM_ACCUMULATE) of
+                                      many rounds of workgroups normally run as a launch of resident
+                                      workgroups that stream the graphs (see bspmm_run_gcn); this
+                                      flag keeps them on the one-launch path                     */
 #define BSPMM_FLOOR_PROBE      4u  /* measurement aid: same grid, LDS and item fetches, but every
                                       item is emptied, so a run computes and writes nothing      */
 
@@ -204,6 +208,11 @@ typedef struct bspmm_info {
     int32_t lean[2];                         /* 1: every task is one staged workgroup item with a
                                                 power-of-two tile, so runs with 16-byte aligned
                                                 operands launch the lean kernel                */
+    int32_t front_stream[4];                 /* whole-layer plans run by resident workgroups
+                                                that stream the graphs (see bspmm_run_gcn):
+                                                graphs in their lists, workgroups, LDS bytes per
+                                                workgroup, graphs left to a launch of their own;
+                                                all 0 otherwise                                */
     int64_t effective_bytes[2];              /* CSR + distinct dense inputs + outputs, once   */
     int64_t flops;                           /* 2 * nnz * F (Sec. V-A)                        */
     uint64_t workspace_bytes;
@@ -295,6 +304,16 @@ int bspmm_run(bspmm_plan* plan, const float* B, float* C, int64_t ldb, int64_t l
  * ElementWiseAdd) with X_i staged once for all channels.  W is then the M weight matrices one
  * under the other (M * n_X rows, channel ch at row ch * n_X) and bias M rows of F floats; the
  * channels of a graph are taken in the order of their operations.
+ *
+ * Whole layers of many rounds of workgroups (8 feature tiles per CU and more; M = 2, 4 or 8
+ * channels, n_X = 16, 32, 64 or 128) run as a launch of RESIDENT workgroups instead, three per CU:
+ * each keeps the weights of its feature tile in registers for the whole launch and streams the
+ * graphs of its list through LDS, the next graph's X_i and merged CSR in flight while the matrix
+ * cores work on this one's; graphs too large for a third of a CU's LDS are taken in two halves
+ * of 16 columns by the same workgroups (M = 4), or follow in a launch of the one-launch kernel
+ * over their items.  bspmm_info.front_stream says what a plan does; BSPMM_ONE_FRONT_LAUNCH keeps
+ * a plan on the one-launch path.  With options.lds_bytes the caller fixes the LDS budget of
+ * both.
  */
 int bspmm_run_gcn(bspmm_plan* plan, const float* X, int64_t ldx, const float* W, int64_t ldw,
                   const float* bias, float* Y, int64_t ldy, int32_t accumulate, void* stream);
@@ -371,6 +390,8 @@ int bspmm_validate(bspmm_plan* plan, int32_t* bad_op, void* stream);
 #define BSPMM_KERNEL_BUILD     5  /* transposed-CSR build, 256 lanes                               */
 #define BSPMM_KERNEL_BUILD_L   6  /* transposed-CSR build, 1024 lanes                              */
 #define BSPMM_KERNEL_COO       7  /* direct COO product                                            */
+#define BSPMM_KERNEL_LAYER_STREAM 8 /* bspmm_run_gcn, whole layer, resident streaming workgroups
+                                       (n_X = 64, two blocks per wavefront)                        */
 typedef struct bspmm_kernel_resources {
     int32_t vgprs;              /* vector registers per lane                                   */
     int32_t sgprs;              /* scalar registers per wavefront (0: the runtime does not say)*/

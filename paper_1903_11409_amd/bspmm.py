@@ -17,6 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libbspmm.so")
 
 OK, EINVAL, ENOSPACE, EHIP, EOVERLAP, ESTATE, EBADCSR, ETOOBIG = 0, -1, -2, -3, -4, -5, -6, -7
 DRY_RUN, BUILD_TRANSPOSE, FLOOR_PROBE, SPLIT_HUB_ROWS, ACCUMULATE, COO_DIRECT, SYMMETRIC = 1, 2, 4, 8, 16, 32, 64
+ONE_FRONT_LAUNCH = 128
 BIN_WORKGROUP, BIN_WAVE, BIN_SLICE32, BIN_SLICE16, BIN_GENERIC = 0, 1, 2, 3, 4
 NUM_BINS = 5
 BIN_COO = 5          # items of a COO_DIRECT plan
@@ -63,6 +64,7 @@ class bspmm_info(ctypes.Structure):
                 ("transposed_supported", ctypes.c_int32),
                 ("transposed_built", ctypes.c_int32),
                 ("lean", ctypes.c_int32 * 2),
+                ("front_stream", ctypes.c_int32 * 4),
                 ("effective_bytes", ctypes.c_int64 * 2), ("flops", ctypes.c_int64),
                 ("workspace_bytes", ctypes.c_uint64)]
 
@@ -85,7 +87,8 @@ EXPORTS = ["bspmm_workspace_bytes", "bspmm_create", "bspmm_run", "bspmm_run_tran
            "bspmm_destroy", "bspmm_strerror", "bspmm_last_hip_error",
            "bspmm_workspace_bytes_coo", "bspmm_create_coo", "bspmm_export_csr", "bspmm_run_gcn",
            "bspmm_create_static", "bspmm_kernel_info"]
-KERNEL_NAMES = ["lean", "general", "general_scalar", "front", "layer", "build", "build_large", "coo"]
+KERNEL_NAMES = ["lean", "general", "general_scalar", "front", "layer", "build", "build_large", "coo",
+                "layer_stream"]
 STATIC_WORKSPACE_BYTES = 8 * 1024 * 1024
 
 _lib = None

@@ -33,7 +33,7 @@ def build(verbose: bool = False) -> str:
            # dependent fetch, the work item, goes out at once instead of after a kernel-argument
            # load
            "-mllvm", "-amdgpu-kernarg-preload-count=16",
-           "-Wall", "-Wno-unused-command-line-argument",
+           "-Wall", "-Wno-unused-command-line-argument", "-Wno-inline-asm",
            "-x", "hip", os.path.join(CSRC, "kernels.hip"),
            "-x", "hip", os.path.join(CSRC, "schedule.cpp"),
            "-x", "hip", os.path.join(CSRC, "api.cpp"),

@@ -24,6 +24,10 @@ hipError_t launch_bspmm_lean(const LeanItem* items, const LaunchParams& P, int g
 hipError_t launch_lean_hints(LeanItem* items, int n, const int32_t* rpt, hipStream_t stream);
 hipError_t launch_bspmm_gcn(const LaunchParams& P, int grid, int lds_bytes, bool accumulate,
                             bool sets, hipStream_t stream);
+hipError_t launch_bspmm_gcn_stream(const StreamParams& S, int nx16, int units, int grid,
+                                   int lds_bytes, hipStream_t stream);
+bool stream_supported(int nx16, int units);
+int stream_workgroups_per_cu(int nx16, int units, int lds_bytes);
 hipError_t launch_build_transpose(const OpRecord* ops, int batch, int threads, int lds_bytes,
                                   const int32_t* rpt, const int32_t* colids,
                                   const float* values, int32_t* rpt_t, int32_t* colids_t,
@@ -80,6 +84,9 @@ struct Layout {
     // summed sets (BSPMM_ACCUMULATE), per direction: their records and their merged CSR arrays
     size_t sets[2] = {0, 0};
     size_t merged[2] = {0, 0};
+    // whole layers run by streaming workgroups: graph records, list bounds, and the items of the
+    // graphs that stay with the one-launch kernel
+    size_t stream_sets = 0, stream_list = 0, stream_rest = 0;
     // plans made from COO operands: the CSR arrays built on the device and what the build needs
     size_t coo_records = 0;
     size_t csr_rpt = 0, csr_colids = 0, csr_values = 0;
@@ -117,6 +124,20 @@ struct bspmm_plan {
     int64_t merged_words[2] = {0, 0};
     bool merged_built[2] = {false, false};
     int front_channels = 1;   // fused front with BSPMM_ACCUMULATE: channels per output block
+    // Whole layers in launches of many rounds: the graphs that fit the LDS budget of the
+    // streaming launch, in list order; list l is sets[list[l]] .. sets[list[l + 1]]; the items of
+    // the other graphs, for a launch of bspmm_gcn_kernel of their own.
+    struct Stream {
+        std::vector<StreamSet> sets;
+        std::vector<int32_t> list;
+        std::vector<WorkItem> rest;
+        int nx16 = 0, units = 0, fw = 0, tiles = 0, lists = 0;
+        int tile_words = 0, x_words = 0, csr_words = 0;
+        int big_csr_words = 0;     // room for the merged CSR block of a graph taken in halves
+        int big = 0;               // graphs taken in halves
+        int lds_bytes() const { return 4 * (tile_words + 2 * x_words + 2 * csr_words + 64); }
+        bool on() const { return !sets.empty(); }
+    } stream;
     int64_t effective_bytes[2] = {0, 0};
     int64_t flops = 0;
     bool reads_dense = false;   // some operation has rows and columns: the runs read the dense input
@@ -253,6 +274,160 @@ void describe_sets(bspmm_plan& p, int d)
             sc.items[j].rpt_off = r.merged_rpt_off;
             sc.items[j].nz_off = r.merged_nz_off;
         }
+}
+
+// Whole layers (front_features with BSPMM_ACCUMULATE) in launches of many rounds of workgroups:
+// the plan of the streaming launch.  Every graph is a set of M channel operations with one
+// merged CSR; a workgroup of the streaming kernel holds the weights of its feature tile in
+// registers (M * fw / 16 blocks of 16 columns over four wavefronts: one or two per wavefront)
+// and takes the graphs of its list one after the other.  The launch's LDS is sized for the
+// graphs it takes: those that fit the budget (three workgroups per CU unless the caller fixed
+// lds_bytes), smallest first; the few larger ones keep their items of the one-launch schedule and
+// run in a launch of their own.  Lists are balanced by longest-processing-time-first on the
+// number of 16-row blocks.
+void make_stream_plan(bspmm_plan& p)
+{
+    bspmm_plan::Stream& st = p.stream;
+    st = bspmm_plan::Stream();
+    const Schedule& sc = p.sched[0];
+    const Knobs& kn = p.knobs;
+    const int M = p.front_channels, nx = kn.front, F = p.F;
+    if (nx <= 0 || !kn.accumulate || kn.one_front_launch || sc.merged_sets.empty() ||
+        !sc.fused_sets.empty() || sc.fused_tasks > 0 || p.merged_words[0] >= (int64_t(1) << 32))
+        return;
+    if (nx % 16 != 0 || (M != 2 && M != 4 && M != 8)) return;
+    const int nx16 = nx / 16;
+    int units = 0, fw = 0;
+    for (int u : {2, 1}) {
+        const int w = 64 * u / M;
+        if (w >= 16 && F % w == 0 && stream_supported(nx16, u)) {
+            units = u;
+            fw = w;
+            break;
+        }
+    }
+    if (!units) return;
+    const int tiles = F / fw;
+    const size_t n_sets = sc.merged_sets.size();
+    // a launch of one or two rounds gains nothing from resident workgroups
+    if ((int64_t)n_sets * tiles < 8 * (int64_t)kn.compute_units) return;
+    if (p.set_records[0].size() != n_sets) return;
+
+    // the graphs by size; take them while the launch's LDS stays inside the budget
+    // (three workgroups per CU: a third of the CU's 160 KiB less what the allocation granule
+    // takes; 53920 bytes were measured to leave room for two only)
+    const int64_t budget_words = (kn.lds_given ? kn.lds_words * 4 : 53248) / 4;
+    const int rows_most = kStreamPasses * (kThreads / (fw / 4));
+    std::vector<int> order(n_sets);
+    for (size_t i = 0; i < n_sets; ++i) order[i] = (int)i;
+    const std::vector<SetRecord>& recs = p.set_records[0];
+    auto nnz_of = [&](int i) {
+        int64_t n = 0;
+        for (int j = 0; j < recs[i].members; ++j) n += recs[i].nnz[j];
+        return n;
+    };
+    // (X_i has k rows, the same for every channel of a graph; Y_i has m)
+    auto words_of = [&](int64_t kx, int64_t csr) { return (int64_t)M * kx * fw + 2 * kx * nx + 2 * csr + 64; };
+    auto csr_of = [&](int i) {
+        return (int64_t)round_up(recs[i].m + 1, 4) + 2 * (int64_t)round_up((int)nnz_of(i), 4);
+    };
+    std::stable_sort(order.begin(), order.end(), [&](int a, int b) {
+        return words_of(recs[a].k[0], csr_of(a)) < words_of(recs[b].k[0], csr_of(b));
+    });
+    int64_t kx_cap = 0, csr_cap = 0;
+    std::vector<int> mine;
+    for (int i : order) {
+        const SetRecord& r = recs[i];
+        // (no output rows: nothing to compute; no rows of X_i or more output rows than the
+        // gather's passes hold: left to the one-launch kernel)
+        if (r.m <= 0 || r.k[0] <= 0 || r.m > rows_most) continue;
+        const int64_t kx = std::max<int64_t>(kx_cap, r.k[0]);
+        const int64_t cw = std::max(csr_cap, csr_of(i));
+        if (words_of(kx, cw) > budget_words) continue;    // (a later one may still fit the caps)
+        kx_cap = kx;
+        csr_cap = cw;
+        mine.push_back(i);
+    }
+    if (mine.empty()) return;
+    st.nx16 = nx16, st.units = units, st.fw = fw, st.tiles = tiles;
+    st.tile_words = (int)(M * kx_cap * fw);
+    st.x_words = (int)(kx_cap * nx);
+    st.csr_words = (int)csr_cap;
+    // Larger graphs, kernels with two blocks per wavefront and 32-column tiles: taken in two
+    // halves of 16 columns, the half tile at the start of the same LDS, the CSR block at its end
+    // and at least one 16-row block of X_i between them.
+    std::vector<int> halves;
+    if (units == 2 && fw == 32) {
+        const int64_t total = (int64_t)st.tile_words + 2 * st.x_words + 2 * st.csr_words;
+        std::vector<char> is_mine(n_sets, 0);
+        for (int i : mine) is_mine[i] = 1;
+        auto fits_halves = [&](int i, int64_t csr_room) {
+            const SetRecord& r = recs[i];
+            return r.m > 0 && r.k[0] > 0 && r.m <= kStreamPasses * (kThreads / 4) && csr_of(i) <= csr_room &&
+                   (int64_t)M * r.k[0] * 16 + 16 * nx + csr_room <= total;
+        };
+        int64_t room = 0;
+        for (size_t i = 0; i < n_sets; ++i)
+            if (!is_mine[i] && fits_halves((int)i, csr_of((int)i))) room = std::max(room, csr_of((int)i));
+        for (size_t i = 0; i < n_sets; ++i)
+            if (!is_mine[i] && fits_halves((int)i, room)) halves.push_back((int)i);
+        st.big_csr_words = halves.empty() ? 0 : (int)room;
+        st.big = (int)halves.size();
+    }
+
+    // lists: as many workgroups as the chip holds at once, the same lists for every tile
+    int per_cu = kn.device_ok ? stream_workgroups_per_cu(nx16, units, st.lds_bytes()) : 0;
+    if (per_cu <= 0) per_cu = std::max(1, std::min(3, kMaxLdsBytes / std::max(1, st.lds_bytes())));
+    const int lists = (int)std::max<size_t>(1, std::min<size_t>(mine.size(), (size_t)per_cu * kn.compute_units / tiles));
+    st.lists = lists;
+    // (a graph taken in halves stages its X_i twice and overlaps nothing)
+    std::vector<char> in_halves(n_sets, 0);
+    for (int i : halves) in_halves[i] = 1;
+    auto cost = [&](int i) {
+        const int blocks = (recs[i].k[0] + 15) / 16;
+        return in_halves[i] ? 8 * blocks + 12 : 3 * blocks + 2;
+    };
+    mine.insert(mine.end(), halves.begin(), halves.end());
+    std::stable_sort(mine.begin(), mine.end(), [&](int a, int b) { return cost(a) > cost(b); });
+    std::vector<std::vector<int>> of_list(lists);
+    {
+        std::set<std::pair<int64_t, int>> load;      // (cost so far, list)
+        for (int l = 0; l < lists; ++l) load.insert({0, l});
+        for (int i : mine) {
+            auto least = *load.begin();
+            load.erase(load.begin());
+            of_list[least.second].push_back(i);
+            least.first += cost(i);
+            load.insert(least);
+        }
+    }
+    const DirOps& o = p.dir[0];
+    st.list.push_back(0);
+    std::vector<char> streamed(n_sets, 0);
+    for (int l = 0; l < lists; ++l) {
+        // the graphs taken in halves first: the kernel takes them before it starts its pipeline
+        std::stable_partition(of_list[l].begin(), of_list[l].end(), [&](int i) { return in_halves[i] != 0; });
+        for (int i : of_list[l]) {
+            const SetRecord& r = recs[i];
+            const int op0 = sc.merged_sets[i][0];
+            StreamSet e;
+            e.in_row = o.in_off[op0];
+            e.out_row = o.out_off[op0];
+            e.csr_off = (uint32_t)r.merged_rpt_off;
+            e.m = r.m;
+            e.kx = r.k[0];
+            e.nnz = (int32_t)nnz_of(i);
+            st.sets.push_back(e);
+            streamed[i] = 1;
+        }
+        st.list.push_back((int32_t)st.sets.size());
+    }
+    // the other graphs: their items of the one-launch schedule, in its order
+    for (size_t j = 0; j < sc.items.size(); ++j) {
+        const int op = j < sc.item_op.size() ? sc.item_op[j] : -1;
+        if (op < sc.first_stand_in || sc.items[j].nrows <= 0) continue;
+        if (!streamed[(size_t)(op - sc.first_stand_in)]) st.rest.push_back(sc.items[j]);
+    }
 }
 
 // The item table of the lean kernel for direction d, when the schedule is lean and every offset
@@ -506,6 +681,13 @@ int plan_host(bspmm_plan& p, const bspmm_batch* b, int32_t F, const Knobs& kn)
         L.merged[d] = at;
         at = align_up(at + (size_t)p.merged_words[d] * 4);
     }
+    make_stream_plan(p);
+    L.stream_sets = at;
+    at = align_up(at + p.stream.sets.size() * sizeof(StreamSet));
+    L.stream_list = at;
+    at = align_up(at + p.stream.list.size() * sizeof(int32_t));
+    L.stream_rest = at;
+    at = align_up(at + p.stream.rest.size() * sizeof(WorkItem));
     L.total = at;
     return BSPMM_OK;
 }
@@ -547,6 +729,7 @@ const DeviceFacts& device_facts(int lds_bytes, bool hubs)
 Knobs knobs_for(const bspmm_options* o, bool ask_device)
 {
     Knobs kn = resolve_knobs(o);
+    kn.device_ok = ask_device;
     const bool cus_given = o && o->compute_units > 0;
     int r = 0, rs = 0;
     if (ask_device) {
@@ -954,6 +1137,16 @@ int upload_plan(bspmm_plan* p, const bspmm_options* options, void* workspace,
         if (!p->set_records[d].empty())
             e = hipMemcpyAsync(p->ws + p->lay.sets[d], p->set_records[d].data(),
                                p->set_records[d].size() * sizeof(SetRecord), hipMemcpyHostToDevice, s);
+    if (e == hipSuccess && p->stream.on()) {
+        e = hipMemcpyAsync(p->ws + p->lay.stream_sets, p->stream.sets.data(),
+                           p->stream.sets.size() * sizeof(StreamSet), hipMemcpyHostToDevice, s);
+        if (e == hipSuccess)
+            e = hipMemcpyAsync(p->ws + p->lay.stream_list, p->stream.list.data(),
+                               p->stream.list.size() * sizeof(int32_t), hipMemcpyHostToDevice, s);
+        if (e == hipSuccess && !p->stream.rest.empty())
+            e = hipMemcpyAsync(p->ws + p->lay.stream_rest, p->stream.rest.data(),
+                               p->stream.rest.size() * sizeof(WorkItem), hipMemcpyHostToDevice, s);
+    }
     if (p->coo_direct) {
         for (int d = 0; d < 2 && e == hipSuccess; ++d)
             if (!p->coo_sched[d].items.empty())
@@ -1012,8 +1205,34 @@ int run_gcn(bspmm_plan* p, const float* X, int64_t ldx, const float* W, int64_t 
         const int mrc = enqueue_merge(p, 0, s);
         if (mrc != BSPMM_OK) return mrc;
     }
+    const bspmm_plan::Stream& st = p->stream;
+    if (st.on()) {
+        // graphs inside the LDS budget: resident workgroups stream them; the others (if any)
+        // follow in a launch of the one-launch kernel over their items
+        if (ldx >= (int64_t(1) << 31) || ldy >= (int64_t(1) << 31)) return BSPMM_EINVAL;
+        StreamParams S;
+        S.sets = reinterpret_cast<const StreamSet*>(p->ws + p->lay.stream_sets);
+        S.list = reinterpret_cast<const int32_t*>(p->ws + p->lay.stream_list);
+        S.merged = reinterpret_cast<const int32_t*>(p->ws + p->lay.merged[0]);
+        S.x = X;
+        S.w = W;
+        S.bias = bias;
+        S.y = Y;
+        StreamShape& sh = S.shape;
+        sh.ld_x = ldx, sh.ld_w = ldw, sh.ld_y = ldy, sh.bias_stride = p->F;
+        sh.tiles = st.tiles, sh.fw = st.fw, sh.channels = p->front_channels;
+        sh.accumulate = accumulate ? 1 : 0;
+        sh.tile_words = st.tile_words, sh.x_words = st.x_words, sh.csr_words = st.csr_words;
+        sh.big_csr_words = st.big_csr_words;
+        sh.reserved_[0] = sh.reserved_[1] = sh.reserved_[2] = sh.reserved_[3] = 0;
+        const hipError_t es = launch_bspmm_gcn_stream(S, st.nx16, st.units, st.lists * st.tiles,
+                                                      st.lds_bytes(), s);
+        if (es != hipSuccess) return hip_fail(es);
+        if (st.rest.empty()) return BSPMM_OK;
+    }
     LaunchParams P;
-    P.items = reinterpret_cast<const WorkItem*>(p->ws + p->lay.items[0]);
+    P.items = st.on() ? reinterpret_cast<const WorkItem*>(p->ws + p->lay.stream_rest)
+                      : reinterpret_cast<const WorkItem*>(p->ws + p->lay.items[0]);
     // (channel sets: every item reads the merged CSR of its set; P.rpt carries its base)
     P.rpt = sets ? reinterpret_cast<const int32_t*>(p->ws + p->lay.merged[0]) : p->rpt;
     P.colids = p->colids;
@@ -1035,7 +1254,8 @@ int run_gcn(bspmm_plan* p, const float* X, int64_t ldx, const float* W, int64_t 
     P.ld_w = ldw;
     P.n_front = nx;
     P.accumulate = accumulate ? 1 : 0;
-    hipError_t e = launch_bspmm_gcn(P, sc.grid, sc.front_lds_words * 4, accumulate != 0, sets, s);
+    const int grid = st.on() ? (int)st.rest.size() : sc.grid;
+    hipError_t e = launch_bspmm_gcn(P, grid, sc.front_lds_words * 4, accumulate != 0, sets, s);
     return e == hipSuccess ? BSPMM_OK : hip_fail(e);
 }
 
@@ -1379,7 +1599,7 @@ int bspmm_validate(bspmm_plan* plan, int32_t* bad_op, void* stream)
 
 int bspmm_kernel_info(int32_t kernel, int32_t dynamic_lds_bytes, bspmm_kernel_resources* out)
 {
-    if (!out || kernel < 0 || kernel > BSPMM_KERNEL_COO || dynamic_lds_bytes < 0) return BSPMM_EINVAL;
+    if (!out || kernel < 0 || kernel > BSPMM_KERNEL_LAYER_STREAM || dynamic_lds_bytes < 0) return BSPMM_EINVAL;
     int v[7] = {0, 0, 0, 0, 0, 0, 0};
     const hipError_t e = kernel_resources(kernel, dynamic_lds_bytes, v);
     if (e != hipSuccess) {
@@ -1423,6 +1643,14 @@ int bspmm_plan_info(const bspmm_plan* plan, bspmm_info* info)
     info->transposed_supported = plan->transposed_supported ? 1 : 0;
     info->transposed_built = plan->transposed_built ? 1 : 0;
     for (int d = 0; d < 2; ++d) info->lean[d] = plan->lean_items[d].empty() ? 0 : 1;
+    if (plan->stream.on()) {
+        info->front_stream[0] = (int32_t)plan->stream.sets.size();
+        info->front_stream[1] = plan->stream.lists * plan->stream.tiles;
+        info->front_stream[2] = plan->stream.lds_bytes();
+        int32_t left = 0;
+        for (const WorkItem& w : plan->stream.rest) left += w.f0 == 0 ? 1 : 0;
+        info->front_stream[3] = left;
+    }
     info->flops = plan->flops;
     info->workspace_bytes = plan->lay.total;
     return BSPMM_OK;

@@ -1652,6 +1652,371 @@ __global__ void __launch_bounds__(kThreads) bspmm_gcn_kernel(const LaunchParams 
 }
 
 // ---------------------------------------------------------------------------------------
+// The whole layer (Fig. 7 with the ElementWiseAdd) for batches of many rounds of workgroups:
+// resident workgroups, each bound to one feature tile, stream the graphs of their list.
+//
+// A workgroup of bspmm_gcn_kernel goes through its phases one after the other - operands from
+// memory, dense tile on the matrix cores, gather, store - stages its weight tile again for
+// every graph, and the launch's LDS is sized for the largest graph of the batch.  Here
+//   * the weights of a wavefront's blocks live in REGISTERS for the whole launch: wavefront w
+//     owns U of the M * fw/16 (channel, 16-column block) pairs, and the B operand of
+//     v_mfma_f32_16x16x4_f32 for lane (g, col) = (l / 16, l % 16) is W[ch][16 s + 4 g + j][col],
+//     s < n_X / 16, j < 4: n_X / 4 registers per pair.  No LDS for W, no LDS reads for it.
+//   * the rows of X_i and the merged CSR block of the NEXT graph are requested (global -> LDS
+//     directly) before the matrix instructions of this graph are issued, into the other one of
+//     two buffers, and nothing waits for them until the top of the next trip; a graph's results
+//     wait in registers and are stored at the top of the next trip, so that wait finds only
+//     requests and stores that are a whole trip old.  The records of the graphs (32 bytes
+//     each) are fetched with scalar loads two trips ahead.
+//   * the launch's LDS is sized for the graphs that fit a budget of a third of a CU's LDS, so
+//     that three workgroups share a CU: one's matrix phase overlaps the others' gathers and
+//     requests.  Larger graphs (a few per cent of a molecule batch) are taken in two halves of
+//     16 columns out of the same LDS (see below); what does not fit even so is not in the
+//     lists at all (the host gives it to bspmm_gcn_kernel in a launch of its own).
+// Arithmetic: the n_X products of a dense element are added by the matrix instructions in
+// the order 4 g + j within 16 s (bias as the initial value of the accumulator; two
+// accumulators per block, k even and odd, in kernels with one block per wavefront and in the
+// halves); a row's entries are added in stored order with fused multiply-adds.  Rows of X_i
+// are XOR-swizzled in LDS as in bspmm_gcn_kernel.
+// Per trip two barriers: "tile free, buffers of the graph after next free, this graph's
+// operands landed" and "tile complete".  Every workgroup's loop runs over a list the host
+// made: it ends.
+// ---------------------------------------------------------------------------------------
+
+// Global -> LDS copy of 16 bytes per lane (lane i lands at lds + 16 i), issued from inline
+// assembly: the compiler then does not know that LDS is written behind its back and does not
+// put a wait for ALL outstanding memory operations in front of the next LDS read.  That wait is
+// what a prefetch into the other buffer must not meet; the kernel waits for its requests
+// itself, where it needs them.  (Untracked requests can only make the waits the compiler
+// computes for its own loads longer, never shorter: the counter runs in issue order.)
+__device__ __forceinline__ void lds_dma16(const void* gp, const void* lds)
+{
+    const int m0 = __builtin_amdgcn_readfirstlane(
+        (int)(uintptr_t)((const __attribute__((address_space(3))) char*)lds));
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+                 :: "v"(gp), "s"(m0) : "memory", "m0");
+}
+
+// Workgroup barrier that orders LDS accesses only (no wait for global stores or for requests
+// in flight, which __syncthreads would add).
+__device__ __forceinline__ void lds_barrier()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+template <int NX16, int U>
+__global__ void __launch_bounds__(kThreads)
+bspmm_gcn_stream_kernel(const StreamSet* __restrict__ sets, const int32_t* __restrict__ list,
+                        const int32_t* __restrict__ merged, const float* __restrict__ x,
+                        const float* __restrict__ wgt, const float* __restrict__ bias,
+                        float* __restrict__ y, const StreamShape S)
+{
+    extern __shared__ __align__(16) int sm[];
+    typedef float mfma4 __attribute__((ext_vector_type(4)));
+    constexpr int NX = 16 * NX16, XVEC = NX / 4, XSH = NX16 == 1 ? 2 : (NX16 == 2 ? 3 : (NX16 == 4 ? 4 : 5));
+    constexpr int SWZ = (XVEC < 16 ? XVEC : 16) - 1;
+    constexpr int C = U == 1 ? 2 : 1;            // accumulators per block: two matrix instructions
+                                                 // between dependent ones either way
+    const int tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), wl = tid & 63;
+    const int col = wl & 15, g = wl >> 4;
+    const int tile_idx = blockIdx.x % S.tiles, lp = blockIdx.x / S.tiles;
+    const int f0 = tile_idx * S.fw;
+    const int j0 = list[lp], j1 = list[lp + 1];
+    if (j0 >= j1) return;
+    const int fsh = ilog2(S.fw);                 // tile row = 1 << fsh floats
+    const int nbw = S.fw >> 4;                   // 16-column blocks per tile row
+
+    float* tile = reinterpret_cast<float*>(sm);
+    float* xbase = tile + S.tile_words;
+    int* cbase = sm + S.tile_words + 2 * S.x_words;
+    float* sink = reinterpret_cast<float*>(cbase + 2 * S.csr_words) + wl;   // rows past the end land here
+
+    // ---- this wavefront's weights and bias, once
+    float w[U][NX16][4];
+    float bv[U];
+    int unit_ch[U], unit_col[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int unit = wave * U + u;
+        const int ch = unit / nbw, nb = unit - ch * nbw;
+        unit_ch[u] = ch;
+        unit_col[u] = 16 * nb + col;
+        const float* wp = wgt + (int64_t)(ch * NX + 4 * g) * S.ld_w + f0 + 16 * nb + col;
+#pragma unroll
+        for (int s = 0; s < NX16; ++s)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) w[u][s][j] = wp[(int64_t)(16 * s + j) * S.ld_w];
+        bv[u] = bias[(int64_t)ch * S.bias_stride + f0 + 16 * nb + col];
+    }
+
+    // rows of X_i and the merged CSR block of a graph -> buffers b
+    auto request = [&](const StreamSet& st, int b) {
+        const int total = st.kx << XSH;
+        const float* xg = x + st.in_row * S.ld_x;
+        float* xd = xbase + b * S.x_words;
+        for (int e0 = wave << 6; e0 < total; e0 += kThreads) {
+            const int e = e0 + wl;
+            if (e < total) {
+                const int r = e >> XSH;
+                const float* gp = xg + (int64_t)r * S.ld_x + (((e & (XVEC - 1)) ^ (r & SWZ)) << 2);
+                lds_dma16(gp, xd + (e0 << 2));
+            }
+        }
+        const int32_t* cg = merged + st.csr_off;
+        int* cd = cbase + b * S.csr_words;
+        const int csr_vecs = (((st.m + 4) & ~3) + 2 * ((st.nnz + 3) & ~3)) >> 2;
+        for (int e0 = wave << 6; e0 < csr_vecs; e0 += kThreads) {
+            const int e = e0 + wl;
+            if (e < csr_vecs) lds_dma16(cg + 4 * e, cd + (e0 << 2));
+        }
+    };
+
+    // gather geometry: fw / 4 lanes per output row
+    const int gsh = fsh - 2;
+    const int r_lane = tid >> gsh, l = tid & ((1 << gsh) - 1);
+    const int rows_per_pass = kThreads >> gsh;
+    float4 yv[kStreamPasses];
+    int pend_m = 0;
+    int64_t pend_row = 0;
+    auto store_pending = [&]() {
+#pragma unroll
+        for (int q = 0; q < kStreamPasses; ++q) {
+            const int r = q * rows_per_pass + r_lane;
+            if (r < pend_m) {
+                float* yp = y + (pend_row + r) * S.ld_y + f0 + 4 * l;
+                float4 v = yv[q];
+                if (S.accumulate) {
+                    const float4 old = *reinterpret_cast<const float4*>(yp);
+                    v.x += old.x, v.y += old.y, v.z += old.z, v.w += old.w;
+                }
+                store_out<4>(yp, v);
+            }
+        }
+    };
+
+    // ---- graphs too large for the buffers above come first in a list and are taken one at a
+    // time, without prefetch, in two halves of 16 columns (kernels with two blocks per wavefront
+    // and tiles of 32 columns: a wavefront then owns one channel): the half tile
+    // (channels x kx x 16) sits at the start of LDS, the merged CSR block at its end, and the
+    // rows of X_i pass through the space between them in chunks of as many 16-row blocks as
+    // fit.  Each half: [chunk from memory, its blocks on the matrix cores] ..., gather, store.
+    int jn = j0;
+    if (U == 2 && nbw == 2) {
+        const int total_words = S.tile_words + 2 * S.x_words + 2 * S.csr_words;
+        int* cbig = sm + total_words - S.big_csr_words;
+        for (; jn < j1; ++jn) {
+            const StreamSet bg = sets[jn];
+            const int csr_w = ((bg.m + 4) & ~3) + 2 * ((bg.nnz + 3) & ~3);
+            const bool big = S.channels * bg.kx * S.fw > S.tile_words || bg.kx * NX > S.x_words ||
+                             csr_w > S.csr_words || bg.m > kStreamPasses * rows_per_pass;
+            if (!big) break;
+            const int kx = bg.kx, m = bg.m;
+            const int half_words = S.channels * kx * 16;
+            float* xbig = tile + half_words;
+            const int rows_chunk = min((kx + 15) & ~15, ((total_words - S.big_csr_words - half_words) / NX) & ~15);
+            if (rows_chunk < 16 || csr_w > S.big_csr_words) return;    // (the host never lists such a graph)
+            {
+                const int32_t* cg = merged + bg.csr_off;
+                const int csr_vecs = csr_w >> 2;
+                for (int e0 = wave << 6; e0 < csr_vecs; e0 += kThreads) {
+                    const int e = e0 + wl;
+                    if (e < csr_vecs) lds_dma16(cg + 4 * e, cbig + (e0 << 2));
+                }
+            }
+            const float* xg = x + bg.in_row * S.ld_x;
+            const int* rp = cbig;
+            const int* cols = rp + ((m + 4) & ~3);
+            const float* vals = reinterpret_cast<const float*>(cols + ((bg.nnz + 3) & ~3));
+            for (int h = 0; h < 2; ++h) {
+                for (int r0 = 0; r0 < kx; r0 += rows_chunk) {
+                    const int rows = min(rows_chunk, kx - r0);
+                    const int total = rows << XSH;
+                    for (int e0 = wave << 6; e0 < total; e0 += kThreads) {
+                        const int e = e0 + wl;
+                        if (e < total) {
+                            const int r = e >> XSH;
+                            lds_dma16(xg + (int64_t)(r0 + r) * S.ld_x + (((e & (XVEC - 1)) ^ (r & SWZ)) << 2),
+                                      xbig + (e0 << 2));
+                        }
+                    }
+                    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                    lds_barrier();
+                    for (int mb = 0; mb < ((rows + 15) >> 4); ++mb) {
+                        const int arow = min(16 * mb + col, rows - 1);
+                        const float* xrow = xbig + arow * NX;
+                        mfma4 acc0 = {bv[h], bv[h], bv[h], bv[h]}, acc1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                        for (int s = 0; s < NX16; ++s) {
+                            const float4 av = *reinterpret_cast<const float4*>(xrow + (((4 * s + g) ^ (arow & SWZ)) << 2));
+                            acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(av.x, w[h][s][0], acc0, 0, 0, 0);
+                            acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(av.y, w[h][s][1], acc1, 0, 0, 0);
+                            acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(av.z, w[h][s][2], acc0, 0, 0, 0);
+                            acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(av.w, w[h][s][3], acc1, 0, 0, 0);
+                        }
+                        const mfma4 r4 = acc0 + acc1;
+                        const int row = r0 + 16 * mb + 4 * g;
+                        float* tp = tile + ((unit_ch[h] * kx + row) << 4) + col;
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            float* q = 16 * mb + 4 * g + i < rows ? tp + (i << 4) : sink;
+                            *q = r4[i];
+                        }
+                    }
+                    lds_barrier();      // the chunk may be replaced; after the last one: half tile complete
+                }
+                // gather over the half tile: four lanes per output row
+                const int hr = tid >> 2, hl = tid & 3;
+                const char* tcol = reinterpret_cast<const char*>(tile) + 16 * hl;
+                for (int r = hr; r < m; r += kThreads >> 2) {
+                    const int p0 = rp[r], p1 = rp[r + 1];
+                    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+                    for (int p = p0; p < p1; p += 4) {
+                        int c[4];
+                        float v[4];
+#pragma unroll
+                        for (int t = 0; t < 4; ++t) {
+                            const int idx = min(p + t, p1 - 1);
+                            c[t] = cols[idx];
+                            v[t] = p + t < p1 ? vals[idx] : 0.f;
+                        }
+                        float4 bq[4];
+#pragma unroll
+                        for (int t = 0; t < 4; ++t) bq[t] = *reinterpret_cast<const float4*>(tcol + (c[t] << 6));
+#pragma unroll
+                        for (int t = 0; t < 4; ++t) {
+                            acc.x = fmaf(v[t], bq[t].x, acc.x);
+                            acc.y = fmaf(v[t], bq[t].y, acc.y);
+                            acc.z = fmaf(v[t], bq[t].z, acc.z);
+                            acc.w = fmaf(v[t], bq[t].w, acc.w);
+                        }
+                    }
+                    float* yp = y + (bg.out_row + r) * S.ld_y + f0 + 16 * h + 4 * hl;
+                    if (S.accumulate) {
+                        const float4 old = *reinterpret_cast<const float4*>(yp);
+                        acc.x += old.x, acc.y += old.y, acc.z += old.z, acc.w += old.w;
+                    }
+                    store_out<4>(yp, acc);
+                }
+                lds_barrier();          // the half tile may be overwritten
+            }
+        }
+        if (jn >= j1) return;
+    }
+
+    // the records of this graph and the next sit in scalar registers; the one after that is
+    // fetched a trip ahead
+    const int jbase = jn;
+    StreamSet cur = sets[jn];
+    StreamSet nxt = sets[min(jn + 1, j1 - 1)];
+    request(cur, 0);
+    for (int j = jn; j < j1; ++j) {
+        const int b = (j - jbase) & 1;
+        const StreamSet ahead = sets[min(j + 2, j1 - 1)];
+        const int kx = cur.kx;
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wavefront's requests for graph j
+        lds_barrier();                                     // everyone's; everyone is done with graph j - 1
+        store_pending();
+        if (j + 1 < j1) request(nxt, b ^ 1);
+
+        // ---- dense tile: [X_i W[0] + bias[0]; ...; X_i W[M-1] + bias[M-1]] -> LDS
+        const float* xs = xbase + b * S.x_words;
+        const int nmb = (kx + 15) >> 4;
+        float4 a[NX16];
+        {
+            const int arow = min(col, kx - 1);
+            const float* xrow = xs + arow * NX;
+#pragma unroll
+            for (int s = 0; s < NX16; ++s)
+                a[s] = *reinterpret_cast<const float4*>(xrow + (((4 * s + g) ^ (arow & SWZ)) << 2));
+        }
+        for (int mb = 0; mb < nmb; ++mb) {
+            float4 an[NX16];
+            {   // the next block's rows before this block's instructions (rows past the end repeat the last)
+                const int arow = min(16 * (mb + 1) + col, kx - 1);
+                const float* xrow = xs + arow * NX;
+#pragma unroll
+                for (int s = 0; s < NX16; ++s)
+                    an[s] = *reinterpret_cast<const float4*>(xrow + (((4 * s + g) ^ (arow & SWZ)) << 2));
+            }
+            mfma4 acc[U][C];
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int c = 0; c < C; ++c)
+                    acc[u][c] = c == 0 ? mfma4{bv[u], bv[u], bv[u], bv[u]} : mfma4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int s = 0; s < NX16; ++s) {
+                const float ak[4] = {a[s].x, a[s].y, a[s].z, a[s].w};
+#pragma unroll
+                for (int k = 0; k < 4; ++k)
+#pragma unroll
+                    for (int u = 0; u < U; ++u)
+                        acc[u][k % C] = __builtin_amdgcn_mfma_f32_16x16x4f32(ak[k], w[u][s][k], acc[u][k % C], 0, 0, 0);
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                mfma4 r = acc[u][0];
+                if (C == 2) r = r + acc[u][C - 1];
+                float* tp = tile + ((unit_ch[u] * kx + 16 * mb + 4 * g) << fsh) + unit_col[u];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    float* q = 16 * mb + 4 * g + i < kx ? tp + (i << fsh) : sink;
+                    *q = r[i];
+                }
+            }
+#pragma unroll
+            for (int s = 0; s < NX16; ++s) a[s] = an[s];
+        }
+        lds_barrier();                                     // tile complete
+
+        // ---- gather over the merged CSR: Y_i = sum_ch A_i^ch tile_ch, into registers
+        const int m = cur.m;
+        const int* rp = cbase + b * S.csr_words;
+        const int* cols = rp + ((m + 4) & ~3);
+        const float* vals = reinterpret_cast<const float*>(cols + ((cur.nnz + 3) & ~3));
+        const char* tcol = reinterpret_cast<const char*>(tile) + 16 * l;
+        const int lsh = fsh + 2;
+#pragma unroll
+        for (int q = 0; q < kStreamPasses; ++q) {
+            float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+            const int r = q * rows_per_pass + r_lane;
+            if (q * rows_per_pass < m && r < m) {
+                const int p0 = rp[r], p1 = rp[r + 1];
+                for (int p = p0; p < p1; p += 8) {      // eight entries a trip, the tail masked
+                    int c[8];
+                    float v[8];
+#pragma unroll
+                    for (int t = 0; t < 8; ++t) {
+                        const int idx = min(p + t, p1 - 1);
+                        c[t] = cols[idx];
+                        v[t] = p + t < p1 ? vals[idx] : 0.f;
+                    }
+                    float4 bq[8];
+#pragma unroll
+                    for (int t = 0; t < 8; ++t) bq[t] = *reinterpret_cast<const float4*>(tcol + (c[t] << lsh));
+#pragma unroll
+                    for (int t = 0; t < 8; ++t) {
+                        acc.x = fmaf(v[t], bq[t].x, acc.x);
+                        acc.y = fmaf(v[t], bq[t].y, acc.y);
+                        acc.z = fmaf(v[t], bq[t].z, acc.z);
+                        acc.w = fmaf(v[t], bq[t].w, acc.w);
+                    }
+                }
+            }
+            yv[q] = acc;
+        }
+        pend_m = m;
+        pend_row = cur.out_row;
+        cur = nxt;
+        nxt = ahead;
+    }
+    store_pending();
+}
+
+// ---------------------------------------------------------------------------------------
 // Direct product for COO / SparseTensor operands (Fig. 3 with the output staged on chip as in
 // Fig. 5(a,b)): the item's output tile lives in LDS; a group of L lanes takes one stored entry
 // at a time (L = the tile's vectors per row rounded up to a power of two, at most 64), reads
@@ -1894,6 +2259,7 @@ hipError_t kernel_resources(int which, int lds_bytes, int out[7])
             threads = kBuildThreadsLarge;
             break;
         case 7: fn = reinterpret_cast<const void*>(&bspmm_coo_kernel<4>); break;
+        case 8: fn = reinterpret_cast<const void*>(&bspmm_gcn_stream_kernel<4, 2>); break;
         default: return hipErrorInvalidValue;
     }
     hipFuncAttributes a;
@@ -1949,6 +2315,55 @@ hipError_t launch_bspmm_gcn(const LaunchParams& P, int grid, int lds_bytes, bool
                                 bspmm_gcn_kernel<false, true>, bspmm_gcn_kernel<true, true>};
     hipLaunchKernelGGL(table[(sets ? 2 : 0) + (accumulate ? 1 : 0)], dim3(grid), dim3(kThreads),
                        lds_bytes, stream, P);
+    return hipGetLastError();
+}
+
+using StreamFn = void (*)(const StreamSet*, const int32_t*, const int32_t*, const float*, const float*,
+                          const float*, float*, const StreamShape);
+
+// (n_X / 16, blocks per wavefront) -> kernel; null for shapes the streaming kernel is not built for
+static StreamFn stream_variant(int nx16, int units)
+{
+    if (units == 1) {
+        switch (nx16) {
+        case 1: return bspmm_gcn_stream_kernel<1, 1>;
+        case 2: return bspmm_gcn_stream_kernel<2, 1>;
+        case 4: return bspmm_gcn_stream_kernel<4, 1>;
+        case 8: return bspmm_gcn_stream_kernel<8, 1>;
+        }
+    } else if (units == 2) {
+        switch (nx16) {
+        case 1: return bspmm_gcn_stream_kernel<1, 2>;
+        case 2: return bspmm_gcn_stream_kernel<2, 2>;
+        case 4: return bspmm_gcn_stream_kernel<4, 2>;
+        }
+    }
+    return nullptr;
+}
+
+bool stream_supported(int nx16, int units) { return stream_variant(nx16, units) != nullptr; }
+
+// Workgroups of the streaming kernel one CU of the current device holds (0 if it cannot be asked).
+int stream_workgroups_per_cu(int nx16, int units, int lds_bytes)
+{
+    const StreamFn fn = stream_variant(nx16, units);
+    int per_cu = 0;
+    if (!fn) return 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, kThreads, (size_t)lds_bytes) != hipSuccess) {
+        (void)hipGetLastError();
+        return 0;
+    }
+    return per_cu;
+}
+
+hipError_t launch_bspmm_gcn_stream(const StreamParams& P, int nx16, int units, int grid,
+                                   int lds_bytes, hipStream_t stream)
+{
+    if (grid <= 0) return hipSuccess;
+    const StreamFn fn = stream_variant(nx16, units);
+    if (!fn) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(fn, dim3(grid), dim3(kThreads), lds_bytes, stream, P.sets, P.list, P.merged, P.x,
+                       P.w, P.bias, P.y, P.shape);
     return hipGetLastError();
 }
 

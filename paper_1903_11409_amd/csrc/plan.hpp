@@ -109,6 +109,47 @@ struct LaunchParams {
     int32_t accumulate;   // add to the output instead of overwriting it
 };
 
+// Whole layers in launches of many rounds (bspmm_run_gcn, plans with front_features and
+// BSPMM_ACCUMULATE): resident workgroups that keep their weight tile in registers and stream
+// the graphs of their list through LDS.  One record per graph (a set of M channel operations
+// with one merged CSR):
+struct alignas(16) StreamSet {
+    int64_t in_row;       // first row of X_i
+    int64_t out_row;      // first row of Y_i
+    uint32_t csr_off;     // word offset, from the base of the merged arrays, of the set's block:
+                          // row pointers (m + 1, padded to 4), columns (nnz, padded to 4), values
+    int32_t m;            // rows of Y_i (rows of every channel matrix)
+    int32_t kx;           // rows of X_i (columns of every channel matrix)
+    int32_t nnz;          // entries of the merged CSR
+};
+static_assert(sizeof(StreamSet) == 32, "StreamSet must be 32 bytes");
+
+constexpr int kStreamPasses = 4;   // row passes of the gather a streamed graph may take: the
+                                   // results of a graph wait in registers for one loop trip
+
+// Arguments of the streaming kernel.  Workgroup w serves feature tile w % tiles (columns
+// [fw * tile, fw * tile + fw)) and the graphs list[w / tiles] .. list[w / tiles + 1].
+// LDS, in words: the dense tile (tile_words), two buffers for rows of X (x_words each), two
+// for merged CSR blocks (csr_words each), 64 words that take the tile rows past a graph's end.
+// (The pointers are kernel arguments of their own, qualified so that the graph records are
+// fetched with scalar loads.)
+struct StreamShape {
+    int64_t ld_x, ld_w, ld_y, bias_stride;
+    int32_t tiles, fw, channels, accumulate;
+    int32_t tile_words, x_words, csr_words, big_csr_words;
+    int32_t reserved_[4];
+};
+struct StreamParams {
+    const StreamSet* sets;
+    const int32_t* list;
+    const int32_t* merged;
+    const float* x;
+    const float* w;
+    const float* bias;
+    float* y;
+    StreamShape shape;
+};
+
 // One unit of work of the direct COO kernel: the output rows [row0, row0+nrows) x feature
 // columns [f0, f0+fw) of one operation, accumulated in LDS from ALL of the operation's entries.
 // LDS, in words, with stride = round_up(fw, 4): output tile nrows*stride, then (mode bit 0)

@@ -439,6 +439,8 @@ Knobs resolve_knobs(const bspmm_options* o)
     k.accumulate = (o->flags & BSPMM_ACCUMULATE) != 0;
     k.coo_direct = (o->flags & BSPMM_COO_DIRECT) != 0;
     k.symmetric = (o->flags & BSPMM_SYMMETRIC) != 0;
+    k.one_front_launch = (o->flags & BSPMM_ONE_FRONT_LAUNCH) != 0;
+    k.lds_given = o->lds_bytes > 0;
     if (o->front_features > 0) {   // the matrix-core blocks of the fused front are 16 columns wide
         k.front = o->front_features;
         // an item also holds X_i and a weight tile: take half the CU's LDS unless told otherwise

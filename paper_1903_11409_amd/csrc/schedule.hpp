@@ -42,6 +42,9 @@ struct Knobs {
     bool symmetric = false;   // A_i == A_i^T promised: the transposed product reads the same CSR
     bool coo_direct = false;  // COO plans: run the direct kernel instead of converting to CSR
     int persistent_wgs = 0;   // > 0: launch only this many workgroups and let them stride
+    bool one_front_launch = false;   // whole layers: never the streaming launch
+    bool lds_given = false;   // the caller fixed lds_words
+    bool device_ok = false;   // planning may ask the current device (occupancy); false: dry runs
     bool need_both = false;   // planning: a transposed product that does not fit is an error too
 };
 

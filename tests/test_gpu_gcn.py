@@ -247,12 +247,61 @@ def test_whole_layer_in_wide_blocks(torch_cuda, oracle, graphs, F, n_x, chans, k
     _whole_layer_case(torch_cuda, oracle, graphs, F, n_x, chans, **kw)
 
 
+@pytest.mark.parametrize("graphs,F,n_x,chans,kw,left", [
+    # launches of many rounds are run by resident workgroups that keep their weights in
+    # registers and stream the graphs: for real (640 graphs), and on small batches by telling
+    # the scheduler that the chip has four CUs; `left` = some graphs exceed the LDS budget of the
+    # streaming launch and run in a launch of their own
+    (640, 128, 64, 4, {}, None),
+    (64, 128, 64, 4, {"compute_units": 4}, None),
+    (64, 128, 64, 4, {"compute_units": 4, "lds_bytes": 49152}, False),   # larger graphs in two halves
+    (48, 64, 32, 4, {"compute_units": 4}, None),
+    (40, 128, 16, 4, {"compute_units": 4}, None),
+    (24, 256, 128, 2, {"compute_units": 4}, None),      # one block per wavefront
+    (24, 128, 64, 2, {"compute_units": 4}, None),       # two channels: tiles of 64 columns
+    (24, 64, 32, 8, {"compute_units": 4, "lds_bytes": 163840}, False),
+])
+def test_whole_layer_streamed(torch_cuda, oracle, graphs, F, n_x, chans, kw, left):
+    info = _whole_layer_case(torch_cuda, oracle, graphs, F, n_x, chans, **kw)
+    assert info.front_stream[0] > 0 and info.front_stream[1] > 0
+    assert info.front_stream[0] + info.front_stream[3] == graphs
+    if left is not None:
+        assert (info.front_stream[3] > 0) == left
+
+
+def test_streamed_layer_agrees_with_the_one_launch_path(torch_cuda):
+    """The streaming launch and the one-launch kernel compute the same layer; they differ only
+    in the order in which the matrix instructions add up a dense element's n_X products."""
+    torch = torch_cuda
+    graphs, F, n_x, chans = 64, 128, 64, 4
+    b = W.config3_multichannel(seed=564, graphs=graphs, F=F, channels=chans, accumulate=True)
+    assert int(b.rows.max()) <= 128      # (more rows than the streaming gather takes: not streamed)
+    X, Ws, biases = _layer(b, n_x, 5, channels=chans)
+    Xd = torch.from_numpy(X).cuda()
+    Wd = torch.from_numpy(np.concatenate(Ws, axis=0)).cuda()
+    bd = torch.from_numpy(np.stack(biases)).cuda()
+    out = []
+    for flags, cus, lds in ((K.ACCUMULATE, 4, 163840), (K.ACCUMULATE | K.ONE_FRONT_LAUNCH, 0, 0)):
+        plan = K.Plan(b, options=K.make_options(flags=flags, front_features=n_x, compute_units=cus,
+                                                lds_bytes=lds))
+        # (the whole chip's LDS as the budget: every graph is streamed)
+        assert plan.info().front_stream[0] == (graphs if cus == 4 else 0)
+        Yd = torch.full((b.n_c_rows, F), SENTINEL, dtype=torch.float32, device="cuda")
+        plan.run_gcn(Xd, Wd, bd, Yd)
+        torch.cuda.synchronize()
+        out.append(Yd.cpu().numpy().astype(np.float64))
+        plan.close()
+    scale = np.abs(out[1]).max()
+    assert np.abs(out[0] - out[1]).max() <= 1e-5 * scale
+
+
 def _whole_layer_case(torch, oracle, graphs, F, n_x, chans, **kw):
     b = W.config3_multichannel(seed=500 + graphs, graphs=graphs, F=F, channels=chans, accumulate=True)
     X, Ws, biases = _layer(b, n_x, 11, channels=chans)
     print(f"layer case: graphs={graphs} F={F} n_X={n_x} channels={chans} {kw}", flush=True)
     plan = K.Plan(b, options=K.make_options(flags=K.ACCUMULATE, front_features=n_x, **kw))
     info = plan.info()
+    print("  streamed graphs / workgroups / LDS / left:", list(info.front_stream), flush=True)
     assert info.fused_tasks[0] == 0
     Xd = torch.from_numpy(X).cuda()
     Wd = torch.from_numpy(np.concatenate(Ws, axis=0)).cuda()
@@ -283,6 +332,7 @@ def _whole_layer_case(torch, oracle, graphs, F, n_x, chans, **kw):
     assert np.array_equal(got[~owned], base[~owned])
     _assert_close(np.where(owned[:, None], got, SENTINEL), Y + base.astype(np.float64),
                   T + np.abs(base.astype(np.float64)), owned, tol, "whole layer, accumulated")
+    return info
 
 
 @pytest.mark.parametrize("seed", range(8))

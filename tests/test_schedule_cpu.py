@@ -37,7 +37,7 @@ def test_struct_sizes_match_header():
     assert ctypes.sizeof(K.bspmm_item) == 32
     assert ctypes.sizeof(K.bspmm_options) == 56
     assert ctypes.sizeof(K.bspmm_batch) == 8 + 10 * 8
-    assert ctypes.sizeof(K.bspmm_info) == 16 + 8 + 8 + 8 + 8 + 40 + 8 + 8 + 8 + 16 + 8 + 8
+    assert ctypes.sizeof(K.bspmm_info) == 16 + 8 + 8 + 8 + 8 + 40 + 8 + 8 + 8 + 16 + 16 + 8 + 8
 
 
 def _slot_lanes(bin_):
@@ -738,3 +738,43 @@ def test_summed_channels_and_fused_fronts_keep_the_general_kernel():
     # products would be sums into the shared input block: not planned without the flag)
     lean, info, _ = _lean_of(W.config3_multichannel(graphs=32))
     assert lean == [1, 0] and not info.transposed_supported
+
+
+def _stream_of(graphs, F, n_x, chans, seed=3, **kw):
+    b = W.config3_multichannel(seed=seed, graphs=graphs, F=F, channels=chans, accumulate=True)
+    flags = kw.pop("flags", 0) | K.ACCUMULATE
+    h = K.dry_plan(b, F, flags=flags, front_features=n_x, **kw)
+    try:
+        return [int(v) for v in K.bspmm_plan_info(h).front_stream], b
+    finally:
+        K.bspmm_destroy(h)
+
+
+@pytest.mark.parametrize("graphs,F,n_x,chans,kw", [
+    (2048, 128, 64, 4, {}), (2048, 128, 32, 4, {}), (600, 128, 16, 4, {}), (1100, 128, 128, 2, {}),
+    (64, 128, 64, 4, {"compute_units": 4}), (64, 64, 32, 8, {"compute_units": 4}),
+    (64, 128, 64, 4, {"compute_units": 4, "lds_bytes": 65536}),
+])
+def test_whole_layers_of_many_rounds_are_streamed(graphs, F, n_x, chans, kw):
+    """Plans with front_features and BSPMM_ACCUMULATE whose launch would take many rounds of
+    workgroups run as resident workgroups that stream the graphs: every graph is either in a
+    list or left to a launch of its own, the launch's LDS stays inside a third of a CU's (or
+    what the caller gave), and there are workgroups for every feature tile."""
+    (streamed, workgroups, lds, left), b = _stream_of(graphs, F, n_x, chans, **kw)
+    assert streamed > 0 and streamed + left == graphs
+    assert 0 < lds <= kw.get("lds_bytes", 53248)
+    tiles = {2: (32, 64), 4: (16, 32), 8: (16,)}[chans]
+    assert any(workgroups % (F // t) == 0 for t in tiles)
+    assert workgroups <= 3 * kw.get("compute_units", 256) + F // 16
+
+
+@pytest.mark.parametrize("why,graphs,F,n_x,chans,kw", [
+    ("a launch of one or two rounds", 128, 128, 64, 4, {}),
+    ("the caller keeps the one-launch path", 2048, 128, 64, 4, {"flags": K.ONE_FRONT_LAUNCH}),
+    ("three channels do not split over four wavefronts", 60, 48, 32, 3, {"compute_units": 1}),
+    ("input width not a multiple of 16", 60, 128, 20, 4, {"compute_units": 1}),
+])
+def test_what_the_streaming_launch_does_not_do_stays_on_the_one_launch_path(why, graphs, F, n_x,
+                                                                            chans, kw):
+    stream, _ = _stream_of(graphs, F, n_x, chans, **kw)
+    assert stream == [0, 0, 0, 0], why
