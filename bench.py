@@ -322,6 +322,7 @@ def layer_whole(torch, K, W, n_x=64, channels=4, graphs=128):
     F = 128
     b = W.config3_multichannel(graphs=graphs, F=F, channels=channels, accumulate=True)
     whole = K.Plan(b, options=K.make_options(flags=K.ACCUMULATE, front_features=n_x))
+    kept = K.Plan(b, options=K.make_options(flags=K.ACCUMULATE | K.ONE_FRONT_LAUNCH, front_features=n_x))
     sel = [slice(c, None, channels) for c in range(channels)]
     per_ch = [K.Plan(dataclasses.replace(b, rows=b.rows[q], cols=b.cols[q], nnz=b.nnz[q],
                                          rpt_off=b.rpt_off[q], nz_off=b.nz_off[q],
@@ -345,6 +346,9 @@ def layer_whole(torch, K, W, n_x=64, channels=4, graphs=128):
 
     def run_whole(i, stream):
         K.bspmm_run_gcn(whole.handle, X[i], n_x, Wt, F, bias, Y[i], F, False, stream)
+
+    def run_kept(i, stream):
+        K.bspmm_run_gcn(kept.handle, X[i], n_x, Wt, F, bias, Y[i], F, False, stream)
 
     def run_per_channel(i, stream):
         for c in range(channels):
@@ -380,12 +384,20 @@ def layer_whole(torch, K, W, n_x=64, channels=4, graphs=128):
 
     nnz = int(b.nnz.sum())
     flops = channels * 2 * b.n_b_rows * n_x * F + 2 * nnz * F
+    info = whole.info()
     out = {"workload": f"cfg3 structure, {graphs} graphs, {channels} channels, n_X={n_x}, F={F}",
            "operand_sets": nsets,
-           "one_launch_us": round(timed(run_whole), 3),
+           "streamed": {"graphs": int(info.front_stream[0]), "workgroups": int(info.front_stream[1]),
+                        "lds_bytes": int(info.front_stream[2]),
+                        "graphs_left_to_a_second_launch": int(info.front_stream[3])},
+           "whole_layer_us": round(timed(run_whole), 3),
+           "whole_layer_one_launch_kernel_us": round(timed(run_kept), 3),
            "one_fused_launch_per_channel_us": round(timed(run_per_channel), 3),
            "blas_addmm_per_channel_then_summed_product_us": round(timed(run_unfused), 3)}
-    out["one_launch_gflops"] = round(flops / out["one_launch_us"] * 1e-3, 1)
+    out["whole_layer_gflops"] = round(flops / out["whole_layer_us"] * 1e-3, 1)
+    # the dense part alone against the fp32 matrix-core peak (157.3 TFLOP/s)
+    out["dense_part_frac_of_fp32_mfma_peak"] = round(
+        channels * 2 * b.n_b_rows * n_x * F / (out["whole_layer_us"] * 1e-6) / 157.3e12, 3)
     return out
 
 
@@ -753,9 +765,11 @@ def main():
         extra["paper_grid_batched_vs_non_batched"] = paper_grid(torch, K, W)
         extra["coo_operands"] = coo_operands(torch, K, W)
         extra["layer_front"] = [layer_front(torch, K, W, n_x=n) for n in (32, 64, 128)]
-        extra["layer_whole"] = [layer_whole(torch, K, W, n_x=n) for n in (32, 64)]
-        # a launch of several rounds of workgroups (32 x 32 matrix-core blocks)
-        extra["layer_whole"].append(layer_whole(torch, K, W, n_x=32, graphs=512))
+        # 128 graphs: two (graph, feature tile) pairs per CU; 512 and 2048 graphs: launches of
+        # resident workgroups that stream many graphs each
+        extra["layer_whole"] = [layer_whole(torch, K, W, n_x=n, graphs=g)
+                                for g, n in ((128, 32), (128, 64), (512, 32), (512, 64), (2048, 32),
+                                             (2048, 64))]
 
     out = {
         "metric": "batched SpMM graphs/sec, F=128, batch 128",

@@ -305,7 +305,7 @@ int bspmm_run(bspmm_plan* plan, const float* B, float* C, int64_t ldb, int64_t l
  * under the other (M * n_X rows, channel ch at row ch * n_X) and bias M rows of F floats; the
  * channels of a graph are taken in the order of their operations.
  *
- * Whole layers of many rounds of workgroups (8 feature tiles per CU and more; M = 2, 4 or 8
+ * Whole layers of two and more (graph, feature tile) pairs per CU (M = 2, 4 or 8
  * channels, n_X = 16, 32, 64 or 128) run as a launch of RESIDENT workgroups instead, three per CU:
  * each keeps the weights of its feature tile in registers for the whole launch and streams the
  * graphs of its list through LDS, the next graph's X_i and merged CSR in flight while the matrix

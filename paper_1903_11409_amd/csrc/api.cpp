@@ -309,8 +309,13 @@ void make_stream_plan(bspmm_plan& p)
     if (!units) return;
     const int tiles = F / fw;
     const size_t n_sets = sc.merged_sets.size();
-    // a launch of one or two rounds gains nothing from resident workgroups
-    if ((int64_t)n_sets * tiles < 8 * (int64_t)kn.compute_units) return;
+    // a launch of less than two workgroups per CU gains nothing from resident workgroups
+    // (measured, four channels, F = 128, n_X = 64 / 32: 64 graphs 9.5 against 9.4 us for the
+    // one-launch kernel; 128 graphs 10.5 / 8.2 against 11.9 / 8.2; 256 graphs 14.6 / 10.4
+    // against 24.4 / 15.8)
+    // Kernels with one block per wavefront (tiles of 16 columns, no halves for the larger
+    // graphs): 128 graphs at n_X = 128 take 22.9 against 18.1 us, 512 graphs 51 against 63.
+    if ((int64_t)n_sets * tiles < (units == 2 ? 2 : 8) * (int64_t)kn.compute_units) return;
     if (p.set_records[0].size() != n_sets) return;
 
     // the graphs by size; take them while the launch's LDS stays inside the budget

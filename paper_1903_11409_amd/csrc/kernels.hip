@@ -1921,6 +1921,27 @@ bspmm_gcn_stream_kernel(const StreamSet* __restrict__ sets, const int32_t* __res
         store_pending();
         if (j + 1 < j1) request(nxt, b ^ 1);
 
+        // The CSR block of this graph arrived a trip ago: the entry range of this lane's first
+        // output row and its first four entries are read now, so that after the matrix phase
+        // the gather starts with the tile reads instead of two more dependent LDS round trips.
+        const int m = cur.m;
+        const int* rp = cbase + b * S.csr_words;
+        const int* cols = rp + ((m + 4) & ~3);
+        const float* vals = reinterpret_cast<const float*>(cols + ((cur.nnz + 3) & ~3));
+        int first_p0 = 0, first_p1 = 0;
+        int fc[4] = {0, 0, 0, 0};
+        float fv[4] = {0.f, 0.f, 0.f, 0.f};
+        if (r_lane < m) {
+            first_p0 = rp[r_lane];
+            first_p1 = rp[r_lane + 1];
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+                if (first_p0 + t < first_p1) {
+                    fc[t] = cols[first_p0 + t];
+                    fv[t] = vals[first_p0 + t];
+                }
+        }
+
         // ---- dense tile: [X_i W[0] + bias[0]; ...; X_i W[M-1] + bias[M-1]] -> LDS
         const float* xs = xbase + b * S.x_words;
         const int nmb = (kx + 15) >> 4;
@@ -1973,39 +1994,46 @@ bspmm_gcn_stream_kernel(const StreamSet* __restrict__ sets, const int32_t* __res
         lds_barrier();                                     // tile complete
 
         // ---- gather over the merged CSR: Y_i = sum_ch A_i^ch tile_ch, into registers
-        const int m = cur.m;
-        const int* rp = cbase + b * S.csr_words;
-        const int* cols = rp + ((m + 4) & ~3);
-        const float* vals = reinterpret_cast<const float*>(cols + ((cur.nnz + 3) & ~3));
         const char* tcol = reinterpret_cast<const char*>(tile) + 16 * l;
         const int lsh = fsh + 2;
+        auto add4 = [&](float4& acc, const int (&c)[4], const float (&v)[4]) {
+            float4 bq[4];
 #pragma unroll
-        for (int q = 0; q < kStreamPasses; ++q) {
+            for (int t = 0; t < 4; ++t) bq[t] = *reinterpret_cast<const float4*>(tcol + (c[t] << lsh));
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                acc.x = fmaf(v[t], bq[t].x, acc.x);
+                acc.y = fmaf(v[t], bq[t].y, acc.y);
+                acc.z = fmaf(v[t], bq[t].z, acc.z);
+                acc.w = fmaf(v[t], bq[t].w, acc.w);
+            }
+        };
+        auto rest_of_row = [&](float4& acc, int p0, int p1) {     // four entries a trip, the tail masked
+            for (int p = p0; p < p1; p += 4) {
+                int c[4];
+                float v[4];
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    const int idx = min(p + t, p1 - 1);
+                    c[t] = cols[idx];
+                    v[t] = p + t < p1 ? vals[idx] : 0.f;
+                }
+                add4(acc, c, v);
+            }
+        };
+        {
+            float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (r_lane < m) {
+                if (first_p0 < first_p1) add4(acc, fc, fv);
+                rest_of_row(acc, first_p0 + 4, first_p1);
+            }
+            yv[0] = acc;
+        }
+#pragma unroll
+        for (int q = 1; q < kStreamPasses; ++q) {
             float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
             const int r = q * rows_per_pass + r_lane;
-            if (q * rows_per_pass < m && r < m) {
-                const int p0 = rp[r], p1 = rp[r + 1];
-                for (int p = p0; p < p1; p += 8) {      // eight entries a trip, the tail masked
-                    int c[8];
-                    float v[8];
-#pragma unroll
-                    for (int t = 0; t < 8; ++t) {
-                        const int idx = min(p + t, p1 - 1);
-                        c[t] = cols[idx];
-                        v[t] = p + t < p1 ? vals[idx] : 0.f;
-                    }
-                    float4 bq[8];
-#pragma unroll
-                    for (int t = 0; t < 8; ++t) bq[t] = *reinterpret_cast<const float4*>(tcol + (c[t] << lsh));
-#pragma unroll
-                    for (int t = 0; t < 8; ++t) {
-                        acc.x = fmaf(v[t], bq[t].x, acc.x);
-                        acc.y = fmaf(v[t], bq[t].y, acc.y);
-                        acc.z = fmaf(v[t], bq[t].z, acc.z);
-                        acc.w = fmaf(v[t], bq[t].w, acc.w);
-                    }
-                }
-            }
+            if (q * rows_per_pass < m && r < m) rest_of_row(acc, rp[r], rp[r + 1]);
             yv[q] = acc;
         }
         pend_m = m;

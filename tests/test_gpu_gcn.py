@@ -244,7 +244,9 @@ def test_whole_layer_in_one_launch(torch_cuda, oracle, graphs, F, n_x, chans):
     (24, 64, 32, 8, {"compute_units": 4, "lds_bytes": 163840}),
 ])
 def test_whole_layer_in_wide_blocks(torch_cuda, oracle, graphs, F, n_x, chans, kw):
-    _whole_layer_case(torch_cuda, oracle, graphs, F, n_x, chans, **kw)
+    # (BSPMM_ONE_FRONT_LAUNCH: the shapes that would otherwise be streamed stay on this path)
+    info = _whole_layer_case(torch_cuda, oracle, graphs, F, n_x, chans, one_launch=True, **kw)
+    assert list(info.front_stream) == [0, 0, 0, 0]
 
 
 @pytest.mark.parametrize("graphs,F,n_x,chans,kw,left", [
@@ -299,7 +301,8 @@ def _whole_layer_case(torch, oracle, graphs, F, n_x, chans, **kw):
     b = W.config3_multichannel(seed=500 + graphs, graphs=graphs, F=F, channels=chans, accumulate=True)
     X, Ws, biases = _layer(b, n_x, 11, channels=chans)
     print(f"layer case: graphs={graphs} F={F} n_X={n_x} channels={chans} {kw}", flush=True)
-    plan = K.Plan(b, options=K.make_options(flags=K.ACCUMULATE, front_features=n_x, **kw))
+    flags = K.ACCUMULATE | (K.ONE_FRONT_LAUNCH if kw.pop("one_launch", False) else 0)
+    plan = K.Plan(b, options=K.make_options(flags=flags, front_features=n_x, **kw))
     info = plan.info()
     print("  streamed graphs / workgroups / LDS / left:", list(info.front_stream), flush=True)
     assert info.fused_tasks[0] == 0
@@ -361,8 +364,9 @@ def test_random_whole_layers(torch_cuda, oracle, seed, **kw):
                    c_block_of_op=c_block_of_op)
     X, Ws, biases = _layer(b, n_x, seed, channels=chans)
     print(f"random layer {seed}: graphs={graphs} channels={chans} F={F} n_X={n_x}", flush=True)
+    flags = K.ACCUMULATE | (K.ONE_FRONT_LAUNCH if kw.pop("one_launch", False) else 0)
     try:
-        plan = K.Plan(b, options=K.make_options(flags=K.ACCUMULATE, front_features=n_x, **kw))
+        plan = K.Plan(b, options=K.make_options(flags=flags, front_features=n_x, **kw))
     except K.BspmmError as e:
         assert e.code == K.ETOOBIG
         pytest.skip("a set does not fit on chip beside its layer input")
@@ -382,10 +386,14 @@ def test_random_whole_layers(torch_cuda, oracle, seed, **kw):
     _assert_close(Yd.cpu().numpy(), Y, T, _owned(b.c_row_off, b.rows, b.n_c_rows), tol, f"random layer {seed}")
 
 
+@pytest.mark.parametrize("one_launch", [False, True], ids=["streamed_where_it_can", "one_launch"])
 @pytest.mark.parametrize("seed", range(20, 32))
-def test_random_whole_layers_in_several_rounds(torch_cuda, oracle, seed):
-    """The same random layers with the scheduler told that the chip has one CU: launches of
-    more than six workgroups then count as several rounds and (up to 64 input features, tiles
-    of 32 columns or a multiple) make their dense tiles in 32 x 32 blocks."""
-    test_random_whole_layers(torch_cuda, oracle, seed, compute_units=1)
+def test_random_whole_layers_in_several_rounds(torch_cuda, oracle, seed, one_launch):
+    """The same random layers with the scheduler told that the chip has one CU.  Shapes the
+    streaming kernel takes (2, 4 or 8 channels, n_X a multiple of 16 up to 128) then run as
+    resident workgroups, larger graphs in halves or in a launch of their own; with
+    BSPMM_ONE_FRONT_LAUNCH, and for every other shape, launches of more than six workgroups count
+    as several rounds and (up to 64 input features, tiles of 32 columns or a multiple) make their
+    dense tiles in 32 x 32 blocks."""
+    test_random_whole_layers(torch_cuda, oracle, seed, compute_units=1, one_launch=one_launch)
 

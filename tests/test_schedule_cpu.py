@@ -769,7 +769,7 @@ def test_whole_layers_of_many_rounds_are_streamed(graphs, F, n_x, chans, kw):
 
 
 @pytest.mark.parametrize("why,graphs,F,n_x,chans,kw", [
-    ("a launch of one or two rounds", 128, 128, 64, 4, {}),
+    ("less than two workgroups per CU", 100, 128, 64, 4, {}),
     ("the caller keeps the one-launch path", 2048, 128, 64, 4, {"flags": K.ONE_FRONT_LAUNCH}),
     ("three channels do not split over four wavefronts", 60, 48, 32, 3, {"compute_units": 1}),
     ("input width not a multiple of 16", 60, 128, 20, 4, {"compute_units": 1}),
