@@ -37,9 +37,12 @@ def parse_args():
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
     ap.add_argument("--only", default=None,
                     choices=["cfg2", "cfg2_F64", "cfg3", "cfg4_F256", "cfg4_F1024", "cfg5",
-                             "cfg5_transposed", "cfg5_staged_ops", "cfg5_row_block_ops"],
+                             "cfg5_transposed", "cfg5_staged_ops", "cfg5_row_block_ops",
+                             "layer_512_nx64", "layer_2048_nx32", "layer_2048_nx64"],
                     help="run only this configuration, HBM-cold, eager launches, and print a "
-                         "short JSON line (for rocprofv3 counter runs per configuration)")
+                         "short JSON line (for rocprofv3 counter runs per configuration); "
+                         "layer_<graphs>_nx<n_X>: one whole graph-convolution layer, four "
+                         "channels, through bspmm_run_gcn and through the BLAS library")
     ap.add_argument("--no-graph", action="store_true",
                     help="with --only: eager launches only (counter passes)")
     ap.add_argument("--calib-copy", action="store_true",
@@ -405,7 +408,7 @@ def kernel_resources(K, lds_bytes):
     """Registers, LDS and workgroups per CU of the library's kernels (bspmm_kernel_info)."""
     out = {}
     for i, name in enumerate(K.KERNEL_NAMES):
-        dyn = lds_bytes if name in ("lean", "general", "general_scalar", "coo") else 0
+        dyn = lds_bytes if name in ("lean", "general", "general_scalar", "coo", "layer_stream") else 0
         r = K.bspmm_kernel_info(i, dyn)
         out[name] = {"vgprs": r.vgprs, "static_lds_bytes": r.static_lds_bytes,
                      "scratch_bytes": r.scratch_bytes, "lanes_per_workgroup": r.threads,
@@ -587,6 +590,13 @@ def main():
     torch.cuda.set_device(0)
     K.lib()
 
+    if args.only and args.only.startswith("layer_"):
+        # one whole graph-convolution layer (4 channels, F = 128), HBM-cold: layer_<graphs>_nx<n_X>
+        graphs, n_x = (int(v) for v in args.only[len("layer_"):].split("_nx"))
+        line = layer_whole(torch, K, W, n_x=n_x, graphs=graphs)
+        line["kernel"] = kernel_resources(K, line["streamed"]["lds_bytes"])["layer_stream"]
+        print(json.dumps(line))
+        return
     if args.only:
         def cfg5_part(generic):
             # config 5 cut in two by what the scheduler does with an operation: staged in LDS, or
