@@ -291,16 +291,23 @@ void make_stream_plan(bspmm_plan& p)
     st = bspmm_plan::Stream();
     const Schedule& sc = p.sched[0];
     const Knobs& kn = p.knobs;
-    const int M = p.front_channels, nx = kn.front, F = p.F;
-    if (nx <= 0 || !kn.accumulate || kn.one_front_launch || sc.merged_sets.empty() ||
-        !sc.fused_sets.empty() || sc.fused_tasks > 0 || p.merged_words[0] >= (int64_t(1) << 32))
-        return;
-    if (nx % 16 != 0 || (M != 2 && M != 4 && M != 8)) return;
+    const int nx = kn.front, F = p.F;
+    if (nx <= 0 || kn.one_front_launch || !sc.fused_sets.empty() || sc.fused_tasks > 0) return;
+    // Plans of single channels (no operations summed: every operation is a graph of its own)
+    // take the same kernel with one channel; their CSR arrays are copied once per plan into
+    // blocks of the same form as the merged ones (row pointers, columns, values back to back),
+    // which is what a workgroup requests in one piece.
+    const bool single = sc.merged_sets.empty();
+    if (single && !p.set_records[0].empty()) return;
+    const int M = single ? 1 : p.front_channels;
+    if (!single && !kn.accumulate) return;
+    if (nx % 16 != 0 || (M != 1 && M != 2 && M != 4 && M != 8)) return;
     const int nx16 = nx / 16;
     int units = 0, fw = 0;
     for (int u : {2, 1}) {
         const int w = 64 * u / M;
-        if (w >= 16 && F % w == 0 && stream_supported(nx16, u)) {
+        // (tiles of up to 64 columns: 16 lanes per output row, 64 rows in the gather's passes)
+        if (w >= 16 && w <= 64 && F % w == 0 && stream_supported(nx16, u)) {
             units = u;
             fw = w;
             break;
@@ -308,15 +315,50 @@ void make_stream_plan(bspmm_plan& p)
     }
     if (!units) return;
     const int tiles = F / fw;
-    const size_t n_sets = sc.merged_sets.size();
+    const DirOps& o = p.dir[0];
+    // the graphs: sets of channel operations, or the operations themselves
+    std::vector<std::vector<int>> single_sets;
+    if (single) {
+        for (int i = 0; i < o.size(); ++i) single_sets.push_back(std::vector<int>(1, i));
+    }
+    const std::vector<std::vector<int>>& graphs = single ? single_sets : sc.merged_sets;
+    const size_t n_sets = graphs.size();
     // a launch of less than two workgroups per CU gains nothing from resident workgroups
     // (measured, four channels, F = 128, n_X = 64 / 32: 64 graphs 9.5 against 9.4 us for the
     // one-launch kernel; 128 graphs 10.5 / 8.2 against 11.9 / 8.2; 256 graphs 14.6 / 10.4
     // against 24.4 / 15.8)
     // Kernels with one block per wavefront (tiles of 16 columns, no halves for the larger
     // graphs): 128 graphs at n_X = 128 take 22.9 against 18.1 us, 512 graphs 51 against 63.
-    if ((int64_t)n_sets * tiles < (units == 2 ? 2 : 8) * (int64_t)kn.compute_units) return;
-    if (p.set_records[0].size() != n_sets) return;
+    if ((int64_t)n_sets * tiles < (units == 2 || single ? 2 : 8) * (int64_t)kn.compute_units) return;
+    if (single) {
+        int64_t words = 0;
+        std::vector<SetRecord>& made = p.set_records[0];
+        for (int i = 0; i < o.size(); ++i) {
+            SetRecord r;
+            std::memset(&r, 0, sizeof r);
+            r.members = 1;
+            r.m = o.m[i];
+            r.plain = 1;
+            r.rpt_off[0] = o.rpt_off[i];
+            r.nz_off[0] = o.nz_off[i];
+            r.nnz[0] = o.nnz[i];
+            r.k[0] = o.k[i];
+            r.tile_row[0] = 0;
+            r.merged_rpt_off = words;
+            words += round_up(r.m + 1, 4);
+            r.merged_nz_off = words;
+            words += 2 * (int64_t)round_up(o.nnz[i], 4);
+            made.push_back(r);
+        }
+        p.merged_words[0] = words;
+    }
+    if (p.set_records[0].size() != n_sets || p.merged_words[0] >= (int64_t(1) << 32)) {
+        if (single) {
+            p.set_records[0].clear();
+            p.merged_words[0] = 0;
+        }
+        return;
+    }
 
     // the graphs by size; take them while the launch's LDS stays inside the budget
     // (three workgroups per CU: a third of the CU's 160 KiB less what the allocation granule
@@ -353,7 +395,13 @@ void make_stream_plan(bspmm_plan& p)
         csr_cap = cw;
         mine.push_back(i);
     }
-    if (mine.empty()) return;
+    if (mine.empty()) {
+        if (single) {
+            p.set_records[0].clear();
+            p.merged_words[0] = 0;
+        }
+        return;
+    }
     st.nx16 = nx16, st.units = units, st.fw = fw, st.tiles = tiles;
     st.tile_words = (int)(M * kx_cap * fw);
     st.x_words = (int)(kx_cap * nx);
@@ -362,14 +410,19 @@ void make_stream_plan(bspmm_plan& p)
     // halves of 16 columns, the half tile at the start of the same LDS, the CSR block at its end
     // and at least one 16-row block of X_i between them.
     std::vector<int> halves;
-    if (units == 2 && fw == 32) {
-        const int64_t total = (int64_t)st.tile_words + 2 * st.x_words + 2 * st.csr_words;
+    if ((units == 2 && fw == 32) || units == 1) {
+        // (kernels with one block per wavefront take such a graph in one piece, its tile at full
+        // width: what they gain is the room of the second X buffer and of the prefetch)
+        const int piece = units == 2 ? 16 : fw;
+        // (such a graph may use the launch's LDS up to the budget: the X buffers are made
+        // larger than the listed graphs need where that is what it takes)
+        const int64_t total = budget_words - 64;
         std::vector<char> is_mine(n_sets, 0);
         for (int i : mine) is_mine[i] = 1;
         auto fits_halves = [&](int i, int64_t csr_room) {
             const SetRecord& r = recs[i];
-            return r.m > 0 && r.k[0] > 0 && r.m <= kStreamPasses * (kThreads / 4) && csr_of(i) <= csr_room &&
-                   (int64_t)M * r.k[0] * 16 + 16 * nx + csr_room <= total;
+            return r.m > 0 && r.k[0] > 0 && csr_of(i) <= csr_room &&
+                   (int64_t)M * r.k[0] * piece + 16 * nx + csr_room <= total;
         };
         int64_t room = 0;
         for (size_t i = 0; i < n_sets; ++i)
@@ -378,6 +431,10 @@ void make_stream_plan(bspmm_plan& p)
             if (!is_mine[i] && fits_halves((int)i, room)) halves.push_back((int)i);
         st.big_csr_words = halves.empty() ? 0 : (int)room;
         st.big = (int)halves.size();
+        int64_t need = 0;
+        for (int i : halves) need = std::max(need, (int64_t)M * recs[i].k[0] * piece + 16 * nx + room);
+        const int64_t have = (int64_t)st.tile_words + 2 * st.x_words + 2 * st.csr_words;
+        if (need > have) st.x_words += (int)round_up((int)((need - have + 1) / 2), 4);
     }
 
     // lists: as many workgroups as the chip holds at once, the same lists for every tile
@@ -406,7 +463,6 @@ void make_stream_plan(bspmm_plan& p)
             load.insert(least);
         }
     }
-    const DirOps& o = p.dir[0];
     st.list.push_back(0);
     std::vector<char> streamed(n_sets, 0);
     for (int l = 0; l < lists; ++l) {
@@ -414,7 +470,7 @@ void make_stream_plan(bspmm_plan& p)
         std::stable_partition(of_list[l].begin(), of_list[l].end(), [&](int i) { return in_halves[i] != 0; });
         for (int i : of_list[l]) {
             const SetRecord& r = recs[i];
-            const int op0 = sc.merged_sets[i][0];
+            const int op0 = graphs[i][0];
             StreamSet e;
             e.in_row = o.in_off[op0];
             e.out_row = o.out_off[op0];
@@ -430,8 +486,8 @@ void make_stream_plan(bspmm_plan& p)
     // the other graphs: their items of the one-launch schedule, in its order
     for (size_t j = 0; j < sc.items.size(); ++j) {
         const int op = j < sc.item_op.size() ? sc.item_op[j] : -1;
-        if (op < sc.first_stand_in || sc.items[j].nrows <= 0) continue;
-        if (!streamed[(size_t)(op - sc.first_stand_in)]) st.rest.push_back(sc.items[j]);
+        if (op < (single ? 0 : sc.first_stand_in) || sc.items[j].nrows <= 0) continue;
+        if (!streamed[(size_t)(op - (single ? 0 : sc.first_stand_in))]) st.rest.push_back(sc.items[j]);
     }
 }
 
@@ -681,12 +737,12 @@ int plan_host(bspmm_plan& p, const bspmm_batch* b, int32_t F, const Knobs& kn)
     at = align_up(at + 4);
     for (int d = 0; d < 2; ++d) {
         describe_sets(p, d);
+        if (d == 0) make_stream_plan(p);      // (may add the blocks of single-channel graphs)
         L.sets[d] = at;
         at = align_up(at + p.set_records[d].size() * sizeof(SetRecord));
         L.merged[d] = at;
         at = align_up(at + (size_t)p.merged_words[d] * 4);
     }
-    make_stream_plan(p);
     L.stream_sets = at;
     at = align_up(at + p.stream.sets.size() * sizeof(StreamSet));
     L.stream_list = at;
@@ -785,6 +841,7 @@ int plan_with_budget(bspmm_plan& p, const Batch* b, int32_t F, const bspmm_optio
                 o.lds_bytes = bytes;
                 Knobs small = knobs_for(&o, !dry);
                 small.need_both = false;
+                small.lds_given = false;      // (the library's choice, not the caller's)
                 p = bspmm_plan();
                 const int rc = plan_fn(p, b, F, small);
                 if (rc != BSPMM_ETOOBIG) return rc;
@@ -803,6 +860,7 @@ int plan_with_budget(bspmm_plan& p, const Batch* b, int32_t F, const bspmm_optio
         o.lds_bytes = a.bytes;
         kn = knobs_for(&o, !dry);
         kn.need_both = a.both;
+        kn.lds_given = false;
         p = bspmm_plan();
         rc = plan_fn(p, b, F, kn);
         if (rc != BSPMM_ETOOBIG) return rc;
@@ -1206,7 +1264,7 @@ int run_gcn(bspmm_plan* p, const float* X, int64_t ldx, const float* W, int64_t 
     if (ldx % 4 || ldw % 4 || ldy % 4 || misaligned(X) || misaligned(W) || misaligned(Y))
         return BSPMM_EINVAL;
     const bool sets = !sc.merged_sets.empty();
-    if (sets) {
+    if (sets || p->stream.on()) {
         const int mrc = enqueue_merge(p, 0, s);
         if (mrc != BSPMM_OK) return mrc;
     }
@@ -1225,7 +1283,7 @@ int run_gcn(bspmm_plan* p, const float* X, int64_t ldx, const float* W, int64_t 
         S.y = Y;
         StreamShape& sh = S.shape;
         sh.ld_x = ldx, sh.ld_w = ldw, sh.ld_y = ldy, sh.bias_stride = p->F;
-        sh.tiles = st.tiles, sh.fw = st.fw, sh.channels = p->front_channels;
+        sh.tiles = st.tiles, sh.fw = st.fw, sh.channels = sets ? p->front_channels : 1;
         sh.accumulate = accumulate ? 1 : 0;
         sh.tile_words = st.tile_words, sh.x_words = st.x_words, sh.csr_words = st.csr_words;
         sh.big_csr_words = st.big_csr_words;

@@ -1652,8 +1652,11 @@ __global__ void __launch_bounds__(kThreads) bspmm_gcn_kernel(const LaunchParams 
 }
 
 // ---------------------------------------------------------------------------------------
-// The whole layer (Fig. 7 with the ElementWiseAdd) for batches of many rounds of workgroups:
-// resident workgroups, each bound to one feature tile, stream the graphs of their list.
+// The layer (Fig. 7: one channel, or all channels with the ElementWiseAdd) for batches of two
+// and more workgroups per CU: resident workgroups, each bound to one feature tile, stream the
+// graphs of their list.  A graph is a set of M channel operations with one merged CSR block
+// (row pointers, columns, values back to back); plans of single channels have such a block per
+// operation (M = 1).
 //
 // A workgroup of bspmm_gcn_kernel goes through its phases one after the other - operands from
 // memory, dense tile on the matrix cores, gather, store - stages its weight tile again for
@@ -1670,9 +1673,9 @@ __global__ void __launch_bounds__(kThreads) bspmm_gcn_kernel(const LaunchParams 
 //     each) are fetched with scalar loads two trips ahead.
 //   * the launch's LDS is sized for the graphs that fit a budget of a third of a CU's LDS, so
 //     that three workgroups share a CU: one's matrix phase overlaps the others' gathers and
-//     requests.  Larger graphs (a few per cent of a molecule batch) are taken in two halves of
-//     16 columns out of the same LDS (see below); what does not fit even so is not in the
-//     lists at all (the host gives it to bspmm_gcn_kernel in a launch of its own).
+//     requests.  Larger graphs (a few per cent of a molecule batch) are taken one at a time
+//     out of the same LDS, their X_i in chunks (see below); what does not fit even so is not
+//     in the lists at all (the host gives it to bspmm_gcn_kernel in a launch of its own).
 // Arithmetic: the n_X products of a dense element are added by the matrix instructions in
 // the order 4 g + j within 16 s (bias as the initial value of the accumulator; two
 // accumulators per block, k even and odd, in kernels with one block per wavefront and in the
@@ -1798,13 +1801,16 @@ bspmm_gcn_stream_kernel(const StreamSet* __restrict__ sets, const int32_t* __res
     };
 
     // ---- graphs too large for the buffers above come first in a list and are taken one at a
-    // time, without prefetch, in two halves of 16 columns (kernels with two blocks per wavefront
-    // and tiles of 32 columns: a wavefront then owns one channel): the half tile
-    // (channels x kx x 16) sits at the start of LDS, the merged CSR block at its end, and the
-    // rows of X_i pass through the space between them in chunks of as many 16-row blocks as
-    // fit.  Each half: [chunk from memory, its blocks on the matrix cores] ..., gather, store.
+    // time, without prefetch: the tile sits at the start of LDS, the merged CSR block at its end,
+    // and the rows of X_i pass through the space between them in chunks of as many 16-row blocks
+    // as fit.  Kernels with two blocks per wavefront (tiles of 32 columns: a wavefront owns one
+    // channel) take such a graph in two halves of 16 columns, each with a half tile
+    // (channels x kx x 16); kernels with one block per wavefront take it in one piece.
+    // Each piece: [chunk from memory, its blocks on the matrix cores] ..., gather, store.
     int jn = j0;
-    if (U == 2 && nbw == 2) {
+    constexpr int PIECES = U == 2 ? 2 : 1;
+    if (U == 1 || nbw == 2) {
+        const int psh = U == 2 ? 4 : fsh;           // a piece's tile row = 1 << psh floats
         const int total_words = S.tile_words + 2 * S.x_words + 2 * S.csr_words;
         int* cbig = sm + total_words - S.big_csr_words;
         for (; jn < j1; ++jn) {
@@ -1814,9 +1820,9 @@ bspmm_gcn_stream_kernel(const StreamSet* __restrict__ sets, const int32_t* __res
                              csr_w > S.csr_words || bg.m > kStreamPasses * rows_per_pass;
             if (!big) break;
             const int kx = bg.kx, m = bg.m;
-            const int half_words = S.channels * kx * 16;
-            float* xbig = tile + half_words;
-            const int rows_chunk = min((kx + 15) & ~15, ((total_words - S.big_csr_words - half_words) / NX) & ~15);
+            const int piece_words = (S.channels * kx) << psh;
+            float* xbig = tile + piece_words;
+            const int rows_chunk = min((kx + 15) & ~15, ((total_words - S.big_csr_words - piece_words) / NX) & ~15);
             if (rows_chunk < 16 || csr_w > S.big_csr_words) return;    // (the host never lists such a graph)
             {
                 const int32_t* cg = merged + bg.csr_off;
@@ -1830,7 +1836,9 @@ bspmm_gcn_stream_kernel(const StreamSet* __restrict__ sets, const int32_t* __res
             const int* rp = cbig;
             const int* cols = rp + ((m + 4) & ~3);
             const float* vals = reinterpret_cast<const float*>(cols + ((bg.nnz + 3) & ~3));
-            for (int h = 0; h < 2; ++h) {
+#pragma unroll
+            for (int h = 0; h < PIECES; ++h) {
+                const int pcol = U == 2 ? col : unit_col[0];      // column inside the piece
                 for (int r0 = 0; r0 < kx; r0 += rows_chunk) {
                     const int rows = min(rows_chunk, kx - r0);
                     const int total = rows << XSH;
@@ -1858,19 +1866,20 @@ bspmm_gcn_stream_kernel(const StreamSet* __restrict__ sets, const int32_t* __res
                         }
                         const mfma4 r4 = acc0 + acc1;
                         const int row = r0 + 16 * mb + 4 * g;
-                        float* tp = tile + ((unit_ch[h] * kx + row) << 4) + col;
+                        float* tp = tile + ((unit_ch[h] * kx + row) << psh) + pcol;
 #pragma unroll
                         for (int i = 0; i < 4; ++i) {
-                            float* q = 16 * mb + 4 * g + i < rows ? tp + (i << 4) : sink;
+                            float* q = 16 * mb + 4 * g + i < rows ? tp + (i << psh) : sink;
                             *q = r4[i];
                         }
                     }
-                    lds_barrier();      // the chunk may be replaced; after the last one: half tile complete
+                    lds_barrier();      // the chunk may be replaced; after the last one: the piece's tile complete
                 }
-                // gather over the half tile: four lanes per output row
-                const int hr = tid >> 2, hl = tid & 3;
+                // gather over the piece: a quarter of its columns per lane
+                const int hsh = psh - 2;
+                const int hr = tid >> hsh, hl = tid & ((1 << hsh) - 1);
                 const char* tcol = reinterpret_cast<const char*>(tile) + 16 * hl;
-                for (int r = hr; r < m; r += kThreads >> 2) {
+                for (int r = hr; r < m; r += kThreads >> hsh) {
                     const int p0 = rp[r], p1 = rp[r + 1];
                     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
                     for (int p = p0; p < p1; p += 4) {
@@ -1884,7 +1893,7 @@ bspmm_gcn_stream_kernel(const StreamSet* __restrict__ sets, const int32_t* __res
                         }
                         float4 bq[4];
 #pragma unroll
-                        for (int t = 0; t < 4; ++t) bq[t] = *reinterpret_cast<const float4*>(tcol + (c[t] << 6));
+                        for (int t = 0; t < 4; ++t) bq[t] = *reinterpret_cast<const float4*>(tcol + (c[t] << (psh + 2)));
 #pragma unroll
                         for (int t = 0; t < 4; ++t) {
                             acc.x = fmaf(v[t], bq[t].x, acc.x);
@@ -1893,14 +1902,14 @@ bspmm_gcn_stream_kernel(const StreamSet* __restrict__ sets, const int32_t* __res
                             acc.w = fmaf(v[t], bq[t].w, acc.w);
                         }
                     }
-                    float* yp = y + (bg.out_row + r) * S.ld_y + f0 + 16 * h + 4 * hl;
+                    float* yp = y + (bg.out_row + r) * S.ld_y + f0 + (h << psh) + 4 * hl;
                     if (S.accumulate) {
                         const float4 old = *reinterpret_cast<const float4*>(yp);
                         acc.x += old.x, acc.y += old.y, acc.z += old.z, acc.w += old.w;
                     }
                     store_out<4>(yp, acc);
                 }
-                lds_barrier();          // the half tile may be overwritten
+                lds_barrier();          // the piece's tile may be overwritten
             }
         }
         if (jn >= j1) return;

@@ -89,6 +89,54 @@ def test_layer_channel_configurations(torch_cuda, oracle, maker, n_x):
     _run_and_check(torch_cuda, oracle, b, n_x)
 
 
+@pytest.mark.parametrize("maker,n_x,kw,left", [
+    # single channels of two and more workgroups per CU are run by resident workgroups that
+    # stream the graphs: for real (600 graphs), and on small batches by telling the scheduler
+    # that the chip has few CUs; `left`: graphs that fit the streaming launch in no way run in a
+    # launch of their own
+    (lambda: W.config2_molecule(graphs=600), 64, {}, False),
+    (lambda: W.config2_molecule(graphs=48), 16, {"compute_units": 4}, False),
+    (lambda: W.config2_molecule(graphs=48), 32, {"compute_units": 4}, False),
+    (lambda: W.config2_molecule(graphs=48, F=64), 64, {"compute_units": 4}, False),
+    (lambda: W.config2_molecule(graphs=48, F=256), 128, {"compute_units": 4}, False),
+    (lambda: W.config3_multichannel(graphs=64), 32, {"compute_units": 8}, False),    # shared input blocks
+    (lambda: W.random_general(55, F=64, shapes=[(100, 90, 700), (60, 60, 300), (12, 150, 80), (150, 20, 300)] * 3),
+     16, {"compute_units": 1}, None),
+    (lambda: W.config5_skewed(graphs=256, F=64, asymmetric=True), 64, {"compute_units": 32}, True),
+    (lambda: W.config4_wide(F=512, graphs=64), 64, {"compute_units": 16}, False),
+])
+def test_single_channel_streamed(torch_cuda, oracle, maker, n_x, kw, left):
+    b = maker()
+    plan = _run_and_check(torch_cuda, oracle, b, n_x, **kw)
+    info = plan.info()
+    print("  streamed graphs / workgroups / LDS / left:", list(info.front_stream), flush=True)
+    assert info.front_stream[0] > 0
+    if left is not None:
+        assert (info.front_stream[3] > 0) == left
+    # the later channels of a layer add onto the output
+    X, Ws, biases = _layer(b, n_x, 1)
+    torch = torch_cuda
+    Xd, Wd, bd = (torch.from_numpy(a).cuda() for a in (X, Ws[0], biases[0]))
+    base = np.random.default_rng(4).uniform(-1, 1, size=(b.n_c_rows, b.F)).astype(np.float32)
+    onto = torch.from_numpy(base).cuda()
+    plan.run_gcn(Xd, Wd, bd, onto, accumulate=True)
+    torch.cuda.synchronize()
+    ref, T = oracle.gcn_channel(b, X, Ws[0], biases[0])
+    owned = _owned(b.c_row_off, b.rows, b.n_c_rows)
+    got = onto.cpu().numpy()
+    assert np.array_equal(got[~owned], base[~owned])
+    _assert_close(np.where(owned[:, None], got, SENTINEL), ref + base.astype(np.float64),
+                  T + np.abs(base.astype(np.float64)), owned, _tol(b, n_x), "streamed channel, accumulated")
+    # and the plan still runs the plain product
+    Bd = torch.from_numpy(b.B).cuda()
+    Cd = torch.full((b.n_c_rows, b.F), SENTINEL, dtype=torch.float32, device="cuda")
+    plan.run(Bd, Cd)
+    torch.cuda.synchronize()
+    refc, S = oracle.forward_batch(b)
+    err = np.abs(Cd.cpu().numpy().astype(np.float64) - refc)[owned]
+    assert np.all(err <= 1e-5 * S[owned])
+
+
 @pytest.mark.parametrize("n_x", [4, 8, 20, 60, 64, 68, 132, 256])
 def test_input_widths_and_ragged_operations(torch_cuda, oracle, n_x):
     b = W.random_general(101, F=48, shapes=[(9, 5, 40), (5, 9, 40), (30, 30, 0), (1, 1, 1),
