@@ -256,10 +256,11 @@ def coo_operands(torch, K, W):
     return out
 
 
-def layer_front(torch, K, W, n_x=64):
-    """One channel of the graph-convolution layer on the headline batch, HBM-cold: the fused
-    launch (bspmm_run_gcn) against MatMul+Add by the BLAS library followed by bspmm_run."""
-    b = W.config2_molecule(F=128)
+def layer_front(torch, K, W, n_x=64, graphs=128):
+    """One channel of the graph-convolution layer on molecule graphs (128: the headline batch),
+    HBM-cold: the fused launch (bspmm_run_gcn) against MatMul+Add by the BLAS library followed by
+    bspmm_run."""
+    b = W.config2_molecule(F=128, graphs=graphs)
     F = b.F
     fused = K.Plan(b, options=K.make_options(front_features=n_x))
     plain = K.Plan(b)
@@ -307,7 +308,11 @@ def layer_front(torch, K, W, n_x=64):
 
     nnz = int(b.nnz.sum())
     flops = 2 * b.n_b_rows * n_x * F + 2 * nnz * F
-    out = {"workload": f"cfg2_molecule, n_X={n_x}, F={F}, one channel", "operand_sets": nsets,
+    info = fused.info()
+    out = {"workload": f"cfg2_molecule, {graphs} graphs, n_X={n_x}, F={F}, one channel", "operand_sets": nsets,
+           "streamed": {"graphs": int(info.front_stream[0]), "workgroups": int(info.front_stream[1]),
+                        "lds_bytes": int(info.front_stream[2]),
+                        "graphs_left_to_a_second_launch": int(info.front_stream[3])},
            "fused_us": round(timed(run_fused), 3),
            "blas_addmm_then_bspmm_run_us": round(timed(run_unfused), 3),
            "blas_addmm_alone_us": round(timed(run_front_only), 3)}
@@ -774,7 +779,8 @@ def main():
         extra["channel_sum"] = acc
         extra["paper_grid_batched_vs_non_batched"] = paper_grid(torch, K, W)
         extra["coo_operands"] = coo_operands(torch, K, W)
-        extra["layer_front"] = [layer_front(torch, K, W, n_x=n) for n in (32, 64, 128)]
+        extra["layer_front"] = [layer_front(torch, K, W, n_x=n, graphs=g)
+                                for g, n in ((128, 32), (128, 64), (128, 128), (1024, 64), (4096, 128))]
         # 128 graphs: two (graph, feature tile) pairs per CU; 512 and 2048 graphs: launches of
         # resident workgroups that stream many graphs each
         extra["layer_whole"] = [layer_whole(torch, K, W, n_x=n, graphs=g)
