@@ -96,10 +96,18 @@ bool fits_slot(const DirOps& o, int i, int tile, int F, int vec, int lanes, int 
 }
 
 // Decide bin and tile of operation i given the batch-wide tile candidates from `first` on.
+// `widest_fit` (optional): per operation, the index of the widest candidate whose whole-workgroup
+// item fits LDS (cand.size() when none does).  Fitting is monotone in the tile width, so with it
+// the plain case - no forced bin, no sub-workgroup slots - is answered without looking at the
+// operation again, however often the search over tiles and row cuts asks.
 Choice choose(const DirOps& o, int i, int F, int vec, const std::vector<int>& cand, size_t first,
-              const Knobs& kn, bool allow_small)
+              const Knobs& kn, bool allow_small, const std::vector<uint8_t>* widest_fit = nullptr)
 {
     const int forced = kn.front > 0 ? BSPMM_BIN_WORKGROUP : kn.force_bin;   // the fused front runs on whole workgroups
+    if (widest_fit && forced < 0 && !allow_small) {
+        const size_t c = std::max<size_t>(first, (*widest_fit)[i]);
+        return c < cand.size() ? Choice{BSPMM_BIN_WORKGROUP, cand[c]} : Choice{BSPMM_BIN_GENERIC, cand[0]};
+    }
     if (forced == BSPMM_BIN_GENERIC) return {BSPMM_BIN_GENERIC, cand[0]};
     if (forced >= 0) {
         for (size_t c = first; c < cand.size(); ++c) {
@@ -357,13 +365,14 @@ int stand_in_tile(const DirOps& o, int v, int F, int vec, const std::vector<int>
 // the set's merged one) stands in for them and is drafted as a workgroup item like any other.
 void draft_all(const DirOps& o, int F, int vec, const std::vector<int>& cand, size_t first,
                const Knobs& kn, int cap, bool allow_small,
-               const Groups& outs, const std::vector<int>& stand_in, bool* fits, Sink& sink)
+               const Groups& outs, const std::vector<int>& stand_in, bool* fits, Sink& sink,
+               const std::vector<uint8_t>* widest_fit = nullptr)
 {
     int nfused = 0;
     for (int g = 0; g < outs.size(); ++g) {
         if (outs.count(g) == 1) {
             const int i = *outs.begin(g);
-            draft_op(o, i, F, vec, choose(o, i, F, vec, cand, first, kn, allow_small), kn, cap, sink);
+            draft_op(o, i, F, vec, choose(o, i, F, vec, cand, first, kn, allow_small, widest_fit), kn, cap, sink);
         } else if (stand_in[g] >= 0) {
             const int v = stand_in[g];
             Choice ch = {BSPMM_BIN_WORKGROUP, stand_in_tile(o, v, F, vec, cand, kn)};
@@ -545,9 +554,18 @@ Schedule make_schedule(const DirOps& ops_in, int F, const Knobs& kn_in)
     }
     bool fits = true;
     int64_t counted_tile_words = 0;
+    std::vector<uint8_t> widest_fit(ops.size(), (uint8_t)std::min<size_t>(cand.size(), 255));
+    if (kn.front == 0 && kn.force_bin < 0 && cand.size() < 255)
+        for (int i = 0; i < ops.size(); ++i)
+            for (size_t c = 0; c < cand.size(); ++c)
+                if (fits_slot(ops, i, cand[c], F, vec, kThreads, 0, kn)) {
+                    widest_fit[i] = (uint8_t)c;
+                    break;
+                }
+    const std::vector<uint8_t>* fit_table = kn.front == 0 && kn.force_bin < 0 && cand.size() < 255 ? &widest_fit : nullptr;
     auto workgroups_of = [&](size_t first, int cap, bool small) {
         Sink counter;
-        draft_all(ops, F, vec, cand, first, kn, cap, small, outs, stand_in, &fits, counter);
+        draft_all(ops, F, vec, cand, first, kn, cap, small, outs, stand_in, &fits, counter, fit_table);
         counted_tile_words = counter.tile_words;
         return counter.workgroups();
     };
@@ -602,7 +620,7 @@ Schedule make_schedule(const DirOps& ops_in, int F, const Knobs& kn_in)
     }
     if (kn.front > 0) {   // every operation must hold its layer input on chip
         Sink probe;
-        draft_all(ops, F, vec, cand, chosen, kn, cap, allow_small, outs, stand_in, &fits, probe);
+        draft_all(ops, F, vec, cand, chosen, kn, cap, allow_small, outs, stand_in, &fits, probe, fit_table);
         if (probe.per_range[1] || probe.generic) {
             s.error = BSPMM_ETOOBIG;
             return s;
@@ -620,7 +638,7 @@ Schedule make_schedule(const DirOps& ops_in, int F, const Knobs& kn_in)
         keep.tiles_per_block = 1;
     }
     d.reserve((size_t)wgs * 4 + 16);
-    draft_all(ops, F, vec, cand, chosen, kn, cap, allow_small, outs, stand_in, &fits, keep);
+    draft_all(ops, F, vec, cand, chosen, kn, cap, allow_small, outs, stand_in, &fits, keep, fit_table);
 
     // group costs, for ordering and XCD placement
     int ngroups = 0;
