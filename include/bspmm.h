@@ -408,7 +408,11 @@ int bspmm_kernel_info(int32_t kernel, int32_t dynamic_lds_bytes, bspmm_kernel_re
 int bspmm_plan_info(const bspmm_plan* plan, bspmm_info* info);
 
 /* Copy up to `capacity` scheduled items of one direction (0 forward, 1 transposed) into
- * `items`; *count receives the total number.  HOST only. */
+ * `items`; *count receives the total number.  HOST only.  These are the items of the one-launch
+ * schedule, which bspmm_run, bspmm_run_transposed and the one-launch kernel of bspmm_run_gcn
+ * work from; a plan whose bspmm_run_gcn is run by streaming workgroups
+ * (bspmm_info.front_stream) takes from it only the items of the graphs left to the second
+ * launch. */
 int bspmm_plan_items(const bspmm_plan* plan, int32_t transposed, bspmm_item* items,
                      int32_t capacity, int32_t* count);
 
