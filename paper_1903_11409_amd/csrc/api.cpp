@@ -483,6 +483,39 @@ void make_stream_plan(bspmm_plan& p)
         }
         st.list.push_back((int32_t)st.sets.size());
     }
+    // Every list as the kernel will read it: the graphs it takes one at a time first and
+    // inside the room of that mode, every other graph inside the buffers (the kernel's own
+    // tests, which decide where its loads and stores go).  A table that fails is not used.
+    {
+        const int rows_per_pass = kThreads / (fw / 4);
+        const int64_t total = (int64_t)st.tile_words + 2 * st.x_words + 2 * st.csr_words;
+        const int piece = units == 2 ? 16 : fw;
+        bool ok = true;
+        for (int l = 0; l < lists && ok; ++l) {
+            bool piped = false;
+            for (int j = st.list[l]; j < st.list[l + 1] && ok; ++j) {
+                const StreamSet& e = st.sets[j];
+                const int64_t csr = (int64_t)round_up(e.m + 1, 4) + 2 * (int64_t)round_up(e.nnz, 4);
+                const bool big = (int64_t)M * e.kx * fw > st.tile_words || (int64_t)e.kx * nx > st.x_words ||
+                                 csr > st.csr_words || e.m > kStreamPasses * rows_per_pass;
+                ok = e.kx > 0 && e.m > 0;
+                if (big) {
+                    const int64_t chunk = ((total - st.big_csr_words - (int64_t)M * e.kx * piece) / nx) & ~int64_t(15);
+                    ok = ok && !piped && ((units == 2 && fw == 32) || units == 1) && csr <= st.big_csr_words && chunk >= 16;
+                } else {
+                    piped = true;
+                }
+            }
+        }
+        if (!ok) {
+            st = bspmm_plan::Stream();
+            if (single) {
+                p.set_records[0].clear();
+                p.merged_words[0] = 0;
+            }
+            return;
+        }
+    }
     // the other graphs: their items of the one-launch schedule, in its order
     for (size_t j = 0; j < sc.items.size(); ++j) {
         const int op = j < sc.item_op.size() ? sc.item_op[j] : -1;
