@@ -1755,16 +1755,29 @@ bspmm_gcn_stream_kernel(const StreamSet* __restrict__ sets, const int32_t* __res
         bv[u] = bias[(int64_t)ch * S.bias_stride + f0 + 16 * nb + col];
     }
 
-    // rows of X_i and the merged CSR block of a graph -> buffers b
+    // rows of X_i and the merged CSR block of a graph -> buffers b.  A lane's element of a
+    // request is 256 elements (256 / XVEC rows) after its element of the previous one: the row
+    // advances by a multiple of the swizzle period, so the swizzled column is the lane's for good
+    // and only the row term changes between requests.
+    constexpr int kRowsPerRequest = kThreads / XVEC;
+    static_assert(kRowsPerRequest % (SWZ + 1) == 0 || XVEC == 32, "swizzle period");
+    const int x_row0 = tid >> XSH;
+    const int64_t x_lane_off = (int64_t)x_row0 * S.ld_x + (((tid & (XVEC - 1)) ^ (x_row0 & SWZ)) << 2);
     auto request = [&](const StreamSet& st, int b) {
         const int total = st.kx << XSH;
-        const float* xg = x + st.in_row * S.ld_x;
+        const float* xg = x + st.in_row * S.ld_x + x_lane_off;
         float* xd = xbase + b * S.x_words;
         for (int e0 = wave << 6; e0 < total; e0 += kThreads) {
             const int e = e0 + wl;
             if (e < total) {
-                const int r = e >> XSH;
-                const float* gp = xg + (int64_t)r * S.ld_x + (((e & (XVEC - 1)) ^ (r & SWZ)) << 2);
+                const int i = e0 >> 8;                       // which request of this wavefront
+                const float* gp;
+                if (XVEC == 32) {                            // (8 rows a request: the row's swizzle moves)
+                    const int r = e >> XSH;
+                    gp = x + st.in_row * S.ld_x + (int64_t)r * S.ld_x + (((e & (XVEC - 1)) ^ (r & SWZ)) << 2);
+                } else {
+                    gp = xg + (int64_t)(i * kRowsPerRequest) * S.ld_x;
+                }
                 lds_dma16(gp, xd + (e0 << 2));
             }
         }
