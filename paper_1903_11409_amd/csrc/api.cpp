@@ -86,7 +86,7 @@ struct Layout {
     size_t merged[2] = {0, 0};
     // whole layers run by streaming workgroups: graph records, list bounds, and the items of the
     // graphs that stay with the one-launch kernel
-    size_t stream_sets = 0, stream_list = 0, stream_rest = 0;
+    size_t stream_records = 0, stream_merged = 0, stream_sets = 0, stream_list = 0, stream_rest = 0;
     // plans made from COO operands: the CSR arrays built on the device and what the build needs
     size_t coo_records = 0;
     size_t csr_rpt = 0, csr_colids = 0, csr_values = 0;
@@ -132,9 +132,13 @@ struct bspmm_plan {
         std::vector<int32_t> list;
         std::vector<WorkItem> rest;
         int nx16 = 0, units = 0, fw = 0, tiles = 0, lists = 0;
+        std::vector<SetRecord> records;   // one per group of graphs, for the kernel that merges CSR arrays
+        int64_t merged_words = 0;  // words of the groups' merged CSR blocks
+        bool merged_built = false;
+        int graphs = 0;            // graphs in the lists (a list entry is a group of one or more)
         int tile_words = 0, x_words = 0, csr_words = 0;
-        int big_csr_words = 0;     // room for the merged CSR block of a graph taken in halves
-        int big = 0;               // graphs taken in halves
+        int big_csr_words = 0;     // room for the merged CSR block of a graph taken one at a time
+        int big = 0;               // graphs taken one at a time
         int lds_bytes() const { return 4 * (tile_words + 2 * x_words + 2 * csr_words + 64); }
         bool on() const { return !sets.empty(); }
     } stream;
@@ -232,6 +236,8 @@ void describe_sets(bspmm_plan& p, int d)
             r.nz_off[j] = o.nz_off[mem[j]];
             r.nnz[j] = o.nnz[mem[j]];
             r.k[j] = o.k[mem[j]];
+            r.row_off[j] = 0;
+            r.rows[j] = o.m[mem[0]];
             size_t owner = j;
             for (size_t e = 0; e < j; ++e)
                 if (o.in_off[mem[e]] == o.in_off[mem[j]] && o.k[mem[e]] == o.k[mem[j]]) {
@@ -276,15 +282,20 @@ void describe_sets(bspmm_plan& p, int d)
         }
 }
 
-// Whole layers (front_features with BSPMM_ACCUMULATE) in launches of many rounds of workgroups:
-// the plan of the streaming launch.  Every graph is a set of M channel operations with one
-// merged CSR; a workgroup of the streaming kernel holds the weights of its feature tile in
-// registers (M * fw / 16 blocks of 16 columns over four wavefronts: one or two per wavefront)
-// and takes the graphs of its list one after the other.  The launch's LDS is sized for the
-// graphs it takes: those that fit the budget (three workgroups per CU unless the caller fixed
-// lds_bytes), smallest first; the few larger ones keep their items of the one-launch schedule and
-// run in a launch of their own.  Lists are balanced by longest-processing-time-first on the
-// number of 16-row blocks.
+// Layers (bspmm_run_gcn) of two and more workgroups per CU: the plan of the streaming launch.
+// A workgroup of the streaming kernel holds the weights of its feature tile in registers
+// (M * fw / 16 blocks of 16 columns over four wavefronts: one or two per wavefront) and takes
+// the graphs of its list one after the other; what it takes per trip is a *group*: one graph, or
+// several small graphs that lie back to back in X and in Y, which are to the kernel one graph
+// with a block-diagonal matrix (fewer trips, fuller 16-row blocks for the matrix instructions).
+// Every group gets one merged CSR block (row pointers, columns, values back to back), built once
+// per plan by the kernel that merges summed sets: its members are the channel operations of the
+// group's graphs, each with its rows' place in the group and its tile's place in the group's
+// dense tile.  The launch's LDS is sized for the groups that fit the budget (three workgroups per
+// CU unless the caller fixed lds_bytes), smallest first; larger graphs are taken one at a time
+// by the same workgroups where the kernel can, and otherwise keep their items of the one-launch
+// schedule and run in a launch of their own.  Lists are balanced by
+// longest-processing-time-first on the number of 16-row blocks.
 void make_stream_plan(bspmm_plan& p)
 {
     bspmm_plan::Stream& st = p.stream;
@@ -293,12 +304,8 @@ void make_stream_plan(bspmm_plan& p)
     const Knobs& kn = p.knobs;
     const int nx = kn.front, F = p.F;
     if (nx <= 0 || kn.one_front_launch || !sc.fused_sets.empty() || sc.fused_tasks > 0) return;
-    // Plans of single channels (no operations summed: every operation is a graph of its own)
-    // take the same kernel with one channel; their CSR arrays are copied once per plan into
-    // blocks of the same form as the merged ones (row pointers, columns, values back to back),
-    // which is what a workgroup requests in one piece.
+    // (plans of single channels - no operations summed - take the same kernel with one channel)
     const bool single = sc.merged_sets.empty();
-    if (single && !p.set_records[0].empty()) return;
     const int M = single ? 1 : p.front_channels;
     if (!single && !kn.accumulate) return;
     if (nx % 16 != 0 || (M != 1 && M != 2 && M != 4 && M != 8)) return;
@@ -318,77 +325,158 @@ void make_stream_plan(bspmm_plan& p)
     const DirOps& o = p.dir[0];
     // the graphs: sets of channel operations, or the operations themselves
     std::vector<std::vector<int>> single_sets;
-    if (single) {
+    if (single)
         for (int i = 0; i < o.size(); ++i) single_sets.push_back(std::vector<int>(1, i));
-    }
     const std::vector<std::vector<int>>& graphs = single ? single_sets : sc.merged_sets;
-    const size_t n_sets = graphs.size();
+    const size_t n_graphs = graphs.size();
     // a launch of less than two workgroups per CU gains nothing from resident workgroups
     // (measured, four channels, F = 128, n_X = 64 / 32: 64 graphs 9.5 against 9.4 us for the
     // one-launch kernel; 128 graphs 10.5 / 8.2 against 11.9 / 8.2; 256 graphs 14.6 / 10.4
     // against 24.4 / 15.8)
-    // Kernels with one block per wavefront (tiles of 16 columns, no halves for the larger
-    // graphs): 128 graphs at n_X = 128 take 22.9 against 18.1 us, 512 graphs 51 against 63.
-    if ((int64_t)n_sets * tiles < (units == 2 || single ? 2 : 8) * (int64_t)kn.compute_units) return;
-    if (single) {
-        int64_t words = 0;
-        std::vector<SetRecord>& made = p.set_records[0];
-        for (int i = 0; i < o.size(); ++i) {
-            SetRecord r;
-            std::memset(&r, 0, sizeof r);
-            r.members = 1;
-            r.m = o.m[i];
-            r.plain = 1;
-            r.rpt_off[0] = o.rpt_off[i];
-            r.nz_off[0] = o.nz_off[i];
-            r.nnz[0] = o.nnz[i];
-            r.k[0] = o.k[i];
-            r.tile_row[0] = 0;
-            r.merged_rpt_off = words;
-            words += round_up(r.m + 1, 4);
-            r.merged_nz_off = words;
-            words += 2 * (int64_t)round_up(o.nnz[i], 4);
-            made.push_back(r);
-        }
-        p.merged_words[0] = words;
-    }
-    if (p.set_records[0].size() != n_sets || p.merged_words[0] >= (int64_t(1) << 32)) {
-        if (single) {
-            p.set_records[0].clear();
-            p.merged_words[0] = 0;
-        }
-        return;
-    }
+    // Kernels with one block per wavefront and several channels (tiles of 16 columns): 128
+    // graphs at n_X = 128 take 22.9 against 18.1 us, 512 graphs 51 against 63.
+    if ((int64_t)n_graphs * tiles < (units == 2 || single ? 2 : 8) * (int64_t)kn.compute_units) return;
 
-    // the graphs by size; take them while the launch's LDS stays inside the budget
+    // ---- groups: graphs back to back in X and in Y, while the members fit a record, the rows of
+    // X three 16-row blocks (four for single channels) and the rows of Y the gather's passes
     // (three workgroups per CU: a third of the CU's 160 KiB less what the allocation granule
     // takes; 53920 bytes were measured to leave room for two only)
     const int64_t budget_words = (kn.lds_given ? kn.lds_words * 4 : 53248) / 4;
     const int rows_most = kStreamPasses * (kThreads / (fw / 4));
+    // (a group must still go through the buffers: its tile, two buffers of X rows and two of CSR
+    // blocks - about ten words a row each - inside the budget)
+    const int group_rows = (int)std::min<int64_t>(single ? 64 : 48, (budget_words - 64) / ((int64_t)M * fw + 2 * nx + 20));
+    const int group_graphs = kMaxMembers / M;
+    std::vector<int> by_input;
+    for (size_t g = 0; g < n_graphs; ++g) {
+        const int op0 = graphs[g][0];
+        if (o.m[op0] > 0 && o.k[op0] > 0) by_input.push_back((int)g);
+    }
+    std::stable_sort(by_input.begin(), by_input.end(),
+                     [&](int a, int b) { return o.in_off[graphs[a][0]] < o.in_off[graphs[b][0]]; });
+    // How many graphs a group may hold is chosen for the launch: larger groups mean fewer and
+    // longer trips, and a list of two long trips beside lists of one is a launch twice as long as
+    // it need be (1024 single-channel graphs at n_X = 128: 28.6 us in groups of up to eight,
+    // 21.8 us ungrouped; 2048 graphs: 33 against 43 us).  Each size is tried and the one with the
+    // smallest estimate - the larger of "work per list" and "trips of the fullest list x work per
+    // trip", in the units of the balancing below - is kept.
+    auto form_groups = [&](int most) {
+        std::vector<std::vector<int>> out;
+        int64_t kx_sum = 0, m_sum = 0;
+        for (int g : by_input) {
+            const int op0 = graphs[g][0];
+            bool joins = false;
+            if (!out.empty() && (int)out.back().size() < most) {
+                const int last = graphs[out.back().back()][0];
+                joins = o.in_off[op0] == o.in_off[last] + o.k[last] && o.out_off[op0] == o.out_off[last] + o.m[last] &&
+                        kx_sum + o.k[op0] <= group_rows && m_sum + o.m[op0] <= rows_most;
+            }
+            if (!joins) {
+                out.push_back(std::vector<int>());
+                kx_sum = m_sum = 0;
+            }
+            out.back().push_back(g);
+            kx_sum += o.k[op0];
+            m_sum += o.m[op0];
+        }
+        return out;
+    };
+    std::vector<std::vector<int>> groups;
+    {
+        const int64_t cap_lists = std::max<int64_t>(1, 3 * (int64_t)kn.compute_units / tiles);
+        double best = 0;
+        for (int most = 1; most <= group_graphs; ++most) {
+            std::vector<std::vector<int>> cand = form_groups(most);
+            int64_t total = 0;
+            for (const std::vector<int>& grp : cand) {
+                int64_t kx = 0;
+                for (int g : grp) kx += o.k[graphs[g][0]];
+                total += 3 * ((kx + 15) / 16) + 2;
+            }
+            const int64_t lists = std::max<int64_t>(1, std::min<int64_t>((int64_t)cand.size(), cap_lists));
+            const double per_trip = cand.empty() ? 0.0 : (double)total / (double)cand.size();
+            const double estimate = std::max((double)total / (double)lists,
+                                             (double)(((int64_t)cand.size() + lists - 1) / lists) * per_trip);
+            if (most == 1 || estimate <= best) {
+                best = estimate;
+                groups.swap(cand);
+            }
+        }
+    }
+    const size_t n_sets = groups.size();
+    if (n_sets == 0) return;
+    // one record per group for the merging kernel; what the rest of this function needs of a group
+    std::vector<SetRecord>& recs = st.records;
+    std::vector<int64_t> nnz_sum(n_sets, 0);
+    {
+        int64_t words = 0;
+        for (size_t s = 0; s < n_sets; ++s) {
+            SetRecord r;
+            std::memset(&r, 0, sizeof r);
+            int64_t kxt = 0, mt = 0;
+            for (int g : groups[s]) {
+                kxt += o.k[graphs[g][0]];
+                mt += o.m[graphs[g][0]];
+            }
+            int j = 0;
+            int64_t x_at = 0, m_at = 0;
+            for (int g : groups[s]) {
+                const int op0 = graphs[g][0];
+                for (int c = 0; c < M; ++c, ++j) {
+                    const int op = graphs[g][c];
+                    r.rpt_off[j] = o.rpt_off[op];
+                    r.nz_off[j] = o.nz_off[op];
+                    r.nnz[j] = o.nnz[op];
+                    r.k[j] = o.k[op0];
+                    r.tile_row[j] = (int32_t)(c * kxt + x_at);     // channel c's tile, this graph's rows of it
+                    r.row_off[j] = (int32_t)m_at;
+                    r.rows[j] = o.m[op0];
+                    nnz_sum[s] += o.nnz[op];
+                }
+                x_at += o.k[op0];
+                m_at += o.m[op0];
+            }
+            r.members = j;
+            r.m = (int32_t)mt;
+            r.plain = 1;
+            r.merged_rpt_off = words;
+            words += round_up((int)mt + 1, 4);
+            r.merged_nz_off = words;
+            words += 2 * (int64_t)round_up((int)nnz_sum[s], 4);
+            recs.push_back(r);
+        }
+        st.merged_words = words;
+        if (words >= (int64_t(1) << 32)) {
+            st = bspmm_plan::Stream();
+            return;
+        }
+    }
+    auto kx_of = [&](int s) {
+        int64_t k = 0;
+        for (int g : groups[s]) k += o.k[graphs[g][0]];
+        return k;
+    };
+
+    // the groups by size; take them while the launch's LDS stays inside the budget
     std::vector<int> order(n_sets);
     for (size_t i = 0; i < n_sets; ++i) order[i] = (int)i;
-    const std::vector<SetRecord>& recs = p.set_records[0];
-    auto nnz_of = [&](int i) {
-        int64_t n = 0;
-        for (int j = 0; j < recs[i].members; ++j) n += recs[i].nnz[j];
-        return n;
-    };
-    // (X_i has k rows, the same for every channel of a graph; Y_i has m)
+    // (X has kx rows; Y has m)
     auto words_of = [&](int64_t kx, int64_t csr) { return (int64_t)M * kx * fw + 2 * kx * nx + 2 * csr + 64; };
     auto csr_of = [&](int i) {
-        return (int64_t)round_up(recs[i].m + 1, 4) + 2 * (int64_t)round_up((int)nnz_of(i), 4);
+        return (int64_t)round_up(recs[i].m + 1, 4) + 2 * (int64_t)round_up((int)nnz_sum[i], 4);
     };
+    std::vector<int64_t> kxs(n_sets);
+    for (size_t i = 0; i < n_sets; ++i) kxs[i] = kx_of((int)i);
     std::stable_sort(order.begin(), order.end(), [&](int a, int b) {
-        return words_of(recs[a].k[0], csr_of(a)) < words_of(recs[b].k[0], csr_of(b));
+        return words_of(kxs[a], csr_of(a)) < words_of(kxs[b], csr_of(b));
     });
     int64_t kx_cap = 0, csr_cap = 0;
     std::vector<int> mine;
     for (int i : order) {
         const SetRecord& r = recs[i];
-        // (no output rows: nothing to compute; no rows of X_i or more output rows than the
-        // gather's passes hold: left to the one-launch kernel)
-        if (r.m <= 0 || r.k[0] <= 0 || r.m > rows_most) continue;
-        const int64_t kx = std::max<int64_t>(kx_cap, r.k[0]);
+        // (more output rows than the gather's passes hold: not through the buffers)
+        if (r.m > rows_most) continue;
+        const int64_t kx = std::max<int64_t>(kx_cap, kxs[i]);
         const int64_t cw = std::max(csr_cap, csr_of(i));
         if (words_of(kx, cw) > budget_words) continue;    // (a later one may still fit the caps)
         kx_cap = kx;
@@ -396,33 +484,25 @@ void make_stream_plan(bspmm_plan& p)
         mine.push_back(i);
     }
     if (mine.empty()) {
-        if (single) {
-            p.set_records[0].clear();
-            p.merged_words[0] = 0;
-        }
+        st = bspmm_plan::Stream();
         return;
     }
     st.nx16 = nx16, st.units = units, st.fw = fw, st.tiles = tiles;
     st.tile_words = (int)(M * kx_cap * fw);
     st.x_words = (int)(kx_cap * nx);
     st.csr_words = (int)csr_cap;
-    // Larger graphs, kernels with two blocks per wavefront and 32-column tiles: taken in two
-    // halves of 16 columns, the half tile at the start of the same LDS, the CSR block at its end
-    // and at least one 16-row block of X_i between them.
+    // Larger graphs: taken one at a time, their tile at the start of the same LDS (kernels with
+    // two blocks per wavefront: two half tiles of 16 columns, one after the other), the CSR block
+    // at its end and at least one 16-row block of X between them; the X buffers are made larger
+    // than the listed groups need where that is what it takes, up to the budget.
     std::vector<int> halves;
     if ((units == 2 && fw == 32) || units == 1) {
-        // (kernels with one block per wavefront take such a graph in one piece, its tile at full
-        // width: what they gain is the room of the second X buffer and of the prefetch)
         const int piece = units == 2 ? 16 : fw;
-        // (such a graph may use the launch's LDS up to the budget: the X buffers are made
-        // larger than the listed graphs need where that is what it takes)
         const int64_t total = budget_words - 64;
         std::vector<char> is_mine(n_sets, 0);
         for (int i : mine) is_mine[i] = 1;
         auto fits_halves = [&](int i, int64_t csr_room) {
-            const SetRecord& r = recs[i];
-            return r.m > 0 && r.k[0] > 0 && csr_of(i) <= csr_room &&
-                   (int64_t)M * r.k[0] * piece + 16 * nx + csr_room <= total;
+            return csr_of(i) <= csr_room && (int64_t)M * kxs[i] * piece + 16 * nx + csr_room <= total;
         };
         int64_t room = 0;
         for (size_t i = 0; i < n_sets; ++i)
@@ -432,7 +512,7 @@ void make_stream_plan(bspmm_plan& p)
         st.big_csr_words = halves.empty() ? 0 : (int)room;
         st.big = (int)halves.size();
         int64_t need = 0;
-        for (int i : halves) need = std::max(need, (int64_t)M * recs[i].k[0] * piece + 16 * nx + room);
+        for (int i : halves) need = std::max(need, (int64_t)M * kxs[i] * piece + 16 * nx + room);
         const int64_t have = (int64_t)st.tile_words + 2 * st.x_words + 2 * st.csr_words;
         if (need > have) st.x_words += (int)round_up((int)((need - have + 1) / 2), 4);
     }
@@ -440,16 +520,16 @@ void make_stream_plan(bspmm_plan& p)
     // lists: as many workgroups as the chip holds at once, the same lists for every tile
     int per_cu = kn.device_ok ? stream_workgroups_per_cu(nx16, units, st.lds_bytes()) : 0;
     if (per_cu <= 0) per_cu = std::max(1, std::min(3, kMaxLdsBytes / std::max(1, st.lds_bytes())));
-    const int lists = (int)std::max<size_t>(1, std::min<size_t>(mine.size(), (size_t)per_cu * kn.compute_units / tiles));
-    st.lists = lists;
-    // (a graph taken in halves stages its X_i twice and overlaps nothing)
+    // (a graph taken one at a time stages its X twice and overlaps nothing)
     std::vector<char> in_halves(n_sets, 0);
     for (int i : halves) in_halves[i] = 1;
     auto cost = [&](int i) {
-        const int blocks = (recs[i].k[0] + 15) / 16;
+        const int blocks = (int)((kxs[i] + 15) / 16);
         return in_halves[i] ? 8 * blocks + 12 : 3 * blocks + 2;
     };
     mine.insert(mine.end(), halves.begin(), halves.end());
+    const int lists = (int)std::max<size_t>(1, std::min<size_t>(mine.size(), (size_t)per_cu * kn.compute_units / tiles));
+    st.lists = lists;
     std::stable_sort(mine.begin(), mine.end(), [&](int a, int b) { return cost(a) > cost(b); });
     std::vector<std::vector<int>> of_list(lists);
     {
@@ -464,22 +544,23 @@ void make_stream_plan(bspmm_plan& p)
         }
     }
     st.list.push_back(0);
-    std::vector<char> streamed(n_sets, 0);
+    std::vector<char> streamed(n_graphs, 0);
     for (int l = 0; l < lists; ++l) {
-        // the graphs taken in halves first: the kernel takes them before it starts its pipeline
+        // the graphs taken one at a time first: the kernel takes them before it starts its pipeline
         std::stable_partition(of_list[l].begin(), of_list[l].end(), [&](int i) { return in_halves[i] != 0; });
         for (int i : of_list[l]) {
             const SetRecord& r = recs[i];
-            const int op0 = graphs[i][0];
+            const int op0 = graphs[groups[i][0]][0];
             StreamSet e;
             e.in_row = o.in_off[op0];
             e.out_row = o.out_off[op0];
             e.csr_off = (uint32_t)r.merged_rpt_off;
             e.m = r.m;
-            e.kx = r.k[0];
-            e.nnz = (int32_t)nnz_of(i);
+            e.kx = (int32_t)kxs[i];
+            e.nnz = (int32_t)nnz_sum[i];
             st.sets.push_back(e);
-            streamed[i] = 1;
+            for (int g : groups[i]) streamed[g] = 1;
+            st.graphs += (int)groups[i].size();
         }
         st.list.push_back((int32_t)st.sets.size());
     }
@@ -509,10 +590,6 @@ void make_stream_plan(bspmm_plan& p)
         }
         if (!ok) {
             st = bspmm_plan::Stream();
-            if (single) {
-                p.set_records[0].clear();
-                p.merged_words[0] = 0;
-            }
             return;
         }
     }
@@ -770,12 +847,16 @@ int plan_host(bspmm_plan& p, const bspmm_batch* b, int32_t F, const Knobs& kn)
     at = align_up(at + 4);
     for (int d = 0; d < 2; ++d) {
         describe_sets(p, d);
-        if (d == 0) make_stream_plan(p);      // (may add the blocks of single-channel graphs)
         L.sets[d] = at;
         at = align_up(at + p.set_records[d].size() * sizeof(SetRecord));
         L.merged[d] = at;
         at = align_up(at + (size_t)p.merged_words[d] * 4);
     }
+    make_stream_plan(p);
+    L.stream_records = at;
+    at = align_up(at + p.stream.records.size() * sizeof(SetRecord));
+    L.stream_merged = at;
+    at = align_up(at + (size_t)p.stream.merged_words * 4);
     L.stream_sets = at;
     at = align_up(at + p.stream.sets.size() * sizeof(StreamSet));
     L.stream_list = at;
@@ -959,6 +1040,18 @@ void csr_of_direction(const bspmm_plan* p, int d, const int32_t** rpt, const int
         *colids = reinterpret_cast<const int32_t*>(p->ws + p->lay.colids_t);
         *values = reinterpret_cast<const float*>(p->ws + p->lay.values_t);
     }
+}
+
+// The merged CSR blocks of the groups of the streaming launch (once per plan).
+int enqueue_stream_merge(bspmm_plan* p, hipStream_t s)
+{
+    if (p->stream.merged_built || !p->stream.on()) return BSPMM_OK;
+    hipError_t e = launch_merge_sets(reinterpret_cast<const SetRecord*>(p->ws + p->lay.stream_records),
+                                     (int)p->stream.records.size(), p->rpt, p->colids, p->values,
+                                     reinterpret_cast<int32_t*>(p->ws + p->lay.stream_merged), s);
+    if (e != hipSuccess) return hip_fail(e);
+    p->stream.merged_built = !capturing(s);
+    return BSPMM_OK;
 }
 
 // Row blocks of the generic bin in a lean table: the device writes each block's entry range
@@ -1234,6 +1327,9 @@ int upload_plan(bspmm_plan* p, const bspmm_options* options, void* workspace,
             e = hipMemcpyAsync(p->ws + p->lay.sets[d], p->set_records[d].data(),
                                p->set_records[d].size() * sizeof(SetRecord), hipMemcpyHostToDevice, s);
     if (e == hipSuccess && p->stream.on()) {
+        e = hipMemcpyAsync(p->ws + p->lay.stream_records, p->stream.records.data(),
+                           p->stream.records.size() * sizeof(SetRecord), hipMemcpyHostToDevice, s);
+        if (e == hipSuccess)
         e = hipMemcpyAsync(p->ws + p->lay.stream_sets, p->stream.sets.data(),
                            p->stream.sets.size() * sizeof(StreamSet), hipMemcpyHostToDevice, s);
         if (e == hipSuccess)
@@ -1275,6 +1371,7 @@ int upload_plan(bspmm_plan* p, const bspmm_options* options, void* workspace,
     if (e != hipSuccess) return hip_fail(e);
     if (options && (options->flags & BSPMM_BUILD_TRANSPOSE)) {
         int rc = enqueue_merge(p, 0, s);
+        if (rc == BSPMM_OK) rc = enqueue_stream_merge(p, s);
         if (rc == BSPMM_OK && p->transposed_supported) rc = enqueue_build(p, s);
         if (rc == BSPMM_OK && p->transposed_supported) rc = enqueue_merge(p, 1, s);
         if (rc == BSPMM_OK) rc = enqueue_hints(p, 0, s);
@@ -1297,7 +1394,11 @@ int run_gcn(bspmm_plan* p, const float* X, int64_t ldx, const float* W, int64_t 
     if (ldx % 4 || ldw % 4 || ldy % 4 || misaligned(X) || misaligned(W) || misaligned(Y))
         return BSPMM_EINVAL;
     const bool sets = !sc.merged_sets.empty();
-    if (sets || p->stream.on()) {
+    if (p->stream.on()) {
+        const int mrc = enqueue_stream_merge(p, s);
+        if (mrc != BSPMM_OK) return mrc;
+    }
+    if (sets && (!p->stream.on() || !p->stream.rest.empty())) {
         const int mrc = enqueue_merge(p, 0, s);
         if (mrc != BSPMM_OK) return mrc;
     }
@@ -1309,7 +1410,7 @@ int run_gcn(bspmm_plan* p, const float* X, int64_t ldx, const float* W, int64_t 
         StreamParams S;
         S.sets = reinterpret_cast<const StreamSet*>(p->ws + p->lay.stream_sets);
         S.list = reinterpret_cast<const int32_t*>(p->ws + p->lay.stream_list);
-        S.merged = reinterpret_cast<const int32_t*>(p->ws + p->lay.merged[0]);
+        S.merged = reinterpret_cast<const int32_t*>(p->ws + p->lay.stream_merged);
         S.x = X;
         S.w = W;
         S.bias = bias;
@@ -1740,7 +1841,7 @@ int bspmm_plan_info(const bspmm_plan* plan, bspmm_info* info)
     info->transposed_built = plan->transposed_built ? 1 : 0;
     for (int d = 0; d < 2; ++d) info->lean[d] = plan->lean_items[d].empty() ? 0 : 1;
     if (plan->stream.on()) {
-        info->front_stream[0] = (int32_t)plan->stream.sets.size();
+        info->front_stream[0] = plan->stream.graphs;
         info->front_stream[1] = plan->stream.lists * plan->stream.tiles;
         info->front_stream[2] = plan->stream.lds_bytes();
         int32_t left = 0;

@@ -634,8 +634,9 @@ __device__ __forceinline__ void run_fused(const LaunchParams& P, int* sm, int fi
 }
 
 // Merged CSR of one set of summed operations (one workgroup per set, once per plan and
-// direction): row r of the set = row r of member 0, then of member 1, ...; an entry becomes
-// (row of the concatenated dense tiles, value).  Row pointers are clamped to the member's entry
+// direction): row r of the set = row r of member 0, then of member 1, ... (of the members that
+// have such a row: the members of a group of graphs each cover their graph's rows only); an
+// entry becomes (row of the concatenated dense tiles, value).  Row pointers are clamped to the member's entry
 // count and columns outside a member's tile point at its row 0, so malformed input cannot make
 // the product leave its LDS.
 __global__ void __launch_bounds__(kThreads)
@@ -649,7 +650,12 @@ merge_sets_kernel(const SetRecord* __restrict__ sets, const int32_t* __restrict_
     const int m = g.m, members = g.members;
     const int per = (m + kThreads - 1) / kThreads;
     const int r0 = min(m, tid * per), r1 = min(m, r0 + per);
-    auto row_range = [&](int j, int r, int& a, int& b) {
+    // (member j holds the set's rows row_off[j] .. row_off[j] + rows[j]: all of them for summed
+    // sets, its graph's share for a group of graphs)
+    auto row_range = [&](int j, int row, int& a, int& b) {
+        const int r = row - g.row_off[j];
+        a = b = 0;
+        if ((unsigned)r >= (unsigned)g.rows[j]) return;
         const int32_t* rp = rpt + g.rpt_off[j];
         b = min(max(rp[r + 1], 0), g.nnz[j]);
         a = min(max(rp[r], 0), b);

@@ -289,6 +289,9 @@ struct alignas(8) SetRecord {
     int32_t nnz[kMaxMembers];
     int32_t k[kMaxMembers];         // dense-input rows of the members (bound of their columns)
     int32_t tile_row[kMaxMembers];  // first row of member j's dense tile in the concatenation
+    int32_t row_off[kMaxMembers];   // the set's row that is member j's row 0, and member j's rows
+    int32_t rows[kMaxMembers];      // (summed sets: 0 and m for every member; groups of graphs in
+                                    // the streaming launch: each graph's members have their own)
     int32_t members;
     int32_t m;
     int32_t plain;                  // 1: the members read one dense block; the merged arrays are
