@@ -105,10 +105,10 @@ extern "C" {
                                       arrays and no transposed CSR is ever built.  Not checked;
                                       with an asymmetric A_i the result is A_i . dY_i.  Operations
                                       must be square (EINVAL)                                    */
-#define BSPMM_ONE_FRONT_LAUNCH 128u /* whole-layer plans (front_features with BSPMM_ACCUMULATE) of
-                                      many rounds of workgroups normally run as a launch of resident
-                                      workgroups that stream the graphs (see bspmm_run_gcn); this
-                                      flag keeps them on the one-launch path                     */
+#define BSPMM_ONE_FRONT_LAUNCH 128u /* plans with front_features of two and more workgroups per CU
+                                      normally run bspmm_run_gcn as a launch of resident
+                                      workgroups that stream the graphs (see there); this flag
+                                      keeps them on the one-launch path                         */
 #define BSPMM_FLOOR_PROBE      4u  /* measurement aid: same grid, LDS and item fetches, but every
                                       item is emptied, so a run computes and writes nothing      */
 
@@ -208,8 +208,8 @@ typedef struct bspmm_info {
     int32_t lean[2];                         /* 1: every task is one staged workgroup item with a
                                                 power-of-two tile, so runs with 16-byte aligned
                                                 operands launch the lean kernel                */
-    int32_t front_stream[4];                 /* whole-layer plans run by resident workgroups
-                                                that stream the graphs (see bspmm_run_gcn):
+    int32_t front_stream[4];                 /* plans whose bspmm_run_gcn is run by resident
+                                                workgroups that stream the graphs (see there):
                                                 graphs in their lists, workgroups, LDS bytes per
                                                 workgroup, graphs left to a launch of their own;
                                                 all 0 otherwise                                */
@@ -305,15 +305,18 @@ int bspmm_run(bspmm_plan* plan, const float* B, float* C, int64_t ldb, int64_t l
  * under the other (M * n_X rows, channel ch at row ch * n_X) and bias M rows of F floats; the
  * channels of a graph are taken in the order of their operations.
  *
- * Whole layers of two and more (graph, feature tile) pairs per CU (M = 2, 4 or 8
- * channels, n_X = 16, 32, 64 or 128) run as a launch of RESIDENT workgroups instead, three per CU:
- * each keeps the weights of its feature tile in registers for the whole launch and streams the
- * graphs of its list through LDS, the next graph's X_i and merged CSR in flight while the matrix
- * cores work on this one's; graphs too large for a third of a CU's LDS are taken in two halves
- * of 16 columns by the same workgroups (M = 4), or follow in a launch of the one-launch kernel
- * over their items.  bspmm_info.front_stream says what a plan does; BSPMM_ONE_FRONT_LAUNCH keeps
- * a plan on the one-launch path.  With options.lds_bytes the caller fixes the LDS budget of
- * both.
+ * Layers of two and more (graph, feature tile) pairs per CU - single channels, or whole layers
+ * of M = 2, 4 or 8 channels - with n_X = 16, 32, 64 or 128 run as a launch of RESIDENT workgroups
+ * instead, three per CU: each keeps the weights of its feature tile in registers for the whole
+ * launch and streams the graphs of its list through LDS, the next graph's X_i and CSR in flight
+ * while the matrix cores work on this one's.  Small graphs whose blocks lie back to back in X
+ * and in Y are taken several per trip; graphs too large for a third of a CU's LDS are taken one
+ * at a time by the same workgroups (M = 1 or 4), or follow in a launch of the one-launch kernel
+ * over their items.  The first run also enqueues a kernel that copies the CSR arrays into one
+ * block per trip (once per plan, like the merged CSR of summed sets; BSPMM_BUILD_TRANSPOSE
+ * moves it into bspmm_create).  bspmm_info.front_stream says what a plan does;
+ * BSPMM_ONE_FRONT_LAUNCH keeps a plan on the one-launch path.  With options.lds_bytes the caller
+ * fixes the LDS budget of both.
  */
 int bspmm_run_gcn(bspmm_plan* plan, const float* X, int64_t ldx, const float* W, int64_t ldw,
                   const float* bias, float* Y, int64_t ldy, int32_t accumulate, void* stream);
