@@ -1421,8 +1421,9 @@ int run_gcn(bspmm_plan* p, const float* X, int64_t ldx, const float* W, int64_t 
         sh.accumulate = accumulate ? 1 : 0;
         sh.tile_words = st.tile_words, sh.x_words = st.x_words, sh.csr_words = st.csr_words;
         sh.big_csr_words = st.big_csr_words;
-        sh.reserved_[0] = sh.reserved_[1] = sh.reserved_[2] = sh.reserved_[3] = 0;
-        const hipError_t es = launch_bspmm_gcn_stream(S, st.nx16, st.units, st.lists * st.tiles,
+        sh.lists = st.lists;
+        sh.reserved_[0] = sh.reserved_[1] = sh.reserved_[2] = 0;
+        const hipError_t es = launch_bspmm_gcn_stream(S, st.nx16, st.units, (st.lists + 7) / 8 * 8 * st.tiles,
                                                       st.lds_bytes(), s);
         if (es != hipSuccess) return hip_fail(es);
         if (st.rest.empty()) return BSPMM_OK;

@@ -1731,7 +1731,12 @@ bspmm_gcn_stream_kernel(const StreamSet* __restrict__ sets, const int32_t* __res
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), wl = tid & 63;
     const int col = wl & 15, g = wl >> 4;
-    const int tile_idx = blockIdx.x % S.tiles, lp = blockIdx.x / S.tiles;
+    // Workgroups go to the XCDs round robin (index mod 8).  The workgroups of one list - one per
+    // feature tile - read the same rows of X: they sit on one XCD, so that its L2 fetches them once
+    // (list = 8 * (slot / tiles) + xcd, tile = slot % tiles; the grid is padded to whole rounds).
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int tile_idx = slot % S.tiles, lp = (slot / S.tiles) * 8 + xcd;
+    if (lp >= S.lists) return;
     const int f0 = tile_idx * S.fw;
     const int j0 = list[lp], j1 = list[lp + 1];
     if (j0 >= j1) return;

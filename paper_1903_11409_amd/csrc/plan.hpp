@@ -127,8 +127,10 @@ static_assert(sizeof(StreamSet) == 32, "StreamSet must be 32 bytes");
 constexpr int kStreamPasses = 4;   // row passes of the gather a streamed graph may take: the
                                    // results of a graph wait in registers for one loop trip
 
-// Arguments of the streaming kernel.  Workgroup w serves feature tile w % tiles (columns
-// [fw * tile, fw * tile + fw)) and the graphs list[w / tiles] .. list[w / tiles + 1].
+// Arguments of the streaming kernel.  Every list l < lists has one workgroup per feature tile
+// (columns [fw * tile, fw * tile + fw)), which takes the graphs list[l] .. list[l + 1]; the
+// workgroups of a list sit on one XCD (see the kernel for the mapping; the grid is
+// round_up(lists, 8) * tiles).
 // LDS, in words: the dense tile (tile_words), two buffers for rows of X (x_words each), two
 // for merged CSR blocks (csr_words each), 64 words that take the tile rows past a graph's end.
 // (The pointers are kernel arguments of their own, qualified so that the graph records are
@@ -137,7 +139,7 @@ struct StreamShape {
     int64_t ld_x, ld_w, ld_y, bias_stride;
     int32_t tiles, fw, channels, accumulate;
     int32_t tile_words, x_words, csr_words, big_csr_words;
-    int32_t reserved_[4];
+    int32_t lists, reserved_[3];
 };
 struct StreamParams {
     const StreamSet* sets;
