@@ -90,15 +90,22 @@ extern "C" {
                                       packed input: the same block, or blocks that follow each
                                       other in member order without a gap                        */
 #define BSPMM_COO_DIRECT       32u  /* bspmm_create_coo only: no conversion to CSR.  Every run is one
-                                      launch of the kernel of Fig. 3 / Fig. 5(a,b): a group of lanes
-                                      per stored entry, products added with LDS floating-point
-                                      atomics into an output tile kept in LDS, column blocking
-                                      when the tile does not fit.  Cheapest when a batch is
-                                      multiplied once or twice; the order of the additions, and
-                                      with it the last bits of the result, vary from run to run.
-                                      The transposed product needs no build (the index roles
-                                      swap).  Not combined with BSPMM_ACCUMULATE or
-                                      BSPMM_SPLIT_HUB_ROWS (EINVAL)                              */
+                                      launch that works from the index pairs as they are (the
+                                      SparseTensor cases of Fig. 3 / Fig. 5(a,b)).  Where an
+                                      operation's entries fit in LDS the workgroup sorts them by
+                                      row there and sums each row in registers; otherwise a group
+                                      of lanes per stored entry adds products with LDS
+                                      floating-point atomics into an output tile kept in LDS, cut
+                                      into row ranges when the tile does not fit.  Cheapest when a
+                                      batch is multiplied once or twice; the order of the
+                                      additions, and with it the last bits of the result, vary
+                                      from run to run.  The transposed product needs no build (the
+                                      index roles swap).  Not combined with BSPMM_ACCUMULATE or
+                                      BSPMM_SPLIT_HUB_ROWS (EINVAL).  With options.lds_bytes 0 the
+                                      launch takes the smallest of 24, 32, 48 and 64 KiB at which
+                                      every operation is sorted on chip (64 KiB if none), and asks
+                                      for no more than its largest item needs: bspmm_info.lds_bytes
+                                      reports that                                               */
 #define BSPMM_SYMMETRIC        64u  /* the caller asserts that every A_i equals its transpose (e.g. the
                                       symmetric normalisation D^-1/2 (A+I) D^-1/2 of an undirected
                                       graph): bspmm_run_transposed then gathers over the same CSR
@@ -228,7 +235,9 @@ typedef struct bspmm_item {
     int32_t f0;        /* first feature column                                                */
     int32_t fw;        /* number of feature columns                                           */
     int32_t workgroup; /* task index; workgroup (task mod grid size) runs it                  */
-    int32_t slot;      /* lane slot inside the workgroup                                      */
+    int32_t slot;      /* lane slot inside the workgroup; items of a BSPMM_COO_DIRECT plan: what
+                          the item keeps in LDS (1 the dense tile, 2 the entries, 4 the entries
+                          sorted by row and no output tile)                                   */
 } bspmm_item;
 
 /*

@@ -1089,7 +1089,7 @@ int run_direction(bspmm_plan* p, int d, const float* in, float* out, int64_t ld_
         const bool v4 = p->F % 4 == 0 && ld_in % 4 == 0 && ld_out % 4 == 0 &&
                         (reinterpret_cast<uintptr_t>(in) & 15) == 0 &&
                         (reinterpret_cast<uintptr_t>(out) & 15) == 0;
-        hipError_t ce = launch_bspmm_coo(C, (int)cs.items.size(), p->knobs.lds_words * 4, v4, s);
+        hipError_t ce = launch_bspmm_coo(C, (int)cs.items.size(), cs.lds_words * 4, v4, s);
         return ce == hipSuccess ? BSPMM_OK : hip_fail(ce);
     }
     const Schedule& sc = p->sched[d];
@@ -1822,6 +1822,8 @@ int bspmm_plan_info(const bspmm_plan* plan, bspmm_info* info)
     info->batch = plan->batch;
     info->F = plan->F;
     info->lds_bytes = plan->knobs.lds_words * 4;
+    if (plan->coo_direct)      // the direct COO launches ask for their largest item's LDS
+        info->lds_bytes = 4 * std::max(plan->coo_sched[0].lds_words, plan->coo_sched[1].lds_words);
     info->compute_units = plan->knobs.compute_units;
     for (int d = 0; d < 2; ++d) {
         info->tile[d] = plan->sched[d].tile;

@@ -2099,7 +2099,8 @@ bspmm_coo_kernel(const CooLaunchParams P)
     const int stride = round_up(it.fw, 4);
     const int nvec = (it.fw + VEC - 1) / VEC;          // VEC == 4 implies fw % 4 == 0
     const bool st_b = (it.mode & 1) != 0, st_e = (it.mode & 2) != 0;
-    float* bt = tile + it.nrows * stride;
+    const bool sorted = (it.mode & 4) != 0 && st_e;
+    float* bt = sorted ? tile : tile + it.nrows * stride;
     int2* ent = reinterpret_cast<int2*>(bt + (st_b ? it.k * stride : 0));
     float* ev = reinterpret_cast<float*>(ent + it.nnz);
 
@@ -2112,6 +2113,15 @@ bspmm_coo_kernel(const CooLaunchParams P)
     const float* __restrict__ va = P.values + it.nz_off;
     const int sel = P.transposed ? 1 : 0;
     const float* __restrict__ in = P.in + it.in_row_off * P.ld_in + it.f0;
+
+    // Items the host marked so (mode bit 2) sort their entries by output row on chip - count
+    // per row, scan, scatter of (dense row, value) pairs into row order - and then run the row
+    // gather of the CSR kernels over them: no floating-point atomics and no output tile, a
+    // row's sum is kept in registers and stored once.  The pairs take the place of the staged
+    // entries; behind them sit the row counts and the row pointers.
+    int2* sp = ent;
+    int* s_cnt = reinterpret_cast<int*>(sp + it.nnz);
+    int* s_rp = s_cnt + it.nrows + 1;
 
     // ---- staging: every load is issued before anything is waited for
     bool direct = false;
@@ -2144,6 +2154,117 @@ bspmm_coo_kernel(const CooLaunchParams P)
                 }
         }
     }
+    if (sorted) {
+        __shared__ int wave_sum[kThreads / 64];
+        __shared__ int carry;
+        // The first four entries of every lane stay in registers between the count and the
+        // scatter; what lies beyond them is read again.
+        constexpr int KEEP = 4;
+        int kr[KEEP], kc[KEEP];
+        float kv[KEEP];
+        auto entry = [&](int p, int& r, int& c, float& v) {
+            r = id[2 * p + sel] - it.row0;
+            c = id[2 * p + 1 - sel];
+            v = va[p];
+        };
+#pragma unroll
+        for (int u = 0; u < KEEP; ++u) {
+            const int p = tid + u * kThreads;
+            kr[u] = -1;
+            kc[u] = 0;
+            kv[u] = 0.f;
+            if (p < it.nnz) entry(p, kr[u], kc[u], kv[u]);
+        }
+        for (int i = tid; i <= it.nrows; i += kThreads) s_cnt[i] = 0;
+        lds_barrier();
+#pragma unroll
+        for (int u = 0; u < KEEP; ++u) {
+            if (!((unsigned)kr[u] < (unsigned)it.nrows && (unsigned)kc[u] < (unsigned)it.k)) kr[u] = -1;
+            if (kr[u] >= 0) atomicAdd(&s_cnt[kr[u]], 1);
+        }
+        for (int p = tid + KEEP * kThreads; p < it.nnz; p += kThreads) {
+            int r, c;
+            float v;
+            entry(p, r, c, v);
+            if ((unsigned)r < (unsigned)it.nrows && (unsigned)c < (unsigned)it.k) atomicAdd(&s_cnt[r], 1);
+        }
+        if (tid == 0) carry = 0;
+        lds_barrier();
+        // exclusive scan over the rows, 256 at a time (the counts are cleared for the scatter)
+        const int wv = tid >> 6, wlane = tid & 63;
+        for (int base = 0; base < it.nrows; base += kThreads) {
+            const int i = base + tid;
+            const int c = i < it.nrows ? s_cnt[i] : 0;
+            int x = c;
+#pragma unroll
+            for (int off = 1; off < 64; off <<= 1) {
+                const int y = __shfl_up(x, off);
+                if (wlane >= off) x += y;
+            }
+            if (wlane == 63) wave_sum[wv] = x;
+            lds_barrier();
+            int before = carry;
+            for (int q = 0; q < wv; ++q) before += wave_sum[q];
+            if (i < it.nrows) {
+                s_rp[i] = before + x - c;
+                s_cnt[i] = 0;
+            }
+            lds_barrier();
+            if (tid == kThreads - 1) carry = before + x;
+            lds_barrier();
+        }
+        if (tid == 0) s_rp[it.nrows] = carry;
+        // (dense row, value) pairs in row order (inside a row: the order the lanes get there)
+#pragma unroll
+        for (int u = 0; u < KEEP; ++u)
+            if (kr[u] >= 0)
+                sp[s_rp[kr[u]] + atomicAdd(&s_cnt[kr[u]], 1)] =
+                    make_int2(st_b ? kc[u] * stride : kc[u], __float_as_int(kv[u]));
+        for (int p = tid + KEEP * kThreads; p < it.nnz; p += kThreads) {
+            int r, c;
+            float v;
+            entry(p, r, c, v);
+            if ((unsigned)r < (unsigned)it.nrows && (unsigned)c < (unsigned)it.k)
+                sp[s_rp[r] + atomicAdd(&s_cnt[r], 1)] = make_int2(st_b ? c * stride : c, __float_as_int(v));
+        }
+        if (direct) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // direct-to-LDS loads landed
+        __syncthreads();
+        // row gather: one lane group per output row; four entries in flight from LDS, eight
+        // from memory
+        float* outp = P.out + (it.out_row_off + it.row0) * P.ld_out + it.f0;
+        auto gather = [&](auto width) {
+            constexpr int W = decltype(width)::value;
+            for (int rr = grp; rr < it.nrows; rr += G) {
+                const int q0 = s_rp[rr], q1 = s_rp[rr + 1];
+                for (int j = lane; j < nvec; j += L) {
+                    V acc = Vec<VEC>::zero();
+                    for (int q = q0; q < q1; q += W) {
+                        int2 e[W];
+#pragma unroll
+                        for (int u = 0; u < W; ++u) e[u] = sp[min(q + u, q1 - 1)];
+                        V b[W];
+#pragma unroll
+                        for (int u = 0; u < W; ++u)
+                            b[u] = st_b ? load_vec<VEC>(bt + e[u].x + j * VEC)
+                                        : load_vec<VEC>(in + (int64_t)e[u].x * P.ld_in + j * VEC);
+#pragma unroll
+                        for (int u = 0; u < W; ++u) {
+                            const float v = q + u < q1 ? __int_as_float(e[u].y) : 0.f;
+                            float* af = reinterpret_cast<float*>(&acc);
+                            const float* bf = reinterpret_cast<const float*>(&b[u]);
+#pragma unroll
+                            for (int c = 0; c < VEC; ++c) af[c] = fmaf(v, bf[c], af[c]);
+                        }
+                    }
+                    store_out<VEC>(outp + (int64_t)rr * P.ld_out + j * VEC, acc);
+                }
+            }
+        };
+        if (st_b) gather(std::integral_constant<int, 4>{});
+        else gather(std::integral_constant<int, 8>{});
+        return;
+    }
+
     if (st_e) {
         for (int p0 = tid; p0 < it.nnz; p0 += 2 * kThreads) {
             int r[2], c[2];

@@ -153,10 +153,13 @@ struct StreamParams {
 };
 
 // One unit of work of the direct COO kernel: the output rows [row0, row0+nrows) x feature
-// columns [f0, f0+fw) of one operation, accumulated in LDS from ALL of the operation's entries.
+// columns [f0, f0+fw) of one operation, computed from ALL of the operation's entries.
 // LDS, in words, with stride = round_up(fw, 4): output tile nrows*stride, then (mode bit 0)
 // the dense tile k*stride, then (mode bit 1) 2*nnz words of (output offset, input offset)
-// pairs and nnz values.
+// pairs and nnz values.  Mode bit 2 (with bit 1): the entries of the item's rows are sorted by
+// output row into LDS as (input offset, value) pairs (2*nnz words) and the rows summed in
+// registers - no output tile; behind the pairs sit the row counts and the row pointers
+// (nrows + 1 words each).
 struct alignas(16) CooItem {
     int64_t nz_off;       // entry offset of the operation (its index pairs start at 2*nz_off)
     int64_t in_row_off;   // first row of the dense input block
@@ -169,7 +172,8 @@ struct alignas(16) CooItem {
     int32_t fw;
     int32_t op;
     int32_t mode;         // bit 0: the dense tile (k rows) is staged in LDS behind the output
-                          // tile; bit 1: the entries are staged in LDS behind that
+                          // tile; bit 1: the entries are staged in LDS behind that; bit 2: the
+                          // entries are sorted by row into LDS, no output tile
     int32_t pad_[2];
 };
 static_assert(sizeof(CooItem) == 64, "CooItem must be 64 bytes");
@@ -204,6 +208,8 @@ BSPMM_HD inline int round_up(int x, int a) { return (x + a - 1) / a * a; }
 BSPMM_HD inline int64_t coo_lds_words(int nrows, int k, int nnz, int fw, int mode)
 {
     const int64_t stride = round_up(fw, 4);
+    if (mode & 4)   // entries sorted by row in LDS, sums in registers: no output tile
+        return ((mode & 1) ? (int64_t)k * stride : 0) + 2 * (int64_t)nnz + 2 * (int64_t)nrows + 4;
     return (int64_t)nrows * stride + ((mode & 1) ? (int64_t)k * stride : 0) +
            ((mode & 2) ? 3 * (int64_t)nnz + 1 : 0);
 }

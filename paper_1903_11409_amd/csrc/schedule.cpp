@@ -893,6 +893,8 @@ Schedule make_schedule(const DirOps& ops_in, int F, const Knobs& kn_in)
 // enough workgroups.
 namespace {
 
+constexpr int kCooSortedRows = 128;   // rows of an item that sorts its entries and reads dense rows from memory
+
 struct CooChoice {
     int fw;      // tile width of this operation
     int nr;      // rows per item
@@ -903,6 +905,20 @@ CooChoice coo_choice(const DirOps& o, int i, int F, size_t first, const std::vec
                      const Knobs& kn)
 {
     const int64_t W = kn.lds_words;
+    // entries sorted by row on chip and the rows summed in registers (no output tile, no
+    // atomics): with the dense tile beside them at the widest tile that fits, else with the
+    // dense rows read from memory at the batch-wide tile
+    for (size_t c = first; c < cand.size(); ++c) {
+        const int fw = std::min(cand[c], F);
+        if (coo_lds_words(o.m[i], o.k[i], o.nnz[i], fw, 7) <= W) return {fw, o.m[i], 7};
+    }
+    {
+        // the dense rows come from memory entry by entry: narrow tiles and short row ranges, so
+        // that a workgroup has many rows in flight and few to go through one after another
+        const int fw = std::min(cand.back(), F);
+        const int nr = std::min(o.m[i], kCooSortedRows);
+        if (coo_lds_words(nr, o.k[i], o.nnz[i], fw, 6) <= W) return {fw, nr, 6};
+    }
     for (size_t c = first; c < cand.size(); ++c) {
         const int fw = std::min(cand[c], F);
         if (coo_lds_words(o.m[i], o.k[i], o.nnz[i], fw, 3) <= W) return {fw, o.m[i], 3};
@@ -917,7 +933,32 @@ CooChoice coo_choice(const DirOps& o, int i, int F, size_t first, const std::vec
 
 }  // namespace
 
-CooSchedule make_coo_schedule(const DirOps& ops, int F, const Knobs& kn_in)
+namespace {
+CooSchedule coo_schedule_at(const DirOps& ops, int F, const Knobs& kn_in);
+}
+
+// Without a budget from the caller the launch gets the smallest of a few LDS sizes at which
+// every operation is sorted on chip (or has its entries and both tiles there): an operation that
+// falls through to the row-range forms goes over all of its entries once per range and holds the
+// whole launch up.
+CooSchedule make_coo_schedule(const DirOps& ops, int F, const Knobs& kn)
+{
+    if (kn.lds_given) return coo_schedule_at(ops, F, kn);
+    CooSchedule s;
+    for (int words : {6144, 8192, 12288, 16384}) {
+        Knobs k2 = kn;
+        k2.lds_words = words;
+        s = coo_schedule_at(ops, F, k2);
+        bool ranges = false;
+        for (const CooItem& it : s.items) ranges = ranges || !(it.mode & 4) && it.mode != 3;
+        if (!ranges) break;
+    }
+    return s;
+}
+
+namespace {
+
+CooSchedule coo_schedule_at(const DirOps& ops, int F, const Knobs& kn_in)
 {
     CooSchedule s;
     Knobs kn = kn_in;
@@ -984,8 +1025,12 @@ CooSchedule make_coo_schedule(const DirOps& ops, int F, const Knobs& kn_in)
         v.slot = it.mode;
         s.items.push_back(it);
         s.view.push_back(v);
+        s.lds_words = (int)std::max<int64_t>(s.lds_words, coo_lds_words(it.nrows, it.k, it.nnz, it.fw, it.mode));
     }
+    s.lds_words = std::min(kn.lds_words, round_up(s.lds_words, 64));
     return s;
 }
+
+}  // namespace
 
 }  // namespace bspmm

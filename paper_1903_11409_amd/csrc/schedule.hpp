@@ -78,6 +78,7 @@ struct CooSchedule {
     std::vector<bspmm_item> view;
     int tile = 0;
     int error = 0;
+    int lds_words = 0;     // what the launch asks for: the largest item's
 };
 
 int workgroups_per_cu(int front_features);

@@ -411,15 +411,20 @@ def _check_direct_coo_schedule(b, F, kw, transposed):
             assert it.nrows > 0 and it.fw > 0 and it.fw <= 256
             assert F % 4 != 0 or (it.f0 % 4 == 0 and it.fw % 4 == 0)
             # the output tile of the item, and whatever else it stages (slot = mode bits: 1 the
-            # dense tile, 2 the entries), sit in LDS together
+            # dense tile, 2 the entries), sit in LDS together; mode bit 4: the entries are
+            # sorted by row on chip (pairs of dense row and value, row counts and row pointers)
+            # and there is no output tile
             k_of = b.rows if transposed else b.cols
             stride = (it.fw + 3) // 4 * 4
-            words = it.nrows * stride
-            assert it.slot in (0, 2, 3)
+            assert it.slot in (0, 2, 3, 6, 7)
+            if it.slot & 4:
+                words = 2 * int(b.nnz[it.op]) + 2 * it.nrows + 4
+            else:
+                words = it.nrows * stride
+                if it.slot & 2:
+                    words += 3 * int(b.nnz[it.op]) + 1
             if it.slot & 1:
                 words += int(k_of[it.op]) * stride
-            if it.slot & 2:
-                words += 3 * int(b.nnz[it.op]) + 1
             assert words * 4 <= info.lds_bytes
             cover[it.op][it.row0:it.row0 + it.nrows, it.f0:it.f0 + it.fw] += 1
         for c in cover:
