@@ -295,7 +295,7 @@ void describe_sets(bspmm_plan& p, int d)
 // CU unless the caller fixed lds_bytes), smallest first; larger graphs are taken one at a time
 // by the same workgroups where the kernel can, and otherwise keep their items of the one-launch
 // schedule and run in a launch of their own.  Lists are balanced by
-// longest-processing-time-first on the number of 16-row blocks.
+// longest-processing-time-first on an estimate of a trip's cycles.
 void make_stream_plan(bspmm_plan& p)
 {
     bspmm_plan::Stream& st = p.stream;
@@ -359,7 +359,7 @@ void make_stream_plan(bspmm_plan& p)
     // it need be (1024 single-channel graphs at n_X = 128: 28.6 us in groups of up to eight,
     // 21.8 us ungrouped; 2048 graphs: 33 against 43 us).  Each size is tried and the one with the
     // smallest estimate - the larger of "work per list" and "trips of the fullest list x work per
-    // trip", in the units of the balancing below - is kept.
+    // trip", a trip counted as two units plus three per 16-row block - is kept.
     auto form_groups = [&](int most) {
         std::vector<std::vector<int>> out;
         int64_t kx_sum = 0, m_sum = 0;
@@ -523,9 +523,22 @@ void make_stream_plan(bspmm_plan& p)
     // (a graph taken one at a time stages its X twice and overlaps nothing)
     std::vector<char> in_halves(n_sets, 0);
     for (int i : halves) in_halves[i] = 1;
+    // What a trip costs, in units of about a hundred cycles, fitted to per-trip clocks of whole
+    // layers (four channels, n_X = 64, tiles of 32 columns, three workgroups per CU: trips of one,
+    // two and three 16-row blocks took 5200, 7400 and 15000 cycles): a fixed part, the matrix
+    // instructions of the wavefront (16-row blocks x n_X / 16 x blocks per wavefront), and every
+    // pass of the gather after the first, which starts from the row pointers in LDS instead of
+    // from registers.
+    const int rows_per_pass_c = kThreads / (fw / 4);
+    auto trip_cost = [&](int64_t blocks, int64_t m) {
+        const int64_t passes = std::max<int64_t>(1, (m + rows_per_pass_c - 1) / rows_per_pass_c);
+        return 20 + 3 * blocks * nx16 * units + 45 * (passes - 1);
+    };
+    // (a graph taken one at a time pays for its chunks and pieces without overlap: four to
+    // eight blocks took 23000 to 41000 cycles in the same launches)
     auto cost = [&](int i) {
-        const int blocks = (int)((kxs[i] + 15) / 16);
-        return in_halves[i] ? 8 * blocks + 12 : 3 * blocks + 2;
+        const int64_t blocks = (kxs[i] + 15) / 16;
+        return in_halves[i] ? 90 + 35 * blocks * nx16 * units / 8 : trip_cost(blocks, recs[i].m);
     };
     mine.insert(mine.end(), halves.begin(), halves.end());
     const int lists = (int)std::max<size_t>(1, std::min<size_t>(mine.size(), (size_t)per_cu * kn.compute_units / tiles));

@@ -950,7 +950,7 @@ CooSchedule make_coo_schedule(const DirOps& ops, int F, const Knobs& kn)
         k2.lds_words = words;
         s = coo_schedule_at(ops, F, k2);
         bool ranges = false;
-        for (const CooItem& it : s.items) ranges = ranges || !(it.mode & 4) && it.mode != 3;
+        for (const CooItem& it : s.items) ranges = ranges || (!(it.mode & 4) && it.mode != 3);
         if (!ranges) break;
     }
     return s;

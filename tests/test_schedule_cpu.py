@@ -434,6 +434,28 @@ def _check_direct_coo_schedule(b, F, kw, transposed):
         K.bspmm_destroy(h)
 
 
+def test_direct_coo_sorts_on_chip_where_the_entries_fit():
+    """Without a caller's budget the launch takes the smallest LDS size at which every operation's
+    entries are sorted on chip (slot bit 4); a small budget from the caller is kept and the
+    operations that do not fit fall back to the output tile with row ranges."""
+    for b, lds_most in ((W.config2_molecule(), 24576), (W.config5_skewed(), 32768)):
+        h = K.dry_plan(b, b.F, coo=True, flags=K.COO_DIRECT)
+        try:
+            info = K.bspmm_plan_info(h)
+            assert all(it.slot & 4 for it in K.bspmm_plan_items(h, False))
+            assert all(it.slot & 4 for it in K.bspmm_plan_items(h, True))
+            assert 0 < info.lds_bytes <= lds_most
+        finally:
+            K.bspmm_destroy(h)
+    b = W.config5_skewed()
+    h = K.dry_plan(b, b.F, coo=True, flags=K.COO_DIRECT, lds_bytes=8192)
+    try:
+        slots = {it.slot for it in K.bspmm_plan_items(h, False)}
+        assert slots & {0, 2} and K.bspmm_plan_info(h).lds_bytes <= 8192
+    finally:
+        K.bspmm_destroy(h)
+
+
 def test_direct_coo_rejects_what_it_cannot_do():
     b = W.config3_multichannel(graphs=4, F=32, accumulate=True)
     hc = K.HostCooBatch(b.rows, b.cols, b.nnz, b.nz_off, b.b_row_off, b.c_row_off)
