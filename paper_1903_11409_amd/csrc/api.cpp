@@ -523,22 +523,26 @@ void make_stream_plan(bspmm_plan& p)
     // (a graph taken one at a time stages its X twice and overlaps nothing)
     std::vector<char> in_halves(n_sets, 0);
     for (int i : halves) in_halves[i] = 1;
-    // What a trip costs, in units of about a hundred cycles, fitted to per-trip clocks of whole
-    // layers (four channels, n_X = 64, tiles of 32 columns, three workgroups per CU: trips of one,
-    // two and three 16-row blocks took 5200, 7400 and 15000 cycles): a fixed part, the matrix
-    // instructions of the wavefront (16-row blocks x n_X / 16 x blocks per wavefront), and every
-    // pass of the gather after the first, which starts from the row pointers in LDS instead of
-    // from registers.
+    // What a trip costs, in units of about a hundred cycles, fitted to per-trip clocks of three
+    // launches of 2048 graphs with three workgroups per CU (four channels at n_X = 64: trips of
+    // one, two and three 16-row blocks took 5200, 7400 and 15000 cycles; one channel at
+    // n_X = 32: 3500 to 11500 for one to four blocks; at n_X = 128: 4900 to 18600 for one to
+    // three): a fixed part, the matrix instructions of the wavefront (16-row blocks x n_X / 16
+    // x blocks per wavefront), and every pass of the gather after the first, which starts from
+    // the row pointers in LDS instead of from registers and costs the more the longer the
+    // matrix phases of the workgroups beside it hold the SIMDs.
     const int rows_per_pass_c = kThreads / (fw / 4);
+    const int64_t sw = (int64_t)nx16 * units;      // matrix instructions per 16-row block, in fours
     auto trip_cost = [&](int64_t blocks, int64_t m) {
         const int64_t passes = std::max<int64_t>(1, (m + rows_per_pass_c - 1) / rows_per_pass_c);
-        return 20 + 3 * blocks * nx16 * units + 45 * (passes - 1);
+        return 20 + 3 * blocks * sw + (20 + 25 * sw / 8) * (passes - 1);
     };
-    // (a graph taken one at a time pays for its chunks and pieces without overlap: four to
-    // eight blocks took 23000 to 41000 cycles in the same launches)
+    // (a graph taken one at a time pays for its chunks and pieces without overlap: in the same
+    // launches four to eight blocks took 23000 to 41000 cycles with four channels, five to nine
+    // blocks 16000 to 36000 with one channel at n_X = 32, three to nine 19000 to 51000 at 128)
     auto cost = [&](int i) {
         const int64_t blocks = (kxs[i] + 15) / 16;
-        return in_halves[i] ? 90 + 35 * blocks * nx16 * units / 8 : trip_cost(blocks, recs[i].m);
+        return in_halves[i] ? std::max<int64_t>(20, 45 * blocks + 10 * sw - 25) : trip_cost(blocks, recs[i].m);
     };
     mine.insert(mine.end(), halves.begin(), halves.end());
     const int lists = (int)std::max<size_t>(1, std::min<size_t>(mine.size(), (size_t)per_cu * kn.compute_units / tiles));
