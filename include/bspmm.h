@@ -170,7 +170,11 @@ typedef struct bspmm_options {
     int32_t  force_bin;        /* 0 = automatic; 1+b forces bin b for every op that fits it    */
     int32_t  lds_bytes;        /* LDS per workgroup; <= 160 KiB (all of a CU's).  0 = 24 KiB,
                                   and 80 KiB, then 160 KiB, are tried before a batch whose
-                                  summed operations need more is refused with ETOOBIG          */
+                                  summed operations need more is refused with ETOOBIG; 52 KiB
+                                  (tiles twice as wide) for F >= 512 when the launch moves
+                                  more than 28 MB in more than one round of workgroups and
+                                  needs no more rounds that way.  bspmm_info.lds_bytes says
+                                  what was taken                                              */
     int32_t  min_tile;         /* narrowest feature tile in floats, 0 = default (32)           */
     int32_t  max_tile;         /* widest feature tile in floats, 0 = default (256), <= 256     */
     int32_t  target_workgroups;/* split tiles until the launch has this many, 0 = 4 per CU    */

@@ -982,6 +982,27 @@ int plan_with_budget(bspmm_plan& p, const Batch* b, int32_t F, const bspmm_optio
     }
     kn.need_both = open && !front;
     int rc = plan_fn(p, b, F, kn);
+    if (rc == BSPMM_OK && open && !front && !p.coo_direct && F >= 512 && p.effective_bytes[0] > 28000000 &&
+        p.sched[0].grid > kn.capacity_wgs) {
+        // Wide feature matrices moved by a launch of more than one round of workgroups, which
+        // runs at the rate of the memory system: with 24 KiB the larger operations get tiles of
+        // 32 columns (row segments of 128 bytes), each staging the operation's CSR again.  A
+        // budget of a third of a CU's LDS doubles the tiles; it is kept when the launch then
+        // takes no more rounds than before, since three workgroups per CU are resident instead of
+        // six (measured, 128 graphs of 20-100 nodes: F = 1024, 1.41 rounds either way, 14.85 ->
+        // 14.19 us, 4.34 -> 4.54 TB/s; F = 512, 0.71 -> 1.33 rounds, 7.46 -> 8.79 us: not taken).
+        bspmm_options o = options ? *options : bspmm_options{};
+        o.lds_bytes = 53248;
+        Knobs wide = knobs_for(&o, !dry);
+        if (dry) wide.capacity_wgs = 3 * wide.compute_units;
+        wide.need_both = kn.need_both;
+        wide.lds_given = false;
+        bspmm_plan q;
+        if (plan_fn(q, b, F, wide) == BSPMM_OK &&
+            (int64_t)q.sched[0].grid * kn.capacity_wgs <= (int64_t)p.sched[0].grid * wide.capacity_wgs)
+            p = std::move(q);
+        return BSPMM_OK;
+    }
     if (rc != BSPMM_ETOOBIG || !open) return rc;
     static const struct { int bytes; bool both; } attempts[] = {
         {kHalfLdsBytes, true}, {kMaxLdsBytes, true}, {0, false}, {kHalfLdsBytes, false}, {kMaxLdsBytes, false}};

@@ -434,6 +434,24 @@ def _check_direct_coo_schedule(b, F, kw, transposed):
         K.bspmm_destroy(h)
 
 
+def test_wide_traffic_bound_launches_take_a_third_of_the_lds():
+    """F >= 512, more than 28 MB moved, more than one round of workgroups: the plan takes 52 KiB
+    per workgroup (tiles twice as wide) when the launch then needs no more rounds than with
+    24 KiB; a budget from the caller is kept as given."""
+    def info_of(b, **kw):
+        h = K.dry_plan(b, b.F, **kw)
+        try:
+            return K.bspmm_plan_info(h)
+        finally:
+            K.bspmm_destroy(h)
+    wide = info_of(W.config4_wide(F=1024))
+    assert wide.lds_bytes == 53248 and wide.workgroups[0] * 6 <= 2168 * 3 and list(wide.lean) == [1, 1]
+    assert info_of(W.config4_wide(F=1024), lds_bytes=24576).lds_bytes == 24576
+    assert info_of(W.config4_wide(F=512)).lds_bytes == 24576          # one round at 24 KiB, two at 52
+    assert info_of(W.config2_molecule(F=1024, graphs=512)).lds_bytes == 24576   # small graphs: wide tiles already
+    assert info_of(W.config5_skewed()).lds_bytes == 24576             # F = 256
+
+
 def test_direct_coo_sorts_on_chip_where_the_entries_fit():
     """Without a caller's budget the launch takes the smallest LDS size at which every operation's
     entries are sorted on chip (slot bit 4); a small budget from the caller is kept and the
