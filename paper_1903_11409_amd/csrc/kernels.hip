@@ -2079,14 +2079,20 @@ bspmm_gcn_stream_kernel(const StreamSet* __restrict__ sets, const int32_t* __res
 
 // ---------------------------------------------------------------------------------------
 // Direct product for COO / SparseTensor operands (Fig. 3 with the output staged on chip as in
-// Fig. 5(a,b)): the item's output tile lives in LDS; a group of L lanes takes one stored entry
-// at a time (L = the tile's vectors per row rounded up to a power of two, at most 64), reads
-// the dense row it names and adds value * row into the tile with LDS floating-point atomics;
-// the tile is then streamed out.  Entries outside the item's row range (or outside the
-// matrix) are skipped.  Four entries per group are in flight at once.
-// What the paper reads from global memory entry by entry - the index pairs, the values and
-// the dense rows - is first copied to LDS in bulk where the scheduler found room (item.mode):
-// a workgroup then pays one round trip to memory instead of one per entry.
+// Fig. 5(a,b)), in two forms per item (item.mode):
+//  * sorted: the workgroup counts the operation's entries per output row (integer LDS atomics),
+//    scans the counts, scatters (dense row, value) pairs into row order in LDS and sums each row
+//    in registers, a lane group per row: no floating-point atomics and no output tile.  The
+//    dense tile sits in LDS beside the pairs where the scheduler found room; otherwise the dense
+//    rows are read from memory, eight in flight per group.
+//  * the paper's form: the item's output tile lives in LDS; a group of L lanes takes one stored
+//    entry at a time (L = the tile's vectors per row rounded up to a power of two, at most 64),
+//    reads the dense row it names and adds value * row into the tile with LDS floating-point
+//    atomics; the tile is then streamed out.  Four entries per group are in flight at once.
+//    What the paper reads from global memory entry by entry - the index pairs, the values and
+//    the dense rows - is first copied to LDS in bulk where the scheduler found room: a
+//    workgroup then pays one round trip to memory instead of one per entry.
+// Entries outside the item's row range (or outside the matrix) are skipped.
 // ---------------------------------------------------------------------------------------
 template <int VEC>
 __global__ void __launch_bounds__(kThreads)
