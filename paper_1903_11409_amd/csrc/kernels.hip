@@ -6,9 +6,14 @@
 //                   output row a group of lanes that accumulates its stored entries in
 //                   registers and writes the row once (the row-wise, atomic-free product of
 //                   Fig. 4, batched as in Sec. IV-C, with the column blocking of Fig. 5(d)).
+// bspmm_lean_kernel the same product for launches made only of whole-workgroup items on the
+//                   float4 path: items carry what the general kernel derives, the dense tile
+//                   goes global -> LDS directly.
 // bspmm_gcn_kernel  the fused front of the graph-convolution layer (Fig. 7): the dense tile is
 //                   made on the matrix cores from the layer input and the weights, for one
 //                   channel or for all channels of the layer, and gathered as above.
+// bspmm_gcn_stream_kernel  the same layer for large batches: resident workgroups with the
+//                   weights in registers stream the graphs of host-made lists through LDS.
 // bspmm_coo_kernel  the direct product for COO / SparseTensor operands (Fig. 3, Fig. 5(a,b)).
 // build_sorted      stable CSR -> transposed CSR of every operation (counting sort by column),
 //                   and COO / SparseTensor -> CSR (the same sort by row).
