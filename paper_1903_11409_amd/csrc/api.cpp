@@ -132,6 +132,7 @@ struct bspmm_plan {
         std::vector<int32_t> list;
         std::vector<WorkItem> rest;
         int nx16 = 0, units = 0, fw = 0, tiles = 0, lists = 0;
+        bool compact = false;            // the groups bring lists of the tile rows in use
         std::vector<SetRecord> records;   // one per group of graphs, for the kernel that merges CSR arrays
         int64_t merged_words = 0;  // words of the groups' merged CSR blocks
         bool merged_built = false;
@@ -405,6 +406,9 @@ void make_stream_plan(bspmm_plan& p)
     }
     const size_t n_sets = groups.size();
     if (n_sets == 0) return;
+    // Layers of several channels in which a wavefront's blocks belong to one channel: the rows of
+    // a channel's dense tile that none of its entries names are not made (see merge_sets_kernel).
+    const bool compact_on = M >= 2 && (units == 1 || fw >= 32);
     // one record per group for the merging kernel; what the rest of this function needs of a group
     std::vector<SetRecord>& recs = st.records;
     std::vector<int64_t> nnz_sum(n_sets, 0);
@@ -442,7 +446,7 @@ void make_stream_plan(bspmm_plan& p)
             r.merged_rpt_off = words;
             words += round_up((int)mt + 1, 4);
             r.merged_nz_off = words;
-            words += 2 * (int64_t)round_up((int)nnz_sum[s], 4);
+            words += 2 * (int64_t)round_up((int)nnz_sum[s], 4) + (compact_on ? compact_words(M, (int)kxt) : 0);
             recs.push_back(r);
         }
         st.merged_words = words;
@@ -467,17 +471,21 @@ void make_stream_plan(bspmm_plan& p)
     };
     std::vector<int64_t> kxs(n_sets);
     for (size_t i = 0; i < n_sets; ++i) kxs[i] = kx_of((int)i);
+    // (a group that goes through the buffers brings its lists of rows in use)
+    auto csr_piped = [&](int i) {
+        return csr_of(i) + (compact_on && (int64_t)M * kxs[i] <= kCompactRows ? compact_words(M, (int)kxs[i]) : 0);
+    };
     std::stable_sort(order.begin(), order.end(), [&](int a, int b) {
-        return words_of(kxs[a], csr_of(a)) < words_of(kxs[b], csr_of(b));
+        return words_of(kxs[a], csr_piped(a)) < words_of(kxs[b], csr_piped(b));
     });
     int64_t kx_cap = 0, csr_cap = 0;
     std::vector<int> mine;
     for (int i : order) {
         const SetRecord& r = recs[i];
         // (more output rows than the gather's passes hold: not through the buffers)
-        if (r.m > rows_most) continue;
+        if (r.m > rows_most || (compact_on && (int64_t)M * kxs[i] > kCompactRows)) continue;
         const int64_t kx = std::max<int64_t>(kx_cap, kxs[i]);
-        const int64_t cw = std::max(csr_cap, csr_of(i));
+        const int64_t cw = std::max(csr_cap, csr_piped(i));
         if (words_of(kx, cw) > budget_words) continue;    // (a later one may still fit the caps)
         kx_cap = kx;
         csr_cap = cw;
@@ -488,6 +496,9 @@ void make_stream_plan(bspmm_plan& p)
         return;
     }
     st.nx16 = nx16, st.units = units, st.fw = fw, st.tiles = tiles;
+    st.compact = compact_on;
+    if (compact_on)
+        for (int i : mine) recs[i].compact = M | ((int32_t)kxs[i] << 8);
     st.tile_words = (int)(M * kx_cap * fw);
     st.x_words = (int)(kx_cap * nx);
     st.csr_words = (int)csr_cap;
@@ -594,8 +605,10 @@ void make_stream_plan(bspmm_plan& p)
             for (int j = st.list[l]; j < st.list[l + 1] && ok; ++j) {
                 const StreamSet& e = st.sets[j];
                 const int64_t csr = (int64_t)round_up(e.m + 1, 4) + 2 * (int64_t)round_up(e.nnz, 4);
+                const int64_t lists_words = st.compact ? compact_words(M, e.kx) : 0;
                 const bool big = (int64_t)M * e.kx * fw > st.tile_words || (int64_t)e.kx * nx > st.x_words ||
-                                 csr > st.csr_words || e.m > kStreamPasses * rows_per_pass;
+                                 csr + lists_words > st.csr_words || e.m > kStreamPasses * rows_per_pass ||
+                                 (st.compact && (int64_t)M * e.kx > kCompactRows);
                 ok = e.kx > 0 && e.m > 0;
                 if (big) {
                     const int64_t chunk = ((total - st.big_csr_words - (int64_t)M * e.kx * piece) / nx) & ~int64_t(15);
@@ -1460,7 +1473,8 @@ int run_gcn(bspmm_plan* p, const float* X, int64_t ldx, const float* W, int64_t 
         sh.tile_words = st.tile_words, sh.x_words = st.x_words, sh.csr_words = st.csr_words;
         sh.big_csr_words = st.big_csr_words;
         sh.lists = st.lists;
-        sh.reserved_[0] = sh.reserved_[1] = sh.reserved_[2] = 0;
+        sh.compact = st.compact ? 1 : 0;
+        sh.reserved_[0] = sh.reserved_[1] = 0;
         const hipError_t es = launch_bspmm_gcn_stream(S, st.nx16, st.units, (st.lists + 7) / 8 * 8 * st.tiles,
                                                       st.lds_bytes(), s);
         if (es != hipSuccess) return hip_fail(es);

@@ -709,6 +709,66 @@ merge_sets_kernel(const SetRecord* __restrict__ sets, const int32_t* __restrict_
         }
     }
     if (tid == kThreads - 1) mr[m] = pos;
+
+    // Rows in use (groups of the streaming launch with several channels): a row of a channel's
+    // dense tile that no entry of that channel names is never read, so it need not be made.
+    // Per channel the rows that are named are listed in ascending order, the columns of the
+    // merged CSR are renumbered to the position in the channels' lists laid end to end, and
+    // behind the values go: the channels' counts, the first tile row of each channel, and the
+    // lists (kxt words per channel, kxt = rows of the group's layer input).
+    const int chans = g.compact & 0xff, kxt = g.compact >> 8;
+    if (chans == 0) return;
+    __shared__ int rank[kCompactRows];         // 1 + position of a row in its channel's list, 0: not in use
+    __shared__ int base[kMaxMembers + 1];
+    const int tile_rows = chans * kxt;          // (the host compacts only sets with tile_rows <= kCompactRows)
+    for (int i = tid; i < tile_rows; i += kThreads) rank[i] = 0;
+    __syncthreads();
+    {
+        int q = partial[tid] - sum;
+        for (int r = r0; r < r1; ++r)
+            for (int j = 0; j < members; ++j) {
+                int a, b;
+                row_range(j, r, a, b);
+                for (int p = a; p < b; ++p) rank[pc[q++]] = 1;
+            }
+    }
+    __syncthreads();
+    int32_t* cnt = reinterpret_cast<int32_t*>(pv + round_up(nnz_sum, 4));
+    int32_t* first_row = cnt + round_up(chans, 4);
+    int32_t* lists = first_row + round_up(chans, 4);
+    if (tid < chans) {
+        int n = 0;
+        for (int j = 0; j < kxt; ++j)
+            if (rank[tid * kxt + j]) {
+                lists[tid * kxt + n] = j;
+                rank[tid * kxt + j] = ++n;
+            }
+        cnt[tid] = n;
+        base[tid] = n;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        int at = 0;
+        for (int c = 0; c < chans; ++c) {
+            const int n = base[c];
+            base[c] = at;
+            first_row[c] = at;
+            at += n;
+        }
+    }
+    __syncthreads();
+    {
+        int q = partial[tid] - sum;
+        for (int r = r0; r < r1; ++r)
+            for (int j = 0; j < members; ++j) {
+                int a, b;
+                row_range(j, r, a, b);
+                for (int p = a; p < b; ++p, ++q) {
+                    const int row = pc[q];
+                    pc[q] = base[row / kxt] + rank[row] - 1;
+                }
+            }
+    }
 }
 
 // One task of a sub-workgroup range: 256/S slots, one staged item each.
@@ -1799,7 +1859,8 @@ bspmm_gcn_stream_kernel(const StreamSet* __restrict__ sets, const int32_t* __res
         }
         const int32_t* cg = merged + st.csr_off;
         int* cd = cbase + b * S.csr_words;
-        const int csr_vecs = (((st.m + 4) & ~3) + 2 * ((st.nnz + 3) & ~3)) >> 2;
+        const int csr_vecs = (((st.m + 4) & ~3) + 2 * ((st.nnz + 3) & ~3) +
+                              (S.compact ? compact_words(S.channels, st.kx) : 0)) >> 2;
         for (int e0 = wave << 6; e0 < csr_vecs; e0 += kThreads) {
             const int e = e0 + wl;
             if (e < csr_vecs) lds_dma16(cg + 4 * e, cd + (e0 << 2));
@@ -1846,7 +1907,9 @@ bspmm_gcn_stream_kernel(const StreamSet* __restrict__ sets, const int32_t* __res
             const StreamSet bg = sets[jn];
             const int csr_w = ((bg.m + 4) & ~3) + 2 * ((bg.nnz + 3) & ~3);
             const bool big = S.channels * bg.kx * S.fw > S.tile_words || bg.kx * NX > S.x_words ||
-                             csr_w > S.csr_words || bg.m > kStreamPasses * rows_per_pass;
+                             csr_w + (S.compact ? compact_words(S.channels, bg.kx) : 0) > S.csr_words ||
+                             bg.m > kStreamPasses * rows_per_pass ||
+                             (S.compact && S.channels * bg.kx > kCompactRows);
             if (!big) break;
             const int kx = bg.kx, m = bg.m;
             const int piece_words = (S.channels * kx) << psh;
@@ -1981,11 +2044,30 @@ bspmm_gcn_stream_kernel(const StreamSet* __restrict__ sets, const int32_t* __res
         }
 
         // ---- dense tile: [X_i W[0] + bias[0]; ...; X_i W[M-1] + bias[M-1]] -> LDS
+        // With lists of the rows in use (S.compact) a wavefront makes only the rows of its
+        // channel's tile that an entry of that channel names: block mb holds the rows
+        // lst[16 mb ..] of X_i and goes to tile rows trow0 + 16 mb ..; without, all kx rows.
         const float* xs = xbase + b * S.x_words;
-        const int nmb = (kx + 15) >> 4;
+        int rows_w = kx, trow0[U];
+        const int* lst = nullptr;
+#pragma unroll
+        for (int u = 0; u < U; ++u) trow0[u] = unit_ch[u] * kx;
+        if (S.compact) {
+            const int* cnt = reinterpret_cast<const int*>(vals + ((cur.nnz + 3) & ~3));
+            const int c4 = (S.channels + 3) & ~3;
+            rows_w = cnt[unit_ch[0]];
+#pragma unroll
+            for (int u = 0; u < U; ++u) trow0[u] = cnt[c4 + unit_ch[u]];
+            lst = cnt + 2 * c4 + unit_ch[0] * kx;
+        }
+        const int nmb = (rows_w + 15) >> 4;
+        auto x_row = [&](int i) {       // the row of X_i that is row i of this wavefront's blocks
+            const int r = min(i, rows_w - 1);
+            return S.compact ? (r >= 0 ? lst[r] : 0) : r;
+        };
         float4 a[NX16];
         {
-            const int arow = min(col, kx - 1);
+            const int arow = x_row(col);
             const float* xrow = xs + arow * NX;
 #pragma unroll
             for (int s = 0; s < NX16; ++s)
@@ -1994,7 +2076,7 @@ bspmm_gcn_stream_kernel(const StreamSet* __restrict__ sets, const int32_t* __res
         for (int mb = 0; mb < nmb; ++mb) {
             float4 an[NX16];
             {   // the next block's rows before this block's instructions (rows past the end repeat the last)
-                const int arow = min(16 * (mb + 1) + col, kx - 1);
+                const int arow = x_row(16 * (mb + 1) + col);
                 const float* xrow = xs + arow * NX;
 #pragma unroll
                 for (int s = 0; s < NX16; ++s)
@@ -2019,10 +2101,10 @@ bspmm_gcn_stream_kernel(const StreamSet* __restrict__ sets, const int32_t* __res
             for (int u = 0; u < U; ++u) {
                 mfma4 r = acc[u][0];
                 if (C == 2) r = r + acc[u][C - 1];
-                float* tp = tile + ((unit_ch[u] * kx + 16 * mb + 4 * g) << fsh) + unit_col[u];
+                float* tp = tile + ((trow0[u] + 16 * mb + 4 * g) << fsh) + unit_col[u];
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    float* q = 16 * mb + 4 * g + i < kx ? tp + (i << fsh) : sink;
+                    float* q = 16 * mb + 4 * g + i < rows_w ? tp + (i << fsh) : sink;
                     *q = r[i];
                 }
             }

@@ -139,7 +139,7 @@ struct StreamShape {
     int64_t ld_x, ld_w, ld_y, bias_stride;
     int32_t tiles, fw, channels, accumulate;
     int32_t tile_words, x_words, csr_words, big_csr_words;
-    int32_t lists, reserved_[3];
+    int32_t lists, compact, reserved_[2];
 };
 struct StreamParams {
     const StreamSet* sets;
@@ -305,8 +305,18 @@ struct alignas(8) SetRecord {
     int32_t plain;                  // 1: the members read one dense block; the merged arrays are
                                     // then an ordinary CSR (row pointers, round_up(sum nnz, 4)
                                     // columns, as many values) that a plain item reads
-    int32_t pad_;
+    int32_t compact;                // 0, or channels | rows of the group's layer input << 8: the
+                                    // rows of each channel's dense tile that are in use are
+                                    // listed behind the values and the columns renumbered
 };
+
+// Words behind the values of a compacted set: counts and first tile rows of the channels
+// (padded to four each), then a list of kxt words per channel.
+BSPMM_HD inline int compact_words(int chans, int kxt)
+{
+    return chans > 0 ? round_up(2 * round_up(chans, 4) + chans * kxt, 4) : 0;
+}
+constexpr int kCompactRows = 1024;   // tile rows (channels x rows of X) of a set that is compacted, at most
 
 // Lanes that share one output row: enough 4-float vectors to cover the tile, a power of two.
 BSPMM_HD inline int lanes_per_row(int fw, int vec)

@@ -399,13 +399,18 @@ def test_random_whole_layers(torch_cuda, oracle, seed, **kw):
     F = [16, 32, 48, 64, 128][int(rng.integers(5))]
     n_x = [4, 12, 20, 32, 64, 100][int(rng.integers(6))]
     graphs = [1, 3, 20, 60][int(rng.integers(4))]
+    densities = kw.pop("densities", None)     # entries per row of every channel, instead of random ones
+    if densities is not None:
+        chans, F, n_x, graphs = len(densities), kw.pop("F"), kw.pop("n_x"), kw.pop("graphs")
     ops, b_block_of_op, b_block_rows, c_block_of_op = [], [], [], []
     for g in range(graphs):
         m = int(rng.integers(1, 90)) if rng.random() < 0.9 else int(rng.integers(90, 260))
         k = m if rng.integers(2) else int(rng.integers(1, 90))
         b_block_rows.append(k)
-        for _ in range(chans):
+        for c in range(chans):
             per_row = [0.0, 0.5, 1.5, 4.0][int(rng.integers(4))]
+            if densities is not None:
+                per_row = densities[c]
             rpt, ci, va = _random_csr(rng, m, k, int(per_row * m), bool(rng.integers(2)))
             ops.append((m, k, rpt, ci, va))
             b_block_of_op.append(g)
@@ -441,6 +446,22 @@ def test_random_whole_layers(torch_cuda, oracle, seed, **kw):
         dsum += max(int(np.diff(bc.op_csr(i)[0]).max()) if int(bc.rows[i]) else 0 for i in range(bc.batch))
     tol = max(1e-5, (chans * (n_x + 2) + dsum) * 2.0 ** -23)
     _assert_close(Yd.cpu().numpy(), Y, T, _owned(b.c_row_off, b.rows, b.n_c_rows), tol, f"random layer {seed}")
+
+
+@pytest.mark.parametrize("densities,n_x,F", [
+    ((0.0, 0.05, 0.7, 6.0), 64, 128),      # an empty channel, one with a handful of entries, a full one
+    ((0.3, 0.3), 32, 128),
+    ((8.0, 8.0, 8.0, 8.0), 32, 64),        # every row of every channel in use
+    ((0.0, 0.0, 0.0, 0.0), 16, 64),        # nothing at all: Y = 0
+])
+def test_streamed_layer_makes_only_the_rows_in_use(torch_cuda, oracle, densities, n_x, F):
+    """Streamed layers of several channels make only the rows of a channel's dense tile that
+    an entry of that channel names (the merged CSR is renumbered once per plan): channels from
+    empty to full, rectangular channel matrices, graphs of 1 to 260 nodes (the largest are
+    taken one at a time, without the lists)."""
+    for seed in (61, 62):
+        test_random_whole_layers(torch_cuda, oracle, seed, compute_units=1, densities=densities,
+                                 n_x=n_x, F=F, graphs=40)
 
 
 @pytest.mark.parametrize("one_launch", [False, True], ids=["streamed_where_it_can", "one_launch"])
