@@ -345,8 +345,9 @@ void make_stream_plan(bspmm_plan& p)
     const int64_t budget_words = (kn.lds_given ? kn.lds_words * 4 : 53248) / 4;
     const int rows_most = kStreamPasses * (kThreads / (fw / 4));
     // (a group must still go through the buffers: its tile, two buffers of X rows and two of CSR
-    // blocks - about ten words a row each - inside the budget)
-    const int group_rows = (int)std::min<int64_t>(single ? 64 : 48, (budget_words - 64) / ((int64_t)M * fw + 2 * nx + 20));
+    // blocks - about ten words a row each, and one per channel for the lists of rows in use -
+    // inside the budget)
+    const int group_rows = (int)std::min<int64_t>(single ? 64 : 48, (budget_words - 64) / ((int64_t)M * fw + 2 * nx + 20 + (single ? 0 : 2 * M)));
     const int group_graphs = kMaxMembers / M;
     std::vector<int> by_input;
     for (size_t g = 0; g < n_graphs; ++g) {
