@@ -327,7 +327,9 @@ int bspmm_run(bspmm_plan* plan, const float* B, float* C, int64_t ldb, int64_t l
  * at a time by the same workgroups (M = 1 or 4), or follow in a launch of the one-launch kernel
  * over their items.  The first run also enqueues a kernel that copies the CSR arrays into one
  * block per trip (once per plan, like the merged CSR of summed sets; BSPMM_BUILD_TRANSPOSE
- * moves it into bspmm_create).  bspmm_info.front_stream says what a plan does;
+ * moves it into bspmm_create).  For whole layers of 2 or 4 channels that kernel also lists, per
+ * channel, the rows of X_i that the channel's entries name: only those rows of X_i W[ch] +
+ * bias[ch] are made (a channel matrix with few entries per row leaves most of them unread).  bspmm_info.front_stream says what a plan does;
  * BSPMM_ONE_FRONT_LAUNCH keeps a plan on the one-launch path.  With options.lds_bytes the caller
  * fixes the LDS budget of both.
  */
