@@ -173,7 +173,7 @@ typedef struct bspmm_options {
                                   summed operations need more is refused with ETOOBIG; 52 KiB
                                   (tiles twice as wide) for F >= 512 when the launch moves
                                   more than 28 MB in more than one round of workgroups and
-                                  needs no more rounds that way.  bspmm_info.lds_bytes says
+                                  needs at most a tenth more rounds that way.  bspmm_info.lds_bytes says
                                   what was taken                                              */
     int32_t  min_tile;         /* narrowest feature tile in floats, 0 = default (32)           */
     int32_t  max_tile;         /* widest feature tile in floats, 0 = default (256), <= 256     */

@@ -1002,9 +1002,11 @@ int plan_with_budget(bspmm_plan& p, const Batch* b, int32_t F, const bspmm_optio
         // runs at the rate of the memory system: with 24 KiB the larger operations get tiles of
         // 32 columns (row segments of 128 bytes), each staging the operation's CSR again.  A
         // budget of a third of a CU's LDS doubles the tiles; it is kept when the launch then
-        // takes no more rounds than before, since three workgroups per CU are resident instead of
-        // six (measured, 128 graphs of 20-100 nodes: F = 1024, 1.41 rounds either way, 14.85 ->
-        // 14.19 us, 4.34 -> 4.54 TB/s; F = 512, 0.71 -> 1.33 rounds, 7.46 -> 8.79 us: not taken).
+        // takes at most a tenth more rounds than before, since three workgroups per CU are resident
+        // instead of six (measured, 128 graphs of 20-100 nodes: F = 1024, six seeds, 1.35-1.45
+        // rounds before and 1.39-1.47 after, 14.3-15.2 -> 13.4-14.4 us, 4.24-4.34 -> 4.49-4.56 TB/s;
+        // F = 512, 0.71 -> 1.33 rounds, 7.46 -> 8.79 us: not taken; 1024 graphs of 25 nodes at
+        // F = 512, 2.19 -> 2.82 rounds, 21.0 -> 21.3 us: not taken).
         bspmm_options o = options ? *options : bspmm_options{};
         o.lds_bytes = 53248;
         Knobs wide = knobs_for(&o, !dry);
@@ -1013,7 +1015,7 @@ int plan_with_budget(bspmm_plan& p, const Batch* b, int32_t F, const bspmm_optio
         wide.lds_given = false;
         bspmm_plan q;
         if (plan_fn(q, b, F, wide) == BSPMM_OK &&
-            (int64_t)q.sched[0].grid * kn.capacity_wgs <= (int64_t)p.sched[0].grid * wide.capacity_wgs)
+            10 * (int64_t)q.sched[0].grid * kn.capacity_wgs <= 11 * (int64_t)p.sched[0].grid * wide.capacity_wgs)
             p = std::move(q);
         return BSPMM_OK;
     }
