@@ -854,7 +854,25 @@ int plan_host(bspmm_plan& p, const bspmm_batch* b, int32_t F, const Knobs& kn)
         at = align_up(at + p.sched[d].items.size() * sizeof(WorkItem));
     }
     for (int d = 0; d < 2; ++d) {
-        make_lean_items(p, d);
+        if (d == 1 && p.transposed_supported && same_shape && p.sched[1].items.size() == p.lean_items[0].size() &&
+            !p.lean_items[0].empty()) {
+            // (the same items again: only the CSR arrays are elsewhere)
+            p.lean_items[1] = p.lean_items[0];
+            p.lean_blocks[1] = p.lean_blocks[0];
+            p.lean_rows[1] = p.lean_rows[0];
+            p.lean_out_rows[1] = p.lean_out_rows[0];
+            bool fits = true;
+            for (size_t j = 0; j < p.lean_items[1].size() && fits; ++j) {
+                const WorkItem& w = p.sched[1].items[j];
+                if (w.nrows <= 0) continue;
+                fits = w.rpt_off < ((int64_t)1 << 31) && w.nz_off < ((int64_t)1 << 31);
+                p.lean_items[1][j].rpt_off = (uint32_t)w.rpt_off;
+                p.lean_items[1][j].nz_off = (uint32_t)w.nz_off;
+            }
+            if (!fits) make_lean_items(p, d);
+        } else {
+            make_lean_items(p, d);
+        }
         L.lean[d] = at;
         at = align_up(at + p.lean_items[d].size() * sizeof(LeanItem));
     }
