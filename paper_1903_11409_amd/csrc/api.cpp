@@ -337,6 +337,17 @@ void make_stream_plan(bspmm_plan& p)
     // Kernels with one block per wavefront and several channels (tiles of 16 columns): 128
     // graphs at n_X = 128 take 22.9 against 18.1 us, 512 graphs 51 against 63.
     if ((int64_t)n_graphs * tiles < (units == 2 || single ? 2 : 8) * (int64_t)kn.compute_units) return;
+    // One channel: a trip holds a quarter of a four-channel trip's matrix work for the same
+    // bookkeeping, and the one-launch kernel stays ahead for longer - measured on molecule
+    // graphs of 25 nodes on 256 CUs, streamed against one launch: n_X = 32: 512 graphs 9.5
+    // against 8.5 us, 1024 graphs 13.6 against 14.4; n_X = 64: 384 graphs 10.5 against 9.2, 448
+    // graphs 10.9 against 11.9; n_X = 128: 256 graphs 15.4 against 15.2, 512 graphs 16.7 against
+    // 19.7.  The crossing sits near 700,000 elements of layer input.
+    if (single) {
+        int64_t x_rows = 0;
+        for (size_t g = 0; g < n_graphs; ++g) x_rows += o.k[graphs[g][0]];
+        if (x_rows * nx * 256 < (int64_t)700000 * kn.compute_units) return;
+    }
 
     // ---- groups: graphs back to back in X and in Y, while the members fit a record, the rows of
     // X three 16-row blocks (four for single channels) and the rows of Y the gather's passes

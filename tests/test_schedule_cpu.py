@@ -816,6 +816,25 @@ def test_whole_layers_of_many_rounds_are_streamed(graphs, F, n_x, chans, kw):
     assert workgroups <= 3 * kw.get("compute_units", 256) + F // 16
 
 
+def test_single_channels_stream_from_a_size_of_the_layer_input():
+    """One channel per launch: the streaming workgroups take over where the layer input has about
+    700,000 elements (on 256 CUs); below that the one-launch kernel is the faster one."""
+    def stream_of(graphs, n_x, **kw):
+        b = W.config2_molecule(F=128, graphs=graphs)
+        h = K.dry_plan(b, 128, front_features=n_x, **kw)
+        try:
+            return [int(v) for v in K.bspmm_plan_info(h).front_stream]
+        finally:
+            K.bspmm_destroy(h)
+    assert stream_of(256, 64) == [0, 0, 0, 0] and stream_of(384, 64) == [0, 0, 0, 0]
+    assert stream_of(512, 32) == [0, 0, 0, 0] and stream_of(200, 128) == [0, 0, 0, 0]
+    for graphs, n_x in ((512, 64), (1024, 32), (256, 128), (4096, 128)):
+        streamed, workgroups, lds, left = stream_of(graphs, n_x)
+        assert streamed + left == graphs and streamed > 0 and workgroups > 0 and 0 < lds <= 53248
+    # the size scales with the chip
+    assert stream_of(64, 64, compute_units=16)[0] > 0
+
+
 @pytest.mark.parametrize("why,graphs,F,n_x,chans,kw", [
     ("less than two workgroups per CU", 100, 128, 64, 4, {}),
     ("the caller keeps the one-launch path", 2048, 128, 64, 4, {"flags": K.ONE_FRONT_LAUNCH}),
