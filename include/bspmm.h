@@ -319,7 +319,8 @@ int bspmm_run(bspmm_plan* plan, const float* B, float* C, int64_t ldb, int64_t l
  * channels of a graph are taken in the order of their operations.
  *
  * Layers of two and more (graph, feature tile) pairs per CU - single channels, or whole layers
- * of M = 2, 4 or 8 channels - with n_X = 16, 32, 64 or 128 run as a launch of RESIDENT workgroups
+ * of M = 2 to 8 channels (3 run as 4, 5 to 7 as 8, the added channels empty) - with n_X = 16, 32,
+ * 64 or 128 run as a launch of RESIDENT workgroups
  * instead, three per CU: each keeps the weights of its feature tile in registers for the whole
  * launch and streams the graphs of its list through LDS, the next graph's X_i and CSR in flight
  * while the matrix cores work on this one's.  Small graphs whose blocks lie back to back in X
@@ -327,7 +328,7 @@ int bspmm_run(bspmm_plan* plan, const float* B, float* C, int64_t ldb, int64_t l
  * at a time by the same workgroups (M = 1 or 4), or follow in a launch of the one-launch kernel
  * over their items.  The first run also enqueues a kernel that copies the CSR arrays into one
  * block per trip (once per plan, like the merged CSR of summed sets; BSPMM_BUILD_TRANSPOSE
- * moves it into bspmm_create).  For whole layers of 2 or 4 channels that kernel also lists, per
+ * moves it into bspmm_create).  For whole layers of 2 to 4 channels that kernel also lists, per
  * channel, the rows of X_i that the channel's entries name: only those rows of X_i W[ch] +
  * bias[ch] are made (a channel matrix with few entries per row leaves most of them unread).  bspmm_info.front_stream says what a plan does;
  * BSPMM_ONE_FRONT_LAUNCH keeps a plan on the one-launch path.  With options.lds_bytes the caller

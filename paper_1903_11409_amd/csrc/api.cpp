@@ -133,6 +133,7 @@ struct bspmm_plan {
         std::vector<WorkItem> rest;
         int nx16 = 0, units = 0, fw = 0, tiles = 0, lists = 0;
         bool compact = false;            // the groups bring lists of the tile rows in use
+        int channels = 1;                // channels the kernel runs with (the layer's, or the next of 4 and 8)
         std::vector<SetRecord> records;   // one per group of graphs, for the kernel that merges CSR arrays
         int64_t merged_words = 0;  // words of the groups' merged CSR blocks
         bool merged_built = false;
@@ -307,9 +308,13 @@ void make_stream_plan(bspmm_plan& p)
     if (nx <= 0 || kn.one_front_launch || !sc.fused_sets.empty() || sc.fused_tasks > 0) return;
     // (plans of single channels - no operations summed - take the same kernel with one channel)
     const bool single = sc.merged_sets.empty();
-    const int M = single ? 1 : p.front_channels;
+    // Layers of 3, 5, 6 or 7 channels run as layers of 4 or 8 whose last channels are empty: no
+    // entry names a row of their tiles, their weights read as zero, and with the lists of rows in
+    // use their wavefronts have no matrix work at all.
+    const int channels = single ? 1 : p.front_channels;
     if (!single && !kn.accumulate) return;
-    if (nx % 16 != 0 || (M != 1 && M != 2 && M != 4 && M != 8)) return;
+    if (nx % 16 != 0 || channels < 1 || channels > 8) return;
+    const int M = channels <= 2 ? channels : (channels <= 4 ? 4 : 8);
     const int nx16 = nx / 16;
     int units = 0, fw = 0;
     // (two blocks per wavefront first, except for two channels: one block per wavefront makes
@@ -363,7 +368,7 @@ void make_stream_plan(bspmm_plan& p)
     // blocks - about ten words a row each, and one per channel for the lists of rows in use -
     // inside the budget)
     const int group_rows = (int)std::min<int64_t>(single ? 64 : 48, (budget_words - 64) / ((int64_t)M * fw + 2 * nx + 20 + (single ? 0 : 2 * M)));
-    const int group_graphs = kMaxMembers / M;
+    const int group_graphs = kMaxMembers / channels;
     std::vector<int> by_input;
     for (size_t g = 0; g < n_graphs; ++g) {
         const int op0 = graphs[g][0];
@@ -442,7 +447,7 @@ void make_stream_plan(bspmm_plan& p)
             int64_t x_at = 0, m_at = 0;
             for (int g : groups[s]) {
                 const int op0 = graphs[g][0];
-                for (int c = 0; c < M; ++c, ++j) {
+                for (int c = 0; c < channels; ++c, ++j) {
                     const int op = graphs[g][c];
                     r.rpt_off[j] = o.rpt_off[op];
                     r.nz_off[j] = o.nz_off[op];
@@ -512,6 +517,7 @@ void make_stream_plan(bspmm_plan& p)
         return;
     }
     st.nx16 = nx16, st.units = units, st.fw = fw, st.tiles = tiles;
+    st.channels = M;
     st.compact = compact_on;
     if (compact_on)
         for (int i : mine) recs[i].compact = M | ((int32_t)kxs[i] << 8);
@@ -1504,13 +1510,14 @@ int run_gcn(bspmm_plan* p, const float* X, int64_t ldx, const float* W, int64_t 
         S.y = Y;
         StreamShape& sh = S.shape;
         sh.ld_x = ldx, sh.ld_w = ldw, sh.ld_y = ldy, sh.bias_stride = p->F;
-        sh.tiles = st.tiles, sh.fw = st.fw, sh.channels = sets ? p->front_channels : 1;
+        sh.tiles = st.tiles, sh.fw = st.fw, sh.channels = st.channels;
         sh.accumulate = accumulate ? 1 : 0;
         sh.tile_words = st.tile_words, sh.x_words = st.x_words, sh.csr_words = st.csr_words;
         sh.big_csr_words = st.big_csr_words;
         sh.lists = st.lists;
         sh.compact = st.compact ? 1 : 0;
-        sh.reserved_[0] = sh.reserved_[1] = 0;
+        sh.real_channels = sets ? p->front_channels : 1;
+        sh.reserved_ = 0;
         const hipError_t es = launch_bspmm_gcn_stream(S, st.nx16, st.units, (st.lists + 7) / 8 * 8 * st.tiles,
                                                       st.lds_bytes(), s);
         if (es != hipSuccess) return hip_fail(es);

@@ -1823,12 +1823,14 @@ bspmm_gcn_stream_kernel(const StreamSet* __restrict__ sets, const int32_t* __res
         const int ch = unit / nbw, nb = unit - ch * nbw;
         unit_ch[u] = ch;
         unit_col[u] = 16 * nb + col;
-        const float* wp = wgt + (int64_t)(ch * NX + 4 * g) * S.ld_w + f0 + 16 * nb + col;
+        // (a channel past the layer's own - the layer runs padded to 4 or 8 - has no weights)
+        const bool live = ch < S.real_channels;
+        const float* wp = wgt + (int64_t)((live ? ch : 0) * NX + 4 * g) * S.ld_w + f0 + 16 * nb + col;
 #pragma unroll
         for (int s = 0; s < NX16; ++s)
 #pragma unroll
-            for (int j = 0; j < 4; ++j) w[u][s][j] = wp[(int64_t)(16 * s + j) * S.ld_w];
-        bv[u] = bias[(int64_t)ch * S.bias_stride + f0 + 16 * nb + col];
+            for (int j = 0; j < 4; ++j) w[u][s][j] = live ? wp[(int64_t)(16 * s + j) * S.ld_w] : 0.f;
+        bv[u] = live ? bias[(int64_t)ch * S.bias_stride + f0 + 16 * nb + col] : 0.f;
     }
 
     // rows of X_i and the merged CSR block of a graph -> buffers b.  A lane's element of a

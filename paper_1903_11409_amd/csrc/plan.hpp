@@ -139,7 +139,7 @@ struct StreamShape {
     int64_t ld_x, ld_w, ld_y, bias_stride;
     int32_t tiles, fw, channels, accumulate;
     int32_t tile_words, x_words, csr_words, big_csr_words;
-    int32_t lists, compact, reserved_[2];
+    int32_t lists, compact, real_channels, reserved_;   // (channels >= real_channels are empty: see the host)
 };
 struct StreamParams {
     const StreamSet* sets;
