@@ -320,19 +320,20 @@ int bspmm_run(bspmm_plan* plan, const float* B, float* C, int64_t ldb, int64_t l
  *
  * Layers of two and more (graph, feature tile) pairs per CU - single channels, or whole layers
  * of M = 2 to 8 channels (3 run as 4, 5 to 7 as 8, the added channels empty) - with n_X = 16, 32,
- * 64 or 128 run as a launch of RESIDENT workgroups
- * instead, three per CU: each keeps the weights of its feature tile in registers for the whole
- * launch and streams the graphs of its list through LDS, the next graph's X_i and CSR in flight
- * while the matrix cores work on this one's.  Small graphs whose blocks lie back to back in X
- * and in Y are taken several per trip; graphs too large for a third of a CU's LDS are taken one
- * at a time by the same workgroups (M = 1 or 4), or follow in a launch of the one-launch kernel
- * over their items.  The first run also enqueues a kernel that copies the CSR arrays into one
- * block per trip (once per plan, like the merged CSR of summed sets; BSPMM_BUILD_TRANSPOSE
- * moves it into bspmm_create).  For whole layers of 2 to 4 channels that kernel also lists, per
- * channel, the rows of X_i that the channel's entries name: only those rows of X_i W[ch] +
- * bias[ch] are made (a channel matrix with few entries per row leaves most of them unread).  bspmm_info.front_stream says what a plan does;
- * BSPMM_ONE_FRONT_LAUNCH keeps a plan on the one-launch path.  With options.lds_bytes the caller
- * fixes the LDS budget of both.
+ * 64 or 128 run as a launch of RESIDENT workgroups instead, three per CU (8 channels: two per
+ * CU, of eight wavefronts, one per channel): each keeps the weights of its feature tile in
+ * registers for the whole launch and streams the graphs of its list through LDS, the next
+ * graph's X_i and CSR in flight while the matrix cores work on this one's.  Small graphs whose
+ * blocks lie back to back in X and in Y are taken several per trip; graphs too large for a
+ * workgroup's share of the LDS are taken one at a time by the same workgroups (M = 1 or 4), or
+ * follow in a launch of the one-launch kernel over their items.  The first run also enqueues a
+ * kernel that copies the CSR arrays into one block per trip (once per plan, like the merged CSR
+ * of summed sets; BSPMM_BUILD_TRANSPOSE moves it into bspmm_create).  For whole layers that
+ * kernel also lists, per channel, the rows of X_i that the channel's entries name: only those
+ * rows of X_i W[ch] + bias[ch] are made (a channel matrix with few entries per row leaves most
+ * of them unread).  bspmm_info.front_stream says what a plan does; BSPMM_ONE_FRONT_LAUNCH keeps
+ * a plan on the one-launch path.  With options.lds_bytes the caller fixes the LDS budget of
+ * both.
  */
 int bspmm_run_gcn(bspmm_plan* plan, const float* X, int64_t ldx, const float* W, int64_t ldw,
                   const float* bias, float* Y, int64_t ldy, int32_t accumulate, void* stream);

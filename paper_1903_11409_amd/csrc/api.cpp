@@ -24,10 +24,10 @@ hipError_t launch_bspmm_lean(const LeanItem* items, const LaunchParams& P, int g
 hipError_t launch_lean_hints(LeanItem* items, int n, const int32_t* rpt, hipStream_t stream);
 hipError_t launch_bspmm_gcn(const LaunchParams& P, int grid, int lds_bytes, bool accumulate,
                             bool sets, hipStream_t stream);
-hipError_t launch_bspmm_gcn_stream(const StreamParams& S, int nx16, int units, int grid,
+hipError_t launch_bspmm_gcn_stream(const StreamParams& S, int nx16, int units, int waves, int grid,
                                    int lds_bytes, hipStream_t stream);
-bool stream_supported(int nx16, int units);
-int stream_workgroups_per_cu(int nx16, int units, int lds_bytes);
+bool stream_supported(int nx16, int units, int waves);
+int stream_workgroups_per_cu(int nx16, int units, int waves, int lds_bytes);
 hipError_t launch_build_transpose(const OpRecord* ops, int batch, int threads, int lds_bytes,
                                   const int32_t* rpt, const int32_t* colids,
                                   const float* values, int32_t* rpt_t, int32_t* colids_t,
@@ -131,7 +131,7 @@ struct bspmm_plan {
         std::vector<StreamSet> sets;
         std::vector<int32_t> list;
         std::vector<WorkItem> rest;
-        int nx16 = 0, units = 0, fw = 0, tiles = 0, lists = 0;
+        int nx16 = 0, units = 0, waves = 4, fw = 0, tiles = 0, lists = 0;
         bool compact = false;            // the groups bring lists of the tile rows in use
         int channels = 1;                // channels the kernel runs with (the layer's, or the next of 4 and 8)
         std::vector<SetRecord> records;   // one per group of graphs, for the kernel that merges CSR arrays
@@ -316,21 +316,26 @@ void make_stream_plan(bspmm_plan& p)
     if (nx % 16 != 0 || channels < 1 || channels > 8) return;
     const int M = channels <= 2 ? channels : (channels <= 4 ? 4 : 8);
     const int nx16 = nx / 16;
-    int units = 0, fw = 0;
+    int units = 0, fw = 0, waves = 4;
     // (two blocks per wavefront first, except for two channels: one block per wavefront makes
     // their tiles 32 columns wide like those of four channels - eight lanes per output row, 32
     // rows per gather pass, larger graphs taken in the same launch - and measured 2048 graphs at
-    // n_X = 64 38 against 51 us, 512 graphs 12 against 23 us)
-    for (int u : {M == 2 ? 1 : 2, M == 2 ? 2 : 1}) {
-        const int w = 64 * u / M;
+    // n_X = 64 38 against 51 us, 512 graphs 12 against 23 us.  Eight channels: workgroups of
+    // eight wavefronts, one per channel, for the same reason.)
+    const int shapes[4][2] = {{M == 2 ? 1 : 2, M == 8 ? 8 : 4}, {M == 2 ? 2 : 1, M == 8 ? 8 : 4}, {2, 4}, {1, 4}};
+    for (const auto& sh : shapes) {
+        const int u = sh[0], wv = sh[1];
+        const int w = 16 * wv * u / M;
         // (tiles of up to 64 columns: 16 lanes per output row, 64 rows in the gather's passes)
-        if (w >= 16 && w <= 64 && F % w == 0 && stream_supported(nx16, u)) {
+        if (w >= 16 && w <= 64 && F % w == 0 && stream_supported(nx16, u, wv)) {
             units = u;
+            waves = wv;
             fw = w;
             break;
         }
     }
     if (!units) return;
+    const int threads = 64 * waves;
     const int tiles = F / fw;
     const DirOps& o = p.dir[0];
     // the graphs: sets of channel operations, or the operations themselves
@@ -362,8 +367,9 @@ void make_stream_plan(bspmm_plan& p)
     // X three 16-row blocks (four for single channels) and the rows of Y the gather's passes
     // (three workgroups per CU: a third of the CU's 160 KiB less what the allocation granule
     // takes; 53920 bytes were measured to leave room for two only)
-    const int64_t budget_words = (kn.lds_given ? kn.lds_words * 4 : 53248) / 4;
-    const int rows_most = kStreamPasses * (kThreads / (fw / 4));
+    // (workgroups of eight wavefronts: two per CU, half of a CU's LDS each)
+    const int64_t budget_words = (kn.lds_given ? kn.lds_words * 4 : (waves == 8 ? 81920 : 53248)) / 4;
+    const int rows_most = kStreamPasses * (threads / (fw / 4));
     // (a group must still go through the buffers: its tile, two buffers of X rows and two of CSR
     // blocks - about ten words a row each, and one per channel for the lists of rows in use -
     // inside the budget)
@@ -405,7 +411,7 @@ void make_stream_plan(bspmm_plan& p)
     };
     std::vector<std::vector<int>> groups;
     {
-        const int64_t cap_lists = std::max<int64_t>(1, 3 * (int64_t)kn.compute_units / tiles);
+        const int64_t cap_lists = std::max<int64_t>(1, (waves == 8 ? 2 : 3) * (int64_t)kn.compute_units / tiles);
         double best = 0;
         for (int most = 1; most <= group_graphs; ++most) {
             std::vector<std::vector<int>> cand = form_groups(most);
@@ -516,7 +522,7 @@ void make_stream_plan(bspmm_plan& p)
         st = bspmm_plan::Stream();
         return;
     }
-    st.nx16 = nx16, st.units = units, st.fw = fw, st.tiles = tiles;
+    st.nx16 = nx16, st.units = units, st.waves = waves, st.fw = fw, st.tiles = tiles;
     st.channels = M;
     st.compact = compact_on;
     if (compact_on)
@@ -551,7 +557,7 @@ void make_stream_plan(bspmm_plan& p)
     }
 
     // lists: as many workgroups as the chip holds at once, the same lists for every tile
-    int per_cu = kn.device_ok ? stream_workgroups_per_cu(nx16, units, st.lds_bytes()) : 0;
+    int per_cu = kn.device_ok ? stream_workgroups_per_cu(nx16, units, waves, st.lds_bytes()) : 0;
     if (per_cu <= 0) per_cu = std::max(1, std::min(3, kMaxLdsBytes / std::max(1, st.lds_bytes())));
     // (a graph taken one at a time stages its X twice and overlaps nothing)
     std::vector<char> in_halves(n_sets, 0);
@@ -564,7 +570,7 @@ void make_stream_plan(bspmm_plan& p)
     // x blocks per wavefront), and every pass of the gather after the first, which starts from
     // the row pointers in LDS instead of from registers and costs the more the longer the
     // matrix phases of the workgroups beside it hold the SIMDs.
-    const int rows_per_pass_c = kThreads / (fw / 4);
+    const int rows_per_pass_c = threads / (fw / 4);
     const int64_t sw = (int64_t)nx16 * units;      // matrix instructions per 16-row block, in fours
     auto trip_cost = [&](int64_t blocks, int64_t m) {
         const int64_t passes = std::max<int64_t>(1, (m + rows_per_pass_c - 1) / rows_per_pass_c);
@@ -618,7 +624,7 @@ void make_stream_plan(bspmm_plan& p)
     // inside the room of that mode, every other graph inside the buffers (the kernel's own
     // tests, which decide where its loads and stores go).  A table that fails is not used.
     {
-        const int rows_per_pass = kThreads / (fw / 4);
+        const int rows_per_pass = threads / (fw / 4);
         const int64_t total = (int64_t)st.tile_words + 2 * st.x_words + 2 * st.csr_words;
         const int piece = units == 2 ? 16 : fw;
         bool ok = true;
@@ -1518,7 +1524,7 @@ int run_gcn(bspmm_plan* p, const float* X, int64_t ldx, const float* W, int64_t 
         sh.compact = st.compact ? 1 : 0;
         sh.real_channels = sets ? p->front_channels : 1;
         sh.reserved_ = 0;
-        const hipError_t es = launch_bspmm_gcn_stream(S, st.nx16, st.units, (st.lists + 7) / 8 * 8 * st.tiles,
+        const hipError_t es = launch_bspmm_gcn_stream(S, st.nx16, st.units, st.waves, (st.lists + 7) / 8 * 8 * st.tiles,
                                                       st.lds_bytes(), s);
         if (es != hipSuccess) return hip_fail(es);
         if (st.rest.empty()) return BSPMM_OK;

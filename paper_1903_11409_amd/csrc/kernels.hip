@@ -1780,8 +1780,8 @@ __device__ __forceinline__ void lds_barrier()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
-template <int NX16, int U>
-__global__ void __launch_bounds__(kThreads)
+template <int NX16, int U, int WV>
+__global__ void __launch_bounds__(64 * WV)
 bspmm_gcn_stream_kernel(const StreamSet* __restrict__ sets, const int32_t* __restrict__ list,
                         const int32_t* __restrict__ merged, const float* __restrict__ x,
                         const float* __restrict__ wgt, const float* __restrict__ bias,
@@ -1791,6 +1791,7 @@ bspmm_gcn_stream_kernel(const StreamSet* __restrict__ sets, const int32_t* __res
     typedef float mfma4 __attribute__((ext_vector_type(4)));
     constexpr int NX = 16 * NX16, XVEC = NX / 4, XSH = NX16 == 1 ? 2 : (NX16 == 2 ? 3 : (NX16 == 4 ? 4 : 5));
     constexpr int SWZ = (XVEC < 16 ? XVEC : 16) - 1;
+    constexpr int T = 64 * WV;                    // lanes of the workgroup (four or eight wavefronts)
     constexpr int C = U == 1 ? 2 : 1;            // accumulators per block: two matrix instructions
                                                  // between dependent ones either way
     const int tid = threadIdx.x;
@@ -1837,7 +1838,7 @@ bspmm_gcn_stream_kernel(const StreamSet* __restrict__ sets, const int32_t* __res
     // request is 256 elements (256 / XVEC rows) after its element of the previous one: the row
     // advances by a multiple of the swizzle period, so the swizzled column is the lane's for good
     // and only the row term changes between requests.
-    constexpr int kRowsPerRequest = kThreads / XVEC;
+    constexpr int kRowsPerRequest = T / XVEC;
     static_assert(kRowsPerRequest % (SWZ + 1) == 0 || XVEC == 32, "swizzle period");
     const int x_row0 = tid >> XSH;
     const int64_t x_lane_off = (int64_t)x_row0 * S.ld_x + (((tid & (XVEC - 1)) ^ (x_row0 & SWZ)) << 2);
@@ -1845,10 +1846,10 @@ bspmm_gcn_stream_kernel(const StreamSet* __restrict__ sets, const int32_t* __res
         const int total = st.kx << XSH;
         const float* xg = x + st.in_row * S.ld_x + x_lane_off;
         float* xd = xbase + b * S.x_words;
-        for (int e0 = wave << 6; e0 < total; e0 += kThreads) {
+        for (int e0 = wave << 6; e0 < total; e0 += T) {
             const int e = e0 + wl;
             if (e < total) {
-                const int i = e0 >> 8;                       // which request of this wavefront
+                const int i = e0 / T;                        // which request of this wavefront
                 const float* gp;
                 if (XVEC == 32) {                            // (8 rows a request: the row's swizzle moves)
                     const int r = e >> XSH;
@@ -1863,7 +1864,7 @@ bspmm_gcn_stream_kernel(const StreamSet* __restrict__ sets, const int32_t* __res
         int* cd = cbase + b * S.csr_words;
         const int csr_vecs = (((st.m + 4) & ~3) + 2 * ((st.nnz + 3) & ~3) +
                               (S.compact ? compact_words(S.channels, st.kx) : 0)) >> 2;
-        for (int e0 = wave << 6; e0 < csr_vecs; e0 += kThreads) {
+        for (int e0 = wave << 6; e0 < csr_vecs; e0 += T) {
             const int e = e0 + wl;
             if (e < csr_vecs) lds_dma16(cg + 4 * e, cd + (e0 << 2));
         }
@@ -1872,7 +1873,7 @@ bspmm_gcn_stream_kernel(const StreamSet* __restrict__ sets, const int32_t* __res
     // gather geometry: fw / 4 lanes per output row
     const int gsh = fsh - 2;
     const int r_lane = tid >> gsh, l = tid & ((1 << gsh) - 1);
-    const int rows_per_pass = kThreads >> gsh;
+    const int rows_per_pass = T >> gsh;
     float4 yv[kStreamPasses];
     int pend_m = 0;
     int64_t pend_row = 0;
@@ -1921,7 +1922,7 @@ bspmm_gcn_stream_kernel(const StreamSet* __restrict__ sets, const int32_t* __res
             {
                 const int32_t* cg = merged + bg.csr_off;
                 const int csr_vecs = csr_w >> 2;
-                for (int e0 = wave << 6; e0 < csr_vecs; e0 += kThreads) {
+                for (int e0 = wave << 6; e0 < csr_vecs; e0 += T) {
                     const int e = e0 + wl;
                     if (e < csr_vecs) lds_dma16(cg + 4 * e, cbig + (e0 << 2));
                 }
@@ -1936,7 +1937,7 @@ bspmm_gcn_stream_kernel(const StreamSet* __restrict__ sets, const int32_t* __res
                 for (int r0 = 0; r0 < kx; r0 += rows_chunk) {
                     const int rows = min(rows_chunk, kx - r0);
                     const int total = rows << XSH;
-                    for (int e0 = wave << 6; e0 < total; e0 += kThreads) {
+                    for (int e0 = wave << 6; e0 < total; e0 += T) {
                         const int e = e0 + wl;
                         if (e < total) {
                             const int r = e >> XSH;
@@ -1973,7 +1974,7 @@ bspmm_gcn_stream_kernel(const StreamSet* __restrict__ sets, const int32_t* __res
                 const int hsh = psh - 2;
                 const int hr = tid >> hsh, hl = tid & ((1 << hsh) - 1);
                 const char* tcol = reinterpret_cast<const char*>(tile) + 16 * hl;
-                for (int r = hr; r < m; r += kThreads >> hsh) {
+                for (int r = hr; r < m; r += T >> hsh) {
                     const int p0 = rp[r], p1 = rp[r + 1];
                     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
                     for (int p = p0; p < p1; p += 4) {
@@ -2536,7 +2537,7 @@ hipError_t kernel_resources(int which, int lds_bytes, int out[7])
             threads = kBuildThreadsLarge;
             break;
         case 7: fn = reinterpret_cast<const void*>(&bspmm_coo_kernel<4>); break;
-        case 8: fn = reinterpret_cast<const void*>(&bspmm_gcn_stream_kernel<4, 2>); break;
+        case 8: fn = reinterpret_cast<const void*>(&bspmm_gcn_stream_kernel<4, 2, 4>); break;
         default: return hipErrorInvalidValue;
     }
     hipFuncAttributes a;
@@ -2598,48 +2599,55 @@ hipError_t launch_bspmm_gcn(const LaunchParams& P, int grid, int lds_bytes, bool
 using StreamFn = void (*)(const StreamSet*, const int32_t*, const int32_t*, const float*, const float*,
                           const float*, float*, const StreamShape);
 
-// (n_X / 16, blocks per wavefront) -> kernel; null for shapes the streaming kernel is not built for
-static StreamFn stream_variant(int nx16, int units)
+// (n_X / 16, blocks per wavefront, wavefronts) -> kernel; null for shapes the streaming kernel is
+// not built for
+static StreamFn stream_variant(int nx16, int units, int waves)
 {
-    if (units == 1) {
+    if (waves == 4 && units == 1) {
         switch (nx16) {
-        case 1: return bspmm_gcn_stream_kernel<1, 1>;
-        case 2: return bspmm_gcn_stream_kernel<2, 1>;
-        case 4: return bspmm_gcn_stream_kernel<4, 1>;
-        case 8: return bspmm_gcn_stream_kernel<8, 1>;
+        case 1: return bspmm_gcn_stream_kernel<1, 1, 4>;
+        case 2: return bspmm_gcn_stream_kernel<2, 1, 4>;
+        case 4: return bspmm_gcn_stream_kernel<4, 1, 4>;
+        case 8: return bspmm_gcn_stream_kernel<8, 1, 4>;
         }
-    } else if (units == 2) {
+    } else if (waves == 4 && units == 2) {
         switch (nx16) {
-        case 1: return bspmm_gcn_stream_kernel<1, 2>;
-        case 2: return bspmm_gcn_stream_kernel<2, 2>;
-        case 4: return bspmm_gcn_stream_kernel<4, 2>;
+        case 1: return bspmm_gcn_stream_kernel<1, 2, 4>;
+        case 2: return bspmm_gcn_stream_kernel<2, 2, 4>;
+        case 4: return bspmm_gcn_stream_kernel<4, 2, 4>;
+        }
+    } else if (waves == 8 && units == 2) {      // eight channels: a wavefront per channel
+        switch (nx16) {
+        case 1: return bspmm_gcn_stream_kernel<1, 2, 8>;
+        case 2: return bspmm_gcn_stream_kernel<2, 2, 8>;
+        case 4: return bspmm_gcn_stream_kernel<4, 2, 8>;
         }
     }
     return nullptr;
 }
 
-bool stream_supported(int nx16, int units) { return stream_variant(nx16, units) != nullptr; }
+bool stream_supported(int nx16, int units, int waves) { return stream_variant(nx16, units, waves) != nullptr; }
 
 // Workgroups of the streaming kernel one CU of the current device holds (0 if it cannot be asked).
-int stream_workgroups_per_cu(int nx16, int units, int lds_bytes)
+int stream_workgroups_per_cu(int nx16, int units, int waves, int lds_bytes)
 {
-    const StreamFn fn = stream_variant(nx16, units);
+    const StreamFn fn = stream_variant(nx16, units, waves);
     int per_cu = 0;
     if (!fn) return 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, kThreads, (size_t)lds_bytes) != hipSuccess) {
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, 64 * waves, (size_t)lds_bytes) != hipSuccess) {
         (void)hipGetLastError();
         return 0;
     }
     return per_cu;
 }
 
-hipError_t launch_bspmm_gcn_stream(const StreamParams& P, int nx16, int units, int grid,
+hipError_t launch_bspmm_gcn_stream(const StreamParams& P, int nx16, int units, int waves, int grid,
                                    int lds_bytes, hipStream_t stream)
 {
     if (grid <= 0) return hipSuccess;
-    const StreamFn fn = stream_variant(nx16, units);
+    const StreamFn fn = stream_variant(nx16, units, waves);
     if (!fn) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(fn, dim3(grid), dim3(kThreads), lds_bytes, stream, P.sets, P.list, P.merged, P.x,
+    hipLaunchKernelGGL(fn, dim3(grid), dim3(64 * waves), lds_bytes, stream, P.sets, P.list, P.merged, P.x,
                        P.w, P.bias, P.y, P.shape);
     return hipGetLastError();
 }

@@ -807,12 +807,14 @@ def _stream_of(graphs, F, n_x, chans, seed=3, **kw):
 def test_whole_layers_of_many_rounds_are_streamed(graphs, F, n_x, chans, kw):
     """Plans with front_features and BSPMM_ACCUMULATE whose launch would take many rounds of
     workgroups run as resident workgroups that stream the graphs: every graph is either in a
-    list or left to a launch of its own, the launch's LDS stays inside a third of a CU's (or
-    what the caller gave), and there are workgroups for every feature tile."""
+    list or left to a launch of its own, the launch's LDS stays inside a third of a CU's (half
+    for layers of more than four channels; or what the caller gave), and there are workgroups for
+    every feature tile."""
     (streamed, workgroups, lds, left), b = _stream_of(graphs, F, n_x, chans, **kw)
     assert streamed > 0 and streamed + left == graphs
-    assert 0 < lds <= kw.get("lds_bytes", 53248)
-    tiles = {2: (32, 64), 3: (16, 32), 4: (16, 32), 5: (16,), 8: (16,)}[chans]
+    # (five to eight channels: workgroups of eight wavefronts, two per CU)
+    assert 0 < lds <= kw.get("lds_bytes", 81920 if chans > 4 else 53248)
+    tiles = {2: (32, 64), 3: (16, 32), 4: (16, 32), 5: (16, 32), 8: (16, 32)}[chans]
     assert any(workgroups % (F // t) == 0 for t in tiles)
     assert workgroups <= 3 * kw.get("compute_units", 256) + F // 16
 
