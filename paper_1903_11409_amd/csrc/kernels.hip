@@ -2622,6 +2622,13 @@ static StreamFn stream_variant(int nx16, int units, int waves)
         case 2: return bspmm_gcn_stream_kernel<2, 2, 8>;
         case 4: return bspmm_gcn_stream_kernel<4, 2, 8>;
         }
+    } else if (waves == 8 && units == 1) {      // the same on tiles of 16 columns (n_X = 128, F = 16, 48, ...)
+        switch (nx16) {
+        case 1: return bspmm_gcn_stream_kernel<1, 1, 8>;
+        case 2: return bspmm_gcn_stream_kernel<2, 1, 8>;
+        case 4: return bspmm_gcn_stream_kernel<4, 1, 8>;
+        case 8: return bspmm_gcn_stream_kernel<8, 1, 8>;
+        }
     }
     return nullptr;
 }

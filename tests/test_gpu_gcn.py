@@ -310,6 +310,13 @@ def test_whole_layer_in_wide_blocks(torch_cuda, oracle, graphs, F, n_x, chans, k
     (24, 256, 128, 2, {"compute_units": 4}, None),      # one block per wavefront
     (24, 128, 64, 2, {"compute_units": 4}, None),       # two channels: tiles of 64 columns
     (24, 64, 32, 8, {"compute_units": 4, "lds_bytes": 163840}, False),
+    # five to eight channels: workgroups of eight wavefronts, one per channel
+    (512, 128, 64, 8, {}, None),
+    (32, 128, 128, 8, {"compute_units": 4}, None),
+    (40, 64, 32, 5, {"compute_units": 4}, None),        # run as eight, three of them empty
+    (24, 32, 16, 6, {"compute_units": 4}, None),
+    (48, 128, 64, 7, {"compute_units": 4}, None),
+    (48, 128, 64, 3, {"compute_units": 4}, None),       # run as four
 ])
 def test_whole_layer_streamed(torch_cuda, oracle, graphs, F, n_x, chans, kw, left):
     info = _whole_layer_case(torch_cuda, oracle, graphs, F, n_x, chans, **kw)
@@ -453,6 +460,9 @@ def test_random_whole_layers(torch_cuda, oracle, seed, **kw):
     ((0.3, 0.3), 32, 128),
     ((8.0, 8.0, 8.0, 8.0), 32, 64),        # every row of every channel in use
     ((0.0, 0.0, 0.0, 0.0), 16, 64),        # nothing at all: Y = 0
+    ((0.5, 0.0, 2.0, 0.1, 8.0, 0.7, 0.0, 1.0), 64, 64),    # eight channels
+    ((1.0, 0.2, 0.0, 4.0, 0.6), 32, 128),                  # five, run as eight
+    ((0.4, 0.0, 3.0), 16, 32),                             # three, run as four
 ])
 def test_streamed_layer_makes_only_the_rows_in_use(torch_cuda, oracle, densities, n_x, F):
     """Streamed layers of several channels make only the rows of a channel's dense tile that
@@ -468,7 +478,7 @@ def test_streamed_layer_makes_only_the_rows_in_use(torch_cuda, oracle, densities
 @pytest.mark.parametrize("seed", range(20, 32))
 def test_random_whole_layers_in_several_rounds(torch_cuda, oracle, seed, one_launch):
     """The same random layers with the scheduler told that the chip has one CU.  Shapes the
-    streaming kernel takes (2, 4 or 8 channels, n_X a multiple of 16 up to 128) then run as
+    streaming kernel takes (2 to 8 channels, n_X = 16, 32, 64 or 128) then run as
     resident workgroups, larger graphs in halves or in a launch of their own; with
     BSPMM_ONE_FRONT_LAUNCH, and for every other shape, launches of more than six workgroups count
     as several rounds and (up to 64 input features, tiles of 32 columns or a multiple) make their
