@@ -1771,6 +1771,19 @@ __device__ __forceinline__ void lds_dma16(const void* gp, const void* lds)
                  :: "v"(gp), "s"(m0) : "memory", "m0");
 }
 
+// The same with the LDS address as a number (a loop that adds to it spares the pointer conversion
+// of every trip).
+__device__ __forceinline__ int lds_address(const void* lds)
+{
+    return (int)(uintptr_t)((const __attribute__((address_space(3))) char*)lds);
+}
+
+__device__ __forceinline__ void lds_dma16_to(const void* gp, int lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+                 :: "v"(gp), "s"(lds_addr) : "memory", "m0");
+}
+
 // Workgroup barrier that orders LDS accesses only (no wait for global stores or for requests
 // in flight, which __syncthreads would add).
 __device__ __forceinline__ void lds_barrier()
@@ -1835,38 +1848,42 @@ bspmm_gcn_stream_kernel(const StreamSet* __restrict__ sets, const int32_t* __res
     }
 
     // rows of X_i and the merged CSR block of a graph -> buffers b.  A lane's element of a
-    // request is 256 elements (256 / XVEC rows) after its element of the previous one: the row
+    // request is T elements (T / XVEC rows) after its element of the previous one: the row
     // advances by a multiple of the swizzle period, so the swizzled column is the lane's for good
-    // and only the row term changes between requests.
+    // and between requests a lane's address moves by a fixed step, like the LDS address of the
+    // wavefront (the loops below are a handful of instructions a request: the wavefronts of the
+    // workgroups beside this one are busy on the same SIMD, and every instruction waits its turn).
+    // n_X = 128 with four wavefronts takes 8 rows a request, half a period: the swizzled column
+    // flips between two places, 128 bytes apart.
     constexpr int kRowsPerRequest = T / XVEC;
-    static_assert(kRowsPerRequest % (SWZ + 1) == 0 || XVEC == 32, "swizzle period");
+    constexpr bool kFlip = kRowsPerRequest % (SWZ + 1) != 0;
+    static_assert(!kFlip || (XVEC == 32 && kRowsPerRequest == 8), "swizzle period");
     const int x_row0 = tid >> XSH;
-    const int64_t x_lane_off = (int64_t)x_row0 * S.ld_x + (((tid & (XVEC - 1)) ^ (x_row0 & SWZ)) << 2);
+    const int x_col0 = (tid & (XVEC - 1)) ^ (x_row0 & SWZ);
+    const int64_t x_lane_off = (int64_t)x_row0 * S.ld_x + (x_col0 << 2);
+    const int64_t x_step = (int64_t)kRowsPerRequest * S.ld_x * 4;            // bytes
+    const int x_flip = kFlip ? ((x_col0 & 8) ? -128 : 128) : 0;              // bytes, to the other place
+    const int w16 = wave << 10;                                              // this wavefront's place in a request
+    const int xbase_lds = lds_address(xbase) + w16, cbase_lds = lds_address(cbase) + w16;
     auto request = [&](const StreamSet& st, int b) {
-        const int total = st.kx << XSH;
-        const float* xg = x + st.in_row * S.ld_x + x_lane_off;
-        float* xd = xbase + b * S.x_words;
-        for (int e0 = wave << 6; e0 < total; e0 += T) {
-            const int e = e0 + wl;
-            if (e < total) {
-                const int i = e0 / T;                        // which request of this wavefront
-                const float* gp;
-                if (XVEC == 32) {                            // (8 rows a request: the row's swizzle moves)
-                    const int r = e >> XSH;
-                    gp = x + st.in_row * S.ld_x + (int64_t)r * S.ld_x + (((e & (XVEC - 1)) ^ (r & SWZ)) << 2);
-                } else {
-                    gp = xg + (int64_t)(i * kRowsPerRequest) * S.ld_x;
-                }
-                lds_dma16(gp, xd + (e0 << 2));
-            }
+        const char* gp = reinterpret_cast<const char*>(x + st.in_row * S.ld_x + x_lane_off);
+        int to = xbase_lds + b * (S.x_words << 2);
+        int64_t step = x_step + x_flip;
+        // (left: elements of the request from this wavefront's first lane on)
+        for (int left = (st.kx << XSH) - (wave << 6); left > 0; left -= T) {
+            if (wl < left) lds_dma16_to(gp, to);
+            gp += step;
+            if (kFlip) step = 2 * x_step - step;
+            to += T * 16;
         }
-        const int32_t* cg = merged + st.csr_off;
-        int* cd = cbase + b * S.csr_words;
         const int csr_vecs = (((st.m + 4) & ~3) + 2 * ((st.nnz + 3) & ~3) +
                               (S.compact ? compact_words(S.channels, st.kx) : 0)) >> 2;
-        for (int e0 = wave << 6; e0 < csr_vecs; e0 += T) {
-            const int e = e0 + wl;
-            if (e < csr_vecs) lds_dma16(cg + 4 * e, cd + (e0 << 2));
+        const char* cg = reinterpret_cast<const char*>(merged + st.csr_off) + (tid << 4);
+        to = cbase_lds + b * (S.csr_words << 2);
+        for (int left = csr_vecs - (wave << 6); left > 0; left -= T) {
+            if (wl < left) lds_dma16_to(cg, to);
+            cg += T * 16;
+            to += T * 16;
         }
     };
 
