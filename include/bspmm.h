@@ -308,7 +308,8 @@ int bspmm_run(bspmm_plan* plan, const float* B, float* C, int64_t ldb, int64_t l
  * (v_mfma_f32_16x16x4_f32; whole layers in large launches: v_mfma_f32_32x32x2_f32) from LDS
  * to LDS; B_i never leaves the chip.  X, W, Y must be
  * 16-byte aligned with ldx, ldw, ldy multiples of 4 (EINVAL).  ESTATE for plans created
- * without front_features.
+ * without front_features.  (Launches of up to two workgroups per CU use workgroups of 512 lanes,
+ * larger ones of 256; the first call asks the device how many fit and keeps the answer.)
  *
  * The whole layer in one launch: a plan created with front_features AND BSPMM_ACCUMULATE, in
  * which every operation is one of M channels of a graph - the M channel operations of a graph

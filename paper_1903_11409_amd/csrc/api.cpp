@@ -23,7 +23,8 @@ hipError_t launch_bspmm_lean(const LeanItem* items, const LaunchParams& P, int g
                              hipStream_t stream);
 hipError_t launch_lean_hints(LeanItem* items, int n, const int32_t* rpt, hipStream_t stream);
 hipError_t launch_bspmm_gcn(const LaunchParams& P, int grid, int lds_bytes, bool accumulate,
-                            bool sets, hipStream_t stream);
+                            bool sets, bool wide, hipStream_t stream);
+int front_workgroups_per_cu(bool sets, bool wide, int lds_bytes);
 hipError_t launch_bspmm_gcn_stream(const StreamParams& S, int nx16, int units, int waves, int grid,
                                    int lds_bytes, hipStream_t stream);
 bool stream_supported(int nx16, int units, int waves);
@@ -102,6 +103,7 @@ struct bspmm_plan {
     int32_t batch = 0;
     int32_t F = 0;
     bool dry = false;
+    int front_wide = -1;            // the one-launch layer kernel runs with eight wavefronts (-1: not decided yet)
     Knobs knobs;
     DirOps dir[2];
     Schedule sched[2];
@@ -1554,7 +1556,18 @@ int run_gcn(bspmm_plan* p, const float* X, int64_t ldx, const float* W, int64_t 
     P.n_front = nx;
     P.accumulate = accumulate ? 1 : 0;
     const int grid = st.on() ? (int)st.rest.size() : sc.grid;
-    hipError_t e = launch_bspmm_gcn(P, grid, sc.front_lds_words * 4, accumulate != 0, sets, s);
+    // A launch of up to two workgroups per CU lasts as long as its largest item: workgroups of
+    // eight wavefronts halve that item's matrix blocks per wavefront and the passes of its
+    // gather.  Measured on 256 CUs, F = 128, four against eight wavefronts: one channel at
+    // n_X = 64, 32 graphs (320 workgroups) 6.4 -> 5.1 us; n_X = 128, 128 graphs (312) 9.3 -> 8.7;
+    // four channels at n_X = 64, 64 graphs (512) 9.3 -> 7.9, 32 graphs 7.1 -> 6.2.  Beyond two per
+    // CU the launch of twice the wavefronts costs more than it gains (128 graphs at n_X = 64, 544
+    // workgroups: 6.6 -> 6.9 us; four channels, 1024 workgroups: 11.9 -> 12.3).
+    if (p->front_wide < 0) {
+        const int per_cu = std::min(2, front_workgroups_per_cu(sets, true, sc.front_lds_words * 4));
+        p->front_wide = grid > 0 && (int64_t)grid <= (int64_t)per_cu * p->knobs.compute_units ? 1 : 0;
+    }
+    hipError_t e = launch_bspmm_gcn(P, grid, sc.front_lds_words * 4, accumulate != 0, sets, p->front_wide == 1, s);
     return e == hipSuccess ? BSPMM_OK : hip_fail(e);
 }
 

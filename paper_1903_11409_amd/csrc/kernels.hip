@@ -1466,6 +1466,7 @@ validate_coo_kernel(const OpRecord* __restrict__ ops, const int32_t* __restrict_
 // `swz` != 0 (only with a power-of-two nvec, swz < nvec) stores the float4 with index v of row r
 // in slot v ^ (r & swz): rows that are a multiple of 64 words apart then no longer fall on the
 // same LDS banks when 16 lanes read the same column of 16 consecutive rows.
+template <int THREADS = kThreads>
 __device__ __forceinline__ void stage_tile4(float* dst, const float* __restrict__ src, int64_t ld,
                                             int rows, int nvec, int tid, int swz = 0)
 {
@@ -1473,7 +1474,7 @@ __device__ __forceinline__ void stage_tile4(float* dst, const float* __restrict_
         const int sh = ilog2(nvec);
         const int total = rows << sh;
         const int wl = tid & 63;
-        for (int e0 = (tid >> 6) << 6; e0 < total; e0 += kThreads) {
+        for (int e0 = (tid >> 6) << 6; e0 < total; e0 += THREADS) {
             const int e = e0 + wl;
             if (e < total) {
                 const int r = e >> sh;
@@ -1486,7 +1487,7 @@ __device__ __forceinline__ void stage_tile4(float* dst, const float* __restrict_
     } else {
         const int gl = min(64, pow2_ceil(nvec));
         const int sh = ilog2(gl);
-        const int g = tid >> sh, l = tid & (gl - 1), G = kThreads >> sh;
+        const int g = tid >> sh, l = tid & (gl - 1), G = THREADS >> sh;
         if (l < nvec)
             for (int r0 = g; r0 < rows; r0 += 4 * G) {
                 float4 t[4];
@@ -1506,8 +1507,11 @@ __device__ __forceinline__ void stage_tile4(float* dst, const float* __restrict_
 // the set's merged one, whose entries of channel c name rows c*kx ... of that tile; W is the M
 // weight matrices one under the other (M*nx rows), bias M rows of P.fused_stride floats apart, and
 // P.rpt is the base of the merged arrays.
-template <bool ACC, bool SETS>
-__global__ void __launch_bounds__(kThreads) bspmm_gcn_kernel(const LaunchParams P)
+// THREADS: 256, or 512 for launches of a single round of workgroups, whose time is the time of
+// the largest item: twice the wavefronts halve its matrix blocks per wavefront and the passes
+// of its gather.
+template <bool ACC, bool SETS, int THREADS = kThreads>
+__global__ void __launch_bounds__(THREADS) bspmm_gcn_kernel(const LaunchParams P)
 {
     extern __shared__ __align__(16) int sm[];
     typedef float mfma4 __attribute__((ext_vector_type(4)));
@@ -1539,7 +1543,7 @@ __global__ void __launch_bounds__(kThreads) bspmm_gcn_kernel(const LaunchParams 
     auto dense_rows = [&](int r0, int rows) {
         const int per_channel = ((rows + 15) >> 4) * nb_count;
         const int blocks = per_channel * M;
-        for (int blk = wave; blk < blocks; blk += kThreads / 64) {
+        for (int blk = wave; blk < blocks; blk += THREADS / 64) {
             const int c = SETS ? blk / per_channel : 0;
             const int rem = blk - c * per_channel;
             const int mb = rem / nb_count, nb = rem - mb * nb_count;
@@ -1614,7 +1618,7 @@ __global__ void __launch_bounds__(kThreads) bspmm_gcn_kernel(const LaunchParams 
         const int per_channel = ((rows + 31) >> 5) * nb32;
         const int blocks = per_channel * M;
         const int c32 = wl & 31, h = wl >> 5;
-        for (int blk = wave; blk < blocks; blk += kThreads / 64) {
+        for (int blk = wave; blk < blocks; blk += THREADS / 64) {
             const int c = blk / per_channel;
             const int rem = blk - c * per_channel;
             const int mb = rem / nb32, nb = rem - mb * nb32;
@@ -1684,20 +1688,20 @@ __global__ void __launch_bounds__(kThreads) bspmm_gcn_kernel(const LaunchParams 
 
     // ---- first pass: everything read from memory is requested at once (the first rows of
     // X_i, the weights, the bias, A_i)
-    stage_tile4(xs, xg, P.ld_in, min(R, kx), xvec, tid, swz);
-    stage_tile4(ws, P.w + it.f0, P.ld_w, M * nx, it.fw >> 2, tid);
+    stage_tile4<THREADS>(xs, xg, P.ld_in, min(R, kx), xvec, tid, swz);
+    stage_tile4<THREADS>(ws, P.w + it.f0, P.ld_w, M * nx, it.fw >> 2, tid);
     float bias_v = 0.f;
     if (tid < it.fw) bias_v = P.bias[it.f0 + tid];
     if (SETS) {
         LaunchParams Q = P;                                   // CSR from the merged arrays
         Q.w = reinterpret_cast<const float*>(P.rpt);
-        stage_item<kThreads, 4, false, false, true>(Q, it, sm, tid);
-        for (int e = tid + it.fw; e < M * it.fw; e += kThreads) {   // the other channels' bias
+        stage_item<THREADS, 4, false, false, true>(Q, it, sm, tid);
+        for (int e = tid + it.fw; e < M * it.fw; e += THREADS) {   // the other channels' bias
             const int c = e / it.fw;
             bias_s[e] = P.bias[(int64_t)c * P.fused_stride + it.f0 + (e - c * it.fw)];
         }
     } else {
-        stage_item<kThreads, 4, false, false>(P, it, sm, tid);    // A_i only
+        stage_item<THREADS, 4, false, false>(P, it, sm, tid);    // A_i only
     }
     if (tid < it.fw) bias_s[tid] = bias_v;
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");          // direct-to-LDS loads landed
@@ -1710,7 +1714,7 @@ __global__ void __launch_bounds__(kThreads) bspmm_gcn_kernel(const LaunchParams 
     // ---- operations with more rows than fit: further passes
     for (int r0 = R; r0 < kx; r0 += R) {
         const int rows = min(R, kx - r0);
-        stage_tile4(xs, xg + (int64_t)r0 * P.ld_in, P.ld_in, rows, xvec, tid, swz);
+        stage_tile4<THREADS>(xs, xg + (int64_t)r0 * P.ld_in, P.ld_in, rows, xvec, tid, swz);
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
         if (blocks32)
@@ -1719,7 +1723,7 @@ __global__ void __launch_bounds__(kThreads) bspmm_gcn_kernel(const LaunchParams 
             dense_rows(r0, rows);
         __syncthreads();
     }
-    compute_staged<kThreads, 4, false, ACC>(P, it, sm, tid);
+    compute_staged<THREADS, 4, false, ACC>(P, it, sm, tid);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -2601,14 +2605,36 @@ hipError_t launch_lean_hints(LeanItem* items, int n, const int32_t* rpt, hipStre
     return hipGetLastError();
 }
 
+using FrontFn = void (*)(const LaunchParams);
+
+static FrontFn front_variant(bool accumulate, bool sets, bool wide)
+{
+    static const FrontFn table[8] = {
+        bspmm_gcn_kernel<false, false>, bspmm_gcn_kernel<true, false>,
+        bspmm_gcn_kernel<false, true>, bspmm_gcn_kernel<true, true>,
+        bspmm_gcn_kernel<false, false, 2 * kThreads>, bspmm_gcn_kernel<true, false, 2 * kThreads>,
+        bspmm_gcn_kernel<false, true, 2 * kThreads>, bspmm_gcn_kernel<true, true, 2 * kThreads>};
+    return table[(wide ? 4 : 0) + (sets ? 2 : 0) + (accumulate ? 1 : 0)];
+}
+
+// Workgroups of the one-launch layer kernel one CU of the current device holds (0 if it cannot
+// be asked); wide: workgroups of eight wavefronts.
+int front_workgroups_per_cu(bool sets, bool wide, int lds_bytes)
+{
+    int per_cu = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, front_variant(false, sets, wide),
+                                                     wide ? 2 * kThreads : kThreads, (size_t)lds_bytes) != hipSuccess) {
+        (void)hipGetLastError();
+        return 0;
+    }
+    return per_cu;
+}
+
 hipError_t launch_bspmm_gcn(const LaunchParams& P, int grid, int lds_bytes, bool accumulate,
-                            bool sets, hipStream_t stream)
+                            bool sets, bool wide, hipStream_t stream)
 {
     if (grid <= 0) return hipSuccess;
-    using Fn = void (*)(const LaunchParams);
-    static const Fn table[4] = {bspmm_gcn_kernel<false, false>, bspmm_gcn_kernel<true, false>,
-                                bspmm_gcn_kernel<false, true>, bspmm_gcn_kernel<true, true>};
-    hipLaunchKernelGGL(table[(sets ? 2 : 0) + (accumulate ? 1 : 0)], dim3(grid), dim3(kThreads),
+    hipLaunchKernelGGL(front_variant(accumulate, sets, wide), dim3(grid), dim3(wide ? 2 * kThreads : kThreads),
                        lds_bytes, stream, P);
     return hipGetLastError();
 }
