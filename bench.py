@@ -789,6 +789,8 @@ def main():
         extra["layer_whole"] = [layer_whole(torch, K, W, n_x=n, graphs=g)
                                 for g, n in ((128, 32), (128, 64), (512, 32), (512, 64), (2048, 32),
                                              (2048, 64))]
+        # other channel counts (two: one block per wavefront; eight: workgroups of eight wavefronts)
+        extra["layer_whole"] += [layer_whole(torch, K, W, n_x=64, channels=c, graphs=2048) for c in (2, 8)]
 
     out = {
         "metric": "batched SpMM graphs/sec, F=128, batch 128",
