@@ -309,7 +309,7 @@ int bspmm_run(bspmm_plan* plan, const float* B, float* C, int64_t ldb, int64_t l
  * to LDS; B_i never leaves the chip.  X, W, Y must be
  * 16-byte aligned with ldx, ldw, ldy multiples of 4 (EINVAL).  ESTATE for plans created
  * without front_features.  (Launches of up to two workgroups per CU use workgroups of 512 lanes,
- * larger ones of 256; the first call asks the device how many fit and keeps the answer.)
+ * larger ones of 256.)
  *
  * The whole layer in one launch: a plan created with front_features AND BSPMM_ACCUMULATE, in
  * which every operation is one of M channels of a graph - the M channel operations of a graph

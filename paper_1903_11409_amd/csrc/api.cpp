@@ -103,7 +103,7 @@ struct bspmm_plan {
     int32_t batch = 0;
     int32_t F = 0;
     bool dry = false;
-    int front_wide = -1;            // the one-launch layer kernel runs with eight wavefronts (-1: not decided yet)
+    int front_wide = 0;             // the one-launch layer kernel runs with workgroups of eight wavefronts
     Knobs knobs;
     DirOps dir[2];
     Schedule sched[2];
@@ -1386,6 +1386,23 @@ int plan_host_coo(bspmm_plan& p, const bspmm_coo_batch* b, int32_t F, const Knob
 int upload_plan(bspmm_plan* p, const bspmm_options* options, void* workspace,
                 size_t workspace_bytes, hipStream_t s)
 {
+    // The one-launch layer kernel's workgroup size, decided here (plans made by
+    // bspmm_workspace_bytes never asked the device) and not in the first run, which may be
+    // inside a stream capture.  A launch of up to two workgroups per CU lasts as long as its
+    // largest item, and workgroups of eight wavefronts halve that item's matrix blocks per
+    // wavefront and the passes of its gather.  Measured on 256 CUs, F = 128, four against eight
+    // wavefronts: one channel at n_X = 64, 32 graphs (320 workgroups) 6.4 -> 5.1 us; n_X = 128,
+    // 128 graphs (312) 9.3 -> 8.7; four channels at n_X = 64, 64 graphs (512) 9.3 -> 7.9, 32
+    // graphs 7.1 -> 6.2.  Beyond two per CU the launch of twice the wavefronts costs more than it
+    // gains (128 graphs at n_X = 64, 544 workgroups: 6.6 -> 6.9 us; four channels, 1024
+    // workgroups: 11.9 -> 12.3).
+    p->front_wide = 0;
+    if (p->knobs.front > 0) {
+        const Schedule& sc = p->sched[0];
+        const int64_t grid = p->stream.on() ? (int64_t)p->stream.rest.size() : sc.grid;
+        const int per_cu = std::min(2, front_workgroups_per_cu(!sc.merged_sets.empty(), true, sc.front_lds_words * 4));
+        p->front_wide = grid > 0 && grid <= (int64_t)per_cu * p->knobs.compute_units ? 1 : 0;
+    }
     if (options && (options->flags & BSPMM_FLOOR_PROBE))
         for (int d = 0; d < 2; ++d) {
             for (WorkItem& w : p->sched[d].items) w.nrows = w.m = w.k = w.nnz = 0;
@@ -1556,17 +1573,6 @@ int run_gcn(bspmm_plan* p, const float* X, int64_t ldx, const float* W, int64_t 
     P.n_front = nx;
     P.accumulate = accumulate ? 1 : 0;
     const int grid = st.on() ? (int)st.rest.size() : sc.grid;
-    // A launch of up to two workgroups per CU lasts as long as its largest item: workgroups of
-    // eight wavefronts halve that item's matrix blocks per wavefront and the passes of its
-    // gather.  Measured on 256 CUs, F = 128, four against eight wavefronts: one channel at
-    // n_X = 64, 32 graphs (320 workgroups) 6.4 -> 5.1 us; n_X = 128, 128 graphs (312) 9.3 -> 8.7;
-    // four channels at n_X = 64, 64 graphs (512) 9.3 -> 7.9, 32 graphs 7.1 -> 6.2.  Beyond two per
-    // CU the launch of twice the wavefronts costs more than it gains (128 graphs at n_X = 64, 544
-    // workgroups: 6.6 -> 6.9 us; four channels, 1024 workgroups: 11.9 -> 12.3).
-    if (p->front_wide < 0) {
-        const int per_cu = std::min(2, front_workgroups_per_cu(sets, true, sc.front_lds_words * 4));
-        p->front_wide = grid > 0 && (int64_t)grid <= (int64_t)per_cu * p->knobs.compute_units ? 1 : 0;
-    }
     hipError_t e = launch_bspmm_gcn(P, grid, sc.front_lds_words * 4, accumulate != 0, sets, p->front_wide == 1, s);
     return e == hipSuccess ? BSPMM_OK : hip_fail(e);
 }
