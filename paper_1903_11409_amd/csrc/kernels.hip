@@ -1748,7 +1748,8 @@ __global__ void __launch_bounds__(THREADS) bspmm_gcn_kernel(const LaunchParams P
 //     each) are fetched with scalar loads two trips ahead.
 //   * the launch's LDS is sized for the graphs that fit a budget of a third of a CU's LDS, so
 //     that three workgroups share a CU: one's matrix phase overlaps the others' gathers and
-//     requests.  Larger graphs (a few per cent of a molecule batch) are taken one at a time
+//     requests.  (Workgroups of eight wavefronts, WV = 8, which give each of eight channels a
+//     wavefront of its own: half a CU's LDS, two per CU.)  Larger graphs (a few per cent of a molecule batch) are taken one at a time
 //     out of the same LDS, their X_i in chunks (see below); what does not fit even so is not
 //     in the lists at all (the host gives it to bspmm_gcn_kernel in a launch of its own).
 // Arithmetic: the n_X products of a dense element are added by the matrix instructions in
@@ -1775,8 +1776,8 @@ __device__ __forceinline__ void lds_dma16(const void* gp, const void* lds)
                  :: "v"(gp), "s"(m0) : "memory", "m0");
 }
 
-// The same with the LDS address as a number (a loop that adds to it spares the pointer conversion
-// of every trip).
+// The same with the LDS address as a number: a loop that adds to it spares the pointer
+// conversion of every trip.
 __device__ __forceinline__ int lds_address(const void* lds)
 {
     return (int)(uintptr_t)((const __attribute__((address_space(3))) char*)lds);
